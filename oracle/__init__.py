@@ -1,0 +1,173 @@
+"""CPU oracle for the DFSS attention forward pass -- TEST INFRASTRUCTURE ONLY.
+
+Only the test-suite, the smoke check and the CPU-baseline leg of the benchmark
+may import this package.  It wraps ``dfss_oracle.c`` (plain C, built with gcc)
+through ctypes and numpy; it shares nothing with the HIP library.
+
+Passages followed (arXiv 2203.00091): Eq. 1 (Sec. 2.1), the N:M selection
+(Sec. 2.3, App. A.1.1), the metadata words (App. A.1.1, A.1.2), the softmax
+over kept entries (Sec. 3.1, App. A.1.3), the L^p quality (Def. 4.1).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dfss_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+_f32p = np.ctypeslib.ndpointer(dtype=np.float32, flags="C_CONTIGUOUS")
+_u8p = np.ctypeslib.ndpointer(dtype=np.uint8, flags="C_CONTIGUOUS")
+_i32p = np.ctypeslib.ndpointer(dtype=np.int32, flags="C_CONTIGUOUS")
+_u16p = np.ctypeslib.ndpointer(dtype=np.uint16, flags="C_CONTIGUOUS")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc.  -ffp-contract=off keeps the fp32 dot
+    product a plain multiply-then-add sequence, as the oracle's header states."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O3", "-march=native", "-ffp-contract=off", "-fopenmp", "-fPIC",
+               "-shared", "-std=c11", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        c_int, c_float, c_double = ctypes.c_int, ctypes.c_float, ctypes.c_double
+        L.oracle_scores.argtypes = [_f32p, _f32p, c_int, c_int, c_int, c_float, _f32p]
+        L.oracle_scores.restype = None
+        L.oracle_prune.argtypes = [_f32p, c_int, c_int, c_int, c_int, _u8p, _f32p, _i32p]
+        L.oracle_prune.restype = c_int
+        L.oracle_encode_meta.argtypes = [_i32p, c_int, c_int, _u16p]
+        L.oracle_encode_meta.restype = c_int
+        L.oracle_decode_meta.argtypes = [_u16p, c_int, c_int, _i32p]
+        L.oracle_decode_meta.restype = c_int
+        L.oracle_softmax_kept.argtypes = [_f32p, c_int, c_int, _f32p]
+        L.oracle_softmax_kept.restype = None
+        L.oracle_spmm.argtypes = [_f32p, _i32p, _f32p, c_int, c_int, c_int, _f32p]
+        L.oracle_spmm.restype = None
+        L.oracle_round_bf16_array.argtypes = [_f32p, ctypes.c_size_t, _f32p]
+        L.oracle_round_bf16_array.restype = None
+        L.oracle_attention_batched.argtypes = [_f32p, _f32p, _f32p, c_int, c_int, c_int, c_int,
+                                               c_int, c_int, c_float, c_int, _f32p]
+        L.oracle_attention_batched.restype = c_int
+        L.oracle_num_threads.argtypes = []
+        L.oracle_num_threads.restype = c_int
+        L.oracle_quality_p.argtypes = [_f32p, _u8p, c_int, c_int, c_double]
+        L.oracle_quality_p.restype = c_double
+        _lib = L
+    return _lib
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def scores(Q, K, scale):
+    """S = scale * Q K^T for one head, fp32 sequential accumulation (Eq. 1)."""
+    Q, K = _f32(Q), _f32(K)
+    Lq, d = Q.shape
+    Lk, d2 = K.shape
+    assert d == d2
+    S = np.empty((Lq, Lk), np.float32)
+    _load().oracle_scores(Q, K, Lq, Lk, d, float(scale), S)
+    return S
+
+
+def prune(S, N, M):
+    """N:M selection on one head's scores -> (mask u8 [Lq,Lk], vals f32 [Lq,Lc], kidx i32 [Lq,Lc])."""
+    S = _f32(S)
+    Lq, Lk = S.shape
+    Lc = Lk // M * N
+    mask = np.empty((Lq, Lk), np.uint8)
+    vals = np.empty((Lq, Lc), np.float32)
+    kidx = np.empty((Lq, Lc), np.int32)
+    rc = _load().oracle_prune(S, Lq, Lk, N, M, mask, vals, kidx)
+    if rc != 0:
+        raise ValueError(f"oracle_prune failed rc={rc}")
+    return mask, vals, kidx
+
+
+def encode_meta(kidx, Lk):
+    """Key indices of kept entries (2 per run of 4 keys) -> canonical uint16 words [Lq, Lk/16]."""
+    kidx = np.ascontiguousarray(kidx, dtype=np.int32)
+    Lq = kidx.shape[0]
+    meta = np.empty((Lq, Lk // 16), np.uint16)
+    rc = _load().oracle_encode_meta(kidx, Lq, Lk, meta)
+    if rc != 0:
+        raise ValueError(f"oracle_encode_meta failed rc={rc}")
+    return meta
+
+
+def decode_meta(meta, Lk):
+    meta = np.ascontiguousarray(meta, dtype=np.uint16)
+    Lq = meta.shape[0]
+    kidx = np.empty((Lq, Lk // 2), np.int32)
+    rc = _load().oracle_decode_meta(meta, Lq, Lk, kidx)
+    if rc != 0:
+        raise ValueError(f"oracle_decode_meta failed rc={rc}")
+    return kidx
+
+
+def softmax_kept(x):
+    x = _f32(x)
+    Lq, Lc = x.shape
+    P = np.empty_like(x)
+    _load().oracle_softmax_kept(x, Lq, Lc, P)
+    return P
+
+
+def spmm(P, kidx, V):
+    P, V = _f32(P), _f32(V)
+    kidx = np.ascontiguousarray(kidx, dtype=np.int32)
+    Lq, Lc = P.shape
+    Lk, d = V.shape
+    O = np.empty((Lq, d), np.float32)
+    _load().oracle_spmm(P, kidx, V, Lq, Lc, d, O)
+    return O
+
+
+def round_bf16(x):
+    x = _f32(x)
+    y = np.empty_like(x)
+    _load().oracle_round_bf16_array(x.reshape(-1), x.size, y.reshape(-1))
+    return y
+
+
+def attention(Q, K, V, N, M, scale, store_bf16=False):
+    """Whole forward for [BH, L, d] (or [L, d]) inputs; heads run on host threads."""
+    Q, K, V = _f32(Q), _f32(K), _f32(V)
+    squeeze = Q.ndim == 2
+    if squeeze:
+        Q, K, V = Q[None], K[None], V[None]
+    BH, Lq, d = Q.shape
+    Lk = K.shape[1]
+    O = np.empty((BH, Lq, d), np.float32)
+    rc = _load().oracle_attention_batched(Q, K, V, BH, Lq, Lk, d, N, M, float(scale),
+                                          int(bool(store_bf16)), O)
+    if rc != 0:
+        raise ValueError(f"oracle_attention failed rc={rc}")
+    return O[0] if squeeze else O
+
+
+def num_threads():
+    return int(_load().oracle_num_threads())
+
+
+def quality_p(S, mask, p):
+    """L^p quality of a mask on one head's score matrix (Def. 4.1)."""
+    S = _f32(S)
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    Lq, Lk = S.shape
+    return float(_load().oracle_quality_p(S, mask, Lq, Lk, float(p)))

@@ -1,0 +1,91 @@
+"""Seeded synthetic inputs for the DFSS attention forward pass.
+
+This module draws random tensors and nothing else: no part of the method's
+arithmetic lives here, so the HIP path and the CPU oracle can both be fed from
+it without sharing any computation.
+
+The workloads stand in for the paper's evaluation inputs, which are not
+available offline: they take the sequence lengths of its tasks (384 for
+question answering, 512 for masked language modelling, 1024/2048/4096 for the
+long-range tasks, Sec. 5.1), the head size of its latency study (d = 64,
+Sec. 5.2) and its own modelling assumption that scaled scores are i.i.d.
+Gaussian (Prop. 4.2): with Q, K ~ N(0, sigma^2) the scaled scores are close to
+N(0, sigma^4 * d * scale^2).
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+
+import torch
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    B: int
+    H: int
+    L: int
+    d: int
+    N: int
+    M: int
+    sigma: float
+    seed: int
+    integer: bool = False  # Q, K integer-valued in [-4, 4] (scores exact in fp32)
+
+    @property
+    def BH(self) -> int:
+        return self.B * self.H
+
+    @property
+    def scale(self) -> float:
+        return 1.0 / math.sqrt(self.d)
+
+
+WORKLOADS = {
+    w.name: w
+    for w in [
+        Workload("tiny_2to4", 1, 1, 256, 64, 2, 4, 1.0, 1001),
+        Workload("tiny_2to4_int", 1, 1, 256, 64, 2, 4, 1.0, 1002, integer=True),
+        Workload("bert_base_L384_2to4", 8, 12, 384, 64, 2, 4, 1.0, 2001),
+        Workload("bert_base_L512_1to2", 16, 12, 512, 64, 1, 2, 1.0, 3001),
+        Workload("long_L1024_2to4", 2, 12, 1024, 64, 2, 4, 1.0, 4001),
+        Workload("long_L2048_2to4", 2, 12, 2048, 64, 2, 4, 1.0, 4002),
+        Workload("long_L4096_2to4", 2, 12, 4096, 64, 2, 4, 1.0, 4003),
+        Workload("large_head_L2048_d128_2to4", 4, 16, 2048, 128, 2, 4, 0.5, 5001),
+        Workload("large_head_L2048_d128_1to2", 4, 16, 2048, 128, 1, 2, 0.5, 5001),
+    ]
+}
+
+
+def gaussian_qkv(BH: int, Lq: int, Lk: int, d: int, sigma: float, seed: int):
+    """Q [BH,Lq,d], K,V [BH,Lk,d] ~ N(0, sigma^2), rounded to bfloat16 (CPU tensors)."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    Q = (torch.randn(BH, Lq, d, generator=g) * sigma).to(torch.bfloat16)
+    K = (torch.randn(BH, Lk, d, generator=g) * sigma).to(torch.bfloat16)
+    V = (torch.randn(BH, Lk, d, generator=g) * sigma).to(torch.bfloat16)
+    return Q, K, V
+
+
+def integer_qkv(BH: int, Lq: int, Lk: int, d: int, seed: int, lo: int = -4, hi: int = 4):
+    """Q, K integers uniform in [lo, hi] (exact in bfloat16), V ~ N(0,1) rounded to bfloat16."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    Q = torch.randint(lo, hi + 1, (BH, Lq, d), generator=g).to(torch.bfloat16)
+    K = torch.randint(lo, hi + 1, (BH, Lk, d), generator=g).to(torch.bfloat16)
+    V = torch.randn(BH, Lk, d, generator=g).to(torch.bfloat16)
+    return Q, K, V
+
+
+def make(workload: Workload | str):
+    """Inputs of a named workload: (Q, K, V) bfloat16 CPU tensors shaped [B*H, L, d]."""
+    w = WORKLOADS[workload] if isinstance(workload, str) else workload
+    if w.integer:
+        return integer_qkv(w.BH, w.L, w.L, w.d, w.seed)
+    return gaussian_qkv(w.BH, w.L, w.L, w.d, w.sigma, w.seed)
+
+
+def to_numpy_f32(t: torch.Tensor):
+    """Widen a (bfloat16) tensor to a float32 numpy array holding the same values."""
+    return t.to(torch.float32).contiguous().numpy()
