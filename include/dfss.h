@@ -1,0 +1,117 @@
+/*
+ * dfss.h -- C ABI of the DFSS attention forward library for AMD MI355X (gfx950).
+ *
+ * DFSS = dynamic N:M fine-grained structured sparse attention, arXiv 2203.00091.
+ * The forward pass of one attention head is (Sec. 3.1, stages of the attention):
+ *
+ *   stage 1  S = scale * Q K^T, and inside the same kernel every aligned run of M
+ *            consecutive keys of a row is pruned to its N largest scores; only the
+ *            kept scores ("non-zeros") and their position codes ("metadata") are
+ *            written (Sec. 3.4, App. A.1.1, A.1.2);
+ *   stage 2  softmax over the kept scores of each row (Sec. 3.1, App. A.1.3);
+ *   stage 3  O = A_sparse V with the compressed weights (Sec. 3.1).
+ *
+ * Supported: bfloat16 inputs, N:M = 2:4 (the paper's bfloat16 mode, Sec. 2.3) and
+ * 1:2 on the same 2-byte data; d in {64, 128}; Lq a multiple of 64, Lk a multiple
+ * of 128.  Selection rule: larger signed score wins, equal scores -> lower key
+ * index wins; comparisons are made on the fp32 value scale*dot, which is then
+ * rounded to bfloat16 (nearest-even) for storage.
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers to contiguous row-major arrays owned by
+ *     the caller; the library allocates, frees and retains nothing.
+ *   - Q is [B*H, Lq, d], K and V are [B*H, Lk, d], O is [B*H, Lq, d]  (bfloat16).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued asynchronously; no call synchronises the host with the device.
+ *   - Return value is a dfss_status; nothing throws, aborts or prints.  Arguments
+ *     are validated before any launch, so an error return means no work was queued
+ *     (except DFSS_ERR_HIP, which reports a failed launch).
+ *   - Results are deterministic: no atomics, fixed reduction order.
+ */
+#ifndef DFSS_H
+#define DFSS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DFSS_OK = 0,
+    DFSS_ERR_NULL = 1,        /* a required pointer is NULL                             */
+    DFSS_ERR_SHAPE = 2,       /* non-positive size, or a size that breaks alignment      */
+    DFSS_ERR_UNSUPPORTED = 3, /* N:M, dtype, d or scale outside what is implemented      */
+    DFSS_ERR_WORKSPACE = 4,   /* workspace smaller than *_workspace_bytes() reports      */
+    DFSS_ERR_HIP = 5          /* the HIP runtime refused a launch                        */
+} dfss_status;
+
+typedef enum { DFSS_BF16 = 0 } dfss_dtype;
+
+typedef struct {
+    int32_t B, H;   /* batch and heads; only the product B*H matters                    */
+    int32_t Lq, Lk; /* number of queries (rows of S) and keys (columns of S)            */
+    int32_t d;      /* head dimension                                                   */
+    int32_t N, M;   /* keep N of every M consecutive keys: (2,4) or (1,2)               */
+    int32_t dtype;  /* dfss_dtype                                                       */
+} dfss_shape;
+
+/* ---- sizes (host only, no GPU needed); 0 if the shape is invalid ---------------- */
+
+/* Kept scores / weights: bfloat16 [B*H, Lq, Lk*N/M], row-major, key order (Sec. 2.3). */
+size_t dfss_vals_bytes(const dfss_shape *s);
+/* Metadata: one 4-bit code per run of 4 keys, four codes per uint16 (Sec. 2.3: 1/16 of
+ * the dense matrix in bits; App. A.1.2: code k of a word at bits [4k,4k+3]).  The words
+ * are held in the library's own order (see dfss_meta_to_canonical). */
+size_t dfss_meta_bytes(const dfss_shape *s);
+/* Workspace of dfss_attention: room for vals, meta and per-row statistics. */
+size_t dfss_workspace_bytes(const dfss_shape *s);
+/* Workspace of dense_attention: the dense bfloat16 score/weight matrix [B*H, Lq, Lk]. */
+size_t dense_workspace_bytes(const dfss_shape *s);
+
+/* ---- stage 1: SDDMM with the pruning epilogue (Sec. 3.4, App. A.1.2) ------------- */
+/* Q, K: device, bfloat16.  scale: finite and > 0 (1/sqrt(d) in Eq. 1).
+ * vals: device out, dfss_vals_bytes().  meta: device out, dfss_meta_bytes(). */
+dfss_status dfss_sddmm_prune(const void *Q, const void *K, const dfss_shape *s, float scale,
+                             void *vals, void *meta, void *stream);
+
+/* ---- stage 2: softmax over the kept entries of each row, in place (App. A.1.3) --- */
+/* vals: device in/out, bfloat16 [B*H, Lq, Lk*N/M]; fp32 arithmetic inside. */
+dfss_status dfss_sparse_softmax(void *vals, const dfss_shape *s, void *stream);
+
+/* ---- stage 3: O = A_sparse V (Sec. 3.1) ------------------------------------------ */
+/* vals, meta: device in, as written by stage 1 (vals after stage 2).  V: device in.
+ * O: device out, bfloat16 [B*H, Lq, d]; fp32 accumulation. */
+dfss_status dfss_spmm(const void *vals, const void *meta, const void *V, const dfss_shape *s,
+                      void *O, void *stream);
+
+/* ---- whole forward pass (Eq. 1 with the pruned score matrix) ---------------------- */
+/* ws: device scratch of at least dfss_workspace_bytes(), 256-byte aligned; contents
+ * undefined afterwards.  Computes the same function as stage 1 -> 2 -> 3; the
+ * normalisation may be folded into the neighbouring stages. */
+dfss_status dfss_attention(const void *Q, const void *K, const void *V, const dfss_shape *s,
+                           float scale, void *O, void *ws, size_t ws_bytes, void *stream);
+
+/* ---- full attention on the same GPU (Eq. 1), the denominator of every speedup ---- */
+/* Same three-stage structure with the dense score matrix stored in bfloat16 in ws
+ * (at least dense_workspace_bytes()).  s->N, s->M are ignored. */
+dfss_status dense_attention(const void *Q, const void *K, const void *V, const dfss_shape *s,
+                            float scale, void *O, void *ws, size_t ws_bytes, void *stream);
+
+/* ---- metadata order ---------------------------------------------------------------- */
+/* Canonical order: uint16 [B*H, Lq, Lk/16], word w of a row = codes of key runs
+ * 4w..4w+3, code = p_lo | p_hi << 2 with p the kept key index mod 4 (the 2-bit
+ * position rule that yields the two codes App. A.1.1 prints, 0x4 and 0xe).
+ * Library order: rows are taken in blocks of 16 and, inside a block, the words of one
+ * key chunk for the 16 rows are adjacent:  lib[bh][r/16][w][r%16] = canon[bh][r][w].
+ * Both calls take device pointers; `meta` and `canon` must not overlap. */
+dfss_status dfss_meta_to_canonical(const void *meta, const dfss_shape *s, void *canon, void *stream);
+dfss_status dfss_meta_from_canonical(const void *canon, const dfss_shape *s, void *meta, void *stream);
+
+const char *dfss_status_string(dfss_status st);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DFSS_H */

@@ -1,0 +1,23 @@
+"""DFSS attention forward pass (arXiv 2203.00091) for AMD MI355X.
+
+Thin Python binding over the C ABI of ``libdfss.so`` (see ``include/dfss.h``):
+argument marshalling only, every step of the path runs in the HIP kernels.
+PyTorch is used for device memory and streams.
+"""
+from .binding import (  # noqa: F401
+    DfssError,
+    Shape,
+    dense_attention,
+    dense_workspace_bytes,
+    dfss_attention,
+    dfss_meta_bytes,
+    dfss_meta_from_canonical,
+    dfss_meta_to_canonical,
+    dfss_sddmm_prune,
+    dfss_sparse_softmax,
+    dfss_spmm,
+    dfss_vals_bytes,
+    dfss_workspace_bytes,
+    library_path,
+    load_library,
+)

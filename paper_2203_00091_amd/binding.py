@@ -1,0 +1,198 @@
+"""ctypes binding of the C ABI declared in include/dfss.h.
+
+Each function has the name of the C entry point it calls and only marshals
+arguments: tensors are passed as raw device pointers, the current PyTorch HIP
+stream as the stream handle.  There is no fallback: if ``libdfss.so`` is
+missing or a call reports an error, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libdfss.so")
+
+EXPORTS = (
+    "dfss_vals_bytes", "dfss_meta_bytes", "dfss_workspace_bytes", "dense_workspace_bytes",
+    "dfss_sddmm_prune", "dfss_sparse_softmax", "dfss_spmm", "dfss_attention", "dense_attention",
+    "dfss_meta_to_canonical", "dfss_meta_from_canonical", "dfss_status_string",
+)
+
+
+class DfssError(RuntimeError):
+    def __init__(self, fn: str, status: int, text: str):
+        super().__init__(f"{fn} failed: status {status} ({text})")
+        self.status = status
+
+
+class _CShape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "H", "Lq", "Lk", "d", "N", "M", "dtype")]
+
+
+@dataclass(frozen=True)
+class Shape:
+    """Mirror of ``dfss_shape``: B*H heads, Lq queries, Lk keys, head size d, keep N of M."""
+    B: int
+    H: int
+    Lq: int
+    Lk: int
+    d: int
+    N: int = 2
+    M: int = 4
+    dtype: int = 0  # DFSS_BF16
+
+    def c(self) -> _CShape:
+        return _CShape(self.B, self.H, self.Lq, self.Lk, self.d, self.N, self.M, self.dtype)
+
+    @property
+    def BH(self) -> int:
+        return self.B * self.H
+
+    @property
+    def Lc(self) -> int:
+        return self.Lk * self.N // self.M
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libdfss.so (built in-tree by ``paper_2203_00091_amd.build``); raise if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} not built: run `python -m paper_2203_00091_amd.build` (needs hipcc)")
+        L = ctypes.CDLL(_LIB_PATH)
+        sp = ctypes.POINTER(_CShape)
+        vp, sz, f32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float
+        for name in ("dfss_vals_bytes", "dfss_meta_bytes", "dfss_workspace_bytes", "dense_workspace_bytes"):
+            getattr(L, name).argtypes = [sp]
+            getattr(L, name).restype = sz
+        L.dfss_sddmm_prune.argtypes = [vp, vp, sp, f32, vp, vp, vp]
+        L.dfss_sparse_softmax.argtypes = [vp, sp, vp]
+        L.dfss_spmm.argtypes = [vp, vp, vp, sp, vp, vp]
+        L.dfss_attention.argtypes = [vp, vp, vp, sp, f32, vp, vp, sz, vp]
+        L.dense_attention.argtypes = [vp, vp, vp, sp, f32, vp, vp, sz, vp]
+        L.dfss_meta_to_canonical.argtypes = [vp, sp, vp, vp]
+        L.dfss_meta_from_canonical.argtypes = [vp, sp, vp, vp]
+        for name in ("dfss_sddmm_prune", "dfss_sparse_softmax", "dfss_spmm", "dfss_attention",
+                     "dense_attention", "dfss_meta_to_canonical", "dfss_meta_from_canonical"):
+            getattr(L, name).restype = ctypes.c_int
+        L.dfss_status_string.argtypes = [ctypes.c_int]
+        L.dfss_status_string.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(fn: str, status: int):
+    if status != 0:
+        raise DfssError(fn, status, load_library().dfss_status_string(status).decode())
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: torch.Tensor | None) -> int | None:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    return t.data_ptr()
+
+
+def dfss_vals_bytes(s: Shape) -> int:
+    return int(load_library().dfss_vals_bytes(ctypes.byref(s.c())))
+
+
+def dfss_meta_bytes(s: Shape) -> int:
+    return int(load_library().dfss_meta_bytes(ctypes.byref(s.c())))
+
+
+def dfss_workspace_bytes(s: Shape) -> int:
+    return int(load_library().dfss_workspace_bytes(ctypes.byref(s.c())))
+
+
+def dense_workspace_bytes(s: Shape) -> int:
+    return int(load_library().dense_workspace_bytes(ctypes.byref(s.c())))
+
+
+def _alloc_bytes(n: int, device) -> torch.Tensor:
+    return torch.empty(max(n, 1), dtype=torch.uint8, device=device)
+
+
+def dfss_sddmm_prune(Q, K, s: Shape, scale: float, vals=None, meta=None):
+    """Stage 1.  Returns (vals bf16 [BH, Lq, Lk*N/M], meta uint16 in library order [BH*Lq*Lk/16])."""
+    if vals is None:
+        vals = torch.empty((s.BH, s.Lq, s.Lc), dtype=torch.bfloat16, device=Q.device)
+    if meta is None:
+        meta = torch.empty((s.BH * s.Lq * (s.Lk // 16),), dtype=torch.int16, device=Q.device)
+    st = load_library().dfss_sddmm_prune(_ptr(Q), _ptr(K), ctypes.byref(s.c()), scale, _ptr(vals), _ptr(meta),
+                                         _stream())
+    _check("dfss_sddmm_prune", st)
+    return vals, meta
+
+
+def dfss_sparse_softmax(vals, s: Shape):
+    """Stage 2, in place on vals."""
+    _check("dfss_sparse_softmax", load_library().dfss_sparse_softmax(_ptr(vals), ctypes.byref(s.c()), _stream()))
+    return vals
+
+
+def dfss_spmm(vals, meta, V, s: Shape, O=None):
+    """Stage 3.  Returns O bf16 [BH, Lq, d]."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=V.device)
+    st = load_library().dfss_spmm(_ptr(vals), _ptr(meta), _ptr(V), ctypes.byref(s.c()), _ptr(O), _stream())
+    _check("dfss_spmm", st)
+    return O
+
+
+def dfss_attention(Q, K, V, s: Shape, scale: float, O=None, ws=None):
+    """Whole DFSS forward.  ``ws`` (uint8 device tensor) is allocated if not given."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=Q.device)
+    if ws is None:
+        ws = _alloc_bytes(dfss_workspace_bytes(s), Q.device)
+    st = load_library().dfss_attention(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(s.c()), scale, _ptr(O), _ptr(ws),
+                                       ws.numel() * ws.element_size(), _stream())
+    _check("dfss_attention", st)
+    return O
+
+
+def dense_attention(Q, K, V, s: Shape, scale: float, O=None, ws=None):
+    """Full attention baseline on the same GPU."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=Q.device)
+    if ws is None:
+        ws = _alloc_bytes(dense_workspace_bytes(s), Q.device)
+    st = load_library().dense_attention(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(s.c()), scale, _ptr(O), _ptr(ws),
+                                        ws.numel() * ws.element_size(), _stream())
+    _check("dense_attention", st)
+    return O
+
+
+def dfss_meta_to_canonical(meta, s: Shape, canon=None):
+    """Library word order -> canonical uint16 [BH, Lq, Lk/16] (held as int16 bits)."""
+    if canon is None:
+        canon = torch.empty((s.BH, s.Lq, s.Lk // 16), dtype=torch.int16, device=meta.device)
+    st = load_library().dfss_meta_to_canonical(_ptr(meta), ctypes.byref(s.c()), _ptr(canon), _stream())
+    _check("dfss_meta_to_canonical", st)
+    return canon
+
+
+def dfss_meta_from_canonical(canon, s: Shape, meta=None):
+    if meta is None:
+        meta = torch.empty((s.BH * s.Lq * (s.Lk // 16),), dtype=torch.int16, device=canon.device)
+    st = load_library().dfss_meta_from_canonical(_ptr(canon), ctypes.byref(s.c()), _ptr(meta), _stream())
+    _check("dfss_meta_from_canonical", st)
+    return meta

@@ -1,0 +1,157 @@
+// C ABI of the DFSS library: argument validation and kernel sequencing.
+// The public contract is documented in include/dfss.h.
+#include <math.h>
+
+#include "../../include/dfss.h"
+#include "dfss_kernels.hpp"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Dims {
+    int BH, Lq, Lk, d, mode;
+};
+
+// Shape rules common to every entry point.  need_nm: also check N:M.
+dfss_status check_shape(const dfss_shape *s, bool need_nm, Dims *out) {
+    if (!s) return DFSS_ERR_NULL;
+    if (s->B <= 0 || s->H <= 0 || s->Lq <= 0 || s->Lk <= 0 || s->d <= 0) return DFSS_ERR_SHAPE;
+    const long long bh = (long long)s->B * s->H;
+    if (bh > 65535) return DFSS_ERR_SHAPE;
+    if (s->Lq % 64 != 0 || s->Lk % 128 != 0) return DFSS_ERR_SHAPE;
+    if (s->Lk > 8192 || s->Lq > (1 << 20)) return DFSS_ERR_SHAPE;
+    if (s->dtype != DFSS_BF16) return DFSS_ERR_UNSUPPORTED;
+    if (s->d != 64 && s->d != 128) return DFSS_ERR_UNSUPPORTED;
+    int mode = -1;
+    if (need_nm) {
+        if (s->N == 2 && s->M == 4) mode = 0;
+        else if (s->N == 1 && s->M == 2) mode = 1;
+        else return DFSS_ERR_UNSUPPORTED;
+    }
+    if (out) *out = Dims{(int)bh, s->Lq, s->Lk, s->d, mode};
+    return DFSS_OK;
+}
+
+inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+inline bool bad_scale(float x) { return !(x > 0.0f) || isinf(x); }
+inline dfss_status hip_status(hipError_t e) { return e == hipSuccess ? DFSS_OK : DFSS_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+size_t dfss_vals_bytes(const dfss_shape *s) {
+    Dims D;
+    if (check_shape(s, true, &D) != DFSS_OK) return 0;
+    return (size_t)D.BH * D.Lq * (D.Lk / 2) * 2;
+}
+
+size_t dfss_meta_bytes(const dfss_shape *s) {
+    Dims D;
+    if (check_shape(s, true, &D) != DFSS_OK) return 0;
+    return (size_t)D.BH * D.Lq * (D.Lk / 16) * 2;
+}
+
+size_t dfss_workspace_bytes(const dfss_shape *s) {
+    const size_t v = dfss_vals_bytes(s), m = dfss_meta_bytes(s);
+    if (!v || !m) return 0;
+    return align_up(v) + align_up(m);
+}
+
+size_t dense_workspace_bytes(const dfss_shape *s) {
+    Dims D;
+    if (check_shape(s, false, &D) != DFSS_OK) return 0;
+    return align_up((size_t)D.BH * D.Lq * D.Lk * 2);
+}
+
+dfss_status dfss_sddmm_prune(const void *Q, const void *K, const dfss_shape *s, float scale, void *vals,
+                             void *meta, void *stream) {
+    Dims D;
+    if (!Q || !K || !vals || !meta) return DFSS_ERR_NULL;
+    if (dfss_status st = check_shape(s, true, &D)) return st;
+    if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
+    if (misaligned(Q) || misaligned(K) || misaligned(vals) || misaligned(meta)) return DFSS_ERR_SHAPE;
+    return hip_status(dfss::launch_sddmm_prune(Q, K, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, vals, meta,
+                                               (hipStream_t)stream));
+}
+
+dfss_status dfss_sparse_softmax(void *vals, const dfss_shape *s, void *stream) {
+    Dims D;
+    if (!vals) return DFSS_ERR_NULL;
+    if (dfss_status st = check_shape(s, true, &D)) return st;
+    if (misaligned(vals)) return DFSS_ERR_SHAPE;
+    return hip_status(dfss::launch_row_softmax(vals, (long)D.BH * D.Lq, D.Lk / 2, (hipStream_t)stream));
+}
+
+dfss_status dfss_spmm(const void *vals, const void *meta, const void *V, const dfss_shape *s, void *O,
+                      void *stream) {
+    Dims D;
+    if (!vals || !meta || !V || !O) return DFSS_ERR_NULL;
+    if (dfss_status st = check_shape(s, true, &D)) return st;
+    if (misaligned(vals) || misaligned(meta) || misaligned(V) || misaligned(O)) return DFSS_ERR_SHAPE;
+    return hip_status(dfss::launch_spmm(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, (hipStream_t)stream));
+}
+
+dfss_status dfss_attention(const void *Q, const void *K, const void *V, const dfss_shape *s, float scale, void *O,
+                           void *ws, size_t ws_bytes, void *stream) {
+    Dims D;
+    if (!Q || !K || !V || !O || !ws) return DFSS_ERR_NULL;
+    if (dfss_status st = check_shape(s, true, &D)) return st;
+    if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O)) return DFSS_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0) return DFSS_ERR_SHAPE;
+    if (ws_bytes < dfss_workspace_bytes(s)) return DFSS_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    char *vals = static_cast<char *>(ws);
+    char *meta = vals + align_up(dfss_vals_bytes(s));
+    hipError_t e = dfss::launch_sddmm_prune(Q, K, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, vals, meta, st);
+    if (e == hipSuccess) e = dfss::launch_row_softmax(vals, (long)D.BH * D.Lq, D.Lk / 2, st);
+    if (e == hipSuccess) e = dfss::launch_spmm(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, st);
+    return hip_status(e);
+}
+
+dfss_status dense_attention(const void *Q, const void *K, const void *V, const dfss_shape *s, float scale, void *O,
+                            void *ws, size_t ws_bytes, void *stream) {
+    Dims D;
+    if (!Q || !K || !V || !O || !ws) return DFSS_ERR_NULL;
+    if (dfss_status st = check_shape(s, false, &D)) return st;
+    if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O)) return DFSS_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0) return DFSS_ERR_SHAPE;
+    if (ws_bytes < dense_workspace_bytes(s)) return DFSS_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = dfss::launch_dense_scores(Q, K, D.BH, D.Lq, D.Lk, D.d, scale, ws, st);
+    if (e == hipSuccess) e = dfss::launch_row_softmax(ws, (long)D.BH * D.Lq, D.Lk, st);
+    if (e == hipSuccess) e = dfss::launch_dense_av(ws, V, D.BH, D.Lq, D.Lk, D.d, O, st);
+    return hip_status(e);
+}
+
+dfss_status dfss_meta_to_canonical(const void *meta, const dfss_shape *s, void *canon, void *stream) {
+    Dims D;
+    if (!meta || !canon) return DFSS_ERR_NULL;
+    if (dfss_status st = check_shape(s, true, &D)) return st;
+    return hip_status(dfss::launch_meta_reorder(meta, canon, D.BH, D.Lq, D.Lk / 16, true, (hipStream_t)stream));
+}
+
+dfss_status dfss_meta_from_canonical(const void *canon, const dfss_shape *s, void *meta, void *stream) {
+    Dims D;
+    if (!meta || !canon) return DFSS_ERR_NULL;
+    if (dfss_status st = check_shape(s, true, &D)) return st;
+    return hip_status(dfss::launch_meta_reorder(canon, meta, D.BH, D.Lq, D.Lk / 16, false, (hipStream_t)stream));
+}
+
+const char *dfss_status_string(dfss_status st) {
+    switch (st) {
+        case DFSS_OK: return "ok";
+        case DFSS_ERR_NULL: return "null pointer";
+        case DFSS_ERR_SHAPE: return "invalid shape or alignment";
+        case DFSS_ERR_UNSUPPORTED: return "unsupported N:M, dtype, head size or scale";
+        case DFSS_ERR_WORKSPACE: return "workspace too small";
+        case DFSS_ERR_HIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

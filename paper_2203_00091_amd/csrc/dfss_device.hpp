@@ -1,0 +1,71 @@
+// Device-side helpers shared by the HIP kernels of the DFSS library (gfx950 only).
+//
+// Register layouts of the matrix instructions used here (wave64, lane l):
+//   v_mfma_f32_16x16x32_bf16   A: row i = l%16, k = 8*(l/16)+e (e = 0..7)
+//                              B: col j = l%16, k = 8*(l/16)+e
+//                              D: col j = l%16, rows i = 4*(l/16)+r (r = 0..3)
+//   v_smfmac_f32_16x16x64_bf16 A (2:4 compressed, 8 kept values per lane): row i = l%16,
+//                              kept value e belongs to dense k = 16*(l/16) + 4*(e/2) + idx_e,
+//                              idx_e = bits [2e, 2e+1] of the low half of the index register
+//                              B (16 values per lane): col j = l%16,
+//                              k = 8*(l/16)+e for e < 8 and k = 32 + 8*(l/16)+(e-8) for e >= 8
+//                              D: as the dense 16x16 instruction.
+// Each lane therefore owns four consecutive output rows of one column.  The kernels put
+// KEYS on the output rows, so that a whole run of four consecutive keys of one query
+// sits in one lane and the N:M selection needs no cross-lane traffic.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dfss {
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+
+// Two fp32 -> two bfloat16 (round to nearest even) packed in one dword, `lo` in bits 15:0.
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    f32x2 v = {lo, hi};
+    bf16x2 b = __builtin_convertvector(v, bf16x2);
+    return __builtin_bit_cast(uint32_t, b);
+}
+
+__device__ __forceinline__ float bf16_lo_to_f32(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
+__device__ __forceinline__ float bf16_hi_to_f32(uint32_t w) { return __builtin_bit_cast(float, w & 0xFFFF0000u); }
+
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// Transposing LDS read: within each group of 16 lanes, lane s supplies the address of
+// four consecutive 16-bit elements; lane t receives element t%4 of source lanes
+// t/4, 4 + t/4, 8 + t/4, 12 + t/4.
+__device__ __forceinline__ s16x4 lds_read_tr16(const void *p) {
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
+}
+
+template <typename T>
+__device__ __forceinline__ T wave_xor_max(T v, int width) {
+    for (int o = width >> 1; o > 0; o >>= 1) {
+        T u = __shfl_xor(v, o, kWave);
+        v = v > u ? v : u;
+    }
+    return v;
+}
+template <typename T>
+__device__ __forceinline__ T wave_xor_sum(T v, int width) {
+    for (int o = width >> 1; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+}  // namespace dfss

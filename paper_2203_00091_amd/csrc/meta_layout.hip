@@ -1,0 +1,37 @@
+// Metadata word order (arXiv 2203.00091, Sec. 2.3 and App. A.1.1-A.1.2 define the 4-bit
+// codes and their packing into 16-bit words; the ORDER of the words in memory is free).
+// Canonical: uint16 [BH, Lq, W], W = Lk/16.  Library: [BH, Lq/16, W, 16], i.e. the words
+// of one 16-key chunk for 16 consecutive rows are adjacent, which is the order in which
+// both the pruning epilogue (writer) and the SpMM (reader) hold them across a wave.
+#include "dfss_device.hpp"
+#include "dfss_kernels.hpp"
+
+namespace dfss {
+
+namespace {
+
+__global__ __launch_bounds__(256) void k_meta_reorder(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
+                                                      long total, int Lq, int W, bool to_canonical) {
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;  // index in canonical order
+    if (i >= total) return;
+    const int w = (int)(i % W);
+    const long r = i / W;  // bh * Lq + row
+    const int row = (int)(r % Lq);
+    const long bh = r / Lq;
+    const long lib = ((bh * (Lq / 16) + row / 16) * W + w) * 16 + row % 16;
+    if (to_canonical) dst[i] = src[lib];
+    else dst[lib] = src[i];
+}
+
+}  // namespace
+
+hipError_t launch_meta_reorder(const void *src, void *dst, int BH, int Lq, int W, bool to_canonical,
+                               hipStream_t st) {
+    const long total = (long)BH * Lq * W;
+    const unsigned grid = (unsigned)((total + 255) / 256);
+    hipLaunchKernelGGL(k_meta_reorder, dim3(grid), dim3(256), 0, st, (const uint16_t *)src, (uint16_t *)dst, total,
+                       Lq, W, to_canonical);
+    return hipGetLastError();
+}
+
+}  // namespace dfss

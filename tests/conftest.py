@@ -32,3 +32,12 @@ def read_golden(name: str) -> dict:
 @pytest.fixture(scope="session")
 def golden():
     return read_golden
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _built_library():
+    """Tests load the library that is built in-tree; build it only if it is absent."""
+    from paper_2203_00091_amd import build as b
+    if not os.path.exists(b.LIB):
+        b.build()
+    yield

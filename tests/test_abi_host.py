@@ -1,0 +1,90 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, sizes follow the paper's footprint, and invalid arguments
+are turned into status codes before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2203_00091_amd as dfss
+from paper_2203_00091_amd import Shape
+from paper_2203_00091_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "dfss.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:dfss|dense)_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = dfss.load_library()
+    names = _declared_functions()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/dfss.h but not exported"
+    assert set(names) == set(binding.EXPORTS)
+
+
+def test_sizes_follow_the_compressed_footprint():
+    s = Shape(8, 12, 384, 384, 64, 2, 4)
+    dense = 96 * 384 * 384 * 2
+    assert dfss.dfss_vals_bytes(s) == dense // 2           # N/M of the dense matrix (Sec. 2.3)
+    assert dfss.dfss_meta_bytes(s) == dense // 16          # 1/16 of the dense bits (Sec. 2.3)
+    assert dfss.dense_workspace_bytes(s) >= dense
+    assert dfss.dfss_workspace_bytes(s) >= dense // 2 + dense // 16
+    s12 = Shape(16, 12, 512, 512, 64, 1, 2)
+    assert dfss.dfss_vals_bytes(s12) == 192 * 512 * 512
+    assert dfss.dfss_meta_bytes(s12) == 192 * 512 * 512 // 8
+
+
+@pytest.mark.parametrize("shape", [
+    Shape(1, 1, 100, 256, 64),       # Lq not a multiple of 64
+    Shape(1, 1, 128, 192, 64),       # Lk not a multiple of 128
+    Shape(0, 1, 128, 128, 64),
+    Shape(1, 1, 128, 128, 64, 3, 4),  # N:M not implemented
+    Shape(1, 1, 128, 128, 96),       # head size not implemented
+    Shape(1, 1, 128, 128, 64, 2, 4, 1),  # dtype not implemented
+    Shape(300, 300, 128, 128, 64),   # too many heads for one launch
+    Shape(1, 1, 128, 16384, 64),     # rows longer than the softmax kernel holds
+])
+def test_invalid_shapes_have_zero_size(shape):
+    assert dfss.dfss_vals_bytes(shape) == 0
+    assert dfss.dfss_workspace_bytes(shape) == 0
+
+
+def test_errors_are_reported_before_any_launch():
+    lib = dfss.load_library()
+    ok = Shape(1, 1, 128, 128, 64).c()
+    buf = ctypes.create_string_buffer(64)          # host memory: never dereferenced on these paths
+    p = ctypes.cast(buf, ctypes.c_void_p)
+    aligned = ctypes.c_void_p((p.value + 15) // 16 * 16)
+    E_NULL, E_SHAPE, E_UNSUP, E_WS = 1, 2, 3, 4
+    assert lib.dfss_sddmm_prune(None, aligned, ctypes.byref(ok), 0.125, aligned, aligned, None) == E_NULL
+    assert lib.dfss_sddmm_prune(aligned, aligned, None, 0.125, aligned, aligned, None) == E_NULL
+    bad = Shape(1, 1, 100, 128, 64).c()
+    assert lib.dfss_sddmm_prune(aligned, aligned, ctypes.byref(bad), 0.125, aligned, aligned, None) == E_SHAPE
+    bad = Shape(1, 1, 128, 128, 64, 4, 8).c()
+    assert lib.dfss_sddmm_prune(aligned, aligned, ctypes.byref(bad), 0.125, aligned, aligned, None) == E_UNSUP
+    for scale in (0.0, -1.0, float("inf"), float("nan")):
+        assert lib.dfss_sddmm_prune(aligned, aligned, ctypes.byref(ok), scale, aligned, aligned, None) == E_UNSUP
+    odd = ctypes.c_void_p(aligned.value + 2)
+    assert lib.dfss_sddmm_prune(odd, aligned, ctypes.byref(ok), 0.125, aligned, aligned, None) == E_SHAPE
+    assert lib.dfss_sparse_softmax(None, ctypes.byref(ok), None) == E_NULL
+    assert lib.dfss_spmm(aligned, aligned, aligned, ctypes.byref(ok), None, None) == E_NULL
+    ws = ctypes.c_void_p((p.value + 255) // 256 * 256)
+    assert lib.dfss_attention(aligned, aligned, aligned, ctypes.byref(ok), 0.125, aligned, ws, 16, None) == E_WS
+    assert lib.dense_attention(aligned, aligned, aligned, ctypes.byref(ok), 0.125, aligned, ws, 16, None) == E_WS
+    assert lib.dfss_status_string(0) == b"ok"
+    assert lib.dfss_status_string(E_WS) == b"workspace too small"
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    s = Shape(1, 1, 128, 128, 64)
+    q = torch.zeros(1, 128, 64, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        dfss.dfss_sddmm_prune(q, q, s, 0.125, vals=q, meta=q)
