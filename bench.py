@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the DFSS attention forward pass on one MI355X.
+
+One "step" = one call of ``dfss_attention`` (all stages of the hot path: SDDMM with the
+pruning epilogue, softmax over kept scores, SpMM) over one batch of synthetic inputs of
+the named workload.  Prints ONE JSON line.
+
+  value           whole-path throughput in TFLOP/s, counting the algorithmic FLOPs of the
+                  sparse path: 3 * BH * L^2 * d per step (2 L^2 d dense QK^T + L^2 d SpMM).
+  extra           the same step for ``dense_attention`` on the same GPU, the speedup, the
+                  dense-equivalent rate (4 * BH * L^2 * d), warm-cache figures.
+  roofline        dominant kernel, algorithmic bytes / measured launch duration vs HBM peak.
+  cpu_baseline    the CPU oracle timed on the host cores (context only).
+
+Inputs are resident in HBM before timing starts.  By default the steps rotate over enough
+independent buffer sets that no step finds its inputs or workspace in the last-level cache
+(``--warm`` keeps one set).  The K timed steps are captured in one HIP graph and replayed
+once between two device synchronisations, so host launch cost is not part of the figure.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
+LLC_BYTES = 256 << 20           # last-level (Infinity) cache; L2 is 8 x 4 MiB on top
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="bert_base_L384_2to4")
+    ap.add_argument("--warm", action="store_true", help="single buffer set (cache-resident)")
+    ap.add_argument("--no-graph", action="store_true", help="launch steps directly instead of one HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only; --gpus N with N > 1 is not supported "
+              "(heads are independent, see DESIGN.md for how the path would shard).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2203_00091_amd as dfss
+    from paper_2203_00091_amd import Shape, synth
+
+    if not os.path.exists(dfss.library_path()):
+        from paper_2203_00091_amd import build as b
+        b.build()
+    dfss.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    w = synth.WORKLOADS[args.workload]
+    s = Shape(w.B, w.H, w.L, w.L, w.d, w.N, w.M)
+    K, W = args.steps, args.warmup
+    BH, L, d = w.BH, w.L, w.d
+
+    # ---- buffers --------------------------------------------------------------------
+    Qc, Kc, Vc = synth.make(w)
+    ws_sparse = dfss.dfss_workspace_bytes(s)
+    ws_dense = dfss.dense_workspace_bytes(s)
+    set_bytes = 4 * BH * L * d * 2 + max(ws_sparse, ws_dense)
+    if args.warm:
+        nsets = 1
+    else:
+        nsets = max(2, math.ceil(3 * LLC_BYTES / set_bytes))
+    sets = []
+    for i in range(nsets):
+        sets.append(dict(
+            Q=Qc.to(dev), K=Kc.to(dev), V=Vc.to(dev),
+            O=torch.empty((BH, L, d), dtype=torch.bfloat16, device=dev),
+            ws=torch.empty(max(ws_sparse, ws_dense), dtype=torch.uint8, device=dev)))
+    torch.cuda.synchronize()
+
+    def step_sparse(i):
+        b = sets[i % nsets]
+        dfss.dfss_attention(b["Q"], b["K"], b["V"], s, w.scale, O=b["O"], ws=b["ws"])
+
+    def step_dense(i):
+        b = sets[i % nsets]
+        dfss.dense_attention(b["Q"], b["K"], b["V"], s, w.scale, O=b["O"], ws=b["ws"])
+
+    def step_stage1(i):
+        b = sets[i % nsets]
+        n_vals = dfss.dfss_vals_bytes(s)
+        vals = b["ws"][:n_vals]
+        meta = b["ws"][(n_vals + 255) // 256 * 256:]
+        dfss.dfss_sddmm_prune(b["Q"], b["K"], s, w.scale, vals=vals, meta=meta)
+
+    def step_stage2(i):
+        b = sets[i % nsets]
+        dfss.dfss_sparse_softmax(b["ws"], s)
+
+    def step_stage3(i):
+        b = sets[i % nsets]
+        n_vals = dfss.dfss_vals_bytes(s)
+        dfss.dfss_spmm(b["ws"][:n_vals], b["ws"][(n_vals + 255) // 256 * 256:], b["V"], s, O=b["O"])
+
+    def timed(step_fn, steps, warmup, use_graph=True):
+        """Wall-clock of `steps` steps between two device synchronisations -> seconds."""
+        for i in range(warmup):
+            step_fn(i)
+        torch.cuda.synchronize()
+        if use_graph:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for i in range(steps):
+                    step_fn(i)
+            g.replay()  # untimed: uploads the graph
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            g.replay()
+            torch.cuda.synchronize()
+            return time.perf_counter() - t0
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step_fn(i)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    def event_avg_ms(step_fn, n):
+        """Average launch duration of one kernel: n launches in one graph between two events
+        recorded on the stream the kernels run on (the current PyTorch stream)."""
+        for i in range(3):
+            step_fn(i)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(n):
+                step_fn(i)
+        g.replay()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    use_graph = not args.no_graph
+    t_sparse = timed(step_sparse, K, W, use_graph)
+    t_dense = timed(step_dense, K, W, use_graph)
+    t_sparse_eager = timed(step_sparse, K, 0, False)
+
+    # ---- per-kernel durations (stage calls on the same buffers) -------------------------
+    step_stage1(0)
+    k1 = event_avg_ms(step_stage1, K)
+    k2 = event_avg_ms(step_stage2, K)
+    k3 = event_avg_ms(step_stage3, K)
+
+    flops_alg = 3.0 * BH * L * L * d
+    flops_eq = 4.0 * BH * L * L * d
+    ms = t_sparse / K * 1e3
+    ms_dense = t_dense / K * 1e3
+    value = flops_alg / (t_sparse / K) / 1e12
+
+    # algorithmic bytes per launch (per head: stage 1 reads Q,K = 4 L d and writes kept values
+    # L^2 plus metadata L^2/8; stage 2 reads and writes L^2; stage 3 reads 1.125 L^2 + V and
+    # writes O = 4 L d)
+    bytes1 = BH * (4.0 * L * d + 1.125 * L * L)
+    bytes2 = BH * (2.0 * L * L)
+    bytes3 = BH * (1.125 * L * L + 4.0 * L * d)
+    kernels = {"sddmm_prune": (k1, bytes1), "sparse_softmax": (k2, bytes2), "spmm": (k3, bytes3)}
+    dom = max(kernels, key=lambda n: kernels[n][0])
+    dom_ms, dom_bytes = kernels[dom]
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "DFSS attention forward TFLOP/s (algorithmic 3*BH*L^2*d per step)",
+        "value": round(value, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": round(ms, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "L": L, "d": d, "N": w.N, "M": w.M,
+                   "buffer_sets": nsets, "cache": "warm" if args.warm else "cold (rotating buffer sets)",
+                   "launch": "hip graph of all timed steps" if use_graph else "direct"},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "avg_launch_ms": round(dom_ms, 5), "algorithmic_bytes_per_launch": int(dom_bytes)},
+        "extra": {
+            "dense_attention_ms_per_step": round(ms_dense, 5),
+            "speedup_vs_dense_attention": round(ms_dense / ms, 4),
+            "dense_equivalent_tflops": round(flops_eq / (t_sparse / K) / 1e12, 3),
+            "dense_attention_tflops": round(flops_eq / (t_dense / K) / 1e12, 3),
+            "ms_per_step_direct_launch": round(t_sparse_eager / K * 1e3, 5),
+            "kernel_ms": {k: round(v[0], 5) for k, v in kernels.items()},
+            "kernel_GBps": {k: round(v[1] / (v[0] * 1e-3) / 1e9, 1) for k, v in kernels.items()},
+            "sddmm_prune_tflops": round(2.0 * BH * L * L * d / (k1 * 1e-3) / 1e12, 2),
+            "sddmm_prune_frac_of_mfma_peak": round(2.0 * BH * L * L * d / (k1 * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        Qn, Kn, Vn = (synth.to_numpy_f32(t) for t in (Qc, Kc, Vc))
+        # bounded sample: as many heads as fit in roughly 10-30 s of host work
+        per_head_flops = 3.0 * L * L * d
+        heads = int(max(1, min(BH, 2.0e10 // per_head_flops)))
+        oracle.attention(Qn[:1], Kn[:1], Vn[:1], w.N, w.M, w.scale)  # load + warm
+        t0 = time.perf_counter()
+        oracle.attention(Qn[:heads], Kn[:heads], Vn[:heads], w.N, w.M, w.scale)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {
+            "value": round(heads * per_head_flops / dt / 1e12, 6), "unit": "TFLOP/s",
+            "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{heads} of {BH} heads of {w.name}, one pass, {dt:.2f} s"}
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

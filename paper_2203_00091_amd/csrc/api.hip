@@ -132,14 +132,16 @@ dfss_status dfss_meta_to_canonical(const void *meta, const dfss_shape *s, void *
     Dims D;
     if (!meta || !canon) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, true, &D)) return st;
-    return hip_status(dfss::launch_meta_reorder(meta, canon, D.BH, D.Lq, D.Lk / 16, true, (hipStream_t)stream));
+    if (misaligned(meta) || misaligned(canon)) return DFSS_ERR_SHAPE;
+    return hip_status(dfss::launch_meta_reorder(meta, canon, D.BH, D.Lq, D.Lk / 32, true, (hipStream_t)stream));
 }
 
 dfss_status dfss_meta_from_canonical(const void *canon, const dfss_shape *s, void *meta, void *stream) {
     Dims D;
     if (!meta || !canon) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, true, &D)) return st;
-    return hip_status(dfss::launch_meta_reorder(canon, meta, D.BH, D.Lq, D.Lk / 16, false, (hipStream_t)stream));
+    if (misaligned(meta) || misaligned(canon)) return DFSS_ERR_SHAPE;
+    return hip_status(dfss::launch_meta_reorder(canon, meta, D.BH, D.Lq, D.Lk / 32, false, (hipStream_t)stream));
 }
 
 const char *dfss_status_string(dfss_status st) {

@@ -1,8 +1,10 @@
 // Metadata word order (arXiv 2203.00091, Sec. 2.3 and App. A.1.1-A.1.2 define the 4-bit
 // codes and their packing into 16-bit words; the ORDER of the words in memory is free).
-// Canonical: uint16 [BH, Lq, W], W = Lk/16.  Library: [BH, Lq/16, W, 16], i.e. the words
-// of one 16-key chunk for 16 consecutive rows are adjacent, which is the order in which
-// both the pruning epilogue (writer) and the SpMM (reader) hold them across a wave.
+// Canonical: uint16 [BH, Lq, Lk/16], taken here as 32-bit words [BH, Lq, W], W = Lk/32 (two
+// consecutive 16-bit words, the earlier one in the low half).  Library: [BH, Lq/16, W, 16],
+// i.e. the 32-bit words of one 32-key chunk for 16 consecutive rows are adjacent, which is
+// the order in which both the pruning epilogue (writer) and the SpMM (reader) hold them
+// across a wave.
 #include "dfss_device.hpp"
 #include "dfss_kernels.hpp"
 
@@ -10,7 +12,7 @@ namespace dfss {
 
 namespace {
 
-__global__ __launch_bounds__(256) void k_meta_reorder(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
+__global__ __launch_bounds__(256) void k_meta_reorder(const uint32_t *__restrict__ src, uint32_t *__restrict__ dst,
                                                       long total, int Lq, int W, bool to_canonical) {
     const long i = (long)blockIdx.x * 256 + threadIdx.x;  // index in canonical order
     if (i >= total) return;
@@ -29,7 +31,7 @@ hipError_t launch_meta_reorder(const void *src, void *dst, int BH, int Lq, int W
                                hipStream_t st) {
     const long total = (long)BH * Lq * W;
     const unsigned grid = (unsigned)((total + 255) / 256);
-    hipLaunchKernelGGL(k_meta_reorder, dim3(grid), dim3(256), 0, st, (const uint16_t *)src, (uint16_t *)dst, total,
+    hipLaunchKernelGGL(k_meta_reorder, dim3(grid), dim3(256), 0, st, (const uint32_t *)src, (uint32_t *)dst, total,
                        Lq, W, to_canonical);
     return hipGetLastError();
 }

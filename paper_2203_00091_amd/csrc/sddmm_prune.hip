@@ -3,15 +3,22 @@
 // (arXiv 2203.00091, Sec. 3.4 and App. A.1.2).  The same mainloop with a plain
 // bfloat16 store is the first stage of the dense baseline (Eq. 1).
 //
-// Tiling.  One workgroup (4 waves) computes 64 queries x 128 keys; each wave owns
-// 32 queries x 64 keys as 2 x 4 MFMA tiles of 16 x 16.  The product is formed transposed
-// (keys on the MFMA rows, queries on its columns) because a lane owns four consecutive
-// ROWS of one column: with that orientation a lane owns runs of four consecutive keys of
-// one query, which is what the selection needs.  Within a 64-key block the key that
-// feeds MFMA row i of tile t is 16*(i/4) + 4*t + i%4, so that after the four tiles lane
-// (column c, row group g) holds the 16 consecutive keys 16g .. 16g+15 of query c: eight
-// kept values (16 bytes, one store) and four 4-bit codes (one 16-bit word).  This plays
-// the role of the column interleaving of App. A.1.2, chosen here for the MFMA layout.
+// Orientation.  The product is formed transposed (keys on the MFMA rows, queries on its
+// columns) because a lane owns four consecutive ROWS of one column of the 16x16 result:
+// with keys on the rows a lane owns runs of four consecutive keys of one query, which is
+// what the selection needs -- no cross-lane traffic.  (App. A.1.2 reaches the same end on
+// its hardware by interleaving the columns of one operand.)
+//
+// Streaming.  A workgroup (4 waves) owns 64*NQ queries; each wave keeps the Q operand of
+// its 16*NQ queries in registers for the whole kernel and walks over blocks of 128 keys.
+// K blocks are copied global -> LDS by the direct-to-LDS load (no register round trip),
+// double buffered, XOR-swizzled so the 16-byte operand reads are conflict free.
+//
+// Key order inside a 128-key block.  LDS row slot 16*t + i (tile t = 0..7, MFMA row i)
+// holds key 32*(i/4) + 4*t + i%4.  After tiles 0..3 lane (column c, row group g) holds the
+// 16 consecutive keys 32g .. 32g+15 of query c, after tiles 4..7 the next 16: per
+// 128-key block a lane emits 32 contiguous bytes of kept values and one 32-bit word of
+// metadata (two canonical 16-bit words), and a row receives 128 contiguous bytes.
 #include "dfss_device.hpp"
 #include "dfss_kernels.hpp"
 
@@ -19,18 +26,13 @@ namespace dfss {
 
 namespace {
 
-constexpr int TQ = 64;    // queries per workgroup
-constexpr int TK = 128;   // keys per workgroup
 constexpr int NT = 256;   // threads per workgroup
+constexpr int KB = 128;   // keys per block
 
 enum { MODE_2TO4 = 0, MODE_1TO2 = 1, MODE_DENSE = 2 };
 
-// Position of key row `r` (0..127) inside the LDS tile: within each block of 64 keys the
-// two 2-bit fields (r/4)%4 and (r/16)%4 are swapped, which makes the 16 rows a wave reads
-// for one MFMA tile adjacent in LDS (conflict-free 16-byte reads).
-__device__ __forceinline__ int lds_key_slot(int r) {
-    return (r & 64) | ((r & 0xC) << 2) | ((r & 0x30) >> 2) | (r & 3);
-}
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void global_cvoid_t;
 
 // The six comparisons of a run of four scores are taken as 64-bit lane masks (one bit per
 // lane of the wave) so that the rank logic runs on the scalar unit, off the vector ALU
@@ -71,109 +73,195 @@ __device__ __forceinline__ void select_1of2(float s0, float s1, float s2, float 
     code = (c01 ? (1u << SHIFT) : 0u) | (c23 ? (12u << SHIFT) : (8u << SHIFT));
 }
 
-template <int D, int MODE>
+// Workgroups are handed to the 8 XCDs round-robin by linear id; each XCD has its own L2.
+// Give every XCD one contiguous range of work items so that the workgroups sharing one
+// head's K meet in one L2.
+__device__ __forceinline__ unsigned xcd_contiguous(unsigned id, unsigned total) {
+    const unsigned per = total / 8;
+    return id < per * 8 ? (id % 8) * per + id / 8 : id;
+}
+
+// PRESCALE: the scale is a power of two and is applied (exactly) to the Q operand once,
+// instead of to every accumulator.
+template <int D, int MODE, int NQ, bool PRESCALE>
 __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
-                                              int Lq, int Lk, float scale, uint32_t *__restrict__ out,
-                                              uint16_t *__restrict__ meta) {
-    constexpr int KC = D / 8;       // 16-byte chunks per row
-    constexpr int KROWS = TK + 1;   // +1 row of padding: conflict-free LDS writes
-    constexpr int QROWS = TQ + 1;
-    __shared__ u32x4 Ks[KC * KROWS];
-    __shared__ u32x4 Qs[KC * QROWS];
+                                                 int Lq, int Lk, float scale, int ksplit, int blocks_per_wg,
+                                                 uint32_t *__restrict__ out, uint32_t *__restrict__ meta) {
+    constexpr int CPR = D / 8;           // 16-byte chunks per row
+    constexpr int TILE = KB * CPR;       // chunks per K block
+    constexpr int LPT = TILE / NT;       // direct-to-LDS loads per thread per block
+    constexpr int STEPS = D / 32;        // MFMA k-steps
+    constexpr int TQ = 64 * NQ;          // queries per workgroup
+    __shared__ u32x4 Ks[2][TILE];
 
     const int tid = threadIdx.x;
-    const int bh = blockIdx.z;
-    const int q0 = blockIdx.y * TQ;
-    const int k0 = blockIdx.x * TK;
-
-    {
-        const u32x4 *Kg = reinterpret_cast<const u32x4 *>(K + ((size_t)bh * Lk + k0) * D);
-        for (int c = tid; c < TK * KC; c += NT) {
-            const int row = c / KC, kc = c % KC;
-            Ks[kc * KROWS + lds_key_slot(row)] = Kg[c];
-        }
-        const u32x4 *Qg = reinterpret_cast<const u32x4 *>(Q + ((size_t)bh * Lq + q0) * D);
-        for (int c = tid; c < TQ * KC; c += NT) {
-            const int row = c / KC, kc = c % KC;
-            Qs[kc * QROWS + row] = Qg[c];
-        }
-    }
-    __syncthreads();
-
     const int w = tid >> 6, l = tid & 63, li = l & 15, kb = l >> 4;
-    const int wq = w & 1, wk = w >> 1;
 
-    f32x4 acc[2][4];
-#pragma unroll
-    for (int qs = 0; qs < 2; ++qs)
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) acc[qs][ks] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // work item -> (head, query tile, key range)
+    const unsigned qtiles = Lq / TQ;
+    const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int ks_id = item % ksplit;
+    const int qt = (item / ksplit) % qtiles;
+    const int bh = item / (ksplit * qtiles);
+    const int jb0 = ks_id * blocks_per_wg;
+    const int q0 = qt * TQ + w * 16 * NQ;
 
+    const __bf16 *Kh = K + (size_t)bh * Lk * D;
+
+    // per-thread source offsets of the direct-to-LDS copies: LDS position p (16-byte units)
+    // = slot * CPR + (c ^ (slot & 7)) holds chunk c of the key stored in row slot `slot`
+    int src_off[LPT];
 #pragma unroll
-    for (int step = 0; step < D / 32; ++step) {
-        bf16x8 bq[2], ak[4];
-        const int kc = 4 * step + kb;
-#pragma unroll
-        for (int qs = 0; qs < 2; ++qs)
-            bq[qs] = __builtin_bit_cast(bf16x8, Qs[kc * QROWS + 32 * wq + 16 * qs + li]);
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-            ak[ks] = __builtin_bit_cast(bf16x8, Ks[kc * KROWS + 64 * wk + 16 * ks + li]);
-#pragma unroll
-        for (int qs = 0; qs < 2; ++qs)
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) acc[qs][ks] = mfma16(ak[ks], bq[qs], acc[qs][ks]);
+    for (int i = 0; i < LPT; ++i) {
+        const int p = i * NT + tid;
+        const int slot = p / CPR, c = (p % CPR) ^ (slot & 7);
+        const int key = (slot & 3) | (((slot >> 4) & 7) << 2) | (((slot >> 2) & 3) << 5);
+        src_off[i] = key * D + c * 8;
     }
+    auto issue_block = [&](int jb, int buf) {
+        const __bf16 *src = Kh + (size_t)jb * KB * D;
+#pragma unroll
+        for (int i = 0; i < LPT; ++i)
+            __builtin_amdgcn_global_load_lds((global_cvoid_t *)(src + src_off[i]),
+                                             (lds_void_t *)&Ks[buf][i * NT + w * 64], 16, 0, 0);
+    };
 
-    // acc[qs][ks][r] = dot(Q[q], K[key]) with q = q0 + 32 wq + 16 qs + li,
-    // key = k0 + 64 wk + 16 kb + 4 ks + r.
-    const int kbase = k0 + 64 * wk + 16 * kb;
+    issue_block(jb0, 0);
+
+    // Q operand: lane (column li, chunk kb) of MFMA step s holds Q[q][32 s + 8 kb .. +7]
+    bf16x8 bq[NQ][STEPS];
 #pragma unroll
-    for (int qs = 0; qs < 2; ++qs) {
-        const int q = q0 + 32 * wq + 16 * qs + li;
-        const size_t row = (size_t)bh * Lq + q;
-        if constexpr (MODE == MODE_DENSE) {
-            uint32_t p[8];
+    for (int qs = 0; qs < NQ; ++qs)
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                p[2 * ks] = pack_bf16x2(acc[qs][ks][0] * scale, acc[qs][ks][1] * scale);
-                p[2 * ks + 1] = pack_bf16x2(acc[qs][ks][2] * scale, acc[qs][ks][3] * scale);
+        for (int s = 0; s < STEPS; ++s) {
+            const u32x4 raw = *reinterpret_cast<const u32x4 *>(Q + ((size_t)bh * Lq + q0 + 16 * qs + li) * D +
+                                                               32 * s + 8 * kb);
+            if constexpr (PRESCALE) {
+                u32x4 sc;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    sc[e] = pack_bf16x2(bf16_lo_to_f32(raw[e]) * scale, bf16_hi_to_f32(raw[e]) * scale);
+                bq[qs][s] = __builtin_bit_cast(bf16x8, sc);
+            } else {
+                bq[qs][s] = __builtin_bit_cast(bf16x8, raw);
             }
-            u32x4 *dst = reinterpret_cast<u32x4 *>(out + (row * Lk + kbase) / 2);
-            dst[0] = u32x4{p[0], p[1], p[2], p[3]};
-            dst[1] = u32x4{p[4], p[5], p[6], p[7]};
-        } else {
-            u32x4 pk;
-            uint32_t word = 0;
+        }
+
+    const int rb0 = q0 >> 4;                 // first 16-row block of this wave
+    const int W32 = Lk / 32;                 // 32-bit metadata words per row
+
+    for (int it = 0; it < blocks_per_wg; ++it) {
+        const int jb = jb0 + it;
+        const int buf = it & 1;
+        // this block's copies (issued one iteration ago) have landed for every wave
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        __syncthreads();
+        // every wave has also finished reading the other buffer: refill it
+        if (it + 1 < blocks_per_wg) issue_block(jb + 1, buf ^ 1);
+
+        uint32_t mword[NQ];
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                const float s0 = acc[qs][ks][0] * scale, s1 = acc[qs][ks][1] * scale;
-                const float s2 = acc[qs][ks][2] * scale, s3 = acc[qs][ks][3] * scale;
-                float lo, hi;
-                uint32_t code;
-                if constexpr (MODE == MODE_2TO4) select_2of4(s0, s1, s2, s3, 4 * ks, lo, hi, code);
-                else select_1of2(s0, s1, s2, s3, 4 * ks, lo, hi, code);
-                pk[ks] = pack_bf16x2(lo, hi);
-                word |= code;
+        for (int qs = 0; qs < NQ; ++qs) mword[qs] = 0;
+
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            f32x4 acc[NQ][4];
+#pragma unroll
+            for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) acc[qs][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                bf16x8 ak[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int slot = 16 * (4 * half + t) + li;
+                    ak[t] = __builtin_bit_cast(bf16x8, Ks[buf][slot * CPR + ((4 * s + kb) ^ (li & 7))]);
+                }
+#pragma unroll
+                for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) acc[qs][t] = mfma16(ak[t], bq[qs][s], acc[qs][t]);
             }
-            *reinterpret_cast<u32x4 *>(out + (row * (size_t)(Lk / 2) + kbase / 2) / 2) = pk;
-            const int W = Lk / 16;
-            meta[(((size_t)bh * (Lq / 16) + q / 16) * W + kbase / 16) * 16 + li] = (uint16_t)word;
+            // acc[qs][t][r] = score of query q0 + 16 qs + li and key 128 jb + 32 kb + 16 half + 4 t + r
+            const int kbase = KB * jb + 32 * kb + 16 * half;
+#pragma unroll
+            for (int qs = 0; qs < NQ; ++qs) {
+                const size_t row = (size_t)bh * Lq + q0 + 16 * qs + li;
+                if constexpr (MODE == MODE_DENSE) {
+                    uint32_t p[8];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        f32x4 a = acc[qs][t];
+                        if constexpr (!PRESCALE) a = a * scale;
+                        p[2 * t] = pack_bf16x2(a[0], a[1]);
+                        p[2 * t + 1] = pack_bf16x2(a[2], a[3]);
+                    }
+                    u32x4 *dst = reinterpret_cast<u32x4 *>(out + (row * Lk + kbase) / 2);
+                    dst[0] = u32x4{p[0], p[1], p[2], p[3]};
+                    dst[1] = u32x4{p[4], p[5], p[6], p[7]};
+                } else {
+                    u32x4 pk;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        f32x4 a = acc[qs][t];
+                        if constexpr (!PRESCALE) a = a * scale;
+                        float lo, hi;
+                        uint32_t code;
+                        if constexpr (MODE == MODE_2TO4)
+                            select_2of4(a[0], a[1], a[2], a[3], 16 * half + 4 * t, lo, hi, code);
+                        else
+                            select_1of2(a[0], a[1], a[2], a[3], 16 * half + 4 * t, lo, hi, code);
+                        pk[t] = pack_bf16x2(lo, hi);
+                        mword[qs] |= code;
+                    }
+                    *reinterpret_cast<u32x4 *>(out + (row * (size_t)(Lk / 2) + kbase / 2) / 2) = pk;
+                }
+            }
+        }
+        if constexpr (MODE != MODE_DENSE) {
+#pragma unroll
+            for (int qs = 0; qs < NQ; ++qs)
+                meta[(((size_t)bh * (Lq / 16) + rb0 + qs) * W32 + 4 * jb + kb) * 16 + li] = mword[qs];
         }
     }
+}
+
+inline bool is_pow2(float x) {
+    int e;
+    return frexpf(x, &e) == 0.5f;
+}
+
+template <int MODE, int NQ>
+hipError_t launch_nq(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale, void *out,
+                     void *meta, hipStream_t st) {
+    const int qtiles = Lq / (64 * NQ);
+    const int kblocks = Lk / KB;
+    // split the key range until the grid has a few workgroups per compute unit
+    int ksplit = 1;
+    while ((long)BH * qtiles * ksplit < 1024 && kblocks % (ksplit * 2) == 0) ksplit *= 2;
+    if ((long)BH * qtiles * ksplit < 1024 && kblocks % 3 == 0 && ksplit == 1) ksplit = 3;
+    const int per_wg = kblocks / ksplit;
+    const unsigned grid = (unsigned)((long)BH * qtiles * ksplit);
+    const bool pre = is_pow2(scale);
+#define DFSS_LAUNCH(DD, PRE)                                                                              \
+    hipLaunchKernelGGL((k_sddmm<DD, MODE, NQ, PRE>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)Q,     \
+                       (const __bf16 *)K, Lq, Lk, scale, ksplit, per_wg, (uint32_t *)out, (uint32_t *)meta)
+    if (d == 64) {
+        if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
+    } else {
+        if (pre) DFSS_LAUNCH(128, true); else DFSS_LAUNCH(128, false);
+    }
+#undef DFSS_LAUNCH
+    return hipGetLastError();
 }
 
 template <int MODE>
 hipError_t launch(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale, void *out,
                   void *meta, hipStream_t st) {
-    dim3 grid(Lk / TK, Lq / TQ, BH), block(NT);
-    if (d == 64)
-        hipLaunchKernelGGL((k_sddmm<64, MODE>), grid, block, 0, st, (const __bf16 *)Q, (const __bf16 *)K, Lq, Lk,
-                           scale, (uint32_t *)out, (uint16_t *)meta);
-    else
-        hipLaunchKernelGGL((k_sddmm<128, MODE>), grid, block, 0, st, (const __bf16 *)Q, (const __bf16 *)K, Lq, Lk,
-                           scale, (uint32_t *)out, (uint16_t *)meta);
-    return hipGetLastError();
+    // 32 queries per wave when the query count allows it, else 16
+    if (Lq % 128 == 0) return launch_nq<MODE, 2>(Q, K, BH, Lq, Lk, d, scale, out, meta, st);
+    return launch_nq<MODE, 1>(Q, K, BH, Lq, Lk, d, scale, out, meta, st);
 }
 
 }  // namespace

@@ -1,13 +1,20 @@
 // Stage 3 of the DFSS forward pass: O = A_sparse V with the 2:4-compressed attention
 // weights (arXiv 2203.00091, Sec. 3.1), on the gfx950 structured-sparse matrix
-// instruction v_smfmac_f32_16x16x64_bf16: per lane eight kept weights (one 16-byte load,
-// exactly what stage 1 stored) plus the lane's 16-bit metadata word as the index operand.
-// Because 1:2 pruning is stored with the same 4-bit codes it runs through the same kernel.
-// The dense variant (full P V of Eq. 1, for the baseline) shares the V staging and uses
-// two v_mfma_f32_16x16x32_bf16 per 64 keys.
+// instruction v_smfmac_f32_16x16x64_bf16.  Per 128-key block a lane loads the 32 bytes of
+// kept weights and the 32-bit metadata word that the same lane of stage 1 stored; the two
+// halves of the word are the index operands of two instructions (selected with ABID), so
+// nothing is decoded or shuffled.  1:2 pruning is stored with the same codes and runs
+// through the same kernel.  The dense variant (P V of Eq. 1, for the baseline) shares the
+// V staging and uses v_mfma_f32_16x16x32_bf16.
 //
-// V tiles (64 keys x d) are staged row-major in LDS; the B operand (keys along the
-// contraction, one d-column per lane) is produced by the transposing LDS read.
+// V blocks (128 keys x d) are copied global -> LDS by the direct-to-LDS load, double
+// buffered, row-major with an XOR swizzle of the 16-byte chunks; the B operand (keys along
+// the contraction, one d-column per lane) comes from the transposing LDS read.
+//
+// Which keys an instruction contracts over is free as long as A and B agree.  Sparse
+// instruction h (0/1) of a block takes, for its 16-wide contraction chunk c, the keys
+// 32c + 16h .. +15 of the block -- the 16 keys whose kept weights lane group c holds in
+// half h of its 32 bytes.
 #include "dfss_device.hpp"
 #include "dfss_kernels.hpp"
 
@@ -15,24 +22,80 @@ namespace dfss {
 
 namespace {
 
-constexpr int NT = 256;        // 4 waves
-constexpr int RB = 1;          // 16-row blocks per wave
-constexpr int TQ = 4 * 16 * RB;  // queries per workgroup
-constexpr int KT = 64;         // keys per step
+constexpr int NT = 256;   // 4 waves
+constexpr int KB = 128;   // keys per block
 
-template <int D, bool SPARSE>
-__global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, const uint16_t *__restrict__ meta,
-                                           const __bf16 *__restrict__ V, int Lq, int Lk,
-                                           uint16_t *__restrict__ O) {
-    constexpr int VSTRIDE = D + 16;  // bf16 elements per LDS row (+32 bytes of padding)
-    constexpr int DS = D / 16;       // 16-column output tiles
-    __shared__ __attribute__((aligned(16))) __bf16 Vs[KT * VSTRIDE];
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void global_cvoid_t;
+
+__device__ __forceinline__ unsigned xcd_contiguous(unsigned id, unsigned total) {
+    const unsigned per = total / 8;
+    return id < per * 8 ? (id % 8) * per + id / 8 : id;
+}
+
+template <int D, bool SPARSE, int RB>
+__global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, const uint32_t *__restrict__ meta,
+                                              const __bf16 *__restrict__ V, int Lq, int Lk,
+                                              uint16_t *__restrict__ O) {
+    constexpr int CPR = D / 8;          // 16-byte chunks per V row
+    constexpr int TILE = KB * CPR;      // chunks per V block
+    constexpr int LPT = TILE / NT;      // direct-to-LDS loads per thread per block
+    constexpr int DS = D / 16;          // 16-column output tiles
+    constexpr int TQ = 64 * RB;         // queries per workgroup
+    __shared__ u32x4 Vs[2][TILE];
 
     const int tid = threadIdx.x;
-    const int bh = blockIdx.y;
-    const int q0 = blockIdx.x * TQ;
     const int w = tid >> 6, l = tid & 63, li = l & 15, kb = l >> 4;
-    const int W = Lk / 16;
+
+    const unsigned qtiles = Lq / TQ;
+    const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int qt = item % qtiles;
+    const int bh = item / qtiles;
+    const int rb0 = (qt * TQ >> 4) + w * RB;   // first 16-row block of this wave
+    const int nblocks = Lk / KB;
+    const int W32 = Lk / 32;
+
+    // LDS position p (16-byte units) = row * CPR + (c ^ ((row & 3) << 1)) holds chunk c of key `row`
+    const __bf16 *Vh = V + (size_t)bh * Lk * D;
+    int src_off[LPT];
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+        const int p = i * NT + tid;
+        const int row = p / CPR, c = (p % CPR) ^ ((row & 3) << 1);
+        src_off[i] = row * D + c * 8;
+    }
+    auto issue_block = [&](int jb, int buf) {
+        const __bf16 *src = Vh + (size_t)jb * KB * D;
+#pragma unroll
+        for (int i = 0; i < LPT; ++i)
+            __builtin_amdgcn_global_load_lds((global_cvoid_t *)(src + src_off[i]),
+                                             (lds_void_t *)&Vs[buf][i * NT + w * 64], 16, 0, 0);
+    };
+
+    // A operand of one block
+    struct AFrag {
+        u32x4 v[SPARSE ? 2 : 4];
+        uint32_t idx;
+    };
+    auto load_a = [&](int jb, AFrag (&a)[RB]) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            const size_t row = (size_t)bh * Lq + (size_t)(rb0 + rb) * 16 + li;
+            if constexpr (SPARSE) {
+                // kept weights of keys 128 jb + 32 kb .. +31: 16 of them, 32 bytes
+                const u32x4 *pr = reinterpret_cast<const u32x4 *>(P + row * (size_t)(Lk / 4)) + jb * 8 + kb * 2;
+                a[rb].v[0] = pr[0];
+                a[rb].v[1] = pr[1];
+                a[rb].idx = meta[(((size_t)bh * (Lq / 16) + rb0 + rb) * W32 + 4 * jb + kb) * 16 + li];
+            } else {
+                // dense weights: MFMA m takes keys 128 jb + 32 m + 8 kb .. +7
+                const u32x4 *pr = reinterpret_cast<const u32x4 *>(P + row * (size_t)(Lk / 2)) + jb * 16 + kb;
+#pragma unroll
+                for (int m = 0; m < 4; ++m) a[rb].v[m] = pr[4 * m];
+                a[rb].idx = 0;
+            }
+        }
+    };
 
     f32x4 acc[RB][DS];
 #pragma unroll
@@ -40,71 +103,79 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
 #pragma unroll
         for (int ds = 0; ds < DS; ++ds) acc[rb][ds] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // row of P this lane feeds (A operand row = li)
-    const int rowblk0 = (q0 >> 4) + w * RB;
-    const int nsteps = Lk / KT;
+    // transposing read: lane li of a 16-lane group addresses V[key0 + li/4][col0 + 4*(li%4)]
+    const int tr_row = li >> 2;
+    const int tr_sub = (li >> 1) & 1;      // which 16-byte chunk of the 32-byte column group
+    const int tr_byte = 8 * (li & 1);
+    const int tr_xor = tr_row << 1;        // (row & 3) << 1, key0 is a multiple of 4
 
-    // per-lane offsets of the four transposing reads of one 16-column tile:
-    // source lane s = li reads 4 elements at V[key0 + s/4][col0 + 4*(s%4)]
-    const int tr_row = li >> 2, tr_col = 4 * (li & 3);
+    issue_block(0, 0);
+    AFrag a_cur[RB], a_nxt[RB];
+    load_a(0, a_cur);
 
-    for (int step = 0; step < nsteps; ++step) {
-        __syncthreads();  // previous step's LDS reads are done
-        {
-            const u32x4 *Vg = reinterpret_cast<const u32x4 *>(V + ((size_t)bh * Lk + (size_t)step * KT) * D);
-            for (int c = tid; c < KT * (D / 8); c += NT) {
-                const int row = c / (D / 8), kc = c % (D / 8);
-                *reinterpret_cast<u32x4 *>(&Vs[row * VSTRIDE + kc * 8]) = Vg[c];
-            }
-        }
-        // A operands for this step (global loads overlap the LDS fill)
-        bf16x8 a_sp[RB];
-        int idx[RB];
-        bf16x8 a_d0[RB], a_d1[RB];
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            const size_t row = (size_t)bh * Lq + (size_t)(rowblk0 + rb) * 16 + li;
-            if constexpr (SPARSE) {
-                const u32x4 *pr = reinterpret_cast<const u32x4 *>(P + row * (size_t)(Lk / 4));
-                a_sp[rb] = __builtin_bit_cast(bf16x8, pr[step * 4 + kb]);
-                idx[rb] = meta[(((size_t)bh * (Lq / 16) + rowblk0 + rb) * W + step * 4 + kb) * 16 + li];
-            } else {
-                const u32x4 *pr = reinterpret_cast<const u32x4 *>(P + row * (size_t)(Lk / 2));
-                a_d0[rb] = __builtin_bit_cast(bf16x8, pr[step * 8 + kb]);
-                a_d1[rb] = __builtin_bit_cast(bf16x8, pr[step * 8 + 4 + kb]);
-            }
-        }
+    for (int jb = 0; jb < nblocks; ++jb) {
+        const int buf = jb & 1;
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this block's V copies and A loads are in
         __syncthreads();
+        if (jb + 1 < nblocks) {
+            issue_block(jb + 1, buf ^ 1);
+            load_a(jb + 1, a_nxt);
+        }
+        const char *vbase = reinterpret_cast<const char *>(&Vs[buf][0]);
+        auto tr = [&](int key0, int ds) {
+            const int row = key0 + tr_row;
+            const int chunk = (2 * ds + tr_sub) ^ tr_xor;
+            return lds_read_tr16(vbase + (row * CPR + chunk) * 16 + tr_byte);
+        };
+        if constexpr (SPARSE) {
 #pragma unroll
-        for (int ds = 0; ds < DS; ++ds) {
-            const __bf16 *base = &Vs[tr_row * VSTRIDE + 16 * ds + tr_col];
-            const s16x4 t0 = lds_read_tr16(base + (8 * kb) * VSTRIDE);
-            const s16x4 t1 = lds_read_tr16(base + (8 * kb + 4) * VSTRIDE);
-            const s16x4 t2 = lds_read_tr16(base + (32 + 8 * kb) * VSTRIDE);
-            const s16x4 t3 = lds_read_tr16(base + (32 + 8 * kb + 4) * VSTRIDE);
-            const s16x8 lo = __builtin_shufflevector(t0, t1, 0, 1, 2, 3, 4, 5, 6, 7);
-            const s16x8 hi = __builtin_shufflevector(t2, t3, 0, 1, 2, 3, 4, 5, 6, 7);
+            for (int h = 0; h < 2; ++h) {
+                const int k0 = 32 * (kb >> 1) + 16 * h + 8 * (kb & 1);
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                if constexpr (SPARSE) {
-                    const s16x16 b = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13,
-                                                             14, 15);
-                    acc[rb][ds] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(
-                        a_sp[rb], __builtin_bit_cast(bf16x16, b), acc[rb][ds], idx[rb], 0, 0);
-                } else {
-                    acc[rb][ds] = mfma16(a_d0[rb], __builtin_bit_cast(bf16x8, lo), acc[rb][ds]);
-                    acc[rb][ds] = mfma16(a_d1[rb], __builtin_bit_cast(bf16x8, hi), acc[rb][ds]);
+                for (int ds = 0; ds < DS; ++ds) {
+                    const s16x4 t0 = tr(k0, ds), t1 = tr(k0 + 4, ds), t2 = tr(64 + k0, ds), t3 = tr(64 + k0 + 4, ds);
+                    const s16x8 lo = __builtin_shufflevector(t0, t1, 0, 1, 2, 3, 4, 5, 6, 7);
+                    const s16x8 hi = __builtin_shufflevector(t2, t3, 0, 1, 2, 3, 4, 5, 6, 7);
+                    const bf16x16 b = __builtin_bit_cast(
+                        bf16x16, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15));
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb) {
+                        const bf16x8 a = __builtin_bit_cast(bf16x8, a_cur[rb].v[h]);
+                        if (h == 0)
+                            acc[rb][ds] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a, b, acc[rb][ds],
+                                                                                    (int)a_cur[rb].idx, 0, 0);
+                        else
+                            acc[rb][ds] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a, b, acc[rb][ds],
+                                                                                    (int)a_cur[rb].idx, 0, 1);
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const int k0 = 32 * m + 8 * kb;
+#pragma unroll
+                for (int ds = 0; ds < DS; ++ds) {
+                    const s16x4 t0 = tr(k0, ds), t1 = tr(k0 + 4, ds);
+                    const bf16x8 b = __builtin_bit_cast(bf16x8, __builtin_shufflevector(t0, t1, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+                        acc[rb][ds] = mfma16(__builtin_bit_cast(bf16x8, a_cur[rb].v[m]), b, acc[rb][ds]);
                 }
             }
         }
+        if (jb + 1 < nblocks) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) a_cur[rb] = a_nxt[rb];
+        }
     }
 
-    // acc[rb][ds][r] = O[q][16 ds + li], q = 16 (rowblk0 + rb) + 4 kb + r
+    // acc[rb][ds][r] = O[q][16 ds + li], q = 16 (rb0 + rb) + 4 kb + r
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const size_t q = (size_t)bh * Lq + (size_t)(rowblk0 + rb) * 16 + 4 * kb + r;
+            const size_t q = (size_t)bh * Lq + (size_t)(rb0 + rb) * 16 + 4 * kb + r;
 #pragma unroll
             for (int ds = 0; ds < DS; ++ds)
                 O[q * D + 16 * ds + li] = (uint16_t)(pack_bf16x2(acc[rb][ds][r], 0.f) & 0xFFFFu);
@@ -114,13 +185,18 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
 template <bool SPARSE>
 hipError_t launch(const void *P, const void *meta, const void *V, int BH, int Lq, int Lk, int d, void *O,
                   hipStream_t st) {
-    dim3 grid(Lq / TQ, BH), block(NT);
-    if (d == 64)
-        hipLaunchKernelGGL((k_av<64, SPARSE>), grid, block, 0, st, (const uint32_t *)P, (const uint16_t *)meta,
-                           (const __bf16 *)V, Lq, Lk, (uint16_t *)O);
-    else
-        hipLaunchKernelGGL((k_av<128, SPARSE>), grid, block, 0, st, (const uint32_t *)P, (const uint16_t *)meta,
-                           (const __bf16 *)V, Lq, Lk, (uint16_t *)O);
+    // two row blocks per wave when that still leaves a few workgroups per compute unit
+    const bool rb2 = (Lq % 128 == 0) && ((long)BH * (Lq / 128) >= 1024);
+    const unsigned grid = (unsigned)((long)BH * (Lq / (rb2 ? 128 : 64)));
+#define DFSS_LAUNCH(DD, RR)                                                                                   \
+    hipLaunchKernelGGL((k_av<DD, SPARSE, RR>), dim3(grid), dim3(NT), 0, st, (const uint32_t *)P,              \
+                       (const uint32_t *)meta, (const __bf16 *)V, Lq, Lk, (uint16_t *)O)
+    if (d == 64) {
+        if (rb2) DFSS_LAUNCH(64, 2); else DFSS_LAUNCH(64, 1);
+    } else {
+        if (rb2) DFSS_LAUNCH(128, 2); else DFSS_LAUNCH(128, 1);
+    }
+#undef DFSS_LAUNCH
     return hipGetLastError();
 }
 

@@ -198,9 +198,9 @@ def test_meta_order_round_trip():
     back = dfss.dfss_meta_to_canonical(lib, s)
     torch.cuda.synchronize()
     assert torch.equal(back.cpu(), canon)
-    # documented order: lib[bh][r/16][w][r%16] = canon[bh][r][w]
-    l4 = lib.cpu().view(3, 8, 16, 16)
-    assert torch.equal(l4.permute(0, 1, 3, 2).reshape(3, 128, 16), canon)
+    # documented order: lib32[bh][r/16][v][r%16] = canon32[bh][r][v]
+    l4 = lib.cpu().view(torch.int32).view(3, 8, 8, 16)
+    assert torch.equal(l4.permute(0, 1, 3, 2).reshape(3, 128, 8), canon.view(torch.int32).view(3, 128, 8))
 
 
 # ----------------------------------------------------------------------------------
