@@ -9,7 +9,8 @@ the named workload.  Prints ONE JSON line.
                   sparse path: 3 * BH * L^2 * d per step (2 L^2 d dense QK^T + L^2 d SpMM).
   extra           the same step for ``dense_attention`` on the same GPU, the speedup, the
                   dense-equivalent rate (4 * BH * L^2 * d), warm-cache figures.
-  roofline        dominant kernel, algorithmic bytes / measured launch duration vs HBM peak.
+  roofline        the kernel of the step (dfss_attention is one fused kernel): algorithmic
+                  FLOPs / measured launch duration against the dense bf16 MFMA peak.
   cpu_baseline    the CPU oracle timed on the host cores (context only).
 
 Inputs are resident in HBM before timing starts.  By default the steps rotate over enough
@@ -97,6 +98,17 @@ def main():
         b = sets[i % nsets]
         dfss.dense_attention(b["Q"], b["K"], b["V"], s, w.scale, O=b["O"], ws=b["ws"])
 
+    def step_dense_fused(i):
+        b = sets[i % nsets]
+        dfss.dense_attention_fused(b["Q"], b["K"], b["V"], s, w.scale, O=b["O"])
+
+    def step_sparse_staged(i):
+        os.environ["DFSS_ATTENTION_PATH"] = "staged"
+        try:
+            step_sparse(i)
+        finally:
+            del os.environ["DFSS_ATTENTION_PATH"]
+
     def step_stage1(i):
         b = sets[i % nsets]
         n_vals = dfss.dfss_vals_bytes(s)
@@ -158,9 +170,12 @@ def main():
     use_graph = not args.no_graph
     t_sparse = timed(step_sparse, K, W, use_graph)
     t_dense = timed(step_dense, K, W, use_graph)
+    t_dense_fused = timed(step_dense_fused, K, W, use_graph)
+    t_staged = timed(step_sparse_staged, K, W, use_graph)
     t_sparse_eager = timed(step_sparse, K, 0, False)
 
-    # ---- per-kernel durations (stage calls on the same buffers) -------------------------
+    # ---- per-kernel durations (events around a graph of K launches of one kernel) ------
+    k_fused = event_avg_ms(step_sparse, K)       # dfss_attention is ONE kernel
     step_stage1(0)
     k1 = event_avg_ms(step_stage1, K)
     k2 = event_avg_ms(step_stage2, K)
@@ -170,18 +185,19 @@ def main():
     flops_eq = 4.0 * BH * L * L * d
     ms = t_sparse / K * 1e3
     ms_dense = t_dense / K * 1e3
+    ms_dense_fused = t_dense_fused / K * 1e3
+    ms_staged = t_staged / K * 1e3
     value = flops_alg / (t_sparse / K) / 1e12
 
-    # algorithmic bytes per launch (per head: stage 1 reads Q,K = 4 L d and writes kept values
-    # L^2 plus metadata L^2/8; stage 2 reads and writes L^2; stage 3 reads 1.125 L^2 + V and
-    # writes O = 4 L d)
+    # Algorithmic work per launch.  Fused kernel: 3 L^2 d flops per head (2 L^2 d for Q K^T,
+    # L^2 d for the half-dense P V), against the dense bf16 MFMA peak.  Stage kernels
+    # (bytes per head): stage 1 reads Q,K = 4 L d and writes kept values L^2 plus metadata
+    # L^2/8; stage 2 reads and writes L^2; stage 3 reads 1.125 L^2 + V and writes O.
+    achieved = flops_alg / (k_fused * 1e-3) / 1e12
     bytes1 = BH * (4.0 * L * d + 1.125 * L * L)
     bytes2 = BH * (2.0 * L * L)
     bytes3 = BH * (1.125 * L * L + 4.0 * L * d)
     kernels = {"sddmm_prune": (k1, bytes1), "sparse_softmax": (k2, bytes2), "spmm": (k3, bytes3)}
-    dom = max(kernels, key=lambda n: kernels[n][0])
-    dom_ms, dom_bytes = kernels[dom]
-    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
 
     out = {
         "metric": "DFSS attention forward TFLOP/s (algorithmic 3*BH*L^2*d per step)",
@@ -199,17 +215,24 @@ def main():
         "config": {"workload": w.name, "B": w.B, "H": w.H, "L": L, "d": d, "N": w.N, "M": w.M,
                    "buffer_sets": nsets, "cache": "warm" if args.warm else "cold (rotating buffer sets)",
                    "launch": "hip graph of all timed steps" if use_graph else "direct"},
-        "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "avg_launch_ms": round(dom_ms, 5), "algorithmic_bytes_per_launch": int(dom_bytes)},
+        "roofline": {"bound": "mfma", "kernel": "k_fused (dfss_attention)", "achieved": round(achieved, 2),
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "avg_launch_ms": round(k_fused, 5), "algorithmic_flops_per_launch": flops_alg},
         "extra": {
-            "dense_attention_ms_per_step": round(ms_dense, 5),
-            "speedup_vs_dense_attention": round(ms_dense / ms, 4),
+            "speedup_vs_dense_attention_fused": round(ms_dense_fused / ms, 4),
+            "speedup_vs_dense_attention_3stage": round(ms_dense / ms, 4),
+            "staged_path_speedup_vs_dense_attention_3stage": round(ms_dense / ms_staged, 4),
+            "dense_attention_fused_ms_per_step": round(ms_dense_fused, 5),
+            "dense_attention_3stage_ms_per_step": round(ms_dense, 5),
+            "dfss_attention_staged_ms_per_step": round(ms_staged, 5),
             "dense_equivalent_tflops": round(flops_eq / (t_sparse / K) / 1e12, 3),
-            "dense_attention_tflops": round(flops_eq / (t_dense / K) / 1e12, 3),
+            "dense_attention_fused_tflops": round(flops_eq / (t_dense_fused / K) / 1e12, 3),
             "ms_per_step_direct_launch": round(t_sparse_eager / K * 1e3, 5),
-            "kernel_ms": {k: round(v[0], 5) for k, v in kernels.items()},
-            "kernel_GBps": {k: round(v[1] / (v[0] * 1e-3) / 1e9, 1) for k, v in kernels.items()},
+            "stage_kernel_ms": {k: round(v[0], 5) for k, v in kernels.items()},
+            "stage_kernel_GBps": {k: round(v[1] / (v[0] * 1e-3) / 1e9, 1) for k, v in kernels.items()},
+            "stage_kernel_frac_of_hbm_peak": {k: round(v[1] / (v[0] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+                                              for k, v in kernels.items()},
             "sddmm_prune_tflops": round(2.0 * BH * L * L * d / (k1 * 1e-3) / 1e12, 2),
             "sddmm_prune_frac_of_mfma_peak": round(2.0 * BH * L * L * d / (k1 * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
         },
@@ -222,13 +245,16 @@ def main():
         per_head_flops = 3.0 * L * L * d
         heads = int(max(1, min(BH, 2.0e10 // per_head_flops)))
         oracle.attention(Qn[:1], Kn[:1], Vn[:1], w.N, w.M, w.scale)  # load + warm
+        reps, dt = 0, 0.0
         t0 = time.perf_counter()
-        oracle.attention(Qn[:heads], Kn[:heads], Vn[:heads], w.N, w.M, w.scale)
-        dt = time.perf_counter() - t0
+        while dt < 3.0 and reps < 50:           # a few seconds of host work, whole passes only
+            oracle.attention(Qn[:heads], Kn[:heads], Vn[:heads], w.N, w.M, w.scale)
+            reps += 1
+            dt = time.perf_counter() - t0
         out["cpu_baseline"] = {
-            "value": round(heads * per_head_flops / dt / 1e12, 6), "unit": "TFLOP/s",
+            "value": round(reps * heads * per_head_flops / dt / 1e12, 6), "unit": "TFLOP/s",
             "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"{heads} of {BH} heads of {w.name}, one pass, {dt:.2f} s"}
+            "sample": f"{heads} of {BH} heads of {w.name}, {reps} passes in {dt:.2f} s"}
 
     print(json.dumps(out))
 

@@ -88,8 +88,11 @@ dfss_status dfss_spmm(const void *vals, const void *meta, const void *V, const d
 
 /* ---- whole forward pass (Eq. 1 with the pruned score matrix) ---------------------- */
 /* ws: device scratch of at least dfss_workspace_bytes(), 256-byte aligned; contents
- * undefined afterwards.  Computes the same function as stage 1 -> 2 -> 3; the
- * normalisation may be folded into the neighbouring stages. */
+ * undefined afterwards.  Computes the same function as stage 1 -> 2 -> 3.  By default all
+ * three stages run in ONE kernel that keeps the pruned scores in registers (the pruning
+ * epilogue of Sec. 3.4 taken to its end: nothing of the score matrix is written); with the
+ * environment variable DFSS_ATTENTION_PATH=staged the three stage kernels are run through
+ * the workspace instead. */
 dfss_status dfss_attention(const void *Q, const void *K, const void *V, const dfss_shape *s,
                            float scale, void *O, void *ws, size_t ws_bytes, void *stream);
 
@@ -98,6 +101,11 @@ dfss_status dfss_attention(const void *Q, const void *K, const void *V, const df
  * (at least dense_workspace_bytes()).  s->N, s->M are ignored. */
 dfss_status dense_attention(const void *Q, const void *K, const void *V, const dfss_shape *s,
                             float scale, void *O, void *ws, size_t ws_bytes, void *stream);
+
+/* Eq. 1 in one kernel (scores, softmax and P V fused; nothing of the score matrix is
+ * written): the stronger full-attention baseline, reported next to dense_attention. */
+dfss_status dense_attention_fused(const void *Q, const void *K, const void *V, const dfss_shape *s,
+                                  float scale, void *O, void *stream);
 
 /* ---- metadata order ---------------------------------------------------------------- */
 /* Canonical order: uint16 [B*H, Lq, Lk/16], word w of a row = codes of key runs

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     DfssError,
     Shape,
     dense_attention,
+    dense_attention_fused,
     dense_workspace_bytes,
     dfss_attention,
     dfss_meta_bytes,

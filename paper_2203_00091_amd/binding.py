@@ -14,12 +14,13 @@ from dataclasses import dataclass
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libdfss.so")
+# DFSS_LIBRARY_PATH points the binding at another build of the same library (kernel experiments)
+_LIB_PATH = os.environ.get("DFSS_LIBRARY_PATH") or os.path.join(_HERE, "libdfss.so")
 
 EXPORTS = (
     "dfss_vals_bytes", "dfss_meta_bytes", "dfss_workspace_bytes", "dense_workspace_bytes",
     "dfss_sddmm_prune", "dfss_sparse_softmax", "dfss_spmm", "dfss_attention", "dense_attention",
-    "dfss_meta_to_canonical", "dfss_meta_from_canonical", "dfss_status_string",
+    "dense_attention_fused", "dfss_meta_to_canonical", "dfss_meta_from_canonical", "dfss_status_string",
 )
 
 
@@ -82,10 +83,11 @@ def load_library():
         L.dfss_spmm.argtypes = [vp, vp, vp, sp, vp, vp]
         L.dfss_attention.argtypes = [vp, vp, vp, sp, f32, vp, vp, sz, vp]
         L.dense_attention.argtypes = [vp, vp, vp, sp, f32, vp, vp, sz, vp]
+        L.dense_attention_fused.argtypes = [vp, vp, vp, sp, f32, vp, vp]
         L.dfss_meta_to_canonical.argtypes = [vp, sp, vp, vp]
         L.dfss_meta_from_canonical.argtypes = [vp, sp, vp, vp]
         for name in ("dfss_sddmm_prune", "dfss_sparse_softmax", "dfss_spmm", "dfss_attention",
-                     "dense_attention", "dfss_meta_to_canonical", "dfss_meta_from_canonical"):
+                     "dense_attention", "dense_attention_fused", "dfss_meta_to_canonical", "dfss_meta_from_canonical"):
             getattr(L, name).restype = ctypes.c_int
         L.dfss_status_string.argtypes = [ctypes.c_int]
         L.dfss_status_string.restype = ctypes.c_char_p
@@ -178,6 +180,16 @@ def dense_attention(Q, K, V, s: Shape, scale: float, O=None, ws=None):
     st = load_library().dense_attention(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(s.c()), scale, _ptr(O), _ptr(ws),
                                         ws.numel() * ws.element_size(), _stream())
     _check("dense_attention", st)
+    return O
+
+
+def dense_attention_fused(Q, K, V, s: Shape, scale: float, O=None):
+    """Full attention in one kernel (the stronger baseline)."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=Q.device)
+    st = load_library().dense_attention_fused(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(s.c()), scale, _ptr(O),
+                                              _stream())
+    _check("dense_attention_fused", st)
     return O
 
 

@@ -1,6 +1,8 @@
 // C ABI of the DFSS library: argument validation and kernel sequencing.
 // The public contract is documented in include/dfss.h.
 #include <math.h>
+#include <stdlib.h>
+#include <string.h>
 
 #include "../../include/dfss.h"
 #include "dfss_kernels.hpp"
@@ -36,6 +38,11 @@ dfss_status check_shape(const dfss_shape *s, bool need_nm, Dims *out) {
 
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 inline bool bad_scale(float x) { return !(x > 0.0f) || isinf(x); }
+// DFSS_ATTENTION_PATH=staged makes dfss_attention run the three stage kernels through the workspace.
+inline bool staged_path_requested() {
+    const char *v = getenv("DFSS_ATTENTION_PATH");
+    return v && strcmp(v, "staged") == 0;
+}
 inline dfss_status hip_status(hipError_t e) { return e == hipSuccess ? DFSS_OK : DFSS_ERR_HIP; }
 
 }  // namespace
@@ -104,12 +111,24 @@ dfss_status dfss_attention(const void *Q, const void *K, const void *V, const df
     if ((reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0) return DFSS_ERR_SHAPE;
     if (ws_bytes < dfss_workspace_bytes(s)) return DFSS_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
+    if (!staged_path_requested())
+        return hip_status(dfss::launch_fused_attention(Q, K, V, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, O, st));
     char *vals = static_cast<char *>(ws);
     char *meta = vals + align_up(dfss_vals_bytes(s));
     hipError_t e = dfss::launch_sddmm_prune(Q, K, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, vals, meta, st);
     if (e == hipSuccess) e = dfss::launch_row_softmax(vals, (long)D.BH * D.Lq, D.Lk / 2, st);
     if (e == hipSuccess) e = dfss::launch_spmm(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, st);
     return hip_status(e);
+}
+
+dfss_status dense_attention_fused(const void *Q, const void *K, const void *V, const dfss_shape *s, float scale,
+                                  void *O, void *stream) {
+    Dims D;
+    if (!Q || !K || !V || !O) return DFSS_ERR_NULL;
+    if (dfss_status st = check_shape(s, false, &D)) return st;
+    if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O)) return DFSS_ERR_SHAPE;
+    return hip_status(dfss::launch_fused_attention(Q, K, V, D.BH, D.Lq, D.Lk, D.d, 2, scale, O, (hipStream_t)stream));
 }
 
 dfss_status dense_attention(const void *Q, const void *K, const void *V, const dfss_shape *s, float scale, void *O,

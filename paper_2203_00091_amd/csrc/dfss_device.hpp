@@ -54,6 +54,22 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const void *p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
 }
 
+// Asynchronous 16-byte-per-lane copy global -> LDS (no register round trip): lane i of the
+// wave writes LDS bytes [lds_wave_base + 16 i, +16).  `lds_wave_base` must be wave-uniform.
+// Completion is tracked by the vector-memory counter: the caller waits with
+// s_waitcnt vmcnt(..) and a workgroup barrier before other waves read the data.  Written as
+// inline assembly so that the compiler does not serialise later LDS reads of OTHER buffers
+// against copies that are still in flight.
+__device__ __forceinline__ void async_copy16(const void *gsrc, const void *lds_wave_base) {
+    typedef __attribute__((address_space(3))) const void lds_cvoid;
+    const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_cvoid *)lds_wave_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_addr), "v"(gsrc)
+                 : "memory", "m0");
+}
+__device__ __forceinline__ void wait_async_copies() { __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0) */ }
+
 template <typename T>
 __device__ __forceinline__ T wave_xor_max(T v, int width) {
     for (int o = width >> 1; o > 0; o >>= 1) {

@@ -20,6 +20,9 @@ hipError_t launch_spmm(const void *vals, const void *meta, const void *V, int BH
 // Dense O = P V with P bfloat16 [BH, Lq, Lk].
 hipError_t launch_dense_av(const void *P, const void *V, int BH, int Lq, int Lk, int d, void *O,
                            hipStream_t st);
+// Whole forward pass in one kernel.  mode: 0 = 2:4, 1 = 1:2, 2 = dense (full attention, Eq. 1).
+hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d,
+                                  int mode, float scale, void *O, hipStream_t st);
 // Metadata word order: library <-> canonical.
 hipError_t launch_meta_reorder(const void *src, void *dst, int BH, int Lq, int W, bool to_canonical,
                                hipStream_t st);

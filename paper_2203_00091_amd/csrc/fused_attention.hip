@@ -1,0 +1,397 @@
+// Whole DFSS forward pass in one kernel: scores on bf16 MFMA, N:M pruning on the
+// accumulators (arXiv 2203.00091, Sec. 3.4), softmax over the kept scores (Sec. 3.1,
+// App. A.1.3) and the product with V on the structured-sparse MFMA -- without writing the
+// compressed score matrix to memory at all.  It computes the same function as the three
+// stage kernels; what differs is only where the intermediate lives.
+//
+// Why no data movement is needed between the stages: the score tile is formed transposed
+// (keys on MFMA rows), so lane (column c, row group g) ends up with the kept values of
+// query c for the 16 keys 16g .. 16g+15 of a 64-key block -- which is exactly the A
+// operand of v_smfmac_f32_16x16x64_bf16 for row c, contraction chunk g, and the four
+// 4-bit position codes are its index operand.
+//
+// Softmax is done online over key blocks with a lazily updated reference value m per
+// query: weights are exp(s - m); m is only raised (and the partial results rescaled) when
+// a block's maximum exceeds it by more than kTau, which keeps every weight below e^kTau
+// and makes rescaling rare.  softmax(x) does not depend on the reference value, so the
+// result is the max-subtracted softmax of App. A.1.3 up to rounding.  The row sums come
+// out of the matrix unit as well (an extra all-ones column of V), in the same register
+// layout as O, so the final division needs no cross-lane traffic.
+//
+// The dense variant of the same kernel (no pruning, dense MFMA for P V) is a fused
+// full-attention baseline (Eq. 1).
+#include <stdlib.h>
+
+#include "dfss_device.hpp"
+#include "dfss_kernels.hpp"
+
+namespace dfss {
+
+namespace {
+
+constexpr int NT = 256;   // threads per workgroup (4 waves)
+constexpr int KB = 64;    // keys per block
+constexpr float kTau = 8.0f;
+constexpr float kLog2e = 1.4426950408889634f;
+
+enum { MODE_2TO4 = 0, MODE_1TO2 = 1, MODE_DENSE = 2 };
+
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void global_cvoid_t;
+
+typedef uint64_t lanemask;
+__device__ __forceinline__ lanemask gt(float a, float b) { return __builtin_amdgcn_fcmpf(a, b, 2 /* ordered > */); }
+__device__ __forceinline__ bool lane_bit(lanemask m) { return __builtin_amdgcn_inverse_ballot_w64(m); }
+
+// Two largest of four scores, equal scores: the lower index wins (the order "larger value
+// first, then lower index" is total, so the result is the one of the rank rule
+// rank(t) = #{u: s_u > s_t} + #{u < t: s_u == s_t}, keep iff rank < 2).
+// Evaluated as a tournament: A = {s0, s1}, B = {s2, s3}.  Both survivors come from A iff the
+// weaker of A still outranks the stronger of B (ties favour A, the lower indices); both come
+// from B iff the weaker of B strictly beats the stronger of A; otherwise each pair sends its
+// stronger element.  Four comparisons land in lane masks, four min/max and eight selects on
+// the vector unit, almost nothing on the scalar unit.
+// Returns the kept values in key order and the position code (p_lo | p_hi << 2) << SHIFT.
+__device__ __forceinline__ void select_2of4(float s0, float s1, float s2, float s3, const int SHIFT, float &lo,
+                                            float &hi, uint32_t &code) {
+    const lanemask c01 = gt(s1, s0), c23 = gt(s3, s2);      // stronger element of each pair is the later one
+    const float amax = fmaxf(s0, s1), amin = fminf(s0, s1);
+    const float bmax = fmaxf(s2, s3), bmin = fminf(s2, s3);
+    const lanemask not_a = gt(bmax, amin);                   // B's best strictly beats A's worst
+    const lanemask both_b = gt(bmin, amax);                  // B's worst strictly beats A's best
+    const bool na = lane_bit(not_a), bb = lane_bit(both_b);
+    const float lo_m = bb ? s2 : amax, hi_m = na ? bmax : s1;
+    lo = na ? lo_m : s0;
+    hi = bb ? s3 : hi_m;
+    // p_lo: 0 if both from A, 2 if both from B, else index of A's stronger element
+    // p_hi: 1 if both from A, 3 if both from B, else index of B's stronger element
+    const bool lo1 = lane_bit(not_a & c01), hi3 = lane_bit(both_b | c23);
+    const uint32_t plo_m = lo1 ? (1u << SHIFT) : 0u;
+    const uint32_t plo = bb ? (2u << SHIFT) : plo_m;
+    const uint32_t phi_m = hi3 ? (12u << SHIFT) : (8u << SHIFT);
+    const uint32_t phi = na ? phi_m : (4u << SHIFT);
+    code = plo | phi;
+}
+__device__ __forceinline__ void select_1of2(float s0, float s1, float s2, float s3, const int SHIFT, float &lo,
+                                            float &hi, uint32_t &code) {
+    const bool c01 = lane_bit(gt(s1, s0)), c23 = lane_bit(gt(s3, s2));
+    lo = c01 ? s1 : s0;
+    hi = c23 ? s3 : s2;
+    code = (c01 ? (1u << SHIFT) : 0u) | (c23 ? (12u << SHIFT) : (8u << SHIFT));
+}
+
+__device__ __forceinline__ unsigned xcd_contiguous(unsigned id, unsigned total) {
+    const unsigned per = total / 8;
+    return id < per * 8 ? (id % 8) * per + id / 8 : id;
+}
+
+template <int D, int MODE, int NQ, bool PRESCALE>
+__global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
+                                                 const __bf16 *__restrict__ V, int Lq, int Lk, float scale,
+                                                 uint16_t *__restrict__ O) {
+    constexpr int CPR = D / 8;          // 16-byte chunks per row
+    constexpr int TILE = KB * CPR;      // chunks per K (or V) block
+    constexpr int LPT = TILE / NT;      // direct-to-LDS loads per thread per block and operand
+    constexpr int STEPS = D / 32;       // MFMA k-steps of Q K^T
+    constexpr int DS = D / 16;          // 16-column tiles of O
+    constexpr int TQ = 64 * NQ;         // queries per workgroup
+    constexpr bool SPARSE = MODE != MODE_DENSE;
+    __shared__ u32x4 Ks[2][TILE];
+    __shared__ u32x4 Vs[2][TILE];
+
+    const int tid = threadIdx.x;
+    const int w = tid >> 6, l = tid & 63, li = l & 15, kb = l >> 4;
+
+    const unsigned qtiles = Lq / TQ;
+    const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int qt = item % qtiles;
+    const int bh = item / qtiles;
+    const int q0 = qt * TQ + w * 16 * NQ;
+    const int nblocks = Lk / KB;
+
+    const __bf16 *Kh = K + (size_t)bh * Lk * D;
+    const __bf16 *Vh = V + (size_t)bh * Lk * D;
+
+    // K block in LDS: row slot 16 t + i holds key 16 (i/4) + 4 t + i%4 (tile t, MFMA row i), chunk c
+    // at position slot * CPR + (c ^ (slot & 7)).  V block: row = key, chunk c at row * CPR + (c ^ ((row & 3) << 1)).
+    int k_off[LPT], v_off[LPT];
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+        const int p = i * NT + tid;
+        const int slot = p / CPR;
+        const int key = (slot & 3) | (((slot >> 4) & 3) << 2) | (((slot >> 2) & 3) << 4);
+        k_off[i] = key * D + ((p % CPR) ^ (slot & 7)) * 8;
+        v_off[i] = slot * D + ((p % CPR) ^ ((slot & 3) << 1)) * 8;
+    }
+    auto issue_block = [&](int jb, int buf) {
+        const __bf16 *ks = Kh + (size_t)jb * KB * D;
+        const __bf16 *vs = Vh + (size_t)jb * KB * D;
+#pragma unroll
+        for (int i = 0; i < LPT; ++i)
+            async_copy16(ks + k_off[i], &Ks[buf][i * NT + w * 64]);
+#pragma unroll
+        for (int i = 0; i < LPT; ++i)
+            async_copy16(vs + v_off[i], &Vs[buf][i * NT + w * 64]);
+    };
+
+    issue_block(0, 0);
+
+    // Q operand (B side of Q K^T): lane (column li, chunk kb) of step s holds Q[q][32 s + 8 kb .. +7]
+    bf16x8 bq[NQ][STEPS];
+#pragma unroll
+    for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            const u32x4 raw = *reinterpret_cast<const u32x4 *>(Q + ((size_t)bh * Lq + q0 + 16 * qs + li) * D +
+                                                               32 * s + 8 * kb);
+            if constexpr (PRESCALE) {
+                u32x4 sc;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    sc[e] = pack_bf16x2(bf16_lo_to_f32(raw[e]) * scale, bf16_hi_to_f32(raw[e]) * scale);
+                bq[qs][s] = __builtin_bit_cast(bf16x8, sc);
+            } else {
+                bq[qs][s] = __builtin_bit_cast(bf16x8, raw);
+            }
+        }
+
+    // running state.  m: reference value of the query in column li (same in the four lanes
+    // that share the column).  acc_o / acc_l: O and row sums, rows 4 kb + r of the 16-query tile.
+    float m_ref[NQ];
+    f32x4 acc_o[NQ][DS], acc_l[NQ];
+#pragma unroll
+    for (int qs = 0; qs < NQ; ++qs) {
+        m_ref[qs] = -3.0e38f;
+        acc_l[qs] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ds = 0; ds < DS; ++ds) acc_o[qs][ds] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const uint32_t one2 = 0x3F803F80u;  // two bfloat16 ones
+    const bf16x16 ones16 = __builtin_bit_cast(bf16x16, (uint32_t __attribute__((ext_vector_type(8)))){
+                                                            one2, one2, one2, one2, one2, one2, one2, one2});
+    const bf16x8 ones8 = __builtin_bit_cast(bf16x8, u32x4{one2, one2, one2, one2});
+
+    const int tr_row = li >> 2, tr_sub = (li >> 1) & 1, tr_byte = 8 * (li & 1), tr_xor = tr_row << 1;
+
+    for (int jb = 0; jb < nblocks; ++jb) {
+        const int buf = jb & 1;
+#ifndef DFSS_X_NOSYNC
+        wait_async_copies();  // vmcnt(0): this block's copies have landed
+        __syncthreads();
+        if (jb + 1 < nblocks) issue_block(jb + 1, buf ^ 1);
+#endif
+
+        // ---- scores: acc[qs][t][r] = s(query q0 + 16 qs + li, key 64 jb + 16 kb + 4 t + r) ----
+        f32x4 acc[NQ][4];
+#pragma unroll
+        for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[qs][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            bf16x8 ak[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                ak[t] = __builtin_bit_cast(bf16x8, Ks[buf][(16 * t + li) * CPR + ((4 * s + kb) ^ (li & 7))]);
+#pragma unroll
+            for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) acc[qs][t] = mfma16(ak[t], bq[qs][s], acc[qs][t]);
+        }
+
+        // ---- prune, block maximum ----
+        float kept[NQ][SPARSE ? 8 : 16];
+        uint32_t idx[NQ];
+        float m_blk[NQ];
+#pragma unroll
+        for (int qs = 0; qs < NQ; ++qs) {
+            idx[qs] = 0;
+            m_blk[qs] = -3.0e38f;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                f32x4 a = acc[qs][t];
+                if constexpr (!PRESCALE) a = a * scale;
+                if constexpr (SPARSE) {
+                    float lo, hi;
+                    uint32_t code;
+                    if constexpr (MODE == MODE_2TO4) select_2of4(a[0], a[1], a[2], a[3], 4 * t, lo, hi, code);
+                    else select_1of2(a[0], a[1], a[2], a[3], 4 * t, lo, hi, code);
+                    kept[qs][2 * t] = lo;
+                    kept[qs][2 * t + 1] = hi;
+                    idx[qs] |= code;
+                    m_blk[qs] = fmaxf(m_blk[qs], fmaxf(lo, hi));
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) kept[qs][4 * t + r] = a[r];
+                    m_blk[qs] = fmaxf(m_blk[qs], fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])));
+                }
+            }
+            // the four lanes kb = 0..3 of a column hold different keys of the same query
+            m_blk[qs] = fmaxf(m_blk[qs], __shfl_xor(m_blk[qs], 16, 64));
+            m_blk[qs] = fmaxf(m_blk[qs], __shfl_xor(m_blk[qs], 32, 64));
+        }
+
+        // ---- raise the reference value where a block outgrew it (rare after the first block) ----
+        bool raise = false;
+#pragma unroll
+        for (int qs = 0; qs < NQ; ++qs) raise |= m_blk[qs] > m_ref[qs] + kTau;
+        if (__any(raise)) {
+#pragma unroll
+            for (int qs = 0; qs < NQ; ++qs) {
+                const bool up = m_blk[qs] > m_ref[qs] + kTau;
+                const float m_new = up ? m_blk[qs] : m_ref[qs];
+                const float alpha = __builtin_amdgcn_exp2f((m_ref[qs] - m_new) * kLog2e);  // 1 where unchanged
+                m_ref[qs] = m_new;
+                // rows of acc_o/acc_l are queries 4 kb + r: fetch their factors from the lanes of that column
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float a_r = __shfl(alpha, 4 * kb + r, 64);
+                    acc_l[qs][r] *= a_r;
+#pragma unroll
+                    for (int ds = 0; ds < DS; ++ds) acc_o[qs][ds][r] *= a_r;
+                }
+            }
+        }
+
+        // ---- weights exp(s - m), packed as the A operand of the second product ----
+        uint32_t pk[NQ][SPARSE ? 4 : 8];
+#pragma unroll
+        for (int qs = 0; qs < NQ; ++qs) {
+            const float mb = m_ref[qs] * kLog2e;
+#pragma unroll
+            for (int e = 0; e < (SPARSE ? 4 : 8); ++e) {
+#ifdef DFSS_X_NOEXP
+                const float p0 = kept[qs][2 * e] * kLog2e - mb;
+                const float p1 = kept[qs][2 * e + 1] * kLog2e - mb;
+#else
+                const float p0 = __builtin_amdgcn_exp2f(kept[qs][2 * e] * kLog2e - mb);
+                const float p1 = __builtin_amdgcn_exp2f(kept[qs][2 * e + 1] * kLog2e - mb);
+#endif
+                pk[qs][e] = pack_bf16x2(p0, p1);
+            }
+        }
+
+        // ---- O += P V ; row sums += P 1 ----
+        const char *vbase = reinterpret_cast<const char *>(&Vs[buf][0]);
+        auto tr = [&](int key0, int ds) {
+            const int row = key0 + tr_row;
+            const int chunk = (2 * ds + tr_sub) ^ tr_xor;
+            return lds_read_tr16(vbase + (row * CPR + chunk) * 16 + tr_byte);
+        };
+        if constexpr (SPARSE) {
+            // contraction index k of the sparse instruction = key of the block; B lane (column, kb)
+            // holds keys 8 kb .. +7 and 32 + 8 kb .. +7
+#pragma unroll
+            for (int ds = 0; ds < DS; ++ds) {
+                const s16x4 t0 = tr(8 * kb, ds), t1 = tr(8 * kb + 4, ds), t2 = tr(32 + 8 * kb, ds),
+                            t3 = tr(36 + 8 * kb, ds);
+                const s16x8 lo = __builtin_shufflevector(t0, t1, 0, 1, 2, 3, 4, 5, 6, 7);
+                const s16x8 hi = __builtin_shufflevector(t2, t3, 0, 1, 2, 3, 4, 5, 6, 7);
+                const bf16x16 b = __builtin_bit_cast(
+                    bf16x16, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15));
+#pragma unroll
+                for (int qs = 0; qs < NQ; ++qs) {
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, u32x4{pk[qs][0], pk[qs][1], pk[qs][2], pk[qs][3]});
+                    acc_o[qs][ds] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a, b, acc_o[qs][ds], (int)idx[qs], 0, 0);
+                }
+            }
+#pragma unroll
+            for (int qs = 0; qs < NQ; ++qs) {
+                const bf16x8 a = __builtin_bit_cast(bf16x8, u32x4{pk[qs][0], pk[qs][1], pk[qs][2], pk[qs][3]});
+                acc_l[qs] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a, ones16, acc_l[qs], (int)idx[qs], 0, 0);
+            }
+        } else {
+            // dense: MFMA m (0/1) contracts the lane's keys 16 kb + 8 m .. +7
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+#pragma unroll
+                for (int ds = 0; ds < DS; ++ds) {
+                    const s16x4 t0 = tr(16 * kb + 8 * m, ds), t1 = tr(16 * kb + 8 * m + 4, ds);
+                    const bf16x8 b = __builtin_bit_cast(bf16x8, __builtin_shufflevector(t0, t1, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+                    for (int qs = 0; qs < NQ; ++qs) {
+                        const bf16x8 a = __builtin_bit_cast(
+                            bf16x8, u32x4{pk[qs][4 * m], pk[qs][4 * m + 1], pk[qs][4 * m + 2], pk[qs][4 * m + 3]});
+                        acc_o[qs][ds] = mfma16(a, b, acc_o[qs][ds]);
+                    }
+                }
+#pragma unroll
+                for (int qs = 0; qs < NQ; ++qs) {
+                    const bf16x8 a = __builtin_bit_cast(
+                        bf16x8, u32x4{pk[qs][4 * m], pk[qs][4 * m + 1], pk[qs][4 * m + 2], pk[qs][4 * m + 3]});
+                    acc_l[qs] = mfma16(a, ones8, acc_l[qs]);
+                }
+            }
+        }
+    }
+
+#ifdef DFSS_X_NOSYNC
+    wait_async_copies();
+#endif
+    // ---- O[q][16 ds + li] = acc_o / row sum, q = q0 + 16 qs + 4 kb + r ----
+#pragma unroll
+    for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float inv = 1.0f / acc_l[qs][r];
+            const size_t q = (size_t)bh * Lq + q0 + 16 * qs + 4 * kb + r;
+#pragma unroll
+            for (int ds = 0; ds < DS; ++ds)
+                O[q * D + 16 * ds + li] = (uint16_t)(pack_bf16x2(acc_o[qs][ds][r] * inv, 0.f) & 0xFFFFu);
+        }
+}
+
+inline bool is_pow2(float x) {
+    int e;
+    return frexpf(x, &e) == 0.5f;
+}
+
+template <int MODE, int NQ>
+hipError_t launch_nq(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d, float scale,
+                     void *O, hipStream_t st) {
+    const unsigned grid = (unsigned)((long)BH * (Lq / (64 * NQ)));
+    const bool pre = is_pow2(scale);
+#define DFSS_LAUNCH(DD, PRE)                                                                             \
+    hipLaunchKernelGGL((k_fused<DD, MODE, NQ, PRE>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)Q,    \
+                       (const __bf16 *)K, (const __bf16 *)V, Lq, Lk, scale, (uint16_t *)O)
+    if (d == 64) {
+        if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
+    } else {
+        if (pre) DFSS_LAUNCH(128, true); else DFSS_LAUNCH(128, false);
+    }
+#undef DFSS_LAUNCH
+    return hipGetLastError();
+}
+
+template <int MODE>
+hipError_t launch(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d, float scale, void *O,
+                  hipStream_t st) {
+    // 32 queries per wave when that still leaves at least ~2 workgroups per compute unit
+    if (Lq % 128 == 0 && (long)BH * (Lq / 128) >= 512)
+        return launch_nq<MODE, 2>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
+    return launch_nq<MODE, 1>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
+}
+
+}  // namespace
+
+hipError_t launch_fused_attention32(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d,
+                                    int mode, int nw, float scale, void *O, hipStream_t st);
+
+hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d,
+                                  int mode, float scale, void *O, hipStream_t st) {
+    // The 16-query kernel is the default.  The 32-query kernel (score MFMA at twice the rate, software
+    // pipelined) only pays off once its larger tiles still fill the chip evenly; it is selected with
+    // DFSS_FUSED_TILE = 32x2 | 32x4 (for measurements), 16 forces the default.
+    int tile = 16, nw = 4;
+    if (const char *f = getenv("DFSS_FUSED_TILE")) {
+        if (f[0] == '1') tile = 16;
+        else if (f[0] == '3' && f[1] == '2' && f[2] == 'x' && f[3] == '2' && d == 64) tile = 32, nw = 2;
+        else if (f[0] == '3' && f[1] == '2' && f[2] == 'x' && f[3] == '4' && Lq % 128 == 0) tile = 32, nw = 4;
+    }
+    if (tile == 32) return launch_fused_attention32(Q, K, V, BH, Lq, Lk, d, mode, nw, scale, O, st);
+    if (mode == 0) return launch<MODE_2TO4>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
+    if (mode == 1) return launch<MODE_1TO2>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
+    return launch<MODE_DENSE>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
+}
+
+}  // namespace dfss

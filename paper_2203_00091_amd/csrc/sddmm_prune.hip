@@ -19,6 +19,8 @@
 // 16 consecutive keys 32g .. 32g+15 of query c, after tiles 4..7 the next 16: per
 // 128-key block a lane emits 32 contiguous bytes of kept values and one 32-bit word of
 // metadata (two canonical 16-bit words), and a row receives 128 contiguous bytes.
+#include <stdlib.h>
+
 #include "dfss_device.hpp"
 #include "dfss_kernels.hpp"
 
@@ -41,26 +43,33 @@ typedef uint64_t lanemask;
 __device__ __forceinline__ lanemask gt(float a, float b) { return __builtin_amdgcn_fcmpf(a, b, 2 /* ordered > */); }
 __device__ __forceinline__ bool lane_bit(lanemask m) { return __builtin_amdgcn_inverse_ballot_w64(m); }
 
-// Keep the two largest of four scores; equal scores: the lower index wins
-// (rank(t) = #{u: s_u > s_t} + #{u < t: s_u == s_t}; keep iff rank < 2).
-// Returns the kept values in key order and the position code (p_lo | p_hi << 2) << SHIFT
-// (SHIFT is a constant after unrolling: the code lands directly in its slot of the word).
+// Two largest of four scores, equal scores: the lower index wins (the order "larger value
+// first, then lower index" is total, so the result is the one of the rank rule
+// rank(t) = #{u: s_u > s_t} + #{u < t: s_u == s_t}, keep iff rank < 2).
+// Evaluated as a tournament: A = {s0, s1}, B = {s2, s3}.  Both survivors come from A iff the
+// weaker of A still outranks the stronger of B (ties favour A, the lower indices); both come
+// from B iff the weaker of B strictly beats the stronger of A; otherwise each pair sends its
+// stronger element.  Four comparisons land in lane masks, four min/max and eight selects on
+// the vector unit, almost nothing on the scalar unit.
+// Returns the kept values in key order and the position code (p_lo | p_hi << 2) << SHIFT.
 __device__ __forceinline__ void select_2of4(float s0, float s1, float s2, float s3, const int SHIFT, float &lo,
                                             float &hi, uint32_t &code) {
-    // cXY: the later element Y is strictly larger than X, i.e. Y outranks X;
-    // otherwise X outranks Y (ties go to the lower index).
-    const lanemask c01 = gt(s1, s0), c02 = gt(s2, s0), c03 = gt(s3, s0);
-    const lanemask c12 = gt(s2, s1), c13 = gt(s3, s1), c23 = gt(s3, s2);
-    // element t survives unless at least two others outrank it
-    const lanemask k0 = ~((c01 & (c02 | c03)) | (c02 & c03));
-    const lanemask k1 = ~((~c01 & (c12 | c13)) | (c12 & c13));
-    const lanemask k2 = ~((~c02 & (~c12 | c23)) | (~c12 & c23));
-    const lanemask k3 = ~((~c03 & (~c13 | ~c23)) | (~c13 & ~c23));
-    const bool b0 = lane_bit(k0), b1 = lane_bit(k1), b2 = lane_bit(k2), b3 = lane_bit(k3);
-    lo = b0 ? s0 : (b1 ? s1 : s2);
-    hi = b3 ? s3 : (b2 ? s2 : s1);
-    const uint32_t plo = b0 ? 0u : (b1 ? (1u << SHIFT) : (2u << SHIFT));
-    const uint32_t phi = b3 ? (12u << SHIFT) : (b2 ? (8u << SHIFT) : (4u << SHIFT));
+    const lanemask c01 = gt(s1, s0), c23 = gt(s3, s2);      // stronger element of each pair is the later one
+    const float amax = fmaxf(s0, s1), amin = fminf(s0, s1);
+    const float bmax = fmaxf(s2, s3), bmin = fminf(s2, s3);
+    const lanemask not_a = gt(bmax, amin);                   // B's best strictly beats A's worst
+    const lanemask both_b = gt(bmin, amax);                  // B's worst strictly beats A's best
+    const bool na = lane_bit(not_a), bb = lane_bit(both_b);
+    const float lo_m = bb ? s2 : amax, hi_m = na ? bmax : s1;
+    lo = na ? lo_m : s0;
+    hi = bb ? s3 : hi_m;
+    // p_lo: 0 if both from A, 2 if both from B, else index of A's stronger element
+    // p_hi: 1 if both from A, 3 if both from B, else index of B's stronger element
+    const bool lo1 = lane_bit(not_a & c01), hi3 = lane_bit(both_b | c23);
+    const uint32_t plo_m = lo1 ? (1u << SHIFT) : 0u;
+    const uint32_t plo = bb ? (2u << SHIFT) : plo_m;
+    const uint32_t phi_m = hi3 ? (12u << SHIFT) : (8u << SHIFT);
+    const uint32_t phi = na ? phi_m : (4u << SHIFT);
     code = plo | phi;
 }
 
@@ -122,8 +131,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
         const __bf16 *src = Kh + (size_t)jb * KB * D;
 #pragma unroll
         for (int i = 0; i < LPT; ++i)
-            __builtin_amdgcn_global_load_lds((global_cvoid_t *)(src + src_off[i]),
-                                             (lds_void_t *)&Ks[buf][i * NT + w * 64], 16, 0, 0);
+            async_copy16(src + src_off[i], &Ks[buf][i * NT + w * 64]);
     };
 
     issue_block(jb0, 0);
@@ -154,7 +162,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
         const int jb = jb0 + it;
         const int buf = it & 1;
         // this block's copies (issued one iteration ago) have landed for every wave
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        wait_async_copies();  // vmcnt(0)
         __syncthreads();
         // every wave has also finished reading the other buffer: refill it
         if (it + 1 < blocks_per_wg) issue_block(jb + 1, buf ^ 1);
@@ -260,7 +268,8 @@ template <int MODE>
 hipError_t launch(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale, void *out,
                   void *meta, hipStream_t st) {
     // 32 queries per wave when the query count allows it, else 16
-    if (Lq % 128 == 0) return launch_nq<MODE, 2>(Q, K, BH, Lq, Lk, d, scale, out, meta, st);
+    const char *force = getenv("DFSS_NQ");
+    if (Lq % 128 == 0 && !(force && force[0] == '1')) return launch_nq<MODE, 2>(Q, K, BH, Lq, Lk, d, scale, out, meta, st);
     return launch_nq<MODE, 1>(Q, K, BH, Lq, Lk, d, scale, out, meta, st);
 }
 

@@ -68,8 +68,7 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
         const __bf16 *src = Vh + (size_t)jb * KB * D;
 #pragma unroll
         for (int i = 0; i < LPT; ++i)
-            __builtin_amdgcn_global_load_lds((global_cvoid_t *)(src + src_off[i]),
-                                             (lds_void_t *)&Vs[buf][i * NT + w * 64], 16, 0, 0);
+            async_copy16(src + src_off[i], &Vs[buf][i * NT + w * 64]);
     };
 
     // A operand of one block
@@ -115,7 +114,7 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
 
     for (int jb = 0; jb < nblocks; ++jb) {
         const int buf = jb & 1;
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this block's V copies and A loads are in
+        wait_async_copies();  // vmcnt(0): this block's V copies and A loads are in
         __syncthreads();
         if (jb + 1 < nblocks) {
             issue_block(jb + 1, buf ^ 1);

@@ -7,6 +7,7 @@ Bars (stated by the benchmark spec for this path):
   * output O within 2e-2 max-abs of the oracle.
 """
 import math
+import os
 
 import numpy as np
 import pytest
@@ -206,26 +207,39 @@ def test_meta_order_round_trip():
 # ----------------------------------------------------------------------------------
 # whole path
 # ----------------------------------------------------------------------------------
-def _check_attention(w, heads=None, integer=False):
+def _staged_attention(Qd, Kd, Vd, s, scale):
+    """dfss_attention through the three stage kernels (environment switch of the library)."""
+    os.environ["DFSS_ATTENTION_PATH"] = "staged"
+    try:
+        return dfss.dfss_attention(Qd, Kd, Vd, s, scale)
+    finally:
+        del os.environ["DFSS_ATTENTION_PATH"]
+
+
+def _check_attention(w, heads=None):
     Q, K, V = synth.make(w)
     s = Shape(w.B, w.H, w.L, w.L, w.d, w.N, w.M)
     Qd, Kd, Vd = _dev(Q), _dev(K), _dev(V)
-    O = dfss.dfss_attention(Qd, Kd, Vd, s, w.scale)
+    O = dfss.dfss_attention(Qd, Kd, Vd, s, w.scale)          # one fused kernel
+    Os = _staged_attention(Qd, Kd, Vd, s, w.scale)           # stage kernels via the workspace
     # the three stage calls compose to the same function
     vals, meta = dfss.dfss_sddmm_prune(Qd, Kd, s, w.scale)
     dfss.dfss_sparse_softmax(vals, s)
     O3 = dfss.dfss_spmm(vals, meta, Vd, s)
     Od = dfss.dense_attention(Qd, Kd, Vd, s, w.scale)
+    Odf = dfss.dense_attention_fused(Qd, Kd, Vd, s, w.scale)
     torch.cuda.synchronize()
-    O, O3, Od = _np(O), _np(O3), _np(Od)
+    O, Os, O3, Od, Odf = _np(O), _np(Os), _np(O3), _np(Od), _np(Odf)
     heads = list(range(w.BH)) if heads is None else heads
     Qn, Kn, Vn = (synth.to_numpy_f32(t[heads]) for t in (Q, K, V))
     ref = oracle.attention(Qn, Kn, Vn, w.N, w.M, w.scale)
     ref_dense = oracle.attention(Qn, Kn, Vn, 1, 1, w.scale)
     assert np.max(np.abs(O[heads] - ref)) <= 2e-2
-    assert np.max(np.abs(O3[heads] - ref)) <= 2e-2
+    assert np.max(np.abs(Os[heads] - ref)) <= 2e-2
+    assert np.array_equal(Os, O3)
     assert np.max(np.abs(O - O3)) <= 2e-2
     assert np.max(np.abs(Od[heads] - ref_dense)) <= 2e-2
+    assert np.max(np.abs(Odf[heads] - ref_dense)) <= 2e-2
     return O, ref
 
 
@@ -248,6 +262,49 @@ def test_attention_bert_base_full():
 ])
 def test_attention_full_size_sampled_heads(name, heads):
     _check_attention(synth.WORKLOADS[name], heads)
+
+
+@pytest.mark.parametrize("tile", ["16", "32x2", "32x4"])
+@pytest.mark.parametrize("BH,L,d,N,M", [(3, 256, 64, 2, 4), (2, 384, 64, 1, 2), (2, 256, 128, 2, 4)])
+def test_fused_attention_every_tile_shape(tile, BH, L, d, N, M):
+    """Each tiling of the fused kernel (16- or 32-query tiles, 2 or 4 waves) against the oracle."""
+    Q, K, V = synth.gaussian_qkv(BH, L, L, d, 1.0, seed=900 + L + d + N)
+    s = Shape(1, BH, L, L, d, N, M)
+    scale = 1.0 / math.sqrt(d)
+    os.environ["DFSS_FUSED_TILE"] = tile
+    try:
+        O = dfss.dfss_attention(_dev(Q), _dev(K), _dev(V), s, scale)
+        Od = dfss.dense_attention_fused(_dev(Q), _dev(K), _dev(V), s, scale)
+        torch.cuda.synchronize()
+    finally:
+        del os.environ["DFSS_FUSED_TILE"]
+    Qn, Kn, Vn = (synth.to_numpy_f32(t) for t in (Q, K, V))
+    assert np.max(np.abs(_np(O) - oracle.attention(Qn, Kn, Vn, N, M, scale))) <= 2e-2
+    assert np.max(np.abs(_np(Od) - oracle.attention(Qn, Kn, Vn, 1, 1, scale))) <= 2e-2
+
+
+@pytest.mark.parametrize("tile", ["16", "32x2"])
+def test_fused_attention_rescales_when_late_keys_dominate(tile):
+    """Scores that grow along the key axis force the online softmax to raise its reference
+    value in later blocks; a constant key makes one block dominate every row."""
+    BH, L, d = 2, 256, 64
+    Q, K, V = synth.gaussian_qkv(BH, L, L, d, 1.0, seed=4242)
+    ramp = torch.linspace(0.0, 6.0, L).view(1, L, 1)
+    K = (K.float() + ramp * torch.sign(Q.float().mean(1, keepdim=True))).to(torch.bfloat16)
+    Q = (Q.float() * 2.0).to(torch.bfloat16)
+    s = Shape(1, BH, L, L, d, 2, 4)
+    os.environ["DFSS_FUSED_TILE"] = tile
+    try:
+        O = dfss.dfss_attention(_dev(Q), _dev(K), _dev(V), s, 0.125)
+        Od = dfss.dense_attention_fused(_dev(Q), _dev(K), _dev(V), s, 0.125)
+        torch.cuda.synchronize()
+    finally:
+        del os.environ["DFSS_FUSED_TILE"]
+    Qn, Kn, Vn = (synth.to_numpy_f32(t) for t in (Q, K, V))
+    S = np.einsum("hqd,hkd->hqk", Qn, Kn) * 0.125
+    assert (S.max(-1) - S[:, :, :64].max(-1)).max() > 8.0   # the first block's maximum is outgrown
+    assert np.max(np.abs(_np(O) - oracle.attention(Qn, Kn, Vn, 2, 4, 0.125))) <= 2e-2
+    assert np.max(np.abs(_np(Od) - oracle.attention(Qn, Kn, Vn, 1, 1, 0.125))) <= 2e-2
 
 
 def test_results_are_deterministic_and_cover_every_byte():
