@@ -45,6 +45,8 @@ def parse_args():
     ap.add_argument("--warm", action="store_true", help="single buffer set (cache-resident)")
     ap.add_argument("--no-graph", action="store_true", help="launch steps directly instead of one HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 64 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -166,6 +168,14 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
+
+    if args.calibrate_copy:
+        src = torch.ones(64 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     use_graph = not args.no_graph
     t_sparse = timed(step_sparse, K, W, use_graph)
