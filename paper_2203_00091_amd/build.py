@@ -14,6 +14,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # inputs are finite by contract: without these every fmaxf/fminf is wrapped in two extra
+    # canonicalising v_max_f32 (signalling-NaN quieting of IEEE mode)
+    "-fno-honor-nans", "-mno-amdgpu-ieee",
     "-I" + os.path.join(ROOT, "include"),
 ]
 

@@ -55,18 +55,28 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const void *p) {
 }
 
 // Asynchronous 16-byte-per-lane copy global -> LDS (no register round trip): lane i of the
-// wave writes LDS bytes [lds_wave_base + 16 i, +16).  `lds_wave_base` must be wave-uniform.
-// Completion is tracked by the vector-memory counter: the caller waits with
+// wave reads 16 bytes at gbase + lane_off and writes LDS bytes [lds_wave_addr + 16 i, +16).
+// `gbase` and `lds_wave_addr` are wave-uniform (scalar registers); `lane_off` is the per-lane
+// byte offset.  Completion is tracked by the vector-memory counter: the caller waits with
 // s_waitcnt vmcnt(..) and a workgroup barrier before other waves read the data.  Written as
 // inline assembly so that the compiler does not serialise later LDS reads of OTHER buffers
-// against copies that are still in flight.
-__device__ __forceinline__ void async_copy16(const void *gsrc, const void *lds_wave_base) {
-    typedef __attribute__((address_space(3))) const void lds_cvoid;
-    const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_cvoid *)lds_wave_base);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+// against copies that are still in flight, and so that no vector ALU work is spent on addresses.
+__device__ __forceinline__ void async_copy16(const void *gbase, uint32_t lane_off, uint32_t lds_wave_addr) {
+    // pin the base into scalar registers (a no-op when the compiler already knows it is uniform)
+    const uint64_t g = (uint64_t)(uintptr_t)gbase;
+    // (readfirstlane returns a signed int: widen through uint32_t, or the low half sign-extends)
+    const uint32_t g_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(g >> 32));
+    const uint32_t g_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)g);
+    const uint64_t gs = ((uint64_t)g_hi << 32) | (uint64_t)g_lo;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(lds_addr), "v"(gsrc)
+                 : "s"(lds_wave_addr), "v"(lane_off), "s"(gs)
                  : "memory", "m0");
+}
+// LDS byte address of a __shared__ object, as a wave-uniform scalar.
+__device__ __forceinline__ uint32_t lds_address(const void *shared_ptr) {
+    typedef __attribute__((address_space(3))) const void lds_cvoid;
+    return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_cvoid *)shared_ptr);
 }
 __device__ __forceinline__ void wait_async_copies() { __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0) */ }
 

@@ -123,15 +123,14 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
         k_off[i] = key * D + ((p % CPR) ^ (slot & 7)) * 8;
         v_off[i] = slot * D + ((p % CPR) ^ ((slot & 3) << 1)) * 8;
     }
+    const uint32_t lds_k = lds_address(&Ks[0][w * 64]), lds_v = lds_address(&Vs[0][w * 64]);
     auto issue_block = [&](int jb, int buf) {
         const __bf16 *ks = Kh + (size_t)jb * KB * D;
         const __bf16 *vs = Vh + (size_t)jb * KB * D;
 #pragma unroll
-        for (int i = 0; i < LPT; ++i)
-            async_copy16(ks + k_off[i], &Ks[buf][i * NT + w * 64]);
+        for (int i = 0; i < LPT; ++i) async_copy16(ks, 2u * k_off[i], lds_k + 16u * (buf * TILE + i * NT));
 #pragma unroll
-        for (int i = 0; i < LPT; ++i)
-            async_copy16(vs + v_off[i], &Vs[buf][i * NT + w * 64]);
+        for (int i = 0; i < LPT; ++i) async_copy16(vs, 2u * v_off[i], lds_v + 16u * (buf * TILE + i * NT));
     };
 
     issue_block(0, 0);
@@ -264,8 +263,8 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
                 const float p0 = kept[qs][2 * e] * kLog2e - mb;
                 const float p1 = kept[qs][2 * e + 1] * kLog2e - mb;
 #else
-                const float p0 = __builtin_amdgcn_exp2f(kept[qs][2 * e] * kLog2e - mb);
-                const float p1 = __builtin_amdgcn_exp2f(kept[qs][2 * e + 1] * kLog2e - mb);
+                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(kept[qs][2 * e], kLog2e, -mb));
+                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(kept[qs][2 * e + 1], kLog2e, -mb));
 #endif
                 pk[qs][e] = pack_bf16x2(p0, p1);
             }
@@ -367,8 +366,9 @@ template <int MODE>
 hipError_t launch(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d, float scale, void *O,
                   hipStream_t st) {
     // 32 queries per wave when that still leaves at least ~2 workgroups per compute unit
-    if (Lq % 128 == 0 && (long)BH * (Lq / 128) >= 512)
-        return launch_nq<MODE, 2>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
+    bool two = Lq % 128 == 0 && (long)BH * (Lq / 128) >= 768;   // at least 3 workgroups per compute unit
+    if (const char *f = getenv("DFSS_FUSED_NQ")) two = Lq % 128 == 0 && f[0] == '2';   // for measurements
+    if (two) return launch_nq<MODE, 2>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
     return launch_nq<MODE, 1>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
 }
 

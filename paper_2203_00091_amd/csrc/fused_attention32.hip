@@ -124,15 +124,15 @@ __global__ __launch_bounds__(64 * NW, 2) void k_fused32(const __bf16 *__restrict
     }
     auto issue_k = [&](int jb, u32x4 *dst) {
         const __bf16 *ks = Kh + (size_t)jb * KB * D;
+        const uint32_t lds = lds_address(&dst[w * 64]);
 #pragma unroll
-        for (int i = 0; i < LPT; ++i)
-            async_copy16(ks + k_off[i], &dst[i * NT + w * 64]);
+        for (int i = 0; i < LPT; ++i) async_copy16(ks, 2u * k_off[i], lds + 16u * (i * NT));
     };
     auto issue_v = [&](int jb, u32x4 *dst) {
         const __bf16 *vs = Vh + (size_t)jb * KB * D;
+        const uint32_t lds = lds_address(&dst[w * 64]);
 #pragma unroll
-        for (int i = 0; i < LPT; ++i)
-            async_copy16(vs + v_off[i], &dst[i * NT + w * 64]);
+        for (int i = 0; i < LPT; ++i) async_copy16(vs, 2u * v_off[i], lds + 16u * (i * NT));
     };
 
     issue_k(0, Ks0);
@@ -328,8 +328,8 @@ __global__ __launch_bounds__(64 * NW, 2) void k_fused32(const __bf16 *__restrict
             idx_prev[kt] = idx[kt];
 #pragma unroll
             for (int e = 0; e < NP; ++e) {
-                const float p0 = __builtin_amdgcn_exp2f(kept[kt][2 * e] * kLog2e - mb);
-                const float p1 = __builtin_amdgcn_exp2f(kept[kt][2 * e + 1] * kLog2e - mb);
+                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(kept[kt][2 * e], kLog2e, -mb));
+                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(kept[kt][2 * e + 1], kLog2e, -mb));
                 pk_prev[kt][e] = pack_bf16x2(p0, p1);
             }
         }

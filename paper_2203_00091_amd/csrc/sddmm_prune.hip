@@ -127,11 +127,11 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
         const int key = (slot & 3) | (((slot >> 4) & 7) << 2) | (((slot >> 2) & 3) << 5);
         src_off[i] = key * D + c * 8;
     }
+    const uint32_t lds_k = lds_address(&Ks[0][w * 64]);   // this wave's 1 KB slice of copy 0, buffer 0
     auto issue_block = [&](int jb, int buf) {
         const __bf16 *src = Kh + (size_t)jb * KB * D;
 #pragma unroll
-        for (int i = 0; i < LPT; ++i)
-            async_copy16(src + src_off[i], &Ks[buf][i * NT + w * 64]);
+        for (int i = 0; i < LPT; ++i) async_copy16(src, 2u * src_off[i], lds_k + 16u * (buf * TILE + i * NT));
     };
 
     issue_block(jb0, 0);

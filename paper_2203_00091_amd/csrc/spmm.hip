@@ -64,11 +64,11 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
         const int row = p / CPR, c = (p % CPR) ^ ((row & 3) << 1);
         src_off[i] = row * D + c * 8;
     }
+    const uint32_t lds_v = lds_address(&Vs[0][w * 64]);   // this wave's 1 KB slice of copy 0, buffer 0
     auto issue_block = [&](int jb, int buf) {
         const __bf16 *src = Vh + (size_t)jb * KB * D;
 #pragma unroll
-        for (int i = 0; i < LPT; ++i)
-            async_copy16(src + src_off[i], &Vs[buf][i * NT + w * 64]);
+        for (int i = 0; i < LPT; ++i) async_copy16(src, 2u * src_off[i], lds_v + 16u * (buf * TILE + i * NT));
     };
 
     // A operand of one block
