@@ -112,8 +112,9 @@ dfss_status dense_attention_fused(const void *Q, const void *K, const void *V, c
  * 4w..4w+3, code = p_lo | p_hi << 2 with p the kept key index mod 4 (the 2-bit
  * position rule that yields the two codes App. A.1.1 prints, 0x4 and 0xe).
  * Library order: the canonical words are taken in pairs as 32-bit words (the earlier one in
- * the low half), rows in blocks of 16, and inside a block the 32-bit words of one 32-key
- * chunk for the 16 rows are adjacent:  lib32[bh][r/16][v][r%16] = canon32[bh][r][v], v < Lk/32.
+ * the low half; word v covers keys 32v..32v+31), rows in blocks of 16, keys in blocks of 128:
+ *   lib32[bh][r/16][v/4][r%16][slot(v%4)] = canon32[bh][r][v],  slot(c) = 2*(c%2) + c/2,
+ * i.e. the four words of a row for one 128-key block are adjacent (chunk order 0, 2, 1, 3).
  * Both calls take device pointers; `meta` and `canon` must not overlap. */
 dfss_status dfss_meta_to_canonical(const void *meta, const dfss_shape *s, void *canon, void *stream);
 dfss_status dfss_meta_from_canonical(const void *canon, const dfss_shape *s, void *meta, void *stream);

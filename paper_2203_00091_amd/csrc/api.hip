@@ -37,7 +37,14 @@ dfss_status check_shape(const dfss_shape *s, bool need_nm, Dims *out) {
 }
 
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
-inline bool bad_scale(float x) { return !(x > 0.0f) || isinf(x); }
+// scale must be finite and > 0.  Tested on the bit pattern: the library is built with finite-math
+// flags, under which a floating-point comparison may not be relied on to reject NaN.
+inline bool bad_scale(float x) {
+    uint32_t u;
+    memcpy(&u, &x, sizeof(u));
+    const bool negative = (u >> 31) != 0, zero = (u & 0x7FFFFFFFu) == 0, inf_or_nan = (u & 0x7F800000u) == 0x7F800000u;
+    return negative || zero || inf_or_nan;
+}
 // DFSS_ATTENTION_PATH=staged makes dfss_attention run the three stage kernels through the workspace.
 inline bool staged_path_requested() {
     const char *v = getenv("DFSS_ATTENTION_PATH");

@@ -79,6 +79,14 @@ __device__ __forceinline__ uint32_t lds_address(const void *shared_ptr) {
     return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_cvoid *)shared_ptr);
 }
 __device__ __forceinline__ void wait_async_copies() { __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0) */ }
+// Wait until at most YOUNGER vector-memory operations of this wave are outstanding.  The counter
+// retires in issue order, so this waits for the copies while leaving the YOUNGER stores that were
+// issued after them in flight (waiting for those would expose the full store latency every block).
+template <int YOUNGER>
+__device__ __forceinline__ void wait_async_copies_keep() {
+    static_assert(YOUNGER >= 0 && YOUNGER < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (YOUNGER & 15) | ((YOUNGER >> 4) << 14));
+}
 
 template <typename T>
 __device__ __forceinline__ T wave_xor_max(T v, int width) {

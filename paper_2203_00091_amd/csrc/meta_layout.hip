@@ -1,10 +1,11 @@
 // Metadata word order (arXiv 2203.00091, Sec. 2.3 and App. A.1.1-A.1.2 define the 4-bit
 // codes and their packing into 16-bit words; the ORDER of the words in memory is free).
 // Canonical: uint16 [BH, Lq, Lk/16], taken here as 32-bit words [BH, Lq, W], W = Lk/32 (two
-// consecutive 16-bit words, the earlier one in the low half).  Library: [BH, Lq/16, W, 16],
-// i.e. the 32-bit words of one 32-key chunk for 16 consecutive rows are adjacent, which is
-// the order in which both the pruning epilogue (writer) and the SpMM (reader) hold them
-// across a wave.
+// consecutive 16-bit words, the earlier one in the low half).  Library: [BH, Lq/16, Lk/128, 16, 4]:
+// per block of 128 keys the four words of a row are adjacent (in the order c = 0, 2, 1, 3 of
+// their 32-key chunks) and the 16 rows of a row block follow each other.  That is the order in
+// which the pruning epilogue holds them (a lane owns the chunks c and c + 2 of one row and
+// writes them with one 8-byte store) and in which the SpMM reads them.
 #include "dfss_device.hpp"
 #include "dfss_kernels.hpp"
 
@@ -20,7 +21,9 @@ __global__ __launch_bounds__(256) void k_meta_reorder(const uint32_t *__restrict
     const long r = i / W;  // bh * Lq + row
     const int row = (int)(r % Lq);
     const long bh = r / Lq;
-    const long lib = ((bh * (Lq / 16) + row / 16) * W + w) * 16 + row % 16;
+    // word w = 4 jb + c of a row; c = 2 p + h (p: 64-key pair, h: 32-key half) is stored at slot 2 h + p
+    const int jb = w >> 2, c = w & 3, slot = ((c & 1) << 1) | (c >> 1);
+    const long lib = (((bh * (Lq / 16) + row / 16) * (W / 4) + jb) * 16 + row % 16) * 4 + slot;
     if (to_canonical) dst[i] = src[lib];
     else dst[lib] = src[i];
 }

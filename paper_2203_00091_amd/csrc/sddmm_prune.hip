@@ -156,13 +156,15 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
         }
 
     const int rb0 = q0 >> 4;                 // first 16-row block of this wave
-    const int W32 = Lk / 32;                 // 32-bit metadata words per row
 
     for (int it = 0; it < blocks_per_wg; ++it) {
         const int jb = jb0 + it;
         const int buf = it & 1;
-        // this block's copies (issued one iteration ago) have landed for every wave
-        wait_async_copies();  // vmcnt(0)
+        // this block's copies (issued one iteration ago) have landed for every wave; the stores of
+        // the previous iteration, issued after those copies, stay in flight
+        constexpr int kStoresPerBlock = MODE == MODE_DENSE ? 4 * NQ : 3 * NQ;
+        if (it == 0) wait_async_copies();
+        else wait_async_copies_keep<kStoresPerBlock>();
         __syncthreads();
         // every wave has also finished reading the other buffer: refill it
         if (it + 1 < blocks_per_wg) issue_block(jb + 1, buf ^ 1);
@@ -230,8 +232,169 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
         if constexpr (MODE != MODE_DENSE) {
 #pragma unroll
             for (int qs = 0; qs < NQ; ++qs)
-                meta[(((size_t)bh * (Lq / 16) + rb0 + qs) * W32 + 4 * jb + kb) * 16 + li] = mword[qs];
+                meta[((((size_t)bh * (Lq / 16) + rb0 + qs) * (Lk / KB) + jb) * 16 + li) * 4 + (((kb & 1) << 1) | (kb >> 1))] =
+                    mword[qs];
         }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// 32-query variant.  Same method, but the scores are formed with v_mfma_f32_32x32x16_bf16, which
+// on gfx950 has twice the flops per cycle of the 16x16x32 form (both take 32 cycles per SIMD).
+// A wave owns 32 queries; lane l holds query l%32 and, per 32-key tile, the 16 registers
+// 4g + x are MFMA rows 8g + 4h + x (h = l/32).  LDS row slot 32 t + i (tile t of a 128-key block,
+// MFMA row i = 8g + 4h' + x) holds key 64 (t/2) + 32 h' + 16 (t%2) + 4 g + x, so that over a PAIR
+// of tiles lane (query, h) owns the 32 consecutive keys 64 p + 32 h .. +31: 32 contiguous bytes of
+// kept values and one 32-bit metadata word, exactly the units of the 16-query kernel.
+// ---------------------------------------------------------------------------------------------
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+template <int D, int MODE, bool PRESCALE>
+__global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
+                                                   int Lq, int Lk, float scale, int ksplit, int blocks_per_wg,
+                                                   uint32_t *__restrict__ out, uint32_t *__restrict__ meta) {
+    constexpr int CPR = D / 8;           // 16-byte chunks per row
+    constexpr int TILE = KB * CPR;       // chunks per K block
+    constexpr int LPT = TILE / NT;       // asynchronous copies per thread per block
+    constexpr int STEPS = D / 16;        // k-steps of the 32x32x16 MFMA
+    constexpr int TQ = 128;              // queries per workgroup (4 waves x 32)
+    __shared__ u32x4 Ks[2][TILE];
+
+    const int tid = threadIdx.x;
+    const int w = tid >> 6, l = tid & 63, lj = l & 31, h = l >> 5;
+
+    const unsigned qtiles = Lq / TQ;
+    const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int ks_id = item % ksplit;
+    const int qt = (item / ksplit) % qtiles;
+    const int bh = item / (ksplit * qtiles);
+    const int jb0 = ks_id * blocks_per_wg;
+    const int q0 = qt * TQ + w * 32;
+
+    const __bf16 *Kh = K + (size_t)bh * Lk * D;
+
+    // LDS position p (16-byte units) = slot * CPR + (c ^ (slot & 7)) holds chunk c of the key of row slot `slot`
+    int src_off[LPT];
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+        const int p = i * NT + tid;
+        const int slot = p / CPR, c = (p % CPR) ^ (slot & 7);
+        const int t = slot >> 5, r = slot & 31;          // tile, MFMA row = 8 g + 4 h' + x
+        const int key = 64 * (t >> 1) + 32 * ((r >> 2) & 1) + 16 * (t & 1) + 4 * (r >> 3) + (r & 3);
+        src_off[i] = key * D + c * 8;
+    }
+    const uint32_t lds_k = lds_address(&Ks[0][w * 64]);
+    auto issue_block = [&](int jb, int buf) {
+        const __bf16 *src = Kh + (size_t)jb * KB * D;
+#pragma unroll
+        for (int i = 0; i < LPT; ++i) async_copy16(src, 2u * src_off[i], lds_k + 16u * (buf * TILE + i * NT));
+    };
+
+    issue_block(jb0, 0);
+
+    // Q operand: lane (column lj, half h) of step s holds Q[q][16 s + 8 h .. +7]
+    bf16x8 bq[STEPS];
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+        const u32x4 raw =
+            *reinterpret_cast<const u32x4 *>(Q + ((size_t)bh * Lq + q0 + lj) * D + 16 * s + 8 * h);
+        if constexpr (PRESCALE) {
+            u32x4 sc;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                sc[e] = pack_bf16x2(bf16_lo_to_f32(raw[e]) * scale, bf16_hi_to_f32(raw[e]) * scale);
+            bq[s] = __builtin_bit_cast(bf16x8, sc);
+        } else {
+            bq[s] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+
+#ifdef DFSS_X_SMALLOUT
+    const size_t row = ((size_t)bh * Lq + q0 + lj) & 255;   // experiment: every wave writes into the first 256 rows
+#else
+    const size_t row = (size_t)bh * Lq + q0 + lj;
+#endif
+    // metadata of (row, block jb): 16 bytes at ((row block * blocks + jb) * 16 + row % 16) * 4 words;
+    // this lane owns the words of chunks (p = 0, h) and (p = 1, h): slots 2 h and 2 h + 1
+    u32x2 *const meta_row = reinterpret_cast<u32x2 *>(
+        meta + (((size_t)bh * (Lq / 16) + ((q0 + lj) >> 4)) * (Lk / KB) * 16 + (lj & 15)) * 4 + 2 * h);
+
+    for (int it = 0; it < blocks_per_wg; ++it) {
+        const int jb = jb0 + it;
+        const int buf = it & 1;
+        // this block's copies (issued one iteration ago) have landed; the stores of the previous
+        // iteration, issued after those copies, stay in flight
+        constexpr int kStoresPerBlock = MODE == MODE_DENSE ? 8 : 5;   // exact count (or lower): see the helper
+        if (it == 0) wait_async_copies();
+        else wait_async_copies_keep<kStoresPerBlock>();
+        __syncthreads();       // ... for every wave, and everybody is done with the other buffer
+        if (it + 1 < blocks_per_wg) issue_block(jb + 1, buf ^ 1);
+
+        u32x2 mwords = {0u, 0u};
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {                 // pair of key tiles = 64 keys
+            f32x16 acc[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int t = 2 * p + u;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[u][r] = 0.f;
+#pragma unroll
+                for (int s = 0; s < STEPS; ++s) {
+                    const bf16x8 ak =
+                        __builtin_bit_cast(bf16x8, Ks[buf][(32 * t + lj) * CPR + ((2 * s + h) ^ (lj & 7))]);
+                    acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, bq[s], acc[u], 0, 0, 0);
+                }
+            }
+            // acc[u][4g + x] = score of query q0 + lj and key 128 jb + 64 p + 32 h + 16 u + 4 g + x
+            const int kbase = KB * jb + 64 * p + 32 * h;
+            if constexpr (MODE == MODE_DENSE) {
+                uint32_t pk[16];
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        float a0 = acc[u][2 * e], a1 = acc[u][2 * e + 1];
+                        if constexpr (!PRESCALE) { a0 *= scale; a1 *= scale; }
+                        pk[8 * u + e] = pack_bf16x2(a0, a1);
+                    }
+                u32x4 *dst = reinterpret_cast<u32x4 *>(out + (row * Lk + kbase) / 2);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) dst[c] = u32x4{pk[4 * c], pk[4 * c + 1], pk[4 * c + 2], pk[4 * c + 3]};
+            } else {
+                uint32_t word = 0;
+                u32x4 pk[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        float a0 = acc[u][4 * g], a1 = acc[u][4 * g + 1], a2 = acc[u][4 * g + 2], a3 = acc[u][4 * g + 3];
+                        if constexpr (!PRESCALE) { a0 *= scale; a1 *= scale; a2 *= scale; a3 *= scale; }
+                        float lo, hi;
+                        uint32_t code;
+#ifdef DFSS_X_NOSELECT
+                        lo = a0 + a2; hi = a1 + a3; code = 0x4u << (16 * u + 4 * g);
+#else
+                        if constexpr (MODE == MODE_2TO4) select_2of4(a0, a1, a2, a3, 16 * u + 4 * g, lo, hi, code);
+                        else select_1of2(a0, a1, a2, a3, 16 * u + 4 * g, lo, hi, code);
+#endif
+                        pk[u][g] = pack_bf16x2(lo, hi);
+                        word |= code;
+                    }
+                u32x4 *dst = reinterpret_cast<u32x4 *>(out + (row * (size_t)(Lk / 2) + kbase / 2) / 2);
+#ifdef DFSS_X_NOSTORE
+                if (scale < 0.f)   // never true: keeps the values alive without storing them
+#endif
+                {
+#ifndef DFSS_X_NOVALS
+                    dst[0] = pk[0];
+                    dst[1] = pk[1];
+#endif
+                }
+                mwords[p] = word;
+            }
+        }
+        if constexpr (MODE != MODE_DENSE) meta_row[(size_t)jb * 32] = mwords;   // 16 rows x 16 bytes per block
     }
 }
 
@@ -265,11 +428,37 @@ hipError_t launch_nq(const void *Q, const void *K, int BH, int Lq, int Lk, int d
 }
 
 template <int MODE>
+hipError_t launch32(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale, void *out,
+                    void *meta, hipStream_t st) {
+    const int qtiles = Lq / 128;
+    const int kblocks = Lk / KB;
+    int ksplit = 1;
+    while ((long)BH * qtiles * ksplit < 1024 && kblocks % (ksplit * 2) == 0) ksplit *= 2;
+    if ((long)BH * qtiles * ksplit < 1024 && kblocks % 3 == 0 && ksplit == 1) ksplit = 3;
+    const int per_wg = kblocks / ksplit;
+    const unsigned grid = (unsigned)((long)BH * qtiles * ksplit);
+    const bool pre = is_pow2(scale);
+#define DFSS_LAUNCH(DD, PRE)                                                                             \
+    hipLaunchKernelGGL((k_sddmm32<DD, MODE, PRE>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)Q,      \
+                       (const __bf16 *)K, Lq, Lk, scale, ksplit, per_wg, (uint32_t *)out, (uint32_t *)meta)
+    if (d == 64) {
+        if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
+    } else {
+        if (pre) DFSS_LAUNCH(128, true); else DFSS_LAUNCH(128, false);
+    }
+#undef DFSS_LAUNCH
+    return hipGetLastError();
+}
+
+template <int MODE>
 hipError_t launch(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale, void *out,
                   void *meta, hipStream_t st) {
-    // 32 queries per wave when the query count allows it, else 16
-    const char *force = getenv("DFSS_NQ");
-    if (Lq % 128 == 0 && !(force && force[0] == '1')) return launch_nq<MODE, 2>(Q, K, BH, Lq, Lk, d, scale, out, meta, st);
+    // 32 queries per wave (32x32x16 MFMA) when the query count allows it, else 16 (16x16x32 MFMA);
+    // DFSS_SDDMM_TILE=16 forces the 16-query kernels (for measurements)
+    const char *force = getenv("DFSS_SDDMM_TILE");
+    const bool t16 = force && force[0] == '1';
+    if (Lq % 128 == 0 && !t16) return launch32<MODE>(Q, K, BH, Lq, Lk, d, scale, out, meta, st);
+    if (Lq % 128 == 0) return launch_nq<MODE, 2>(Q, K, BH, Lq, Lk, d, scale, out, meta, st);
     return launch_nq<MODE, 1>(Q, K, BH, Lq, Lk, d, scale, out, meta, st);
 }
 

@@ -53,7 +53,7 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
     const int bh = item / qtiles;
     const int rb0 = (qt * TQ >> 4) + w * RB;   // first 16-row block of this wave
     const int nblocks = Lk / KB;
-    const int W32 = Lk / 32;
+    const int meta_slot = ((kb & 1) << 1) | (kb >> 1);   // where the word of 32-key chunk kb sits in a row's 16 bytes
 
     // LDS position p (16-byte units) = row * CPR + (c ^ ((row & 3) << 1)) holds chunk c of key `row`
     const __bf16 *Vh = V + (size_t)bh * Lk * D;
@@ -85,7 +85,7 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
                 const u32x4 *pr = reinterpret_cast<const u32x4 *>(P + row * (size_t)(Lk / 4)) + jb * 8 + kb * 2;
                 a[rb].v[0] = pr[0];
                 a[rb].v[1] = pr[1];
-                a[rb].idx = meta[(((size_t)bh * (Lq / 16) + rb0 + rb) * W32 + 4 * jb + kb) * 16 + li];
+                a[rb].idx = meta[((((size_t)bh * (Lq / 16) + rb0 + rb) * nblocks + jb) * 16 + li) * 4 + meta_slot];
             } else {
                 // dense weights: MFMA m takes keys 128 jb + 32 m + 8 kb .. +7
                 const u32x4 *pr = reinterpret_cast<const u32x4 *>(P + row * (size_t)(Lk / 2)) + jb * 16 + kb;

@@ -199,9 +199,12 @@ def test_meta_order_round_trip():
     back = dfss.dfss_meta_to_canonical(lib, s)
     torch.cuda.synchronize()
     assert torch.equal(back.cpu(), canon)
-    # documented order: lib32[bh][r/16][v][r%16] = canon32[bh][r][v]
-    l4 = lib.cpu().view(torch.int32).view(3, 8, 8, 16)
-    assert torch.equal(l4.permute(0, 1, 3, 2).reshape(3, 128, 8), canon.view(torch.int32).view(3, 128, 8))
+    # documented order: lib32[bh][r/16][v/4][r%16][slot(v%4)] = canon32[bh][r][v], slot(c) = 2*(c%2) + c/2
+    lib5 = lib.cpu().view(torch.int32).view(3, 8, 2, 16, 4)          # [bh][r/16][v/4][r%16][slot]
+    c32 = canon.view(torch.int32).view(3, 8, 16, 2, 4)               # [bh][r/16][r%16][v/4][c]
+    for c in range(4):
+        slot = 2 * (c % 2) + c // 2
+        assert torch.equal(lib5[:, :, :, :, slot], c32[:, :, :, :, c].permute(0, 1, 3, 2))
 
 
 # ----------------------------------------------------------------------------------
