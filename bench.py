@@ -34,6 +34,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
 LLC_BYTES = 256 << 20           # last-level (Infinity) cache; L2 is 8 x 4 MiB on top
+# HBM bytes per launch of the fused kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (scaled by what the same counters read for a plain 64 MiB copy); summaries under profiles/.
+MEASURED_TRAFFIC_BYTES = {"bert_base_L384_2to4": 14.23e6 + 4.72e6}
 
 
 def parse_args():
@@ -227,7 +230,9 @@ def main():
                    "launch": "hip graph of all timed steps" if use_graph else "direct"},
         "roofline": {"bound": "mfma", "kernel": "k_fused (dfss_attention)", "achieved": round(achieved, 2),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+                     "algorithmic_hbm_bytes_per_launch": 8.0 * BH * L * d,
                      "avg_launch_ms": round(k_fused, 5), "algorithmic_flops_per_launch": flops_alg},
         "extra": {
             "speedup_vs_dense_attention_fused": round(ms_dense_fused / ms, 4),
@@ -257,7 +262,7 @@ def main():
         oracle.attention(Qn[:1], Kn[:1], Vn[:1], w.N, w.M, w.scale)  # load + warm
         reps, dt = 0, 0.0
         t0 = time.perf_counter()
-        while dt < 3.0 and reps < 50:           # a few seconds of host work, whole passes only
+        while dt < 10.0 and reps < 500:         # about ten seconds of host work, whole passes only
             oracle.attention(Qn[:heads], Kn[:heads], Vn[:heads], w.N, w.M, w.scale)
             reps += 1
             dt = time.perf_counter() - t0

@@ -88,6 +88,15 @@ __device__ __forceinline__ void wait_async_copies_keep() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (YOUNGER & 15) | ((YOUNGER >> 4) << 14));
 }
 
+// Orders this wave's own LDS traffic: writes issued before the call are visible to reads of any
+// lane of the same wave issued after it.  The hardware executes a wave's LDS operations in order;
+// the fences (wavefront scope, no instructions) only keep the compiler from moving them across.
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <typename T>
 __device__ __forceinline__ T wave_xor_max(T v, int width) {
     for (int o = width >> 1; o > 0; o >>= 1) {

@@ -174,11 +174,9 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
 
     for (int jb = 0; jb < nblocks; ++jb) {
         const int buf = jb & 1;
-#ifndef DFSS_X_NOSYNC
         wait_async_copies();  // vmcnt(0): this block's copies have landed
         __syncthreads();
         if (jb + 1 < nblocks) issue_block(jb + 1, buf ^ 1);
-#endif
 
         // ---- scores: acc[qs][t][r] = s(query q0 + 16 qs + li, key 64 jb + 16 kb + 4 t + r) ----
         f32x4 acc[NQ][4];
@@ -259,13 +257,8 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
             const float mb = m_ref[qs] * kLog2e;
 #pragma unroll
             for (int e = 0; e < (SPARSE ? 4 : 8); ++e) {
-#ifdef DFSS_X_NOEXP
-                const float p0 = kept[qs][2 * e] * kLog2e - mb;
-                const float p1 = kept[qs][2 * e + 1] * kLog2e - mb;
-#else
                 const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(kept[qs][2 * e], kLog2e, -mb));
                 const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(kept[qs][2 * e + 1], kLog2e, -mb));
-#endif
                 pk[qs][e] = pack_bf16x2(p0, p1);
             }
         }
@@ -324,9 +317,6 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
         }
     }
 
-#ifdef DFSS_X_NOSYNC
-    wait_async_copies();
-#endif
     // ---- O[q][16 ds + li] = acc_o / row sum, q = q0 + 16 qs + 4 kb + r ----
 #pragma unroll
     for (int qs = 0; qs < NQ; ++qs)

@@ -249,7 +249,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
 // ---------------------------------------------------------------------------------------------
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-template <int D, int MODE, bool PRESCALE, int NST>
+template <int D, int MODE, bool PRESCALE>
 __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
                                                    int Lq, int Lk, float scale, int ksplit, int blocks_per_wg,
                                                    uint32_t *__restrict__ out, uint32_t *__restrict__ meta) {
@@ -258,7 +258,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
     constexpr int LPT = TILE / NT;       // asynchronous copies per thread per block
     constexpr int STEPS = D / 16;        // k-steps of the 32x32x16 MFMA
     constexpr int TQ = 128;              // queries per workgroup (4 waves x 32)
-    __shared__ u32x4 Ks[NST][TILE];   // ring of NST K blocks: copies run NST-1 blocks ahead of the reads
+    __shared__ u32x4 Ks[2][TILE];        // double buffer: the copy of block it+1 runs under the work on block it
     // per-wave staging of the kept values of one 64-key pair (32 rows x 64 bytes), so that they leave
     // as 64-byte row segments from consecutive lanes instead of 16-byte pieces scattered over 32 rows
     __shared__ u32x4 Stage[MODE == MODE_DENSE ? 1 : 4][32 * 4];
@@ -294,9 +294,6 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
     };
 
     issue_block(jb0, 0);
-    if constexpr (NST == 3) {
-        if (blocks_per_wg > 1) issue_block(jb0 + 1, 1);
-    }
 
     // Q operand: lane (column lj, half h) of step s holds Q[q][16 s + 8 h .. +7]
     bf16x8 bq[STEPS];
@@ -315,19 +312,11 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
         }
     }
 
-#ifdef DFSS_X_SMALLOUT
-    const size_t row = ((size_t)bh * Lq + q0 + lj) & 255;   // experiment: every wave writes into the first 256 rows
-#else
     const size_t row = (size_t)bh * Lq + q0 + lj;
-#endif
     // read-back role of this lane when the staged pair is written out: store c (0/1) covers rows
     // 16 c + l/4, 16-byte chunk l%4 of the row's 64 bytes; chunks are XOR-swizzled by (row/2)%4
     const int sb_row = l >> 2, sb_chunk = l & 3;
-#ifdef DFSS_X_SMALLOUT
-    uint32_t *const out_sb0 = out + ((((size_t)bh * Lq + q0 + sb_row) & 127) * (size_t)(Lk / 2)) / 2 + sb_chunk * 4;
-#else
     uint32_t *const out_sb0 = out + (((size_t)bh * Lq + q0 + sb_row) * (size_t)(Lk / 2)) / 2 + sb_chunk * 4;
-#endif
     uint32_t *const out_sb1 = out_sb0 + (size_t)16 * (Lk / 4);
     // metadata of (row, block jb): 16 bytes at ((row block * blocks + jb) * 16 + row % 16) * 4 words;
     // a lane computes the words of chunks (p = 0, h) and (p = 1, h) = slots 2 h and 2 h + 1 of its row
@@ -336,17 +325,14 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
 
     for (int it = 0; it < blocks_per_wg; ++it) {
         const int jb = jb0 + it;
-        const int buf = it % NST;
-        // Block `it` must have landed.  Younger vector-memory operations of this wave may stay in
-        // flight: the stores of the previous iteration(s) and, with a 3-deep ring, the copies of the
-        // next block.  (All waves of a compute unit share one in-order memory pipeline, so a copy
-        // issued just one block ahead would queue behind everybody's stores; two blocks ahead hides it.)
-        constexpr int kStores = MODE == MODE_DENSE ? 8 : 5;   // exact count per iteration (or lower): 2 x 2 values + 1 metadata
+        const int buf = it & 1;
+        // Block `it` must have landed.  The stores of the previous iteration were issued after its
+        // copy and may stay in flight (waiting for them would expose the store latency every block).
+        constexpr int kStores = MODE == MODE_DENSE ? 8 : 5;   // stores per iteration, exactly (or lower): 2 x 2 values + 1 metadata
         if (it == 0) wait_async_copies();
-        else if (NST == 3 && it + 1 < blocks_per_wg) wait_async_copies_keep<kStores + LPT>();
         else wait_async_copies_keep<kStores>();
         __syncthreads();       // ... for every wave, and everybody is done with the block before
-        if (it + NST - 1 < blocks_per_wg) issue_block(jb + NST - 1, (it + NST - 1) % NST);
+        if (it + 1 < blocks_per_wg) issue_block(jb + 1, buf ^ 1);
 
         u32x2 mwords = {0u, 0u};
 #pragma unroll
@@ -390,32 +376,24 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
                         if constexpr (!PRESCALE) { a0 *= scale; a1 *= scale; a2 *= scale; a3 *= scale; }
                         float lo, hi;
                         uint32_t code;
-#ifdef DFSS_X_NOSELECT
-                        lo = a0 + a2; hi = a1 + a3; code = 0x4u << (16 * u + 4 * g);
-#else
                         if constexpr (MODE == MODE_2TO4) select_2of4(a0, a1, a2, a3, 16 * u + 4 * g, lo, hi, code);
                         else select_1of2(a0, a1, a2, a3, 16 * u + 4 * g, lo, hi, code);
-#endif
                         pk[u][g] = pack_bf16x2(lo, hi);
                         word |= code;
                     }
-#ifdef DFSS_X_DIRECTSTORE
-                u32x4 *dst = reinterpret_cast<u32x4 *>(out + (row * (size_t)(Lk / 2) + kbase / 2) / 2);
-                dst[0] = pk[0];
-                dst[1] = pk[1];
-#else
                 // stage: this lane's 32 bytes are chunks 2h, 2h+1 of row lj
                 u32x4 *const st = Stage[w];
                 const int sw = (lj >> 1) & 3;
                 st[lj * 4 + ((2 * h) ^ sw)] = pk[0];
                 st[lj * 4 + ((2 * h + 1) ^ sw)] = pk[1];
+                wave_lds_sync();
                 // write out: two stores of 16 rows x 64 contiguous bytes
                 const size_t pair_off = (size_t)(KB * jb + 64 * p) / 4;   // dwords into the row of kept values
                 const u32x4 v0 = st[sb_row * 4 + (sb_chunk ^ ((sb_row >> 1) & 3))];
                 const u32x4 v1 = st[(16 + sb_row) * 4 + (sb_chunk ^ (((16 + sb_row) >> 1) & 3))];
+                wave_lds_sync();   // the staging rows are free for the next pair
                 *reinterpret_cast<u32x4 *>(out_sb0 + pair_off) = v0;
                 *reinterpret_cast<u32x4 *>(out_sb1 + pair_off) = v1;
-#endif
                 mwords[p] = word;
             }
         }
@@ -424,7 +402,9 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
             // buffer so that lanes 0..31 store the 16 bytes of rows 0..31 (two contiguous 256-byte runs)
             u32x2 *const sm = reinterpret_cast<u32x2 *>(Stage[w]);
             sm[lj * 2 + h] = mwords;
+            wave_lds_sync();
             const u32x4 m4 = Stage[w][lj];
+            wave_lds_sync();
             if (h == 0) meta_row4[(size_t)jb * 16] = m4;
         }
     }
@@ -471,7 +451,7 @@ hipError_t launch32(const void *Q, const void *K, int BH, int Lq, int Lk, int d,
     const unsigned grid = (unsigned)((long)BH * qtiles * ksplit);
     const bool pre = is_pow2(scale);
 #define DFSS_LAUNCH(DD, PRE)                                                                             \
-    hipLaunchKernelGGL((k_sddmm32<DD, MODE, PRE, 2>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)Q, \
+    hipLaunchKernelGGL((k_sddmm32<DD, MODE, PRE>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)Q, \
                        (const __bf16 *)K, Lq, Lk, scale, ksplit, per_wg, (uint32_t *)out, (uint32_t *)meta)
     if (d == 64) {
         if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);

@@ -15,6 +15,7 @@
 // instruction h (0/1) of a block takes, for its 16-wide contraction chunk c, the keys
 // 32c + 16h .. +15 of the block -- the 16 keys whose kept weights lane group c holds in
 // half h of its 32 bytes.
+#include <cstdlib>
 #include "dfss_device.hpp"
 #include "dfss_kernels.hpp"
 
@@ -184,8 +185,10 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
 template <bool SPARSE>
 hipError_t launch(const void *P, const void *meta, const void *V, int BH, int Lq, int Lk, int d, void *O,
                   hipStream_t st) {
-    // two row blocks per wave when that still leaves a few workgroups per compute unit
-    const bool rb2 = (Lq % 128 == 0) && ((long)BH * (Lq / 128) >= 1024);
+    // two row blocks per wave when that still leaves two workgroups per compute unit (measured:
+    // from there on the larger tile wins, below it the finer grid does)
+    bool rb2 = (Lq % 128 == 0) && ((long)BH * (Lq / 128) >= 512);
+    if (const char *f = getenv("DFSS_SPMM_RB")) rb2 = (Lq % 128 == 0) && f[0] == '2';   // for measurements
     const unsigned grid = (unsigned)((long)BH * (Lq / (rb2 ? 128 : 64)));
 #define DFSS_LAUNCH(DD, RR)                                                                                   \
     hipLaunchKernelGGL((k_av<DD, SPARSE, RR>), dim3(grid), dim3(NT), 0, st, (const uint32_t *)P,              \

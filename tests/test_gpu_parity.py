@@ -54,17 +54,19 @@ def _stage1(Qt, Kt, s, scale):
 # ----------------------------------------------------------------------------------
 # stage 1: bit-exact on integer inputs
 # ----------------------------------------------------------------------------------
-@pytest.mark.parametrize("BH,Lq,Lk,d,N,M", [
-    (1, 256, 256, 64, 2, 4),     # the tiny check of the task
-    (3, 128, 384, 64, 2, 4),     # several heads, rectangular, several key tiles
-    (2, 192, 256, 128, 2, 4),    # d = 128
-    (2, 128, 256, 64, 1, 2),     # 1:2
-    (1, 64, 128, 128, 1, 2),     # smallest legal shape
+@pytest.mark.parametrize("BH,Lq,Lk,d,N,M,scale", [
+    (1, 256, 256, 64, 2, 4, 0.125),     # the tiny check of the task
+    (3, 128, 384, 64, 2, 4, 0.125),     # several heads, rectangular, several key tiles
+    (2, 192, 256, 128, 2, 4, 0.125),    # d = 128, 16-query tiles (Lq not a multiple of 128)
+    (2, 128, 256, 64, 1, 2, 0.125),     # 1:2
+    (1, 64, 128, 128, 1, 2, 0.125),     # smallest legal shape
+    (1, 128, 8192, 64, 2, 4, 0.125),    # longest key sequence the library accepts
+    (2, 128, 256, 128, 2, 4, float(np.float32(1.0 / math.sqrt(128.0)))),   # scale applied after the product
+    (2, 192, 384, 64, 1, 2, float(np.float32(1.0 / 3.0))),                  # same, 16-query tiles, 1:2
 ])
-def test_stage1_bit_exact_on_integer_inputs(BH, Lq, Lk, d, N, M):
+def test_stage1_bit_exact_on_integer_inputs(BH, Lq, Lk, d, N, M, scale):
     Q, K, _ = synth.integer_qkv(BH, Lq, Lk, d, seed=1002 + Lq + d + N)
     s = Shape(1, BH, Lq, Lk, d, N, M)
-    scale = 0.125
     vals, meta = _stage1(Q, K, s, scale)
     Qn, Kn = synth.to_numpy_f32(Q), synth.to_numpy_f32(K)
     ties = 0
@@ -284,6 +286,31 @@ def test_fused_attention_every_tile_shape(tile, BH, L, d, N, M):
     Qn, Kn, Vn = (synth.to_numpy_f32(t) for t in (Q, K, V))
     assert np.max(np.abs(_np(O) - oracle.attention(Qn, Kn, Vn, N, M, scale))) <= 2e-2
     assert np.max(np.abs(_np(Od) - oracle.attention(Qn, Kn, Vn, 1, 1, scale))) <= 2e-2
+
+
+@pytest.mark.parametrize("BH,Lq,Lk,d,N,M", [
+    (2, 128, 640, 64, 2, 4),     # more keys than queries, 5 key blocks of 128
+    (3, 320, 128, 64, 1, 2),     # more queries than keys, Lq a multiple of 64 only
+    (1, 64, 8192, 128, 2, 4),    # longest key sequence, smallest query tile
+])
+def test_attention_rectangular(BH, Lq, Lk, d, N, M):
+    """Lq != Lk (cross attention): fused kernel, stage kernels and both dense baselines."""
+    Q, K, V = synth.gaussian_qkv(BH, Lq, Lk, d, 1.0, seed=31 + Lq + Lk)
+    s = Shape(1, BH, Lq, Lk, d, N, M)
+    scale = 1.0 / math.sqrt(d)
+    Qd, Kd, Vd = _dev(Q), _dev(K), _dev(V)
+    O = dfss.dfss_attention(Qd, Kd, Vd, s, scale)
+    Os = _staged_attention(Qd, Kd, Vd, s, scale)
+    Od = dfss.dense_attention(Qd, Kd, Vd, s, scale)
+    Odf = dfss.dense_attention_fused(Qd, Kd, Vd, s, scale)
+    torch.cuda.synchronize()
+    Qn, Kn, Vn = (synth.to_numpy_f32(t) for t in (Q, K, V))
+    ref = oracle.attention(Qn, Kn, Vn, N, M, scale)
+    ref_dense = oracle.attention(Qn, Kn, Vn, 1, 1, scale)
+    assert np.max(np.abs(_np(O) - ref)) <= 2e-2
+    assert np.max(np.abs(_np(Os) - ref)) <= 2e-2
+    assert np.max(np.abs(_np(Od) - ref_dense)) <= 2e-2
+    assert np.max(np.abs(_np(Odf) - ref_dense)) <= 2e-2
 
 
 @pytest.mark.parametrize("tile", ["16", "32x2"])
