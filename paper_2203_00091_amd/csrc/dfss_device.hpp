@@ -61,17 +61,23 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const void *p) {
 // s_waitcnt vmcnt(..) and a workgroup barrier before other waves read the data.  Written as
 // inline assembly so that the compiler does not serialise later LDS reads of OTHER buffers
 // against copies that are still in flight, and so that no vector ALU work is spent on addresses.
-__device__ __forceinline__ void async_copy16(const void *gbase, uint32_t lane_off, uint32_t lds_wave_addr) {
-    // pin the base into scalar registers (a no-op when the compiler already knows it is uniform)
-    const uint64_t g = (uint64_t)(uintptr_t)gbase;
+// A global address known to be the same in every lane, moved into scalar registers once (so that
+// address arithmetic derived from it stays on the scalar unit).
+__device__ __forceinline__ uint64_t uniform_address(const void *p) {
+    const uint64_t g = (uint64_t)(uintptr_t)p;
     // (readfirstlane returns a signed int: widen through uint32_t, or the low half sign-extends)
     const uint32_t g_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(g >> 32));
     const uint32_t g_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)g);
-    const uint64_t gs = ((uint64_t)g_hi << 32) | (uint64_t)g_lo;
+    return ((uint64_t)g_hi << 32) | (uint64_t)g_lo;
+}
+__device__ __forceinline__ void async_copy16(uint64_t uniform_base, uint32_t lane_off, uint32_t lds_wave_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(lds_wave_addr), "v"(lane_off), "s"(gs)
+                 : "s"(lds_wave_addr), "v"(lane_off), "s"(uniform_base)
                  : "memory", "m0");
+}
+__device__ __forceinline__ void async_copy16(const void *gbase, uint32_t lane_off, uint32_t lds_wave_addr) {
+    async_copy16(uniform_address(gbase), lane_off, lds_wave_addr);
 }
 // LDS byte address of a __shared__ object, as a wave-uniform scalar.
 __device__ __forceinline__ uint32_t lds_address(const void *shared_ptr) {

@@ -124,9 +124,10 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
         v_off[i] = slot * D + ((p % CPR) ^ ((slot & 3) << 1)) * 8;
     }
     const uint32_t lds_k = lds_address(&Ks[0][w * 64]), lds_v = lds_address(&Vs[0][w * 64]);
+    const uint64_t k_base = uniform_address(Kh), v_base = uniform_address(Vh);
     auto issue_block = [&](int jb, int buf) {
-        const __bf16 *ks = Kh + (size_t)jb * KB * D;
-        const __bf16 *vs = Vh + (size_t)jb * KB * D;
+        const uint64_t ks = k_base + (uint64_t)jb * (KB * D * 2);
+        const uint64_t vs = v_base + (uint64_t)jb * (KB * D * 2);
 #pragma unroll
         for (int i = 0; i < LPT; ++i) async_copy16(ks, 2u * k_off[i], lds_k + 16u * (buf * TILE + i * NT));
 #pragma unroll
@@ -216,27 +217,30 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
                     kept[qs][2 * t] = lo;
                     kept[qs][2 * t + 1] = hi;
                     idx[qs] |= code;
-                    m_blk[qs] = fmaxf(m_blk[qs], fmaxf(lo, hi));
+                    m_blk[qs] = fmaxf(fmaxf(m_blk[qs], lo), hi);   // one v_max3_f32
                 } else {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) kept[qs][4 * t + r] = a[r];
                     m_blk[qs] = fmaxf(m_blk[qs], fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])));
                 }
             }
-            // the four lanes kb = 0..3 of a column hold different keys of the same query
-            m_blk[qs] = fmaxf(m_blk[qs], __shfl_xor(m_blk[qs], 16, 64));
-            m_blk[qs] = fmaxf(m_blk[qs], __shfl_xor(m_blk[qs], 32, 64));
         }
 
         // ---- raise the reference value where a block outgrew it (rare after the first block) ----
+        // Every lane tests its own 16 keys; only when some lane of the wave sees a score above
+        // reference + tau are the maxima of the four lanes kb = 0..3 of a column (different keys of the
+        // same query) combined, so that the common path has no cross-lane traffic.
         bool raise = false;
 #pragma unroll
         for (int qs = 0; qs < NQ; ++qs) raise |= m_blk[qs] > m_ref[qs] + kTau;
         if (__any(raise)) {
 #pragma unroll
             for (int qs = 0; qs < NQ; ++qs) {
-                const bool up = m_blk[qs] > m_ref[qs] + kTau;
-                const float m_new = up ? m_blk[qs] : m_ref[qs];
+                float mb = m_blk[qs];
+                mb = fmaxf(mb, __shfl_xor(mb, 16, 64));
+                mb = fmaxf(mb, __shfl_xor(mb, 32, 64));
+                const bool up = mb > m_ref[qs] + kTau;
+                const float m_new = up ? mb : m_ref[qs];
                 const float alpha = __builtin_amdgcn_exp2f((m_ref[qs] - m_new) * kLog2e);  // 1 where unchanged
                 m_ref[qs] = m_new;
                 // rows of acc_o/acc_l are queries 4 kb + r: fetch their factors from the lanes of that column
@@ -322,7 +326,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
     for (int qs = 0; qs < NQ; ++qs)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const float inv = 1.0f / acc_l[qs][r];
+            const float inv = __builtin_amdgcn_rcpf(acc_l[qs][r]);   // 1 ulp; the row sum is >= ~1: the reference never exceeds the row maximum
             const size_t q = (size_t)bh * Lq + q0 + 16 * qs + 4 * kb + r;
 #pragma unroll
             for (int ds = 0; ds < DS; ++ds)
