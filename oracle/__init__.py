@@ -62,6 +62,11 @@ def _load():
         L.oracle_attention_batched.argtypes = [_f32p, _f32p, _f32p, c_int, c_int, c_int, c_int,
                                                c_int, c_int, c_float, c_int, _f32p]
         L.oracle_attention_batched.restype = c_int
+        L.oracle_attention_bias_batched.argtypes = [_f32p, _f32p, _f32p, _f32p, c_int, c_int, c_int, c_int,
+                                                    c_int, c_int, c_int, c_float, c_int, _f32p]
+        L.oracle_attention_bias_batched.restype = c_int
+        L.oracle_add_key_bias.argtypes = [_f32p, c_int, c_int, _f32p]
+        L.oracle_add_key_bias.restype = None
         L.oracle_num_threads.argtypes = []
         L.oracle_num_threads.restype = c_int
         L.oracle_quality_p.argtypes = [_f32p, _u8p, c_int, c_int, c_double]
@@ -82,6 +87,16 @@ def scores(Q, K, scale):
     assert d == d2
     S = np.empty((Lq, Lk), np.float32)
     _load().oracle_scores(Q, K, Lq, Lk, d, float(scale), S)
+    return S
+
+
+def add_key_bias(S, bias):
+    """S + bias[None, :] in fp32 (additive key mask applied before the N:M comparison)."""
+    S = _f32(S).copy()
+    bias = _f32(bias)
+    Lq, Lk = S.shape
+    assert bias.shape == (Lk,)
+    _load().oracle_add_key_bias(S, Lq, Lk, bias)
     return S
 
 
@@ -145,8 +160,12 @@ def round_bf16(x):
     return y
 
 
-def attention(Q, K, V, N, M, scale, store_bf16=False):
-    """Whole forward for [BH, L, d] (or [L, d]) inputs; heads run on host threads."""
+def attention(Q, K, V, N, M, scale, store_bf16=False, key_bias=None, heads_per_batch=1):
+    """Whole forward for [BH, L, d] (or [L, d]) inputs; heads run on host threads.
+
+    key_bias: optional float32 [BH // heads_per_batch, Lk] (or [Lk] for a single head), added to
+    the scaled scores before the N:M selection; -inf masks a key.
+    """
     Q, K, V = _f32(Q), _f32(K), _f32(V)
     squeeze = Q.ndim == 2
     if squeeze:
@@ -154,8 +173,16 @@ def attention(Q, K, V, N, M, scale, store_bf16=False):
     BH, Lq, d = Q.shape
     Lk = K.shape[1]
     O = np.empty((BH, Lq, d), np.float32)
-    rc = _load().oracle_attention_batched(Q, K, V, BH, Lq, Lk, d, N, M, float(scale),
-                                          int(bool(store_bf16)), O)
+    if key_bias is None:
+        rc = _load().oracle_attention_batched(Q, K, V, BH, Lq, Lk, d, N, M, float(scale),
+                                              int(bool(store_bf16)), O)
+    else:
+        kb = _f32(key_bias)
+        if kb.ndim == 1:
+            kb = kb[None]
+        assert BH % heads_per_batch == 0 and kb.shape == (BH // heads_per_batch, Lk), kb.shape
+        rc = _load().oracle_attention_bias_batched(Q, K, V, kb, int(heads_per_batch), BH, Lq, Lk, d, N, M,
+                                                   float(scale), int(bool(store_bf16)), O)
     if rc != 0:
         raise ValueError(f"oracle_attention failed rc={rc}")
     return O[0] if squeeze else O

@@ -26,6 +26,8 @@
  *     comparison, so the comparison sees exactly the value that is stored;
  *   - accumulation of the dot product is fp32, sequential in k (the paper
  *     accumulates in float regardless of input type, App. A.1.2);
+ *   - masks are not in the paper: an optional per-key bias is added to the
+ *     scaled score in fp32 before the comparison (-inf masks a key);
  *   - position code = lower kept position in bits [1:0], higher in bits [3:2];
  *     this is the unique 2-bit-per-position rule that reproduces the two
  *     codes the paper prints (0x4 for "first float", 0xe for "second float").
@@ -59,6 +61,23 @@ void oracle_scores(const float *Q, const float *K, int Lq, int Lk, int d,
             S[(size_t)i * Lk + j] = acc * scale;
         }
     }
+}
+
+/* ------------------------------------------------------------------ */
+/* Stage 1a': additive key bias (padding mask).                        */
+/* The paper never mentions masks; real inputs (padded batches) need   */
+/* one, so the reading taken is the usual one for Eq. 1: a per-key     */
+/* term is ADDED to the scaled score in fp32, BEFORE the N:M           */
+/* comparison (so that a masked key loses against any unmasked one of  */
+/* its group), S[i][j] <- S[i][j] + bias[j].  bias[j] = -inf masks key */
+/* j; a group whose keys are all masked still emits N entries, which   */
+/* the softmax then weights with exactly 0.  bias is [Lk].             */
+/* ------------------------------------------------------------------ */
+void oracle_add_key_bias(float *S, int Lq, int Lk, const float *bias)
+{
+    for (int i = 0; i < Lq; ++i)
+        for (int j = 0; j < Lk; ++j)
+            S[(size_t)i * Lk + j] = S[(size_t)i * Lk + j] + bias[j];
 }
 
 /* ------------------------------------------------------------------ */
@@ -230,10 +249,10 @@ void oracle_round_bf16_array(const float *x, size_t n, float *y)
 /* Optional outputs (may be NULL): mask, vals (after optional rounding,*/
 /* before softmax), kidx, P.                                           */
 /* ------------------------------------------------------------------ */
-int oracle_attention(const float *Q, const float *K, const float *V,
-                     int Lq, int Lk, int d, int N, int M, float scale,
-                     int store_bf16, float *O,
-                     uint8_t *mask_out, float *vals_out, int32_t *kidx_out, float *P_out)
+int oracle_attention_bias(const float *Q, const float *K, const float *V, const float *key_bias,
+                          int Lq, int Lk, int d, int N, int M, float scale,
+                          int store_bf16, float *O,
+                          uint8_t *mask_out, float *vals_out, int32_t *kidx_out, float *P_out)
 {
     if (M <= 0 || N <= 0 || N > M || Lk % M != 0) return -1;
     const int Lc = Lk / M * N;
@@ -245,6 +264,7 @@ int oracle_attention(const float *Q, const float *K, const float *V,
     int rc = -3;
     if (S && mask && vals && kidx && P) {
         oracle_scores(Q, K, Lq, Lk, d, scale, S);
+        if (key_bias) oracle_add_key_bias(S, Lq, Lk, key_bias);   /* NULL = no mask (the paper's case) */
         rc = oracle_prune(S, Lq, Lk, N, M, mask, vals, kidx);
         if (rc == 0) {
             if (store_bf16) oracle_round_bf16_array(vals, (size_t)Lq * Lc, vals);
@@ -261,21 +281,33 @@ int oracle_attention(const float *Q, const float *K, const float *V,
     return rc;
 }
 
+int oracle_attention(const float *Q, const float *K, const float *V,
+                     int Lq, int Lk, int d, int N, int M, float scale,
+                     int store_bf16, float *O,
+                     uint8_t *mask_out, float *vals_out, int32_t *kidx_out, float *P_out)
+{
+    return oracle_attention_bias(Q, K, V, NULL, Lq, Lk, d, N, M, scale, store_bf16, O,
+                                 mask_out, vals_out, kidx_out, P_out);
+}
+
 /* Heads are independent (App. A.1.2, batched kernel): loop them, in parallel
  * over host threads when built with OpenMP.  Q,K,V,O are [BH][L][d]. */
-int oracle_attention_batched(const float *Q, const float *K, const float *V,
-                             int BH, int Lq, int Lk, int d, int N, int M,
-                             float scale, int store_bf16, float *O)
+/* key_bias (may be NULL) is [BH / heads_per_batch][Lk]: the heads of one batch element share
+ * one bias vector (a padding mask belongs to the sequence, not to the head). */
+int oracle_attention_bias_batched(const float *Q, const float *K, const float *V, const float *key_bias,
+                                  int heads_per_batch, int BH, int Lq, int Lk, int d, int N, int M,
+                                  float scale, int store_bf16, float *O)
 {
     int bad = 0;
 #ifdef _OPENMP
 #pragma omp parallel for schedule(dynamic, 1)
 #endif
     for (int h = 0; h < BH; ++h) {
-        int rc = oracle_attention(Q + (size_t)h * Lq * d, K + (size_t)h * Lk * d,
-                                  V + (size_t)h * Lk * d, Lq, Lk, d, N, M, scale,
-                                  store_bf16, O + (size_t)h * Lq * d,
-                                  NULL, NULL, NULL, NULL);
+        const float *bias = key_bias ? key_bias + (size_t)(h / heads_per_batch) * Lk : NULL;
+        int rc = oracle_attention_bias(Q + (size_t)h * Lq * d, K + (size_t)h * Lk * d,
+                                       V + (size_t)h * Lk * d, bias, Lq, Lk, d, N, M, scale,
+                                       store_bf16, O + (size_t)h * Lq * d,
+                                       NULL, NULL, NULL, NULL);
         if (rc != 0) {
 #ifdef _OPENMP
 #pragma omp atomic write
@@ -284,6 +316,13 @@ int oracle_attention_batched(const float *Q, const float *K, const float *V,
         }
     }
     return bad;
+}
+
+int oracle_attention_batched(const float *Q, const float *K, const float *V,
+                             int BH, int Lq, int Lk, int d, int N, int M,
+                             float scale, int store_bf16, float *O)
+{
+    return oracle_attention_bias_batched(Q, K, V, NULL, 1, BH, Lq, Lk, d, N, M, scale, store_bf16, O);
 }
 
 int oracle_num_threads(void)
