@@ -48,6 +48,8 @@ def parse_args():
     ap.add_argument("--warm", action="store_true", help="single buffer set (cache-resident)")
     ap.add_argument("--no-graph", action="store_true", help="launch steps directly instead of one HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--key-padding", action="store_true",
+                    help="run the key-bias entry points on a padded batch (seeded lengths in [L/2, L])")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 64 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
@@ -95,17 +97,32 @@ def main():
             ws=torch.empty(max(ws_sparse, ws_dense), dtype=torch.uint8, device=dev)))
     torch.cuda.synchronize()
 
+    # padded batch: additive key bias, 0 for real keys and -inf for padding (None = no mask)
+    bias = None
+    if args.key_padding:
+        lengths = synth.padding_lengths(w.B, L, w.seed + 7)
+        bias = synth.key_padding_bias(lengths, L).to(dev)
+
     def step_sparse(i):
         b = sets[i % nsets]
-        dfss.dfss_attention(b["Q"], b["K"], b["V"], s, w.scale, O=b["O"], ws=b["ws"])
+        if bias is None:
+            dfss.dfss_attention(b["Q"], b["K"], b["V"], s, w.scale, O=b["O"], ws=b["ws"])
+        else:
+            dfss.dfss_attention_bias(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"], ws=b["ws"])
 
     def step_dense(i):
         b = sets[i % nsets]
-        dfss.dense_attention(b["Q"], b["K"], b["V"], s, w.scale, O=b["O"], ws=b["ws"])
+        if bias is None:
+            dfss.dense_attention(b["Q"], b["K"], b["V"], s, w.scale, O=b["O"], ws=b["ws"])
+        else:
+            dfss.dense_attention_bias(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"], ws=b["ws"])
 
     def step_dense_fused(i):
         b = sets[i % nsets]
-        dfss.dense_attention_fused(b["Q"], b["K"], b["V"], s, w.scale, O=b["O"])
+        if bias is None:
+            dfss.dense_attention_fused(b["Q"], b["K"], b["V"], s, w.scale, O=b["O"])
+        else:
+            dfss.dense_attention_fused_bias(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"])
 
     def step_sparse_staged(i):
         os.environ["DFSS_ATTENTION_PATH"] = "staged"
@@ -119,7 +136,10 @@ def main():
         n_vals = dfss.dfss_vals_bytes(s)
         vals = b["ws"][:n_vals]
         meta = b["ws"][(n_vals + 255) // 256 * 256:]
-        dfss.dfss_sddmm_prune(b["Q"], b["K"], s, w.scale, vals=vals, meta=meta)
+        if bias is None:
+            dfss.dfss_sddmm_prune(b["Q"], b["K"], s, w.scale, vals=vals, meta=meta)
+        else:
+            dfss.dfss_sddmm_prune_bias(b["Q"], b["K"], bias, s, w.scale, vals=vals, meta=meta)
 
     def step_stage2(i):
         b = sets[i % nsets]
@@ -226,7 +246,7 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "L": L, "d": d, "N": w.N, "M": w.M,
-                   "buffer_sets": nsets, "cache": "warm" if args.warm else "cold (rotating buffer sets)",
+                   "key_padding": bool(args.key_padding), "buffer_sets": nsets, "cache": "warm" if args.warm else "cold (rotating buffer sets)",
                    "launch": "hip graph of all timed steps" if use_graph else "direct"},
         "roofline": {"bound": "mfma", "kernel": "k_fused (dfss_attention)", "achieved": round(achieved, 2),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",

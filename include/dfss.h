@@ -50,7 +50,8 @@ typedef enum {
 typedef enum { DFSS_BF16 = 0 } dfss_dtype;
 
 typedef struct {
-    int32_t B, H;   /* batch and heads; only the product B*H matters                    */
+    int32_t B, H;   /* batch and heads; only the product B*H matters, except that a     */
+                    /* key bias is indexed by the batch element b = (b*H + h) / H       */
     int32_t Lq, Lk; /* number of queries (rows of S) and keys (columns of S)            */
     int32_t d;      /* head dimension                                                   */
     int32_t N, M;   /* keep N of every M consecutive keys: (2,4) or (1,2)               */
@@ -106,6 +107,31 @@ dfss_status dense_attention(const void *Q, const void *K, const void *V, const d
  * written): the stronger full-attention baseline, reported next to dense_attention. */
 dfss_status dense_attention_fused(const void *Q, const void *K, const void *V, const dfss_shape *s,
                                   float scale, void *O, void *stream);
+
+/* ---- additive key bias (padding mask) ---------------------------------------------- */
+/* The paper has no mask; padded batches need one.  Reading taken: key_bias[b][j] (float32,
+ * device, [B, Lk] row-major, 16-byte aligned, shared by the H heads and all queries of batch
+ * element b) is ADDED to the scaled score in fp32 BEFORE the N:M comparison of stage 1, so a
+ * masked key (bias = -inf) loses against any unmasked key of its group; a run of M keys that is
+ * entirely masked still emits N entries, whose softmax weight is exactly 0.  Sequences whose
+ * length is not a multiple of the tile sizes are run by padding the buffers up to Lq % 64 == 0,
+ * Lk % 128 == 0 and masking the padded keys this way (padded query rows produce rows the caller
+ * ignores).  Precondition: every batch element has at least one key with a finite bias.
+ * key_bias == NULL means no bias: each call then equals the call without the suffix.  All other
+ * arguments, layouts and error behaviour are those of the call without the suffix.
+ * Arithmetic: when scale is a power of two the bias is the initial value of the fp32 accumulator
+ * (identical to a separate addition whenever the bias is 0 or -inf, else equal up to the
+ * rounding order); otherwise it is added by a separate fp32 addition after the scaling. */
+dfss_status dfss_sddmm_prune_bias(const void *Q, const void *K, const void *key_bias, const dfss_shape *s,
+                                  float scale, void *vals, void *meta, void *stream);
+dfss_status dfss_attention_bias(const void *Q, const void *K, const void *V, const void *key_bias,
+                                const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes,
+                                void *stream);
+dfss_status dense_attention_bias(const void *Q, const void *K, const void *V, const void *key_bias,
+                                 const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes,
+                                 void *stream);
+dfss_status dense_attention_fused_bias(const void *Q, const void *K, const void *V, const void *key_bias,
+                                       const dfss_shape *s, float scale, void *O, void *stream);
 
 /* ---- metadata order ---------------------------------------------------------------- */
 /* Canonical order: uint16 [B*H, Lq, Lk/16], word w of a row = codes of key runs

@@ -8,13 +8,17 @@ from .binding import (  # noqa: F401
     DfssError,
     Shape,
     dense_attention,
+    dense_attention_bias,
     dense_attention_fused,
+    dense_attention_fused_bias,
     dense_workspace_bytes,
     dfss_attention,
+    dfss_attention_bias,
     dfss_meta_bytes,
     dfss_meta_from_canonical,
     dfss_meta_to_canonical,
     dfss_sddmm_prune,
+    dfss_sddmm_prune_bias,
     dfss_sparse_softmax,
     dfss_spmm,
     dfss_vals_bytes,

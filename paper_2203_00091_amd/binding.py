@@ -21,6 +21,7 @@ EXPORTS = (
     "dfss_vals_bytes", "dfss_meta_bytes", "dfss_workspace_bytes", "dense_workspace_bytes",
     "dfss_sddmm_prune", "dfss_sparse_softmax", "dfss_spmm", "dfss_attention", "dense_attention",
     "dense_attention_fused", "dfss_meta_to_canonical", "dfss_meta_from_canonical", "dfss_status_string",
+    "dfss_sddmm_prune_bias", "dfss_attention_bias", "dense_attention_bias", "dense_attention_fused_bias",
 )
 
 
@@ -84,10 +85,16 @@ def load_library():
         L.dfss_attention.argtypes = [vp, vp, vp, sp, f32, vp, vp, sz, vp]
         L.dense_attention.argtypes = [vp, vp, vp, sp, f32, vp, vp, sz, vp]
         L.dense_attention_fused.argtypes = [vp, vp, vp, sp, f32, vp, vp]
+        L.dfss_sddmm_prune_bias.argtypes = [vp, vp, vp, sp, f32, vp, vp, vp]
+        L.dfss_attention_bias.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
+        L.dense_attention_bias.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
+        L.dense_attention_fused_bias.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_meta_to_canonical.argtypes = [vp, sp, vp, vp]
         L.dfss_meta_from_canonical.argtypes = [vp, sp, vp, vp]
         for name in ("dfss_sddmm_prune", "dfss_sparse_softmax", "dfss_spmm", "dfss_attention",
-                     "dense_attention", "dense_attention_fused", "dfss_meta_to_canonical", "dfss_meta_from_canonical"):
+                     "dense_attention", "dense_attention_fused", "dfss_meta_to_canonical", "dfss_meta_from_canonical",
+                     "dfss_sddmm_prune_bias", "dfss_attention_bias", "dense_attention_bias",
+                     "dense_attention_fused_bias"):
             getattr(L, name).restype = ctypes.c_int
         L.dfss_status_string.argtypes = [ctypes.c_int]
         L.dfss_status_string.restype = ctypes.c_char_p
@@ -190,6 +197,60 @@ def dense_attention_fused(Q, K, V, s: Shape, scale: float, O=None):
     st = load_library().dense_attention_fused(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(s.c()), scale, _ptr(O),
                                               _stream())
     _check("dense_attention_fused", st)
+    return O
+
+
+def _bias_ptr(key_bias, s: Shape):
+    if key_bias is None:
+        return None
+    if key_bias.dtype != torch.float32 or tuple(key_bias.shape) != (s.B, s.Lk):
+        raise ValueError(f"key_bias must be float32 [B, Lk] = [{s.B}, {s.Lk}]")
+    return _ptr(key_bias)
+
+
+def dfss_sddmm_prune_bias(Q, K, key_bias, s: Shape, scale: float, vals=None, meta=None):
+    """Stage 1 with an additive key bias (float32 [B, Lk] device tensor, -inf masks a key)."""
+    if vals is None:
+        vals = torch.empty((s.BH, s.Lq, s.Lc), dtype=torch.bfloat16, device=Q.device)
+    if meta is None:
+        meta = torch.empty((s.BH * s.Lq * (s.Lk // 16),), dtype=torch.int16, device=Q.device)
+    st = load_library().dfss_sddmm_prune_bias(_ptr(Q), _ptr(K), _bias_ptr(key_bias, s), ctypes.byref(s.c()), scale,
+                                              _ptr(vals), _ptr(meta), _stream())
+    _check("dfss_sddmm_prune_bias", st)
+    return vals, meta
+
+
+def dfss_attention_bias(Q, K, V, key_bias, s: Shape, scale: float, O=None, ws=None):
+    """Whole DFSS forward with an additive key bias."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=Q.device)
+    if ws is None:
+        ws = _alloc_bytes(dfss_workspace_bytes(s), Q.device)
+    st = load_library().dfss_attention_bias(_ptr(Q), _ptr(K), _ptr(V), _bias_ptr(key_bias, s), ctypes.byref(s.c()),
+                                            scale, _ptr(O), _ptr(ws), ws.numel() * ws.element_size(), _stream())
+    _check("dfss_attention_bias", st)
+    return O
+
+
+def dense_attention_bias(Q, K, V, key_bias, s: Shape, scale: float, O=None, ws=None):
+    """Full attention (three stages) with an additive key bias."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=Q.device)
+    if ws is None:
+        ws = _alloc_bytes(dense_workspace_bytes(s), Q.device)
+    st = load_library().dense_attention_bias(_ptr(Q), _ptr(K), _ptr(V), _bias_ptr(key_bias, s), ctypes.byref(s.c()),
+                                             scale, _ptr(O), _ptr(ws), ws.numel() * ws.element_size(), _stream())
+    _check("dense_attention_bias", st)
+    return O
+
+
+def dense_attention_fused_bias(Q, K, V, key_bias, s: Shape, scale: float, O=None):
+    """Full attention in one kernel with an additive key bias."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=Q.device)
+    st = load_library().dense_attention_fused_bias(_ptr(Q), _ptr(K), _ptr(V), _bias_ptr(key_bias, s),
+                                                   ctypes.byref(s.c()), scale, _ptr(O), _stream())
+    _check("dense_attention_fused_bias", st)
     return O
 
 

@@ -13,7 +13,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Dims {
-    int BH, Lq, Lk, d, mode;
+    int BH, H, Lq, Lk, d, mode;
 };
 
 // Shape rules common to every entry point.  need_nm: also check N:M.
@@ -32,7 +32,7 @@ dfss_status check_shape(const dfss_shape *s, bool need_nm, Dims *out) {
         else if (s->N == 1 && s->M == 2) mode = 1;
         else return DFSS_ERR_UNSUPPORTED;
     }
-    if (out) *out = Dims{(int)bh, s->Lq, s->Lk, s->d, mode};
+    if (out) *out = Dims{(int)bh, s->H, s->Lq, s->Lk, s->d, mode};
     return DFSS_OK;
 }
 
@@ -80,15 +80,21 @@ size_t dense_workspace_bytes(const dfss_shape *s) {
     return align_up((size_t)D.BH * D.Lq * D.Lk * 2);
 }
 
-dfss_status dfss_sddmm_prune(const void *Q, const void *K, const dfss_shape *s, float scale, void *vals,
-                             void *meta, void *stream) {
+dfss_status dfss_sddmm_prune_bias(const void *Q, const void *K, const void *key_bias, const dfss_shape *s,
+                                  float scale, void *vals, void *meta, void *stream) {
     Dims D;
     if (!Q || !K || !vals || !meta) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, true, &D)) return st;
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
-    if (misaligned(Q) || misaligned(K) || misaligned(vals) || misaligned(meta)) return DFSS_ERR_SHAPE;
-    return hip_status(dfss::launch_sddmm_prune(Q, K, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, vals, meta,
-                                               (hipStream_t)stream));
+    if (misaligned(Q) || misaligned(K) || misaligned(vals) || misaligned(meta) || misaligned(key_bias))
+        return DFSS_ERR_SHAPE;
+    return hip_status(dfss::launch_sddmm_prune(Q, K, (const float *)key_bias, D.H, D.BH, D.Lq, D.Lk, D.d, D.mode,
+                                               scale, vals, meta, (hipStream_t)stream));
+}
+
+dfss_status dfss_sddmm_prune(const void *Q, const void *K, const dfss_shape *s, float scale, void *vals,
+                             void *meta, void *stream) {
+    return dfss_sddmm_prune_bias(Q, K, nullptr, s, scale, vals, meta, stream);
 }
 
 dfss_status dfss_sparse_softmax(void *vals, const dfss_shape *s, void *stream) {
@@ -108,50 +114,70 @@ dfss_status dfss_spmm(const void *vals, const void *meta, const void *V, const d
     return hip_status(dfss::launch_spmm(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, (hipStream_t)stream));
 }
 
-dfss_status dfss_attention(const void *Q, const void *K, const void *V, const dfss_shape *s, float scale, void *O,
-                           void *ws, size_t ws_bytes, void *stream) {
+dfss_status dfss_attention_bias(const void *Q, const void *K, const void *V, const void *key_bias,
+                                const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes, void *stream) {
     Dims D;
     if (!Q || !K || !V || !O || !ws) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, true, &D)) return st;
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
-    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O)) return DFSS_ERR_SHAPE;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias))
+        return DFSS_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0) return DFSS_ERR_SHAPE;
     if (ws_bytes < dfss_workspace_bytes(s)) return DFSS_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
+    const float *bias = (const float *)key_bias;
     if (!staged_path_requested())
-        return hip_status(dfss::launch_fused_attention(Q, K, V, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, O, st));
+        return hip_status(dfss::launch_fused_attention(Q, K, V, bias, D.H, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, O, st));
     char *vals = static_cast<char *>(ws);
     char *meta = vals + align_up(dfss_vals_bytes(s));
-    hipError_t e = dfss::launch_sddmm_prune(Q, K, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, vals, meta, st);
+    hipError_t e = dfss::launch_sddmm_prune(Q, K, bias, D.H, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, vals, meta, st);
     if (e == hipSuccess) e = dfss::launch_row_softmax(vals, (long)D.BH * D.Lq, D.Lk / 2, st);
     if (e == hipSuccess) e = dfss::launch_spmm(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, st);
     return hip_status(e);
 }
 
-dfss_status dense_attention_fused(const void *Q, const void *K, const void *V, const dfss_shape *s, float scale,
-                                  void *O, void *stream) {
+dfss_status dfss_attention(const void *Q, const void *K, const void *V, const dfss_shape *s, float scale, void *O,
+                           void *ws, size_t ws_bytes, void *stream) {
+    return dfss_attention_bias(Q, K, V, nullptr, s, scale, O, ws, ws_bytes, stream);
+}
+
+dfss_status dense_attention_fused_bias(const void *Q, const void *K, const void *V, const void *key_bias,
+                                       const dfss_shape *s, float scale, void *O, void *stream) {
     Dims D;
     if (!Q || !K || !V || !O) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, false, &D)) return st;
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
-    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O)) return DFSS_ERR_SHAPE;
-    return hip_status(dfss::launch_fused_attention(Q, K, V, D.BH, D.Lq, D.Lk, D.d, 2, scale, O, (hipStream_t)stream));
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias))
+        return DFSS_ERR_SHAPE;
+    return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, D.BH, D.Lq, D.Lk, D.d, 2,
+                                                   scale, O, (hipStream_t)stream));
 }
 
-dfss_status dense_attention(const void *Q, const void *K, const void *V, const dfss_shape *s, float scale, void *O,
-                            void *ws, size_t ws_bytes, void *stream) {
+dfss_status dense_attention_fused(const void *Q, const void *K, const void *V, const dfss_shape *s, float scale,
+                                  void *O, void *stream) {
+    return dense_attention_fused_bias(Q, K, V, nullptr, s, scale, O, stream);
+}
+
+dfss_status dense_attention_bias(const void *Q, const void *K, const void *V, const void *key_bias,
+                                 const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes, void *stream) {
     Dims D;
     if (!Q || !K || !V || !O || !ws) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, false, &D)) return st;
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
-    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O)) return DFSS_ERR_SHAPE;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias))
+        return DFSS_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0) return DFSS_ERR_SHAPE;
     if (ws_bytes < dense_workspace_bytes(s)) return DFSS_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    hipError_t e = dfss::launch_dense_scores(Q, K, D.BH, D.Lq, D.Lk, D.d, scale, ws, st);
+    hipError_t e = dfss::launch_dense_scores(Q, K, (const float *)key_bias, D.H, D.BH, D.Lq, D.Lk, D.d, scale, ws, st);
     if (e == hipSuccess) e = dfss::launch_row_softmax(ws, (long)D.BH * D.Lq, D.Lk, st);
     if (e == hipSuccess) e = dfss::launch_dense_av(ws, V, D.BH, D.Lq, D.Lk, D.d, O, st);
     return hip_status(e);
+}
+
+dfss_status dense_attention(const void *Q, const void *K, const void *V, const dfss_shape *s, float scale, void *O,
+                            void *ws, size_t ws_bytes, void *stream) {
+    return dense_attention_bias(Q, K, V, nullptr, s, scale, O, ws, ws_bytes, stream);
 }
 
 dfss_status dfss_meta_to_canonical(const void *meta, const dfss_shape *s, void *canon, void *stream) {

@@ -6,12 +6,14 @@
 
 namespace dfss {
 
+// key_bias (where present): fp32 [BH / H][Lk] added to the scaled scores before the selection, or
+// nullptr for none (then H is ignored).
 // Stage 1 (Sec. 3.4, App. A.1.2): scores + N:M pruning epilogue.  mode: 0 = 2:4, 1 = 1:2.
-hipError_t launch_sddmm_prune(const void *Q, const void *K, int BH, int Lq, int Lk, int d, int mode,
-                              float scale, void *vals, void *meta, hipStream_t st);
+hipError_t launch_sddmm_prune(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
+                              int d, int mode, float scale, void *vals, void *meta, hipStream_t st);
 // Dense scores S = scale * Q K^T stored as bfloat16 [BH, Lq, Lk] (Eq. 1), same mainloop.
-hipError_t launch_dense_scores(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale,
-                               void *S, hipStream_t st);
+hipError_t launch_dense_scores(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
+                               int d, float scale, void *S, hipStream_t st);
 // Row softmax in place over bfloat16 rows (App. A.1.3); rows of `cols` elements.
 hipError_t launch_row_softmax(void *x, long rows, int cols, hipStream_t st);
 // Stage 3 (Sec. 3.1): O = A_sparse V from compressed weights + metadata.
@@ -21,8 +23,8 @@ hipError_t launch_spmm(const void *vals, const void *meta, const void *V, int BH
 hipError_t launch_dense_av(const void *P, const void *V, int BH, int Lq, int Lk, int d, void *O,
                            hipStream_t st);
 // Whole forward pass in one kernel.  mode: 0 = 2:4, 1 = 1:2, 2 = dense (full attention, Eq. 1).
-hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d,
-                                  int mode, float scale, void *O, hipStream_t st);
+hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, const float *key_bias, int H, int BH,
+                                  int Lq, int Lk, int d, int mode, float scale, void *O, hipStream_t st);
 // Metadata word order: library <-> canonical.
 hipError_t launch_meta_reorder(const void *src, void *dst, int BH, int Lq, int W, bool to_canonical,
                                hipStream_t st);

@@ -85,10 +85,13 @@ __device__ __forceinline__ unsigned xcd_contiguous(unsigned id, unsigned total) 
     return id < per * 8 ? (id % 8) * per + id / 8 : id;
 }
 
-template <int D, int MODE, int NQ, bool PRESCALE>
+// BIAS: an additive per-key term (fp32, [B][Lk], shared by the H heads of a batch element; -inf masks a
+// key) joins the scaled score before the selection.  With the scale folded into Q it is simply the
+// initial value of the accumulators; otherwise it is added after the multiplication by scale.
+template <int D, int MODE, int NQ, bool PRESCALE, bool BIAS>
 __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
-                                                 const __bf16 *__restrict__ V, int Lq, int Lk, float scale,
-                                                 uint16_t *__restrict__ O) {
+                                                 const __bf16 *__restrict__ V, const float *__restrict__ key_bias,
+                                                 int H, int Lq, int Lk, float scale, uint16_t *__restrict__ O) {
     constexpr int CPR = D / 8;          // 16-byte chunks per row
     constexpr int TILE = KB * CPR;      // chunks per K (or V) block
     constexpr int LPT = TILE / NT;      // direct-to-LDS loads per thread per block and operand
@@ -161,7 +164,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
     f32x4 acc_o[NQ][DS], acc_l[NQ];
 #pragma unroll
     for (int qs = 0; qs < NQ; ++qs) {
-        m_ref[qs] = -3.0e38f;
+        m_ref[qs] = -1.0e30f;   // below any real score, and small enough that exp2((-inf) - m_ref) is 0, not NaN
         acc_l[qs] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ds = 0; ds < DS; ++ds) acc_o[qs][ds] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -172,6 +175,15 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
     const bf16x8 ones8 = __builtin_bit_cast(bf16x8, u32x4{one2, one2, one2, one2});
 
     const int tr_row = li >> 2, tr_sub = (li >> 1) & 1, tr_byte = 8 * (li & 1), tr_xor = tr_row << 1;
+
+    // bias of this lane's 16 keys of a block: keys 64 jb + 16 kb + 4 t + r  ->  four float4
+    const f32x4 *bias4 = nullptr;
+    f32x4 kb4[4];
+    if constexpr (BIAS) {
+        bias4 = reinterpret_cast<const f32x4 *>(key_bias + (size_t)(bh / H) * Lk + 16 * kb);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) kb4[t] = bias4[t];
+    }
 
     for (int jb = 0; jb < nblocks; ++jb) {
         const int buf = jb & 1;
@@ -184,7 +196,10 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
 #pragma unroll
         for (int qs = 0; qs < NQ; ++qs)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) acc[qs][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int t = 0; t < 4; ++t) {
+                if constexpr (BIAS && PRESCALE) acc[qs][t] = kb4[t];
+                else acc[qs][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
             bf16x8 ak[4];
@@ -208,7 +223,13 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 f32x4 a = acc[qs][t];
-                if constexpr (!PRESCALE) a = a * scale;
+                if constexpr (!PRESCALE) {
+                    a = a * scale;
+                    if constexpr (BIAS) {   // two roundings (product, then sum), never a fused multiply-add
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) a[r] = __fadd_rn(a[r], kb4[t][r]);
+                    }
+                }
                 if constexpr (SPARSE) {
                     float lo, hi;
                     uint32_t code;
@@ -223,6 +244,13 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
                     for (int r = 0; r < 4; ++r) kept[qs][4 * t + r] = a[r];
                     m_blk[qs] = fmaxf(m_blk[qs], fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])));
                 }
+            }
+        }
+
+        if constexpr (BIAS) {   // next block's bias, in flight during the rest of this block
+            if (jb + 1 < nblocks) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) kb4[t] = bias4[16 * (jb + 1) + t];
             }
         }
 
@@ -339,14 +367,14 @@ inline bool is_pow2(float x) {
     return frexpf(x, &e) == 0.5f;
 }
 
-template <int MODE, int NQ>
-hipError_t launch_nq(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d, float scale,
-                     void *O, hipStream_t st) {
+template <int MODE, int NQ, bool BIAS>
+hipError_t launch_nq(const void *Q, const void *K, const void *V, const float *key_bias, int H, int BH, int Lq,
+                     int Lk, int d, float scale, void *O, hipStream_t st) {
     const unsigned grid = (unsigned)((long)BH * (Lq / (64 * NQ)));
     const bool pre = is_pow2(scale);
-#define DFSS_LAUNCH(DD, PRE)                                                                             \
-    hipLaunchKernelGGL((k_fused<DD, MODE, NQ, PRE>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)Q,    \
-                       (const __bf16 *)K, (const __bf16 *)V, Lq, Lk, scale, (uint16_t *)O)
+#define DFSS_LAUNCH(DD, PRE)                                                                                  \
+    hipLaunchKernelGGL((k_fused<DD, MODE, NQ, PRE, BIAS>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)Q,   \
+                       (const __bf16 *)K, (const __bf16 *)V, key_bias, H, Lq, Lk, scale, (uint16_t *)O)
     if (d == 64) {
         if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
     } else {
@@ -357,13 +385,17 @@ hipError_t launch_nq(const void *Q, const void *K, const void *V, int BH, int Lq
 }
 
 template <int MODE>
-hipError_t launch(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d, float scale, void *O,
-                  hipStream_t st) {
+hipError_t launch(const void *Q, const void *K, const void *V, const float *key_bias, int H, int BH, int Lq, int Lk,
+                  int d, float scale, void *O, hipStream_t st) {
     // 32 queries per wave when that still leaves at least ~2 workgroups per compute unit
     bool two = Lq % 128 == 0 && (long)BH * (Lq / 128) >= 768;   // at least 3 workgroups per compute unit
     if (const char *f = getenv("DFSS_FUSED_NQ")) two = Lq % 128 == 0 && f[0] == '2';   // for measurements
-    if (two) return launch_nq<MODE, 2>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
-    return launch_nq<MODE, 1>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
+    if (key_bias) {
+        if (two) return launch_nq<MODE, 2, true>(Q, K, V, key_bias, H, BH, Lq, Lk, d, scale, O, st);
+        return launch_nq<MODE, 1, true>(Q, K, V, key_bias, H, BH, Lq, Lk, d, scale, O, st);
+    }
+    if (two) return launch_nq<MODE, 2, false>(Q, K, V, nullptr, 1, BH, Lq, Lk, d, scale, O, st);
+    return launch_nq<MODE, 1, false>(Q, K, V, nullptr, 1, BH, Lq, Lk, d, scale, O, st);
 }
 
 }  // namespace
@@ -371,8 +403,8 @@ hipError_t launch(const void *Q, const void *K, const void *V, int BH, int Lq, i
 hipError_t launch_fused_attention32(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d,
                                     int mode, int nw, float scale, void *O, hipStream_t st);
 
-hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d,
-                                  int mode, float scale, void *O, hipStream_t st) {
+hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, const float *key_bias, int H, int BH,
+                                  int Lq, int Lk, int d, int mode, float scale, void *O, hipStream_t st) {
     // The 16-query kernel is the default.  The 32-query kernel (score MFMA at twice the rate, software
     // pipelined) only pays off once its larger tiles still fill the chip evenly; it is selected with
     // DFSS_FUSED_TILE = 32x2 | 32x4 (for measurements), 16 forces the default.
@@ -382,10 +414,10 @@ hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, i
         else if (f[0] == '3' && f[1] == '2' && f[2] == 'x' && f[3] == '2' && d == 64) tile = 32, nw = 2;
         else if (f[0] == '3' && f[1] == '2' && f[2] == 'x' && f[3] == '4' && Lq % 128 == 0) tile = 32, nw = 4;
     }
-    if (tile == 32) return launch_fused_attention32(Q, K, V, BH, Lq, Lk, d, mode, nw, scale, O, st);
-    if (mode == 0) return launch<MODE_2TO4>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
-    if (mode == 1) return launch<MODE_1TO2>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
-    return launch<MODE_DENSE>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
+    if (tile == 32 && !key_bias) return launch_fused_attention32(Q, K, V, BH, Lq, Lk, d, mode, nw, scale, O, st);
+    if (mode == 0) return launch<MODE_2TO4>(Q, K, V, key_bias, H, BH, Lq, Lk, d, scale, O, st);
+    if (mode == 1) return launch<MODE_1TO2>(Q, K, V, key_bias, H, BH, Lq, Lk, d, scale, O, st);
+    return launch<MODE_DENSE>(Q, K, V, key_bias, H, BH, Lq, Lk, d, scale, O, st);
 }
 
 }  // namespace dfss

@@ -92,8 +92,12 @@ __device__ __forceinline__ unsigned xcd_contiguous(unsigned id, unsigned total) 
 
 // PRESCALE: the scale is a power of two and is applied (exactly) to the Q operand once,
 // instead of to every accumulator.
-template <int D, int MODE, int NQ, bool PRESCALE>
+// BIAS: an additive per-key term (fp32 [B][Lk], shared by the H heads of a batch element; -inf masks a
+// key) joins the scaled score before the selection: as the initial value of the accumulators when the
+// scale is folded into Q, else added (as a separate fp32 addition) after the multiplication by scale.
+template <int D, int MODE, int NQ, bool PRESCALE, bool BIAS>
 __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
+                                                 const float *__restrict__ key_bias, int H,
                                                  int Lq, int Lk, float scale, int ksplit, int blocks_per_wg,
                                                  uint32_t *__restrict__ out, uint32_t *__restrict__ meta) {
     constexpr int CPR = D / 8;           // 16-byte chunks per row
@@ -156,6 +160,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
         }
 
     const int rb0 = q0 >> 4;                 // first 16-row block of this wave
+    const float *bias_b = BIAS ? key_bias + (size_t)(bh / H) * Lk : nullptr;
 
     for (int it = 0; it < blocks_per_wg; ++it) {
         const int jb = jb0 + it;
@@ -176,10 +181,19 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             f32x4 acc[NQ][4];
+            f32x4 kb4[4];    // bias of keys 128 jb + 32 kb + 16 half + 4 t + r
+            if constexpr (BIAS) {
+                const f32x4 *bp = reinterpret_cast<const f32x4 *>(bias_b + KB * jb + 32 * kb + 16 * half);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) kb4[t] = bp[t];
+            }
 #pragma unroll
             for (int qs = 0; qs < NQ; ++qs)
 #pragma unroll
-                for (int t = 0; t < 4; ++t) acc[qs][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+                for (int t = 0; t < 4; ++t) {
+                    if constexpr (BIAS && PRESCALE) acc[qs][t] = kb4[t];
+                    else acc[qs][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
 #pragma unroll
             for (int s = 0; s < STEPS; ++s) {
                 bf16x8 ak[4];
@@ -203,7 +217,13 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
                         f32x4 a = acc[qs][t];
-                        if constexpr (!PRESCALE) a = a * scale;
+                        if constexpr (!PRESCALE) {
+                            a = a * scale;
+                            if constexpr (BIAS) {
+#pragma unroll
+                                for (int r = 0; r < 4; ++r) a[r] = __fadd_rn(a[r], kb4[t][r]);
+                            }
+                        }
                         p[2 * t] = pack_bf16x2(a[0], a[1]);
                         p[2 * t + 1] = pack_bf16x2(a[2], a[3]);
                     }
@@ -215,7 +235,13 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
                         f32x4 a = acc[qs][t];
-                        if constexpr (!PRESCALE) a = a * scale;
+                        if constexpr (!PRESCALE) {
+                            a = a * scale;
+                            if constexpr (BIAS) {
+#pragma unroll
+                                for (int r = 0; r < 4; ++r) a[r] = __fadd_rn(a[r], kb4[t][r]);
+                            }
+                        }
                         float lo, hi;
                         uint32_t code;
                         if constexpr (MODE == MODE_2TO4)
@@ -249,8 +275,9 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
 // ---------------------------------------------------------------------------------------------
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-template <int D, int MODE, bool PRESCALE>
+template <int D, int MODE, bool PRESCALE, bool BIAS>
 __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
+                                                   const float *__restrict__ key_bias, int H,
                                                    int Lq, int Lk, float scale, int ksplit, int blocks_per_wg,
                                                    uint32_t *__restrict__ out, uint32_t *__restrict__ meta) {
     constexpr int CPR = D / 8;           // 16-byte chunks per row
@@ -322,6 +349,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
     // a lane computes the words of chunks (p = 0, h) and (p = 1, h) = slots 2 h and 2 h + 1 of its row
     u32x4 *const meta_row4 = reinterpret_cast<u32x4 *>(
         meta + (((size_t)bh * (Lq / 16) + ((q0 + lj) >> 4)) * (Lk / KB) * 16 + (lj & 15)) * 4);
+    const float *bias_b = BIAS ? key_bias + (size_t)(bh / H) * Lk : nullptr;
 
     for (int it = 0; it < blocks_per_wg; ++it) {
         const int jb = jb0 + it;
@@ -338,11 +366,22 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
 #pragma unroll
         for (int p = 0; p < 2; ++p) {                 // pair of key tiles = 64 keys
             f32x16 acc[2];
+            f32x4 kb4[2][4];   // bias of keys 128 jb + 64 p + 32 h + 16 u + 4 g + x
+            if constexpr (BIAS) {
+                const f32x4 *bp = reinterpret_cast<const f32x4 *>(bias_b + KB * jb + 64 * p + 32 * h);
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) kb4[u][g] = bp[4 * u + g];
+            }
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 const int t = 2 * p + u;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[u][r] = 0.f;
+                for (int r = 0; r < 16; ++r) {
+                    if constexpr (BIAS && PRESCALE) acc[u][r] = kb4[u][r >> 2][r & 3];
+                    else acc[u][r] = 0.f;
+                }
 #pragma unroll
                 for (int s = 0; s < STEPS; ++s) {
                     const bf16x8 ak =
@@ -359,7 +398,13 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
                         float a0 = acc[u][2 * e], a1 = acc[u][2 * e + 1];
-                        if constexpr (!PRESCALE) { a0 *= scale; a1 *= scale; }
+                        if constexpr (!PRESCALE) {
+                            a0 *= scale; a1 *= scale;
+                            if constexpr (BIAS) {
+                                a0 = __fadd_rn(a0, kb4[u][e >> 1][2 * (e & 1)]);
+                                a1 = __fadd_rn(a1, kb4[u][e >> 1][2 * (e & 1) + 1]);
+                            }
+                        }
                         pk[8 * u + e] = pack_bf16x2(a0, a1);
                     }
                 u32x4 *dst = reinterpret_cast<u32x4 *>(out + (row * Lk + kbase) / 2);
@@ -373,7 +418,13 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         float a0 = acc[u][4 * g], a1 = acc[u][4 * g + 1], a2 = acc[u][4 * g + 2], a3 = acc[u][4 * g + 3];
-                        if constexpr (!PRESCALE) { a0 *= scale; a1 *= scale; a2 *= scale; a3 *= scale; }
+                        if constexpr (!PRESCALE) {
+                            a0 *= scale; a1 *= scale; a2 *= scale; a3 *= scale;
+                            if constexpr (BIAS) {
+                                a0 = __fadd_rn(a0, kb4[u][g][0]); a1 = __fadd_rn(a1, kb4[u][g][1]);
+                                a2 = __fadd_rn(a2, kb4[u][g][2]); a3 = __fadd_rn(a3, kb4[u][g][3]);
+                            }
+                        }
                         float lo, hi;
                         uint32_t code;
                         if constexpr (MODE == MODE_2TO4) select_2of4(a0, a1, a2, a3, 16 * u + 4 * g, lo, hi, code);
@@ -415,9 +466,9 @@ inline bool is_pow2(float x) {
     return frexpf(x, &e) == 0.5f;
 }
 
-template <int MODE, int NQ>
-hipError_t launch_nq(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale, void *out,
-                     void *meta, hipStream_t st) {
+template <int MODE, int NQ, bool BIAS>
+hipError_t launch_nq(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk, int d,
+                     float scale, void *out, void *meta, hipStream_t st) {
     const int qtiles = Lq / (64 * NQ);
     const int kblocks = Lk / KB;
     // split the key range until the grid has a few workgroups per compute unit
@@ -428,8 +479,9 @@ hipError_t launch_nq(const void *Q, const void *K, int BH, int Lq, int Lk, int d
     const unsigned grid = (unsigned)((long)BH * qtiles * ksplit);
     const bool pre = is_pow2(scale);
 #define DFSS_LAUNCH(DD, PRE)                                                                              \
-    hipLaunchKernelGGL((k_sddmm<DD, MODE, NQ, PRE>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)Q,     \
-                       (const __bf16 *)K, Lq, Lk, scale, ksplit, per_wg, (uint32_t *)out, (uint32_t *)meta)
+    hipLaunchKernelGGL((k_sddmm<DD, MODE, NQ, PRE, BIAS>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)Q, \
+                       (const __bf16 *)K, key_bias, H, Lq, Lk, scale, ksplit, per_wg, (uint32_t *)out,      \
+                       (uint32_t *)meta)
     if (d == 64) {
         if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
     } else {
@@ -439,9 +491,9 @@ hipError_t launch_nq(const void *Q, const void *K, int BH, int Lq, int Lk, int d
     return hipGetLastError();
 }
 
-template <int MODE>
-hipError_t launch32(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale, void *out,
-                    void *meta, hipStream_t st) {
+template <int MODE, bool BIAS>
+hipError_t launch32(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk, int d,
+                    float scale, void *out, void *meta, hipStream_t st) {
     const int qtiles = Lq / 128;
     const int kblocks = Lk / KB;
     int ksplit = 1;
@@ -451,8 +503,9 @@ hipError_t launch32(const void *Q, const void *K, int BH, int Lq, int Lk, int d,
     const unsigned grid = (unsigned)((long)BH * qtiles * ksplit);
     const bool pre = is_pow2(scale);
 #define DFSS_LAUNCH(DD, PRE)                                                                             \
-    hipLaunchKernelGGL((k_sddmm32<DD, MODE, PRE>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)Q, \
-                       (const __bf16 *)K, Lq, Lk, scale, ksplit, per_wg, (uint32_t *)out, (uint32_t *)meta)
+    hipLaunchKernelGGL((k_sddmm32<DD, MODE, PRE, BIAS>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)Q,  \
+                       (const __bf16 *)K, key_bias, H, Lq, Lk, scale, ksplit, per_wg, (uint32_t *)out,      \
+                       (uint32_t *)meta)
     if (d == 64) {
         if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
     } else {
@@ -462,29 +515,36 @@ hipError_t launch32(const void *Q, const void *K, int BH, int Lq, int Lk, int d,
     return hipGetLastError();
 }
 
-template <int MODE>
-hipError_t launch(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale, void *out,
-                  void *meta, hipStream_t st) {
+template <int MODE, bool BIAS>
+hipError_t launch_b(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk, int d,
+                    float scale, void *out, void *meta, hipStream_t st) {
     // 32 queries per wave (32x32x16 MFMA) when the query count allows it, else 16 (16x16x32 MFMA);
     // DFSS_SDDMM_TILE=16 forces the 16-query kernels (for measurements)
     const char *force = getenv("DFSS_SDDMM_TILE");
     const bool t16 = force && force[0] == '1';
-    if (Lq % 128 == 0 && !t16) return launch32<MODE>(Q, K, BH, Lq, Lk, d, scale, out, meta, st);
-    if (Lq % 128 == 0) return launch_nq<MODE, 2>(Q, K, BH, Lq, Lk, d, scale, out, meta, st);
-    return launch_nq<MODE, 1>(Q, K, BH, Lq, Lk, d, scale, out, meta, st);
+    if (Lq % 128 == 0 && !t16) return launch32<MODE, BIAS>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
+    if (Lq % 128 == 0) return launch_nq<MODE, 2, BIAS>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
+    return launch_nq<MODE, 1, BIAS>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
+}
+
+template <int MODE>
+hipError_t launch(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk, int d,
+                  float scale, void *out, void *meta, hipStream_t st) {
+    if (key_bias) return launch_b<MODE, true>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
+    return launch_b<MODE, false>(Q, K, nullptr, 1, BH, Lq, Lk, d, scale, out, meta, st);
 }
 
 }  // namespace
 
-hipError_t launch_sddmm_prune(const void *Q, const void *K, int BH, int Lq, int Lk, int d, int mode, float scale,
-                              void *vals, void *meta, hipStream_t st) {
-    return mode == 0 ? launch<MODE_2TO4>(Q, K, BH, Lq, Lk, d, scale, vals, meta, st)
-                     : launch<MODE_1TO2>(Q, K, BH, Lq, Lk, d, scale, vals, meta, st);
+hipError_t launch_sddmm_prune(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
+                              int d, int mode, float scale, void *vals, void *meta, hipStream_t st) {
+    return mode == 0 ? launch<MODE_2TO4>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, vals, meta, st)
+                     : launch<MODE_1TO2>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, vals, meta, st);
 }
 
-hipError_t launch_dense_scores(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale, void *S,
-                               hipStream_t st) {
-    return launch<MODE_DENSE>(Q, K, BH, Lq, Lk, d, scale, S, nullptr, st);
+hipError_t launch_dense_scores(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
+                               int d, float scale, void *S, hipStream_t st) {
+    return launch<MODE_DENSE>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, S, nullptr, st);
 }
 
 }  // namespace dfss

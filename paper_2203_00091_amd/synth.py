@@ -86,6 +86,26 @@ def make(workload: Workload | str):
     return gaussian_qkv(w.BH, w.L, w.L, w.d, w.sigma, w.seed)
 
 
+def padding_lengths(B: int, Lk: int, seed: int, min_frac: float = 0.5):
+    """Valid key counts of a padded batch: one integer per batch element, uniform in
+    [min_frac * Lk, Lk] and not aligned to anything (a stand-in for the length mix of a padded
+    question-answering batch).  Element 0 always has full length."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    lo = max(1, int(min_frac * Lk))
+    lengths = torch.randint(lo, Lk + 1, (B,), generator=g)
+    lengths[0] = Lk
+    return lengths
+
+
+def key_padding_bias(lengths: torch.Tensor, Lk: int):
+    """float32 [B, Lk]: 0 for the first lengths[b] keys of batch element b, -inf for the padding."""
+    j = torch.arange(Lk).view(1, Lk)
+    bias = torch.zeros((lengths.numel(), Lk), dtype=torch.float32)
+    bias[j >= lengths.view(-1, 1)] = float("-inf")
+    return bias
+
+
 def to_numpy_f32(t: torch.Tensor):
     """Widen a (bfloat16) tensor to a float32 numpy array holding the same values."""
     return t.to(torch.float32).contiguous().numpy()

@@ -78,6 +78,13 @@ def test_errors_are_reported_before_any_launch():
     ws = ctypes.c_void_p((p.value + 255) // 256 * 256)
     assert lib.dfss_attention(aligned, aligned, aligned, ctypes.byref(ok), 0.125, aligned, ws, 16, None) == E_WS
     assert lib.dense_attention(aligned, aligned, aligned, ctypes.byref(ok), 0.125, aligned, ws, 16, None) == E_WS
+    # the key-bias entry points validate the same way, and reject a misaligned bias pointer
+    assert lib.dfss_sddmm_prune_bias(None, aligned, aligned, ctypes.byref(ok), 0.125, aligned, aligned, None) == E_NULL
+    assert lib.dfss_sddmm_prune_bias(aligned, aligned, odd, ctypes.byref(ok), 0.125, aligned, aligned, None) == E_SHAPE
+    assert lib.dfss_attention_bias(aligned, aligned, aligned, aligned, ctypes.byref(ok), 0.125, aligned, ws, 16, None) == E_WS
+    assert lib.dense_attention_bias(aligned, aligned, aligned, aligned, ctypes.byref(ok), 0.125, aligned, ws, 16, None) == E_WS
+    assert lib.dense_attention_fused_bias(aligned, aligned, aligned, odd, ctypes.byref(ok), 0.125, aligned, None) == E_SHAPE
+    assert lib.dense_attention_fused_bias(aligned, aligned, aligned, aligned, ctypes.byref(ok), -1.0, aligned, None) == E_UNSUP
     assert lib.dfss_status_string(0) == b"ok"
     assert lib.dfss_status_string(E_WS) == b"workspace too small"
 
@@ -88,3 +95,5 @@ def test_binding_refuses_host_tensors():
     q = torch.zeros(1, 128, 64, dtype=torch.bfloat16)
     with pytest.raises(ValueError):
         dfss.dfss_sddmm_prune(q, q, s, 0.125, vals=q, meta=q)
+    with pytest.raises(ValueError):   # key bias of the wrong shape or type
+        dfss.dfss_attention_bias(q, q, q, torch.zeros(2, 128), s, 0.125, O=q, ws=q)
