@@ -22,6 +22,7 @@
 // full-attention baseline (Eq. 1).
 #include <stdlib.h>
 
+#include <type_traits>
 #include "dfss_device.hpp"
 #include "dfss_kernels.hpp"
 
@@ -137,7 +138,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
         for (int i = 0; i < LPT; ++i) async_copy16(vs, 2u * v_off[i], lds_v + 16u * (buf * TILE + i * NT));
     };
 
-    issue_block(0, 0);
+    issue_block(0, 0);   // block 0 is copied before anything else (with a key bias: speculatively)
 
     // Q operand (B side of Q K^T): lane (column li, chunk kb) of step s holds Q[q][32 s + 8 kb .. +7]
     bf16x8 bq[NQ][STEPS];
@@ -176,40 +177,99 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
 
     const int tr_row = li >> 2, tr_sub = (li >> 1) & 1, tr_byte = 8 * (li & 1), tr_xor = tr_row << 1;
 
-    // bias of this lane's 16 keys of a block: keys 64 jb + 16 kb + 4 t + r  ->  four float4
-    const f32x4 *bias4 = nullptr;
+    // Blocks to visit.  With a key bias, blocks whose 64 keys are all masked (-inf) contribute exactly
+    // nothing and are skipped, copies included; blocks whose biases are all zero (with a padding mask:
+    // every block but the one the sequence ends in) take the arithmetic of the call without bias.  Every
+    // wave derives both bitmaps from the bias row of its batch element by itself (Lk <= 8192, so at most
+    // 128 blocks: two 64-bit masks each, in scalar registers; no LDS, no barrier).
+    uint64_t live_lo = ~0ull, live_hi = ~0ull;   // block holds a key that is not masked
+    uint64_t bias_lo = 0ull, bias_hi = 0ull;     // block holds a non-zero bias
+    const f32x4 *bias4 = nullptr;   // bias of this lane's 16 keys of a block: keys 64 jb + 16 kb + 4 t + r
     f32x4 kb4[4];
     if constexpr (BIAS) {
-        bias4 = reinterpret_cast<const f32x4 *>(key_bias + (size_t)(bh / H) * Lk + 16 * kb);
+        const float *brow = key_bias + (size_t)(bh / H) * Lk;
+        live_lo = 0ull, live_hi = 0ull;
+        for (int k0 = 0; k0 < Lk; k0 += 4 * 4 * kWave) {   // 256 keys = 4 blocks per load, 4 loads in flight
+            f32x4 b[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) kb4[t] = bias4[t];
-    }
-
-    for (int jb = 0; jb < nblocks; ++jb) {
-        const int buf = jb & 1;
-        wait_async_copies();  // vmcnt(0): this block's copies have landed
-        __syncthreads();
-        if (jb + 1 < nblocks) issue_block(jb + 1, buf ^ 1);
-
-        // ---- scores: acc[qs][t][r] = s(query q0 + 16 qs + li, key 64 jb + 16 kb + 4 t + r) ----
-        f32x4 acc[NQ][4];
-#pragma unroll
-        for (int qs = 0; qs < NQ; ++qs)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                if constexpr (BIAS && PRESCALE) acc[qs][t] = kb4[t];
-                else acc[qs][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int u = 0; u < 4; ++u) {
+                const int key = k0 + 4 * kWave * u + 4 * l;
+                b[u] = key < Lk ? *reinterpret_cast<const f32x4 *>(brow + key)
+                                : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
             }
 #pragma unroll
-        for (int s = 0; s < STEPS; ++s) {
-            bf16x8 ak[4];
+            for (int u = 0; u < 4; ++u) {
+                // lanes 16 g .. 16 g + 15 looked at block blk0 + g
+                const uint64_t m =
+                    __ballot(b[u][0] > -INFINITY || b[u][1] > -INFINITY || b[u][2] > -INFINITY || b[u][3] > -INFINITY);
+                const uint64_t z =
+                    __ballot(b[u][0] != 0.f || b[u][1] != 0.f || b[u][2] != 0.f || b[u][3] != 0.f);
+                const uint64_t nib = (uint64_t)((m & 0xFFFFull) != 0) | (uint64_t)(((m >> 16) & 0xFFFFull) != 0) << 1 |
+                                     (uint64_t)(((m >> 32) & 0xFFFFull) != 0) << 2 | (uint64_t)((m >> 48) != 0) << 3;
+                const uint64_t znib = (uint64_t)((z & 0xFFFFull) != 0) | (uint64_t)(((z >> 16) & 0xFFFFull) != 0) << 1 |
+                                      (uint64_t)(((z >> 32) & 0xFFFFull) != 0) << 2 | (uint64_t)((z >> 48) != 0) << 3;
+                const int blk0 = (k0 + 4 * kWave * u) / KB;
+                if (blk0 < 64) live_lo |= nib << blk0, bias_lo |= znib << blk0;
+                else if (blk0 < 128) live_hi |= nib << (blk0 - 64), bias_hi |= znib << (blk0 - 64);
+            }
+        }
+        bias4 = reinterpret_cast<const f32x4 *>(brow + 16 * kb);
+    }
+    // smallest live block index >= from, or nblocks
+    auto next_live = [&](int from) -> int {
+        if constexpr (!BIAS) return from;
+        if (from < 64) {
+            const uint64_t m = live_lo >> from;
+            if (m) return from + __builtin_ctzll(m);
+            from = 64;
+        }
+        if (from < 128) {
+            const uint64_t m = live_hi >> (from - 64);
+            if (m) return from + __builtin_ctzll(m);
+        }
+        return nblocks;
+    };
+
+    int jb = next_live(0);
+    // block 0 (copied speculatively at the top) turned out to be fully masked: overwrite the buffer
+    // with the first live block (the two copies of a wave complete in issue order)
+    if (BIAS && jb != 0 && jb < nblocks) issue_block(jb, 0);
+
+    for (int it = 0; jb < nblocks; ++it) {
+        const int buf = it & 1;
+        const int jn = next_live(jb + 1);   // the block after this one
+        wait_async_copies();  // vmcnt(0): this block's copies have landed
+        __syncthreads();
+        if (jn < nblocks) issue_block(jn, buf ^ 1);
+
+        // ---- scores: acc[qs][t][r] = s(query q0 + 16 qs + li, key 64 jb + 16 kb + 4 t + r) ----
+        bool with_bias = false;   // does this block hold a non-zero bias?
+        if constexpr (BIAS) with_bias = ((jb < 64 ? bias_lo >> jb : bias_hi >> (jb - 64)) & 1ull) != 0;
+        f32x4 acc[NQ][4];
+        auto scores = [&](auto init_from_bias) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
-                ak[t] = __builtin_bit_cast(bf16x8, Ks[buf][(16 * t + li) * CPR + ((4 * s + kb) ^ (li & 7))]);
+            for (int s = 0; s < STEPS; ++s) {
+                bf16x8 ak[4];
 #pragma unroll
-            for (int qs = 0; qs < NQ; ++qs)
+                for (int t = 0; t < 4; ++t)
+                    ak[t] = __builtin_bit_cast(bf16x8, Ks[buf][(16 * t + li) * CPR + ((4 * s + kb) ^ (li & 7))]);
 #pragma unroll
-                for (int t = 0; t < 4; ++t) acc[qs][t] = mfma16(ak[t], bq[qs][s], acc[qs][t]);
+                for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        f32x4 c = acc[qs][t];
+                        if (s == 0) c = decltype(init_from_bias)::value ? kb4[t] : f32x4{0.f, 0.f, 0.f, 0.f};
+                        acc[qs][t] = mfma16(ak[t], bq[qs][s], c);
+                    }
+            }
+        };
+        if (BIAS && with_bias) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) kb4[t] = bias4[16 * jb + t];
+            if constexpr (PRESCALE) scores(std::true_type{});    // bias = initial value of the accumulators
+            else scores(std::false_type{});                      // bias added after the scaling, below
+        } else {
+            scores(std::false_type{});
         }
 
         // ---- prune, block maximum ----
@@ -226,8 +286,10 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
                 if constexpr (!PRESCALE) {
                     a = a * scale;
                     if constexpr (BIAS) {   // two roundings (product, then sum), never a fused multiply-add
+                        if (with_bias) {
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) a[r] = __fadd_rn(a[r], kb4[t][r]);
+                            for (int r = 0; r < 4; ++r) a[r] = __fadd_rn(a[r], kb4[t][r]);
+                        }
                     }
                 }
                 if constexpr (SPARSE) {
@@ -244,13 +306,6 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
                     for (int r = 0; r < 4; ++r) kept[qs][4 * t + r] = a[r];
                     m_blk[qs] = fmaxf(m_blk[qs], fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])));
                 }
-            }
-        }
-
-        if constexpr (BIAS) {   // next block's bias, in flight during the rest of this block
-            if (jb + 1 < nblocks) {
-#pragma unroll
-                for (int t = 0; t < 4; ++t) kb4[t] = bias4[16 * (jb + 1) + t];
             }
         }
 
@@ -347,7 +402,9 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
                 }
             }
         }
+        jb = jn;
     }
+    if constexpr (BIAS) wait_async_copies();   // (only matters if no block was live: the speculative copy)
 
     // ---- O[q][16 ds + li] = acc_o / row sum, q = q0 + 16 qs + 4 kb + r ----
 #pragma unroll

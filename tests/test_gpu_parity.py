@@ -461,3 +461,25 @@ def test_attention_finite_key_bias():
         assert np.max(np.abs(_np(O) - ref)) <= 2e-2
         plain = oracle.attention(Qn, Kn, Vn, 2, 4, scale)
         assert np.max(np.abs(plain - ref)) > 0.05       # the bias really changes the result
+
+
+def test_attention_key_bias_skips_masked_blocks_anywhere():
+    """Fully masked 64-key blocks are skipped by the fused kernel; masks at the start, across the
+    64-block boundary of the block bitmap and at the end of the longest key sequence."""
+    B, H, Lq, Lk, d = 2, 1, 64, 8192, 64
+    Q, K, V = synth.gaussian_qkv(B * H, Lq, Lk, d, 1.0, seed=7500)
+    bias = torch.zeros((B, Lk), dtype=torch.float32)
+    bias[0, :70] = float("-inf")            # block 0 and a piece of block 1
+    bias[0, 3800:4500] = float("-inf")      # blocks 60..69 (crosses block 64)
+    bias[0, 6400:] = float("-inf")          # blocks 100..127
+    bias[1, 64:8128] = float("-inf")        # only the first and the last block stay
+    s = Shape(B, H, Lq, Lk, d, 2, 4)
+    Qd, Kd, Vd, bd = _dev(Q), _dev(K), _dev(V), _dev(bias)
+    O = dfss.dfss_attention_bias(Qd, Kd, Vd, bd, s, 0.125)
+    Odf = dfss.dense_attention_fused_bias(Qd, Kd, Vd, bd, s, 0.125)
+    torch.cuda.synchronize()
+    Qn, Kn, Vn = (synth.to_numpy_f32(t) for t in (Q, K, V))
+    ref = oracle.attention(Qn, Kn, Vn, 2, 4, 0.125, key_bias=bias.numpy(), heads_per_batch=H)
+    ref_dense = oracle.attention(Qn, Kn, Vn, 1, 1, 0.125, key_bias=bias.numpy(), heads_per_batch=H)
+    assert np.max(np.abs(_np(O) - ref)) <= 2e-2
+    assert np.max(np.abs(_np(Odf) - ref_dense)) <= 2e-2
