@@ -407,16 +407,32 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
     if constexpr (BIAS) wait_async_copies();   // (only matters if no block was live: the speculative copy)
 
     // ---- O[q][16 ds + li] = acc_o / row sum, q = q0 + 16 qs + 4 kb + r ----
+    // A lane holds single elements of 4 rows; they pass through LDS (the K buffers, free now) so that
+    // every lane stores 16 contiguous bytes and a row leaves as one 2 D-byte run.
+    __syncthreads();   // every wave is done reading K
+    constexpr int ROWB = 2 * D + 16;   // padded row: the four lane groups of a column fall into different banks
+    char *const stage = reinterpret_cast<char *>(&Ks[0][0]) + w * (16 * ROWB);
+    static_assert(4 * 16 * ROWB <= 2 * TILE * 16, "the staging rows fit into the K buffers");
+    constexpr int RPP = kWave / CPR;   // rows per read-back pass (CPR lanes x 16 bytes cover a row)
 #pragma unroll
-    for (int qs = 0; qs < NQ; ++qs)
+    for (int qs = 0; qs < NQ; ++qs) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const float inv = __builtin_amdgcn_rcpf(acc_l[qs][r]);   // 1 ulp; the row sum is >= ~1: the reference never exceeds the row maximum
-            const size_t q = (size_t)bh * Lq + q0 + 16 * qs + 4 * kb + r;
 #pragma unroll
             for (int ds = 0; ds < DS; ++ds)
-                O[q * D + 16 * ds + li] = (uint16_t)(pack_bf16x2(acc_o[qs][ds][r] * inv, 0.f) & 0xFFFFu);
+                *reinterpret_cast<uint16_t *>(stage + (4 * kb + r) * ROWB + (16 * ds + li) * 2) =
+                    (uint16_t)(pack_bf16x2(acc_o[qs][ds][r] * inv, 0.f) & 0xFFFFu);
         }
+        wave_lds_sync();
+#pragma unroll
+        for (int pass = 0; pass < 16 / RPP; ++pass) {
+            const int row = pass * RPP + l / CPR, c = l % CPR;
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(stage + row * ROWB + c * 16);
+            *reinterpret_cast<u32x4 *>(O + ((size_t)bh * Lq + q0 + 16 * qs + row) * D + c * 8) = v;
+        }
+        wave_lds_sync();   // the staging rows are free for the next tile
+    }
 }
 
 inline bool is_pow2(float x) {
