@@ -65,6 +65,12 @@ def _load():
         L.oracle_attention_bias_batched.argtypes = [_f32p, _f32p, _f32p, _f32p, c_int, c_int, c_int, c_int,
                                                     c_int, c_int, c_int, c_float, c_int, _f32p]
         L.oracle_attention_bias_batched.restype = c_int
+        L.oracle_attention_masked_batched.argtypes = [_f32p, _f32p, _f32p, ctypes.c_void_p, c_int, ctypes.c_void_p,
+                                                      c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_float,
+                                                      c_int, _f32p]
+        L.oracle_attention_masked_batched.restype = c_int
+        L.oracle_apply_block_mask.argtypes = [_f32p, c_int, c_int, _u8p, c_int]
+        L.oracle_apply_block_mask.restype = c_int
         L.oracle_add_key_bias.argtypes = [_f32p, c_int, c_int, _f32p]
         L.oracle_add_key_bias.restype = None
         L.oracle_num_threads.argtypes = []
@@ -97,6 +103,18 @@ def add_key_bias(S, bias):
     Lq, Lk = S.shape
     assert bias.shape == (Lk,)
     _load().oracle_add_key_bias(S, Lq, Lk, bias)
+    return S
+
+
+def apply_block_mask(S, block_mask, block_size):
+    """Scores of blocks the block pattern prunes (block_mask == 0) become -inf (blocked-ELL, App. A.1.2)."""
+    S = _f32(S).copy()
+    bm = np.ascontiguousarray(block_mask, dtype=np.uint8)
+    Lq, Lk = S.shape
+    assert bm.shape == (Lq // block_size, Lk // block_size)
+    rc = _load().oracle_apply_block_mask(S, Lq, Lk, bm, int(block_size))
+    if rc != 0:
+        raise ValueError(f"oracle_apply_block_mask failed rc={rc}")
     return S
 
 
@@ -160,11 +178,14 @@ def round_bf16(x):
     return y
 
 
-def attention(Q, K, V, N, M, scale, store_bf16=False, key_bias=None, heads_per_batch=1):
+def attention(Q, K, V, N, M, scale, store_bf16=False, key_bias=None, heads_per_batch=1,
+              block_mask=None, block_size=64):
     """Whole forward for [BH, L, d] (or [L, d]) inputs; heads run on host threads.
 
     key_bias: optional float32 [BH // heads_per_batch, Lk] (or [Lk] for a single head), added to
     the scaled scores before the N:M selection; -inf masks a key.
+    block_mask: optional uint8 [Lq // block_size, Lk // block_size] shared by all heads; blocks with a
+    zero entry are not part of the attention (their scores count as -inf).
     """
     Q, K, V = _f32(Q), _f32(K), _f32(V)
     squeeze = Q.ndim == 2
@@ -173,16 +194,23 @@ def attention(Q, K, V, N, M, scale, store_bf16=False, key_bias=None, heads_per_b
     BH, Lq, d = Q.shape
     Lk = K.shape[1]
     O = np.empty((BH, Lq, d), np.float32)
-    if key_bias is None:
+    if key_bias is None and block_mask is None:
         rc = _load().oracle_attention_batched(Q, K, V, BH, Lq, Lk, d, N, M, float(scale),
                                               int(bool(store_bf16)), O)
     else:
-        kb = _f32(key_bias)
-        if kb.ndim == 1:
-            kb = kb[None]
-        assert BH % heads_per_batch == 0 and kb.shape == (BH // heads_per_batch, Lk), kb.shape
-        rc = _load().oracle_attention_bias_batched(Q, K, V, kb, int(heads_per_batch), BH, Lq, Lk, d, N, M,
-                                                   float(scale), int(bool(store_bf16)), O)
+        kb = bm = None
+        if key_bias is not None:
+            kb = _f32(key_bias)
+            if kb.ndim == 1:
+                kb = kb[None]
+            assert BH % heads_per_batch == 0 and kb.shape == (BH // heads_per_batch, Lk), kb.shape
+        if block_mask is not None:
+            bm = np.ascontiguousarray(block_mask, dtype=np.uint8)
+            assert bm.shape == (Lq // block_size, Lk // block_size), bm.shape
+        rc = _load().oracle_attention_masked_batched(
+            Q, K, V, kb.ctypes.data if kb is not None else None, int(heads_per_batch),
+            bm.ctypes.data if bm is not None else None, int(block_size),
+            BH, Lq, Lk, d, N, M, float(scale), int(bool(store_bf16)), O)
     if rc != 0:
         raise ValueError(f"oracle_attention failed rc={rc}")
     return O[0] if squeeze else O

@@ -28,6 +28,8 @@
  *     accumulates in float regardless of input type, App. A.1.2);
  *   - masks are not in the paper: an optional per-key bias is added to the
  *     scaled score in fp32 before the comparison (-inf masks a key);
+ *   - a block of the score matrix pruned by the block pattern (blocked-ELL,
+ *     App. A.1.2) acts as if all its scores were -inf;
  *   - position code = lower kept position in bits [1:0], higher in bits [3:2];
  *     this is the unique 2-bit-per-position rule that reproduces the two
  *     codes the paper prints (0x4 for "first float", 0xe for "second float").
@@ -78,6 +80,24 @@ void oracle_add_key_bias(float *S, int Lq, int Lk, const float *bias)
     for (int i = 0; i < Lq; ++i)
         for (int j = 0; j < Lk; ++j)
             S[(size_t)i * Lk + j] = S[(size_t)i * Lk + j] + bias[j];
+}
+
+/* ------------------------------------------------------------------ */
+/* Stage 1a'': block mask (hybrid blocked-ELL x N:M sparsity,          */
+/* App. A.1.2 "Blocked-ELL Sparsity": blocks of the score matrix that  */
+/* the block pattern prunes are simply not computed).  As a function:  */
+/* every score of a pruned block is -inf, i.e. it loses every          */
+/* comparison and gets softmax weight 0.  block_mask is                */
+/* [Lq/bs][Lk/bs], non-zero = the block is kept.                       */
+/* ------------------------------------------------------------------ */
+int oracle_apply_block_mask(float *S, int Lq, int Lk, const uint8_t *block_mask, int bs)
+{
+    if (bs <= 0 || Lq % bs != 0 || Lk % bs != 0) return -1;
+    const int nbk = Lk / bs;
+    for (int i = 0; i < Lq; ++i)
+        for (int j = 0; j < Lk; ++j)
+            if (!block_mask[(size_t)(i / bs) * nbk + j / bs]) S[(size_t)i * Lk + j] = -INFINITY;
+    return 0;
 }
 
 /* ------------------------------------------------------------------ */
@@ -249,10 +269,11 @@ void oracle_round_bf16_array(const float *x, size_t n, float *y)
 /* Optional outputs (may be NULL): mask, vals (after optional rounding,*/
 /* before softmax), kidx, P.                                           */
 /* ------------------------------------------------------------------ */
-int oracle_attention_bias(const float *Q, const float *K, const float *V, const float *key_bias,
-                          int Lq, int Lk, int d, int N, int M, float scale,
-                          int store_bf16, float *O,
-                          uint8_t *mask_out, float *vals_out, int32_t *kidx_out, float *P_out)
+int oracle_attention_masked(const float *Q, const float *K, const float *V, const float *key_bias,
+                            const uint8_t *block_mask, int block_size,
+                            int Lq, int Lk, int d, int N, int M, float scale,
+                            int store_bf16, float *O,
+                            uint8_t *mask_out, float *vals_out, int32_t *kidx_out, float *P_out)
 {
     if (M <= 0 || N <= 0 || N > M || Lk % M != 0) return -1;
     const int Lc = Lk / M * N;
@@ -265,7 +286,8 @@ int oracle_attention_bias(const float *Q, const float *K, const float *V, const 
     if (S && mask && vals && kidx && P) {
         oracle_scores(Q, K, Lq, Lk, d, scale, S);
         if (key_bias) oracle_add_key_bias(S, Lq, Lk, key_bias);   /* NULL = no mask (the paper's case) */
-        rc = oracle_prune(S, Lq, Lk, N, M, mask, vals, kidx);
+        rc = block_mask ? oracle_apply_block_mask(S, Lq, Lk, block_mask, block_size) : 0;
+        if (rc == 0) rc = oracle_prune(S, Lq, Lk, N, M, mask, vals, kidx);
         if (rc == 0) {
             if (store_bf16) oracle_round_bf16_array(vals, (size_t)Lq * Lc, vals);
             oracle_softmax_kept(vals, Lq, Lc, P);
@@ -281,22 +303,32 @@ int oracle_attention_bias(const float *Q, const float *K, const float *V, const 
     return rc;
 }
 
+int oracle_attention_bias(const float *Q, const float *K, const float *V, const float *key_bias,
+                          int Lq, int Lk, int d, int N, int M, float scale,
+                          int store_bf16, float *O,
+                          uint8_t *mask_out, float *vals_out, int32_t *kidx_out, float *P_out)
+{
+    return oracle_attention_masked(Q, K, V, key_bias, NULL, 0, Lq, Lk, d, N, M, scale, store_bf16, O,
+                                   mask_out, vals_out, kidx_out, P_out);
+}
+
 int oracle_attention(const float *Q, const float *K, const float *V,
                      int Lq, int Lk, int d, int N, int M, float scale,
                      int store_bf16, float *O,
                      uint8_t *mask_out, float *vals_out, int32_t *kidx_out, float *P_out)
 {
-    return oracle_attention_bias(Q, K, V, NULL, Lq, Lk, d, N, M, scale, store_bf16, O,
-                                 mask_out, vals_out, kidx_out, P_out);
+    return oracle_attention_masked(Q, K, V, NULL, NULL, 0, Lq, Lk, d, N, M, scale, store_bf16, O,
+                                   mask_out, vals_out, kidx_out, P_out);
 }
 
 /* Heads are independent (App. A.1.2, batched kernel): loop them, in parallel
  * over host threads when built with OpenMP.  Q,K,V,O are [BH][L][d]. */
 /* key_bias (may be NULL) is [BH / heads_per_batch][Lk]: the heads of one batch element share
  * one bias vector (a padding mask belongs to the sequence, not to the head). */
-int oracle_attention_bias_batched(const float *Q, const float *K, const float *V, const float *key_bias,
-                                  int heads_per_batch, int BH, int Lq, int Lk, int d, int N, int M,
-                                  float scale, int store_bf16, float *O)
+int oracle_attention_masked_batched(const float *Q, const float *K, const float *V, const float *key_bias,
+                                    int heads_per_batch, const uint8_t *block_mask, int block_size,
+                                    int BH, int Lq, int Lk, int d, int N, int M,
+                                    float scale, int store_bf16, float *O)
 {
     int bad = 0;
 #ifdef _OPENMP
@@ -304,10 +336,11 @@ int oracle_attention_bias_batched(const float *Q, const float *K, const float *V
 #endif
     for (int h = 0; h < BH; ++h) {
         const float *bias = key_bias ? key_bias + (size_t)(h / heads_per_batch) * Lk : NULL;
-        int rc = oracle_attention_bias(Q + (size_t)h * Lq * d, K + (size_t)h * Lk * d,
-                                       V + (size_t)h * Lk * d, bias, Lq, Lk, d, N, M, scale,
-                                       store_bf16, O + (size_t)h * Lq * d,
-                                       NULL, NULL, NULL, NULL);
+        int rc = oracle_attention_masked(Q + (size_t)h * Lq * d, K + (size_t)h * Lk * d,
+                                         V + (size_t)h * Lk * d, bias, block_mask, block_size,
+                                         Lq, Lk, d, N, M, scale,
+                                         store_bf16, O + (size_t)h * Lq * d,
+                                         NULL, NULL, NULL, NULL);
         if (rc != 0) {
 #ifdef _OPENMP
 #pragma omp atomic write
@@ -318,11 +351,19 @@ int oracle_attention_bias_batched(const float *Q, const float *K, const float *V
     return bad;
 }
 
+int oracle_attention_bias_batched(const float *Q, const float *K, const float *V, const float *key_bias,
+                                  int heads_per_batch, int BH, int Lq, int Lk, int d, int N, int M,
+                                  float scale, int store_bf16, float *O)
+{
+    return oracle_attention_masked_batched(Q, K, V, key_bias, heads_per_batch, NULL, 0, BH, Lq, Lk, d, N, M,
+                                           scale, store_bf16, O);
+}
+
 int oracle_attention_batched(const float *Q, const float *K, const float *V,
                              int BH, int Lq, int Lk, int d, int N, int M,
                              float scale, int store_bf16, float *O)
 {
-    return oracle_attention_bias_batched(Q, K, V, NULL, 1, BH, Lq, Lk, d, N, M, scale, store_bf16, O);
+    return oracle_attention_masked_batched(Q, K, V, NULL, 1, NULL, 0, BH, Lq, Lk, d, N, M, scale, store_bf16, O);
 }
 
 int oracle_num_threads(void)
