@@ -133,6 +133,23 @@ dfss_status dense_attention_bias(const void *Q, const void *K, const void *V, co
 dfss_status dense_attention_fused_bias(const void *Q, const void *K, const void *V, const void *key_bias,
                                        const dfss_shape *s, float scale, void *O, void *stream);
 
+/* ---- hybrid block sparsity x N:M (App. A.1.2, "Blocked-ELL Sparsity") ---------------- */
+/* block_mask: device, uint8 [Lq/64, Lk/64] row-major, shared by all B*H heads.  A 64 x 64 block
+ * of the score matrix whose entry is zero is not part of the attention: it is skipped (neither
+ * its K/V blocks are read nor its scores formed), which as a function means that all its scores
+ * are -inf.  Within the kept blocks the N:M pruning, softmax and product with V are those of
+ * dfss_attention.  The block size equals the workgroup tile (64 queries x 64 keys), as the paper
+ * prescribes.  key_bias (may be NULL) as in dfss_attention_bias.  Precondition: every row of
+ * blocks keeps at least one block that holds an unmasked key.  Runs as one fused kernel; no
+ * workspace.  dense_attention_fused_blocked is the same block pattern without N:M pruning
+ * (block-sparse full attention), the baseline for this mode. */
+dfss_status dfss_attention_blocked(const void *Q, const void *K, const void *V, const void *key_bias,
+                                   const void *block_mask, const dfss_shape *s, float scale, void *O,
+                                   void *stream);
+dfss_status dense_attention_fused_blocked(const void *Q, const void *K, const void *V, const void *key_bias,
+                                          const void *block_mask, const dfss_shape *s, float scale, void *O,
+                                          void *stream);
+
 /* ---- metadata order ---------------------------------------------------------------- */
 /* Canonical order: uint16 [B*H, Lq, Lk/16], word w of a row = codes of key runs
  * 4w..4w+3, code = p_lo | p_hi << 2 with p the kept key index mod 4 (the 2-bit

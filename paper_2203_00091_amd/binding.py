@@ -22,6 +22,7 @@ EXPORTS = (
     "dfss_sddmm_prune", "dfss_sparse_softmax", "dfss_spmm", "dfss_attention", "dense_attention",
     "dense_attention_fused", "dfss_meta_to_canonical", "dfss_meta_from_canonical", "dfss_status_string",
     "dfss_sddmm_prune_bias", "dfss_attention_bias", "dense_attention_bias", "dense_attention_fused_bias",
+    "dfss_attention_blocked", "dense_attention_fused_blocked",
 )
 
 
@@ -89,12 +90,14 @@ def load_library():
         L.dfss_attention_bias.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
         L.dense_attention_bias.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
         L.dense_attention_fused_bias.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
+        L.dfss_attention_blocked.argtypes = [vp, vp, vp, vp, vp, sp, f32, vp, vp]
+        L.dense_attention_fused_blocked.argtypes = [vp, vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_meta_to_canonical.argtypes = [vp, sp, vp, vp]
         L.dfss_meta_from_canonical.argtypes = [vp, sp, vp, vp]
         for name in ("dfss_sddmm_prune", "dfss_sparse_softmax", "dfss_spmm", "dfss_attention",
                      "dense_attention", "dense_attention_fused", "dfss_meta_to_canonical", "dfss_meta_from_canonical",
                      "dfss_sddmm_prune_bias", "dfss_attention_bias", "dense_attention_bias",
-                     "dense_attention_fused_bias"):
+                     "dense_attention_fused_bias", "dfss_attention_blocked", "dense_attention_fused_blocked"):
             getattr(L, name).restype = ctypes.c_int
         L.dfss_status_string.argtypes = [ctypes.c_int]
         L.dfss_status_string.restype = ctypes.c_char_p
@@ -251,6 +254,34 @@ def dense_attention_fused_bias(Q, K, V, key_bias, s: Shape, scale: float, O=None
     st = load_library().dense_attention_fused_bias(_ptr(Q), _ptr(K), _ptr(V), _bias_ptr(key_bias, s),
                                                    ctypes.byref(s.c()), scale, _ptr(O), _stream())
     _check("dense_attention_fused_bias", st)
+    return O
+
+
+def _block_mask_ptr(block_mask, s: Shape):
+    if block_mask.dtype != torch.uint8 or tuple(block_mask.shape) != (s.Lq // 64, s.Lk // 64):
+        raise ValueError(f"block_mask must be uint8 [Lq/64, Lk/64] = [{s.Lq // 64}, {s.Lk // 64}]")
+    return _ptr(block_mask)
+
+
+def dfss_attention_blocked(Q, K, V, key_bias, block_mask, s: Shape, scale: float, O=None):
+    """DFSS forward restricted to the 64 x 64 score blocks with a non-zero entry in block_mask."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=Q.device)
+    st = load_library().dfss_attention_blocked(_ptr(Q), _ptr(K), _ptr(V), _bias_ptr(key_bias, s),
+                                               _block_mask_ptr(block_mask, s), ctypes.byref(s.c()), scale, _ptr(O),
+                                               _stream())
+    _check("dfss_attention_blocked", st)
+    return O
+
+
+def dense_attention_fused_blocked(Q, K, V, key_bias, block_mask, s: Shape, scale: float, O=None):
+    """Block-sparse full attention (same block pattern, no N:M pruning)."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=Q.device)
+    st = load_library().dense_attention_fused_blocked(_ptr(Q), _ptr(K), _ptr(V), _bias_ptr(key_bias, s),
+                                                      _block_mask_ptr(block_mask, s), ctypes.byref(s.c()), scale,
+                                                      _ptr(O), _stream())
+    _check("dense_attention_fused_blocked", st)
     return O
 
 

@@ -127,7 +127,7 @@ dfss_status dfss_attention_bias(const void *Q, const void *K, const void *V, con
     hipStream_t st = (hipStream_t)stream;
     const float *bias = (const float *)key_bias;
     if (!staged_path_requested())
-        return hip_status(dfss::launch_fused_attention(Q, K, V, bias, D.H, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, O, st));
+        return hip_status(dfss::launch_fused_attention(Q, K, V, bias, D.H, nullptr, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, O, st));
     char *vals = static_cast<char *>(ws);
     char *meta = vals + align_up(dfss_vals_bytes(s));
     hipError_t e = dfss::launch_sddmm_prune(Q, K, bias, D.H, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, vals, meta, st);
@@ -149,8 +149,8 @@ dfss_status dense_attention_fused_bias(const void *Q, const void *K, const void 
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias))
         return DFSS_ERR_SHAPE;
-    return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, D.BH, D.Lq, D.Lk, D.d, 2,
-                                                   scale, O, (hipStream_t)stream));
+    return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, nullptr, D.BH, D.Lq, D.Lk,
+                                                   D.d, 2, scale, O, (hipStream_t)stream));
 }
 
 dfss_status dense_attention_fused(const void *Q, const void *K, const void *V, const dfss_shape *s, float scale,
@@ -178,6 +178,32 @@ dfss_status dense_attention_bias(const void *Q, const void *K, const void *V, co
 dfss_status dense_attention(const void *Q, const void *K, const void *V, const dfss_shape *s, float scale, void *O,
                             void *ws, size_t ws_bytes, void *stream) {
     return dense_attention_bias(Q, K, V, nullptr, s, scale, O, ws, ws_bytes, stream);
+}
+
+// mode: the N:M of the shape, or dense (N, M ignored)
+static dfss_status attention_blocked(const void *Q, const void *K, const void *V, const void *key_bias,
+                                     const void *block_mask, const dfss_shape *s, bool dense, float scale, void *O,
+                                     void *stream) {
+    Dims D;
+    if (!Q || !K || !V || !O || !block_mask) return DFSS_ERR_NULL;
+    if (dfss_status st = check_shape(s, !dense, &D)) return st;
+    if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias))
+        return DFSS_ERR_SHAPE;
+    return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, (const uint8_t *)block_mask,
+                                                   D.BH, D.Lq, D.Lk, D.d, dense ? 2 : D.mode, scale, O,
+                                                   (hipStream_t)stream));
+}
+
+dfss_status dfss_attention_blocked(const void *Q, const void *K, const void *V, const void *key_bias,
+                                   const void *block_mask, const dfss_shape *s, float scale, void *O, void *stream) {
+    return attention_blocked(Q, K, V, key_bias, block_mask, s, false, scale, O, stream);
+}
+
+dfss_status dense_attention_fused_blocked(const void *Q, const void *K, const void *V, const void *key_bias,
+                                          const void *block_mask, const dfss_shape *s, float scale, void *O,
+                                          void *stream) {
+    return attention_blocked(Q, K, V, key_bias, block_mask, s, true, scale, O, stream);
 }
 
 dfss_status dfss_meta_to_canonical(const void *meta, const dfss_shape *s, void *canon, void *stream) {

@@ -23,8 +23,10 @@ hipError_t launch_spmm(const void *vals, const void *meta, const void *V, int BH
 hipError_t launch_dense_av(const void *P, const void *V, int BH, int Lq, int Lk, int d, void *O,
                            hipStream_t st);
 // Whole forward pass in one kernel.  mode: 0 = 2:4, 1 = 1:2, 2 = dense (full attention, Eq. 1).
-hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, const float *key_bias, int H, int BH,
-                                  int Lq, int Lk, int d, int mode, float scale, void *O, hipStream_t st);
+// block_mask: uint8 [Lq/64][Lk/64] shared by all heads (zero = block not part of the attention), or nullptr.
+hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, const float *key_bias, int H,
+                                  const uint8_t *block_mask, int BH, int Lq, int Lk, int d, int mode, float scale,
+                                  void *O, hipStream_t st);
 // Metadata word order: library <-> canonical.
 hipError_t launch_meta_reorder(const void *src, void *dst, int BH, int Lq, int W, bool to_canonical,
                                hipStream_t st);

@@ -86,13 +86,18 @@ __device__ __forceinline__ unsigned xcd_contiguous(unsigned id, unsigned total) 
     return id < per * 8 ? (id % 8) * per + id / 8 : id;
 }
 
-// BIAS: an additive per-key term (fp32, [B][Lk], shared by the H heads of a batch element; -inf masks a
-// key) joins the scaled score before the selection.  With the scale folded into Q it is simply the
-// initial value of the accumulators; otherwise it is added after the multiplication by scale.
-template <int D, int MODE, int NQ, bool PRESCALE, bool BIAS>
+// MASKED: the call carries a key bias and/or a block mask (either pointer may be null).
+//   key_bias   additive per-key term (fp32, [B][Lk], shared by the H heads of a batch element; -inf masks
+//              a key), joined to the scaled score before the selection: as the initial value of the
+//              accumulators when the scale is folded into Q, else added after the multiplication by scale.
+//   block_mask uint8 [Lq/64][Lk/64], shared by all heads: 64 x 64 blocks of the score matrix with a zero
+//              entry are not part of the attention (hybrid blocked-ELL x N:M sparsity, App. A.1.2: the
+//              block equals the workgroup tile and pruned blocks are skipped).  Needs 64-query workgroups.
+template <int D, int MODE, int NQ, bool PRESCALE, bool MASKED>
 __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
                                                  const __bf16 *__restrict__ V, const float *__restrict__ key_bias,
-                                                 int H, int Lq, int Lk, float scale, uint16_t *__restrict__ O) {
+                                                 int H, const uint8_t *__restrict__ block_mask, int Lq, int Lk,
+                                                 float scale, uint16_t *__restrict__ O) {
     constexpr int CPR = D / 8;          // 16-byte chunks per row
     constexpr int TILE = KB * CPR;      // chunks per K (or V) block
     constexpr int LPT = TILE / NT;      // direct-to-LDS loads per thread per block and operand
@@ -177,47 +182,55 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
 
     const int tr_row = li >> 2, tr_sub = (li >> 1) & 1, tr_byte = 8 * (li & 1), tr_xor = tr_row << 1;
 
-    // Blocks to visit.  With a key bias, blocks whose 64 keys are all masked (-inf) contribute exactly
-    // nothing and are skipped, copies included; blocks whose biases are all zero (with a padding mask:
-    // every block but the one the sequence ends in) take the arithmetic of the call without bias.  Every
-    // wave derives both bitmaps from the bias row of its batch element by itself (Lk <= 8192, so at most
-    // 128 blocks: two 64-bit masks each, in scalar registers; no LDS, no barrier).
-    uint64_t live_lo = ~0ull, live_hi = ~0ull;   // block holds a key that is not masked
+    // Blocks to visit.  Blocks that the block mask prunes, and blocks whose 64 keys are all masked by the
+    // key bias (-inf), contribute exactly nothing and are skipped, copies included; blocks whose biases
+    // are all zero (with a padding mask: every block but the one the sequence ends in) take the
+    // arithmetic of the call without bias.  Every wave derives the bitmaps by itself (Lk <= 8192, so at
+    // most 128 blocks: two 64-bit masks each, in scalar registers; no LDS, no barrier).
+    uint64_t live_lo = ~0ull, live_hi = ~0ull;   // block is visited
     uint64_t bias_lo = 0ull, bias_hi = 0ull;     // block holds a non-zero bias
     const f32x4 *bias4 = nullptr;   // bias of this lane's 16 keys of a block: keys 64 jb + 16 kb + 4 t + r
     f32x4 kb4[4];
-    if constexpr (BIAS) {
-        const float *brow = key_bias + (size_t)(bh / H) * Lk;
-        live_lo = 0ull, live_hi = 0ull;
-        for (int k0 = 0; k0 < Lk; k0 += 4 * 4 * kWave) {   // 256 keys = 4 blocks per load, 4 loads in flight
-            f32x4 b[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int key = k0 + 4 * kWave * u + 4 * l;
-                b[u] = key < Lk ? *reinterpret_cast<const f32x4 *>(brow + key)
-                                : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                // lanes 16 g .. 16 g + 15 looked at block blk0 + g
-                const uint64_t m =
-                    __ballot(b[u][0] > -INFINITY || b[u][1] > -INFINITY || b[u][2] > -INFINITY || b[u][3] > -INFINITY);
-                const uint64_t z =
-                    __ballot(b[u][0] != 0.f || b[u][1] != 0.f || b[u][2] != 0.f || b[u][3] != 0.f);
-                const uint64_t nib = (uint64_t)((m & 0xFFFFull) != 0) | (uint64_t)(((m >> 16) & 0xFFFFull) != 0) << 1 |
-                                     (uint64_t)(((m >> 32) & 0xFFFFull) != 0) << 2 | (uint64_t)((m >> 48) != 0) << 3;
-                const uint64_t znib = (uint64_t)((z & 0xFFFFull) != 0) | (uint64_t)(((z >> 16) & 0xFFFFull) != 0) << 1 |
-                                      (uint64_t)(((z >> 32) & 0xFFFFull) != 0) << 2 | (uint64_t)((z >> 48) != 0) << 3;
-                const int blk0 = (k0 + 4 * kWave * u) / KB;
-                if (blk0 < 64) live_lo |= nib << blk0, bias_lo |= znib << blk0;
-                else if (blk0 < 128) live_hi |= nib << (blk0 - 64), bias_hi |= znib << (blk0 - 64);
-            }
+    if constexpr (MASKED) {
+        if (block_mask) {   // row of the mask that belongs to this workgroup's 64 queries
+            const uint8_t *row = block_mask + (size_t)(qt * TQ / 64) * nblocks;
+            live_lo = __ballot(l < nblocks && row[l < nblocks ? l : 0] != 0);
+            live_hi = __ballot(64 + l < nblocks && row[64 + l < nblocks ? 64 + l : 0] != 0);
         }
-        bias4 = reinterpret_cast<const f32x4 *>(brow + 16 * kb);
+        if (key_bias) {
+            const float *brow = key_bias + (size_t)(bh / H) * Lk;
+            uint64_t real_lo = 0ull, real_hi = 0ull;
+            for (int k0 = 0; k0 < Lk; k0 += 4 * 4 * kWave) {   // 256 keys = 4 blocks per load, 4 loads in flight
+                f32x4 b[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int key = k0 + 4 * kWave * u + 4 * l;
+                    b[u] = key < Lk ? *reinterpret_cast<const f32x4 *>(brow + key)
+                                    : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    // lanes 16 g .. 16 g + 15 looked at block blk0 + g
+                    const uint64_t m = __ballot(b[u][0] > -INFINITY || b[u][1] > -INFINITY || b[u][2] > -INFINITY ||
+                                                b[u][3] > -INFINITY);
+                    const uint64_t z =
+                        __ballot(b[u][0] != 0.f || b[u][1] != 0.f || b[u][2] != 0.f || b[u][3] != 0.f);
+                    const uint64_t nib = (uint64_t)((m & 0xFFFFull) != 0) | (uint64_t)(((m >> 16) & 0xFFFFull) != 0) << 1 |
+                                         (uint64_t)(((m >> 32) & 0xFFFFull) != 0) << 2 | (uint64_t)((m >> 48) != 0) << 3;
+                    const uint64_t znib = (uint64_t)((z & 0xFFFFull) != 0) | (uint64_t)(((z >> 16) & 0xFFFFull) != 0) << 1 |
+                                          (uint64_t)(((z >> 32) & 0xFFFFull) != 0) << 2 | (uint64_t)((z >> 48) != 0) << 3;
+                    const int blk0 = (k0 + 4 * kWave * u) / KB;
+                    if (blk0 < 64) real_lo |= nib << blk0, bias_lo |= znib << blk0;
+                    else if (blk0 < 128) real_hi |= nib << (blk0 - 64), bias_hi |= znib << (blk0 - 64);
+                }
+            }
+            live_lo &= real_lo, live_hi &= real_hi;
+            bias4 = reinterpret_cast<const f32x4 *>(brow + 16 * kb);
+        }
     }
     // smallest live block index >= from, or nblocks
     auto next_live = [&](int from) -> int {
-        if constexpr (!BIAS) return from;
+        if constexpr (!MASKED) return from;
         if (from < 64) {
             const uint64_t m = live_lo >> from;
             if (m) return from + __builtin_ctzll(m);
@@ -233,7 +246,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
     int jb = next_live(0);
     // block 0 (copied speculatively at the top) turned out to be fully masked: overwrite the buffer
     // with the first live block (the two copies of a wave complete in issue order)
-    if (BIAS && jb != 0 && jb < nblocks) issue_block(jb, 0);
+    if (MASKED && jb != 0 && jb < nblocks) issue_block(jb, 0);
 
     for (int it = 0; jb < nblocks; ++it) {
         const int buf = it & 1;
@@ -244,7 +257,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
 
         // ---- scores: acc[qs][t][r] = s(query q0 + 16 qs + li, key 64 jb + 16 kb + 4 t + r) ----
         bool with_bias = false;   // does this block hold a non-zero bias?
-        if constexpr (BIAS) with_bias = ((jb < 64 ? bias_lo >> jb : bias_hi >> (jb - 64)) & 1ull) != 0;
+        if constexpr (MASKED) with_bias = ((jb < 64 ? bias_lo >> jb : bias_hi >> (jb - 64)) & 1ull) != 0;
         f32x4 acc[NQ][4];
         auto scores = [&](auto init_from_bias) {
 #pragma unroll
@@ -263,7 +276,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
                     }
             }
         };
-        if (BIAS && with_bias) {
+        if (MASKED && with_bias) {
 #pragma unroll
             for (int t = 0; t < 4; ++t) kb4[t] = bias4[16 * jb + t];
             if constexpr (PRESCALE) scores(std::true_type{});    // bias = initial value of the accumulators
@@ -285,7 +298,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
                 f32x4 a = acc[qs][t];
                 if constexpr (!PRESCALE) {
                     a = a * scale;
-                    if constexpr (BIAS) {   // two roundings (product, then sum), never a fused multiply-add
+                    if constexpr (MASKED) {   // two roundings (product, then sum), never a fused multiply-add
                         if (with_bias) {
 #pragma unroll
                             for (int r = 0; r < 4; ++r) a[r] = __fadd_rn(a[r], kb4[t][r]);
@@ -404,7 +417,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
         }
         jb = jn;
     }
-    if constexpr (BIAS) wait_async_copies();   // (only matters if no block was live: the speculative copy)
+    if constexpr (MASKED) wait_async_copies();   // (only matters if no block was live: the speculative copy)
 
     // ---- O[q][16 ds + li] = acc_o / row sum, q = q0 + 16 qs + 4 kb + r ----
     // A lane holds single elements of 4 rows; they pass through LDS (the K buffers, free now) so that
@@ -440,14 +453,15 @@ inline bool is_pow2(float x) {
     return frexpf(x, &e) == 0.5f;
 }
 
-template <int MODE, int NQ, bool BIAS>
-hipError_t launch_nq(const void *Q, const void *K, const void *V, const float *key_bias, int H, int BH, int Lq,
-                     int Lk, int d, float scale, void *O, hipStream_t st) {
+template <int MODE, int NQ, bool MASKED>
+hipError_t launch_nq(const void *Q, const void *K, const void *V, const float *key_bias, int H,
+                     const uint8_t *block_mask, int BH, int Lq, int Lk, int d, float scale, void *O, hipStream_t st) {
     const unsigned grid = (unsigned)((long)BH * (Lq / (64 * NQ)));
     const bool pre = is_pow2(scale);
-#define DFSS_LAUNCH(DD, PRE)                                                                                  \
-    hipLaunchKernelGGL((k_fused<DD, MODE, NQ, PRE, BIAS>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)Q,   \
-                       (const __bf16 *)K, (const __bf16 *)V, key_bias, H, Lq, Lk, scale, (uint16_t *)O)
+#define DFSS_LAUNCH(DD, PRE)                                                                                    \
+    hipLaunchKernelGGL((k_fused<DD, MODE, NQ, PRE, MASKED>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)Q,   \
+                       (const __bf16 *)K, (const __bf16 *)V, key_bias, H, block_mask, Lq, Lk, scale,            \
+                       (uint16_t *)O)
     if (d == 64) {
         if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
     } else {
@@ -458,17 +472,18 @@ hipError_t launch_nq(const void *Q, const void *K, const void *V, const float *k
 }
 
 template <int MODE>
-hipError_t launch(const void *Q, const void *K, const void *V, const float *key_bias, int H, int BH, int Lq, int Lk,
-                  int d, float scale, void *O, hipStream_t st) {
+hipError_t launch(const void *Q, const void *K, const void *V, const float *key_bias, int H,
+                  const uint8_t *block_mask, int BH, int Lq, int Lk, int d, float scale, void *O, hipStream_t st) {
     // 32 queries per wave when that still leaves at least ~2 workgroups per compute unit
     bool two = Lq % 128 == 0 && (long)BH * (Lq / 128) >= 768;   // at least 3 workgroups per compute unit
     if (const char *f = getenv("DFSS_FUSED_NQ")) two = Lq % 128 == 0 && f[0] == '2';   // for measurements
-    if (key_bias) {
-        if (two) return launch_nq<MODE, 2, true>(Q, K, V, key_bias, H, BH, Lq, Lk, d, scale, O, st);
-        return launch_nq<MODE, 1, true>(Q, K, V, key_bias, H, BH, Lq, Lk, d, scale, O, st);
+    if (block_mask) two = false;   // the block of the mask is the 64-query workgroup tile
+    if (key_bias || block_mask) {
+        if (two) return launch_nq<MODE, 2, true>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, st);
+        return launch_nq<MODE, 1, true>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, st);
     }
-    if (two) return launch_nq<MODE, 2, false>(Q, K, V, nullptr, 1, BH, Lq, Lk, d, scale, O, st);
-    return launch_nq<MODE, 1, false>(Q, K, V, nullptr, 1, BH, Lq, Lk, d, scale, O, st);
+    if (two) return launch_nq<MODE, 2, false>(Q, K, V, nullptr, 1, nullptr, BH, Lq, Lk, d, scale, O, st);
+    return launch_nq<MODE, 1, false>(Q, K, V, nullptr, 1, nullptr, BH, Lq, Lk, d, scale, O, st);
 }
 
 }  // namespace
@@ -476,8 +491,9 @@ hipError_t launch(const void *Q, const void *K, const void *V, const float *key_
 hipError_t launch_fused_attention32(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d,
                                     int mode, int nw, float scale, void *O, hipStream_t st);
 
-hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, const float *key_bias, int H, int BH,
-                                  int Lq, int Lk, int d, int mode, float scale, void *O, hipStream_t st) {
+hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, const float *key_bias, int H,
+                                  const uint8_t *block_mask, int BH, int Lq, int Lk, int d, int mode, float scale,
+                                  void *O, hipStream_t st) {
     // The 16-query kernel is the default.  The 32-query kernel (score MFMA at twice the rate, software
     // pipelined) only pays off once its larger tiles still fill the chip evenly; it is selected with
     // DFSS_FUSED_TILE = 32x2 | 32x4 (for measurements), 16 forces the default.
@@ -487,10 +503,11 @@ hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, c
         else if (f[0] == '3' && f[1] == '2' && f[2] == 'x' && f[3] == '2' && d == 64) tile = 32, nw = 2;
         else if (f[0] == '3' && f[1] == '2' && f[2] == 'x' && f[3] == '4' && Lq % 128 == 0) tile = 32, nw = 4;
     }
-    if (tile == 32 && !key_bias) return launch_fused_attention32(Q, K, V, BH, Lq, Lk, d, mode, nw, scale, O, st);
-    if (mode == 0) return launch<MODE_2TO4>(Q, K, V, key_bias, H, BH, Lq, Lk, d, scale, O, st);
-    if (mode == 1) return launch<MODE_1TO2>(Q, K, V, key_bias, H, BH, Lq, Lk, d, scale, O, st);
-    return launch<MODE_DENSE>(Q, K, V, key_bias, H, BH, Lq, Lk, d, scale, O, st);
+    if (tile == 32 && !key_bias && !block_mask)
+        return launch_fused_attention32(Q, K, V, BH, Lq, Lk, d, mode, nw, scale, O, st);
+    if (mode == 0) return launch<MODE_2TO4>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, st);
+    if (mode == 1) return launch<MODE_1TO2>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, st);
+    return launch<MODE_DENSE>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, st);
 }
 
 }  // namespace dfss

@@ -106,6 +106,24 @@ def key_padding_bias(lengths: torch.Tensor, Lk: int):
     return bias
 
 
+def block_pattern(nq: int, nk: int, seed: int, window: int = 1, n_global: int = 1, n_random: int = 2):
+    """uint8 [nq, nk] block pattern in the style of the block-sparse long-sequence models the paper
+    combines with (sliding window of +-`window` blocks around the diagonal, `n_global` leading key
+    blocks seen by every row block and `n_global` leading row blocks that see everything, plus
+    `n_random` random key blocks per row block).  Every row keeps at least its diagonal block."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    m = torch.zeros((nq, nk), dtype=torch.uint8)
+    for i in range(nq):
+        c = min(nk - 1, i * nk // nq)                       # diagonal block of this row block
+        m[i, max(0, c - window):min(nk, c + window + 1)] = 1
+        m[i, :min(n_global, nk)] = 1
+        if n_random > 0:
+            m[i, torch.randint(0, nk, (n_random,), generator=g)] = 1
+    m[:min(n_global, nq), :] = 1
+    return m
+
+
 def to_numpy_f32(t: torch.Tensor):
     """Widen a (bfloat16) tensor to a float32 numpy array holding the same values."""
     return t.to(torch.float32).contiguous().numpy()

@@ -85,6 +85,9 @@ def test_errors_are_reported_before_any_launch():
     assert lib.dense_attention_bias(aligned, aligned, aligned, aligned, ctypes.byref(ok), 0.125, aligned, ws, 16, None) == E_WS
     assert lib.dense_attention_fused_bias(aligned, aligned, aligned, odd, ctypes.byref(ok), 0.125, aligned, None) == E_SHAPE
     assert lib.dense_attention_fused_bias(aligned, aligned, aligned, aligned, ctypes.byref(ok), -1.0, aligned, None) == E_UNSUP
+    assert lib.dfss_attention_blocked(aligned, aligned, aligned, None, None, ctypes.byref(ok), 0.125, aligned, None) == E_NULL
+    assert lib.dfss_attention_blocked(aligned, aligned, aligned, None, aligned, ctypes.byref(bad), 0.125, aligned, None) == E_UNSUP
+    assert lib.dense_attention_fused_blocked(aligned, aligned, aligned, odd, aligned, ctypes.byref(ok), 0.125, aligned, None) == E_SHAPE
     assert lib.dfss_status_string(0) == b"ok"
     assert lib.dfss_status_string(E_WS) == b"workspace too small"
 

@@ -483,3 +483,55 @@ def test_attention_key_bias_skips_masked_blocks_anywhere():
     ref_dense = oracle.attention(Qn, Kn, Vn, 1, 1, 0.125, key_bias=bias.numpy(), heads_per_batch=H)
     assert np.max(np.abs(_np(O) - ref)) <= 2e-2
     assert np.max(np.abs(_np(Odf) - ref_dense)) <= 2e-2
+
+
+# ----------------------------------------------------------------------------------
+# hybrid block sparsity x N:M (blocked-ELL)
+# ----------------------------------------------------------------------------------
+@pytest.mark.parametrize("BH,Lq,Lk,d,N,M", [
+    (3, 512, 512, 64, 2, 4),
+    (2, 256, 640, 64, 1, 2),        # rectangular
+    (2, 256, 256, 128, 2, 4),       # d = 128
+    (1, 128, 8192, 64, 2, 4),       # longest key sequence: both halves of the block bitmap
+])
+def test_attention_blocked(BH, Lq, Lk, d, N, M):
+    Q, K, V = synth.gaussian_qkv(BH, Lq, Lk, d, 1.0, seed=8000 + Lq + Lk + d)
+    small = Lk // 64 <= 4
+    bm = synth.block_pattern(Lq // 64, Lk // 64, seed=8001 + Lk, window=0 if small else 1, n_random=0 if small else 3)
+    assert 0 < int(bm.sum()) < bm.numel()
+    s = Shape(1, BH, Lq, Lk, d, N, M)
+    scale = 1.0 / math.sqrt(d)
+    Qd, Kd, Vd, bmd = _dev(Q), _dev(K), _dev(V), _dev(bm)
+    O = dfss.dfss_attention_blocked(Qd, Kd, Vd, None, bmd, s, scale)
+    Od = dfss.dense_attention_fused_blocked(Qd, Kd, Vd, None, bmd, s, scale)
+    torch.cuda.synchronize()
+    Qn, Kn, Vn = (synth.to_numpy_f32(t) for t in (Q, K, V))
+    ref = oracle.attention(Qn, Kn, Vn, N, M, scale, block_mask=bm.numpy(), block_size=64)
+    ref_dense = oracle.attention(Qn, Kn, Vn, 1, 1, scale, block_mask=bm.numpy(), block_size=64)
+    assert np.max(np.abs(_np(O) - ref)) <= 2e-2
+    assert np.max(np.abs(_np(Od) - ref_dense)) <= 2e-2
+    # the pattern matters: full attention gives something else
+    assert np.max(np.abs(ref - oracle.attention(Qn, Kn, Vn, N, M, scale))) > 0.05
+
+
+def test_attention_blocked_with_key_bias_and_full_pattern():
+    B, H, L, d = 2, 2, 384, 64
+    Q, K, V, lengths, bias = _padding_case(B, H, L, L, d, 8100, integer=False)
+    s = Shape(B, H, L, L, d, 2, 4)
+    Qd, Kd, Vd, bd = _dev(Q), _dev(K), _dev(V), _dev(bias)
+    Qn, Kn, Vn = (synth.to_numpy_f32(t) for t in (Q, K, V))
+    # block pattern and padding mask together (row blocks keep block 0, which always holds real keys)
+    bm = synth.block_pattern(L // 64, L // 64, seed=8101, n_random=1)
+    O = dfss.dfss_attention_blocked(Qd, Kd, Vd, bd, _dev(bm), s, 0.125)
+    torch.cuda.synchronize()
+    ref = oracle.attention(Qn, Kn, Vn, 2, 4, 0.125, key_bias=bias.numpy(), heads_per_batch=H,
+                           block_mask=bm.numpy(), block_size=64)
+    assert np.max(np.abs(_np(O) - ref)) <= 2e-2
+    # a pattern that keeps every block is the unblocked call, bit for bit
+    ones = torch.ones((L // 64, L // 64), dtype=torch.uint8)
+    O1 = dfss.dfss_attention_blocked(Qd, Kd, Vd, bd, _dev(ones), s, 0.125)
+    O2 = dfss.dfss_attention_bias(Qd, Kd, Vd, bd, s, 0.125)
+    O3 = dfss.dfss_attention_blocked(Qd, Kd, Vd, None, _dev(ones), s, 0.125)
+    O4 = dfss.dfss_attention(Qd, Kd, Vd, s, 0.125)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2) and torch.equal(O3, O4)
