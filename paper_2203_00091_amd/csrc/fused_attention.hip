@@ -112,9 +112,19 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
     const int w = tid >> 6, l = tid & 63, li = l & 15, kb = l >> 4;
 
     const unsigned qtiles = Lq / TQ;
-    const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
-    const int qt = item % qtiles;
-    const int bh = item / qtiles;
+    int qt, bh;
+    if (MASKED && block_mask) {
+        // Row blocks of a block pattern differ widely in work (rows that see every key next to rows
+        // that see a window), and the heavy ones usually come first: hand out row block 0 of every
+        // head, then row block 1, ... in launch order, so that the long workgroups start at once.
+        const unsigned heads = gridDim.x / qtiles;
+        qt = blockIdx.x / heads;
+        bh = blockIdx.x % heads;
+    } else {
+        const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
+        qt = item % qtiles;
+        bh = item / qtiles;
+    }
     const int q0 = qt * TQ + w * 16 * NQ;
     const int nblocks = Lk / KB;
 
