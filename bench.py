@@ -50,6 +50,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--key-padding", action="store_true",
                     help="run the key-bias entry points on a padded batch (seeded lengths in [L/2, L])")
+    ap.add_argument("--block-pattern", action="store_true",
+                    help="run the block-masked entry points with a seeded window + global + random pattern of "
+                         "64 x 64 blocks (fused kernels only; FLOPs are counted on the kept blocks)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 64 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
@@ -103,9 +106,17 @@ def main():
         lengths = synth.padding_lengths(w.B, L, w.seed + 7)
         bias = synth.key_padding_bias(lengths, L).to(dev)
 
+    block_mask, density = None, 1.0
+    if args.block_pattern:
+        bm = synth.block_pattern(L // 64, L // 64, seed=w.seed + 9, window=1, n_global=1, n_random=2)
+        density = float(bm.float().mean())
+        block_mask = bm.to(dev)
+
     def step_sparse(i):
         b = sets[i % nsets]
-        if bias is None:
+        if block_mask is not None:
+            dfss.dfss_attention_blocked(b["Q"], b["K"], b["V"], bias, block_mask, s, w.scale, O=b["O"])
+        elif bias is None:
             dfss.dfss_attention(b["Q"], b["K"], b["V"], s, w.scale, O=b["O"], ws=b["ws"])
         else:
             dfss.dfss_attention_bias(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"], ws=b["ws"])
@@ -119,7 +130,9 @@ def main():
 
     def step_dense_fused(i):
         b = sets[i % nsets]
-        if bias is None:
+        if block_mask is not None:
+            dfss.dense_attention_fused_blocked(b["Q"], b["K"], b["V"], bias, block_mask, s, w.scale, O=b["O"])
+        elif bias is None:
             dfss.dense_attention_fused(b["Q"], b["K"], b["V"], s, w.scale, O=b["O"])
         else:
             dfss.dense_attention_fused_bias(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"])
@@ -214,8 +227,8 @@ def main():
     k2 = event_avg_ms(step_stage2, K)
     k3 = event_avg_ms(step_stage3, K)
 
-    flops_alg = 3.0 * BH * L * L * d
-    flops_eq = 4.0 * BH * L * L * d
+    flops_alg = 3.0 * BH * L * L * d * density      # kept blocks only when a block pattern is given
+    flops_eq = 4.0 * BH * L * L * d * density
     ms = t_sparse / K * 1e3
     ms_dense = t_dense / K * 1e3
     ms_dense_fused = t_dense_fused / K * 1e3
@@ -246,7 +259,9 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "L": L, "d": d, "N": w.N, "M": w.M,
-                   "key_padding": bool(args.key_padding), "buffer_sets": nsets, "cache": "warm" if args.warm else "cold (rotating buffer sets)",
+                   "key_padding": bool(args.key_padding),
+                   "block_pattern": (f"window +-1, 1 global, 2 random blocks of 64 x 64, density {density:.3f}"
+                                     if args.block_pattern else None), "buffer_sets": nsets, "cache": "warm" if args.warm else "cold (rotating buffer sets)",
                    "launch": "hip graph of all timed steps" if use_graph else "direct"},
         "roofline": {"bound": "mfma", "kernel": "k_fused (dfss_attention)", "achieved": round(achieved, 2),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -273,6 +288,16 @@ def main():
         },
     }
 
+    if args.block_pattern:
+        # only the fused kernels take a block pattern: the three-stage figures would be those of a
+        # different function
+        for k in ("speedup_vs_dense_attention_3stage", "staged_path_speedup_vs_dense_attention_3stage",
+                  "dense_attention_3stage_ms_per_step", "dfss_attention_staged_ms_per_step", "stage_kernel_ms",
+                  "stage_kernel_GBps", "stage_kernel_frac_of_hbm_peak", "sddmm_prune_tflops",
+                  "sddmm_prune_frac_of_mfma_peak"):
+            out["extra"][k] = None
+        out["roofline"]["algorithmic_hbm_bytes_per_launch"] = None
+
     if not args.no_cpu_baseline:
         import oracle
         Qn, Kn, Vn = (synth.to_numpy_f32(t) for t in (Qc, Kc, Vc))
@@ -283,7 +308,8 @@ def main():
         reps, dt = 0, 0.0
         t0 = time.perf_counter()
         while dt < 10.0 and reps < 500:         # about ten seconds of host work, whole passes only
-            oracle.attention(Qn[:heads], Kn[:heads], Vn[:heads], w.N, w.M, w.scale)
+            oracle.attention(Qn[:heads], Kn[:heads], Vn[:heads], w.N, w.M, w.scale,
+                             block_mask=None if block_mask is None else block_mask.cpu().numpy())
             reps += 1
             dt = time.perf_counter() - t0
         out["cpu_baseline"] = {
