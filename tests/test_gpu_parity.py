@@ -535,3 +535,49 @@ def test_attention_blocked_with_key_bias_and_full_pattern():
     O4 = dfss.dfss_attention(Qd, Kd, Vd, s, 0.125)
     torch.cuda.synchronize()
     assert torch.equal(O1, O2) and torch.equal(O3, O4)
+
+
+# ----------------------------------------------------------------------------------
+# capture into a HIP graph (no allocation, no synchronisation, no host state inside the calls)
+# ----------------------------------------------------------------------------------
+def test_calls_replay_correctly_from_a_hip_graph():
+    """Every entry point is enqueued into one graph; each replay (with eager work and
+    synchronisations in between, and the inputs changed between replays) must reproduce the eager
+    result of the same inputs."""
+    w = synth.WORKLOADS["tiny_2to4"]
+    s = Shape(2, 2, 256, 256, 64, 2, 4)
+    Q, K, V = (_dev(t) for t in synth.gaussian_qkv(4, 256, 256, 64, 1.0, seed=9100))
+    lengths = synth.padding_lengths(2, 256, 9101)
+    bias = _dev(synth.key_padding_bias(lengths, 256))
+    bm = _dev(synth.block_pattern(4, 4, seed=9102, window=0, n_random=0))
+    ws = torch.empty(max(dfss.dfss_workspace_bytes(s), dfss.dense_workspace_bytes(s)), dtype=torch.uint8, device=DEV)
+    outs = {k: torch.empty_like(Q) for k in ("fused", "bias", "blocked", "dense", "dense_fused", "stages")}
+    vals = torch.empty((s.BH, s.Lq, s.Lc), dtype=torch.bfloat16, device=DEV)
+    meta = torch.empty((s.BH * s.Lq * (s.Lk // 16),), dtype=torch.int16, device=DEV)
+
+    def run_all():
+        dfss.dfss_attention(Q, K, V, s, w.scale, O=outs["fused"], ws=ws)
+        dfss.dfss_attention_bias(Q, K, V, bias, s, w.scale, O=outs["bias"], ws=ws)
+        dfss.dfss_attention_blocked(Q, K, V, bias, bm, s, w.scale, O=outs["blocked"])
+        dfss.dense_attention(Q, K, V, s, w.scale, O=outs["dense"], ws=ws)
+        dfss.dense_attention_fused(Q, K, V, s, w.scale, O=outs["dense_fused"])
+        dfss.dfss_sddmm_prune(Q, K, s, w.scale, vals=vals, meta=meta)
+        dfss.dfss_sparse_softmax(vals, s)
+        dfss.dfss_spmm(vals, meta, V, s, O=outs["stages"])
+
+    run_all()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run_all()
+    for rep in range(3):
+        Q.copy_((torch.randn(Q.shape, generator=torch.Generator().manual_seed(9200 + rep))).to(torch.bfloat16))
+        run_all()                                   # eager reference on the new inputs
+        torch.cuda.synchronize()
+        eager = {k: v.clone() for k, v in outs.items()}
+        for v in outs.values():
+            v.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        for k in outs:
+            assert torch.equal(outs[k], eager[k]), (rep, k)
