@@ -106,6 +106,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
     constexpr int STEPS = D / 32;        // MFMA k-steps
     constexpr int TQ = 64 * NQ;          // queries per workgroup
     __shared__ u32x4 Ks[2][TILE];
+    __shared__ f32x4 Bs[BIAS ? 2 : 1][KB / 4];   // bias of the block's 128 keys, copied along with K
 
     const int tid = threadIdx.x;
     const int w = tid >> 6, l = tid & 63, li = l & 15, kb = l >> 4;
@@ -132,10 +133,15 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
         src_off[i] = key * D + c * 8;
     }
     const uint32_t lds_k = lds_address(&Ks[0][w * 64]);   // this wave's 1 KB slice of copy 0, buffer 0
+    const float *bias_b = BIAS ? key_bias + (size_t)(bh / H) * Lk : nullptr;
+    const uint32_t lds_b = lds_address(&Bs[0][0]);
     auto issue_block = [&](int jb, int buf) {
         const __bf16 *src = Kh + (size_t)jb * KB * D;
 #pragma unroll
         for (int i = 0; i < LPT; ++i) async_copy16(src, 2u * src_off[i], lds_k + 16u * (buf * TILE + i * NT));
+        if constexpr (BIAS) {   // 512 bytes: lanes 0..31 of wave 0 (the copy lands through the same counter as K)
+            if (tid < KB / 4) async_copy16(bias_b + (size_t)jb * KB, 16u * tid, lds_b + (uint32_t)(buf * KB * 4));
+        }
     };
 
     issue_block(jb0, 0);
@@ -160,7 +166,6 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
         }
 
     const int rb0 = q0 >> 4;                 // first 16-row block of this wave
-    const float *bias_b = BIAS ? key_bias + (size_t)(bh / H) * Lk : nullptr;
 
     for (int it = 0; it < blocks_per_wg; ++it) {
         const int jb = jb0 + it;
@@ -183,9 +188,8 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
             f32x4 acc[NQ][4];
             f32x4 kb4[4];    // bias of keys 128 jb + 32 kb + 16 half + 4 t + r
             if constexpr (BIAS) {
-                const f32x4 *bp = reinterpret_cast<const f32x4 *>(bias_b + KB * jb + 32 * kb + 16 * half);
 #pragma unroll
-                for (int t = 0; t < 4; ++t) kb4[t] = bp[t];
+                for (int t = 0; t < 4; ++t) kb4[t] = Bs[buf][8 * kb + 4 * half + t];
             }
 #pragma unroll
             for (int qs = 0; qs < NQ; ++qs)
@@ -289,6 +293,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
     // per-wave staging of the kept values of one 64-key pair (32 rows x 64 bytes), so that they leave
     // as 64-byte row segments from consecutive lanes instead of 16-byte pieces scattered over 32 rows
     __shared__ u32x4 Stage[MODE == MODE_DENSE ? 1 : 4][32 * 4];
+    __shared__ f32x4 Bs[BIAS ? 2 : 1][KB / 4];   // bias of the block's 128 keys, copied along with K
 
     const int tid = threadIdx.x;
     const int w = tid >> 6, l = tid & 63, lj = l & 31, h = l >> 5;
@@ -314,10 +319,15 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
         src_off[i] = key * D + c * 8;
     }
     const uint32_t lds_k = lds_address(&Ks[0][w * 64]);
+    const float *bias_b = BIAS ? key_bias + (size_t)(bh / H) * Lk : nullptr;
+    const uint32_t lds_b = lds_address(&Bs[0][0]);
     auto issue_block = [&](int jb, int buf) {
         const __bf16 *src = Kh + (size_t)jb * KB * D;
 #pragma unroll
         for (int i = 0; i < LPT; ++i) async_copy16(src, 2u * src_off[i], lds_k + 16u * (buf * TILE + i * NT));
+        if constexpr (BIAS) {   // 512 bytes: lanes 0..31 of wave 0 (the copy lands through the same counter as K)
+            if (tid < KB / 4) async_copy16(bias_b + (size_t)jb * KB, 16u * tid, lds_b + (uint32_t)(buf * KB * 4));
+        }
     };
 
     issue_block(jb0, 0);
@@ -349,7 +359,6 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
     // a lane computes the words of chunks (p = 0, h) and (p = 1, h) = slots 2 h and 2 h + 1 of its row
     u32x4 *const meta_row4 = reinterpret_cast<u32x4 *>(
         meta + (((size_t)bh * (Lq / 16) + ((q0 + lj) >> 4)) * (Lk / KB) * 16 + (lj & 15)) * 4);
-    const float *bias_b = BIAS ? key_bias + (size_t)(bh / H) * Lk : nullptr;
 
     for (int it = 0; it < blocks_per_wg; ++it) {
         const int jb = jb0 + it;
@@ -368,11 +377,10 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
             f32x16 acc[2];
             f32x4 kb4[2][4];   // bias of keys 128 jb + 64 p + 32 h + 16 u + 4 g + x
             if constexpr (BIAS) {
-                const f32x4 *bp = reinterpret_cast<const f32x4 *>(bias_b + KB * jb + 64 * p + 32 * h);
 #pragma unroll
                 for (int u = 0; u < 2; ++u)
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) kb4[u][g] = bp[4 * u + g];
+                    for (int g = 0; g < 4; ++g) kb4[u][g] = Bs[buf][16 * p + 8 * h + 4 * u + g];
             }
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
