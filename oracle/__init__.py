@@ -73,6 +73,9 @@ def _load():
         L.oracle_apply_block_mask.restype = c_int
         L.oracle_add_key_bias.argtypes = [_f32p, c_int, c_int, _f32p]
         L.oracle_add_key_bias.restype = None
+        L.oracle_attention_backward.argtypes = [_f32p, _f32p, _f32p, _f32p, _f32p, _i32p, c_int, c_int, c_int, c_int,
+                                                c_float, _f32p, _f32p, _f32p, ctypes.c_void_p]
+        L.oracle_attention_backward.restype = None
         L.oracle_num_threads.argtypes = []
         L.oracle_num_threads.restype = c_int
         L.oracle_quality_p.argtypes = [_f32p, _u8p, c_int, c_int, c_double]
@@ -214,6 +217,25 @@ def attention(Q, K, V, N, M, scale, store_bf16=False, key_bias=None, heads_per_b
     if rc != 0:
         raise ValueError(f"oracle_attention failed rc={rc}")
     return O[0] if squeeze else O
+
+
+def attention_backward(Q, K, V, dO, P, kidx, scale, return_dS=False):
+    """Gradients of one head through the fixed selection: (dQ, dK, dV[, dS]).
+
+    P [Lq, Lc] are the softmax weights of the kept entries and kidx [Lq, Lc] their key indices, both
+    from the forward pass (prune + softmax_kept)."""
+    Q, K, V, dO, P = _f32(Q), _f32(K), _f32(V), _f32(dO), _f32(P)
+    kidx = np.ascontiguousarray(kidx, dtype=np.int32)
+    Lq, d = Q.shape
+    Lk = K.shape[0]
+    Lc = P.shape[1]
+    dQ = np.empty((Lq, d), np.float32)
+    dK = np.empty((Lk, d), np.float32)
+    dV = np.empty((Lk, d), np.float32)
+    dS = np.empty((Lq, Lc), np.float32) if return_dS else None
+    _load().oracle_attention_backward(Q, K, V, dO, P, kidx, Lq, Lk, Lc, d, float(scale), dQ, dK, dV,
+                                      dS.ctypes.data if dS is not None else None)
+    return (dQ, dK, dV, dS) if return_dS else (dQ, dK, dV)
 
 
 def num_threads():

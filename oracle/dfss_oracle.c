@@ -366,6 +366,59 @@ int oracle_attention_batched(const float *Q, const float *K, const float *V,
     return oracle_attention_masked_batched(Q, K, V, NULL, 1, NULL, 0, BH, Lq, Lk, d, N, M, scale, store_bf16, O);
 }
 
+/* ------------------------------------------------------------------ */
+/* Backward pass of one head through the FIXED selection of the        */
+/* forward pass (the paper finetunes with DFSS attention, Sec. 5.1,    */
+/* but does not describe a backward kernel; the reading taken is the   */
+/* usual one for pruning masks: the selection is a constant of the     */
+/* step, gradients flow through the kept entries only).  With          */
+/*   S = scale Q K^T (+ bias), kept set and P = softmax over the kept  */
+/*   entries, O = P V   (Sec. 3.1)                                     */
+/* the chain rule gives, for an upstream gradient dO:                  */
+/*   dV[j]   = sum_i P[i][j] dO[i]                                      */
+/*   dP[i][j] = dO[i] . V[j]                  (kept j only)             */
+/*   delta_i = sum_j P[i][j] dP[i][j]                                   */
+/*   dS[i][j] = P[i][j] (dP[i][j] - delta_i)                            */
+/*   dQ[i]   = scale sum_j dS[i][j] K[j],  dK[j] = scale sum_i dS[i][j] Q[i] */
+/* All sums in double.  P (the weights, [Lq][Lc]) and kidx come from   */
+/* the forward pass; dS_out (may be NULL) receives dS, [Lq][Lc].       */
+/* ------------------------------------------------------------------ */
+void oracle_attention_backward(const float *Q, const float *K, const float *V, const float *dO,
+                               const float *P, const int32_t *kidx,
+                               int Lq, int Lk, int Lc, int d, float scale,
+                               float *dQ, float *dK, float *dV, float *dS_out)
+{
+    double *aQ = (double *)calloc((size_t)Lq * d, sizeof(double));
+    double *aK = (double *)calloc((size_t)Lk * d, sizeof(double));
+    double *aV = (double *)calloc((size_t)Lk * d, sizeof(double));
+    double *dP = (double *)malloc(sizeof(double) * (size_t)Lc);
+    for (int i = 0; i < Lq; ++i) {
+        const float *doi = dO + (size_t)i * d;
+        double delta = 0.0;
+        for (int c = 0; c < Lc; ++c) {
+            const float *v = V + (size_t)kidx[(size_t)i * Lc + c] * d;
+            double acc = 0.0;
+            for (int k = 0; k < d; ++k) acc += (double)doi[k] * (double)v[k];
+            dP[c] = acc;
+            delta += (double)P[(size_t)i * Lc + c] * acc;
+        }
+        for (int c = 0; c < Lc; ++c) {
+            const int j = kidx[(size_t)i * Lc + c];
+            const double p = (double)P[(size_t)i * Lc + c];
+            const double ds = p * (dP[c] - delta);
+            if (dS_out) dS_out[(size_t)i * Lc + c] = (float)ds;
+            for (int k = 0; k < d; ++k) {
+                aV[(size_t)j * d + k] += p * (double)doi[k];
+                aQ[(size_t)i * d + k] += (double)scale * ds * (double)K[(size_t)j * d + k];
+                aK[(size_t)j * d + k] += (double)scale * ds * (double)Q[(size_t)i * d + k];
+            }
+        }
+    }
+    for (size_t t = 0; t < (size_t)Lq * d; ++t) dQ[t] = (float)aQ[t];
+    for (size_t t = 0; t < (size_t)Lk * d; ++t) { dK[t] = (float)aK[t]; dV[t] = (float)aV[t]; }
+    free(aQ); free(aK); free(aV); free(dP);
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP
