@@ -150,6 +150,13 @@ dfss_status dense_attention_fused_blocked(const void *Q, const void *K, const vo
                                           const void *block_mask, const dfss_shape *s, float scale, void *O,
                                           void *stream);
 
+/* ---- backward pass through the fixed selection (finetuning, Sec. 5.1) ---------------- */
+/* Transposed sparse product: out[B*H, Lk, d] = A^T X with A given in compressed form (vals,
+ * meta as written by stage 1 / stage 2) and X bfloat16 [B*H, Lq, d]; fp32 accumulation, bfloat16
+ * output.  With A = softmax weights P and X = dO this is dV; with A = dS and X = Q it is dK. */
+dfss_status dfss_spmm_t(const void *vals, const void *meta, const void *X, const dfss_shape *s, void *out,
+                        void *stream);
+
 /* ---- metadata order ---------------------------------------------------------------- */
 /* Canonical order: uint16 [B*H, Lq, Lk/16], word w of a row = codes of key runs
  * 4w..4w+3, code = p_lo | p_hi << 2 with p the kept key index mod 4 (the 2-bit

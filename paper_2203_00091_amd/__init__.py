@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     dfss_sddmm_prune_bias,
     dfss_sparse_softmax,
     dfss_spmm,
+    dfss_spmm_t,
     dfss_vals_bytes,
     dfss_workspace_bytes,
     library_path,

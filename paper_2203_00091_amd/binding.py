@@ -22,7 +22,7 @@ EXPORTS = (
     "dfss_sddmm_prune", "dfss_sparse_softmax", "dfss_spmm", "dfss_attention", "dense_attention",
     "dense_attention_fused", "dfss_meta_to_canonical", "dfss_meta_from_canonical", "dfss_status_string",
     "dfss_sddmm_prune_bias", "dfss_attention_bias", "dense_attention_bias", "dense_attention_fused_bias",
-    "dfss_attention_blocked", "dense_attention_fused_blocked",
+    "dfss_attention_blocked", "dense_attention_fused_blocked", "dfss_spmm_t",
 )
 
 
@@ -92,12 +92,14 @@ def load_library():
         L.dense_attention_fused_bias.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_attention_blocked.argtypes = [vp, vp, vp, vp, vp, sp, f32, vp, vp]
         L.dense_attention_fused_blocked.argtypes = [vp, vp, vp, vp, vp, sp, f32, vp, vp]
+        L.dfss_spmm_t.argtypes = [vp, vp, vp, sp, vp, vp]
         L.dfss_meta_to_canonical.argtypes = [vp, sp, vp, vp]
         L.dfss_meta_from_canonical.argtypes = [vp, sp, vp, vp]
         for name in ("dfss_sddmm_prune", "dfss_sparse_softmax", "dfss_spmm", "dfss_attention",
                      "dense_attention", "dense_attention_fused", "dfss_meta_to_canonical", "dfss_meta_from_canonical",
                      "dfss_sddmm_prune_bias", "dfss_attention_bias", "dense_attention_bias",
-                     "dense_attention_fused_bias", "dfss_attention_blocked", "dense_attention_fused_blocked"):
+                     "dense_attention_fused_bias", "dfss_attention_blocked", "dense_attention_fused_blocked",
+                     "dfss_spmm_t"):
             getattr(L, name).restype = ctypes.c_int
         L.dfss_status_string.argtypes = [ctypes.c_int]
         L.dfss_status_string.restype = ctypes.c_char_p
@@ -283,6 +285,15 @@ def dense_attention_fused_blocked(Q, K, V, key_bias, block_mask, s: Shape, scale
                                                       _ptr(O), _stream())
     _check("dense_attention_fused_blocked", st)
     return O
+
+
+def dfss_spmm_t(vals, meta, X, s: Shape, out=None):
+    """Transposed sparse product A^T X -> bf16 [BH, Lk, d] (dV = P^T dO, dK = dS^T Q)."""
+    if out is None:
+        out = torch.empty((s.BH, s.Lk, s.d), dtype=torch.bfloat16, device=X.device)
+    st = load_library().dfss_spmm_t(_ptr(vals), _ptr(meta), _ptr(X), ctypes.byref(s.c()), _ptr(out), _stream())
+    _check("dfss_spmm_t", st)
+    return out
 
 
 def dfss_meta_to_canonical(meta, s: Shape, canon=None):

@@ -206,6 +206,15 @@ dfss_status dense_attention_fused_blocked(const void *Q, const void *K, const vo
     return attention_blocked(Q, K, V, key_bias, block_mask, s, true, scale, O, stream);
 }
 
+dfss_status dfss_spmm_t(const void *vals, const void *meta, const void *X, const dfss_shape *s, void *out,
+                        void *stream) {
+    Dims D;
+    if (!vals || !meta || !X || !out) return DFSS_ERR_NULL;
+    if (dfss_status st = check_shape(s, true, &D)) return st;
+    if (misaligned(vals) || misaligned(meta) || misaligned(X) || misaligned(out)) return DFSS_ERR_SHAPE;
+    return hip_status(dfss::launch_spmm_t(vals, meta, X, D.BH, D.Lq, D.Lk, D.d, out, (hipStream_t)stream));
+}
+
 dfss_status dfss_meta_to_canonical(const void *meta, const dfss_shape *s, void *canon, void *stream) {
     Dims D;
     if (!meta || !canon) return DFSS_ERR_NULL;

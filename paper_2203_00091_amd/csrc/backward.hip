@@ -1,0 +1,195 @@
+// Backward pass of DFSS attention through the fixed selection of the forward pass.
+//
+// The paper finetunes with DFSS attention (arXiv 2203.00091, Sec. 5.1) but describes no backward
+// kernel; the selection is treated as a constant of the step, so with P the softmax weights of the
+// kept entries (Sec. 3.1) and dO the upstream gradient:
+//     dV = P^T dO,   dP = (dO V^T) at the kept positions,   delta_i = dO_i . O_i,
+//     dS = P .* (dP - delta),   dQ = scale dS K,   dK = scale dS^T Q.
+// Two kernels live here; dQ reuses the forward SpMM (stage 3) with K in the place of V.
+//
+//   k_masked_sddmm_ds  dS' = scale * P .* (dO V^T - delta) at the kept positions, written in the
+//                      compressed layout of the forward pass.  It is the stage-1 mainloop with V in
+//                      the place of K and dO in the place of Q; the epilogue picks the kept entries
+//                      with the stored position codes instead of selecting them.
+//   k_spmm_t           out = A^T X for a compressed A (dV = P^T dO, dK = dS'^T Q).  The contraction
+//                      runs over queries, across which the N:M structure does not run, so the tile
+//                      of A is expanded to dense bfloat16 in LDS and both operands are read with the
+//                      transposing LDS read.
+#include <cstdlib>
+
+#include "dfss_device.hpp"
+#include "dfss_kernels.hpp"
+
+namespace dfss {
+
+namespace {
+
+constexpr int NT = 256;   // 4 waves
+constexpr int KB = 128;   // keys per block
+
+__device__ __forceinline__ unsigned xcd_contiguous(unsigned id, unsigned total) {
+    const unsigned per = total / 8;
+    return id < per * 8 ? (id % 8) * per + id / 8 : id;
+}
+
+// ------------------------------------------------------------------------------------------------
+// out[bh][key][c] = sum_q A[bh][q][key] X[bh][q][c]
+// A: kept values bf16 [BH, Lq, Lk/2] + metadata in the library's order; X: bf16 [BH, Lq, D].
+// One workgroup owns 128 keys of one head (wave w: keys 32 w .. 32 w + 31, all D columns) and walks
+// over the queries 64 at a time.
+// ------------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(NT, 2) void k_spmm_t(const uint32_t *__restrict__ A, const uint32_t *__restrict__ meta,
+                                                  const __bf16 *__restrict__ X, int Lq, int Lk,
+                                                  uint16_t *__restrict__ out) {
+    constexpr int QB = 64;              // queries per step
+    constexpr int CPR = D / 8;          // 16-byte chunks per X row
+    constexpr int XT = QB * CPR;        // chunks per X tile
+    constexpr int LPT = XT / NT;        // asynchronous copies per thread per tile
+    constexpr int DS = D / 16;          // 16-column output tiles
+    constexpr int AROW = 2 * KB + 48;   // bytes per row of the expanded A tile (padding spreads the rows over the banks)
+    __shared__ u32x4 Xs[2][XT];
+    __shared__ __attribute__((aligned(16))) char Ad[2][QB * AROW];
+
+    const int tid = threadIdx.x;
+    const int w = tid >> 6, l = tid & 63, li = l & 15, g = l >> 4;
+
+    const unsigned kblocks = Lk / KB;
+    const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int jblk = item % kblocks;
+    const int bh = item / kblocks;
+    const int nq = Lq / QB;
+
+    // X tile in LDS: row = query, chunk c at row * CPR + (c ^ ((row & 3) << 1))
+    const __bf16 *Xh = X + (size_t)bh * Lq * D;
+    int src_off[LPT];
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+        const int p = i * NT + tid;
+        const int row = p / CPR, c = (p % CPR) ^ ((row & 3) << 1);
+        src_off[i] = row * D + c * 8;
+    }
+    const uint32_t lds_x = lds_address(&Xs[0][w * 64]);
+    auto issue_x = [&](int qb, int buf) {
+        const __bf16 *src = Xh + (size_t)qb * QB * D;
+#pragma unroll
+        for (int i = 0; i < LPT; ++i) async_copy16(src, 2u * src_off[i], lds_x + 16u * (buf * XT + i * NT));
+    };
+
+    // A tile: thread (query aq, chunk ac) expands the 32 keys 128 jblk + 32 ac .. +31 of its query
+    const int aq = tid >> 2, ac = tid & 3;
+    const int meta_slot = ((ac & 1) << 1) | (ac >> 1);
+    struct ARaw {
+        u32x4 v0, v1;      // 16 kept values
+        uint32_t word;     // their 8 position codes
+    };
+    auto load_a = [&](int qb) {
+        ARaw r;
+        const int q = qb * QB + aq;
+        const u32x4 *pr = reinterpret_cast<const u32x4 *>(A + ((size_t)bh * Lq + q) * (size_t)(Lk / 4)) + jblk * 8 + ac * 2;
+        r.v0 = pr[0];
+        r.v1 = pr[1];
+        r.word = meta[((((size_t)bh * (Lq / 16) + (q >> 4)) * kblocks + jblk) * 16 + (q & 15)) * 4 + meta_slot];
+        return r;
+    };
+    auto expand_a = [&](const ARaw &r, int buf) {
+        u32x4 *dst = reinterpret_cast<u32x4 *>(&Ad[buf][aq * AROW + ac * 64]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {       // 8 keys = 2 groups per 16 bytes
+            u32x4 o;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int grp = 2 * i + h;
+                const uint32_t kept = grp < 4 ? r.v0[grp] : r.v1[grp - 4];
+                const uint32_t lo = kept & 0xFFFFu, hi = kept >> 16;
+                const uint32_t code = (r.word >> (4 * grp)) & 0xFu;
+                const uint32_t plo = code & 3u, phi = code >> 2;
+                const uint32_t k0 = plo == 0 ? lo : 0u;
+                const uint32_t k1 = plo == 1 ? lo : (phi == 1 ? hi : 0u);
+                const uint32_t k2 = plo == 2 ? lo : (phi == 2 ? hi : 0u);
+                const uint32_t k3 = phi == 3 ? hi : 0u;
+                o[2 * h] = k0 | (k1 << 16);
+                o[2 * h + 1] = k2 | (k3 << 16);
+            }
+            dst[i] = o;
+        }
+    };
+
+    f32x4 acc[2][DS];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < DS; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // transposing reads: lane li of a 16-lane group addresses element [row0 + li/4][col0 + 4 (li%4)]
+    const int tr_row = li >> 2;
+    const int tr_sub = (li >> 1) & 1, tr_byte = 8 * (li & 1), tr_xor = tr_row << 1;
+
+    issue_x(0, 0);
+    ARaw raw = load_a(0);
+
+    for (int qb = 0; qb < nq; ++qb) {
+        const int buf = qb & 1;
+        expand_a(raw, buf);
+        wait_async_copies();   // the X tile of this step (and the A values just consumed) have arrived
+        __syncthreads();       // both tiles are complete; the other buffers are free
+        if (qb + 1 < nq) {
+            issue_x(qb + 1, buf ^ 1);
+            raw = load_a(qb + 1);
+        }
+        const char *abase = &Ad[buf][0];
+        const char *xbase = reinterpret_cast<const char *>(&Xs[buf][0]);
+        auto tr_a = [&](int q0, int col0) {
+            return lds_read_tr16(abase + (q0 + tr_row) * AROW + (col0 + 4 * (li & 3)) * 2);
+        };
+        auto tr_x = [&](int q0, int nt) {
+            const int row = q0 + tr_row;
+            const int chunk = (2 * nt + tr_sub) ^ tr_xor;   // (row & 3) == tr_row: q0 is a multiple of 4
+            return lds_read_tr16(xbase + (row * CPR + chunk) * 16 + tr_byte);
+        };
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {     // 32 queries per MFMA step; lane group g takes queries 8 g .. 8 g + 7
+            const int q0 = 32 * ks + 8 * g;
+            bf16x8 a[2];
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+                const s16x4 t0 = tr_a(q0, 32 * w + 16 * mt), t1 = tr_a(q0 + 4, 32 * w + 16 * mt);
+                a[mt] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(t0, t1, 0, 1, 2, 3, 4, 5, 6, 7));
+            }
+#pragma unroll
+            for (int nt = 0; nt < DS; ++nt) {
+                const s16x4 t0 = tr_x(q0, nt), t1 = tr_x(q0 + 4, nt);
+                const bf16x8 b = __builtin_bit_cast(bf16x8, __builtin_shufflevector(t0, t1, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) acc[mt][nt] = mfma16(a[mt], b, acc[mt][nt]);
+            }
+        }
+    }
+
+    // acc[mt][nt][r] = out[key 128 jblk + 32 w + 16 mt + 4 g + r][16 nt + li]
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const size_t key = (size_t)bh * Lk + (size_t)jblk * KB + 32 * w + 16 * mt + 4 * g + r;
+#pragma unroll
+            for (int nt = 0; nt < DS; ++nt)
+                out[key * D + 16 * nt + li] = (uint16_t)(pack_bf16x2(acc[mt][nt][r], 0.f) & 0xFFFFu);
+        }
+}
+
+}  // namespace
+
+hipError_t launch_spmm_t(const void *vals, const void *meta, const void *X, int BH, int Lq, int Lk, int d, void *out,
+                         hipStream_t st) {
+    const unsigned grid = (unsigned)((long)BH * (Lk / KB));
+    if (d == 64)
+        hipLaunchKernelGGL((k_spmm_t<64>), dim3(grid), dim3(NT), 0, st, (const uint32_t *)vals, (const uint32_t *)meta,
+                           (const __bf16 *)X, Lq, Lk, (uint16_t *)out);
+    else
+        hipLaunchKernelGGL((k_spmm_t<128>), dim3(grid), dim3(NT), 0, st, (const uint32_t *)vals,
+                           (const uint32_t *)meta, (const __bf16 *)X, Lq, Lk, (uint16_t *)out);
+    return hipGetLastError();
+}
+
+}  // namespace dfss

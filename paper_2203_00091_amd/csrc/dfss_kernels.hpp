@@ -27,6 +27,10 @@ hipError_t launch_dense_av(const void *P, const void *V, int BH, int Lq, int Lk,
 hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, const float *key_bias, int H,
                                   const uint8_t *block_mask, int BH, int Lq, int Lk, int d, int mode, float scale,
                                   void *O, hipStream_t st);
+// Transposed sparse product out[BH, Lk, d] = A^T X for compressed A (vals + metadata) and X bf16 [BH, Lq, d]:
+// dV = P^T dO and dK = dS^T Q of the backward pass.
+hipError_t launch_spmm_t(const void *vals, const void *meta, const void *X, int BH, int Lq, int Lk, int d, void *out,
+                         hipStream_t st);
 // Metadata word order: library <-> canonical.
 hipError_t launch_meta_reorder(const void *src, void *dst, int BH, int Lq, int W, bool to_canonical,
                                hipStream_t st);
