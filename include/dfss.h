@@ -157,6 +157,25 @@ dfss_status dense_attention_fused_blocked(const void *Q, const void *K, const vo
 dfss_status dfss_spmm_t(const void *vals, const void *meta, const void *X, const dfss_shape *s, void *out,
                         void *stream);
 
+/* Gradients of O = dfss attention(Q, K, V) with respect to Q, K, V, the N:M selection of the forward
+ * pass held fixed (the paper finetunes with this attention but gives no backward kernel; a pruning
+ * decision has no gradient, so gradients flow through the kept entries only).  With P the softmax
+ * weights of the kept entries:
+ *     dV = P^T dO,  dP = dO V^T at the kept positions,  delta_i = dO_i . O_i,
+ *     dS = P .* (dP - delta),  dQ = scale dS K,  dK = scale dS^T Q.
+ * Inputs (device, bfloat16 unless noted): dO [B*H, Lq, d]; Q, K, V, O as in the forward pass; P, meta =
+ * the vals buffer after dfss_sparse_softmax and the metadata of dfss_sddmm_prune of the SAME forward pass
+ * (run the three stage calls to keep them; they compose to dfss_attention).  Outputs: dQ [B*H, Lq, d],
+ * dK, dV [B*H, Lk, d], bfloat16.  ws: device scratch of at least dfss_backward_workspace_bytes(),
+ * 256-byte aligned (holds dS).  A key bias of the forward pass needs no extra argument: masked
+ * entries have weight 0 and so receive and pass on no gradient.  Four kernels: the stage-1 mainloop
+ * with the stored position codes in the place of the selection, the stage-3 SpMM (dQ), and the
+ * transposed sparse product twice (dV, dK). */
+size_t dfss_backward_workspace_bytes(const dfss_shape *s);
+dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K, const void *V, const void *O,
+                                    const void *P, const void *meta, const dfss_shape *s, float scale, void *dQ,
+                                    void *dK, void *dV, void *ws, size_t ws_bytes, void *stream);
+
 /* ---- metadata order ---------------------------------------------------------------- */
 /* Canonical order: uint16 [B*H, Lq, Lk/16], word w of a row = codes of key runs
  * 4w..4w+3, code = p_lo | p_hi << 2 with p the kept key index mod 4 (the 2-bit

@@ -14,8 +14,10 @@ from .binding import (  # noqa: F401
     dense_attention_fused_blocked,
     dense_workspace_bytes,
     dfss_attention,
+    dfss_attention_backward,
     dfss_attention_bias,
     dfss_attention_blocked,
+    dfss_backward_workspace_bytes,
     dfss_meta_bytes,
     dfss_meta_from_canonical,
     dfss_meta_to_canonical,

@@ -23,6 +23,7 @@ EXPORTS = (
     "dense_attention_fused", "dfss_meta_to_canonical", "dfss_meta_from_canonical", "dfss_status_string",
     "dfss_sddmm_prune_bias", "dfss_attention_bias", "dense_attention_bias", "dense_attention_fused_bias",
     "dfss_attention_blocked", "dense_attention_fused_blocked", "dfss_spmm_t",
+    "dfss_backward_workspace_bytes", "dfss_attention_backward",
 )
 
 
@@ -77,7 +78,8 @@ def load_library():
         L = ctypes.CDLL(_LIB_PATH)
         sp = ctypes.POINTER(_CShape)
         vp, sz, f32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float
-        for name in ("dfss_vals_bytes", "dfss_meta_bytes", "dfss_workspace_bytes", "dense_workspace_bytes"):
+        for name in ("dfss_vals_bytes", "dfss_meta_bytes", "dfss_workspace_bytes", "dense_workspace_bytes",
+                     "dfss_backward_workspace_bytes"):
             getattr(L, name).argtypes = [sp]
             getattr(L, name).restype = sz
         L.dfss_sddmm_prune.argtypes = [vp, vp, sp, f32, vp, vp, vp]
@@ -93,13 +95,14 @@ def load_library():
         L.dfss_attention_blocked.argtypes = [vp, vp, vp, vp, vp, sp, f32, vp, vp]
         L.dense_attention_fused_blocked.argtypes = [vp, vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_spmm_t.argtypes = [vp, vp, vp, sp, vp, vp]
+        L.dfss_attention_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, sp, f32, vp, vp, vp, vp, sz, vp]
         L.dfss_meta_to_canonical.argtypes = [vp, sp, vp, vp]
         L.dfss_meta_from_canonical.argtypes = [vp, sp, vp, vp]
         for name in ("dfss_sddmm_prune", "dfss_sparse_softmax", "dfss_spmm", "dfss_attention",
                      "dense_attention", "dense_attention_fused", "dfss_meta_to_canonical", "dfss_meta_from_canonical",
                      "dfss_sddmm_prune_bias", "dfss_attention_bias", "dense_attention_bias",
                      "dense_attention_fused_bias", "dfss_attention_blocked", "dense_attention_fused_blocked",
-                     "dfss_spmm_t"):
+                     "dfss_spmm_t", "dfss_attention_backward"):
             getattr(L, name).restype = ctypes.c_int
         L.dfss_status_string.argtypes = [ctypes.c_int]
         L.dfss_status_string.restype = ctypes.c_char_p
@@ -294,6 +297,27 @@ def dfss_spmm_t(vals, meta, X, s: Shape, out=None):
     st = load_library().dfss_spmm_t(_ptr(vals), _ptr(meta), _ptr(X), ctypes.byref(s.c()), _ptr(out), _stream())
     _check("dfss_spmm_t", st)
     return out
+
+
+def dfss_backward_workspace_bytes(s: Shape) -> int:
+    return int(load_library().dfss_backward_workspace_bytes(ctypes.byref(s.c())))
+
+
+def dfss_attention_backward(dO, Q, K, V, O, P, meta, s: Shape, scale: float, dQ=None, dK=None, dV=None, ws=None):
+    """Gradients through the fixed selection.  P, meta: weights and metadata kept from the forward stages."""
+    if dQ is None:
+        dQ = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=Q.device)
+    if dK is None:
+        dK = torch.empty((s.BH, s.Lk, s.d), dtype=torch.bfloat16, device=Q.device)
+    if dV is None:
+        dV = torch.empty((s.BH, s.Lk, s.d), dtype=torch.bfloat16, device=Q.device)
+    if ws is None:
+        ws = _alloc_bytes(dfss_backward_workspace_bytes(s), Q.device)
+    st = load_library().dfss_attention_backward(_ptr(dO), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(P), _ptr(meta),
+                                                ctypes.byref(s.c()), scale, _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ws),
+                                                ws.numel() * ws.element_size(), _stream())
+    _check("dfss_attention_backward", st)
+    return dQ, dK, dV
 
 
 def dfss_meta_to_canonical(meta, s: Shape, canon=None):

@@ -215,6 +215,32 @@ dfss_status dfss_spmm_t(const void *vals, const void *meta, const void *X, const
     return hip_status(dfss::launch_spmm_t(vals, meta, X, D.BH, D.Lq, D.Lk, D.d, out, (hipStream_t)stream));
 }
 
+dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K, const void *V, const void *O,
+                                    const void *P, const void *meta, const dfss_shape *s, float scale, void *dQ,
+                                    void *dK, void *dV, void *ws, size_t ws_bytes, void *stream) {
+    Dims D;
+    if (!dO || !Q || !K || !V || !O || !P || !meta || !dQ || !dK || !dV || !ws) return DFSS_ERR_NULL;
+    if (dfss_status st = check_shape(s, true, &D)) return st;
+    if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
+    if (misaligned(dO) || misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(P) ||
+        misaligned(meta) || misaligned(dQ) || misaligned(dK) || misaligned(dV))
+        return DFSS_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0) return DFSS_ERR_SHAPE;
+    if (ws_bytes < align_up(dfss_vals_bytes(s))) return DFSS_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    void *dS = ws;   // scale * dS in the compressed layout of P
+    hipError_t e = dfss::launch_masked_sddmm_ds(dO, V, O, P, meta, D.BH, D.Lq, D.Lk, D.d, scale, dS, st);
+    if (e == hipSuccess) e = dfss::launch_spmm(dS, meta, K, D.BH, D.Lq, D.Lk, D.d, dQ, st);      // dQ = dS' K
+    if (e == hipSuccess) e = dfss::launch_spmm_t(P, meta, dO, D.BH, D.Lq, D.Lk, D.d, dV, st);    // dV = P^T dO
+    if (e == hipSuccess) e = dfss::launch_spmm_t(dS, meta, Q, D.BH, D.Lq, D.Lk, D.d, dK, st);    // dK = dS'^T Q
+    return hip_status(e);
+}
+
+size_t dfss_backward_workspace_bytes(const dfss_shape *s) {
+    const size_t v = dfss_vals_bytes(s);
+    return v ? align_up(v) : 0;
+}
+
 dfss_status dfss_meta_to_canonical(const void *meta, const dfss_shape *s, void *canon, void *stream) {
     Dims D;
     if (!meta || !canon) return DFSS_ERR_NULL;

@@ -178,6 +178,148 @@ __global__ __launch_bounds__(NT, 2) void k_spmm_t(const uint32_t *__restrict__ A
         }
 }
 
+// ------------------------------------------------------------------------------------------------
+// dS'[q][c] = scale * P[q][c] * (dO[q] . V[key(q, c)] - delta_q),  delta_q = dO[q] . O[q]
+// for the kept entries c of every row, in the compressed layout (same addresses as the weights P).
+// Mainloop and data layout of the 16-query stage-1 kernel: keys on the MFMA rows, so lane
+// (column li, row group kb) of a 128-key block holds, per half, the 16 consecutive keys
+// 32 kb + 16 half .. +15 of query li: four runs of four, of which the position codes name the two
+// kept ones.
+// ------------------------------------------------------------------------------------------------
+template <int D, int NQ>
+__global__ __launch_bounds__(NT, 2) void k_masked_sddmm_ds(const __bf16 *__restrict__ dO, const __bf16 *__restrict__ V,
+                                                           const __bf16 *__restrict__ O,
+                                                           const uint32_t *__restrict__ P,
+                                                           const uint32_t *__restrict__ meta, int Lq, int Lk,
+                                                           float scale, int ksplit, int blocks_per_wg,
+                                                           uint32_t *__restrict__ dS) {
+    constexpr int CPR = D / 8;           // 16-byte chunks per row
+    constexpr int TILE = KB * CPR;       // chunks per V block
+    constexpr int LPT = TILE / NT;       // asynchronous copies per thread per block
+    constexpr int STEPS = D / 32;        // MFMA k-steps
+    constexpr int TQ = 64 * NQ;          // queries per workgroup
+    __shared__ u32x4 Vs[2][TILE];
+
+    const int tid = threadIdx.x;
+    const int w = tid >> 6, l = tid & 63, li = l & 15, kb = l >> 4;
+
+    const unsigned qtiles = Lq / TQ;
+    const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int ks_id = item % ksplit;
+    const int qt = (item / ksplit) % qtiles;
+    const int bh = item / (ksplit * qtiles);
+    const int jb0 = ks_id * blocks_per_wg;
+    const int q0 = qt * TQ + w * 16 * NQ;
+
+    // LDS position p (16-byte units) = slot * CPR + (c ^ (slot & 7)) holds chunk c of the key stored in row
+    // slot `slot`; slot 16 t' + i (MFMA tile t', row i) holds key 32 (i/4) + 4 t' + i%4 ... in the order that
+    // gives a lane 16 consecutive keys per half
+    const __bf16 *Vh = V + (size_t)bh * Lk * D;
+    int src_off[LPT];
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+        const int p = i * NT + tid;
+        const int slot = p / CPR, c = (p % CPR) ^ (slot & 7);
+        const int key = (slot & 3) | (((slot >> 4) & 7) << 2) | (((slot >> 2) & 3) << 5);
+        src_off[i] = key * D + c * 8;
+    }
+    const uint32_t lds_v = lds_address(&Vs[0][w * 64]);
+    auto issue_block = [&](int jb, int buf) {
+        const __bf16 *src = Vh + (size_t)jb * KB * D;
+#pragma unroll
+        for (int i = 0; i < LPT; ++i) async_copy16(src, 2u * src_off[i], lds_v + 16u * (buf * TILE + i * NT));
+    };
+
+    issue_block(jb0, 0);
+
+    // dO operand: lane (column li, chunk kb) of MFMA step s holds dO[q][32 s + 8 kb .. +7]; the same
+    // elements of O give this lane's share of delta_q
+    bf16x8 bq[NQ][STEPS];
+    float delta[NQ];
+#pragma unroll
+    for (int qs = 0; qs < NQ; ++qs) {
+        float part = 0.f;
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            const size_t off = ((size_t)bh * Lq + q0 + 16 * qs + li) * D + 32 * s + 8 * kb;
+            const u32x4 g = *reinterpret_cast<const u32x4 *>(dO + off);
+            const u32x4 o = *reinterpret_cast<const u32x4 *>(O + off);
+            bq[qs][s] = __builtin_bit_cast(bf16x8, g);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                part += bf16_lo_to_f32(g[e]) * bf16_lo_to_f32(o[e]) + bf16_hi_to_f32(g[e]) * bf16_hi_to_f32(o[e]);
+        }
+        part += __shfl_xor(part, 16, 64);
+        part += __shfl_xor(part, 32, 64);
+        delta[qs] = part;
+    }
+
+    const int rb0 = q0 >> 4;                 // first 16-row block of this wave
+    const int meta_slot = ((kb & 1) << 1) | (kb >> 1);
+
+    for (int it = 0; it < blocks_per_wg; ++it) {
+        const int jb = jb0 + it;
+        const int buf = it & 1;
+        // this block's copy has landed; the 2 NQ stores of the previous iteration may stay in flight
+        if (it == 0) wait_async_copies();
+        else wait_async_copies_keep<2 * NQ>();
+        __syncthreads();
+        if (it + 1 < blocks_per_wg) issue_block(jb + 1, buf ^ 1);
+
+        uint32_t mword[NQ];
+#pragma unroll
+        for (int qs = 0; qs < NQ; ++qs)
+            mword[qs] = meta[((((size_t)bh * (Lq / 16) + rb0 + qs) * (Lk / KB) + jb) * 16 + li) * 4 + meta_slot];
+
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int kbase = KB * jb + 32 * kb + 16 * half;
+            u32x4 pw[NQ];   // the weights of this lane's 8 kept entries
+#pragma unroll
+            for (int qs = 0; qs < NQ; ++qs) {
+                const size_t row = (size_t)bh * Lq + q0 + 16 * qs + li;
+                pw[qs] = *reinterpret_cast<const u32x4 *>(P + (row * (size_t)(Lk / 2) + kbase / 2) / 2);
+            }
+            f32x4 acc[NQ][4];
+#pragma unroll
+            for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) acc[qs][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                bf16x8 av[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int slot = 16 * (4 * half + t) + li;
+                    av[t] = __builtin_bit_cast(bf16x8, Vs[buf][slot * CPR + ((4 * s + kb) ^ (li & 7))]);
+                }
+#pragma unroll
+                for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) acc[qs][t] = mfma16(av[t], bq[qs][s], acc[qs][t]);
+            }
+            // acc[qs][t][r] = dO[q] . V[key], key = 128 jb + 32 kb + 16 half + 4 t + r
+#pragma unroll
+            for (int qs = 0; qs < NQ; ++qs) {
+                const size_t row = (size_t)bh * Lq + q0 + 16 * qs + li;
+                u32x4 o;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const uint32_t code = (mword[qs] >> (16 * half + 4 * t)) & 0xFu;
+                    const uint32_t plo = code & 3u, phi = code >> 2;     // plo in {0,1,2}, phi in {1,2,3}
+                    const f32x4 a = acc[qs][t];
+                    const float dp_lo = plo == 0 ? a[0] : (plo == 1 ? a[1] : a[2]);
+                    const float dp_hi = phi == 3 ? a[3] : (phi == 2 ? a[2] : a[1]);
+                    const float ds_lo = bf16_lo_to_f32(pw[qs][t]) * (dp_lo - delta[qs]) * scale;
+                    const float ds_hi = bf16_hi_to_f32(pw[qs][t]) * (dp_hi - delta[qs]) * scale;
+                    o[t] = pack_bf16x2(ds_lo, ds_hi);
+                }
+                *reinterpret_cast<u32x4 *>(dS + (row * (size_t)(Lk / 2) + kbase / 2) / 2) = o;
+            }
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_spmm_t(const void *vals, const void *meta, const void *X, int BH, int Lq, int Lk, int d, void *out,
@@ -190,6 +332,40 @@ hipError_t launch_spmm_t(const void *vals, const void *meta, const void *X, int 
         hipLaunchKernelGGL((k_spmm_t<128>), dim3(grid), dim3(NT), 0, st, (const uint32_t *)vals,
                            (const uint32_t *)meta, (const __bf16 *)X, Lq, Lk, (uint16_t *)out);
     return hipGetLastError();
+}
+
+}  // namespace dfss
+
+namespace dfss {
+
+namespace {
+template <int NQ>
+hipError_t launch_ds_nq(const void *dO, const void *V, const void *O, const void *P, const void *meta, int BH, int Lq,
+                        int Lk, int d, float scale, void *dS, hipStream_t st) {
+    const int qtiles = Lq / (64 * NQ);
+    const int kblocks = Lk / KB;
+    // split the key range until the grid has a few workgroups per compute unit
+    int ksplit = 1;
+    while ((long)BH * qtiles * ksplit < 1024 && kblocks % (ksplit * 2) == 0) ksplit *= 2;
+    if ((long)BH * qtiles * ksplit < 1024 && kblocks % 3 == 0 && ksplit == 1) ksplit = 3;
+    const int per_wg = kblocks / ksplit;
+    const unsigned grid = (unsigned)((long)BH * qtiles * ksplit);
+    if (d == 64)
+        hipLaunchKernelGGL((k_masked_sddmm_ds<64, NQ>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)dO,
+                           (const __bf16 *)V, (const __bf16 *)O, (const uint32_t *)P, (const uint32_t *)meta, Lq, Lk,
+                           scale, ksplit, per_wg, (uint32_t *)dS);
+    else
+        hipLaunchKernelGGL((k_masked_sddmm_ds<128, NQ>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)dO,
+                           (const __bf16 *)V, (const __bf16 *)O, (const uint32_t *)P, (const uint32_t *)meta, Lq, Lk,
+                           scale, ksplit, per_wg, (uint32_t *)dS);
+    return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_masked_sddmm_ds(const void *dO, const void *V, const void *O, const void *P, const void *meta,
+                                  int BH, int Lq, int Lk, int d, float scale, void *dS, hipStream_t st) {
+    if (Lq % 128 == 0) return launch_ds_nq<2>(dO, V, O, P, meta, BH, Lq, Lk, d, scale, dS, st);
+    return launch_ds_nq<1>(dO, V, O, P, meta, BH, Lq, Lk, d, scale, dS, st);
 }
 
 }  // namespace dfss

@@ -31,6 +31,9 @@ hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, c
 // dV = P^T dO and dK = dS^T Q of the backward pass.
 hipError_t launch_spmm_t(const void *vals, const void *meta, const void *X, int BH, int Lq, int Lk, int d, void *out,
                          hipStream_t st);
+// dS' = scale * P .* (dO V^T - delta) at the kept positions (delta_q = dO_q . O_q), compressed like P.
+hipError_t launch_masked_sddmm_ds(const void *dO, const void *V, const void *O, const void *P, const void *meta,
+                                  int BH, int Lq, int Lk, int d, float scale, void *dS, hipStream_t st);
 // Metadata word order: library <-> canonical.
 hipError_t launch_meta_reorder(const void *src, void *dst, int BH, int Lq, int W, bool to_canonical,
                                hipStream_t st);

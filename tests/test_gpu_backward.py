@@ -66,3 +66,63 @@ def test_transposed_spmm(BH, Lq, Lk, d, N, M):
         ref = Pd.T @ Xn[h].astype(np.float64)
         # bf16 output rounding (2^-9 relative) + fp32 accumulation of <= Lq terms
         assert np.max(np.abs(out[h] - ref)) <= 2.0 ** -8 * np.max(np.abs(ref)) + 1e-4
+
+
+def _oracle_backward_case(BH, Lq, Lk, d, N, M, seed, scale):
+    Q, K, V = synth.gaussian_qkv(BH, Lq, Lk, d, 1.0, seed=seed)
+    g = torch.Generator().manual_seed(seed + 1)
+    dO = torch.randn(BH, Lq, d, generator=g).to(torch.bfloat16)
+    Qn, Kn, Vn, dOn = (synth.to_numpy_f32(t) for t in (Q, K, V, dO))
+    kidx, P, meta_c = _oracle_forward(Qn, Kn, N, M, scale)
+    O = np.stack([oracle.round_bf16(oracle.spmm(P[h], kidx[h], Vn[h])) for h in range(BH)])
+    return (Q, K, V, dO), (Qn, Kn, Vn, dOn), kidx, P, meta_c, O
+
+
+@pytest.mark.parametrize("BH,Lq,Lk,d,N,M", [
+    (2, 128, 256, 64, 2, 4),       # 32 queries per wave in the dS kernel
+    (2, 192, 384, 64, 1, 2),       # 16 queries per wave, key range split three ways
+    (2, 128, 128, 128, 2, 4),      # d = 128
+])
+def test_backward_against_oracle_through_the_same_selection(BH, Lq, Lk, d, N, M):
+    scale = 1.0 / math.sqrt(d)
+    (Q, K, V, dO), (Qn, Kn, Vn, dOn), kidx, P, meta_c, O = _oracle_backward_case(BH, Lq, Lk, d, N, M, 9400 + Lq + d, scale)
+    s = Shape(1, BH, Lq, Lk, d, N, M)
+    meta = dfss.dfss_meta_from_canonical(_dev(torch.from_numpy(meta_c.view(np.int16))), s)
+    dQ, dK, dV = dfss.dfss_attention_backward(_dev(dO), _dev(Q), _dev(K), _dev(V), _dev(_bf16(O)), _dev(_bf16(P)),
+                                              meta, s, scale)
+    torch.cuda.synchronize()
+    dQ, dK, dV = _np(dQ), _np(dK), _np(dV)
+    for h in range(BH):
+        rQ, rK, rV = oracle.attention_backward(Qn[h], Kn[h], Vn[h], dOn[h], P[h], kidx[h], scale)
+        for name, got, ref in (("dQ", dQ[h], rQ), ("dK", dK[h], rK), ("dV", dV[h], rV)):
+            # operands (P, dS, O) and results are bfloat16: 2^-9 relative each, summed over a row or column
+            tol = 2.0 ** -6 * np.max(np.abs(ref)) + 1e-4
+            err = np.max(np.abs(got - ref))
+            assert err <= tol, (name, h, err, tol)
+
+
+def test_forward_stages_then_backward_on_exact_scores():
+    """GPU forward (three stage calls, integer Q and K: the selection equals the oracle's exactly)
+    followed by the GPU backward, against the oracle end to end."""
+    BH, L, d = 2, 256, 64
+    Q, K, V = synth.integer_qkv(BH, L, L, d, seed=9500)
+    Q, K = (Q.float() * 0.25).to(torch.bfloat16), (K.float() * 0.25).to(torch.bfloat16)   # keeps the softmax soft
+    g = torch.Generator().manual_seed(9501)
+    dO = torch.randn(BH, L, d, generator=g).to(torch.bfloat16)
+    s = Shape(1, BH, L, L, d, 2, 4)
+    Qd, Kd, Vd, dOd = _dev(Q), _dev(K), _dev(V), _dev(dO)
+    vals, meta = dfss.dfss_sddmm_prune(Qd, Kd, s, 0.125)
+    dfss.dfss_sparse_softmax(vals, s)
+    O = dfss.dfss_spmm(vals, meta, Vd, s)
+    dQ, dK, dV = dfss.dfss_attention_backward(dOd, Qd, Kd, Vd, O, vals, meta, s, 0.125)
+    torch.cuda.synchronize()
+    Qn, Kn, Vn, dOn = (synth.to_numpy_f32(t) for t in (Q, K, V, dO))
+    kidx, P, meta_c = _oracle_forward(Qn, Kn, 2, 4, 0.125)
+    canon = dfss.dfss_meta_to_canonical(meta, s)
+    torch.cuda.synchronize()
+    assert np.array_equal(canon.cpu().numpy().view(np.uint16), meta_c)       # same selection on both sides
+    for h in range(BH):
+        rQ, rK, rV = oracle.attention_backward(Qn[h], Kn[h], Vn[h], dOn[h], P[h], kidx[h], 0.125)
+        for name, got, ref in (("dQ", _np(dQ[h]), rQ), ("dK", _np(dK[h]), rK), ("dV", _np(dV[h]), rV)):
+            tol = 2.0 ** -6 * np.max(np.abs(ref)) + 1e-4
+            assert np.max(np.abs(got - ref)) <= tol, (name, h)
