@@ -53,6 +53,9 @@ def parse_args():
     ap.add_argument("--block-pattern", action="store_true",
                     help="run the block-masked entry points with a seeded window + global + random pattern of "
                          "64 x 64 blocks (fused kernels only; FLOPs are counted on the kept blocks)")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time dfss_attention_backward (gradients through the fixed selection) on the "
+                         "results of the three forward stages; reported under extra")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 64 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
@@ -287,6 +290,31 @@ def main():
             "sddmm_prune_frac_of_mfma_peak": round(2.0 * BH * L * L * d / (k1 * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
         },
     }
+
+    if args.backward and block_mask is None:
+        b = sets[0]
+        n_vals = dfss.dfss_vals_bytes(s)
+        vals = torch.empty((BH, L, s.Lc), dtype=torch.bfloat16, device=dev)
+        meta = torch.empty((BH * L * (L // 16),), dtype=torch.int16, device=dev)
+        if bias is None:
+            dfss.dfss_sddmm_prune(b["Q"], b["K"], s, w.scale, vals=vals, meta=meta)
+        else:
+            dfss.dfss_sddmm_prune_bias(b["Q"], b["K"], bias, s, w.scale, vals=vals, meta=meta)
+        dfss.dfss_sparse_softmax(vals, s)
+        O_fwd = dfss.dfss_spmm(vals, meta, b["V"], s)
+        dO = torch.randn(BH, L, d, device=dev).to(torch.bfloat16)
+        grads = [torch.empty((BH, L, d), dtype=torch.bfloat16, device=dev) for _ in range(3)]
+        ws_b = torch.empty(dfss.dfss_backward_workspace_bytes(s), dtype=torch.uint8, device=dev)
+
+        def step_backward(i):
+            dfss.dfss_attention_backward(dO, b["Q"], b["K"], b["V"], O_fwd, vals, meta, s, w.scale,
+                                         dQ=grads[0], dK=grads[1], dV=grads[2], ws=ws_b)
+
+        t_bwd = timed(step_backward, K, W, use_graph)
+        flops_bwd = 5.0 * BH * L * L * d      # dP: 2 L^2 d (formed densely), dQ, dK, dV: L^2 d each on kept entries
+        out["extra"]["backward_ms_per_step"] = round(t_bwd / K * 1e3, 5)
+        out["extra"]["backward_tflops"] = round(flops_bwd / (t_bwd / K) / 1e12, 2)
+        out["extra"]["backward_over_staged_forward"] = round((t_bwd / K * 1e3) / ms_staged, 3)
 
     if args.block_pattern:
         # only the fused kernels take a block pattern: the three-stage figures would be those of a

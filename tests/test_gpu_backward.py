@@ -95,8 +95,8 @@ def test_backward_against_oracle_through_the_same_selection(BH, Lq, Lk, d, N, M)
     for h in range(BH):
         rQ, rK, rV = oracle.attention_backward(Qn[h], Kn[h], Vn[h], dOn[h], P[h], kidx[h], scale)
         for name, got, ref in (("dQ", dQ[h], rQ), ("dK", dK[h], rK), ("dV", dV[h], rV)):
-            # operands (P, dS, O) and results are bfloat16: 2^-9 relative each, summed over a row or column
-            tol = 2.0 ** -6 * np.max(np.abs(ref)) + 1e-4
+            # operands (P, dS, O) and results are bfloat16 (2^-9 relative each); observed <= 0.0053 of the largest entry
+            tol = 2.0 ** -7 * np.max(np.abs(ref)) + 1e-4
             err = np.max(np.abs(got - ref))
             assert err <= tol, (name, h, err, tol)
 
@@ -124,5 +124,5 @@ def test_forward_stages_then_backward_on_exact_scores():
     for h in range(BH):
         rQ, rK, rV = oracle.attention_backward(Qn[h], Kn[h], Vn[h], dOn[h], P[h], kidx[h], 0.125)
         for name, got, ref in (("dQ", _np(dQ[h]), rQ), ("dK", _np(dK[h]), rK), ("dV", _np(dV[h]), rV)):
-            tol = 2.0 ** -6 * np.max(np.abs(ref)) + 1e-4
+            tol = 2.0 ** -7 * np.max(np.abs(ref)) + 1e-4
             assert np.max(np.abs(got - ref)) <= tol, (name, h)
