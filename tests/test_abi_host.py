@@ -36,6 +36,7 @@ def test_sizes_follow_the_compressed_footprint():
     assert dfss.dfss_meta_bytes(s) == dense // 16          # 1/16 of the dense bits (Sec. 2.3)
     assert dfss.dense_workspace_bytes(s) >= dense
     assert dfss.dfss_workspace_bytes(s) >= dense // 2 + dense // 16
+    assert dfss.dfss_backward_workspace_bytes(s) >= dense // 2      # dS in the layout of the kept values
     s12 = Shape(16, 12, 512, 512, 64, 1, 2)
     assert dfss.dfss_vals_bytes(s12) == 192 * 512 * 512
     assert dfss.dfss_meta_bytes(s12) == 192 * 512 * 512 // 8
@@ -88,6 +89,11 @@ def test_errors_are_reported_before_any_launch():
     assert lib.dfss_attention_blocked(aligned, aligned, aligned, None, None, ctypes.byref(ok), 0.125, aligned, None) == E_NULL
     assert lib.dfss_attention_blocked(aligned, aligned, aligned, None, aligned, ctypes.byref(bad), 0.125, aligned, None) == E_UNSUP
     assert lib.dense_attention_fused_blocked(aligned, aligned, aligned, odd, aligned, ctypes.byref(ok), 0.125, aligned, None) == E_SHAPE
+    assert lib.dfss_spmm_t(aligned, aligned, None, ctypes.byref(ok), aligned, None) == E_NULL
+    assert lib.dfss_attention_backward(aligned, aligned, aligned, aligned, aligned, aligned, aligned, ctypes.byref(ok),
+                                       0.125, aligned, aligned, aligned, ws, 16, None) == E_WS
+    assert lib.dfss_attention_backward(aligned, aligned, aligned, aligned, aligned, aligned, aligned, ctypes.byref(ok),
+                                       0.0, aligned, aligned, aligned, ws, 1 << 30, None) == E_UNSUP
     assert lib.dfss_status_string(0) == b"ok"
     assert lib.dfss_status_string(E_WS) == b"workspace too small"
 
