@@ -47,7 +47,7 @@ __global__ __launch_bounds__(NT, 2) void k_spmm_t(const uint32_t *__restrict__ A
     constexpr int XT = QB * CPR;        // chunks per X tile
     constexpr int LPT = XT / NT;        // asynchronous copies per thread per tile
     constexpr int DS = D / 16;          // 16-column output tiles
-    constexpr int AROW = 2 * KB + 48;   // bytes per row of the expanded A tile (padding spreads the rows over the banks)
+    constexpr int AROW = 2 * KB + 16;   // bytes per row of the expanded A tile (padded; three workgroups fit a CU at D = 64)
     __shared__ u32x4 Xs[2][XT];
     __shared__ __attribute__((aligned(16))) char Ad[2][QB * AROW];
 
@@ -125,18 +125,18 @@ __global__ __launch_bounds__(NT, 2) void k_spmm_t(const uint32_t *__restrict__ A
     const int tr_row = li >> 2;
     const int tr_sub = (li >> 1) & 1, tr_byte = 8 * (li & 1), tr_xor = tr_row << 1;
 
-    issue_x(0, 0);
-    ARaw raw = load_a(0);
-
-    for (int qb = 0; qb < nq; ++qb) {
+    // One step = 64 queries.  The compressed operand is loaded two steps ahead into registers (r0 for
+    // even steps, r1 for odd ones: fixed names, so no register is copied while its load is in flight),
+    // the X tile one step ahead into the other LDS buffer.
+    auto step = [&](int qb, ARaw &r) {
         const int buf = qb & 1;
-        expand_a(raw, buf);
-        wait_async_copies();   // the X tile of this step (and the A values just consumed) have arrived
+        expand_a(r, buf);
+        // X(qb) must have landed; the three loads of A(qb + 1), issued after its copy, may stay in flight
+        if (qb >= 1 && qb + 1 < nq) wait_async_copies_keep<3>();
+        else wait_async_copies();
         __syncthreads();       // both tiles are complete; the other buffers are free
-        if (qb + 1 < nq) {
-            issue_x(qb + 1, buf ^ 1);
-            raw = load_a(qb + 1);
-        }
+        if (qb + 1 < nq) issue_x(qb + 1, buf ^ 1);
+        if (qb + 2 < nq) r = load_a(qb + 2);
         const char *abase = &Ad[buf][0];
         const char *xbase = reinterpret_cast<const char *>(&Xs[buf][0]);
         auto tr_a = [&](int q0, int col0) {
@@ -164,6 +164,14 @@ __global__ __launch_bounds__(NT, 2) void k_spmm_t(const uint32_t *__restrict__ A
                 for (int mt = 0; mt < 2; ++mt) acc[mt][nt] = mfma16(a[mt], b, acc[mt][nt]);
             }
         }
+    };
+
+    issue_x(0, 0);
+    ARaw r0 = load_a(0), r1 = r0;
+    if (nq > 1) r1 = load_a(1);
+    for (int qb = 0; qb < nq; qb += 2) {
+        step(qb, r0);
+        if (qb + 1 < nq) step(qb + 1, r1);
     }
 
     // acc[mt][nt][r] = out[key 128 jblk + 32 w + 16 mt + 4 g + r][16 nt + li]
