@@ -27,11 +27,6 @@ namespace {
 constexpr int NT = 256;   // 4 waves
 constexpr int KB = 128;   // keys per block
 
-__device__ __forceinline__ unsigned xcd_contiguous(unsigned id, unsigned total) {
-    const unsigned per = total / 8;
-    return id < per * 8 ? (id % 8) * per + id / 8 : id;
-}
-
 // ------------------------------------------------------------------------------------------------
 // out[bh][key][c] = sum_q A[bh][q][key] X[bh][q][c]
 // A: kept values bf16 [BH, Lq, Lk/2] + metadata in the library's order; X: bf16 [BH, Lq, D].

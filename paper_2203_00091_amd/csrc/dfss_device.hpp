@@ -103,6 +103,61 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// N:M selection on the fp32 accumulators (arXiv 2203.00091, Sec. 2.3, App. A.1.1).  The comparisons of
+// a run of four scores are taken as 64-bit lane masks (one bit per lane of the wave) so that the
+// boolean logic runs on the scalar unit, off the vector ALU that the MFMA epilogue is short of; the
+// vector unit only does the compares, min/max and the final selects.
+typedef uint64_t lanemask;
+__device__ __forceinline__ lanemask gt(float a, float b) { return __builtin_amdgcn_fcmpf(a, b, 2 /* ordered > */); }
+__device__ __forceinline__ bool lane_bit(lanemask m) { return __builtin_amdgcn_inverse_ballot_w64(m); }
+
+// Two largest of four scores, equal scores: the lower index wins (the order "larger value
+// first, then lower index" is total, so the result is the one of the rank rule
+// rank(t) = #{u: s_u > s_t} + #{u < t: s_u == s_t}, keep iff rank < 2).
+// Evaluated as a tournament: A = {s0, s1}, B = {s2, s3}.  Both survivors come from A iff the
+// weaker of A still outranks the stronger of B (ties favour A, the lower indices); both come
+// from B iff the weaker of B strictly beats the stronger of A; otherwise each pair sends its
+// stronger element.  Four comparisons land in lane masks, four min/max and eight selects on
+// the vector unit, almost nothing on the scalar unit.
+// Returns the kept values in key order and the position code (p_lo | p_hi << 2) << SHIFT.
+__device__ __forceinline__ void select_2of4(float s0, float s1, float s2, float s3, const int SHIFT, float &lo,
+                                            float &hi, uint32_t &code) {
+    const lanemask c01 = gt(s1, s0), c23 = gt(s3, s2);      // stronger element of each pair is the later one
+    const float amax = fmaxf(s0, s1), amin = fminf(s0, s1);
+    const float bmax = fmaxf(s2, s3), bmin = fminf(s2, s3);
+    const lanemask not_a = gt(bmax, amin);                   // B's best strictly beats A's worst
+    const lanemask both_b = gt(bmin, amax);                  // B's worst strictly beats A's best
+    const bool na = lane_bit(not_a), bb = lane_bit(both_b);
+    const float lo_m = bb ? s2 : amax, hi_m = na ? bmax : s1;
+    lo = na ? lo_m : s0;
+    hi = bb ? s3 : hi_m;
+    // p_lo: 0 if both from A, 2 if both from B, else index of A's stronger element
+    // p_hi: 1 if both from A, 3 if both from B, else index of B's stronger element
+    const bool lo1 = lane_bit(not_a & c01), hi3 = lane_bit(both_b | c23);
+    const uint32_t plo_m = lo1 ? (1u << SHIFT) : 0u;
+    const uint32_t plo = bb ? (2u << SHIFT) : plo_m;
+    const uint32_t phi_m = hi3 ? (12u << SHIFT) : (8u << SHIFT);
+    const uint32_t phi = na ? phi_m : (4u << SHIFT);
+    code = plo | phi;
+}
+
+// Keep the larger of each aligned pair; equal scores: the lower index wins.
+__device__ __forceinline__ void select_1of2(float s0, float s1, float s2, float s3, const int SHIFT, float &lo,
+                                            float &hi, uint32_t &code) {
+    const bool c01 = lane_bit(gt(s1, s0)), c23 = lane_bit(gt(s3, s2));
+    lo = c01 ? s1 : s0;
+    hi = c23 ? s3 : s2;
+    code = (c01 ? (1u << SHIFT) : 0u) | (c23 ? (12u << SHIFT) : (8u << SHIFT));
+}
+
+// Workgroups are handed to the 8 XCDs round-robin by linear id; each XCD has its own L2.
+// Give every XCD one contiguous range of work items so that the workgroups sharing one
+// head's K meet in one L2.
+__device__ __forceinline__ unsigned xcd_contiguous(unsigned id, unsigned total) {
+    const unsigned per = total / 8;
+    return id < per * 8 ? (id % 8) * per + id / 8 : id;
+}
+
 template <typename T>
 __device__ __forceinline__ T wave_xor_max(T v, int width) {
     for (int o = width >> 1; o > 0; o >>= 1) {
