@@ -37,9 +37,6 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 enum { MODE_2TO4 = 0, MODE_1TO2 = 1, MODE_DENSE = 2 };
 
-typedef __attribute__((address_space(3))) void lds_void_t;
-typedef __attribute__((address_space(1))) const void global_cvoid_t;
-
 // MASKED: the call carries a key bias and/or a block mask (either pointer may be null).
 //   key_bias   additive per-key term (fp32, [B][Lk], shared by the H heads of a batch element; -inf masks
 //              a key), joined to the scaled score before the selection: as the initial value of the

@@ -30,9 +30,6 @@ enum { MODE_2TO4 = 0, MODE_1TO2 = 1, MODE_DENSE = 2 };
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
-typedef __attribute__((address_space(3))) void lds_void_t;
-typedef __attribute__((address_space(1))) const void global_cvoid_t;
-
 template <int D, int MODE, int NW, bool PRESCALE>
 __global__ __launch_bounds__(64 * NW, 2) void k_fused32(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
                                                         const __bf16 *__restrict__ V, int Lq, int Lk, float scale,

@@ -33,9 +33,6 @@ constexpr int KB = 128;   // keys per block
 
 enum { MODE_2TO4 = 0, MODE_1TO2 = 1, MODE_DENSE = 2 };
 
-typedef __attribute__((address_space(3))) void lds_void_t;
-typedef __attribute__((address_space(1))) const void global_cvoid_t;
-
 // PRESCALE: the scale is a power of two and is applied (exactly) to the Q operand once,
 // instead of to every accumulator.
 // BIAS: an additive per-key term (fp32 [B][Lk], shared by the H heads of a batch element; -inf masks a

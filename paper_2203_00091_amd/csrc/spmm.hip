@@ -26,9 +26,6 @@ namespace {
 constexpr int NT = 256;   // 4 waves
 constexpr int KB = 128;   // keys per block
 
-typedef __attribute__((address_space(3))) void lds_void_t;
-typedef __attribute__((address_space(1))) const void global_cvoid_t;
-
 template <int D, bool SPARSE, int RB>
 __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, const uint32_t *__restrict__ meta,
                                               const __bf16 *__restrict__ V, int Lq, int Lk,
