@@ -53,6 +53,10 @@ def _load():
         L.oracle_encode_meta.restype = c_int
         L.oracle_decode_meta.argtypes = [_u16p, c_int, c_int, _i32p]
         L.oracle_decode_meta.restype = c_int
+        L.oracle_encode_meta_f32.argtypes = [_i32p, c_int, c_int, _u16p]
+        L.oracle_encode_meta_f32.restype = c_int
+        L.oracle_decode_meta_f32.argtypes = [_u16p, c_int, c_int, _i32p]
+        L.oracle_decode_meta_f32.restype = c_int
         L.oracle_softmax_kept.argtypes = [_f32p, c_int, c_int, _f32p]
         L.oracle_softmax_kept.restype = None
         L.oracle_spmm.argtypes = [_f32p, _i32p, _f32p, c_int, c_int, c_int, _f32p]
@@ -153,6 +157,27 @@ def decode_meta(meta, Lk):
     rc = _load().oracle_decode_meta(meta, Lq, Lk, kidx)
     if rc != 0:
         raise ValueError(f"oracle_decode_meta failed rc={rc}")
+    return kidx
+
+
+def encode_meta_f32(kidx, Lk):
+    """4-byte mode (1:2 on float data): one kept key per aligned pair -> uint16 words [Lq, Lk/8]."""
+    kidx = np.ascontiguousarray(kidx, dtype=np.int32)
+    Lq = kidx.shape[0]
+    meta = np.empty((Lq, Lk // 8), np.uint16)
+    rc = _load().oracle_encode_meta_f32(kidx, Lq, Lk, meta)
+    if rc != 0:
+        raise ValueError(f"oracle_encode_meta_f32 failed rc={rc}")
+    return meta
+
+
+def decode_meta_f32(meta, Lk):
+    meta = np.ascontiguousarray(meta, dtype=np.uint16)
+    Lq = meta.shape[0]
+    kidx = np.empty((Lq, Lk // 2), np.int32)
+    rc = _load().oracle_decode_meta_f32(meta, Lq, Lk, kidx)
+    if rc != 0:
+        raise ValueError(f"oracle_decode_meta_f32 failed rc={rc}")
     return kidx
 
 

@@ -194,6 +194,61 @@ int oracle_decode_meta(const uint16_t *meta, int Lq, int Lk, int32_t *kidx)
 }
 
 /* ------------------------------------------------------------------ */
+/* Metadata of the 4-byte mode (1:2 on float data, Sec. 2.3; App.      */
+/* A.1.1).  A code still describes a run of four 2-byte slots, two of  */
+/* which survive; a 4-byte element fills two consecutive slots, so a   */
+/* run is one aligned pair of keys and element e of the pair covers    */
+/* slots 2e and 2e+1.  code = p_lo | (p_hi << 2) over slot positions,  */
+/* exactly as in the 2-byte mode.  Word w of a row holds the codes of  */
+/* pairs 4w..4w+3, pair 4w+k at bits [4k, 4k+3] (App. A.1.2).          */
+/* kidx is [Lq][Lk/2] (one kept key per pair), meta [Lq][Lk/8] uint16. */
+/* Lk % 8 == 0 required.                                               */
+/* ------------------------------------------------------------------ */
+int oracle_encode_meta_f32(const int32_t *kidx, int Lq, int Lk, uint16_t *meta)
+{
+    if (Lk % 8 != 0) return -1;
+    const int Lc = Lk / 2;
+    const int W = Lk / 8;
+    for (int i = 0; i < Lq; ++i) {
+        for (int w = 0; w < W; ++w) {
+            unsigned word = 0;
+            for (int k = 0; k < 4; ++k) {
+                const int pair = 4 * w + k;         /* keys 2pair, 2pair+1 */
+                const int j = kidx[(size_t)i * Lc + pair];
+                if (j / 2 != pair) return -2;
+                const unsigned e = (unsigned)(j % 2);
+                const unsigned slot_lo = 2u * e, slot_hi = 2u * e + 1u;
+                const unsigned code = slot_lo | (slot_hi << 2);
+                word |= code << (4 * k);
+            }
+            meta[(size_t)i * W + w] = (uint16_t)word;
+        }
+    }
+    return 0;
+}
+
+/* Inverse; returns -2 if a code does not name two consecutive slots of one element. */
+int oracle_decode_meta_f32(const uint16_t *meta, int Lq, int Lk, int32_t *kidx)
+{
+    if (Lk % 8 != 0) return -1;
+    const int Lc = Lk / 2;
+    const int W = Lk / 8;
+    for (int i = 0; i < Lq; ++i) {
+        for (int w = 0; w < W; ++w) {
+            const unsigned word = meta[(size_t)i * W + w];
+            for (int k = 0; k < 4; ++k) {
+                const unsigned code = (word >> (4 * k)) & 0xFu;
+                const unsigned slot_lo = code & 3u, slot_hi = (code >> 2) & 3u;
+                if ((slot_lo & 1u) != 0u || slot_hi != slot_lo + 1u) return -2;
+                const int pair = 4 * w + k;
+                kidx[(size_t)i * Lc + pair] = 2 * pair + (int)(slot_lo >> 1);
+            }
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
 /* Stage 2: softmax over the kept entries of each row                  */
 /* (Sec. 3.1; max-subtracted form of App. A.1.3).                      */
 /* x, P are [Lq][Lc].  The sum is carried in double so the oracle's    */
