@@ -12,10 +12,11 @@
  *   stage 3  O = A_sparse V with the compressed weights (Sec. 3.1).
  *
  * Supported: bfloat16 inputs, N:M = 2:4 (the paper's bfloat16 mode, Sec. 2.3) and
- * 1:2 on the same 2-byte data; d in {64, 128}; Lq a multiple of 64, Lk a multiple
+ * 1:2 on the same 2-byte data; float inputs with 1:2 (the paper's 4-byte mode, see
+ * "the 4-byte mode" below); d in {64, 128}; Lq a multiple of 64, Lk a multiple
  * of 128.  Selection rule: larger signed score wins, equal scores -> lower key
  * index wins; comparisons are made on the fp32 value scale*dot, which is then
- * rounded to bfloat16 (nearest-even) for storage.
+ * rounded to bfloat16 (nearest-even) for storage (kept as it is in the 4-byte mode).
  *
  * Conventions for every call
  *   - All data pointers are DEVICE pointers to contiguous row-major arrays owned by
@@ -47,7 +48,7 @@ typedef enum {
     DFSS_ERR_HIP = 5          /* the HIP runtime refused a launch                        */
 } dfss_status;
 
-typedef enum { DFSS_BF16 = 0 } dfss_dtype;
+typedef enum { DFSS_BF16 = 0, DFSS_F32 = 1 } dfss_dtype;
 
 typedef struct {
     int32_t B, H;   /* batch and heads; only the product B*H matters, except that a     */
@@ -175,6 +176,23 @@ size_t dfss_backward_workspace_bytes(const dfss_shape *s);
 dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K, const void *V, const void *O,
                                     const void *P, const void *meta, const dfss_shape *s, float scale, void *dQ,
                                     void *dK, void *dV, void *ws, size_t ws_bytes, void *stream);
+
+/* ---- the 4-byte mode (Sec. 2.3: 1:2 on float data; App. A.1.1) ------------------------ */
+/* With dfss_shape.dtype = DFSS_F32 the arrays Q, K, V, O, vals (kept scores / weights) and the dense
+ * workspace hold float32 instead of bfloat16, and N:M must be 1:2 (2:4 is DFSS_ERR_UNSUPPORTED).
+ * Calls that take this dtype: the size functions, dfss_sddmm_prune, dfss_sparse_softmax, dfss_spmm,
+ * dfss_attention (always the three stage kernels through the workspace), dense_attention and the two
+ * metadata conversions; the *_bias variants take it with key_bias == NULL only.  Every other call
+ * returns DFSS_ERR_UNSUPPORTED for it.
+ * Arithmetic: fp32 products and fp32 accumulation on the fp32 matrix instruction (the paper rounds
+ * the float inputs to a shorter mantissa for its tensor cores; this GPU has no such format, so the
+ * scores are at least that accurate); the kept scores are stored unrounded.
+ * Metadata: a float fills two consecutive 2-byte slots of a run of four, so a run is one aligned
+ * pair of keys and only two codes occur, the ones App. A.1.1 prints: 0x4 = the first float of the
+ * pair is kept, 0xE = the second.  uint16 [B*H, Lq, Lk/8], word w of a row = codes of pairs
+ * 4w..4w+3, pair 4w+k at bits [4k, 4k+3] -- again 1/16 of the dense matrix in bits.  The library
+ * holds these words in exactly this (canonical) order; dfss_meta_to_canonical and
+ * dfss_meta_from_canonical are plain copies in this mode. */
 
 /* ---- metadata order ---------------------------------------------------------------- */
 /* Canonical order: uint16 [B*H, Lq, Lk/16], word w of a row = codes of key runs

@@ -5,6 +5,8 @@ argument marshalling only, every step of the path runs in the HIP kernels.
 PyTorch is used for device memory and streams.
 """
 from .binding import (  # noqa: F401
+    DFSS_BF16,
+    DFSS_F32,
     DfssError,
     Shape,
     dense_attention,

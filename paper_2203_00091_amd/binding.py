@@ -27,6 +27,9 @@ EXPORTS = (
 )
 
 
+DFSS_BF16, DFSS_F32 = 0, 1
+
+
 class DfssError(RuntimeError):
     def __init__(self, fn: str, status: int, text: str):
         super().__init__(f"{fn} failed: status {status} ({text})")
@@ -47,7 +50,16 @@ class Shape:
     d: int
     N: int = 2
     M: int = 4
-    dtype: int = 0  # DFSS_BF16
+    dtype: int = 0  # DFSS_BF16 = 0, DFSS_F32 = 1 (the 4-byte mode: 1:2 only)
+
+    @property
+    def torch_dtype(self):
+        return torch.float32 if self.dtype == DFSS_F32 else torch.bfloat16
+
+    @property
+    def meta_words(self) -> int:
+        """uint16 metadata words per row: one 4-bit code per 8 bytes of dense data."""
+        return self.Lk // (8 if self.dtype == DFSS_F32 else 16)
 
     def c(self) -> _CShape:
         return _CShape(self.B, self.H, self.Lq, self.Lk, self.d, self.N, self.M, self.dtype)
@@ -127,6 +139,39 @@ def _ptr(t: torch.Tensor | None) -> int | None:
     return t.data_ptr()
 
 
+def _data(t: torch.Tensor | None, s: Shape, *shape) -> int | None:
+    """Pointer of a Q/K/V/O/vals-like tensor after checking that its element type is the one the shape
+    declares and its size the one the call will touch (the C side sees raw pointers only)."""
+    if t is None:
+        return None
+    if t.dtype != s.torch_dtype:
+        raise ValueError(f"expected a {s.torch_dtype} tensor for dfss_shape.dtype = {s.dtype}, got {t.dtype}")
+    n = 1
+    for k in shape:
+        n *= k
+    if t.numel() != n:
+        raise ValueError(f"expected {n} elements {shape}, got {t.numel()}")
+    return _ptr(t)
+
+
+def _q(t, s: Shape):      # Q, O and their gradients: [BH, Lq, d]
+    return _data(t, s, s.BH, s.Lq, s.d)
+
+
+def _kv(t, s: Shape):     # K, V and their gradients: [BH, Lk, d]
+    return _data(t, s, s.BH, s.Lk, s.d)
+
+
+def _kept(t, s: Shape):   # kept scores / weights: [BH, Lq, Lk*N/M]
+    return _data(t, s, s.BH, s.Lq, s.Lc)
+
+
+def _meta(t: torch.Tensor, s: Shape) -> int:
+    if t.element_size() != 2 or t.numel() != s.BH * s.Lq * s.meta_words:
+        raise ValueError(f"metadata must hold {s.BH * s.Lq * s.meta_words} 16-bit words")
+    return _ptr(t)
+
+
 def dfss_vals_bytes(s: Shape) -> int:
     return int(load_library().dfss_vals_bytes(ctypes.byref(s.c())))
 
@@ -148,28 +193,29 @@ def _alloc_bytes(n: int, device) -> torch.Tensor:
 
 
 def dfss_sddmm_prune(Q, K, s: Shape, scale: float, vals=None, meta=None):
-    """Stage 1.  Returns (vals bf16 [BH, Lq, Lk*N/M], meta uint16 in library order [BH*Lq*Lk/16])."""
+    """Stage 1.  Returns (vals [BH, Lq, Lk*N/M] in the shape's dtype, meta: 16-bit words in library order)."""
     if vals is None:
-        vals = torch.empty((s.BH, s.Lq, s.Lc), dtype=torch.bfloat16, device=Q.device)
+        vals = torch.empty((s.BH, s.Lq, s.Lc), dtype=s.torch_dtype, device=Q.device)
     if meta is None:
-        meta = torch.empty((s.BH * s.Lq * (s.Lk // 16),), dtype=torch.int16, device=Q.device)
-    st = load_library().dfss_sddmm_prune(_ptr(Q), _ptr(K), ctypes.byref(s.c()), scale, _ptr(vals), _ptr(meta),
-                                         _stream())
+        meta = torch.empty((s.BH * s.Lq * s.meta_words,), dtype=torch.int16, device=Q.device)
+    st = load_library().dfss_sddmm_prune(_q(Q, s), _kv(K, s), ctypes.byref(s.c()), scale,
+                                         _kept(vals, s), _meta(meta, s), _stream())
     _check("dfss_sddmm_prune", st)
     return vals, meta
 
 
 def dfss_sparse_softmax(vals, s: Shape):
     """Stage 2, in place on vals."""
-    _check("dfss_sparse_softmax", load_library().dfss_sparse_softmax(_ptr(vals), ctypes.byref(s.c()), _stream()))
+    _check("dfss_sparse_softmax", load_library().dfss_sparse_softmax(_kept(vals, s), ctypes.byref(s.c()), _stream()))
     return vals
 
 
 def dfss_spmm(vals, meta, V, s: Shape, O=None):
-    """Stage 3.  Returns O bf16 [BH, Lq, d]."""
+    """Stage 3.  Returns O [BH, Lq, d]."""
     if O is None:
-        O = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=V.device)
-    st = load_library().dfss_spmm(_ptr(vals), _ptr(meta), _ptr(V), ctypes.byref(s.c()), _ptr(O), _stream())
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=V.device)
+    st = load_library().dfss_spmm(_kept(vals, s), _meta(meta, s), _kv(V, s),
+                                  ctypes.byref(s.c()), _q(O, s), _stream())
     _check("dfss_spmm", st)
     return O
 
@@ -177,10 +223,11 @@ def dfss_spmm(vals, meta, V, s: Shape, O=None):
 def dfss_attention(Q, K, V, s: Shape, scale: float, O=None, ws=None):
     """Whole DFSS forward.  ``ws`` (uint8 device tensor) is allocated if not given."""
     if O is None:
-        O = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=Q.device)
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
     if ws is None:
         ws = _alloc_bytes(dfss_workspace_bytes(s), Q.device)
-    st = load_library().dfss_attention(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(s.c()), scale, _ptr(O), _ptr(ws),
+    st = load_library().dfss_attention(_q(Q, s), _kv(K, s), _kv(V, s),
+                                       ctypes.byref(s.c()), scale, _q(O, s), _ptr(ws),
                                        ws.numel() * ws.element_size(), _stream())
     _check("dfss_attention", st)
     return O
@@ -189,10 +236,11 @@ def dfss_attention(Q, K, V, s: Shape, scale: float, O=None, ws=None):
 def dense_attention(Q, K, V, s: Shape, scale: float, O=None, ws=None):
     """Full attention baseline on the same GPU."""
     if O is None:
-        O = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=Q.device)
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
     if ws is None:
         ws = _alloc_bytes(dense_workspace_bytes(s), Q.device)
-    st = load_library().dense_attention(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(s.c()), scale, _ptr(O), _ptr(ws),
+    st = load_library().dense_attention(_q(Q, s), _kv(K, s), _kv(V, s),
+                                        ctypes.byref(s.c()), scale, _q(O, s), _ptr(ws),
                                         ws.numel() * ws.element_size(), _stream())
     _check("dense_attention", st)
     return O
@@ -201,8 +249,9 @@ def dense_attention(Q, K, V, s: Shape, scale: float, O=None, ws=None):
 def dense_attention_fused(Q, K, V, s: Shape, scale: float, O=None):
     """Full attention in one kernel (the stronger baseline)."""
     if O is None:
-        O = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=Q.device)
-    st = load_library().dense_attention_fused(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(s.c()), scale, _ptr(O),
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    st = load_library().dense_attention_fused(_q(Q, s), _kv(K, s), _kv(V, s),
+                                              ctypes.byref(s.c()), scale, _q(O, s),
                                               _stream())
     _check("dense_attention_fused", st)
     return O
@@ -219,11 +268,11 @@ def _bias_ptr(key_bias, s: Shape):
 def dfss_sddmm_prune_bias(Q, K, key_bias, s: Shape, scale: float, vals=None, meta=None):
     """Stage 1 with an additive key bias (float32 [B, Lk] device tensor, -inf masks a key)."""
     if vals is None:
-        vals = torch.empty((s.BH, s.Lq, s.Lc), dtype=torch.bfloat16, device=Q.device)
+        vals = torch.empty((s.BH, s.Lq, s.Lc), dtype=s.torch_dtype, device=Q.device)
     if meta is None:
-        meta = torch.empty((s.BH * s.Lq * (s.Lk // 16),), dtype=torch.int16, device=Q.device)
-    st = load_library().dfss_sddmm_prune_bias(_ptr(Q), _ptr(K), _bias_ptr(key_bias, s), ctypes.byref(s.c()), scale,
-                                              _ptr(vals), _ptr(meta), _stream())
+        meta = torch.empty((s.BH * s.Lq * s.meta_words,), dtype=torch.int16, device=Q.device)
+    st = load_library().dfss_sddmm_prune_bias(_q(Q, s), _kv(K, s), _bias_ptr(key_bias, s),
+                                              ctypes.byref(s.c()), scale, _kept(vals, s), _meta(meta, s), _stream())
     _check("dfss_sddmm_prune_bias", st)
     return vals, meta
 
@@ -231,11 +280,12 @@ def dfss_sddmm_prune_bias(Q, K, key_bias, s: Shape, scale: float, vals=None, met
 def dfss_attention_bias(Q, K, V, key_bias, s: Shape, scale: float, O=None, ws=None):
     """Whole DFSS forward with an additive key bias."""
     if O is None:
-        O = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=Q.device)
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
     if ws is None:
         ws = _alloc_bytes(dfss_workspace_bytes(s), Q.device)
-    st = load_library().dfss_attention_bias(_ptr(Q), _ptr(K), _ptr(V), _bias_ptr(key_bias, s), ctypes.byref(s.c()),
-                                            scale, _ptr(O), _ptr(ws), ws.numel() * ws.element_size(), _stream())
+    st = load_library().dfss_attention_bias(_q(Q, s), _kv(K, s), _kv(V, s),
+                                            _bias_ptr(key_bias, s), ctypes.byref(s.c()), scale, _q(O, s), _ptr(ws),
+                                            ws.numel() * ws.element_size(), _stream())
     _check("dfss_attention_bias", st)
     return O
 
@@ -243,11 +293,12 @@ def dfss_attention_bias(Q, K, V, key_bias, s: Shape, scale: float, O=None, ws=No
 def dense_attention_bias(Q, K, V, key_bias, s: Shape, scale: float, O=None, ws=None):
     """Full attention (three stages) with an additive key bias."""
     if O is None:
-        O = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=Q.device)
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
     if ws is None:
         ws = _alloc_bytes(dense_workspace_bytes(s), Q.device)
-    st = load_library().dense_attention_bias(_ptr(Q), _ptr(K), _ptr(V), _bias_ptr(key_bias, s), ctypes.byref(s.c()),
-                                             scale, _ptr(O), _ptr(ws), ws.numel() * ws.element_size(), _stream())
+    st = load_library().dense_attention_bias(_q(Q, s), _kv(K, s), _kv(V, s),
+                                             _bias_ptr(key_bias, s), ctypes.byref(s.c()), scale, _q(O, s), _ptr(ws),
+                                            ws.numel() * ws.element_size(), _stream())
     _check("dense_attention_bias", st)
     return O
 
@@ -255,9 +306,9 @@ def dense_attention_bias(Q, K, V, key_bias, s: Shape, scale: float, O=None, ws=N
 def dense_attention_fused_bias(Q, K, V, key_bias, s: Shape, scale: float, O=None):
     """Full attention in one kernel with an additive key bias."""
     if O is None:
-        O = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=Q.device)
-    st = load_library().dense_attention_fused_bias(_ptr(Q), _ptr(K), _ptr(V), _bias_ptr(key_bias, s),
-                                                   ctypes.byref(s.c()), scale, _ptr(O), _stream())
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    st = load_library().dense_attention_fused_bias(_q(Q, s), _kv(K, s), _kv(V, s), _bias_ptr(key_bias, s),
+                                                   ctypes.byref(s.c()), scale, _q(O, s), _stream())
     _check("dense_attention_fused_bias", st)
     return O
 
@@ -271,9 +322,9 @@ def _block_mask_ptr(block_mask, s: Shape):
 def dfss_attention_blocked(Q, K, V, key_bias, block_mask, s: Shape, scale: float, O=None):
     """DFSS forward restricted to the 64 x 64 score blocks with a non-zero entry in block_mask."""
     if O is None:
-        O = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=Q.device)
-    st = load_library().dfss_attention_blocked(_ptr(Q), _ptr(K), _ptr(V), _bias_ptr(key_bias, s),
-                                               _block_mask_ptr(block_mask, s), ctypes.byref(s.c()), scale, _ptr(O),
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    st = load_library().dfss_attention_blocked(_q(Q, s), _kv(K, s), _kv(V, s), _bias_ptr(key_bias, s),
+                                               _block_mask_ptr(block_mask, s), ctypes.byref(s.c()), scale, _q(O, s),
                                                _stream())
     _check("dfss_attention_blocked", st)
     return O
@@ -282,10 +333,10 @@ def dfss_attention_blocked(Q, K, V, key_bias, block_mask, s: Shape, scale: float
 def dense_attention_fused_blocked(Q, K, V, key_bias, block_mask, s: Shape, scale: float, O=None):
     """Block-sparse full attention (same block pattern, no N:M pruning)."""
     if O is None:
-        O = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=Q.device)
-    st = load_library().dense_attention_fused_blocked(_ptr(Q), _ptr(K), _ptr(V), _bias_ptr(key_bias, s),
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    st = load_library().dense_attention_fused_blocked(_q(Q, s), _kv(K, s), _kv(V, s), _bias_ptr(key_bias, s),
                                                       _block_mask_ptr(block_mask, s), ctypes.byref(s.c()), scale,
-                                                      _ptr(O), _stream())
+                                                      _q(O, s), _stream())
     _check("dense_attention_fused_blocked", st)
     return O
 
@@ -293,8 +344,9 @@ def dense_attention_fused_blocked(Q, K, V, key_bias, block_mask, s: Shape, scale
 def dfss_spmm_t(vals, meta, X, s: Shape, out=None):
     """Transposed sparse product A^T X -> bf16 [BH, Lk, d] (dV = P^T dO, dK = dS^T Q)."""
     if out is None:
-        out = torch.empty((s.BH, s.Lk, s.d), dtype=torch.bfloat16, device=X.device)
-    st = load_library().dfss_spmm_t(_ptr(vals), _ptr(meta), _ptr(X), ctypes.byref(s.c()), _ptr(out), _stream())
+        out = torch.empty((s.BH, s.Lk, s.d), dtype=s.torch_dtype, device=X.device)
+    st = load_library().dfss_spmm_t(_kept(vals, s), _meta(meta, s), _q(X, s),
+                                    ctypes.byref(s.c()), _kv(out, s), _stream())
     _check("dfss_spmm_t", st)
     return out
 
@@ -306,15 +358,17 @@ def dfss_backward_workspace_bytes(s: Shape) -> int:
 def dfss_attention_backward(dO, Q, K, V, O, P, meta, s: Shape, scale: float, dQ=None, dK=None, dV=None, ws=None):
     """Gradients through the fixed selection.  P, meta: weights and metadata kept from the forward stages."""
     if dQ is None:
-        dQ = torch.empty((s.BH, s.Lq, s.d), dtype=torch.bfloat16, device=Q.device)
+        dQ = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
     if dK is None:
-        dK = torch.empty((s.BH, s.Lk, s.d), dtype=torch.bfloat16, device=Q.device)
+        dK = torch.empty((s.BH, s.Lk, s.d), dtype=s.torch_dtype, device=Q.device)
     if dV is None:
-        dV = torch.empty((s.BH, s.Lk, s.d), dtype=torch.bfloat16, device=Q.device)
+        dV = torch.empty((s.BH, s.Lk, s.d), dtype=s.torch_dtype, device=Q.device)
     if ws is None:
         ws = _alloc_bytes(dfss_backward_workspace_bytes(s), Q.device)
-    st = load_library().dfss_attention_backward(_ptr(dO), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(P), _ptr(meta),
-                                                ctypes.byref(s.c()), scale, _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ws),
+    st = load_library().dfss_attention_backward(_q(dO, s), _q(Q, s), _kv(K, s), _kv(V, s), _q(O, s),
+                                                _kept(P, s), _meta(meta, s), ctypes.byref(s.c()), scale,
+                                                _q(dQ, s), _kv(dK, s),
+                                                _kv(dV, s), _ptr(ws),
                                                 ws.numel() * ws.element_size(), _stream())
     _check("dfss_attention_backward", st)
     return dQ, dK, dV
@@ -323,15 +377,15 @@ def dfss_attention_backward(dO, Q, K, V, O, P, meta, s: Shape, scale: float, dQ=
 def dfss_meta_to_canonical(meta, s: Shape, canon=None):
     """Library word order -> canonical uint16 [BH, Lq, Lk/16] (held as int16 bits)."""
     if canon is None:
-        canon = torch.empty((s.BH, s.Lq, s.Lk // 16), dtype=torch.int16, device=meta.device)
-    st = load_library().dfss_meta_to_canonical(_ptr(meta), ctypes.byref(s.c()), _ptr(canon), _stream())
+        canon = torch.empty((s.BH, s.Lq, s.meta_words), dtype=torch.int16, device=meta.device)
+    st = load_library().dfss_meta_to_canonical(_meta(meta, s), ctypes.byref(s.c()), _meta(canon, s), _stream())
     _check("dfss_meta_to_canonical", st)
     return canon
 
 
 def dfss_meta_from_canonical(canon, s: Shape, meta=None):
     if meta is None:
-        meta = torch.empty((s.BH * s.Lq * (s.Lk // 16),), dtype=torch.int16, device=canon.device)
-    st = load_library().dfss_meta_from_canonical(_ptr(canon), ctypes.byref(s.c()), _ptr(meta), _stream())
+        meta = torch.empty((s.BH * s.Lq * s.meta_words,), dtype=torch.int16, device=canon.device)
+    st = load_library().dfss_meta_from_canonical(_meta(canon, s), ctypes.byref(s.c()), _meta(meta, s), _stream())
     _check("dfss_meta_from_canonical", st)
     return meta

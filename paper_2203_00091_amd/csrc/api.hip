@@ -14,6 +14,8 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Dims {
     int BH, H, Lq, Lk, d, mode;
+    bool f32;      // the 4-byte mode: fp32 data, 1:2 only, staged kernels only
+    size_t elem() const { return f32 ? 4 : 2; }
 };
 
 // Shape rules common to every entry point.  need_nm: also check N:M.
@@ -24,15 +26,16 @@ dfss_status check_shape(const dfss_shape *s, bool need_nm, Dims *out) {
     if (bh > 65535) return DFSS_ERR_SHAPE;
     if (s->Lq % 64 != 0 || s->Lk % 128 != 0) return DFSS_ERR_SHAPE;
     if (s->Lk > 8192 || s->Lq > (1 << 20)) return DFSS_ERR_SHAPE;
-    if (s->dtype != DFSS_BF16) return DFSS_ERR_UNSUPPORTED;
+    if (s->dtype != DFSS_BF16 && s->dtype != DFSS_F32) return DFSS_ERR_UNSUPPORTED;
+    const bool f32 = s->dtype == DFSS_F32;
     if (s->d != 64 && s->d != 128) return DFSS_ERR_UNSUPPORTED;
     int mode = -1;
     if (need_nm) {
-        if (s->N == 2 && s->M == 4) mode = 0;
+        if (s->N == 2 && s->M == 4 && !f32) mode = 0;   // 2:4 belongs to 2-byte data (Sec. 2.3)
         else if (s->N == 1 && s->M == 2) mode = 1;
         else return DFSS_ERR_UNSUPPORTED;
     }
-    if (out) *out = Dims{(int)bh, s->H, s->Lq, s->Lk, s->d, mode};
+    if (out) *out = Dims{(int)bh, s->H, s->Lq, s->Lk, s->d, mode, f32};
     return DFSS_OK;
 }
 
@@ -59,13 +62,13 @@ extern "C" {
 size_t dfss_vals_bytes(const dfss_shape *s) {
     Dims D;
     if (check_shape(s, true, &D) != DFSS_OK) return 0;
-    return (size_t)D.BH * D.Lq * (D.Lk / 2) * 2;
+    return (size_t)D.BH * D.Lq * (D.Lk / 2) * D.elem();
 }
 
 size_t dfss_meta_bytes(const dfss_shape *s) {
     Dims D;
     if (check_shape(s, true, &D) != DFSS_OK) return 0;
-    return (size_t)D.BH * D.Lq * (D.Lk / 16) * 2;
+    return (size_t)D.BH * D.Lq * (D.Lk / (D.f32 ? 8 : 16)) * 2;   // one code per 8 bytes of dense data
 }
 
 size_t dfss_workspace_bytes(const dfss_shape *s) {
@@ -77,7 +80,7 @@ size_t dfss_workspace_bytes(const dfss_shape *s) {
 size_t dense_workspace_bytes(const dfss_shape *s) {
     Dims D;
     if (check_shape(s, false, &D) != DFSS_OK) return 0;
-    return align_up((size_t)D.BH * D.Lq * D.Lk * 2);
+    return align_up((size_t)D.BH * D.Lq * D.Lk * D.elem());
 }
 
 dfss_status dfss_sddmm_prune_bias(const void *Q, const void *K, const void *key_bias, const dfss_shape *s,
@@ -88,6 +91,11 @@ dfss_status dfss_sddmm_prune_bias(const void *Q, const void *K, const void *key_
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
     if (misaligned(Q) || misaligned(K) || misaligned(vals) || misaligned(meta) || misaligned(key_bias))
         return DFSS_ERR_SHAPE;
+    if (D.f32) {
+        if (key_bias) return DFSS_ERR_UNSUPPORTED;
+        return hip_status(dfss::launch_sddmm_prune_f32(Q, K, D.BH, D.Lq, D.Lk, D.d, scale, vals, meta,
+                                                       (hipStream_t)stream));
+    }
     return hip_status(dfss::launch_sddmm_prune(Q, K, (const float *)key_bias, D.H, D.BH, D.Lq, D.Lk, D.d, D.mode,
                                                scale, vals, meta, (hipStream_t)stream));
 }
@@ -102,6 +110,7 @@ dfss_status dfss_sparse_softmax(void *vals, const dfss_shape *s, void *stream) {
     if (!vals) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, true, &D)) return st;
     if (misaligned(vals)) return DFSS_ERR_SHAPE;
+    if (D.f32) return hip_status(dfss::launch_row_softmax_f32(vals, (long)D.BH * D.Lq, D.Lk / 2, (hipStream_t)stream));
     return hip_status(dfss::launch_row_softmax(vals, (long)D.BH * D.Lq, D.Lk / 2, (hipStream_t)stream));
 }
 
@@ -111,6 +120,7 @@ dfss_status dfss_spmm(const void *vals, const void *meta, const void *V, const d
     if (!vals || !meta || !V || !O) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, true, &D)) return st;
     if (misaligned(vals) || misaligned(meta) || misaligned(V) || misaligned(O)) return DFSS_ERR_SHAPE;
+    if (D.f32) return hip_status(dfss::launch_spmm_f32(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, (hipStream_t)stream));
     return hip_status(dfss::launch_spmm(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, (hipStream_t)stream));
 }
 
@@ -126,6 +136,15 @@ dfss_status dfss_attention_bias(const void *Q, const void *K, const void *V, con
     if (ws_bytes < dfss_workspace_bytes(s)) return DFSS_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     const float *bias = (const float *)key_bias;
+    if (D.f32) {
+        if (key_bias) return DFSS_ERR_UNSUPPORTED;
+        char *vals = static_cast<char *>(ws);
+        char *meta = vals + align_up(dfss_vals_bytes(s));
+        hipError_t e = dfss::launch_sddmm_prune_f32(Q, K, D.BH, D.Lq, D.Lk, D.d, scale, vals, meta, st);
+        if (e == hipSuccess) e = dfss::launch_row_softmax_f32(vals, (long)D.BH * D.Lq, D.Lk / 2, st);
+        if (e == hipSuccess) e = dfss::launch_spmm_f32(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, st);
+        return hip_status(e);
+    }
     if (!staged_path_requested())
         return hip_status(dfss::launch_fused_attention(Q, K, V, bias, D.H, nullptr, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, O, st));
     char *vals = static_cast<char *>(ws);
@@ -149,6 +168,7 @@ dfss_status dense_attention_fused_bias(const void *Q, const void *K, const void 
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias))
         return DFSS_ERR_SHAPE;
+    if (D.f32) return DFSS_ERR_UNSUPPORTED;
     return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, nullptr, D.BH, D.Lq, D.Lk,
                                                    D.d, 2, scale, O, (hipStream_t)stream));
 }
@@ -169,6 +189,13 @@ dfss_status dense_attention_bias(const void *Q, const void *K, const void *V, co
     if ((reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0) return DFSS_ERR_SHAPE;
     if (ws_bytes < dense_workspace_bytes(s)) return DFSS_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
+    if (D.f32) {
+        if (key_bias) return DFSS_ERR_UNSUPPORTED;
+        hipError_t e = dfss::launch_dense_scores_f32(Q, K, D.BH, D.Lq, D.Lk, D.d, scale, ws, st);
+        if (e == hipSuccess) e = dfss::launch_row_softmax_f32(ws, (long)D.BH * D.Lq, D.Lk, st);
+        if (e == hipSuccess) e = dfss::launch_dense_av_f32(ws, V, D.BH, D.Lq, D.Lk, D.d, O, st);
+        return hip_status(e);
+    }
     hipError_t e = dfss::launch_dense_scores(Q, K, (const float *)key_bias, D.H, D.BH, D.Lq, D.Lk, D.d, scale, ws, st);
     if (e == hipSuccess) e = dfss::launch_row_softmax(ws, (long)D.BH * D.Lq, D.Lk, st);
     if (e == hipSuccess) e = dfss::launch_dense_av(ws, V, D.BH, D.Lq, D.Lk, D.d, O, st);
@@ -190,6 +217,7 @@ static dfss_status attention_blocked(const void *Q, const void *K, const void *V
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias))
         return DFSS_ERR_SHAPE;
+    if (D.f32) return DFSS_ERR_UNSUPPORTED;
     return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, (const uint8_t *)block_mask,
                                                    D.BH, D.Lq, D.Lk, D.d, dense ? 2 : D.mode, scale, O,
                                                    (hipStream_t)stream));
@@ -212,6 +240,7 @@ dfss_status dfss_spmm_t(const void *vals, const void *meta, const void *X, const
     if (!vals || !meta || !X || !out) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, true, &D)) return st;
     if (misaligned(vals) || misaligned(meta) || misaligned(X) || misaligned(out)) return DFSS_ERR_SHAPE;
+    if (D.f32) return DFSS_ERR_UNSUPPORTED;
     return hip_status(dfss::launch_spmm_t(vals, meta, X, D.BH, D.Lq, D.Lk, D.d, out, (hipStream_t)stream));
 }
 
@@ -226,6 +255,7 @@ dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K
         misaligned(meta) || misaligned(dQ) || misaligned(dK) || misaligned(dV))
         return DFSS_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0) return DFSS_ERR_SHAPE;
+    if (D.f32) return DFSS_ERR_UNSUPPORTED;
     if (ws_bytes < align_up(dfss_vals_bytes(s))) return DFSS_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     void *dS = ws;   // scale * dS in the compressed layout of P
@@ -237,8 +267,14 @@ dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K
 }
 
 size_t dfss_backward_workspace_bytes(const dfss_shape *s) {
+    if (s && s->dtype != DFSS_BF16) return 0;
     const size_t v = dfss_vals_bytes(s);
     return v ? align_up(v) : 0;
+}
+
+// The metadata of the 4-byte mode is kept in canonical order: the conversions are plain copies.
+static dfss_status copy_meta(const void *src, void *dst, const dfss_shape *s, void *stream) {
+    return hip_status(hipMemcpyAsync(dst, src, dfss_meta_bytes(s), hipMemcpyDeviceToDevice, (hipStream_t)stream));
 }
 
 dfss_status dfss_meta_to_canonical(const void *meta, const dfss_shape *s, void *canon, void *stream) {
@@ -246,6 +282,7 @@ dfss_status dfss_meta_to_canonical(const void *meta, const dfss_shape *s, void *
     if (!meta || !canon) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, true, &D)) return st;
     if (misaligned(meta) || misaligned(canon)) return DFSS_ERR_SHAPE;
+    if (D.f32) return copy_meta(meta, canon, s, stream);
     return hip_status(dfss::launch_meta_reorder(meta, canon, D.BH, D.Lq, D.Lk / 32, true, (hipStream_t)stream));
 }
 
@@ -254,6 +291,7 @@ dfss_status dfss_meta_from_canonical(const void *canon, const dfss_shape *s, voi
     if (!meta || !canon) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, true, &D)) return st;
     if (misaligned(meta) || misaligned(canon)) return DFSS_ERR_SHAPE;
+    if (D.f32) return copy_meta(canon, meta, s, stream);
     return hip_status(dfss::launch_meta_reorder(canon, meta, D.BH, D.Lq, D.Lk / 32, false, (hipStream_t)stream));
 }
 

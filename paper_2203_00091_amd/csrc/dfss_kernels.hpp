@@ -34,6 +34,16 @@ hipError_t launch_spmm_t(const void *vals, const void *meta, const void *X, int 
 // dS' = scale * P .* (dO V^T - delta) at the kept positions (delta_q = dO_q . O_q), compressed like P.
 hipError_t launch_masked_sddmm_ds(const void *dO, const void *V, const void *O, const void *P, const void *meta,
                                   int BH, int Lq, int Lk, int d, float scale, void *dS, hipStream_t st);
+// The 4-byte mode (Sec. 2.3: float data, 1:2): fp32 Q, K, V, kept scores, weights and O; metadata = one
+// 4-bit code per kept float in canonical word order, uint16 [BH, Lq, Lk/8].
+hipError_t launch_sddmm_prune_f32(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale,
+                                  void *vals, void *meta, hipStream_t st);
+hipError_t launch_dense_scores_f32(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale, void *S,
+                                   hipStream_t st);
+hipError_t launch_row_softmax_f32(void *x, long rows, int cols, hipStream_t st);
+hipError_t launch_spmm_f32(const void *vals, const void *meta, const void *V, int BH, int Lq, int Lk, int d, void *O,
+                           hipStream_t st);
+hipError_t launch_dense_av_f32(const void *P, const void *V, int BH, int Lq, int Lk, int d, void *O, hipStream_t st);
 // Metadata word order: library <-> canonical.
 hipError_t launch_meta_reorder(const void *src, void *dst, int BH, int Lq, int W, bool to_canonical,
                                hipStream_t st);

@@ -32,6 +32,7 @@ class Workload:
     sigma: float
     seed: int
     integer: bool = False  # Q, K integer-valued in [-4, 4] (scores exact in fp32)
+    float32: bool = False  # the paper's 4-byte mode: float32 tensors, not rounded to bfloat16
 
     @property
     def BH(self) -> int:
@@ -54,36 +55,44 @@ WORKLOADS = {
         Workload("long_L4096_2to4", 2, 12, 4096, 64, 2, 4, 1.0, 4003),
         Workload("large_head_L2048_d128_2to4", 4, 16, 2048, 128, 2, 4, 0.5, 5001),
         Workload("large_head_L2048_d128_1to2", 4, 16, 2048, 128, 1, 2, 0.5, 5001),
+        # the paper's second precision (float data, 1:2) on the same shapes
+        Workload("tiny_1to2_f32", 1, 1, 256, 64, 1, 2, 1.0, 6001, float32=True),
+        Workload("tiny_1to2_f32_int", 1, 1, 256, 64, 1, 2, 1.0, 6002, integer=True, float32=True),
+        Workload("bert_base_L512_1to2_f32", 16, 12, 512, 64, 1, 2, 1.0, 6003, float32=True),
+        Workload("long_L4096_1to2_f32", 2, 12, 4096, 64, 1, 2, 1.0, 6004, float32=True),
+        Workload("large_head_L2048_d128_1to2_f32", 4, 16, 2048, 128, 1, 2, 0.5, 6005, float32=True),
     ]
 }
 
 
-def gaussian_qkv(BH: int, Lq: int, Lk: int, d: int, sigma: float, seed: int):
-    """Q [BH,Lq,d], K,V [BH,Lk,d] ~ N(0, sigma^2), rounded to bfloat16 (CPU tensors)."""
+def gaussian_qkv(BH: int, Lq: int, Lk: int, d: int, sigma: float, seed: int, dtype=torch.bfloat16):
+    """Q [BH,Lq,d], K,V [BH,Lk,d] ~ N(0, sigma^2), rounded to `dtype` (CPU tensors)."""
     g = torch.Generator(device="cpu")
     g.manual_seed(seed)
-    Q = (torch.randn(BH, Lq, d, generator=g) * sigma).to(torch.bfloat16)
-    K = (torch.randn(BH, Lk, d, generator=g) * sigma).to(torch.bfloat16)
-    V = (torch.randn(BH, Lk, d, generator=g) * sigma).to(torch.bfloat16)
+    Q = (torch.randn(BH, Lq, d, generator=g) * sigma).to(dtype)
+    K = (torch.randn(BH, Lk, d, generator=g) * sigma).to(dtype)
+    V = (torch.randn(BH, Lk, d, generator=g) * sigma).to(dtype)
     return Q, K, V
 
 
-def integer_qkv(BH: int, Lq: int, Lk: int, d: int, seed: int, lo: int = -4, hi: int = 4):
-    """Q, K integers uniform in [lo, hi] (exact in bfloat16), V ~ N(0,1) rounded to bfloat16."""
+def integer_qkv(BH: int, Lq: int, Lk: int, d: int, seed: int, lo: int = -4, hi: int = 4, dtype=torch.bfloat16):
+    """Q, K integers uniform in [lo, hi] (exact in bfloat16), V ~ N(0,1) rounded to `dtype`."""
     g = torch.Generator(device="cpu")
     g.manual_seed(seed)
-    Q = torch.randint(lo, hi + 1, (BH, Lq, d), generator=g).to(torch.bfloat16)
-    K = torch.randint(lo, hi + 1, (BH, Lk, d), generator=g).to(torch.bfloat16)
-    V = torch.randn(BH, Lk, d, generator=g).to(torch.bfloat16)
+    Q = torch.randint(lo, hi + 1, (BH, Lq, d), generator=g).to(dtype)
+    K = torch.randint(lo, hi + 1, (BH, Lk, d), generator=g).to(dtype)
+    V = torch.randn(BH, Lk, d, generator=g).to(dtype)
     return Q, K, V
 
 
 def make(workload: Workload | str):
-    """Inputs of a named workload: (Q, K, V) bfloat16 CPU tensors shaped [B*H, L, d]."""
+    """Inputs of a named workload: (Q, K, V) CPU tensors shaped [B*H, L, d], bfloat16 (float32 for
+    the workloads of the 4-byte mode)."""
     w = WORKLOADS[workload] if isinstance(workload, str) else workload
+    dtype = torch.float32 if w.float32 else torch.bfloat16
     if w.integer:
-        return integer_qkv(w.BH, w.L, w.L, w.d, w.seed)
-    return gaussian_qkv(w.BH, w.L, w.L, w.d, w.sigma, w.seed)
+        return integer_qkv(w.BH, w.L, w.L, w.d, w.seed, dtype=dtype)
+    return gaussian_qkv(w.BH, w.L, w.L, w.d, w.sigma, w.seed, dtype=dtype)
 
 
 def padding_lengths(B: int, Lk: int, seed: int, min_frac: float = 0.5):

@@ -40,6 +40,13 @@ def test_sizes_follow_the_compressed_footprint():
     s12 = Shape(16, 12, 512, 512, 64, 1, 2)
     assert dfss.dfss_vals_bytes(s12) == 192 * 512 * 512
     assert dfss.dfss_meta_bytes(s12) == 192 * 512 * 512 // 8
+    # the 4-byte mode: half of the dense floats, metadata again 1/16 of the dense bits
+    f32 = Shape(16, 12, 512, 512, 64, 1, 2, dfss.DFSS_F32)
+    dense32 = 192 * 512 * 512 * 4
+    assert dfss.dfss_vals_bytes(f32) == dense32 // 2
+    assert dfss.dfss_meta_bytes(f32) == dense32 // 16
+    assert dfss.dense_workspace_bytes(f32) >= dense32
+    assert dfss.dfss_backward_workspace_bytes(f32) == 0     # no backward pass in this mode
 
 
 @pytest.mark.parametrize("shape", [
@@ -48,7 +55,8 @@ def test_sizes_follow_the_compressed_footprint():
     Shape(0, 1, 128, 128, 64),
     Shape(1, 1, 128, 128, 64, 3, 4),  # N:M not implemented
     Shape(1, 1, 128, 128, 96),       # head size not implemented
-    Shape(1, 1, 128, 128, 64, 2, 4, 1),  # dtype not implemented
+    Shape(1, 1, 128, 128, 64, 2, 4, 1),  # 2:4 on float data: not a mode of the method (Sec. 2.3)
+    Shape(1, 1, 128, 128, 64, 1, 2, 2),  # dtype not implemented
     Shape(300, 300, 128, 128, 64),   # too many heads for one launch
     Shape(1, 1, 128, 16384, 64),     # rows longer than the softmax kernel holds
 ])
@@ -94,6 +102,16 @@ def test_errors_are_reported_before_any_launch():
                                        0.125, aligned, aligned, aligned, ws, 16, None) == E_WS
     assert lib.dfss_attention_backward(aligned, aligned, aligned, aligned, aligned, aligned, aligned, ctypes.byref(ok),
                                        0.0, aligned, aligned, aligned, ws, 1 << 30, None) == E_UNSUP
+    # the 4-byte mode: calls without a float path refuse it, the others validate as usual
+    f32 = Shape(1, 1, 128, 128, 64, 1, 2, dfss.DFSS_F32).c()
+    assert lib.dense_attention_fused(aligned, aligned, aligned, ctypes.byref(f32), 0.125, aligned, None) == E_UNSUP
+    assert lib.dfss_sddmm_prune_bias(aligned, aligned, aligned, ctypes.byref(f32), 0.125, aligned, aligned, None) == E_UNSUP
+    assert lib.dfss_attention_blocked(aligned, aligned, aligned, None, aligned, ctypes.byref(f32), 0.125, aligned, None) == E_UNSUP
+    assert lib.dfss_spmm_t(aligned, aligned, aligned, ctypes.byref(f32), aligned, None) == E_UNSUP
+    assert lib.dfss_attention_backward(aligned, aligned, aligned, aligned, aligned, aligned, aligned, ctypes.byref(f32),
+                                       0.125, aligned, aligned, aligned, ws, 1 << 30, None) == E_UNSUP
+    assert lib.dfss_attention(aligned, aligned, aligned, ctypes.byref(f32), 0.125, aligned, ws, 16, None) == E_WS
+    assert lib.dense_attention(aligned, aligned, aligned, ctypes.byref(f32), 0.125, aligned, ws, 16, None) == E_WS
     assert lib.dfss_status_string(0) == b"ok"
     assert lib.dfss_status_string(E_WS) == b"workspace too small"
 
@@ -104,5 +122,7 @@ def test_binding_refuses_host_tensors():
     q = torch.zeros(1, 128, 64, dtype=torch.bfloat16)
     with pytest.raises(ValueError):
         dfss.dfss_sddmm_prune(q, q, s, 0.125, vals=q, meta=q)
+    with pytest.raises(ValueError):   # element type that does not match dfss_shape.dtype (checked before the device check)
+        dfss.dfss_sddmm_prune(q.float(), q.float(), s, 0.125, vals=q, meta=q)
     with pytest.raises(ValueError):   # key bias of the wrong shape or type
         dfss.dfss_attention_bias(q, q, q, torch.zeros(2, 128), s, 0.125, O=q, ws=q)

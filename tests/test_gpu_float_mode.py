@@ -1,0 +1,176 @@
+"""Parity of the 4-byte mode (float data, 1:2 selection; Sec. 2.3, App. A.1.1) against the CPU oracle,
+through the C ABI (needs an MI355X).
+
+Bars:
+  * kept scores and metadata bit-exact on integer-valued Q, K (every product and sum exact in fp32);
+  * on Gaussian inputs a pair may be decided differently only if its two scores are closer than the
+    rounding error both sides can have; kept scores within that error bound.  The bound is the
+    textbook forward error of a length-d dot product accumulated in fp32 in any order,
+    d * 2^-24 * sum_k |q_k k_k|, plus one rounding for the multiplication by scale;
+  * softmax and SpMM stages, fed with the GPU's own stage-1 output, within fp32 rounding of the oracle;
+  * whole path within 2e-2 of the oracle everywhere and within 1e-4 on rows whose selection agrees.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2203_00091_amd as dfss
+from paper_2203_00091_amd import DFSS_F32, Shape, synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+U = 2.0 ** -24   # unit roundoff of fp32
+
+
+def _dev(t):
+    return t.to(DEV).contiguous()
+
+
+def _meta_np(meta, s):
+    return meta.cpu().numpy().view(np.uint16).reshape(s.BH, s.Lq, s.meta_words)
+
+
+def _shape(B, H, Lq, Lk, d):
+    return Shape(B, H, Lq, Lk, d, 1, 2, DFSS_F32)
+
+
+def _score_error_bound(Q, K, scale):
+    """Per-element bound on |computed - exact| of scale * q.k for fp32 accumulation in any order."""
+    d = Q.shape[-1]
+    absdot = np.abs(Q).astype(np.float64) @ np.abs(K).astype(np.float64).T
+    return (d * U * absdot + U * absdot) * scale
+
+
+@pytest.mark.parametrize("BH,Lq,Lk,d,scale", [
+    (1, 256, 256, 64, 0.125),
+    (3, 128, 384, 64, 0.125),                                   # several heads, rectangular
+    (2, 192, 256, 128, 0.125),                                  # d = 128
+    (1, 64, 128, 128, float(np.float32(1 / math.sqrt(128)))),   # smallest legal shape, scale not a power of two
+    (1, 64, 8192, 64, 0.125),                                   # longest key sequence
+])
+def test_stage1_bit_exact_on_integer_inputs(BH, Lq, Lk, d, scale):
+    Q, K, _ = synth.integer_qkv(BH, Lq, Lk, d, seed=6100 + Lq + d, dtype=torch.float32)
+    s = _shape(1, BH, Lq, Lk, d)
+    vals, meta = dfss.dfss_sddmm_prune(_dev(Q), _dev(K), s, scale)
+    torch.cuda.synchronize()
+    vals, meta = vals.cpu().numpy(), _meta_np(meta, s)
+    ties = 0
+    for h in range(BH):
+        S = oracle.scores(Q[h].numpy(), K[h].numpy(), scale)
+        _, ovals, kidx = oracle.prune(S, 1, 2)
+        assert np.array_equal(meta[h], oracle.encode_meta_f32(kidx, Lk)), f"metadata differs in head {h}"
+        assert np.array_equal(vals[h], ovals), f"kept scores differ in head {h}"
+        ties += int(np.sum(S[:, 0::2] == S[:, 1::2]))
+    assert ties > 0   # the tie rule was exercised
+
+
+def test_stage1_all_equal_scores_keep_the_first():
+    Q = torch.zeros(1, 64, 64)
+    K = torch.ones(1, 128, 64)
+    s = _shape(1, 1, 64, 128, 64)
+    vals, meta = dfss.dfss_sddmm_prune(_dev(Q), _dev(K), s, 0.125)
+    torch.cuda.synchronize()
+    assert np.all(_meta_np(meta, s) == 0x4444) and np.all(vals.cpu().numpy() == 0)
+
+
+def test_meta_conversions_are_copies():
+    Q, K, _ = synth.integer_qkv(2, 64, 128, 64, seed=6200, dtype=torch.float32)
+    s = _shape(1, 2, 64, 128, 64)
+    _, meta = dfss.dfss_sddmm_prune(_dev(Q), _dev(K), s, 0.125)
+    canon = dfss.dfss_meta_to_canonical(meta, s)
+    back = dfss.dfss_meta_from_canonical(canon, s)
+    torch.cuda.synchronize()
+    assert torch.equal(canon.reshape(-1), meta) and torch.equal(back, meta)
+
+
+@pytest.mark.parametrize("name", ["tiny_1to2_f32", "bert_base_L512_1to2_f32", "large_head_L2048_d128_1to2_f32"])
+def test_stages_on_gaussian_inputs(name):
+    w = synth.WORKLOADS[name]
+    Q, K, V = synth.make(w)
+    s = _shape(w.B, w.H, w.L, w.L, w.d)
+    vals, meta = dfss.dfss_sddmm_prune(_dev(Q), _dev(K), s, w.scale)
+    torch.cuda.synchronize()
+    scores_gpu = vals.cpu().numpy()
+    meta_np = _meta_np(meta, s)
+    P = dfss.dfss_sparse_softmax(vals.clone(), s)
+    O = dfss.dfss_spmm(P, meta, _dev(V), s)
+    torch.cuda.synchronize()
+    P, O = P.cpu().numpy(), O.cpu().numpy()
+
+    heads = range(w.BH) if w.BH <= 4 else [0, w.BH // 2, w.BH - 1]     # sampled heads at the full sizes
+    pairs = differ_total = 0
+    for h in heads:
+        Qn, Kn, Vn = Q[h].numpy(), K[h].numpy(), V[h].numpy()
+        S = oracle.scores(Qn, Kn, w.scale)
+        _, ovals, okidx = oracle.prune(S, 1, 2)
+        kidx = oracle.decode_meta_f32(meta_np[h], w.L)        # raises on any code other than 0x4 / 0xE
+        bound = _score_error_bound(Qn, Kn, w.scale)
+        # stage 1: the score each side kept, and where they chose differently
+        err_kept = np.abs(scores_gpu[h] - np.take_along_axis(S, kidx, 1))
+        assert np.all(err_kept <= 2 * np.take_along_axis(bound, kidx, 1) + 1e-12)
+        differ = kidx != okidx
+        gap = np.abs(S[:, 0::2] - S[:, 1::2])
+        room = 2 * (bound[:, 0::2] + bound[:, 1::2])
+        assert np.all(gap[differ] <= room[differ]), "a pair was decided differently outside the rounding error"
+        pairs += differ.size
+        differ_total += int(differ.sum())
+        # stage 2 and 3 on the GPU's own selection
+        Pref = oracle.softmax_kept(scores_gpu[h])
+        assert np.abs(P[h] - Pref).max() <= 1e-6
+        assert np.abs(P[h].sum(-1) - 1).max() <= 1e-5
+        Oref = oracle.spmm(P[h], kidx, Vn)
+        assert np.abs(O[h] - Oref).max() <= 1e-5 * max(1.0, float(np.abs(Vn).max()))
+    assert differ_total <= 1e-3 * pairs
+
+
+@pytest.mark.parametrize("BH,Lq,Lk,d", [(2, 128, 256, 64), (2, 64, 384, 128), (1, 192, 128, 64)])
+def test_attention_and_dense_baseline(BH, Lq, Lk, d):
+    Q, K, V = synth.gaussian_qkv(BH, Lq, Lk, d, 1.0, seed=6300 + Lq + d, dtype=torch.float32)
+    scale = 1 / math.sqrt(d)
+    s = _shape(1, BH, Lq, Lk, d)
+    O = dfss.dfss_attention(_dev(Q), _dev(K), _dev(V), s, scale)
+    Od = dfss.dense_attention(_dev(Q), _dev(K), _dev(V), s, scale)
+    torch.cuda.synchronize()
+    O, Od = O.cpu().numpy(), Od.cpu().numpy()
+    Qn, Kn, Vn = Q.numpy(), K.numpy(), V.numpy()
+    ref = oracle.attention(Qn, Kn, Vn, 1, 2, scale, store_bf16=False)
+    assert np.abs(O - ref).max() <= 2e-2
+    # rows whose selection cannot have differed (no pair inside the rounding error): fp32 accuracy
+    for h in range(BH):
+        S = oracle.scores(Qn[h], Kn[h], scale)
+        bound = _score_error_bound(Qn[h], Kn[h], scale)
+        safe = (np.abs(S[:, 0::2] - S[:, 1::2]) > 2 * (bound[:, 0::2] + bound[:, 1::2])).all(-1)
+        assert safe.sum() > Lq // 2
+        assert np.abs(O[h] - ref[h])[safe].max() <= 1e-4
+    # full attention (Eq. 1): N = M in the oracle
+    refd = oracle.attention(Qn, Kn, Vn, 2, 2, scale, store_bf16=False)
+    assert np.abs(Od - refd).max() <= 1e-4
+
+
+def test_stage_calls_compose_to_attention():
+    w = synth.WORKLOADS["tiny_1to2_f32"]
+    Q, K, V = (_dev(t) for t in synth.make(w))
+    s = _shape(w.B, w.H, w.L, w.L, w.d)
+    vals, meta = dfss.dfss_sddmm_prune(Q, K, s, w.scale)
+    O1 = dfss.dfss_spmm(dfss.dfss_sparse_softmax(vals, s), meta, V, s)
+    O2 = dfss.dfss_attention(Q, K, V, s, w.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2)
+
+
+def test_unsupported_combinations_are_refused():
+    s24 = Shape(1, 1, 64, 128, 64, 2, 4, DFSS_F32)
+    assert dfss.dfss_vals_bytes(s24) == 0
+    s = _shape(1, 1, 64, 128, 64)
+    Q = torch.zeros(1, 64, 64, device=DEV)
+    K = torch.zeros(1, 128, 64, device=DEV)
+    with pytest.raises(dfss.DfssError):
+        dfss.dense_attention_fused(Q, K, K, s, 0.125)
+    with pytest.raises(dfss.DfssError):
+        dfss.dfss_attention_bias(Q, K, K, torch.zeros(1, 128, device=DEV), s, 0.125)
+    with pytest.raises(ValueError):          # bfloat16 tensors with a float shape
+        dfss.dfss_attention(Q.bfloat16(), K.bfloat16(), K.bfloat16(), s, 0.125)
