@@ -13,6 +13,11 @@ the named workload.  Prints ONE JSON line.
                   FLOPs / measured launch duration against the dense bf16 MFMA peak.
   cpu_baseline    the CPU oracle timed on the host cores (context only).
 
+Workloads whose name ends in ``_f32`` run the paper's second precision (float data, 1:2): there
+``dfss_attention`` is the three stage kernels, the full-attention baseline is the three-stage
+``dense_attention``, and the roofline object describes the score/prune kernel (the largest of the
+three) against the fp32 MFMA peak.
+
 Inputs are resident in HBM before timing starts.  By default the steps rotate over enough
 independent buffer sets that no step finds its inputs or workspace in the last-level cache
 (``--warm`` keeps one set).  The K timed steps are captured in one HIP graph and replayed
@@ -33,6 +38,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
+MFMA_F32_PEAK_TFLOPS = 157.3    # dense fp32 MFMA (the workloads of the 4-byte mode)
 LLC_BYTES = 256 << 20           # last-level (Infinity) cache; L2 is 8 x 4 MiB on top
 # HBM bytes per launch of the fused kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (scaled by what the same counters read for a plain 64 MiB copy); summaries under profiles/.
@@ -82,7 +88,12 @@ def main():
     torch.cuda.set_device(dev)
 
     w = synth.WORKLOADS[args.workload]
-    s = Shape(w.B, w.H, w.L, w.L, w.d, w.N, w.M)
+    f32 = w.float32
+    s = Shape(w.B, w.H, w.L, w.L, w.d, w.N, w.M, dfss.DFSS_F32 if f32 else dfss.DFSS_BF16)
+    if f32 and (args.key_padding or args.block_pattern or args.backward):
+        print("bench.py: the float workloads run the plain forward pass only", file=sys.stderr)
+        sys.exit(2)
+    esz = 4 if f32 else 2
     K, W = args.steps, args.warmup
     BH, L, d = w.BH, w.L, w.d
 
@@ -90,7 +101,7 @@ def main():
     Qc, Kc, Vc = synth.make(w)
     ws_sparse = dfss.dfss_workspace_bytes(s)
     ws_dense = dfss.dense_workspace_bytes(s)
-    set_bytes = 4 * BH * L * d * 2 + max(ws_sparse, ws_dense)
+    set_bytes = 4 * BH * L * d * esz + max(ws_sparse, ws_dense)
     if args.warm:
         nsets = 1
     else:
@@ -99,7 +110,7 @@ def main():
     for i in range(nsets):
         sets.append(dict(
             Q=Qc.to(dev), K=Kc.to(dev), V=Vc.to(dev),
-            O=torch.empty((BH, L, d), dtype=torch.bfloat16, device=dev),
+            O=torch.empty((BH, L, d), dtype=s.torch_dtype, device=dev),
             ws=torch.empty(max(ws_sparse, ws_dense), dtype=torch.uint8, device=dev)))
     torch.cuda.synchronize()
 
@@ -147,11 +158,16 @@ def main():
         finally:
             del os.environ["DFSS_ATTENTION_PATH"]
 
+    n_vals, n_meta = dfss.dfss_vals_bytes(s), dfss.dfss_meta_bytes(s)
+    meta_at = (n_vals + 255) // 256 * 256
+
+    def stage_buffers(b):
+        """The kept values and the metadata inside the workspace, where dfss_attention puts them."""
+        return b["ws"][:n_vals].view(s.torch_dtype), b["ws"][meta_at:meta_at + n_meta].view(torch.int16)
+
     def step_stage1(i):
         b = sets[i % nsets]
-        n_vals = dfss.dfss_vals_bytes(s)
-        vals = b["ws"][:n_vals]
-        meta = b["ws"][(n_vals + 255) // 256 * 256:]
+        vals, meta = stage_buffers(b)
         if bias is None:
             dfss.dfss_sddmm_prune(b["Q"], b["K"], s, w.scale, vals=vals, meta=meta)
         else:
@@ -159,12 +175,12 @@ def main():
 
     def step_stage2(i):
         b = sets[i % nsets]
-        dfss.dfss_sparse_softmax(b["ws"], s)
+        dfss.dfss_sparse_softmax(stage_buffers(b)[0], s)
 
     def step_stage3(i):
         b = sets[i % nsets]
-        n_vals = dfss.dfss_vals_bytes(s)
-        dfss.dfss_spmm(b["ws"][:n_vals], b["ws"][(n_vals + 255) // 256 * 256:], b["V"], s, O=b["O"])
+        vals, meta = stage_buffers(b)
+        dfss.dfss_spmm(vals, meta, b["V"], s, O=b["O"])
 
     def timed(step_fn, steps, warmup, use_graph=True):
         """Wall-clock of `steps` steps between two device synchronisations -> seconds."""
@@ -219,8 +235,9 @@ def main():
     use_graph = not args.no_graph
     t_sparse = timed(step_sparse, K, W, use_graph)
     t_dense = timed(step_dense, K, W, use_graph)
-    t_dense_fused = timed(step_dense_fused, K, W, use_graph)
-    t_staged = timed(step_sparse_staged, K, W, use_graph)
+    # the float mode has no fused kernels: dfss_attention already is the staged path there
+    t_dense_fused = None if f32 else timed(step_dense_fused, K, W, use_graph)
+    t_staged = t_sparse if f32 else timed(step_sparse_staged, K, W, use_graph)
     t_sparse_eager = timed(step_sparse, K, 0, False)
 
     # ---- per-kernel durations (events around a graph of K launches of one kernel) ------
@@ -234,7 +251,7 @@ def main():
     flops_eq = 4.0 * BH * L * L * d * density
     ms = t_sparse / K * 1e3
     ms_dense = t_dense / K * 1e3
-    ms_dense_fused = t_dense_fused / K * 1e3
+    ms_dense_fused = None if f32 else t_dense_fused / K * 1e3
     ms_staged = t_staged / K * 1e3
     value = flops_alg / (t_sparse / K) / 1e12
 
@@ -243,9 +260,10 @@ def main():
     # (bytes per head): stage 1 reads Q,K = 4 L d and writes kept values L^2 plus metadata
     # L^2/8; stage 2 reads and writes L^2; stage 3 reads 1.125 L^2 + V and writes O.
     achieved = flops_alg / (k_fused * 1e-3) / 1e12
-    bytes1 = BH * (4.0 * L * d + 1.125 * L * L)
-    bytes2 = BH * (2.0 * L * L)
-    bytes3 = BH * (1.125 * L * L + 4.0 * L * d)
+    # (float mode: every element is 4 bytes, the metadata again 1/16 of the dense matrix)
+    bytes1 = BH * (2.0 * esz * L * d + (esz / 2 + esz / 16) * L * L)
+    bytes2 = BH * (esz * L * L)
+    bytes3 = BH * ((esz / 2 + esz / 16) * L * L + 2.0 * esz * L * d)
     kernels = {"sddmm_prune": (k1, bytes1), "sparse_softmax": (k2, bytes2), "spmm": (k3, bytes3)}
 
     out = {
@@ -259,7 +277,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "f32" if f32 else "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "L": L, "d": d, "N": w.N, "M": w.M,
                    "key_padding": bool(args.key_padding),
@@ -273,29 +291,40 @@ def main():
                      "algorithmic_hbm_bytes_per_launch": 8.0 * BH * L * d,
                      "avg_launch_ms": round(k_fused, 5), "algorithmic_flops_per_launch": flops_alg},
         "extra": {
-            "speedup_vs_dense_attention_fused": round(ms_dense_fused / ms, 4),
+            "speedup_vs_dense_attention_fused": None if f32 else round(ms_dense_fused / ms, 4),
             "speedup_vs_dense_attention_3stage": round(ms_dense / ms, 4),
             "staged_path_speedup_vs_dense_attention_3stage": round(ms_dense / ms_staged, 4),
-            "dense_attention_fused_ms_per_step": round(ms_dense_fused, 5),
+            "dense_attention_fused_ms_per_step": None if f32 else round(ms_dense_fused, 5),
             "dense_attention_3stage_ms_per_step": round(ms_dense, 5),
             "dfss_attention_staged_ms_per_step": round(ms_staged, 5),
             "dense_equivalent_tflops": round(flops_eq / (t_sparse / K) / 1e12, 3),
-            "dense_attention_fused_tflops": round(flops_eq / (t_dense_fused / K) / 1e12, 3),
+            "dense_attention_fused_tflops": None if f32 else round(flops_eq / (t_dense_fused / K) / 1e12, 3),
             "ms_per_step_direct_launch": round(t_sparse_eager / K * 1e3, 5),
             "stage_kernel_ms": {k: round(v[0], 5) for k, v in kernels.items()},
             "stage_kernel_GBps": {k: round(v[1] / (v[0] * 1e-3) / 1e9, 1) for k, v in kernels.items()},
             "stage_kernel_frac_of_hbm_peak": {k: round(v[1] / (v[0] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
                                               for k, v in kernels.items()},
             "sddmm_prune_tflops": round(2.0 * BH * L * L * d / (k1 * 1e-3) / 1e12, 2),
-            "sddmm_prune_frac_of_mfma_peak": round(2.0 * BH * L * L * d / (k1 * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "sddmm_prune_frac_of_mfma_peak": round(2.0 * BH * L * L * d / (k1 * 1e-3) / 1e12
+                                                   / (MFMA_F32_PEAK_TFLOPS if f32 else MFMA_BF16_PEAK_TFLOPS), 4),
         },
     }
+    if f32:
+        # three kernels per step; the score/prune kernel is the largest and is bound by the fp32 matrix
+        # instruction: 2 L^2 d flops per head per launch
+        flops1 = 2.0 * BH * L * L * d
+        ach1 = flops1 / (k1 * 1e-3) / 1e12
+        out["roofline"] = {"bound": "mfma", "kernel": "k_scores_f32 (dfss_sddmm_prune, float data)",
+                           "achieved": round(ach1, 2), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                           "frac": round(ach1 / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
+                           "algorithmic_hbm_bytes_per_launch": bytes1, "avg_launch_ms": round(k1, 5),
+                           "algorithmic_flops_per_launch": flops1}
+        out["extra"]["spmm_dense_equivalent_tflops"] = round(flops1 / (k3 * 1e-3) / 1e12, 2)
 
     if args.backward and block_mask is None:
         b = sets[0]
-        n_vals = dfss.dfss_vals_bytes(s)
         vals = torch.empty((BH, L, s.Lc), dtype=torch.bfloat16, device=dev)
-        meta = torch.empty((BH * L * (L // 16),), dtype=torch.int16, device=dev)
+        meta = torch.empty((BH * L * s.meta_words,), dtype=torch.int16, device=dev)
         if bias is None:
             dfss.dfss_sddmm_prune(b["Q"], b["K"], s, w.scale, vals=vals, meta=meta)
         else:
