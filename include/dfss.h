@@ -48,7 +48,7 @@ typedef enum {
     DFSS_ERR_HIP = 5          /* the HIP runtime refused a launch                        */
 } dfss_status;
 
-typedef enum { DFSS_BF16 = 0, DFSS_F32 = 1 } dfss_dtype;
+typedef enum { DFSS_BF16 = 0, DFSS_F32 = 1, DFSS_F32_BF16X3 = 2 } dfss_dtype;
 
 typedef struct {
     int32_t B, H;   /* batch and heads; only the product B*H matters, except that a     */
@@ -192,7 +192,14 @@ dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K
  * pair is kept, 0xE = the second.  uint16 [B*H, Lq, Lk/8], word w of a row = codes of pairs
  * 4w..4w+3, pair 4w+k at bits [4k, 4k+3] -- again 1/16 of the dense matrix in bits.  The library
  * holds these words in exactly this (canonical) order; dfss_meta_to_canonical and
- * dfss_meta_from_canonical are plain copies in this mode. */
+ * dfss_meta_from_canonical are plain copies in this mode.
+ * DFSS_F32_BF16X3 is the same mode (same arrays, layouts, calls and restrictions) with the products
+ * formed on the bfloat16 matrix pipe, the analogue of the paper's reduced-mantissa multiplication
+ * (App. A.1.2): each fp32 operand is split as x = hi + lo with hi = bf16(x), lo = bf16(x - hi), and
+ * a*b is taken as a_hi*b_hi + a_hi*b_lo + a_lo*b_hi, accumulated in fp32.  The dropped terms are at
+ * most 3 * 2^-18 |a*b| per product (the paper's format drops about 2^-10); operands that are exact
+ * in bfloat16 (e.g. small integers) give exactly the DFSS_F32 result.  The softmax stage is the same
+ * fp32 kernel.  Several times faster than DFSS_F32, whose matrix instruction is 16x slower. */
 
 /* ---- metadata order ---------------------------------------------------------------- */
 /* Canonical order: uint16 [B*H, Lq, Lk/16], word w of a row = codes of key runs

@@ -7,6 +7,7 @@ PyTorch is used for device memory and streams.
 from .binding import (  # noqa: F401
     DFSS_BF16,
     DFSS_F32,
+    DFSS_F32_BF16X3,
     DfssError,
     Shape,
     dense_attention,

@@ -27,7 +27,7 @@ EXPORTS = (
 )
 
 
-DFSS_BF16, DFSS_F32 = 0, 1
+DFSS_BF16, DFSS_F32, DFSS_F32_BF16X3 = 0, 1, 2
 
 
 class DfssError(RuntimeError):
@@ -50,16 +50,16 @@ class Shape:
     d: int
     N: int = 2
     M: int = 4
-    dtype: int = 0  # DFSS_BF16 = 0, DFSS_F32 = 1 (the 4-byte mode: 1:2 only)
+    dtype: int = 0  # DFSS_BF16 = 0; DFSS_F32 = 1, DFSS_F32_BF16X3 = 2 (the 4-byte mode: 1:2 only)
 
     @property
     def torch_dtype(self):
-        return torch.float32 if self.dtype == DFSS_F32 else torch.bfloat16
+        return torch.bfloat16 if self.dtype == DFSS_BF16 else torch.float32
 
     @property
     def meta_words(self) -> int:
         """uint16 metadata words per row: one 4-bit code per 8 bytes of dense data."""
-        return self.Lk // (8 if self.dtype == DFSS_F32 else 16)
+        return self.Lk // (16 if self.dtype == DFSS_BF16 else 8)
 
     def c(self) -> _CShape:
         return _CShape(self.B, self.H, self.Lq, self.Lk, self.d, self.N, self.M, self.dtype)

@@ -15,6 +15,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct Dims {
     int BH, H, Lq, Lk, d, mode;
     bool f32;      // the 4-byte mode: fp32 data, 1:2 only, staged kernels only
+    bool split;    // ... with products formed from bfloat16 pieces on the bf16 matrix pipe
     size_t elem() const { return f32 ? 4 : 2; }
 };
 
@@ -26,8 +27,8 @@ dfss_status check_shape(const dfss_shape *s, bool need_nm, Dims *out) {
     if (bh > 65535) return DFSS_ERR_SHAPE;
     if (s->Lq % 64 != 0 || s->Lk % 128 != 0) return DFSS_ERR_SHAPE;
     if (s->Lk > 8192 || s->Lq > (1 << 20)) return DFSS_ERR_SHAPE;
-    if (s->dtype != DFSS_BF16 && s->dtype != DFSS_F32) return DFSS_ERR_UNSUPPORTED;
-    const bool f32 = s->dtype == DFSS_F32;
+    if (s->dtype != DFSS_BF16 && s->dtype != DFSS_F32 && s->dtype != DFSS_F32_BF16X3) return DFSS_ERR_UNSUPPORTED;
+    const bool f32 = s->dtype != DFSS_BF16, split = s->dtype == DFSS_F32_BF16X3;
     if (s->d != 64 && s->d != 128) return DFSS_ERR_UNSUPPORTED;
     int mode = -1;
     if (need_nm) {
@@ -35,7 +36,7 @@ dfss_status check_shape(const dfss_shape *s, bool need_nm, Dims *out) {
         else if (s->N == 1 && s->M == 2) mode = 1;
         else return DFSS_ERR_UNSUPPORTED;
     }
-    if (out) *out = Dims{(int)bh, s->H, s->Lq, s->Lk, s->d, mode, f32};
+    if (out) *out = Dims{(int)bh, s->H, s->Lq, s->Lk, s->d, mode, f32, split};
     return DFSS_OK;
 }
 
@@ -54,6 +55,17 @@ inline bool staged_path_requested() {
     return v && strcmp(v, "staged") == 0;
 }
 inline dfss_status hip_status(hipError_t e) { return e == hipSuccess ? DFSS_OK : DFSS_ERR_HIP; }
+
+// stage 1 and stage 3 of the 4-byte mode, by the way the products are formed
+inline hipError_t sddmm_prune_f32(const Dims &D, const void *Q, const void *K, float scale, void *vals, void *meta,
+                                  hipStream_t st) {
+    return D.split ? dfss::launch_sddmm_prune_split(Q, K, D.BH, D.Lq, D.Lk, D.d, scale, vals, meta, st)
+                   : dfss::launch_sddmm_prune_f32(Q, K, D.BH, D.Lq, D.Lk, D.d, scale, vals, meta, st);
+}
+inline hipError_t spmm_f32(const Dims &D, const void *vals, const void *meta, const void *V, void *O, hipStream_t st) {
+    return D.split ? dfss::launch_spmm_split(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, st)
+                   : dfss::launch_spmm_f32(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, st);
+}
 
 }  // namespace
 
@@ -93,8 +105,7 @@ dfss_status dfss_sddmm_prune_bias(const void *Q, const void *K, const void *key_
         return DFSS_ERR_SHAPE;
     if (D.f32) {
         if (key_bias) return DFSS_ERR_UNSUPPORTED;
-        return hip_status(dfss::launch_sddmm_prune_f32(Q, K, D.BH, D.Lq, D.Lk, D.d, scale, vals, meta,
-                                                       (hipStream_t)stream));
+        return hip_status(sddmm_prune_f32(D, Q, K, scale, vals, meta, (hipStream_t)stream));
     }
     return hip_status(dfss::launch_sddmm_prune(Q, K, (const float *)key_bias, D.H, D.BH, D.Lq, D.Lk, D.d, D.mode,
                                                scale, vals, meta, (hipStream_t)stream));
@@ -120,7 +131,7 @@ dfss_status dfss_spmm(const void *vals, const void *meta, const void *V, const d
     if (!vals || !meta || !V || !O) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, true, &D)) return st;
     if (misaligned(vals) || misaligned(meta) || misaligned(V) || misaligned(O)) return DFSS_ERR_SHAPE;
-    if (D.f32) return hip_status(dfss::launch_spmm_f32(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, (hipStream_t)stream));
+    if (D.f32) return hip_status(spmm_f32(D, vals, meta, V, O, (hipStream_t)stream));
     return hip_status(dfss::launch_spmm(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, (hipStream_t)stream));
 }
 
@@ -140,9 +151,9 @@ dfss_status dfss_attention_bias(const void *Q, const void *K, const void *V, con
         if (key_bias) return DFSS_ERR_UNSUPPORTED;
         char *vals = static_cast<char *>(ws);
         char *meta = vals + align_up(dfss_vals_bytes(s));
-        hipError_t e = dfss::launch_sddmm_prune_f32(Q, K, D.BH, D.Lq, D.Lk, D.d, scale, vals, meta, st);
+        hipError_t e = sddmm_prune_f32(D, Q, K, scale, vals, meta, st);
         if (e == hipSuccess) e = dfss::launch_row_softmax_f32(vals, (long)D.BH * D.Lq, D.Lk / 2, st);
-        if (e == hipSuccess) e = dfss::launch_spmm_f32(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, st);
+        if (e == hipSuccess) e = spmm_f32(D, vals, meta, V, O, st);
         return hip_status(e);
     }
     if (!staged_path_requested())
@@ -191,9 +202,12 @@ dfss_status dense_attention_bias(const void *Q, const void *K, const void *V, co
     hipStream_t st = (hipStream_t)stream;
     if (D.f32) {
         if (key_bias) return DFSS_ERR_UNSUPPORTED;
-        hipError_t e = dfss::launch_dense_scores_f32(Q, K, D.BH, D.Lq, D.Lk, D.d, scale, ws, st);
+        hipError_t e = D.split ? dfss::launch_dense_scores_split(Q, K, D.BH, D.Lq, D.Lk, D.d, scale, ws, st)
+                               : dfss::launch_dense_scores_f32(Q, K, D.BH, D.Lq, D.Lk, D.d, scale, ws, st);
         if (e == hipSuccess) e = dfss::launch_row_softmax_f32(ws, (long)D.BH * D.Lq, D.Lk, st);
-        if (e == hipSuccess) e = dfss::launch_dense_av_f32(ws, V, D.BH, D.Lq, D.Lk, D.d, O, st);
+        if (e == hipSuccess)
+            e = D.split ? dfss::launch_dense_av_split(ws, V, D.BH, D.Lq, D.Lk, D.d, O, st)
+                        : dfss::launch_dense_av_f32(ws, V, D.BH, D.Lq, D.Lk, D.d, O, st);
         return hip_status(e);
     }
     hipError_t e = dfss::launch_dense_scores(Q, K, (const float *)key_bias, D.H, D.BH, D.Lq, D.Lk, D.d, scale, ws, st);

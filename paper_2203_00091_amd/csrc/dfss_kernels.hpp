@@ -44,6 +44,16 @@ hipError_t launch_row_softmax_f32(void *x, long rows, int cols, hipStream_t st);
 hipError_t launch_spmm_f32(const void *vals, const void *meta, const void *V, int BH, int Lq, int Lk, int d, void *O,
                            hipStream_t st);
 hipError_t launch_dense_av_f32(const void *P, const void *V, int BH, int Lq, int Lk, int d, void *O, hipStream_t st);
+// The same four operations with every fp32 product formed from bfloat16 pieces on the bf16 matrix pipe
+// (x = hi + lo; a.b ~ a_hi b_hi + a_hi b_lo + a_lo b_hi, fp32 accumulation); same layouts.
+hipError_t launch_sddmm_prune_split(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale,
+                                    void *vals, void *meta, hipStream_t st);
+hipError_t launch_dense_scores_split(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale,
+                                     void *S, hipStream_t st);
+hipError_t launch_spmm_split(const void *vals, const void *meta, const void *V, int BH, int Lq, int Lk, int d,
+                             void *O, hipStream_t st);
+hipError_t launch_dense_av_split(const void *P, const void *V, int BH, int Lq, int Lk, int d, void *O,
+                                 hipStream_t st);
 // Metadata word order: library <-> canonical.
 hipError_t launch_meta_reorder(const void *src, void *dst, int BH, int Lq, int W, bool to_canonical,
                                hipStream_t st);

@@ -56,7 +56,8 @@ def test_sizes_follow_the_compressed_footprint():
     Shape(1, 1, 128, 128, 64, 3, 4),  # N:M not implemented
     Shape(1, 1, 128, 128, 96),       # head size not implemented
     Shape(1, 1, 128, 128, 64, 2, 4, 1),  # 2:4 on float data: not a mode of the method (Sec. 2.3)
-    Shape(1, 1, 128, 128, 64, 1, 2, 2),  # dtype not implemented
+    Shape(1, 1, 128, 128, 64, 2, 4, 2),  # ... whichever way its products are formed
+    Shape(1, 1, 128, 128, 64, 1, 2, 3),  # dtype not implemented
     Shape(300, 300, 128, 128, 64),   # too many heads for one launch
     Shape(1, 1, 128, 16384, 64),     # rows longer than the softmax kernel holds
 ])

@@ -9,6 +9,12 @@ Bars:
     d * 2^-24 * sum_k |q_k k_k|, plus one rounding for the multiplication by scale;
   * softmax and SpMM stages, fed with the GPU's own stage-1 output, within fp32 rounding of the oracle;
   * whole path within 2e-2 of the oracle everywhere and within 1e-4 on rows whose selection agrees.
+
+Every test runs for both ways of forming the products: DFSS_F32 (fp32 matrix instruction) and DFSS_F32_BF16X3
+(each operand split as x = hi + lo, hi = bf16(x), lo = bf16(x - hi); a*b ~ hi*hi + hi*lo + lo*hi).  For the
+second the bound gains the dropped terms: |x - hi - lo| <= 2^-18 |x| and |lo| <= 2^-9 |x| (1 + 2^-9), so
+a*b - (three products) = a_lo b_lo + r_a b + a r_b is at most 3.01 * 2^-18 |a b|; three times as many terms
+are accumulated.  Integer-valued inputs have lo = 0: the bit-exact bar is unchanged.
 """
 import math
 
@@ -18,9 +24,11 @@ import torch
 
 import oracle
 import paper_2203_00091_amd as dfss
-from paper_2203_00091_amd import DFSS_F32, Shape, synth
+from paper_2203_00091_amd import DFSS_F32, DFSS_F32_BF16X3, Shape, synth
 
 pytestmark = pytest.mark.gpu
+
+DTYPES = pytest.mark.parametrize("dtype", [DFSS_F32, DFSS_F32_BF16X3], ids=["fp32_mfma", "bf16x3"])
 
 DEV = "cuda:0"
 U = 2.0 ** -24   # unit roundoff of fp32
@@ -34,15 +42,23 @@ def _meta_np(meta, s):
     return meta.cpu().numpy().view(np.uint16).reshape(s.BH, s.Lq, s.meta_words)
 
 
-def _shape(B, H, Lq, Lk, d):
-    return Shape(B, H, Lq, Lk, d, 1, 2, DFSS_F32)
+def _shape(B, H, Lq, Lk, d, dtype=DFSS_F32):
+    return Shape(B, H, Lq, Lk, d, 1, 2, dtype)
 
 
-def _score_error_bound(Q, K, scale):
-    """Per-element bound on |computed - exact| of scale * q.k for fp32 accumulation in any order."""
+def _score_error_bound(Q, K, scale, dtype=DFSS_F32):
+    """Per-element bound on |computed - exact| of scale * q.k for fp32 accumulation in any order
+    (plus the dropped terms of the bf16 split where the products are formed that way)."""
     d = Q.shape[-1]
     absdot = np.abs(Q).astype(np.float64) @ np.abs(K).astype(np.float64).T
+    if dtype == DFSS_F32_BF16X3:
+        return (3.01 * 2.0 ** -18 * absdot + 3 * d * U * absdot + U * absdot) * scale
     return (d * U * absdot + U * absdot) * scale
+
+
+# whole-path and SpMM tolerances: fp32 rounding, resp. the split's dropped terms (3.01 * 2^-18 per product)
+TOL_SPMM = {DFSS_F32: 1e-5, DFSS_F32_BF16X3: 3e-5}
+TOL_O = {DFSS_F32: 1e-4, DFSS_F32_BF16X3: 5e-4}
 
 
 @pytest.mark.parametrize("BH,Lq,Lk,d,scale", [
@@ -52,9 +68,10 @@ def _score_error_bound(Q, K, scale):
     (1, 64, 128, 128, float(np.float32(1 / math.sqrt(128)))),   # smallest legal shape, scale not a power of two
     (1, 64, 8192, 64, 0.125),                                   # longest key sequence
 ])
-def test_stage1_bit_exact_on_integer_inputs(BH, Lq, Lk, d, scale):
+@DTYPES
+def test_stage1_bit_exact_on_integer_inputs(BH, Lq, Lk, d, scale, dtype):
     Q, K, _ = synth.integer_qkv(BH, Lq, Lk, d, seed=6100 + Lq + d, dtype=torch.float32)
-    s = _shape(1, BH, Lq, Lk, d)
+    s = _shape(1, BH, Lq, Lk, d, dtype)
     vals, meta = dfss.dfss_sddmm_prune(_dev(Q), _dev(K), s, scale)
     torch.cuda.synchronize()
     vals, meta = vals.cpu().numpy(), _meta_np(meta, s)
@@ -68,10 +85,11 @@ def test_stage1_bit_exact_on_integer_inputs(BH, Lq, Lk, d, scale):
     assert ties > 0   # the tie rule was exercised
 
 
-def test_stage1_all_equal_scores_keep_the_first():
+@DTYPES
+def test_stage1_all_equal_scores_keep_the_first(dtype):
     Q = torch.zeros(1, 64, 64)
     K = torch.ones(1, 128, 64)
-    s = _shape(1, 1, 64, 128, 64)
+    s = _shape(1, 1, 64, 128, 64, dtype)
     vals, meta = dfss.dfss_sddmm_prune(_dev(Q), _dev(K), s, 0.125)
     torch.cuda.synchronize()
     assert np.all(_meta_np(meta, s) == 0x4444) and np.all(vals.cpu().numpy() == 0)
@@ -88,10 +106,11 @@ def test_meta_conversions_are_copies():
 
 
 @pytest.mark.parametrize("name", ["tiny_1to2_f32", "bert_base_L512_1to2_f32", "large_head_L2048_d128_1to2_f32"])
-def test_stages_on_gaussian_inputs(name):
+@DTYPES
+def test_stages_on_gaussian_inputs(name, dtype):
     w = synth.WORKLOADS[name]
     Q, K, V = synth.make(w)
-    s = _shape(w.B, w.H, w.L, w.L, w.d)
+    s = _shape(w.B, w.H, w.L, w.L, w.d, dtype)
     vals, meta = dfss.dfss_sddmm_prune(_dev(Q), _dev(K), s, w.scale)
     torch.cuda.synchronize()
     scores_gpu = vals.cpu().numpy()
@@ -108,7 +127,7 @@ def test_stages_on_gaussian_inputs(name):
         S = oracle.scores(Qn, Kn, w.scale)
         _, ovals, okidx = oracle.prune(S, 1, 2)
         kidx = oracle.decode_meta_f32(meta_np[h], w.L)        # raises on any code other than 0x4 / 0xE
-        bound = _score_error_bound(Qn, Kn, w.scale)
+        bound = _score_error_bound(Qn, Kn, w.scale, dtype)
         # stage 1: the score each side kept, and where they chose differently
         err_kept = np.abs(scores_gpu[h] - np.take_along_axis(S, kidx, 1))
         assert np.all(err_kept <= 2 * np.take_along_axis(bound, kidx, 1) + 1e-12)
@@ -123,15 +142,16 @@ def test_stages_on_gaussian_inputs(name):
         assert np.abs(P[h] - Pref).max() <= 1e-6
         assert np.abs(P[h].sum(-1) - 1).max() <= 1e-5
         Oref = oracle.spmm(P[h], kidx, Vn)
-        assert np.abs(O[h] - Oref).max() <= 1e-5 * max(1.0, float(np.abs(Vn).max()))
+        assert np.abs(O[h] - Oref).max() <= TOL_SPMM[dtype] * max(1.0, float(np.abs(Vn).max()))
     assert differ_total <= 1e-3 * pairs
 
 
 @pytest.mark.parametrize("BH,Lq,Lk,d", [(2, 128, 256, 64), (2, 64, 384, 128), (1, 192, 128, 64)])
-def test_attention_and_dense_baseline(BH, Lq, Lk, d):
+@DTYPES
+def test_attention_and_dense_baseline(BH, Lq, Lk, d, dtype):
     Q, K, V = synth.gaussian_qkv(BH, Lq, Lk, d, 1.0, seed=6300 + Lq + d, dtype=torch.float32)
     scale = 1 / math.sqrt(d)
-    s = _shape(1, BH, Lq, Lk, d)
+    s = _shape(1, BH, Lq, Lk, d, dtype)
     O = dfss.dfss_attention(_dev(Q), _dev(K), _dev(V), s, scale)
     Od = dfss.dense_attention(_dev(Q), _dev(K), _dev(V), s, scale)
     torch.cuda.synchronize()
@@ -142,19 +162,20 @@ def test_attention_and_dense_baseline(BH, Lq, Lk, d):
     # rows whose selection cannot have differed (no pair inside the rounding error): fp32 accuracy
     for h in range(BH):
         S = oracle.scores(Qn[h], Kn[h], scale)
-        bound = _score_error_bound(Qn[h], Kn[h], scale)
+        bound = _score_error_bound(Qn[h], Kn[h], scale, dtype)
         safe = (np.abs(S[:, 0::2] - S[:, 1::2]) > 2 * (bound[:, 0::2] + bound[:, 1::2])).all(-1)
         assert safe.sum() > Lq // 2
-        assert np.abs(O[h] - ref[h])[safe].max() <= 1e-4
+        assert np.abs(O[h] - ref[h])[safe].max() <= TOL_O[dtype]
     # full attention (Eq. 1): N = M in the oracle
     refd = oracle.attention(Qn, Kn, Vn, 2, 2, scale, store_bf16=False)
-    assert np.abs(Od - refd).max() <= 1e-4
+    assert np.abs(Od - refd).max() <= TOL_O[dtype]
 
 
-def test_stage_calls_compose_to_attention():
+@DTYPES
+def test_stage_calls_compose_to_attention(dtype):
     w = synth.WORKLOADS["tiny_1to2_f32"]
     Q, K, V = (_dev(t) for t in synth.make(w))
-    s = _shape(w.B, w.H, w.L, w.L, w.d)
+    s = _shape(w.B, w.H, w.L, w.L, w.d, dtype)
     vals, meta = dfss.dfss_sddmm_prune(Q, K, s, w.scale)
     O1 = dfss.dfss_spmm(dfss.dfss_sparse_softmax(vals, s), meta, V, s)
     O2 = dfss.dfss_attention(Q, K, V, s, w.scale)
@@ -162,10 +183,11 @@ def test_stage_calls_compose_to_attention():
     assert torch.equal(O1, O2)
 
 
-def test_unsupported_combinations_are_refused():
-    s24 = Shape(1, 1, 64, 128, 64, 2, 4, DFSS_F32)
+@DTYPES
+def test_unsupported_combinations_are_refused(dtype):
+    s24 = Shape(1, 1, 64, 128, 64, 2, 4, dtype)
     assert dfss.dfss_vals_bytes(s24) == 0
-    s = _shape(1, 1, 64, 128, 64)
+    s = _shape(1, 1, 64, 128, 64, dtype)
     Q = torch.zeros(1, 64, 64, device=DEV)
     K = torch.zeros(1, 128, 64, device=DEV)
     with pytest.raises(dfss.DfssError):
@@ -174,3 +196,16 @@ def test_unsupported_combinations_are_refused():
         dfss.dfss_attention_bias(Q, K, K, torch.zeros(1, 128, device=DEV), s, 0.125)
     with pytest.raises(ValueError):          # bfloat16 tensors with a float shape
         dfss.dfss_attention(Q.bfloat16(), K.bfloat16(), K.bfloat16(), s, 0.125)
+
+
+def test_split_products_equal_fp32_on_bf16_exact_operands():
+    """Operands that are exact in bfloat16 have lo = 0: both ways of forming the products then agree bit
+    for bit in stage 1 whenever the fp32 sums are exact (small integers)."""
+    Q, K, _ = synth.integer_qkv(2, 128, 256, 64, seed=6400, dtype=torch.float32)
+    out = []
+    for dtype in (DFSS_F32, DFSS_F32_BF16X3):
+        s = _shape(1, 2, 128, 256, 64, dtype)
+        vals, meta = dfss.dfss_sddmm_prune(_dev(Q), _dev(K), s, 0.125)
+        torch.cuda.synchronize()
+        out.append((vals.cpu(), meta.cpu()))
+    assert torch.equal(out[0][0], out[1][0]) and torch.equal(out[0][1], out[1][1])
