@@ -16,7 +16,8 @@ the named workload.  Prints ONE JSON line.
 Workloads whose name ends in ``_f32`` run the paper's second precision (float data, 1:2): there
 ``dfss_attention`` is the three stage kernels, the full-attention baseline is the three-stage
 ``dense_attention``, and the roofline object describes the score/prune kernel (the largest of the
-three) against the fp32 MFMA peak.
+three): against HBM with the default ``--products bf16x3`` (fp32 products formed from bfloat16 pieces
+on the bf16 matrix pipe), against the fp32 MFMA peak with ``--products fp32``.
 
 Inputs are resident in HBM before timing starts.  By default the steps rotate over enough
 independent buffer sets that no step finds its inputs or workspace in the last-level cache
@@ -62,6 +63,9 @@ def parse_args():
     ap.add_argument("--backward", action="store_true",
                     help="also time dfss_attention_backward (gradients through the fixed selection) on the "
                          "results of the three forward stages; reported under extra")
+    ap.add_argument("--products", choices=("fp32", "bf16x3"), default="bf16x3",
+                    help="float workloads only: form the fp32 products on the fp32 matrix instruction (DFSS_F32) or "
+                         "from bfloat16 pieces on the bf16 matrix pipe (DFSS_F32_BF16X3, the default)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 64 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
@@ -89,7 +93,9 @@ def main():
 
     w = synth.WORKLOADS[args.workload]
     f32 = w.float32
-    s = Shape(w.B, w.H, w.L, w.L, w.d, w.N, w.M, dfss.DFSS_F32 if f32 else dfss.DFSS_BF16)
+    split = f32 and args.products == "bf16x3"
+    s = Shape(w.B, w.H, w.L, w.L, w.d, w.N, w.M,
+              (dfss.DFSS_F32_BF16X3 if split else dfss.DFSS_F32) if f32 else dfss.DFSS_BF16)
     if f32 and (args.key_padding or args.block_pattern or args.backward):
         print("bench.py: the float workloads run the plain forward pass only", file=sys.stderr)
         sys.exit(2)
@@ -280,6 +286,7 @@ def main():
         "dtype": "f32" if f32 else "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "L": L, "d": d, "N": w.N, "M": w.M,
+                   "products": (args.products if f32 else "bf16"),
                    "key_padding": bool(args.key_padding),
                    "block_pattern": (f"window +-1, 1 global, 2 random blocks of 64 x 64, density {density:.3f}"
                                      if args.block_pattern else None), "buffer_sets": nsets, "cache": "warm" if args.warm else "cold (rotating buffer sets)",
@@ -306,7 +313,8 @@ def main():
                                               for k, v in kernels.items()},
             "sddmm_prune_tflops": round(2.0 * BH * L * L * d / (k1 * 1e-3) / 1e12, 2),
             "sddmm_prune_frac_of_mfma_peak": round(2.0 * BH * L * L * d / (k1 * 1e-3) / 1e12
-                                                   / (MFMA_F32_PEAK_TFLOPS if f32 else MFMA_BF16_PEAK_TFLOPS), 4),
+                                                   / (MFMA_F32_PEAK_TFLOPS if f32 and not split
+                                                      else MFMA_BF16_PEAK_TFLOPS), 4),
         },
     }
     if f32:
@@ -314,11 +322,20 @@ def main():
         # instruction: 2 L^2 d flops per head per launch
         flops1 = 2.0 * BH * L * L * d
         ach1 = flops1 / (k1 * 1e-3) / 1e12
-        out["roofline"] = {"bound": "mfma", "kernel": "k_scores_f32 (dfss_sddmm_prune, float data)",
-                           "achieved": round(ach1, 2), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                           "frac": round(ach1 / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
-                           "algorithmic_hbm_bytes_per_launch": bytes1, "avg_launch_ms": round(k1, 5),
-                           "algorithmic_flops_per_launch": flops1}
+        if split:
+            # on the bf16 matrix pipe the kernel is bound by writing the kept scores and the metadata
+            gbs1 = bytes1 / (k1 * 1e-3) / 1e9
+            out["roofline"] = {"bound": "hbm", "kernel": "k_scores_split (dfss_sddmm_prune, float data, bf16x3 products)",
+                               "achieved": round(gbs1, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                               "frac": round(gbs1 / HBM_PEAK_GBS, 4), "traffic": None,
+                               "algorithmic_hbm_bytes_per_launch": bytes1, "avg_launch_ms": round(k1, 5),
+                               "algorithmic_flops_per_launch": flops1}
+        else:
+            out["roofline"] = {"bound": "mfma", "kernel": "k_scores_f32 (dfss_sddmm_prune, float data)",
+                               "achieved": round(ach1, 2), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                               "frac": round(ach1 / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
+                               "algorithmic_hbm_bytes_per_launch": bytes1, "avg_launch_ms": round(k1, 5),
+                               "algorithmic_flops_per_launch": flops1}
         out["extra"]["spmm_dense_equivalent_tflops"] = round(flops1 / (k3 * 1e-3) / 1e12, 2)
 
     if args.backward and block_mask is None:

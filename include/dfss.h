@@ -190,9 +190,12 @@ dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K
  * Metadata: a float fills two consecutive 2-byte slots of a run of four, so a run is one aligned
  * pair of keys and only two codes occur, the ones App. A.1.1 prints: 0x4 = the first float of the
  * pair is kept, 0xE = the second.  uint16 [B*H, Lq, Lk/8], word w of a row = codes of pairs
- * 4w..4w+3, pair 4w+k at bits [4k, 4k+3] -- again 1/16 of the dense matrix in bits.  The library
- * holds these words in exactly this (canonical) order; dfss_meta_to_canonical and
- * dfss_meta_from_canonical are plain copies in this mode.
+ * 4w..4w+3, pair 4w+k at bits [4k, 4k+3] -- again 1/16 of the dense matrix in bits.  That is the
+ * canonical order; the library holds the words pairwise as 32-bit words (word v of a row = keys
+ * 16v..16v+15), rows in blocks of 16, keys in blocks of 64:
+ *   lib32[bh][r/16][v/4][r%16][v%4] = canon32[bh][r][v]
+ * (the blocking of the 2-byte modes without their slot permutation); dfss_meta_to_canonical and
+ * dfss_meta_from_canonical convert.
  * DFSS_F32_BF16X3 is the same mode (same arrays, layouts, calls and restrictions) with the products
  * formed on the bfloat16 matrix pipe, the analogue of the paper's reduced-mantissa multiplication
  * (App. A.1.2): each fp32 operand is split as x = hi + lo with hi = bf16(x), lo = bf16(x - hi), and

@@ -286,18 +286,13 @@ size_t dfss_backward_workspace_bytes(const dfss_shape *s) {
     return v ? align_up(v) : 0;
 }
 
-// The metadata of the 4-byte mode is kept in canonical order: the conversions are plain copies.
-static dfss_status copy_meta(const void *src, void *dst, const dfss_shape *s, void *stream) {
-    return hip_status(hipMemcpyAsync(dst, src, dfss_meta_bytes(s), hipMemcpyDeviceToDevice, (hipStream_t)stream));
-}
-
 dfss_status dfss_meta_to_canonical(const void *meta, const dfss_shape *s, void *canon, void *stream) {
     Dims D;
     if (!meta || !canon) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, true, &D)) return st;
     if (misaligned(meta) || misaligned(canon)) return DFSS_ERR_SHAPE;
-    if (D.f32) return copy_meta(meta, canon, s, stream);
-    return hip_status(dfss::launch_meta_reorder(meta, canon, D.BH, D.Lq, D.Lk / 32, true, (hipStream_t)stream));
+    return hip_status(dfss::launch_meta_reorder(meta, canon, D.BH, D.Lq, D.Lk / (D.f32 ? 16 : 32), true, !D.f32,
+                                                (hipStream_t)stream));
 }
 
 dfss_status dfss_meta_from_canonical(const void *canon, const dfss_shape *s, void *meta, void *stream) {
@@ -305,8 +300,8 @@ dfss_status dfss_meta_from_canonical(const void *canon, const dfss_shape *s, voi
     if (!meta || !canon) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, true, &D)) return st;
     if (misaligned(meta) || misaligned(canon)) return DFSS_ERR_SHAPE;
-    if (D.f32) return copy_meta(canon, meta, s, stream);
-    return hip_status(dfss::launch_meta_reorder(canon, meta, D.BH, D.Lq, D.Lk / 32, false, (hipStream_t)stream));
+    return hip_status(dfss::launch_meta_reorder(canon, meta, D.BH, D.Lq, D.Lk / (D.f32 ? 16 : 32), false, !D.f32,
+                                                (hipStream_t)stream));
 }
 
 const char *dfss_status_string(dfss_status st) {

@@ -35,7 +35,7 @@ hipError_t launch_spmm_t(const void *vals, const void *meta, const void *X, int 
 hipError_t launch_masked_sddmm_ds(const void *dO, const void *V, const void *O, const void *P, const void *meta,
                                   int BH, int Lq, int Lk, int d, float scale, void *dS, hipStream_t st);
 // The 4-byte mode (Sec. 2.3: float data, 1:2): fp32 Q, K, V, kept scores, weights and O; metadata = one
-// 4-bit code per kept float in canonical word order, uint16 [BH, Lq, Lk/8].
+// 4-bit code per kept float, 32-bit words in the blocked order [BH, Lq/16, Lk/64, 16, 4].
 hipError_t launch_sddmm_prune_f32(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale,
                                   void *vals, void *meta, hipStream_t st);
 hipError_t launch_dense_scores_f32(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale, void *S,
@@ -54,8 +54,9 @@ hipError_t launch_spmm_split(const void *vals, const void *meta, const void *V, 
                              void *O, hipStream_t st);
 hipError_t launch_dense_av_split(const void *P, const void *V, int BH, int Lq, int Lk, int d, void *O,
                                  hipStream_t st);
-// Metadata word order: library <-> canonical.
-hipError_t launch_meta_reorder(const void *src, void *dst, int BH, int Lq, int W, bool to_canonical,
+// Metadata word order: library <-> canonical.  W = 32-bit words per row; permute: the 2-byte modes' order of
+// the four words of a (row, block), false for the 4-byte mode.
+hipError_t launch_meta_reorder(const void *src, void *dst, int BH, int Lq, int W, bool to_canonical, bool permute,
                                hipStream_t st);
 
 }  // namespace dfss

@@ -15,8 +15,10 @@
 // 32-bit metadata word per block, or 64 contiguous bytes of the dense row.
 //
 // Metadata of this mode: one 4-bit code per kept float (0x4 = first of the pair, 0xE = second),
-// the code of pair p of a row at bits [4(p%4), 4(p%4)+3] of uint16 word p/4; words are stored in
-// that canonical order (a lane's 8 codes are exactly one aligned pair of words).
+// the code of pair p of a row at bits [4(p%4), 4(p%4)+3] of uint16 word p/4.  A lane's 8 codes are
+// one aligned pair of words = one 32-bit word; the 32-bit words are stored blocked,
+// [BH, Lq/16, Lk/64, 16 rows, 4 words], so that the 16 rows x 16 bytes a wave produces per block are
+// 256 contiguous bytes (16-byte pieces of 16 rows cost a partial-line write each).
 #include "dfss_device.hpp"
 #include "dfss_kernels.hpp"
 
@@ -94,7 +96,8 @@ __global__ __launch_bounds__(NT, 2) void k_scores_f32(const float *__restrict__ 
     };
 
     float *orow = out + ((size_t)bh * Lq + q) * (PRUNE ? Lk / 2 : Lk);
-    uint32_t *mrow = PRUNE ? meta + ((size_t)bh * Lq + q) * (Lk / 16) : nullptr;
+    // metadata word of (row group, block jb, row n, lane group g)
+    uint32_t *mrow = PRUNE ? meta + ((size_t)bh * (Lq / 16) + (q >> 4)) * nkb * 64 + n * 4 + g : nullptr;
 
     issue_block(0);
     for (int jb = 0; jb < nkb; ++jb) {
@@ -138,7 +141,7 @@ __global__ __launch_bounds__(NT, 2) void k_scores_f32(const float *__restrict__ 
             f32x4 *vp = reinterpret_cast<f32x4 *>(orow + jb * (KB / 2) + 8 * g);
             vp[0] = kept[0];
             vp[1] = kept[1];
-            mrow[jb * 4 + g] = word;
+            mrow[jb * 64] = word;
         } else {
             f32x4 *sp = reinterpret_cast<f32x4 *>(orow + jb * KB + 16 * g);
 #pragma unroll
@@ -193,12 +196,12 @@ __global__ __launch_bounds__(NT, 2) void k_av_f32(const float *__restrict__ A, c
     };
 
     const float *arow = A + ((size_t)bh * Lq + q) * (SPARSE ? Lk / 2 : Lk) + (SPARSE ? 8 : 16) * g;
-    const uint32_t *mrow = SPARSE ? meta + ((size_t)bh * Lq + q) * (Lk / 16) + g : nullptr;
+    const uint32_t *mrow = SPARSE ? meta + ((size_t)bh * (Lq / 16) + (q >> 4)) * nkb * 64 + n * 4 + g : nullptr;
     auto load_a = [&](int jb, f32x4 (&a)[NA], uint32_t &w) {
         const f32x4 *ap = reinterpret_cast<const f32x4 *>(arow + jb * (SPARSE ? KB / 2 : KB));
 #pragma unroll
         for (int c = 0; c < NA; ++c) a[c] = ap[c];
-        if constexpr (SPARSE) w = mrow[jb * 4];
+        if constexpr (SPARSE) w = mrow[jb * 64];
     };
 
     f32x4 acc[DS];

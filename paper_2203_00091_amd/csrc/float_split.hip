@@ -8,9 +8,11 @@
 // mantissa bits than the paper's own multiplication format keeps.  Integer-valued inputs up to 256 have
 // lo = 0 and give exactly the fp32 result.
 //
-// Blocks of K (or V) arrive in LDS as fp32 by asynchronous copies; the workgroup converts each block
-// once into its two bf16 images, which the waves then read as ordinary bf16 matrix operands.  The
-// layouts, the 1:2 epilogue and the metadata are those of the exact fp32 kernels (float_mode.hip).
+// The workgroup converts each 64-row block of K (or V) once: every thread loads its 32-byte pieces of the
+// fp32 block into registers one block ahead, splits them, and writes the two bf16 images into LDS (double
+// buffered), which the waves then read as ordinary bf16 matrix operands -- one barrier per block, and the
+// conversion of block j+1 sits next to the matrix instructions of block j.  The layouts, the 1:2
+// epilogue and the metadata are those of the exact fp32 kernels (float_mode.hip).
 #include "dfss_device.hpp"
 #include "dfss_kernels.hpp"
 
@@ -18,8 +20,8 @@ namespace dfss {
 
 namespace {
 
-constexpr int NT = 256;   // 4 waves, 16 queries each
-constexpr int QT = 64;    // queries per workgroup
+constexpr int NT = 256;   // 4 waves
+constexpr int QT = 64;    // queries per workgroup (A V kernel; the score kernel takes 64 NQ)
 constexpr int KB = 64;    // keys per block
 
 // x[0..7] -> bf16 images (hi, lo), element e in the low/high half of dword e/2
@@ -44,42 +46,39 @@ __device__ __forceinline__ f32x4 mfma_split(const u32x4 &ah, const u32x4 &al, co
     return mfma16(as_bf16x8(ah), as_bf16x8(bh), acc);
 }
 
-// Asynchronous copy of one 64-row fp32 block (rows of D floats, contiguous in memory) into LDS, in
-// memory order: 16 D bytes per wave instruction.
-template <int D>
-struct BlockCopy {
-    static constexpr int NCOPY = KB * D * 4 / (NT * 16);
-    uint64_t base;
-    uint32_t lds, lane_off;
-    int wave;
-    __device__ void issue(int jb) const {
-        const uint64_t b = base + (uint64_t)jb * (KB * D * 4);
+// One thread's share of a 64-row fp32 block (rows of D floats, contiguous in memory): NCONV pieces of 8
+// floats, piece i = the 8 floats at float offset 8 * (i * NT + tid) of the block.
+template <int NCONV>
+struct RawBlock {
+    f32x4 v[NCONV][2];
+    __device__ __forceinline__ void load(const float *block, int tid) {
 #pragma unroll
-        for (int c = 0; c < NCOPY; ++c) {
-            const uint32_t piece = (uint32_t)(c * 4 + wave) * 1024u;
-            async_copy16(b, piece + lane_off, lds + piece);
+        for (int i = 0; i < NCONV; ++i) {
+            const f32x4 *p = reinterpret_cast<const f32x4 *>(block + 8 * (i * NT + tid));
+            v[i][0] = p[0];
+            v[i][1] = p[1];
         }
     }
 };
 
 // ---------------------------------------------------------------------------------------------
 // Scores.  PRUNE: 1:2 selection, kept fp32 scores [BH, Lq, Lk/2] + metadata words; else S fp32.
-// Per 64-key block: (1) wait for the fp32 copy, barrier; (2) every thread converts its share of the
-// block to the two bf16 images, stored at the permuted row (so that a lane ends up with 16 consecutive
-// keys, as in the fp32 kernel) with the 16-byte chunks XOR-swizzled by row; barrier; (3) the copy of the
-// next block is issued (the fp32 buffer is free again) and the waves run 3 matrix instructions per
-// 16 x 16 x 32 product piece, then the epilogue.
+// Per 64-key block j, after the barrier: every thread converts its share of block j+1 (loaded during block
+// j-1) to the two bf16 images, stored at the permuted row (so that a lane ends up with 16 consecutive
+// keys, as in the fp32 kernel) with the 16-byte chunks XOR-swizzled by row; loads its share of block j+2;
+// then the waves run 3 matrix instructions per 16 x 16 x 32 product piece of block j, and the epilogue.
 // ---------------------------------------------------------------------------------------------
-template <int D, bool PRUNE>
+// A wave owns NQ groups of 16 queries: the conversion of a block and the reads of its images are
+// shared by NQ times as many matrix instructions.
+template <int D, bool PRUNE, int NQ>
 __global__ __launch_bounds__(NT, 2) void k_scores_split(const float *__restrict__ Q, const float *__restrict__ K,
                                                         int Lq, int Lk, float scale, float *__restrict__ out,
                                                         uint32_t *__restrict__ meta) {
     constexpr int CPR = D / 8;                   // 16-byte chunks per bf16 row
     constexpr int KS = D / 32;                   // contraction steps of 32
     constexpr int NCONV = KB * CPR / NT;         // bf16 chunks each thread converts per block
-    constexpr int NSTORE = PRUNE ? 3 : 4;        // vector stores per lane per block
-    __shared__ __attribute__((aligned(16))) float Kf[KB * D];
-    __shared__ u32x4 Kh[KB * CPR], Kl[KB * CPR];
+    constexpr int QT = 64 * NQ;                  // queries per workgroup
+    __shared__ u32x4 Kh[2][KB * CPR], Kl[2][KB * CPR];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, g = lane >> 4;
@@ -87,76 +86,92 @@ __global__ __launch_bounds__(NT, 2) void k_scores_split(const float *__restrict_
     const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
     const unsigned bh = item / nqt, qt = item % nqt;
     const int nkb = Lk / KB;
-    const int q = qt * QT + wave * 16 + n;
+    const int q = qt * QT + wave * (16 * NQ) + n;     // first of this lane's NQ queries (16 apart)
 
-    // B operand: query q, k = 32 s + 8 g + e
-    u32x4 qh[KS], ql[KS];
-    {
-        const f32x4 *qp = reinterpret_cast<const f32x4 *>(Q + ((size_t)bh * Lq + q) * D + 8 * g);
+    // B operand: query q + 16 j, k = 32 s + 8 g + e
+    u32x4 qh[NQ][KS], ql[NQ][KS];
 #pragma unroll
-        for (int s = 0; s < KS; ++s) split8(qp[8 * s], qp[8 * s + 1], qh[s], ql[s]);
+    for (int j = 0; j < NQ; ++j) {
+        const f32x4 *qp = reinterpret_cast<const f32x4 *>(Q + ((size_t)bh * Lq + q + 16 * j) * D + 8 * g);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) split8(qp[8 * s], qp[8 * s + 1], qh[j][s], ql[j][s]);
     }
 
-    const BlockCopy<D> copy{uniform_address(K + (size_t)bh * Lk * D), lds_address(&Kf[0]), (uint32_t)lane * 16u, wave};
-
-    float *orow = out + ((size_t)bh * Lq + q) * (PRUNE ? Lk / 2 : Lk);
-    uint32_t *mrow = PRUNE ? meta + ((size_t)bh * Lq + q) * (Lk / 16) : nullptr;
-
-    copy.issue(0);
-    for (int jb = 0; jb < nkb; ++jb) {
-        // the copy of block jb is older than the stores of block jb-1: leave those in flight
-        if (jb == 0) wait_async_copies();
-        else wait_async_copies_keep<NSTORE>();
-        __syncthreads();            // fp32 block landed; every wave is done with the bf16 images of block jb-1
+    const float *kblocks = K + (size_t)bh * Lk * D;
+    // where this thread's pieces go: piece idx = (key, c); row of the matrix tile that holds this key:
+    // tile (key/4)%4, row 4*(key/16) + key%4
+    int dst[NCONV];
+#pragma unroll
+    for (int i = 0; i < NCONV; ++i) {
+        const int idx = i * NT + tid;
+        const int key = idx / CPR, c = idx % CPR;
+        const int slot = 16 * ((key >> 2) & 3) + 4 * (key >> 4) + (key & 3);
+        dst[i] = slot * CPR + (c ^ (slot & 7));
+    }
+    auto convert = [&](const RawBlock<NCONV> &raw, int buf) {
 #pragma unroll
         for (int i = 0; i < NCONV; ++i) {
-            const int idx = i * NT + tid;
-            const int key = idx / CPR, c = idx % CPR;
-            const f32x4 *src = reinterpret_cast<const f32x4 *>(&Kf[key * D + 8 * c]);
             u32x4 h, l;
-            split8(src[0], src[1], h, l);
-            // row of the matrix tile that holds this key: tile (key/4)%4, row 4*(key/16) + key%4
-            const int slot = 16 * ((key >> 2) & 3) + 4 * (key >> 4) + (key & 3);
-            const int pos = slot * CPR + (c ^ (slot & 7));
-            Kh[pos] = h;
-            Kl[pos] = l;
+            split8(raw.v[i][0], raw.v[i][1], h, l);
+            Kh[buf][dst[i]] = h;
+            Kl[buf][dst[i]] = l;
         }
-        __syncthreads();            // images complete; the fp32 buffer may be overwritten
-        if (jb + 1 < nkb) copy.issue(jb + 1);
+    };
 
-        f32x4 acc[4];
+    const size_t ostride = PRUNE ? Lk / 2 : Lk;       // floats per output row
+    float *orow = out + ((size_t)bh * Lq + q) * ostride;
+    // metadata word of (row group, block jb, row n, lane group g); the next 16 queries are the next row group
+    uint32_t *mrow = PRUNE ? meta + ((size_t)bh * (Lq / 16) + (q >> 4)) * nkb * 64 + n * 4 + g : nullptr;
+
+    RawBlock<NCONV> raw;
+    raw.load(kblocks, tid);
+    convert(raw, 0);
+    if (nkb > 1) raw.load(kblocks + (size_t)KB * D, tid);
+    for (int jb = 0; jb < nkb; ++jb) {
+        const int buf = jb & 1;
+        __syncthreads();            // images of block jb complete; every wave is done with those of block jb-1
+        if (jb + 1 < nkb) convert(raw, buf ^ 1);
+        if (jb + 2 < nkb) raw.load(kblocks + (size_t)(jb + 2) * KB * D, tid);
+
+        f32x4 acc[NQ][4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < NQ; ++j) acc[j][t] = f32x4{0.f, 0.f, 0.f, 0.f};
             const int slot = 16 * t + n;
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 const int pos = slot * CPR + ((4 * s + g) ^ (n & 7));
-                acc[t] = mfma_split(Kh[pos], Kl[pos], qh[s], ql[s], acc[t]);
+                const u32x4 ah = Kh[buf][pos], al = Kl[buf][pos];
+#pragma unroll
+                for (int j = 0; j < NQ; ++j) acc[j][t] = mfma_split(ah, al, qh[j][s], ql[j][s], acc[j][t]);
             }
         }
 
-        if constexpr (PRUNE) {
-            f32x4 kept[2];
-            uint32_t word = 0;
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+        for (int j = 0; j < NQ; ++j) {
+            if constexpr (PRUNE) {
+                f32x4 kept[2];
+                uint32_t word = 0;
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const float s0 = acc[t][2 * h] * scale, s1 = acc[t][2 * h + 1] * scale;
-                    const bool second = s1 > s0;
-                    const int p = 2 * t + h;
-                    kept[p >> 2][p & 3] = second ? s1 : s0;
-                    word |= (second ? 0xEu : 0x4u) << (4 * p);
-                }
-            f32x4 *vp = reinterpret_cast<f32x4 *>(orow + jb * (KB / 2) + 8 * g);
-            vp[0] = kept[0];
-            vp[1] = kept[1];
-            mrow[jb * 4 + g] = word;
-        } else {
-            f32x4 *sp = reinterpret_cast<f32x4 *>(orow + jb * KB + 16 * g);
+                for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) sp[t] = acc[t] * scale;
+                    for (int h = 0; h < 2; ++h) {
+                        const float s0 = acc[j][t][2 * h] * scale, s1 = acc[j][t][2 * h + 1] * scale;
+                        const bool second = s1 > s0;
+                        const int p = 2 * t + h;
+                        kept[p >> 2][p & 3] = second ? s1 : s0;
+                        word |= (second ? 0xEu : 0x4u) << (4 * p);
+                    }
+                f32x4 *vp = reinterpret_cast<f32x4 *>(orow + (size_t)(16 * j) * ostride + jb * (KB / 2) + 8 * g);
+                vp[0] = kept[0];
+                vp[1] = kept[1];
+                mrow[((size_t)j * nkb + jb) * 64] = word;
+            } else {
+                f32x4 *sp = reinterpret_cast<f32x4 *>(orow + (size_t)(16 * j) * ostride + jb * KB + 16 * g);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) sp[t] = acc[j][t] * scale;
+            }
         }
     }
 }
@@ -165,8 +180,9 @@ __global__ __launch_bounds__(NT, 2) void k_scores_split(const float *__restrict_
 // O = A V.  SPARSE: A = kept weights [BH, Lq, Lk/2] fp32 + metadata of the 4-byte mode, expanded and
 // split in registers; else A dense [BH, Lq, Lk] fp32.  Matrix step m (0, 1) of a 64-key block takes, in
 // lane group g, the keys 32 m + 8 g .. +7: four kept weights and one 16-bit metadata word.  V blocks are
-// converted like K blocks, into row-major bf16 images whose 16-byte chunk c of key k sits at chunk
-// c ^ 2 (k % 4); the B operand (keys along the contraction) comes from the transposing LDS read.
+// converted like K blocks (one block ahead, double-buffered images), into row-major bf16 images whose
+// 16-byte chunk c of key k sits at chunk c ^ 2 (k % 4); the B operand (keys along the contraction) comes
+// from the transposing LDS read.
 // ---------------------------------------------------------------------------------------------
 template <int D, bool SPARSE>
 __global__ __launch_bounds__(NT, 2) void k_av_split(const float *__restrict__ A, const uint16_t *__restrict__ meta,
@@ -175,8 +191,7 @@ __global__ __launch_bounds__(NT, 2) void k_av_split(const float *__restrict__ A,
     constexpr int CPR = D / 8;
     constexpr int NCONV = KB * CPR / NT;
     constexpr int DS = D / 16;
-    __shared__ __attribute__((aligned(16))) float Vf[KB * D];
-    __shared__ u32x4 Vh[KB * CPR], Vl[KB * CPR];
+    __shared__ u32x4 Vh[2][KB * CPR], Vl[2][KB * CPR];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, g = lane >> 4;
@@ -186,7 +201,23 @@ __global__ __launch_bounds__(NT, 2) void k_av_split(const float *__restrict__ A,
     const int nkb = Lk / KB;
     const int q = qt * QT + wave * 16 + li;      // A operand row of this lane
 
-    const BlockCopy<D> copy{uniform_address(V + (size_t)bh * Lk * D), lds_address(&Vf[0]), (uint32_t)lane * 16u, wave};
+    const float *vblocks = V + (size_t)bh * Lk * D;
+    int dst[NCONV];
+#pragma unroll
+    for (int i = 0; i < NCONV; ++i) {
+        const int idx = i * NT + tid;
+        const int key = idx / CPR, c = idx % CPR;
+        dst[i] = key * CPR + (c ^ ((key & 3) << 1));
+    }
+    auto convert = [&](const RawBlock<NCONV> &raw, int buf) {
+#pragma unroll
+        for (int i = 0; i < NCONV; ++i) {
+            u32x4 h, l;
+            split8(raw.v[i][0], raw.v[i][1], h, l);
+            Vh[buf][dst[i]] = h;
+            Vl[buf][dst[i]] = l;
+        }
+    };
 
     // weights of this lane for one block: two runs of 8 keys
     struct AFrag {
@@ -194,13 +225,14 @@ __global__ __launch_bounds__(NT, 2) void k_av_split(const float *__restrict__ A,
         uint32_t code[2];
     };
     const float *arow = A + ((size_t)bh * Lq + q) * (SPARSE ? Lk / 2 : Lk);
-    const uint16_t *mrow = SPARSE ? meta + ((size_t)bh * Lq + q) * (Lk / 8) : nullptr;
+    // 16-bit words of (row group, block jb, row li): 8 of them, word 4 m + g belongs to matrix step m
+    const uint16_t *mrow = SPARSE ? meta + (((size_t)bh * (Lq / 16) + (q >> 4)) * nkb * 64 + li * 4) * 2 : nullptr;
     auto load_a = [&](int jb, AFrag &a) {
 #pragma unroll
         for (int m = 0; m < 2; ++m) {
             if constexpr (SPARSE) {
                 a.v[m] = *reinterpret_cast<const f32x4 *>(arow + jb * (KB / 2) + 16 * m + 4 * g);
-                a.code[m] = mrow[jb * (KB / 8) + 4 * m + g];
+                a.code[m] = mrow[jb * 128 + 4 * m + g];
             } else {
                 const f32x4 *p = reinterpret_cast<const f32x4 *>(arow + jb * KB + 32 * m + 8 * g);
                 a.v[2 * m] = p[0];
@@ -229,26 +261,18 @@ __global__ __launch_bounds__(NT, 2) void k_av_split(const float *__restrict__ A,
 
     AFrag a_cur, a_nxt;
     load_a(0, a_cur);
-    copy.issue(0);
+    RawBlock<NCONV> raw;
+    raw.load(vblocks, tid);
+    convert(raw, 0);
+    if (nkb > 1) raw.load(vblocks + (size_t)KB * D, tid);
     for (int jb = 0; jb < nkb; ++jb) {
-        wait_async_copies();        // this block's V copy and weights
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < NCONV; ++i) {
-            const int idx = i * NT + tid;
-            const int key = idx / CPR, c = idx % CPR;
-            const f32x4 *src = reinterpret_cast<const f32x4 *>(&Vf[key * D + 8 * c]);
-            u32x4 h, l;
-            split8(src[0], src[1], h, l);
-            const int pos = key * CPR + (c ^ ((key & 3) << 1));
-            Vh[pos] = h;
-            Vl[pos] = l;
-        }
-        __syncthreads();
+        const int buf = jb & 1;
+        __syncthreads();            // images of block jb complete; every wave is done with those of block jb-1
         if (jb + 1 < nkb) {
-            copy.issue(jb + 1);
+            convert(raw, buf ^ 1);
             load_a(jb + 1, a_nxt);
         }
+        if (jb + 2 < nkb) raw.load(vblocks + (size_t)(jb + 2) * KB * D, tid);
 
 #pragma unroll
         for (int m = 0; m < 2; ++m) {
@@ -273,7 +297,7 @@ __global__ __launch_bounds__(NT, 2) void k_av_split(const float *__restrict__ A,
             const int key0 = 32 * m + 8 * g;
 #pragma unroll
             for (int ds = 0; ds < DS; ++ds)
-                acc[ds] = mfma_split(ah, al, tr8(Vh, key0, ds), tr8(Vl, key0, ds), acc[ds]);
+                acc[ds] = mfma_split(ah, al, tr8(Vh[buf], key0, ds), tr8(Vl[buf], key0, ds), acc[ds]);
         }
         if (jb + 1 < nkb) a_cur = a_nxt;
     }
@@ -286,19 +310,27 @@ __global__ __launch_bounds__(NT, 2) void k_av_split(const float *__restrict__ A,
         for (int r = 0; r < 4; ++r) op[(size_t)r * D + ds * 16] = acc[ds][r];
 }
 
+template <int D, bool PRUNE, int NQ>
+hipError_t launch_scores_nq(const void *Q, const void *K, int BH, int Lq, int Lk, float scale, void *out, void *meta,
+                            hipStream_t st) {
+    const unsigned grid = (unsigned)BH * (unsigned)(Lq / (64 * NQ));
+    hipLaunchKernelGGL((k_scores_split<D, PRUNE, NQ>), dim3(grid), dim3(NT), 0, st, (const float *)Q,
+                       (const float *)K, Lq, Lk, scale, (float *)out, (uint32_t *)meta);
+    return hipGetLastError();
+}
+
 template <bool PRUNE>
 hipError_t launch_scores(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale, void *out,
                          void *meta, hipStream_t st) {
-    const unsigned grid = (unsigned)BH * (unsigned)(Lq / QT);
+    // 32 queries per wave where Lq allows and the grid still fills the chip
+    const bool wide = Lq % 128 == 0 && (long)BH * (Lq / 128) >= 512;
     if (d == 64)
-        hipLaunchKernelGGL((k_scores_split<64, PRUNE>), dim3(grid), dim3(NT), 0, st, (const float *)Q,
-                           (const float *)K, Lq, Lk, scale, (float *)out, (uint32_t *)meta);
-    else if (d == 128)
-        hipLaunchKernelGGL((k_scores_split<128, PRUNE>), dim3(grid), dim3(NT), 0, st, (const float *)Q,
-                           (const float *)K, Lq, Lk, scale, (float *)out, (uint32_t *)meta);
-    else
-        return hipErrorInvalidValue;
-    return hipGetLastError();
+        return wide ? launch_scores_nq<64, PRUNE, 2>(Q, K, BH, Lq, Lk, scale, out, meta, st)
+                    : launch_scores_nq<64, PRUNE, 1>(Q, K, BH, Lq, Lk, scale, out, meta, st);
+    if (d == 128)
+        return wide ? launch_scores_nq<128, PRUNE, 2>(Q, K, BH, Lq, Lk, scale, out, meta, st)
+                    : launch_scores_nq<128, PRUNE, 1>(Q, K, BH, Lq, Lk, scale, out, meta, st);
+    return hipErrorInvalidValue;
 }
 
 template <bool SPARSE>

@@ -39,7 +39,10 @@ def _dev(t):
 
 
 def _meta_np(meta, s):
-    return meta.cpu().numpy().view(np.uint16).reshape(s.BH, s.Lq, s.meta_words)
+    """Metadata of a stage-1 call in canonical word order, as uint16 [BH, Lq, Lk/8]."""
+    canon = dfss.dfss_meta_to_canonical(meta, s)
+    torch.cuda.synchronize()
+    return canon.cpu().numpy().view(np.uint16).reshape(s.BH, s.Lq, s.meta_words)
 
 
 def _shape(B, H, Lq, Lk, d, dtype=DFSS_F32):
@@ -67,6 +70,8 @@ TOL_O = {DFSS_F32: 1e-4, DFSS_F32_BF16X3: 5e-4}
     (2, 192, 256, 128, 0.125),                                  # d = 128
     (1, 64, 128, 128, float(np.float32(1 / math.sqrt(128)))),   # smallest legal shape, scale not a power of two
     (1, 64, 8192, 64, 0.125),                                   # longest key sequence
+    (64, 1024, 128, 64, 0.125),                                 # enough work for the 32-queries-per-wave tiling
+    (64, 1024, 128, 128, 0.125),
 ])
 @DTYPES
 def test_stage1_bit_exact_on_integer_inputs(BH, Lq, Lk, d, scale, dtype):
@@ -95,14 +100,18 @@ def test_stage1_all_equal_scores_keep_the_first(dtype):
     assert np.all(_meta_np(meta, s) == 0x4444) and np.all(vals.cpu().numpy() == 0)
 
 
-def test_meta_conversions_are_copies():
-    Q, K, _ = synth.integer_qkv(2, 64, 128, 64, seed=6200, dtype=torch.float32)
-    s = _shape(1, 2, 64, 128, 64)
+def test_meta_order_conversions_round_trip():
+    """Library order = canonical 32-bit words blocked as [row/16][key block of 64][row%16][4 words]."""
+    Q, K, _ = synth.integer_qkv(2, 64, 256, 64, seed=6200, dtype=torch.float32)
+    s = _shape(1, 2, 64, 256, 64)
     _, meta = dfss.dfss_sddmm_prune(_dev(Q), _dev(K), s, 0.125)
     canon = dfss.dfss_meta_to_canonical(meta, s)
     back = dfss.dfss_meta_from_canonical(canon, s)
     torch.cuda.synchronize()
-    assert torch.equal(canon.reshape(-1), meta) and torch.equal(back, meta)
+    assert torch.equal(back, meta)
+    lib = meta.cpu().numpy().view(np.uint32).reshape(2, 64 // 16, 256 // 64, 16, 4)
+    can = canon.cpu().numpy().view(np.uint32).reshape(2, 64 // 16, 16, 256 // 64, 4)
+    assert np.array_equal(lib.transpose(0, 1, 3, 2, 4), can)
 
 
 @pytest.mark.parametrize("name", ["tiny_1to2_f32", "bert_base_L512_1to2_f32", "large_head_L2048_d128_1to2_f32"])
