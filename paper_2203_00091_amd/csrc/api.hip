@@ -149,6 +149,8 @@ dfss_status dfss_attention_bias(const void *Q, const void *K, const void *V, con
     const float *bias = (const float *)key_bias;
     if (D.f32) {
         if (key_bias) return DFSS_ERR_UNSUPPORTED;
+        if (D.split && D.d == 64 && !staged_path_requested())
+            return hip_status(dfss::launch_fused_attention_split(Q, K, V, D.BH, D.Lq, D.Lk, D.d, true, scale, O, st));
         char *vals = static_cast<char *>(ws);
         char *meta = vals + align_up(dfss_vals_bytes(s));
         hipError_t e = sddmm_prune_f32(D, Q, K, scale, vals, meta, st);
@@ -179,7 +181,11 @@ dfss_status dense_attention_fused_bias(const void *Q, const void *K, const void 
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias))
         return DFSS_ERR_SHAPE;
-    if (D.f32) return DFSS_ERR_UNSUPPORTED;
+    if (D.f32) {
+        if (!D.split || D.d != 64 || key_bias) return DFSS_ERR_UNSUPPORTED;
+        return hip_status(dfss::launch_fused_attention_split(Q, K, V, D.BH, D.Lq, D.Lk, D.d, false, scale, O,
+                                                             (hipStream_t)stream));
+    }
     return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, nullptr, D.BH, D.Lq, D.Lk,
                                                    D.d, 2, scale, O, (hipStream_t)stream));
 }

@@ -310,6 +310,212 @@ __global__ __launch_bounds__(NT, 2) void k_av_split(const float *__restrict__ A,
         for (int r = 0; r < 4; ++r) op[(size_t)r * D + ds * 16] = acc[ds][r];
 }
 
+// ---------------------------------------------------------------------------------------------
+// The whole forward pass of the 4-byte mode in one kernel: scores on split products, 1:2 selection on
+// the accumulators, softmax over the kept scores kept up to date block by block (running maximum and
+// sum per query, the output accumulators rescaled when a maximum rises), and A V on split products,
+// with the weights never leaving registers.  Nothing of the score matrix is written.
+//
+// Per 64-key block a lane (query n = l%16, lane group g) holds the scores of keys 16g .. 16g+15 of its
+// query (keys on the rows of the score tiles, as in k_scores_split).  For the second product the lane's
+// weights ARE the A operand.  With pruning it is the compressed operand of the structured-sparse matrix
+// instruction (v_smfmac_f32_16x16x64_bf16: 8 kept values per lane out of 16, one from each aligned pair
+// is a valid 2-of-4 pattern), whose 2-bit position codes are 2 (i%2) + [the later key of pair i was
+// kept]; one instruction covers the whole 64-key block, with B = the V rows 8g .. 8g+7 and
+// 32+8g .. 32+8g+7 read (transposed) from the images.  Without pruning matrix step m (0, 1) contracts, in
+// lane group g, the keys 16g + 8m .. +7 on the dense instruction.  The softmax statistics of
+// query n live in the lanes with l%16 = n; the output tiles hold queries 4g + r, so the factors they need
+// are fetched from lanes 4g + r.
+// PRUNE = false is full attention (Eq. 1) in the same structure, the baseline of this mode.
+// ---------------------------------------------------------------------------------------------
+template <int D, bool PRUNE>
+__global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__ Q, const float *__restrict__ K,
+                                                       const float *__restrict__ V, int Lq, int Lk, float scale,
+                                                       float *__restrict__ O) {
+    constexpr int CPR = D / 8;
+    constexpr int KS = D / 32;
+    constexpr int NCONV = KB * CPR / NT;
+    constexpr int DS = D / 16;
+    constexpr int NV = PRUNE ? 8 : 16;           // weights per lane per block
+    constexpr float kLog2e = 1.4426950408889634f;
+    __shared__ u32x4 Kh[2][KB * CPR], Kl[2][KB * CPR], Vh[2][KB * CPR], Vl[2][KB * CPR];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, g = lane >> 4;
+    const unsigned nqt = Lq / QT;
+    const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
+    const unsigned bh = item / nqt, qt = item % nqt;
+    const int nkb = Lk / KB;
+    const int q = qt * QT + wave * 16 + n;
+
+    u32x4 qh[KS], ql[KS];
+    {
+        const f32x4 *qp = reinterpret_cast<const f32x4 *>(Q + ((size_t)bh * Lq + q) * D + 8 * g);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) split8(qp[8 * s], qp[8 * s + 1], qh[s], ql[s]);
+    }
+
+    const float *kblocks = K + (size_t)bh * Lk * D;
+    const float *vblocks = V + (size_t)bh * Lk * D;
+    int dst_k[NCONV], dst_v[NCONV];
+#pragma unroll
+    for (int i = 0; i < NCONV; ++i) {
+        const int idx = i * NT + tid;
+        const int key = idx / CPR, c = idx % CPR;
+        const int slot = 16 * ((key >> 2) & 3) + 4 * (key >> 4) + (key & 3);
+        dst_k[i] = slot * CPR + (c ^ (slot & 7));
+        dst_v[i] = key * CPR + (c ^ ((key & 3) << 1));
+    }
+    auto convert = [&](const RawBlock<NCONV> &rk, const RawBlock<NCONV> &rv, int buf) {
+#pragma unroll
+        for (int i = 0; i < NCONV; ++i) {
+            u32x4 h, l;
+            split8(rk.v[i][0], rk.v[i][1], h, l);
+            Kh[buf][dst_k[i]] = h;
+            Kl[buf][dst_k[i]] = l;
+            split8(rv.v[i][0], rv.v[i][1], h, l);
+            Vh[buf][dst_v[i]] = h;
+            Vl[buf][dst_v[i]] = l;
+        }
+    };
+
+    // transposing read of the V images (see k_av_split)
+    const int tr_row = n >> 2;
+    const int tr_sub = (n >> 1) & 1;
+    const int tr_byte = 8 * (n & 1);
+    const int tr_xor = tr_row << 1;
+    auto tr8 = [&](const u32x4 *img, int key0, int ds) {
+        const char *base = reinterpret_cast<const char *>(img);
+        const int chunk = (2 * ds + tr_sub) ^ tr_xor;
+        const s16x4 t0 = lds_read_tr16(base + ((key0 + tr_row) * CPR + chunk) * 16 + tr_byte);
+        const s16x4 t1 = lds_read_tr16(base + ((key0 + 4 + tr_row) * CPR + chunk) * 16 + tr_byte);
+        return __builtin_bit_cast(u32x4, __builtin_shufflevector(t0, t1, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+
+    f32x4 acc_o[DS];
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds) acc_o[ds] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -1e30f;      // running maximum of query n (the same in its four lanes)
+    float l_run = 0.f;         // this lane's share of the running sum of query n
+
+    RawBlock<NCONV> rk, rv;
+    rk.load(kblocks, tid);
+    rv.load(vblocks, tid);
+    convert(rk, rv, 0);
+    if (nkb > 1) {
+        rk.load(kblocks + (size_t)KB * D, tid);
+        rv.load(vblocks + (size_t)KB * D, tid);
+    }
+    for (int jb = 0; jb < nkb; ++jb) {
+        const int buf = jb & 1;
+        __syncthreads();            // images of block jb complete; every wave is done with those of block jb-1
+        if (jb + 1 < nkb) convert(rk, rv, buf ^ 1);
+        if (jb + 2 < nkb) {
+            rk.load(kblocks + (size_t)(jb + 2) * KB * D, tid);
+            rv.load(vblocks + (size_t)(jb + 2) * KB * D, tid);
+        }
+
+        // scores of keys 16g + 4t + r (tile t, register r) of query n
+        f32x4 acc[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+            const int slot = 16 * t + n;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const int pos = slot * CPR + ((4 * s + g) ^ (n & 7));
+                acc[t] = mfma_split(Kh[buf][pos], Kl[buf][pos], qh[s], ql[s], acc[t]);
+            }
+        }
+
+        // selection: w[i] = kept score of pair i (keys 16g + 2i, +1), bit i of `second` = the later one was kept
+        float w[NV];
+        uint32_t second = 0;
+        float m_loc;
+        if constexpr (PRUNE) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const float s0 = acc[t][2 * h] * scale, s1 = acc[t][2 * h + 1] * scale;
+                    const bool sec = s1 > s0;
+                    w[2 * t + h] = sec ? s1 : s0;
+                    second |= (sec ? 1u : 0u) << (2 * (2 * t + h));     // bit 2i: position code of pair i
+                }
+        } else {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) w[4 * t + r] = acc[t][r] * scale;
+        }
+        m_loc = w[0];
+#pragma unroll
+        for (int i = 1; i < NV; ++i) m_loc = fmaxf(m_loc, w[i]);
+        m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 16, kWave));
+        m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, kWave));
+        const float m_new = fmaxf(m_run, m_loc);
+        if (__ballot(m_new > m_run) != 0) {     // some query of this wave has a new maximum: rescale
+            const float alpha = exp2f((m_run - m_new) * kLog2e);
+            l_run *= alpha;
+            m_run = m_new;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float a_r = __shfl(alpha, 4 * g + r, kWave);
+#pragma unroll
+                for (int ds = 0; ds < DS; ++ds) acc_o[ds][r] *= a_r;
+            }
+        }
+        const float mb = m_run * kLog2e;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            w[i] = exp2f(w[i] * kLog2e - mb);
+            l_run += w[i];
+        }
+
+        if constexpr (PRUNE) {
+            // weights x V on the structured-sparse instruction: kept value i sits at dense position
+            // 4 (i/2) + 2 (i%2) + second_i of this lane's 16 keys
+            u32x4 ah, al;
+            split8(f32x4{w[0], w[1], w[2], w[3]}, f32x4{w[4], w[5], w[6], w[7]}, ah, al);
+            const int idx = (int)(0x8888u | second);
+#pragma unroll
+            for (int ds = 0; ds < DS; ++ds) {
+                const u32x4 h0 = tr8(Vh[buf], 8 * g, ds), h1 = tr8(Vh[buf], 32 + 8 * g, ds);
+                const u32x4 l0 = tr8(Vl[buf], 8 * g, ds), l1 = tr8(Vl[buf], 32 + 8 * g, ds);
+                const bf16x16 bh16 = __builtin_bit_cast(bf16x16, __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7));
+                const bf16x16 bl16 = __builtin_bit_cast(bf16x16, __builtin_shufflevector(l0, l1, 0, 1, 2, 3, 4, 5, 6, 7));
+                acc_o[ds] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(al), bh16, acc_o[ds], idx, 0, 0);
+                acc_o[ds] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(ah), bl16, acc_o[ds], idx, 0, 0);
+                acc_o[ds] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(ah), bh16, acc_o[ds], idx, 0, 0);
+            }
+        } else {
+            // weights x V: matrix step m takes keys 16g + 8m .. +7 in lane group g
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+                u32x4 ah, al;
+                split8(f32x4{w[8 * m], w[8 * m + 1], w[8 * m + 2], w[8 * m + 3]},
+                       f32x4{w[8 * m + 4], w[8 * m + 5], w[8 * m + 6], w[8 * m + 7]}, ah, al);
+                const int key0 = 16 * g + 8 * m;
+#pragma unroll
+                for (int ds = 0; ds < DS; ++ds)
+                    acc_o[ds] = mfma_split(ah, al, tr8(Vh[buf], key0, ds), tr8(Vl[buf], key0, ds), acc_o[ds]);
+            }
+        }
+    }
+
+    // row sums: the four lanes of a query add up; then the factor of query 4g + r comes from lane 4g + r
+    l_run += __shfl_xor(l_run, 16, kWave);
+    l_run += __shfl_xor(l_run, 32, kWave);
+    const float inv = 1.0f / l_run;
+    float *op = O + ((size_t)bh * Lq + qt * QT + wave * 16 + 4 * g) * D + n;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const float inv_r = __shfl(inv, 4 * g + r, kWave);
+#pragma unroll
+        for (int ds = 0; ds < DS; ++ds) op[(size_t)r * D + ds * 16] = acc_o[ds][r] * inv_r;
+    }
+}
+
 template <int D, bool PRUNE, int NQ>
 hipError_t launch_scores_nq(const void *Q, const void *K, int BH, int Lq, int Lk, float scale, void *out, void *meta,
                             hipStream_t st) {
@@ -349,6 +555,19 @@ hipError_t launch_av(const void *A, const void *meta, const void *V, int BH, int
 }
 
 }  // namespace
+
+hipError_t launch_fused_attention_split(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d,
+                                        bool prune, float scale, void *O, hipStream_t st) {
+    if (d != 64) return hipErrorInvalidValue;      // the double-buffered images of d = 128 do not fit two workgroups
+    const unsigned grid = (unsigned)BH * (unsigned)(Lq / QT);
+    if (prune)
+        hipLaunchKernelGGL((k_fused_split<64, true>), dim3(grid), dim3(NT), 0, st, (const float *)Q, (const float *)K,
+                           (const float *)V, Lq, Lk, scale, (float *)O);
+    else
+        hipLaunchKernelGGL((k_fused_split<64, false>), dim3(grid), dim3(NT), 0, st, (const float *)Q, (const float *)K,
+                           (const float *)V, Lq, Lk, scale, (float *)O);
+    return hipGetLastError();
+}
 
 hipError_t launch_sddmm_prune_split(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale,
                                     void *vals, void *meta, hipStream_t st) {

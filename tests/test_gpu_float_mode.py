@@ -157,12 +157,19 @@ def test_stages_on_gaussian_inputs(name, dtype):
 
 @pytest.mark.parametrize("BH,Lq,Lk,d", [(2, 128, 256, 64), (2, 64, 384, 128), (1, 192, 128, 64)])
 @DTYPES
-def test_attention_and_dense_baseline(BH, Lq, Lk, d, dtype):
+@pytest.mark.parametrize("path", ["default", "staged"])
+def test_attention_and_dense_baseline(BH, Lq, Lk, d, dtype, path, monkeypatch):
+    """default: one kernel where the library has one (bf16x3 products, d = 64), else the three stages."""
+    if path == "staged":
+        monkeypatch.setenv("DFSS_ATTENTION_PATH", "staged")
     Q, K, V = synth.gaussian_qkv(BH, Lq, Lk, d, 1.0, seed=6300 + Lq + d, dtype=torch.float32)
     scale = 1 / math.sqrt(d)
     s = _shape(1, BH, Lq, Lk, d, dtype)
     O = dfss.dfss_attention(_dev(Q), _dev(K), _dev(V), s, scale)
-    Od = dfss.dense_attention(_dev(Q), _dev(K), _dev(V), s, scale)
+    if path == "default" and dtype == DFSS_F32_BF16X3 and d == 64:
+        Od = dfss.dense_attention_fused(_dev(Q), _dev(K), _dev(V), s, scale)
+    else:
+        Od = dfss.dense_attention(_dev(Q), _dev(K), _dev(V), s, scale)
     torch.cuda.synchronize()
     O, Od = O.cpu().numpy(), Od.cpu().numpy()
     Qn, Kn, Vn = Q.numpy(), K.numpy(), V.numpy()
@@ -181,15 +188,49 @@ def test_attention_and_dense_baseline(BH, Lq, Lk, d, dtype):
 
 
 @DTYPES
-def test_stage_calls_compose_to_attention(dtype):
+def test_stage_calls_compose_to_attention(dtype, monkeypatch):
     w = synth.WORKLOADS["tiny_1to2_f32"]
     Q, K, V = (_dev(t) for t in synth.make(w))
     s = _shape(w.B, w.H, w.L, w.L, w.d, dtype)
     vals, meta = dfss.dfss_sddmm_prune(Q, K, s, w.scale)
     O1 = dfss.dfss_spmm(dfss.dfss_sparse_softmax(vals, s), meta, V, s)
+    monkeypatch.setenv("DFSS_ATTENTION_PATH", "staged")
     O2 = dfss.dfss_attention(Q, K, V, s, w.scale)
     torch.cuda.synchronize()
     assert torch.equal(O1, O2)
+    if dtype == DFSS_F32_BF16X3:
+        # the one-kernel path computes the same function with the softmax in another order
+        monkeypatch.delenv("DFSS_ATTENTION_PATH")
+        O3 = dfss.dfss_attention(Q, K, V, s, w.scale)
+        torch.cuda.synchronize()
+        assert (O3 - O1).abs().max().item() <= 2e-5
+        assert not torch.equal(O3, O1)          # (it really is the other kernel)
+
+
+@pytest.mark.parametrize("name", ["bert_base_L512_1to2_f32", "long_L4096_1to2_f32"])
+def test_fused_kernels_at_full_size(name):
+    """One-kernel DFSS and full attention of the bf16x3 mode on sampled heads of the full-size workloads."""
+    w = synth.WORKLOADS[name]
+    Q, K, V = synth.make(w)
+    s = _shape(w.B, w.H, w.L, w.L, w.d, DFSS_F32_BF16X3)
+    Qd, Kd, Vd = _dev(Q), _dev(K), _dev(V)
+    O = dfss.dfss_attention(Qd, Kd, Vd, s, w.scale)
+    Od = dfss.dense_attention_fused(Qd, Kd, Vd, s, w.scale)
+    torch.cuda.synchronize()
+    O, Od = O.cpu().numpy(), Od.cpu().numpy()
+    assert np.isfinite(O).all() and np.isfinite(Od).all()
+    for h in (0, w.BH - 1):
+        Qn, Kn, Vn = Q[h].numpy(), K[h].numpy(), V[h].numpy()
+        rows = slice(0, w.L, max(1, w.L // 256))            # every row block, a sample of rows
+        ref = oracle.attention(Qn[rows], Kn, Vn, 1, 2, w.scale, store_bf16=False)
+        assert np.abs(O[h][rows] - ref).max() <= 2e-2
+        S = oracle.scores(Qn[rows], Kn, w.scale)
+        bound = _score_error_bound(Qn[rows], Kn, w.scale, DFSS_F32_BF16X3)
+        safe = (np.abs(S[:, 0::2] - S[:, 1::2]) > 2 * (bound[:, 0::2] + bound[:, 1::2])).all(-1)
+        assert safe.sum() > 0
+        assert np.abs(O[h][rows] - ref)[safe].max() <= TOL_O[DFSS_F32_BF16X3]
+        refd = oracle.attention(Qn[rows], Kn, Vn, 2, 2, w.scale, store_bf16=False)
+        assert np.abs(Od[h][rows] - refd).max() <= TOL_O[DFSS_F32_BF16X3]
 
 
 @DTYPES
@@ -199,8 +240,14 @@ def test_unsupported_combinations_are_refused(dtype):
     s = _shape(1, 1, 64, 128, 64, dtype)
     Q = torch.zeros(1, 64, 64, device=DEV)
     K = torch.zeros(1, 128, 64, device=DEV)
+    if dtype == DFSS_F32:
+        with pytest.raises(dfss.DfssError):
+            dfss.dense_attention_fused(Q, K, K, s, 0.125)
+    s128 = _shape(1, 1, 64, 128, 128, dtype)
+    Q128 = torch.zeros(1, 64, 128, device=DEV)
+    K128 = torch.zeros(1, 128, 128, device=DEV)
     with pytest.raises(dfss.DfssError):
-        dfss.dense_attention_fused(Q, K, K, s, 0.125)
+        dfss.dense_attention_fused(Q128, K128, K128, s128, 0.125)
     with pytest.raises(dfss.DfssError):
         dfss.dfss_attention_bias(Q, K, K, torch.zeros(1, 128, device=DEV), s, 0.125)
     with pytest.raises(ValueError):          # bfloat16 tensors with a float shape
