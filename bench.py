@@ -13,11 +13,12 @@ the named workload.  Prints ONE JSON line.
                   FLOPs / measured launch duration against the dense bf16 MFMA peak.
   cpu_baseline    the CPU oracle timed on the host cores (context only).
 
-Workloads whose name ends in ``_f32`` run the paper's second precision (float data, 1:2): there
-``dfss_attention`` is the three stage kernels, the full-attention baseline is the three-stage
+Workloads whose name ends in ``_f32`` run the paper's second precision (float data, 1:2).  With the
+default ``--products bf16x3`` (fp32 products formed from bfloat16 pieces on the bf16 matrix pipe) and
+d = 64 everything is as for the 2-byte workloads (``dfss_attention`` is one kernel).  Otherwise
+``dfss_attention`` is the three stage kernels, the only full-attention baseline is the three-stage
 ``dense_attention``, and the roofline object describes the score/prune kernel (the largest of the
-three): against HBM with the default ``--products bf16x3`` (fp32 products formed from bfloat16 pieces
-on the bf16 matrix pipe), against the fp32 MFMA peak with ``--products fp32``.
+three): against HBM for bf16x3 products, against the fp32 MFMA peak with ``--products fp32``.
 
 Inputs are resident in HBM before timing starts.  By default the steps rotate over enough
 independent buffer sets that no step finds its inputs or workspace in the last-level cache
@@ -100,6 +101,8 @@ def main():
         print("bench.py: the float workloads run the plain forward pass only", file=sys.stderr)
         sys.exit(2)
     esz = 4 if f32 else 2
+    # one-kernel paths exist for the 2-byte modes and, in the float mode, for bf16x3 products with d = 64
+    has_fused = (not f32) or (split and w.d == 64)
     K, W = args.steps, args.warmup
     BH, L, d = w.BH, w.L, w.d
 
@@ -242,8 +245,8 @@ def main():
     t_sparse = timed(step_sparse, K, W, use_graph)
     t_dense = timed(step_dense, K, W, use_graph)
     # the float mode has no fused kernels: dfss_attention already is the staged path there
-    t_dense_fused = None if f32 else timed(step_dense_fused, K, W, use_graph)
-    t_staged = t_sparse if f32 else timed(step_sparse_staged, K, W, use_graph)
+    t_dense_fused = timed(step_dense_fused, K, W, use_graph) if has_fused else None
+    t_staged = timed(step_sparse_staged, K, W, use_graph) if has_fused else t_sparse
     t_sparse_eager = timed(step_sparse, K, 0, False)
 
     # ---- per-kernel durations (events around a graph of K launches of one kernel) ------
@@ -257,7 +260,7 @@ def main():
     flops_eq = 4.0 * BH * L * L * d * density
     ms = t_sparse / K * 1e3
     ms_dense = t_dense / K * 1e3
-    ms_dense_fused = None if f32 else t_dense_fused / K * 1e3
+    ms_dense_fused = t_dense_fused / K * 1e3 if has_fused else None
     ms_staged = t_staged / K * 1e3
     value = flops_alg / (t_sparse / K) / 1e12
 
@@ -298,14 +301,14 @@ def main():
                      "algorithmic_hbm_bytes_per_launch": 8.0 * BH * L * d,
                      "avg_launch_ms": round(k_fused, 5), "algorithmic_flops_per_launch": flops_alg},
         "extra": {
-            "speedup_vs_dense_attention_fused": None if f32 else round(ms_dense_fused / ms, 4),
+            "speedup_vs_dense_attention_fused": round(ms_dense_fused / ms, 4) if has_fused else None,
             "speedup_vs_dense_attention_3stage": round(ms_dense / ms, 4),
             "staged_path_speedup_vs_dense_attention_3stage": round(ms_dense / ms_staged, 4),
-            "dense_attention_fused_ms_per_step": None if f32 else round(ms_dense_fused, 5),
+            "dense_attention_fused_ms_per_step": round(ms_dense_fused, 5) if has_fused else None,
             "dense_attention_3stage_ms_per_step": round(ms_dense, 5),
             "dfss_attention_staged_ms_per_step": round(ms_staged, 5),
             "dense_equivalent_tflops": round(flops_eq / (t_sparse / K) / 1e12, 3),
-            "dense_attention_fused_tflops": None if f32 else round(flops_eq / (t_dense_fused / K) / 1e12, 3),
+            "dense_attention_fused_tflops": round(flops_eq / (t_dense_fused / K) / 1e12, 3) if has_fused else None,
             "ms_per_step_direct_launch": round(t_sparse_eager / K * 1e3, 5),
             "stage_kernel_ms": {k: round(v[0], 5) for k, v in kernels.items()},
             "stage_kernel_GBps": {k: round(v[1] / (v[0] * 1e-3) / 1e9, 1) for k, v in kernels.items()},
@@ -318,11 +321,16 @@ def main():
         },
     }
     if f32:
-        # three kernels per step; the score/prune kernel is the largest and is bound by the fp32 matrix
-        # instruction: 2 L^2 d flops per head per launch
         flops1 = 2.0 * BH * L * L * d
         ach1 = flops1 / (k1 * 1e-3) / 1e12
-        if split:
+        if has_fused:
+            # one kernel (k_fused_split) on the bf16 matrix pipe; every algorithmic product is executed as
+            # three bf16 products, so a third of the bf16 peak is the most this route can reach
+            out["roofline"]["kernel"] = "k_fused_split (dfss_attention, float data, bf16x3 products)"
+            out["roofline"]["traffic"] = None
+            out["roofline"]["algorithmic_hbm_bytes_per_launch"] = 4.0 * esz * BH * L * d
+            out["roofline"]["executed_matrix_flops_per_launch"] = 3.0 * flops_alg
+        elif split:
             # on the bf16 matrix pipe the kernel is bound by writing the kept scores and the metadata
             gbs1 = bytes1 / (k1 * 1e-3) / 1e9
             out["roofline"] = {"bound": "hbm", "kernel": "k_scores_split (dfss_sddmm_prune, float data, bf16x3 products)",
@@ -331,6 +339,8 @@ def main():
                                "algorithmic_hbm_bytes_per_launch": bytes1, "avg_launch_ms": round(k1, 5),
                                "algorithmic_flops_per_launch": flops1}
         else:
+            # three kernels per step; the score/prune kernel is the largest and is bound by the fp32 matrix
+            # instruction: 2 L^2 d flops per head per launch
             out["roofline"] = {"bound": "mfma", "kernel": "k_scores_f32 (dfss_sddmm_prune, float data)",
                                "achieved": round(ach1, 2), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                                "frac": round(ach1 / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,

@@ -178,8 +178,11 @@ __global__ __launch_bounds__(NT, 2) void k_scores_split(const float *__restrict_
 
 // ---------------------------------------------------------------------------------------------
 // O = A V.  SPARSE: A = kept weights [BH, Lq, Lk/2] fp32 + metadata of the 4-byte mode, expanded and
-// split in registers; else A dense [BH, Lq, Lk] fp32.  Matrix step m (0, 1) of a 64-key block takes, in
-// lane group g, the keys 32 m + 8 g .. +7: four kept weights and one 16-bit metadata word.  V blocks are
+// split in registers; else A dense [BH, Lq, Lk] fp32.  SPARSE: the lane's 8 kept weights of keys
+// 16g .. 16g+15 are the compressed operand of the structured-sparse matrix instruction
+// (v_smfmac_f32_16x16x64_bf16; one kept value per aligned pair is a valid 2-of-4 pattern), with position
+// codes 2 (i%2) + [code of pair i is 0xE]; one instruction covers the 64-key block.  Dense: matrix step
+// m (0, 1) takes, in lane group g, the keys 32 m + 8 g .. +7 on the dense instruction.  V blocks are
 // converted like K blocks (one block ahead, double-buffered images), into row-major bf16 images whose
 // 16-byte chunk c of key k sits at chunk c ^ 2 (k % 4); the B operand (keys along the contraction) comes
 // from the transposing LDS read.
@@ -219,26 +222,29 @@ __global__ __launch_bounds__(NT, 2) void k_av_split(const float *__restrict__ A,
         }
     };
 
-    // weights of this lane for one block: two runs of 8 keys
+    // weights of this lane for one block
     struct AFrag {
         f32x4 v[SPARSE ? 2 : 4];
-        uint32_t code[2];
+        uint32_t word;          // the metadata word of keys 16g .. 16g+15 (8 codes)
     };
     const float *arow = A + ((size_t)bh * Lq + q) * (SPARSE ? Lk / 2 : Lk);
-    // 16-bit words of (row group, block jb, row li): 8 of them, word 4 m + g belongs to matrix step m
-    const uint16_t *mrow = SPARSE ? meta + (((size_t)bh * (Lq / 16) + (q >> 4)) * nkb * 64 + li * 4) * 2 : nullptr;
+    const uint32_t *mrow = SPARSE ? reinterpret_cast<const uint32_t *>(meta) +
+                                        ((size_t)bh * (Lq / 16) + (q >> 4)) * nkb * 64 + li * 4 + g
+                                  : nullptr;
     auto load_a = [&](int jb, AFrag &a) {
+        if constexpr (SPARSE) {
+            const f32x4 *p = reinterpret_cast<const f32x4 *>(arow + jb * (KB / 2) + 8 * g);
+            a.v[0] = p[0];
+            a.v[1] = p[1];
+            a.word = mrow[jb * 64];
+        } else {
 #pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            if constexpr (SPARSE) {
-                a.v[m] = *reinterpret_cast<const f32x4 *>(arow + jb * (KB / 2) + 16 * m + 4 * g);
-                a.code[m] = mrow[jb * 128 + 4 * m + g];
-            } else {
+            for (int m = 0; m < 2; ++m) {
                 const f32x4 *p = reinterpret_cast<const f32x4 *>(arow + jb * KB + 32 * m + 8 * g);
                 a.v[2 * m] = p[0];
                 a.v[2 * m + 1] = p[1];
-                a.code[m] = 0;
             }
+            a.word = 0;
         }
     };
 
@@ -274,30 +280,35 @@ __global__ __launch_bounds__(NT, 2) void k_av_split(const float *__restrict__ A,
         }
         if (jb + 2 < nkb) raw.load(vblocks + (size_t)(jb + 2) * KB * D, tid);
 
-#pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            f32x4 a0, a1;       // the 8 dense weights of keys 32 m + 8 g .. +7
-            if constexpr (SPARSE) {
-                // pair p: code 0x4 keeps element 0, 0xE element 1 (they differ in bit 1)
-                float d[8];
-#pragma unroll
-                for (int p = 0; p < 4; ++p) {
-                    const bool second = (a_cur.code[m] >> (4 * p + 1)) & 1u;
-                    d[2 * p] = second ? 0.f : a_cur.v[m][p];
-                    d[2 * p + 1] = second ? a_cur.v[m][p] : 0.f;
-                }
-                a0 = f32x4{d[0], d[1], d[2], d[3]};
-                a1 = f32x4{d[4], d[5], d[6], d[7]};
-            } else {
-                a0 = a_cur.v[2 * m];
-                a1 = a_cur.v[2 * m + 1];
-            }
+        if constexpr (SPARSE) {
+            // bit 1 of code i (0x4 / 0xE) -> bit 2i of the instruction's index operand; bits 2i+1 = i%2
+            uint32_t x = (a_cur.word >> 1) & 0x11111111u;
+            x = (x | (x >> 2)) & 0x05050505u;
+            x = (x | (x >> 4)) & 0x00FF00FFu;
+            x = (x | (x >> 8)) & 0xFFFFu;
+            const int idx = (int)(0x8888u | x);
             u32x4 ah, al;
-            split8(a0, a1, ah, al);
-            const int key0 = 32 * m + 8 * g;
+            split8(a_cur.v[0], a_cur.v[1], ah, al);
 #pragma unroll
-            for (int ds = 0; ds < DS; ++ds)
-                acc[ds] = mfma_split(ah, al, tr8(Vh[buf], key0, ds), tr8(Vl[buf], key0, ds), acc[ds]);
+            for (int ds = 0; ds < DS; ++ds) {
+                const u32x4 h0 = tr8(Vh[buf], 8 * g, ds), h1 = tr8(Vh[buf], 32 + 8 * g, ds);
+                const u32x4 l0 = tr8(Vl[buf], 8 * g, ds), l1 = tr8(Vl[buf], 32 + 8 * g, ds);
+                const bf16x16 bh16 = __builtin_bit_cast(bf16x16, __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7));
+                const bf16x16 bl16 = __builtin_bit_cast(bf16x16, __builtin_shufflevector(l0, l1, 0, 1, 2, 3, 4, 5, 6, 7));
+                acc[ds] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(al), bh16, acc[ds], idx, 0, 0);
+                acc[ds] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(ah), bl16, acc[ds], idx, 0, 0);
+                acc[ds] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(ah), bh16, acc[ds], idx, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+                u32x4 ah, al;
+                split8(a_cur.v[2 * m], a_cur.v[2 * m + 1], ah, al);
+                const int key0 = 32 * m + 8 * g;
+#pragma unroll
+                for (int ds = 0; ds < DS; ++ds)
+                    acc[ds] = mfma_split(ah, al, tr8(Vh[buf], key0, ds), tr8(Vl[buf], key0, ds), acc[ds]);
+            }
         }
         if (jb + 1 < nkb) a_cur = a_nxt;
     }
