@@ -265,3 +265,42 @@ def test_split_products_equal_fp32_on_bf16_exact_operands():
         torch.cuda.synchronize()
         out.append((vals.cpu(), meta.cpu()))
     assert torch.equal(out[0][0], out[1][0]) and torch.equal(out[0][1], out[1][1])
+
+
+@DTYPES
+def test_calls_replay_correctly_from_a_hip_graph(dtype):
+    """The float-mode entry points enqueued into one graph: each replay (eager work, synchronisations and
+    changed inputs in between) must reproduce the eager result of the same inputs bit for bit."""
+    s = _shape(2, 2, 128, 256, 64, dtype)
+    Q, K, V = (_dev(t) for t in synth.gaussian_qkv(4, 128, 256, 64, 1.0, seed=6500, dtype=torch.float32))
+    ws = torch.empty(max(dfss.dfss_workspace_bytes(s), dfss.dense_workspace_bytes(s)), dtype=torch.uint8, device=DEV)
+    names = ["attention", "dense", "stages"] + (["dense_fused"] if dtype == DFSS_F32_BF16X3 else [])
+    outs = {k: torch.empty_like(Q) for k in names}
+    vals = torch.empty((s.BH, s.Lq, s.Lc), dtype=torch.float32, device=DEV)
+    meta = torch.empty((s.BH * s.Lq * s.meta_words,), dtype=torch.int16, device=DEV)
+
+    def run_all():
+        dfss.dfss_attention(Q, K, V, s, 0.125, O=outs["attention"], ws=ws)
+        dfss.dense_attention(Q, K, V, s, 0.125, O=outs["dense"], ws=ws)
+        if "dense_fused" in outs:
+            dfss.dense_attention_fused(Q, K, V, s, 0.125, O=outs["dense_fused"])
+        dfss.dfss_sddmm_prune(Q, K, s, 0.125, vals=vals, meta=meta)
+        dfss.dfss_sparse_softmax(vals, s)
+        dfss.dfss_spmm(vals, meta, V, s, O=outs["stages"])
+
+    run_all()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run_all()
+    for rep in range(3):
+        Q.copy_(torch.randn(Q.shape, generator=torch.Generator().manual_seed(6600 + rep)))
+        run_all()
+        torch.cuda.synchronize()
+        eager = {k: v.clone() for k, v in outs.items()}
+        for v in outs.values():
+            v.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        for k in outs:
+            assert torch.equal(outs[k], eager[k]), (rep, k)
