@@ -21,7 +21,7 @@ namespace dfss {
 namespace {
 
 constexpr int NT = 256;   // 4 waves
-constexpr int QT = 64;    // queries per workgroup (A V kernel; the score kernel takes 64 NQ)
+constexpr int QT = 64;    // queries per workgroup (the score kernel takes 64 NQ)
 constexpr int KB = 64;    // keys per block
 
 // x[0..7] -> bf16 images (hi, lo), element e in the low/high half of dword e/2
@@ -67,9 +67,9 @@ struct RawBlock {
 // j-1) to the two bf16 images, stored at the permuted row (so that a lane ends up with 16 consecutive
 // keys, as in the fp32 kernel) with the 16-byte chunks XOR-swizzled by row; loads its share of block j+2;
 // then the waves run 3 matrix instructions per 16 x 16 x 32 product piece of block j, and the epilogue.
-// ---------------------------------------------------------------------------------------------
 // A wave owns NQ groups of 16 queries: the conversion of a block and the reads of its images are
 // shared by NQ times as many matrix instructions.
+// ---------------------------------------------------------------------------------------------
 template <int D, bool PRUNE, int NQ>
 __global__ __launch_bounds__(NT, 2) void k_scores_split(const float *__restrict__ Q, const float *__restrict__ K,
                                                         int Lq, int Lk, float scale, float *__restrict__ out,
