@@ -14,11 +14,11 @@ the named workload.  Prints ONE JSON line.
   cpu_baseline    the CPU oracle timed on the host cores (context only).
 
 Workloads whose name ends in ``_f32`` run the paper's second precision (float data, 1:2).  With the
-default ``--products bf16x3`` (fp32 products formed from bfloat16 pieces on the bf16 matrix pipe) and
-d = 64 everything is as for the 2-byte workloads (``dfss_attention`` is one kernel).  Otherwise
+default ``--products bf16x3`` (fp32 products formed from bfloat16 pieces on the bf16 matrix pipe)
+everything is as for the 2-byte workloads (``dfss_attention`` is one kernel).  With ``--products fp32``
 ``dfss_attention`` is the three stage kernels, the only full-attention baseline is the three-stage
 ``dense_attention``, and the roofline object describes the score/prune kernel (the largest of the
-three): against HBM for bf16x3 products, against the fp32 MFMA peak with ``--products fp32``.
+three) against the fp32 MFMA peak.
 
 Inputs are resident in HBM before timing starts.  By default the steps rotate over enough
 independent buffer sets that no step finds its inputs or workspace in the last-level cache
@@ -101,8 +101,8 @@ def main():
         print("bench.py: the float workloads run the plain forward pass only", file=sys.stderr)
         sys.exit(2)
     esz = 4 if f32 else 2
-    # one-kernel paths exist for the 2-byte modes and, in the float mode, for bf16x3 products with d = 64
-    has_fused = (not f32) or (split and w.d == 64)
+    # one-kernel paths exist for the 2-byte modes and, in the float mode, for bf16x3 products
+    has_fused = (not f32) or split
     K, W = args.steps, args.warmup
     BH, L, d = w.BH, w.L, w.d
 
@@ -330,14 +330,6 @@ def main():
             out["roofline"]["traffic"] = None
             out["roofline"]["algorithmic_hbm_bytes_per_launch"] = 4.0 * esz * BH * L * d
             out["roofline"]["executed_matrix_flops_per_launch"] = 3.0 * flops_alg
-        elif split:
-            # on the bf16 matrix pipe the kernel is bound by writing the kept scores and the metadata
-            gbs1 = bytes1 / (k1 * 1e-3) / 1e9
-            out["roofline"] = {"bound": "hbm", "kernel": "k_scores_split (dfss_sddmm_prune, float data, bf16x3 products)",
-                               "achieved": round(gbs1, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                               "frac": round(gbs1 / HBM_PEAK_GBS, 4), "traffic": None,
-                               "algorithmic_hbm_bytes_per_launch": bytes1, "avg_launch_ms": round(k1, 5),
-                               "algorithmic_flops_per_launch": flops1}
         else:
             # three kernels per step; the score/prune kernel is the largest and is bound by the fp32 matrix
             # instruction: 2 L^2 d flops per head per launch

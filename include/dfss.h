@@ -203,11 +203,10 @@ dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K
  * most 3 * 2^-18 |a*b| per product (the paper's format drops about 2^-10); operands that are exact
  * in bfloat16 (e.g. small integers) give exactly the DFSS_F32 result.  The softmax stage is the same
  * fp32 kernel.  Several times faster than DFSS_F32, whose matrix instruction is 16x slower.
- * With this dtype and d = 64, dfss_attention runs as ONE kernel that keeps the pruned scores and
- * the weights in registers (same function as the three stages, softmax kept up to date block by
- * block; DFSS_ATTENTION_PATH=staged selects the stage kernels), and dense_attention_fused is
- * available as the matching full-attention kernel; with d = 128 dfss_attention stays staged and
- * dense_attention_fused returns DFSS_ERR_UNSUPPORTED. */
+ * With this dtype dfss_attention runs as ONE kernel that keeps the pruned scores and the weights in
+ * registers (same function as the three stages, softmax kept up to date block by block;
+ * DFSS_ATTENTION_PATH=staged selects the stage kernels), and dense_attention_fused is available as
+ * the matching full-attention kernel. */
 
 /* ---- metadata order ---------------------------------------------------------------- */
 /* Canonical order: uint16 [B*H, Lq, Lk/16], word w of a row = codes of key runs

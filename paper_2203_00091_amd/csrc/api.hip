@@ -149,7 +149,7 @@ dfss_status dfss_attention_bias(const void *Q, const void *K, const void *V, con
     const float *bias = (const float *)key_bias;
     if (D.f32) {
         if (key_bias) return DFSS_ERR_UNSUPPORTED;
-        if (D.split && D.d == 64 && !staged_path_requested())
+        if (D.split && !staged_path_requested())
             return hip_status(dfss::launch_fused_attention_split(Q, K, V, D.BH, D.Lq, D.Lk, D.d, true, scale, O, st));
         char *vals = static_cast<char *>(ws);
         char *meta = vals + align_up(dfss_vals_bytes(s));
@@ -182,7 +182,7 @@ dfss_status dense_attention_fused_bias(const void *Q, const void *K, const void 
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias))
         return DFSS_ERR_SHAPE;
     if (D.f32) {
-        if (!D.split || D.d != 64 || key_bias) return DFSS_ERR_UNSUPPORTED;
+        if (!D.split || key_bias) return DFSS_ERR_UNSUPPORTED;
         return hip_status(dfss::launch_fused_attention_split(Q, K, V, D.BH, D.Lq, D.Lk, D.d, false, scale, O,
                                                              (hipStream_t)stream));
     }

@@ -54,7 +54,7 @@ hipError_t launch_spmm_split(const void *vals, const void *meta, const void *V, 
                              void *O, hipStream_t st);
 hipError_t launch_dense_av_split(const void *P, const void *V, int BH, int Lq, int Lk, int d, void *O,
                                  hipStream_t st);
-// Whole forward pass of the 4-byte mode in one kernel (split products; d = 64 only).  prune = false: full attention.
+// Whole forward pass of the 4-byte mode in one kernel (split products).  prune = false: full attention.
 hipError_t launch_fused_attention_split(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d,
                                         bool prune, float scale, void *O, hipStream_t st);
 // Metadata word order: library <-> canonical.  W = 32-bit words per row; permute: the 2-byte modes' order of

@@ -349,7 +349,11 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
     constexpr int DS = D / 16;
     constexpr int NV = PRUNE ? 8 : 16;           // weights per lane per block
     constexpr float kLog2e = 1.4426950408889634f;
-    __shared__ u32x4 Kh[2][KB * CPR], Kl[2][KB * CPR], Vh[2][KB * CPR], Vl[2][KB * CPR];
+    // d = 64: the images are double buffered and block j+1 is converted next to the arithmetic of block j (one
+    // barrier per block).  d = 128: four images of one block already fill the 64 KB a workgroup may declare, so
+    // they are single buffered with a second barrier between conversion and use.
+    constexpr int NBUF = D == 64 ? 2 : 1;
+    __shared__ u32x4 Kh[NBUF][KB * CPR], Kl[NBUF][KB * CPR], Vh[NBUF][KB * CPR], Vl[NBUF][KB * CPR];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, g = lane >> 4;
@@ -412,18 +416,29 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
     RawBlock<NCONV> rk, rv;
     rk.load(kblocks, tid);
     rv.load(vblocks, tid);
-    convert(rk, rv, 0);
-    if (nkb > 1) {
-        rk.load(kblocks + (size_t)KB * D, tid);
-        rv.load(vblocks + (size_t)KB * D, tid);
+    if constexpr (NBUF == 2) {
+        convert(rk, rv, 0);
+        if (nkb > 1) {
+            rk.load(kblocks + (size_t)KB * D, tid);
+            rv.load(vblocks + (size_t)KB * D, tid);
+        }
     }
     for (int jb = 0; jb < nkb; ++jb) {
-        const int buf = jb & 1;
-        __syncthreads();            // images of block jb complete; every wave is done with those of block jb-1
-        if (jb + 1 < nkb) convert(rk, rv, buf ^ 1);
-        if (jb + 2 < nkb) {
-            rk.load(kblocks + (size_t)(jb + 2) * KB * D, tid);
-            rv.load(vblocks + (size_t)(jb + 2) * KB * D, tid);
+        const int buf = NBUF == 2 ? jb & 1 : 0;
+        __syncthreads();            // every wave is done with the images of block jb-1 (NBUF = 2: those of jb complete)
+        if constexpr (NBUF == 2) {
+            if (jb + 1 < nkb) convert(rk, rv, buf ^ 1);
+            if (jb + 2 < nkb) {
+                rk.load(kblocks + (size_t)(jb + 2) * KB * D, tid);
+                rv.load(vblocks + (size_t)(jb + 2) * KB * D, tid);
+            }
+        } else {
+            convert(rk, rv, 0);
+            if (jb + 1 < nkb) {
+                rk.load(kblocks + (size_t)(jb + 1) * KB * D, tid);
+                rv.load(vblocks + (size_t)(jb + 1) * KB * D, tid);
+            }
+            __syncthreads();        // images of block jb complete
         }
 
         // scores of keys 16g + 4t + r (tile t, register r) of query n
@@ -569,14 +584,16 @@ hipError_t launch_av(const void *A, const void *meta, const void *V, int BH, int
 
 hipError_t launch_fused_attention_split(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d,
                                         bool prune, float scale, void *O, hipStream_t st) {
-    if (d != 64) return hipErrorInvalidValue;      // the double-buffered images of d = 128 do not fit two workgroups
     const unsigned grid = (unsigned)BH * (unsigned)(Lq / QT);
-    if (prune)
-        hipLaunchKernelGGL((k_fused_split<64, true>), dim3(grid), dim3(NT), 0, st, (const float *)Q, (const float *)K,
-                           (const float *)V, Lq, Lk, scale, (float *)O);
-    else
-        hipLaunchKernelGGL((k_fused_split<64, false>), dim3(grid), dim3(NT), 0, st, (const float *)Q, (const float *)K,
-                           (const float *)V, Lq, Lk, scale, (float *)O);
+#define DFSS_LAUNCH_FUSED_SPLIT(DD, PP)                                                                          \
+    hipLaunchKernelGGL((k_fused_split<DD, PP>), dim3(grid), dim3(NT), 0, st, (const float *)Q, (const float *)K, \
+                       (const float *)V, Lq, Lk, scale, (float *)O)
+    if (d == 64 && prune) DFSS_LAUNCH_FUSED_SPLIT(64, true);
+    else if (d == 64) DFSS_LAUNCH_FUSED_SPLIT(64, false);
+    else if (d == 128 && prune) DFSS_LAUNCH_FUSED_SPLIT(128, true);
+    else if (d == 128) DFSS_LAUNCH_FUSED_SPLIT(128, false);
+    else return hipErrorInvalidValue;
+#undef DFSS_LAUNCH_FUSED_SPLIT
     return hipGetLastError();
 }
 
