@@ -9,9 +9,10 @@
 // lo = 0 and give exactly the fp32 result.
 //
 // The workgroup converts each 64-row block of K (or V) once: every thread loads its 32-byte pieces of the
-// fp32 block into registers one block ahead, splits them, and writes the two bf16 images into LDS (double
-// buffered), which the waves then read as ordinary bf16 matrix operands -- one barrier per block, and the
-// conversion of block j+1 sits next to the matrix instructions of block j.  The layouts, the 1:2
+// fp32 block into registers one block ahead, splits them, and writes the two bf16 images into LDS, which the
+// waves then read as ordinary bf16 matrix operands.  The stage kernels double-buffer the images (one barrier
+// per block, the conversion of block j+1 next to the matrix instructions of block j); the one-kernel path
+// holds four images per block and keeps a single copy.  The layouts, the 1:2
 // epilogue and the metadata are those of the exact fp32 kernels (float_mode.hip).
 #include "dfss_device.hpp"
 #include "dfss_kernels.hpp"
@@ -349,11 +350,10 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
     constexpr int DS = D / 16;
     constexpr int NV = PRUNE ? 8 : 16;           // weights per lane per block
     constexpr float kLog2e = 1.4426950408889634f;
-    // d = 64: the images are double buffered and block j+1 is converted next to the arithmetic of block j (one
-    // barrier per block).  d = 128: four images of one block already fill the 64 KB a workgroup may declare, so
-    // they are single buffered with a second barrier between conversion and use.
-    constexpr int NBUF = D == 64 ? 2 : 1;
-    __shared__ u32x4 Kh[NBUF][KB * CPR], Kl[NBUF][KB * CPR], Vh[NBUF][KB * CPR], Vl[NBUF][KB * CPR];
+    // The four images are single buffered (two barriers per block: before the conversion, and between conversion
+    // and use): for d = 128 they fill the 64 KB a workgroup may declare, and for d = 64 the halved footprint lets a
+    // third workgroup share the CU, which gains more than overlapping the conversion with the arithmetic does.
+    __shared__ u32x4 Kh[KB * CPR], Kl[KB * CPR], Vh[KB * CPR], Vl[KB * CPR];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, g = lane >> 4;
@@ -381,16 +381,16 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
         dst_k[i] = slot * CPR + (c ^ (slot & 7));
         dst_v[i] = key * CPR + (c ^ ((key & 3) << 1));
     }
-    auto convert = [&](const RawBlock<NCONV> &rk, const RawBlock<NCONV> &rv, int buf) {
+    auto convert = [&](const RawBlock<NCONV> &rk, const RawBlock<NCONV> &rv) {
 #pragma unroll
         for (int i = 0; i < NCONV; ++i) {
             u32x4 h, l;
             split8(rk.v[i][0], rk.v[i][1], h, l);
-            Kh[buf][dst_k[i]] = h;
-            Kl[buf][dst_k[i]] = l;
+            Kh[dst_k[i]] = h;
+            Kl[dst_k[i]] = l;
             split8(rv.v[i][0], rv.v[i][1], h, l);
-            Vh[buf][dst_v[i]] = h;
-            Vl[buf][dst_v[i]] = l;
+            Vh[dst_v[i]] = h;
+            Vl[dst_v[i]] = l;
         }
     };
 
@@ -416,30 +416,14 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
     RawBlock<NCONV> rk, rv;
     rk.load(kblocks, tid);
     rv.load(vblocks, tid);
-    if constexpr (NBUF == 2) {
-        convert(rk, rv, 0);
-        if (nkb > 1) {
-            rk.load(kblocks + (size_t)KB * D, tid);
-            rv.load(vblocks + (size_t)KB * D, tid);
-        }
-    }
     for (int jb = 0; jb < nkb; ++jb) {
-        const int buf = NBUF == 2 ? jb & 1 : 0;
-        __syncthreads();            // every wave is done with the images of block jb-1 (NBUF = 2: those of jb complete)
-        if constexpr (NBUF == 2) {
-            if (jb + 1 < nkb) convert(rk, rv, buf ^ 1);
-            if (jb + 2 < nkb) {
-                rk.load(kblocks + (size_t)(jb + 2) * KB * D, tid);
-                rv.load(vblocks + (size_t)(jb + 2) * KB * D, tid);
-            }
-        } else {
-            convert(rk, rv, 0);
-            if (jb + 1 < nkb) {
-                rk.load(kblocks + (size_t)(jb + 1) * KB * D, tid);
-                rv.load(vblocks + (size_t)(jb + 1) * KB * D, tid);
-            }
-            __syncthreads();        // images of block jb complete
+        __syncthreads();            // every wave is done with the images of block jb-1
+        convert(rk, rv);
+        if (jb + 1 < nkb) {         // the next block travels while this one is used
+            rk.load(kblocks + (size_t)(jb + 1) * KB * D, tid);
+            rv.load(vblocks + (size_t)(jb + 1) * KB * D, tid);
         }
+        __syncthreads();            // images of block jb complete
 
         // scores of keys 16g + 4t + r (tile t, register r) of query n
         f32x4 acc[4];
@@ -450,7 +434,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 const int pos = slot * CPR + ((4 * s + g) ^ (n & 7));
-                acc[t] = mfma_split(Kh[buf][pos], Kl[buf][pos], qh[s], ql[s], acc[t]);
+                acc[t] = mfma_split(Kh[pos], Kl[pos], qh[s], ql[s], acc[t]);
             }
         }
 
@@ -506,8 +490,8 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
             const int idx = (int)(0x8888u | second);
 #pragma unroll
             for (int ds = 0; ds < DS; ++ds) {
-                const u32x4 h0 = tr8(Vh[buf], 8 * g, ds), h1 = tr8(Vh[buf], 32 + 8 * g, ds);
-                const u32x4 l0 = tr8(Vl[buf], 8 * g, ds), l1 = tr8(Vl[buf], 32 + 8 * g, ds);
+                const u32x4 h0 = tr8(Vh, 8 * g, ds), h1 = tr8(Vh, 32 + 8 * g, ds);
+                const u32x4 l0 = tr8(Vl, 8 * g, ds), l1 = tr8(Vl, 32 + 8 * g, ds);
                 const bf16x16 bh16 = __builtin_bit_cast(bf16x16, __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7));
                 const bf16x16 bl16 = __builtin_bit_cast(bf16x16, __builtin_shufflevector(l0, l1, 0, 1, 2, 3, 4, 5, 6, 7));
                 acc_o[ds] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(al), bh16, acc_o[ds], idx, 0, 0);
@@ -524,7 +508,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
                 const int key0 = 16 * g + 8 * m;
 #pragma unroll
                 for (int ds = 0; ds < DS; ++ds)
-                    acc_o[ds] = mfma_split(ah, al, tr8(Vh[buf], key0, ds), tr8(Vl[buf], key0, ds), acc_o[ds]);
+                    acc_o[ds] = mfma_split(ah, al, tr8(Vh, key0, ds), tr8(Vl, key0, ds), acc_o[ds]);
             }
         }
     }
