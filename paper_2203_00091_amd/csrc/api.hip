@@ -57,9 +57,10 @@ inline bool staged_path_requested() {
 inline dfss_status hip_status(hipError_t e) { return e == hipSuccess ? DFSS_OK : DFSS_ERR_HIP; }
 
 // stage 1 and stage 3 of the 4-byte mode, by the way the products are formed
-inline hipError_t sddmm_prune_f32(const Dims &D, const void *Q, const void *K, float scale, void *vals, void *meta,
-                                  hipStream_t st) {
-    return D.split ? dfss::launch_sddmm_prune_split(Q, K, D.BH, D.Lq, D.Lk, D.d, scale, vals, meta, st)
+// (a key bias is taken with split products only; callers have rejected it otherwise)
+inline hipError_t sddmm_prune_f32(const Dims &D, const void *Q, const void *K, const float *bias, float scale,
+                                  void *vals, void *meta, hipStream_t st) {
+    return D.split ? dfss::launch_sddmm_prune_split(Q, K, bias, D.H, D.BH, D.Lq, D.Lk, D.d, scale, vals, meta, st)
                    : dfss::launch_sddmm_prune_f32(Q, K, D.BH, D.Lq, D.Lk, D.d, scale, vals, meta, st);
 }
 inline hipError_t spmm_f32(const Dims &D, const void *vals, const void *meta, const void *V, void *O, hipStream_t st) {
@@ -104,8 +105,8 @@ dfss_status dfss_sddmm_prune_bias(const void *Q, const void *K, const void *key_
     if (misaligned(Q) || misaligned(K) || misaligned(vals) || misaligned(meta) || misaligned(key_bias))
         return DFSS_ERR_SHAPE;
     if (D.f32) {
-        if (key_bias) return DFSS_ERR_UNSUPPORTED;
-        return hip_status(sddmm_prune_f32(D, Q, K, scale, vals, meta, (hipStream_t)stream));
+        if (key_bias && !D.split) return DFSS_ERR_UNSUPPORTED;
+        return hip_status(sddmm_prune_f32(D, Q, K, (const float *)key_bias, scale, vals, meta, (hipStream_t)stream));
     }
     return hip_status(dfss::launch_sddmm_prune(Q, K, (const float *)key_bias, D.H, D.BH, D.Lq, D.Lk, D.d, D.mode,
                                                scale, vals, meta, (hipStream_t)stream));
@@ -148,12 +149,13 @@ dfss_status dfss_attention_bias(const void *Q, const void *K, const void *V, con
     hipStream_t st = (hipStream_t)stream;
     const float *bias = (const float *)key_bias;
     if (D.f32) {
-        if (key_bias) return DFSS_ERR_UNSUPPORTED;
+        if (key_bias && !D.split) return DFSS_ERR_UNSUPPORTED;
         if (D.split && !staged_path_requested())
-            return hip_status(dfss::launch_fused_attention_split(Q, K, V, D.BH, D.Lq, D.Lk, D.d, true, scale, O, st));
+            return hip_status(dfss::launch_fused_attention_split(Q, K, V, bias, D.H, D.BH, D.Lq, D.Lk, D.d, true, scale,
+                                                                 O, st));
         char *vals = static_cast<char *>(ws);
         char *meta = vals + align_up(dfss_vals_bytes(s));
-        hipError_t e = sddmm_prune_f32(D, Q, K, scale, vals, meta, st);
+        hipError_t e = sddmm_prune_f32(D, Q, K, bias, scale, vals, meta, st);
         if (e == hipSuccess) e = dfss::launch_row_softmax_f32(vals, (long)D.BH * D.Lq, D.Lk / 2, st);
         if (e == hipSuccess) e = spmm_f32(D, vals, meta, V, O, st);
         return hip_status(e);
@@ -182,9 +184,9 @@ dfss_status dense_attention_fused_bias(const void *Q, const void *K, const void 
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias))
         return DFSS_ERR_SHAPE;
     if (D.f32) {
-        if (!D.split || key_bias) return DFSS_ERR_UNSUPPORTED;
-        return hip_status(dfss::launch_fused_attention_split(Q, K, V, D.BH, D.Lq, D.Lk, D.d, false, scale, O,
-                                                             (hipStream_t)stream));
+        if (!D.split) return DFSS_ERR_UNSUPPORTED;
+        return hip_status(dfss::launch_fused_attention_split(Q, K, V, (const float *)key_bias, D.H, D.BH, D.Lq, D.Lk, D.d,
+                                                             false, scale, O, (hipStream_t)stream));
     }
     return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, nullptr, D.BH, D.Lq, D.Lk,
                                                    D.d, 2, scale, O, (hipStream_t)stream));
@@ -207,8 +209,9 @@ dfss_status dense_attention_bias(const void *Q, const void *K, const void *V, co
     if (ws_bytes < dense_workspace_bytes(s)) return DFSS_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     if (D.f32) {
-        if (key_bias) return DFSS_ERR_UNSUPPORTED;
-        hipError_t e = D.split ? dfss::launch_dense_scores_split(Q, K, D.BH, D.Lq, D.Lk, D.d, scale, ws, st)
+        if (key_bias && !D.split) return DFSS_ERR_UNSUPPORTED;
+        hipError_t e = D.split ? dfss::launch_dense_scores_split(Q, K, (const float *)key_bias, D.H, D.BH, D.Lq, D.Lk, D.d,
+                                                                 scale, ws, st)
                                : dfss::launch_dense_scores_f32(Q, K, D.BH, D.Lq, D.Lk, D.d, scale, ws, st);
         if (e == hipSuccess) e = dfss::launch_row_softmax_f32(ws, (long)D.BH * D.Lq, D.Lk, st);
         if (e == hipSuccess)

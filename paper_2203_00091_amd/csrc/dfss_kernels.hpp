@@ -46,17 +46,18 @@ hipError_t launch_spmm_f32(const void *vals, const void *meta, const void *V, in
 hipError_t launch_dense_av_f32(const void *P, const void *V, int BH, int Lq, int Lk, int d, void *O, hipStream_t st);
 // The same four operations with every fp32 product formed from bfloat16 pieces on the bf16 matrix pipe
 // (x = hi + lo; a.b ~ a_hi b_hi + a_hi b_lo + a_lo b_hi, fp32 accumulation); same layouts.
-hipError_t launch_sddmm_prune_split(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale,
-                                    void *vals, void *meta, hipStream_t st);
-hipError_t launch_dense_scores_split(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale,
-                                     void *S, hipStream_t st);
+hipError_t launch_sddmm_prune_split(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
+                                    int d, float scale, void *vals, void *meta, hipStream_t st);
+hipError_t launch_dense_scores_split(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq,
+                                     int Lk, int d, float scale, void *S, hipStream_t st);
 hipError_t launch_spmm_split(const void *vals, const void *meta, const void *V, int BH, int Lq, int Lk, int d,
                              void *O, hipStream_t st);
 hipError_t launch_dense_av_split(const void *P, const void *V, int BH, int Lq, int Lk, int d, void *O,
                                  hipStream_t st);
 // Whole forward pass of the 4-byte mode in one kernel (split products).  prune = false: full attention.
-hipError_t launch_fused_attention_split(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d,
-                                        bool prune, float scale, void *O, hipStream_t st);
+hipError_t launch_fused_attention_split(const void *Q, const void *K, const void *V, const float *key_bias, int H,
+                                        int BH, int Lq, int Lk, int d, bool prune, float scale, void *O,
+                                        hipStream_t st);
 // Metadata word order: library <-> canonical.  W = 32-bit words per row; permute: the 2-byte modes' order of
 // the four words of a (row, block), false for the 4-byte mode.
 hipError_t launch_meta_reorder(const void *src, void *dst, int BH, int Lq, int W, bool to_canonical, bool permute,

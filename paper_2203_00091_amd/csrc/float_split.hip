@@ -39,6 +39,13 @@ __device__ __forceinline__ void split8(const f32x4 &x0, const f32x4 &x1, u32x4 &
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const u32x4 &v) { return __builtin_bit_cast(bf16x8, v); }
 
+// scale * dot (+ key bias): two separately rounded fp32 operations, the order the scores are defined in
+template <bool BIAS>
+__device__ __forceinline__ float scaled_score(float dot, float scale, float bias) {
+    const float s = __fmul_rn(dot, scale);
+    return BIAS ? __fadd_rn(s, bias) : s;
+}
+
 // acc += a . b with a = ah + al, b = bh + bl (small terms first)
 __device__ __forceinline__ f32x4 mfma_split(const u32x4 &ah, const u32x4 &al, const u32x4 &bh, const u32x4 &bl,
                                             f32x4 acc) {
@@ -71,9 +78,11 @@ struct RawBlock {
 // A wave owns NQ groups of 16 queries: the conversion of a block and the reads of its images are
 // shared by NQ times as many matrix instructions.
 // ---------------------------------------------------------------------------------------------
-template <int D, bool PRUNE, int NQ>
+// BIAS: key_bias[b][j] (b = head / H) is added to the scaled score before the selection (-inf masks a key).
+template <int D, bool PRUNE, int NQ, bool BIAS>
 __global__ __launch_bounds__(NT, 2) void k_scores_split(const float *__restrict__ Q, const float *__restrict__ K,
-                                                        int Lq, int Lk, float scale, float *__restrict__ out,
+                                                        const float *__restrict__ key_bias, int H, int Lq, int Lk,
+                                                        float scale, float *__restrict__ out,
                                                         uint32_t *__restrict__ meta) {
     constexpr int CPR = D / 8;                   // 16-byte chunks per bf16 row
     constexpr int KS = D / 32;                   // contraction steps of 32
@@ -99,6 +108,7 @@ __global__ __launch_bounds__(NT, 2) void k_scores_split(const float *__restrict_
     }
 
     const float *kblocks = K + (size_t)bh * Lk * D;
+    const float *bias_b = BIAS ? key_bias + (size_t)(bh / H) * Lk + 16 * g : nullptr;   // this lane's 16 keys of block 0
     // where this thread's pieces go: piece idx = (key, c); row of the matrix tile that holds this key:
     // tile (key/4)%4, row 4*(key/16) + key%4
     int dst[NCONV];
@@ -133,6 +143,10 @@ __global__ __launch_bounds__(NT, 2) void k_scores_split(const float *__restrict_
         __syncthreads();            // images of block jb complete; every wave is done with those of block jb-1
         if (jb + 1 < nkb) convert(raw, buf ^ 1);
         if (jb + 2 < nkb) raw.load(kblocks + (size_t)(jb + 2) * KB * D, tid);
+        f32x4 kb[4];                // bias of keys 16g + 4t + r of this block
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            kb[t] = BIAS ? *reinterpret_cast<const f32x4 *>(bias_b + jb * KB + 4 * t) : f32x4{0.f, 0.f, 0.f, 0.f};
 
         f32x4 acc[NQ][4];
 #pragma unroll
@@ -158,7 +172,8 @@ __global__ __launch_bounds__(NT, 2) void k_scores_split(const float *__restrict_
                 for (int t = 0; t < 4; ++t)
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
-                        const float s0 = acc[j][t][2 * h] * scale, s1 = acc[j][t][2 * h + 1] * scale;
+                        const float s0 = scaled_score<BIAS>(acc[j][t][2 * h], scale, kb[t][2 * h]);
+                        const float s1 = scaled_score<BIAS>(acc[j][t][2 * h + 1], scale, kb[t][2 * h + 1]);
                         const bool second = s1 > s0;
                         const int p = 2 * t + h;
                         kept[p >> 2][p & 3] = second ? s1 : s0;
@@ -171,7 +186,12 @@ __global__ __launch_bounds__(NT, 2) void k_scores_split(const float *__restrict_
             } else {
                 f32x4 *sp = reinterpret_cast<f32x4 *>(orow + (size_t)(16 * j) * ostride + jb * KB + 16 * g);
 #pragma unroll
-                for (int t = 0; t < 4; ++t) sp[t] = acc[j][t] * scale;
+                for (int t = 0; t < 4; ++t) {
+                    f32x4 v;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v[r] = scaled_score<BIAS>(acc[j][t][r], scale, kb[t][r]);
+                    sp[t] = v;
+                }
             }
         }
     }
@@ -340,10 +360,11 @@ __global__ __launch_bounds__(NT, 2) void k_av_split(const float *__restrict__ A,
 // are fetched from lanes 4g + r.
 // PRUNE = false is full attention (Eq. 1) in the same structure, the baseline of this mode.
 // ---------------------------------------------------------------------------------------------
-template <int D, bool PRUNE>
+// BIAS: additive key bias as in k_scores_split; a masked key gets weight exactly 0.
+template <int D, bool PRUNE, bool BIAS>
 __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__ Q, const float *__restrict__ K,
-                                                       const float *__restrict__ V, int Lq, int Lk, float scale,
-                                                       float *__restrict__ O) {
+                                                       const float *__restrict__ V, const float *__restrict__ key_bias,
+                                                       int H, int Lq, int Lk, float scale, float *__restrict__ O) {
     constexpr int CPR = D / 8;
     constexpr int KS = D / 32;
     constexpr int NCONV = KB * CPR / NT;
@@ -372,6 +393,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
 
     const float *kblocks = K + (size_t)bh * Lk * D;
     const float *vblocks = V + (size_t)bh * Lk * D;
+    const float *bias_b = BIAS ? key_bias + (size_t)(bh / H) * Lk + 16 * g : nullptr;
     int dst_k[NCONV], dst_v[NCONV];
 #pragma unroll
     for (int i = 0; i < NCONV; ++i) {
@@ -424,6 +446,10 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
             rv.load(vblocks + (size_t)(jb + 1) * KB * D, tid);
         }
         __syncthreads();            // images of block jb complete
+        f32x4 kb[4];                // bias of keys 16g + 4t + r of this block
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            kb[t] = BIAS ? *reinterpret_cast<const f32x4 *>(bias_b + jb * KB + 4 * t) : f32x4{0.f, 0.f, 0.f, 0.f};
 
         // scores of keys 16g + 4t + r (tile t, register r) of query n
         f32x4 acc[4];
@@ -447,7 +473,8 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
             for (int t = 0; t < 4; ++t)
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
-                    const float s0 = acc[t][2 * h] * scale, s1 = acc[t][2 * h + 1] * scale;
+                    const float s0 = scaled_score<BIAS>(acc[t][2 * h], scale, kb[t][2 * h]);
+                    const float s1 = scaled_score<BIAS>(acc[t][2 * h + 1], scale, kb[t][2 * h + 1]);
                     const bool sec = s1 > s0;
                     w[2 * t + h] = sec ? s1 : s0;
                     second |= (sec ? 1u : 0u) << (2 * (2 * t + h));     // bit 2i: position code of pair i
@@ -456,7 +483,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
 #pragma unroll
             for (int t = 0; t < 4; ++t)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) w[4 * t + r] = acc[t][r] * scale;
+                for (int r = 0; r < 4; ++r) w[4 * t + r] = scaled_score<BIAS>(acc[t][r], scale, kb[t][r]);
         }
         m_loc = w[0];
 #pragma unroll
@@ -527,25 +554,29 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
 }
 
 template <int D, bool PRUNE, int NQ>
-hipError_t launch_scores_nq(const void *Q, const void *K, int BH, int Lq, int Lk, float scale, void *out, void *meta,
-                            hipStream_t st) {
+hipError_t launch_scores_nq(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
+                            float scale, void *out, void *meta, hipStream_t st) {
     const unsigned grid = (unsigned)BH * (unsigned)(Lq / (64 * NQ));
-    hipLaunchKernelGGL((k_scores_split<D, PRUNE, NQ>), dim3(grid), dim3(NT), 0, st, (const float *)Q,
-                       (const float *)K, Lq, Lk, scale, (float *)out, (uint32_t *)meta);
+    if (key_bias)
+        hipLaunchKernelGGL((k_scores_split<D, PRUNE, NQ, true>), dim3(grid), dim3(NT), 0, st, (const float *)Q,
+                           (const float *)K, key_bias, H, Lq, Lk, scale, (float *)out, (uint32_t *)meta);
+    else
+        hipLaunchKernelGGL((k_scores_split<D, PRUNE, NQ, false>), dim3(grid), dim3(NT), 0, st, (const float *)Q,
+                           (const float *)K, key_bias, H, Lq, Lk, scale, (float *)out, (uint32_t *)meta);
     return hipGetLastError();
 }
 
 template <bool PRUNE>
-hipError_t launch_scores(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale, void *out,
-                         void *meta, hipStream_t st) {
+hipError_t launch_scores(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk, int d,
+                         float scale, void *out, void *meta, hipStream_t st) {
     // 32 queries per wave where Lq allows and the grid still fills the chip
     const bool wide = Lq % 128 == 0 && (long)BH * (Lq / 128) >= 512;
     if (d == 64)
-        return wide ? launch_scores_nq<64, PRUNE, 2>(Q, K, BH, Lq, Lk, scale, out, meta, st)
-                    : launch_scores_nq<64, PRUNE, 1>(Q, K, BH, Lq, Lk, scale, out, meta, st);
+        return wide ? launch_scores_nq<64, PRUNE, 2>(Q, K, key_bias, H, BH, Lq, Lk, scale, out, meta, st)
+                    : launch_scores_nq<64, PRUNE, 1>(Q, K, key_bias, H, BH, Lq, Lk, scale, out, meta, st);
     if (d == 128)
-        return wide ? launch_scores_nq<128, PRUNE, 2>(Q, K, BH, Lq, Lk, scale, out, meta, st)
-                    : launch_scores_nq<128, PRUNE, 1>(Q, K, BH, Lq, Lk, scale, out, meta, st);
+        return wide ? launch_scores_nq<128, PRUNE, 2>(Q, K, key_bias, H, BH, Lq, Lk, scale, out, meta, st)
+                    : launch_scores_nq<128, PRUNE, 1>(Q, K, key_bias, H, BH, Lq, Lk, scale, out, meta, st);
     return hipErrorInvalidValue;
 }
 
@@ -566,28 +597,35 @@ hipError_t launch_av(const void *A, const void *meta, const void *V, int BH, int
 
 }  // namespace
 
-hipError_t launch_fused_attention_split(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d,
-                                        bool prune, float scale, void *O, hipStream_t st) {
+hipError_t launch_fused_attention_split(const void *Q, const void *K, const void *V, const float *key_bias, int H,
+                                        int BH, int Lq, int Lk, int d, bool prune, float scale, void *O,
+                                        hipStream_t st) {
     const unsigned grid = (unsigned)BH * (unsigned)(Lq / QT);
-#define DFSS_LAUNCH_FUSED_SPLIT(DD, PP)                                                                          \
-    hipLaunchKernelGGL((k_fused_split<DD, PP>), dim3(grid), dim3(NT), 0, st, (const float *)Q, (const float *)K, \
-                       (const float *)V, Lq, Lk, scale, (float *)O)
-    if (d == 64 && prune) DFSS_LAUNCH_FUSED_SPLIT(64, true);
-    else if (d == 64) DFSS_LAUNCH_FUSED_SPLIT(64, false);
-    else if (d == 128 && prune) DFSS_LAUNCH_FUSED_SPLIT(128, true);
-    else if (d == 128) DFSS_LAUNCH_FUSED_SPLIT(128, false);
+#define DFSS_LAUNCH_FUSED_SPLIT(DD, PP, BB)                                                                            \
+    hipLaunchKernelGGL((k_fused_split<DD, PP, BB>), dim3(grid), dim3(NT), 0, st, (const float *)Q, (const float *)K,   \
+                       (const float *)V, key_bias, H, Lq, Lk, scale, (float *)O)
+#define DFSS_LAUNCH_FUSED_SPLIT_B(DD, PP)                 \
+    do {                                                  \
+        if (key_bias) DFSS_LAUNCH_FUSED_SPLIT(DD, PP, true); \
+        else DFSS_LAUNCH_FUSED_SPLIT(DD, PP, false);      \
+    } while (0)
+    if (d == 64 && prune) DFSS_LAUNCH_FUSED_SPLIT_B(64, true);
+    else if (d == 64) DFSS_LAUNCH_FUSED_SPLIT_B(64, false);
+    else if (d == 128 && prune) DFSS_LAUNCH_FUSED_SPLIT_B(128, true);
+    else if (d == 128) DFSS_LAUNCH_FUSED_SPLIT_B(128, false);
     else return hipErrorInvalidValue;
+#undef DFSS_LAUNCH_FUSED_SPLIT_B
 #undef DFSS_LAUNCH_FUSED_SPLIT
     return hipGetLastError();
 }
 
-hipError_t launch_sddmm_prune_split(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale,
-                                    void *vals, void *meta, hipStream_t st) {
-    return launch_scores<true>(Q, K, BH, Lq, Lk, d, scale, vals, meta, st);
+hipError_t launch_sddmm_prune_split(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
+                                    int d, float scale, void *vals, void *meta, hipStream_t st) {
+    return launch_scores<true>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, vals, meta, st);
 }
-hipError_t launch_dense_scores_split(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale,
-                                     void *S, hipStream_t st) {
-    return launch_scores<false>(Q, K, BH, Lq, Lk, d, scale, S, nullptr, st);
+hipError_t launch_dense_scores_split(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq,
+                                     int Lk, int d, float scale, void *S, hipStream_t st) {
+    return launch_scores<false>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, S, nullptr, st);
 }
 hipError_t launch_spmm_split(const void *vals, const void *meta, const void *V, int BH, int Lq, int Lk, int d,
                              void *O, hipStream_t st) {

@@ -243,8 +243,9 @@ def test_unsupported_combinations_are_refused(dtype):
     if dtype == DFSS_F32:
         with pytest.raises(dfss.DfssError):
             dfss.dense_attention_fused(Q, K, K, s, 0.125)
-    with pytest.raises(dfss.DfssError):
-        dfss.dfss_attention_bias(Q, K, K, torch.zeros(1, 128, device=DEV), s, 0.125)
+    if dtype == DFSS_F32:      # a key bias is taken with bf16x3 products only
+        with pytest.raises(dfss.DfssError):
+            dfss.dfss_attention_bias(Q, K, K, torch.zeros(1, 128, device=DEV), s, 0.125)
     with pytest.raises(ValueError):          # bfloat16 tensors with a float shape
         dfss.dfss_attention(Q.bfloat16(), K.bfloat16(), K.bfloat16(), s, 0.125)
 
@@ -320,5 +321,95 @@ def test_one_kernel_path_when_every_block_raises_the_maximum():
     refd = oracle.attention(Q.numpy(), K.numpy(), V.numpy(), 2, 2, scale, store_bf16=False)
     assert np.isfinite(O.cpu().numpy()).all()
     # (near-tied pairs may be decided differently: neighbouring keys differ by little here, hence the path bar)
+    assert np.abs(O.cpu().numpy() - ref).max() <= 2e-2
+    assert np.abs(Od.cpu().numpy() - refd).max() <= TOL_O[DFSS_F32_BF16X3]
+
+
+# ----------------------------------------------------------------------------------
+# additive key bias (padding mask) in the float mode: bf16x3 products only
+# ----------------------------------------------------------------------------------
+def _padding_case(B, H, Lq, Lk, d, seed, integer):
+    """Float inputs of a padded batch: lengths that cut through pairs and blocks, bias 0 / -inf, plus a few
+    finite bias values (multiples of 1/4: exact in every sum that occurs on integer inputs)."""
+    gen = synth.integer_qkv if integer else synth.gaussian_qkv
+    args = (B * H, Lq, Lk, d, seed) if integer else (B * H, Lq, Lk, d, 1.0, seed)
+    Q, K, V = gen(*args, dtype=torch.float32)
+    lengths = synth.padding_lengths(B, Lk, seed + 1, min_frac=0.3)
+    lengths[lengths % 2 == 0] -= 1                       # odd lengths: the mask cuts a pair
+    lengths[0] = Lk
+    bias = synth.key_padding_bias(lengths, Lk)
+    g = torch.Generator().manual_seed(seed + 2)
+    finite = torch.randint(-8, 9, (B, Lk), generator=g).float() / 4
+    bias = torch.where(torch.isinf(bias), bias, torch.where(torch.rand(B, Lk, generator=g) < 0.2, finite, bias))
+    return Q, K, V, lengths, bias
+
+
+@pytest.mark.parametrize("B,H,Lq,Lk,d", [(2, 2, 128, 256, 64), (3, 1, 64, 384, 128), (16, 4, 1024, 128, 64)])
+def test_stage1_key_bias_bit_exact_on_integer_inputs(B, H, Lq, Lk, d):
+    Q, K, _, lengths, bias = _padding_case(B, H, Lq, Lk, d, 6800 + Lq + d, integer=True)
+    s = _shape(B, H, Lq, Lk, d, DFSS_F32_BF16X3)
+    vals, meta = dfss.dfss_sddmm_prune_bias(_dev(Q), _dev(K), _dev(bias), s, 0.125)
+    torch.cuda.synchronize()
+    vals, meta = vals.cpu().numpy(), _meta_np(meta, s)
+    assert int((lengths % 2 != 0).sum()) > 0
+    for h in range(B * H) if B * H <= 8 else (0, 5, B * H - 1):
+        S = oracle.add_key_bias(oracle.scores(Q[h].numpy(), K[h].numpy(), 0.125), bias[h // H].numpy())
+        _, v, kidx = oracle.prune(S, 1, 2)
+        assert np.array_equal(meta[h], oracle.encode_meta_f32(kidx, Lk)), f"metadata differs in head {h}"
+        assert np.array_equal(vals[h], v), f"kept scores differ in head {h}"      # includes -inf entries
+
+
+@pytest.mark.parametrize("B,H,Lq,Lk,d", [(2, 2, 128, 256, 64), (2, 2, 64, 384, 128)])
+def test_attention_key_bias(B, H, Lq, Lk, d, monkeypatch):
+    """Whole path with a padding mask: one kernel, stage kernels, both full-attention baselines."""
+    Q, K, V, lengths, bias = _padding_case(B, H, Lq, Lk, d, 6900 + Lq + d, integer=False)
+    s = _shape(B, H, Lq, Lk, d, DFSS_F32_BF16X3)
+    scale = 1.0 / math.sqrt(d)
+    Qd, Kd, Vd, bd = _dev(Q), _dev(K), _dev(V), _dev(bias)
+    O = dfss.dfss_attention_bias(Qd, Kd, Vd, bd, s, scale)
+    Odf = dfss.dense_attention_fused_bias(Qd, Kd, Vd, bd, s, scale)
+    Od = dfss.dense_attention_bias(Qd, Kd, Vd, bd, s, scale)
+    O0 = dfss.dfss_attention_bias(Qd, Kd, Vd, None, s, scale)          # NULL bias = the plain call
+    O1 = dfss.dfss_attention(Qd, Kd, Vd, s, scale)
+    monkeypatch.setenv("DFSS_ATTENTION_PATH", "staged")
+    Os = dfss.dfss_attention_bias(Qd, Kd, Vd, bd, s, scale)
+    torch.cuda.synchronize()
+    assert torch.equal(O0, O1)
+    Qn, Kn, Vn = Q.numpy(), K.numpy(), V.numpy()
+    ref = oracle.attention(Qn, Kn, Vn, 1, 2, scale, store_bf16=False, key_bias=bias.numpy(), heads_per_batch=H)
+    refd = oracle.attention(Qn, Kn, Vn, 2, 2, scale, store_bf16=False, key_bias=bias.numpy(), heads_per_batch=H)
+    for name, got in (("one kernel", O), ("staged", Os)):
+        got = got.cpu().numpy()
+        assert np.isfinite(got).all(), name
+        assert np.abs(got - ref).max() <= 2e-2, name
+    for name, got in (("dense fused", Odf), ("dense 3-stage", Od)):
+        assert np.abs(got.cpu().numpy() - refd).max() <= TOL_O[DFSS_F32_BF16X3], name
+    # rows with no pair inside the error window: fp32-like accuracy of the pruned path
+    for h in range(B * H):
+        S = oracle.add_key_bias(oracle.scores(Qn[h], Kn[h], scale), bias[h // H].numpy())
+        bound = _score_error_bound(Qn[h], Kn[h], scale, DFSS_F32_BF16X3)
+        with np.errstate(invalid="ignore"):
+            gap = np.abs(S[:, 0::2] - S[:, 1::2])              # nan where both keys of a pair are masked
+        safe = (np.isnan(gap) | (gap > 2 * (bound[:, 0::2] + bound[:, 1::2]))).all(-1)
+        assert safe.sum() > 0
+        assert np.abs(O.cpu().numpy()[h] - ref[h])[safe].max() <= TOL_O[DFSS_F32_BF16X3]
+
+
+def test_attention_key_bias_first_blocks_fully_masked():
+    """Leading key blocks that are entirely masked: the running maximum stays at its start value until the
+    first real key, and nothing of the masked blocks reaches the output."""
+    B, H, Lq, Lk, d = 1, 2, 64, 512, 64
+    Q, K, V = synth.gaussian_qkv(B * H, Lq, Lk, d, 1.0, 6950, dtype=torch.float32)
+    bias = torch.zeros(B, Lk)
+    bias[:, :200] = float("-inf")
+    s = _shape(B, H, Lq, Lk, d, DFSS_F32_BF16X3)
+    O = dfss.dfss_attention_bias(_dev(Q), _dev(K), _dev(V), _dev(bias), s, 0.125)
+    Od = dfss.dense_attention_fused_bias(_dev(Q), _dev(K), _dev(V), _dev(bias), s, 0.125)
+    torch.cuda.synchronize()
+    ref = oracle.attention(Q.numpy(), K.numpy(), V.numpy(), 1, 2, 0.125, store_bf16=False, key_bias=bias.numpy(),
+                           heads_per_batch=H)
+    refd = oracle.attention(Q.numpy(), K.numpy(), V.numpy(), 2, 2, 0.125, store_bf16=False, key_bias=bias.numpy(),
+                            heads_per_batch=H)
+    assert np.isfinite(O.cpu().numpy()).all()
     assert np.abs(O.cpu().numpy() - ref).max() <= 2e-2
     assert np.abs(Od.cpu().numpy() - refd).max() <= TOL_O[DFSS_F32_BF16X3]
