@@ -62,6 +62,11 @@ WORKLOADS = {
         Workload("long_L4096_1to2_f32", 2, 12, 4096, 64, 1, 2, 1.0, 6004, float32=True),
         Workload("large_head_L2048_d128_1to2_f32", 4, 16, 2048, 128, 1, 2, 0.5, 6005, float32=True),
     ]
+    # the paper's latency study (Sec. 5.2): 4 heads, d = 64, L = 256 .. 4096, batch large enough to keep the GPU
+    # busy (here B * L = 32768 tokens at every length), in its two precisions
+    + [Workload(f"curve_L{L}_2to4", 32768 // L, 4, L, 64, 2, 4, 1.0, 7000 + L) for L in (256, 512, 1024, 2048, 4096)]
+    + [Workload(f"curve_L{L}_1to2_f32", 32768 // L, 4, L, 64, 1, 2, 1.0, 7500 + L, float32=True)
+       for L in (256, 512, 1024, 2048, 4096)]
 }
 
 
