@@ -492,7 +492,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
         m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, kWave));
         const float m_new = fmaxf(m_run, m_loc);
         if (__ballot(m_new > m_run) != 0) {     // some query of this wave has a new maximum: rescale
-            const float alpha = exp2f((m_run - m_new) * kLog2e);
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * kLog2e);   // 1 where unchanged
             l_run *= alpha;
             m_run = m_new;
 #pragma unroll
@@ -505,7 +505,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
         const float mb = m_run * kLog2e;
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
-            w[i] = exp2f(w[i] * kLog2e - mb);
+            w[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(w[i], kLog2e, -mb));   // the bare instruction: tiny results flush to 0
             l_run += w[i];
         }
 
