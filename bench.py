@@ -44,7 +44,8 @@ MFMA_F32_PEAK_TFLOPS = 157.3    # dense fp32 MFMA (the workloads of the 4-byte m
 LLC_BYTES = 256 << 20           # last-level (Infinity) cache; L2 is 8 x 4 MiB on top
 # HBM bytes per launch of the fused kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (scaled by what the same counters read for a plain 64 MiB copy); summaries under profiles/.
-MEASURED_TRAFFIC_BYTES = {"bert_base_L384_2to4": 14.23e6 + 4.72e6}
+MEASURED_TRAFFIC_BYTES = {"bert_base_L384_2to4": 14.23e6 + 4.72e6,
+                          "bert_base_L512_1to2_f32": 75.6e6 + 25.2e6}   # (one-kernel path, bf16x3 products)
 
 
 def parse_args():
@@ -328,7 +329,6 @@ def main():
             # one kernel (k_fused_split) on the bf16 matrix pipe; every algorithmic product is executed as
             # three bf16 products, so a third of the bf16 peak is the most this route can reach
             out["roofline"]["kernel"] = "k_fused_split (dfss_attention, float data, bf16x3 products)"
-            out["roofline"]["traffic"] = None
             out["roofline"]["algorithmic_hbm_bytes_per_launch"] = 4.0 * esz * BH * L * d
             out["roofline"]["executed_matrix_flops_per_launch"] = 3.0 * flops_alg
         else:
