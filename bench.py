@@ -98,9 +98,9 @@ def main():
     split = f32 and args.products == "bf16x3"
     s = Shape(w.B, w.H, w.L, w.L, w.d, w.N, w.M,
               (dfss.DFSS_F32_BF16X3 if split else dfss.DFSS_F32) if f32 else dfss.DFSS_BF16)
-    if f32 and (args.block_pattern or args.backward or (args.key_padding and not split)):
-        print("bench.py: the float workloads run the forward pass only, without block patterns; a key bias is "
-              "taken with --products bf16x3 only", file=sys.stderr)
+    if f32 and (args.backward or ((args.key_padding or args.block_pattern) and not split)):
+        print("bench.py: the float workloads run the forward pass only; a key bias or a block pattern is taken "
+              "with --products bf16x3 only", file=sys.stderr)
         sys.exit(2)
     esz = 4 if f32 else 2
     # one-kernel paths exist for the 2-byte modes and, in the float mode, for bf16x3 products

@@ -151,8 +151,8 @@ dfss_status dfss_attention_bias(const void *Q, const void *K, const void *V, con
     if (D.f32) {
         if (key_bias && !D.split) return DFSS_ERR_UNSUPPORTED;
         if (D.split && !staged_path_requested())
-            return hip_status(dfss::launch_fused_attention_split(Q, K, V, bias, D.H, D.BH, D.Lq, D.Lk, D.d, true, scale,
-                                                                 O, st));
+            return hip_status(dfss::launch_fused_attention_split(Q, K, V, bias, D.H, nullptr, D.BH, D.Lq, D.Lk, D.d, true,
+                                                                 scale, O, st));
         char *vals = static_cast<char *>(ws);
         char *meta = vals + align_up(dfss_vals_bytes(s));
         hipError_t e = sddmm_prune_f32(D, Q, K, bias, scale, vals, meta, st);
@@ -185,8 +185,8 @@ dfss_status dense_attention_fused_bias(const void *Q, const void *K, const void 
         return DFSS_ERR_SHAPE;
     if (D.f32) {
         if (!D.split) return DFSS_ERR_UNSUPPORTED;
-        return hip_status(dfss::launch_fused_attention_split(Q, K, V, (const float *)key_bias, D.H, D.BH, D.Lq, D.Lk, D.d,
-                                                             false, scale, O, (hipStream_t)stream));
+        return hip_status(dfss::launch_fused_attention_split(Q, K, V, (const float *)key_bias, D.H, nullptr, D.BH, D.Lq,
+                                                             D.Lk, D.d, false, scale, O, (hipStream_t)stream));
     }
     return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, nullptr, D.BH, D.Lq, D.Lk,
                                                    D.d, 2, scale, O, (hipStream_t)stream));
@@ -240,7 +240,12 @@ static dfss_status attention_blocked(const void *Q, const void *K, const void *V
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias))
         return DFSS_ERR_SHAPE;
-    if (D.f32) return DFSS_ERR_UNSUPPORTED;
+    if (D.f32) {
+        if (!D.split) return DFSS_ERR_UNSUPPORTED;
+        return hip_status(dfss::launch_fused_attention_split(Q, K, V, (const float *)key_bias, D.H,
+                                                             (const uint8_t *)block_mask, D.BH, D.Lq, D.Lk, D.d, !dense,
+                                                             scale, O, (hipStream_t)stream));
+    }
     return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, (const uint8_t *)block_mask,
                                                    D.BH, D.Lq, D.Lk, D.d, dense ? 2 : D.mode, scale, O,
                                                    (hipStream_t)stream));

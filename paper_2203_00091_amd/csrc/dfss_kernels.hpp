@@ -55,9 +55,10 @@ hipError_t launch_spmm_split(const void *vals, const void *meta, const void *V, 
 hipError_t launch_dense_av_split(const void *P, const void *V, int BH, int Lq, int Lk, int d, void *O,
                                  hipStream_t st);
 // Whole forward pass of the 4-byte mode in one kernel (split products).  prune = false: full attention.
+// key_bias and block_mask (both may be null) as in launch_fused_attention.
 hipError_t launch_fused_attention_split(const void *Q, const void *K, const void *V, const float *key_bias, int H,
-                                        int BH, int Lq, int Lk, int d, bool prune, float scale, void *O,
-                                        hipStream_t st);
+                                        const uint8_t *block_mask, int BH, int Lq, int Lk, int d, bool prune,
+                                        float scale, void *O, hipStream_t st);
 // Metadata word order: library <-> canonical.  W = 32-bit words per row; permute: the 2-byte modes' order of
 // the four words of a (row, block), false for the 4-byte mode.
 hipError_t launch_meta_reorder(const void *src, void *dst, int BH, int Lq, int W, bool to_canonical, bool permute,

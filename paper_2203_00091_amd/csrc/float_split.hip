@@ -361,10 +361,13 @@ __global__ __launch_bounds__(NT, 2) void k_av_split(const float *__restrict__ A,
 // PRUNE = false is full attention (Eq. 1) in the same structure, the baseline of this mode.
 // ---------------------------------------------------------------------------------------------
 // BIAS: additive key bias as in k_scores_split; a masked key gets weight exactly 0.
+// block_mask (may be null): uint8 [Lq/64][Lk/64] shared by all heads; the 64 x 64 blocks of the score matrix with a
+// zero entry are skipped (the workgroup's 64 queries are one row of blocks), as if all their scores were -inf.
 template <int D, bool PRUNE, bool BIAS>
 __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__ Q, const float *__restrict__ K,
                                                        const float *__restrict__ V, const float *__restrict__ key_bias,
-                                                       int H, int Lq, int Lk, float scale, float *__restrict__ O) {
+                                                       int H, const uint8_t *__restrict__ block_mask, int Lq, int Lk,
+                                                       float scale, float *__restrict__ O) {
     constexpr int CPR = D / 8;
     constexpr int KS = D / 32;
     constexpr int NCONV = KB * CPR / NT;
@@ -435,15 +438,27 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
     float m_run = -1e30f;      // running maximum of query n (the same in its four lanes)
     float l_run = 0.f;         // this lane's share of the running sum of query n
 
+    // the blocks of this row of blocks that take part, in order (all of them without a block pattern)
+    const uint8_t *live = block_mask ? block_mask + (size_t)qt * nkb : nullptr;
+    auto next_block = [&](int j) {
+        if (live)
+            while (j < nkb && live[j] == 0) ++j;
+        return j;
+    };
+
     RawBlock<NCONV> rk, rv;
-    rk.load(kblocks, tid);
-    rv.load(vblocks, tid);
-    for (int jb = 0; jb < nkb; ++jb) {
-        __syncthreads();            // every wave is done with the images of block jb-1
+    int jb = next_block(0);
+    if (jb < nkb) {
+        rk.load(kblocks + (size_t)jb * KB * D, tid);
+        rv.load(vblocks + (size_t)jb * KB * D, tid);
+    }
+    while (jb < nkb) {
+        const int jnext = next_block(jb + 1);
+        __syncthreads();            // every wave is done with the images of the previous block
         convert(rk, rv);
-        if (jb + 1 < nkb) {         // the next block travels while this one is used
-            rk.load(kblocks + (size_t)(jb + 1) * KB * D, tid);
-            rv.load(vblocks + (size_t)(jb + 1) * KB * D, tid);
+        if (jnext < nkb) {          // the next block travels while this one is used
+            rk.load(kblocks + (size_t)jnext * KB * D, tid);
+            rv.load(vblocks + (size_t)jnext * KB * D, tid);
         }
         __syncthreads();            // images of block jb complete
         f32x4 kb[4];                // bias of keys 16g + 4t + r of this block
@@ -538,6 +553,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
                     acc_o[ds] = mfma_split(ah, al, tr8(Vh, key0, ds), tr8(Vl, key0, ds), acc_o[ds]);
             }
         }
+        jb = jnext;
     }
 
     // row sums: the four lanes of a query add up; then the factor of query 4g + r comes from lane 4g + r
@@ -598,12 +614,12 @@ hipError_t launch_av(const void *A, const void *meta, const void *V, int BH, int
 }  // namespace
 
 hipError_t launch_fused_attention_split(const void *Q, const void *K, const void *V, const float *key_bias, int H,
-                                        int BH, int Lq, int Lk, int d, bool prune, float scale, void *O,
-                                        hipStream_t st) {
+                                        const uint8_t *block_mask, int BH, int Lq, int Lk, int d, bool prune,
+                                        float scale, void *O, hipStream_t st) {
     const unsigned grid = (unsigned)BH * (unsigned)(Lq / QT);
 #define DFSS_LAUNCH_FUSED_SPLIT(DD, PP, BB)                                                                            \
     hipLaunchKernelGGL((k_fused_split<DD, PP, BB>), dim3(grid), dim3(NT), 0, st, (const float *)Q, (const float *)K,   \
-                       (const float *)V, key_bias, H, Lq, Lk, scale, (float *)O)
+                       (const float *)V, key_bias, H, block_mask, Lq, Lk, scale, (float *)O)
 #define DFSS_LAUNCH_FUSED_SPLIT_B(DD, PP)                 \
     do {                                                  \
         if (key_bias) DFSS_LAUNCH_FUSED_SPLIT(DD, PP, true); \

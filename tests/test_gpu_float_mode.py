@@ -243,7 +243,9 @@ def test_unsupported_combinations_are_refused(dtype):
     if dtype == DFSS_F32:
         with pytest.raises(dfss.DfssError):
             dfss.dense_attention_fused(Q, K, K, s, 0.125)
-    if dtype == DFSS_F32:      # a key bias is taken with bf16x3 products only
+    if dtype == DFSS_F32:      # block patterns and a key bias are taken with bf16x3 products only
+        with pytest.raises(dfss.DfssError):
+            dfss.dfss_attention_blocked(Q, K, K, None, torch.ones(1, 2, dtype=torch.uint8, device=DEV), s, 0.125)
         with pytest.raises(dfss.DfssError):
             dfss.dfss_attention_bias(Q, K, K, torch.zeros(1, 128, device=DEV), s, 0.125)
     with pytest.raises(ValueError):          # bfloat16 tensors with a float shape
@@ -413,3 +415,49 @@ def test_attention_key_bias_first_blocks_fully_masked():
     assert np.isfinite(O.cpu().numpy()).all()
     assert np.abs(O.cpu().numpy() - ref).max() <= 2e-2
     assert np.abs(Od.cpu().numpy() - refd).max() <= TOL_O[DFSS_F32_BF16X3]
+
+
+# ----------------------------------------------------------------------------------
+# hybrid block sparsity x 1:2 (64 x 64 block patterns) in the float mode: bf16x3 products only
+# ----------------------------------------------------------------------------------
+@pytest.mark.parametrize("BH,Lq,Lk,d", [(2, 256, 256, 64), (2, 128, 1024, 64), (1, 192, 512, 128)])
+def test_attention_blocked(BH, Lq, Lk, d):
+    Q, K, V = synth.gaussian_qkv(BH, Lq, Lk, d, 1.0, seed=7000 + Lq + Lk + d, dtype=torch.float32)
+    small = Lk // 64 <= 4
+    bm = synth.block_pattern(Lq // 64, Lk // 64, seed=7001 + Lk, window=0 if small else 1, n_random=0 if small else 3)
+    assert 0 < int(bm.sum()) < bm.numel()
+    s = _shape(1, BH, Lq, Lk, d, DFSS_F32_BF16X3)
+    scale = 1.0 / math.sqrt(d)
+    Qd, Kd, Vd, bmd = _dev(Q), _dev(K), _dev(V), _dev(bm)
+    O = dfss.dfss_attention_blocked(Qd, Kd, Vd, None, bmd, s, scale)
+    Od = dfss.dense_attention_fused_blocked(Qd, Kd, Vd, None, bmd, s, scale)
+    torch.cuda.synchronize()
+    Qn, Kn, Vn = Q.numpy(), K.numpy(), V.numpy()
+    ref = oracle.attention(Qn, Kn, Vn, 1, 2, scale, store_bf16=False, block_mask=bm.numpy(), block_size=64)
+    ref_dense = oracle.attention(Qn, Kn, Vn, 2, 2, scale, store_bf16=False, block_mask=bm.numpy(), block_size=64)
+    assert np.abs(O.cpu().numpy() - ref).max() <= 2e-2
+    assert np.abs(Od.cpu().numpy() - ref_dense).max() <= TOL_O[DFSS_F32_BF16X3]
+    # the pattern matters: full attention gives something else
+    assert np.abs(ref - oracle.attention(Qn, Kn, Vn, 1, 2, scale, store_bf16=False)).max() > 0.05
+
+
+def test_attention_blocked_with_key_bias_and_full_pattern():
+    B, H, L, d = 2, 2, 384, 64
+    Q, K, V, lengths, bias = _padding_case(B, H, L, L, d, 7100, integer=False)
+    s = _shape(B, H, L, L, d, DFSS_F32_BF16X3)
+    Qd, Kd, Vd, bd = _dev(Q), _dev(K), _dev(V), _dev(bias)
+    # block pattern and padding mask together (row blocks keep block 0, which always holds real keys)
+    bm = synth.block_pattern(L // 64, L // 64, seed=7101, n_random=1)
+    O = dfss.dfss_attention_blocked(Qd, Kd, Vd, bd, _dev(bm), s, 0.125)
+    torch.cuda.synchronize()
+    ref = oracle.attention(Q.numpy(), K.numpy(), V.numpy(), 1, 2, 0.125, store_bf16=False, key_bias=bias.numpy(),
+                           heads_per_batch=H, block_mask=bm.numpy(), block_size=64)
+    assert np.abs(O.cpu().numpy() - ref).max() <= 2e-2
+    # a pattern that keeps every block is the unblocked call, bit for bit
+    ones = torch.ones((L // 64, L // 64), dtype=torch.uint8)
+    O1 = dfss.dfss_attention_blocked(Qd, Kd, Vd, bd, _dev(ones), s, 0.125)
+    O2 = dfss.dfss_attention_bias(Qd, Kd, Vd, bd, s, 0.125)
+    O3 = dfss.dense_attention_fused_blocked(Qd, Kd, Vd, None, _dev(ones), s, 0.125)
+    O4 = dfss.dense_attention_fused(Qd, Kd, Vd, s, 0.125)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2) and torch.equal(O3, O4)
