@@ -77,7 +77,8 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only; --gpus N with N > 1 is not supported "
-              "(heads are independent, see DESIGN.md for how the path would shard).", file=sys.stderr)
+              "(heads are independent: the path would shard by splitting them across GPUs, with no exchange).",
+              file=sys.stderr)
         sys.exit(2)
 
     import torch
