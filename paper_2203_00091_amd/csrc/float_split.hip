@@ -55,14 +55,14 @@ __device__ __forceinline__ f32x4 mfma_split(const u32x4 &ah, const u32x4 &al, co
 }
 
 // One thread's share of a 64-row fp32 block (rows of D floats, contiguous in memory): NCONV pieces of 8
-// floats, piece i = the 8 floats at float offset 8 * (i * NT + tid) of the block.
-template <int NCONV>
+// floats, piece i = the 8 floats at float offset 8 * (i * THREADS + tid) of the block.
+template <int NCONV, int THREADS = NT>
 struct RawBlock {
     f32x4 v[NCONV][2];
     __device__ __forceinline__ void load(const float *block, int tid) {
 #pragma unroll
         for (int i = 0; i < NCONV; ++i) {
-            const f32x4 *p = reinterpret_cast<const f32x4 *>(block + 8 * (i * NT + tid));
+            const f32x4 *p = reinterpret_cast<const f32x4 *>(block + 8 * (i * THREADS + tid));
             v[i][0] = p[0];
             v[i][1] = p[1];
         }
@@ -363,13 +363,17 @@ __global__ __launch_bounds__(NT, 2) void k_av_split(const float *__restrict__ A,
 // BIAS: additive key bias as in k_scores_split; a masked key gets weight exactly 0.
 // block_mask (may be null): uint8 [Lq/64][Lk/64] shared by all heads; the 64 x 64 blocks of the score matrix with a
 // zero entry are skipped (the workgroup's 64 queries are one row of blocks), as if all their scores were -inf.
-template <int D, bool PRUNE, bool BIAS>
-__global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__ Q, const float *__restrict__ K,
+// NW waves of 16 queries per workgroup: with 8 waves (Lq a multiple of 128, no block pattern) the conversion
+// of a block is spread over twice the threads and shared by twice the queries (at d = 64 the register budget
+// is then held to 128 so that two such workgroups share a CU).
+template <int D, bool PRUNE, bool BIAS, int NW>
+__global__ __launch_bounds__(NW * 64, (D == 64 && NW == 8) ? 4 : 2) void k_fused_split(const float *__restrict__ Q, const float *__restrict__ K,
                                                        const float *__restrict__ V, const float *__restrict__ key_bias,
                                                        int H, const uint8_t *__restrict__ block_mask, int Lq, int Lk,
                                                        float scale, float *__restrict__ O) {
     constexpr int CPR = D / 8;
     constexpr int KS = D / 32;
+    constexpr int NT = NW * 64, QT = NW * 16;    // threads and queries per workgroup
     constexpr int NCONV = KB * CPR / NT;
     constexpr int DS = D / 16;
     constexpr int NV = PRUNE ? 8 : 16;           // weights per lane per block
@@ -406,7 +410,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
         dst_k[i] = slot * CPR + (c ^ (slot & 7));
         dst_v[i] = key * CPR + (c ^ ((key & 3) << 1));
     }
-    auto convert = [&](const RawBlock<NCONV> &rk, const RawBlock<NCONV> &rv) {
+    auto convert = [&](const RawBlock<NCONV, NT> &rk, const RawBlock<NCONV, NT> &rv) {
 #pragma unroll
         for (int i = 0; i < NCONV; ++i) {
             u32x4 h, l;
@@ -446,7 +450,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused_split(const float *__restrict__
         return j;
     };
 
-    RawBlock<NCONV> rk, rv;
+    RawBlock<NCONV, NT> rk, rv;
     int jb = next_block(0);
     if (jb < nkb) {
         rk.load(kblocks + (size_t)jb * KB * D, tid);
@@ -616,14 +620,19 @@ hipError_t launch_av(const void *A, const void *meta, const void *V, int BH, int
 hipError_t launch_fused_attention_split(const void *Q, const void *K, const void *V, const float *key_bias, int H,
                                         const uint8_t *block_mask, int BH, int Lq, int Lk, int d, bool prune,
                                         float scale, void *O, hipStream_t st) {
-    const unsigned grid = (unsigned)BH * (unsigned)(Lq / QT);
-#define DFSS_LAUNCH_FUSED_SPLIT(DD, PP, BB)                                                                            \
-    hipLaunchKernelGGL((k_fused_split<DD, PP, BB>), dim3(grid), dim3(NT), 0, st, (const float *)Q, (const float *)K,   \
-                       (const float *)V, key_bias, H, block_mask, Lq, Lk, scale, (float *)O)
-#define DFSS_LAUNCH_FUSED_SPLIT_B(DD, PP)                 \
-    do {                                                  \
-        if (key_bias) DFSS_LAUNCH_FUSED_SPLIT(DD, PP, true); \
-        else DFSS_LAUNCH_FUSED_SPLIT(DD, PP, false);      \
+    // 8 waves per workgroup where the 128-query tile divides Lq, is not cut by a 64 x 64 block pattern, and still
+    // leaves at least two workgroups per compute unit
+    const bool wide = Lq % 128 == 0 && !block_mask && (long)BH * (Lq / 128) >= 512;
+    const unsigned grid = (unsigned)BH * (unsigned)(Lq / (wide ? 128 : 64));
+#define DFSS_LAUNCH_FUSED_SPLIT(DD, PP, BB, WW)                                                                   \
+    hipLaunchKernelGGL((k_fused_split<DD, PP, BB, WW>), dim3(grid), dim3(WW * 64), 0, st, (const float *)Q,       \
+                       (const float *)K, (const float *)V, key_bias, H, block_mask, Lq, Lk, scale, (float *)O)
+#define DFSS_LAUNCH_FUSED_SPLIT_B(DD, PP)                                 \
+    do {                                                                  \
+        if (key_bias && wide) DFSS_LAUNCH_FUSED_SPLIT(DD, PP, true, 8);   \
+        else if (key_bias) DFSS_LAUNCH_FUSED_SPLIT(DD, PP, true, 4);      \
+        else if (wide) DFSS_LAUNCH_FUSED_SPLIT(DD, PP, false, 8);         \
+        else DFSS_LAUNCH_FUSED_SPLIT(DD, PP, false, 4);                   \
     } while (0)
     if (d == 64 && prune) DFSS_LAUNCH_FUSED_SPLIT_B(64, true);
     else if (d == 64) DFSS_LAUNCH_FUSED_SPLIT_B(64, false);
