@@ -14,6 +14,8 @@
 // per block, the conversion of block j+1 next to the matrix instructions of block j); the one-kernel path
 // holds four images per block and keeps a single copy.  The layouts, the 1:2
 // epilogue and the metadata are those of the exact fp32 kernels (float_mode.hip).
+#include <cstdlib>
+
 #include "dfss_device.hpp"
 #include "dfss_kernels.hpp"
 
@@ -79,15 +81,18 @@ struct RawBlock {
 // shared by NQ times as many matrix instructions.
 // ---------------------------------------------------------------------------------------------
 // BIAS: key_bias[b][j] (b = head / H) is added to the scaled score before the selection (-inf masks a key).
-template <int D, bool PRUNE, int NQ, bool BIAS>
-__global__ __launch_bounds__(NT, 2) void k_scores_split(const float *__restrict__ Q, const float *__restrict__ K,
+// NW waves per workgroup (4 or 8): with 8 the conversion of a block is spread over twice the threads and shared by
+// twice the queries.
+template <int D, bool PRUNE, int NQ, bool BIAS, int NW>
+__global__ __launch_bounds__(NW * 64, 2) void k_scores_split(const float *__restrict__ Q, const float *__restrict__ K,
                                                         const float *__restrict__ key_bias, int H, int Lq, int Lk,
                                                         float scale, float *__restrict__ out,
                                                         uint32_t *__restrict__ meta) {
     constexpr int CPR = D / 8;                   // 16-byte chunks per bf16 row
     constexpr int KS = D / 32;                   // contraction steps of 32
+    constexpr int NT = NW * 64;                  // threads per workgroup
     constexpr int NCONV = KB * CPR / NT;         // bf16 chunks each thread converts per block
-    constexpr int QT = 64 * NQ;                  // queries per workgroup
+    constexpr int QT = 16 * NW * NQ;             // queries per workgroup
     __shared__ u32x4 Kh[2][KB * CPR], Kl[2][KB * CPR];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -119,7 +124,7 @@ __global__ __launch_bounds__(NT, 2) void k_scores_split(const float *__restrict_
         const int slot = 16 * ((key >> 2) & 3) + 4 * (key >> 4) + (key & 3);
         dst[i] = slot * CPR + (c ^ (slot & 7));
     }
-    auto convert = [&](const RawBlock<NCONV> &raw, int buf) {
+    auto convert = [&](const RawBlock<NCONV, NT> &raw, int buf) {
 #pragma unroll
         for (int i = 0; i < NCONV; ++i) {
             u32x4 h, l;
@@ -134,7 +139,7 @@ __global__ __launch_bounds__(NT, 2) void k_scores_split(const float *__restrict_
     // metadata word of (row group, block jb, row n, lane group g); the next 16 queries are the next row group
     uint32_t *mrow = PRUNE ? meta + ((size_t)bh * (Lq / 16) + (q >> 4)) * nkb * 64 + n * 4 + g : nullptr;
 
-    RawBlock<NCONV> raw;
+    RawBlock<NCONV, NT> raw;
     raw.load(kblocks, tid);
     convert(raw, 0);
     if (nkb > 1) raw.load(kblocks + (size_t)KB * D, tid);
@@ -208,11 +213,12 @@ __global__ __launch_bounds__(NT, 2) void k_scores_split(const float *__restrict_
 // 16-byte chunk c of key k sits at chunk c ^ 2 (k % 4); the B operand (keys along the contraction) comes
 // from the transposing LDS read.
 // ---------------------------------------------------------------------------------------------
-template <int D, bool SPARSE>
-__global__ __launch_bounds__(NT, 2) void k_av_split(const float *__restrict__ A, const uint16_t *__restrict__ meta,
+template <int D, bool SPARSE, int NW>
+__global__ __launch_bounds__(NW * 64, 2) void k_av_split(const float *__restrict__ A, const uint16_t *__restrict__ meta,
                                                     const float *__restrict__ V, int Lq, int Lk,
                                                     float *__restrict__ O) {
     constexpr int CPR = D / 8;
+    constexpr int NT = NW * 64, QT = NW * 16;    // threads and queries per workgroup
     constexpr int NCONV = KB * CPR / NT;
     constexpr int DS = D / 16;
     __shared__ u32x4 Vh[2][KB * CPR], Vl[2][KB * CPR];
@@ -233,7 +239,7 @@ __global__ __launch_bounds__(NT, 2) void k_av_split(const float *__restrict__ A,
         const int key = idx / CPR, c = idx % CPR;
         dst[i] = key * CPR + (c ^ ((key & 3) << 1));
     }
-    auto convert = [&](const RawBlock<NCONV> &raw, int buf) {
+    auto convert = [&](const RawBlock<NCONV, NT> &raw, int buf) {
 #pragma unroll
         for (int i = 0; i < NCONV; ++i) {
             u32x4 h, l;
@@ -288,7 +294,7 @@ __global__ __launch_bounds__(NT, 2) void k_av_split(const float *__restrict__ A,
 
     AFrag a_cur, a_nxt;
     load_a(0, a_cur);
-    RawBlock<NCONV> raw;
+    RawBlock<NCONV, NT> raw;
     raw.load(vblocks, tid);
     convert(raw, 0);
     if (nkb > 1) raw.load(vblocks + (size_t)KB * D, tid);
@@ -573,46 +579,71 @@ __global__ __launch_bounds__(NW * 64, (D == 64 && NW == 8) ? 4 : 2) void k_fused
     }
 }
 
-template <int D, bool PRUNE, int NQ>
+template <int D, bool PRUNE, int NQ, int NW>
 hipError_t launch_scores_nq(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
                             float scale, void *out, void *meta, hipStream_t st) {
-    const unsigned grid = (unsigned)BH * (unsigned)(Lq / (64 * NQ));
+    const unsigned grid = (unsigned)BH * (unsigned)(Lq / (16 * NW * NQ));
     if (key_bias)
-        hipLaunchKernelGGL((k_scores_split<D, PRUNE, NQ, true>), dim3(grid), dim3(NT), 0, st, (const float *)Q,
-                           (const float *)K, key_bias, H, Lq, Lk, scale, (float *)out, (uint32_t *)meta);
+        hipLaunchKernelGGL((k_scores_split<D, PRUNE, NQ, true, NW>), dim3(grid), dim3(NW * 64), 0, st,
+                           (const float *)Q, (const float *)K, key_bias, H, Lq, Lk, scale, (float *)out,
+                           (uint32_t *)meta);
     else
-        hipLaunchKernelGGL((k_scores_split<D, PRUNE, NQ, false>), dim3(grid), dim3(NT), 0, st, (const float *)Q,
-                           (const float *)K, key_bias, H, Lq, Lk, scale, (float *)out, (uint32_t *)meta);
+        hipLaunchKernelGGL((k_scores_split<D, PRUNE, NQ, false, NW>), dim3(grid), dim3(NW * 64), 0, st,
+                           (const float *)Q, (const float *)K, key_bias, H, Lq, Lk, scale, (float *)out,
+                           (uint32_t *)meta);
     return hipGetLastError();
+}
+
+// which tiling: DFSS_SPLIT_TILE = "<waves>x<query groups per wave>" overrides the choice (for measurements)
+inline void split_tile_override(int &nw, int &nq) {
+    if (const char *f = getenv("DFSS_SPLIT_TILE")) {
+        if ((f[0] == '4' || f[0] == '8') && f[1] == 'x' && (f[2] == '1' || f[2] == '2')) nw = f[0] - '0', nq = f[2] - '0';
+    }
 }
 
 template <bool PRUNE>
 hipError_t launch_scores(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk, int d,
                          float scale, void *out, void *meta, hipStream_t st) {
-    // 32 queries per wave where Lq allows and the grid still fills the chip
-    const bool wide = Lq % 128 == 0 && (long)BH * (Lq / 128) >= 512;
-    if (d == 64)
-        return wide ? launch_scores_nq<64, PRUNE, 2>(Q, K, key_bias, H, BH, Lq, Lk, scale, out, meta, st)
-                    : launch_scores_nq<64, PRUNE, 1>(Q, K, key_bias, H, BH, Lq, Lk, scale, out, meta, st);
-    if (d == 128)
-        return wide ? launch_scores_nq<128, PRUNE, 2>(Q, K, key_bias, H, BH, Lq, Lk, scale, out, meta, st)
-                    : launch_scores_nq<128, PRUNE, 1>(Q, K, key_bias, H, BH, Lq, Lk, scale, out, meta, st);
+    // 128 queries per workgroup (4 waves x 32 queries) where Lq allows and the grid still fills the chip
+    int nw = 4, nq = (Lq % 128 == 0 && (long)BH * (Lq / 128) >= 512) ? 2 : 1;
+    split_tile_override(nw, nq);
+    if (Lq % (16 * nw * nq) != 0) nw = 4, nq = 1;
+#define DFSS_LAUNCH_SCORES(DD)                                                                                   \
+    do {                                                                                                         \
+        if (nw == 8 && nq == 2) return launch_scores_nq<DD, PRUNE, 2, 8>(Q, K, key_bias, H, BH, Lq, Lk, scale, out, meta, st); \
+        if (nw == 8) return launch_scores_nq<DD, PRUNE, 1, 8>(Q, K, key_bias, H, BH, Lq, Lk, scale, out, meta, st);            \
+        if (nq == 2) return launch_scores_nq<DD, PRUNE, 2, 4>(Q, K, key_bias, H, BH, Lq, Lk, scale, out, meta, st);            \
+        return launch_scores_nq<DD, PRUNE, 1, 4>(Q, K, key_bias, H, BH, Lq, Lk, scale, out, meta, st);                         \
+    } while (0)
+    if (d == 64) DFSS_LAUNCH_SCORES(64);
+    if (d == 128) DFSS_LAUNCH_SCORES(128);
+#undef DFSS_LAUNCH_SCORES
     return hipErrorInvalidValue;
+}
+
+template <int D, bool SPARSE, int NW>
+hipError_t launch_av_nw(const void *A, const void *meta, const void *V, int BH, int Lq, int Lk, void *O,
+                        hipStream_t st) {
+    const unsigned grid = (unsigned)BH * (unsigned)(Lq / (16 * NW));
+    hipLaunchKernelGGL((k_av_split<D, SPARSE, NW>), dim3(grid), dim3(NW * 64), 0, st, (const float *)A,
+                       (const uint16_t *)meta, (const float *)V, Lq, Lk, (float *)O);
+    return hipGetLastError();
 }
 
 template <bool SPARSE>
 hipError_t launch_av(const void *A, const void *meta, const void *V, int BH, int Lq, int Lk, int d, void *O,
                      hipStream_t st) {
-    const unsigned grid = (unsigned)BH * (unsigned)(Lq / QT);
+    // 8 waves per workgroup where the 128-query tile divides Lq and the grid still fills the chip
+    int nw = (Lq % 128 == 0 && (long)BH * (Lq / 128) >= 512) ? 8 : 4, nq = 1;
+    split_tile_override(nw, nq);
+    if (Lq % (16 * nw) != 0) nw = 4;
     if (d == 64)
-        hipLaunchKernelGGL((k_av_split<64, SPARSE>), dim3(grid), dim3(NT), 0, st, (const float *)A,
-                           (const uint16_t *)meta, (const float *)V, Lq, Lk, (float *)O);
-    else if (d == 128)
-        hipLaunchKernelGGL((k_av_split<128, SPARSE>), dim3(grid), dim3(NT), 0, st, (const float *)A,
-                           (const uint16_t *)meta, (const float *)V, Lq, Lk, (float *)O);
-    else
-        return hipErrorInvalidValue;
-    return hipGetLastError();
+        return nw == 8 ? launch_av_nw<64, SPARSE, 8>(A, meta, V, BH, Lq, Lk, O, st)
+                       : launch_av_nw<64, SPARSE, 4>(A, meta, V, BH, Lq, Lk, O, st);
+    if (d == 128)
+        return nw == 8 ? launch_av_nw<128, SPARSE, 8>(A, meta, V, BH, Lq, Lk, O, st)
+                       : launch_av_nw<128, SPARSE, 4>(A, meta, V, BH, Lq, Lk, O, st);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace
