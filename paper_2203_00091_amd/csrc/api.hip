@@ -268,7 +268,10 @@ dfss_status dfss_spmm_t(const void *vals, const void *meta, const void *X, const
     if (!vals || !meta || !X || !out) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, true, &D)) return st;
     if (misaligned(vals) || misaligned(meta) || misaligned(X) || misaligned(out)) return DFSS_ERR_SHAPE;
-    if (D.f32) return DFSS_ERR_UNSUPPORTED;
+    if (D.f32) {
+        if (!D.split) return DFSS_ERR_UNSUPPORTED;
+        return hip_status(dfss::launch_spmm_t_split(vals, meta, X, D.BH, D.Lq, D.Lk, D.d, out, (hipStream_t)stream));
+    }
     return hip_status(dfss::launch_spmm_t(vals, meta, X, D.BH, D.Lq, D.Lk, D.d, out, (hipStream_t)stream));
 }
 

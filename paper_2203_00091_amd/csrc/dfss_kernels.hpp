@@ -54,6 +54,9 @@ hipError_t launch_spmm_split(const void *vals, const void *meta, const void *V, 
                              void *O, hipStream_t st);
 hipError_t launch_dense_av_split(const void *P, const void *V, int BH, int Lq, int Lk, int d, void *O,
                                  hipStream_t st);
+// out[BH, Lk, d] = A^T X for A in the compressed form of the 4-byte mode, X fp32 [BH, Lq, d] (split products).
+hipError_t launch_spmm_t_split(const void *vals, const void *meta, const void *X, int BH, int Lq, int Lk, int d,
+                               void *out, hipStream_t st);
 // Whole forward pass of the 4-byte mode in one kernel (split products).  prune = false: full attention.
 // key_bias and block_mask (both may be null) as in launch_fused_attention.
 hipError_t launch_fused_attention_split(const void *Q, const void *K, const void *V, const float *key_bias, int H,

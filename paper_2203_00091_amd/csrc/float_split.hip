@@ -349,6 +349,129 @@ __global__ __launch_bounds__(NW * 64, 2) void k_av_split(const float *__restrict
 }
 
 // ---------------------------------------------------------------------------------------------
+// Transposed sparse product out[BH, Lk, D] = A^T X for A given as kept fp32 values + metadata of the 4-byte
+// mode and X fp32 [BH, Lq, D] (dV = P^T dO and dK = dS^T Q of the backward pass).  The contraction runs over
+// the queries, across which the 1:2 structure does not run, so a workgroup (64 keys of one head) walks the
+// queries in blocks of 64: every thread expands its share of the 64 x 64 tile of A to dense values (8 kept
+// values + one metadata word -> 16 keys of one query), splits it and X's tile into bf16 images in LDS, and
+// both matrix operands come from the transposing LDS read (the images hold queries along their rows):
+// output rows = keys (wave w owns keys 16w .. 16w+15 of the block), contraction step m = queries 32m + 8g ..+7.
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(NT, 2) void k_spmm_t_split(const float *__restrict__ A, const uint32_t *__restrict__ meta,
+                                                        const float *__restrict__ X, int Lq, int Lk,
+                                                        float *__restrict__ out) {
+    constexpr int CPRA = KB / 8;                 // 16-byte chunks per row of the A images (64 keys)
+    constexpr int CPRX = D / 8;
+    constexpr int NCX = KB * CPRX / NT;          // pieces of X each thread converts per block
+    constexpr int DS = D / 16;
+    __shared__ u32x4 Ah[KB * CPRA], Al[KB * CPRA], Xh[KB * CPRX], Xl[KB * CPRX];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 15, g = lane >> 4;
+    const int nkb = Lk / KB, nqb = Lq / KB;
+    const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
+    const unsigned bh = item / nkb, kb = item % nkb;
+
+    // this thread's share of a tile of A: query row aq of the block, keys 16 ag .. 16 ag + 15
+    const int aq = tid >> 2, ag = tid & 3;
+    const float *arow = A + ((size_t)bh * Lq + aq) * (Lk / 2) + kb * (KB / 2) + 8 * ag;
+    const uint32_t *mrow = meta + ((size_t)bh * (Lq / 16) + (aq >> 4)) * nkb * 64 + kb * 64 + (aq & 15) * 4 + ag;
+    // chunk c of image row r sits at chunk c ^ 2 (r % 4), the layout the transposing read expects
+    const int a_dst0 = aq * CPRA + ((2 * ag) ^ ((aq & 3) << 1)), a_dst1 = aq * CPRA + ((2 * ag + 1) ^ ((aq & 3) << 1));
+    const float *xblocks = X + (size_t)bh * Lq * D;
+    int x_dst[NCX];
+#pragma unroll
+    for (int i = 0; i < NCX; ++i) {
+        const int idx = i * NT + tid;
+        const int row = idx / CPRX, c = idx % CPRX;
+        x_dst[i] = row * CPRX + (c ^ ((row & 3) << 1));
+    }
+
+    struct ATile {
+        f32x4 v[2];
+        uint32_t word;
+    };
+    auto load_a = [&](int qb, ATile &t) {
+        const f32x4 *p = reinterpret_cast<const f32x4 *>(arow + (size_t)qb * KB * (Lk / 2));
+        t.v[0] = p[0];
+        t.v[1] = p[1];
+        t.word = mrow[(size_t)qb * 4 * nkb * 64];     // 64 queries = 4 row groups further
+    };
+
+    const int tr_row = li >> 2;
+    const int tr_sub = (li >> 1) & 1;
+    const int tr_byte = 8 * (li & 1);
+    const int tr_xor = tr_row << 1;
+    // rows row0 .. row0+7 (queries) of column tile `ct` (16 columns) of an image with CPR chunks per row
+    auto tr8 = [&](const u32x4 *img, int cpr, int row0, int ct) {
+        const char *base = reinterpret_cast<const char *>(img);
+        const int chunk = (2 * ct + tr_sub) ^ tr_xor;
+        const s16x4 t0 = lds_read_tr16(base + ((row0 + tr_row) * cpr + chunk) * 16 + tr_byte);
+        const s16x4 t1 = lds_read_tr16(base + ((row0 + 4 + tr_row) * cpr + chunk) * 16 + tr_byte);
+        return __builtin_bit_cast(u32x4, __builtin_shufflevector(t0, t1, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+
+    f32x4 acc[DS];
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds) acc[ds] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    ATile at;
+    RawBlock<NCX> rx;
+    load_a(0, at);
+    rx.load(xblocks, tid);
+    for (int qb = 0; qb < nqb; ++qb) {
+        __syncthreads();            // every wave is done with the images of the previous block of queries
+        {
+            // expand: pair i keeps its second key iff code i is 0xE (bit 1 of the nibble)
+            float dlo[8], dhi[8];   // keys 16 ag + 0..7 and + 8..15
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const bool s0 = (at.word >> (4 * i + 1)) & 1u, s1 = (at.word >> (4 * (i + 4) + 1)) & 1u;
+                dlo[2 * i] = s0 ? 0.f : at.v[0][i];
+                dlo[2 * i + 1] = s0 ? at.v[0][i] : 0.f;
+                dhi[2 * i] = s1 ? 0.f : at.v[1][i];
+                dhi[2 * i + 1] = s1 ? at.v[1][i] : 0.f;
+            }
+            u32x4 h, l;
+            split8(f32x4{dlo[0], dlo[1], dlo[2], dlo[3]}, f32x4{dlo[4], dlo[5], dlo[6], dlo[7]}, h, l);
+            Ah[a_dst0] = h;
+            Al[a_dst0] = l;
+            split8(f32x4{dhi[0], dhi[1], dhi[2], dhi[3]}, f32x4{dhi[4], dhi[5], dhi[6], dhi[7]}, h, l);
+            Ah[a_dst1] = h;
+            Al[a_dst1] = l;
+#pragma unroll
+            for (int i = 0; i < NCX; ++i) {
+                split8(rx.v[i][0], rx.v[i][1], h, l);
+                Xh[x_dst[i]] = h;
+                Xl[x_dst[i]] = l;
+            }
+        }
+        if (qb + 1 < nqb) {
+            load_a(qb + 1, at);
+            rx.load(xblocks + (size_t)(qb + 1) * KB * D, tid);
+        }
+        __syncthreads();            // images complete
+
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const int q0 = 32 * m + 8 * g;
+            const u32x4 ah = tr8(Ah, CPRA, q0, wave), al = tr8(Al, CPRA, q0, wave);   // A^T: rows = keys 16 wave + li
+#pragma unroll
+            for (int ds = 0; ds < DS; ++ds)
+                acc[ds] = mfma_split(ah, al, tr8(Xh, CPRX, q0, ds), tr8(Xl, CPRX, q0, ds), acc[ds]);
+        }
+    }
+
+    // acc[ds][r] = out[key 64 kb + 16 wave + 4 g + r][16 ds + li]
+    float *op = out + ((size_t)bh * Lk + kb * KB + wave * 16 + 4 * g) * D + li;
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) op[(size_t)r * D + ds * 16] = acc[ds][r];
+}
+
+// ---------------------------------------------------------------------------------------------
 // The whole forward pass of the 4-byte mode in one kernel: scores on split products, 1:2 selection on
 // the accumulators, softmax over the kept scores kept up to date block by block (running maximum and
 // sum per query, the output accumulators rescaled when a maximum rises), and A V on split products,
@@ -683,6 +806,20 @@ hipError_t launch_dense_scores_split(const void *Q, const void *K, const float *
                                      int Lk, int d, float scale, void *S, hipStream_t st) {
     return launch_scores<false>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, S, nullptr, st);
 }
+hipError_t launch_spmm_t_split(const void *vals, const void *meta, const void *X, int BH, int Lq, int Lk, int d,
+                               void *out, hipStream_t st) {
+    const unsigned grid = (unsigned)BH * (unsigned)(Lk / KB);
+    if (d == 64)
+        hipLaunchKernelGGL((k_spmm_t_split<64>), dim3(grid), dim3(NT), 0, st, (const float *)vals,
+                           (const uint32_t *)meta, (const float *)X, Lq, Lk, (float *)out);
+    else if (d == 128)
+        hipLaunchKernelGGL((k_spmm_t_split<128>), dim3(grid), dim3(NT), 0, st, (const float *)vals,
+                           (const uint32_t *)meta, (const float *)X, Lq, Lk, (float *)out);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
 hipError_t launch_spmm_split(const void *vals, const void *meta, const void *V, int BH, int Lq, int Lk, int d,
                              void *O, hipStream_t st) {
     return launch_av<true>(vals, meta, V, BH, Lq, Lk, d, O, st);

@@ -461,3 +461,38 @@ def test_attention_blocked_with_key_bias_and_full_pattern():
     O4 = dfss.dense_attention_fused(Qd, Kd, Vd, s, 0.125)
     torch.cuda.synchronize()
     assert torch.equal(O1, O2) and torch.equal(O3, O4)
+
+
+# ----------------------------------------------------------------------------------
+# backward pass through the fixed selection in the float mode (bf16x3 products)
+# ----------------------------------------------------------------------------------
+def _oracle_forward_f32(Qn, Kn, scale):
+    """Selection, softmax weights and canonical metadata of the oracle, per head."""
+    kidx, P, meta = [], [], []
+    for h in range(Qn.shape[0]):
+        S = oracle.scores(Qn[h], Kn[h], scale)
+        _, v, ki = oracle.prune(S, 1, 2)
+        kidx.append(ki)
+        P.append(oracle.softmax_kept(v))
+        meta.append(oracle.encode_meta_f32(ki, Kn.shape[1]))
+    return np.stack(kidx), np.stack(P), np.stack(meta)
+
+
+@pytest.mark.parametrize("BH,Lq,Lk,d", [(2, 128, 256, 64), (1, 192, 128, 128), (2, 64, 384, 64)])
+def test_transposed_spmm(BH, Lq, Lk, d):
+    Q, K, _ = synth.gaussian_qkv(BH, Lq, Lk, d, 1.0, seed=7300 + Lq + Lk, dtype=torch.float32)
+    X = torch.randn(BH, Lq, d, generator=torch.Generator().manual_seed(7301 + d))
+    s = _shape(1, BH, Lq, Lk, d, DFSS_F32_BF16X3)
+    kidx, P, meta_c = _oracle_forward_f32(Q.numpy(), K.numpy(), 1.0 / math.sqrt(d))
+    meta = dfss.dfss_meta_from_canonical(_dev(torch.from_numpy(meta_c.view(np.int16))), s)
+    out = dfss.dfss_spmm_t(_dev(torch.from_numpy(P)), meta, _dev(X), s)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    for h in range(BH):
+        Pd = np.zeros((Lq, Lk))
+        np.put_along_axis(Pd, kidx[h].astype(np.int64), P[h].astype(np.float64), axis=1)
+        Xh = X[h].numpy().astype(np.float64)
+        ref = Pd.T @ Xh
+        # split products (3.01 * 2^-18 per product) + fp32 accumulation of 3 Lq terms
+        bound = (3.01 * 2.0 ** -18 + 3 * Lq * U) * (np.abs(Pd).T @ np.abs(Xh))
+        assert np.all(np.abs(out[h] - ref) <= bound + 1e-12)
