@@ -101,9 +101,8 @@ def main():
     split = f32 and args.products == "bf16x3"
     s = Shape(w.B, w.H, w.L, w.L, w.d, w.N, w.M,
               (dfss.DFSS_F32_BF16X3 if split else dfss.DFSS_F32) if f32 else dfss.DFSS_BF16)
-    if f32 and (args.backward or ((args.key_padding or args.block_pattern) and not split)):
-        print("bench.py: the float workloads run the forward pass only; a key bias or a block pattern is taken "
-              "with --products bf16x3 only", file=sys.stderr)
+    if f32 and not split and (args.backward or args.key_padding or args.block_pattern):
+        print("bench.py: with --products fp32 the float workloads run the plain forward pass only", file=sys.stderr)
         sys.exit(2)
     esz = 4 if f32 else 2
     # one-kernel paths exist for the 2-byte modes and, in the float mode, for bf16x3 products
@@ -346,7 +345,7 @@ def main():
 
     if args.backward and block_mask is None:
         b = sets[0]
-        vals = torch.empty((BH, L, s.Lc), dtype=torch.bfloat16, device=dev)
+        vals = torch.empty((BH, L, s.Lc), dtype=s.torch_dtype, device=dev)
         meta = torch.empty((BH * L * s.meta_words,), dtype=torch.int16, device=dev)
         if bias is None:
             dfss.dfss_sddmm_prune(b["Q"], b["K"], s, w.scale, vals=vals, meta=meta)
@@ -354,8 +353,8 @@ def main():
             dfss.dfss_sddmm_prune_bias(b["Q"], b["K"], bias, s, w.scale, vals=vals, meta=meta)
         dfss.dfss_sparse_softmax(vals, s)
         O_fwd = dfss.dfss_spmm(vals, meta, b["V"], s)
-        dO = torch.randn(BH, L, d, device=dev).to(torch.bfloat16)
-        grads = [torch.empty((BH, L, d), dtype=torch.bfloat16, device=dev) for _ in range(3)]
+        dO = torch.randn(BH, L, d, device=dev).to(s.torch_dtype)
+        grads = [torch.empty((BH, L, d), dtype=s.torch_dtype, device=dev) for _ in range(3)]
         ws_b = torch.empty(dfss.dfss_backward_workspace_bytes(s), dtype=torch.uint8, device=dev)
 
         def step_backward(i):

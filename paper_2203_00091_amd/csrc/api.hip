@@ -286,10 +286,17 @@ dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K
         misaligned(meta) || misaligned(dQ) || misaligned(dK) || misaligned(dV))
         return DFSS_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0) return DFSS_ERR_SHAPE;
-    if (D.f32) return DFSS_ERR_UNSUPPORTED;
+    if (D.f32 && !D.split) return DFSS_ERR_UNSUPPORTED;
     if (ws_bytes < align_up(dfss_vals_bytes(s))) return DFSS_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     void *dS = ws;   // scale * dS in the compressed layout of P
+    if (D.f32) {
+        hipError_t e = dfss::launch_masked_sddmm_ds_split(dO, V, O, P, meta, D.BH, D.Lq, D.Lk, D.d, scale, dS, st);
+        if (e == hipSuccess) e = dfss::launch_spmm_split(dS, meta, K, D.BH, D.Lq, D.Lk, D.d, dQ, st);       // dQ = dS' K
+        if (e == hipSuccess) e = dfss::launch_spmm_t_split(P, meta, dO, D.BH, D.Lq, D.Lk, D.d, dV, st);     // dV = P^T dO
+        if (e == hipSuccess) e = dfss::launch_spmm_t_split(dS, meta, Q, D.BH, D.Lq, D.Lk, D.d, dK, st);     // dK = dS'^T Q
+        return hip_status(e);
+    }
     hipError_t e = dfss::launch_masked_sddmm_ds(dO, V, O, P, meta, D.BH, D.Lq, D.Lk, D.d, scale, dS, st);
     if (e == hipSuccess) e = dfss::launch_spmm(dS, meta, K, D.BH, D.Lq, D.Lk, D.d, dQ, st);      // dQ = dS' K
     if (e == hipSuccess) e = dfss::launch_spmm_t(P, meta, dO, D.BH, D.Lq, D.Lk, D.d, dV, st);    // dV = P^T dO
@@ -298,7 +305,7 @@ dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K
 }
 
 size_t dfss_backward_workspace_bytes(const dfss_shape *s) {
-    if (s && s->dtype != DFSS_BF16) return 0;
+    if (s && s->dtype == DFSS_F32) return 0;     // the backward pass of the float mode takes split products only
     const size_t v = dfss_vals_bytes(s);
     return v ? align_up(v) : 0;
 }

@@ -54,6 +54,9 @@ hipError_t launch_spmm_split(const void *vals, const void *meta, const void *V, 
                              void *O, hipStream_t st);
 hipError_t launch_dense_av_split(const void *P, const void *V, int BH, int Lq, int Lk, int d, void *O,
                                  hipStream_t st);
+// dS' = scale * P .* (dO V^T - delta) at the kept positions of the 4-byte mode (split products), compressed like P.
+hipError_t launch_masked_sddmm_ds_split(const void *dO, const void *V, const void *O, const void *P, const void *meta,
+                                        int BH, int Lq, int Lk, int d, float scale, void *dS, hipStream_t st);
 // out[BH, Lk, d] = A^T X for A in the compressed form of the 4-byte mode, X fp32 [BH, Lq, d] (split products).
 hipError_t launch_spmm_t_split(const void *vals, const void *meta, const void *X, int BH, int Lq, int Lk, int d,
                                void *out, hipStream_t st);

@@ -349,6 +349,113 @@ __global__ __launch_bounds__(NW * 64, 2) void k_av_split(const float *__restrict
 }
 
 // ---------------------------------------------------------------------------------------------
+// Backward pass, first step: dS' = scale * P .* (dO V^T - delta) at the kept positions, delta_q = dO_q . O_q,
+// written in the compressed layout of P.  The mainloop is k_scores_split's with V in the place of K and dO
+// in the place of Q; the epilogue reads the stored position codes instead of selecting.  delta comes from the
+// slices of dO and O the lane holds anyway (its share of d) and two cross-lane additions.
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(NT, 2) void k_ds_split(const float *__restrict__ dO, const float *__restrict__ V,
+                                                    const float *__restrict__ O, const float *__restrict__ P,
+                                                    const uint32_t *__restrict__ meta, int Lq, int Lk, float scale,
+                                                    float *__restrict__ dS) {
+    constexpr int CPR = D / 8;
+    constexpr int KS = D / 32;
+    constexpr int NCONV = KB * CPR / NT;
+    __shared__ u32x4 Vh[2][KB * CPR], Vl[2][KB * CPR];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, g = lane >> 4;
+    const unsigned nqt = Lq / QT;
+    const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
+    const unsigned bh = item / nqt, qt = item % nqt;
+    const int nkb = Lk / KB;
+    const int q = qt * QT + wave * 16 + n;
+
+    // B operand: dO of query q, k = 32 s + 8 g + e; delta from the same slices of dO and O
+    u32x4 gh[KS], gl[KS];
+    float delta = 0.f;
+    {
+        const f32x4 *gp = reinterpret_cast<const f32x4 *>(dO + ((size_t)bh * Lq + q) * D + 8 * g);
+        const f32x4 *op = reinterpret_cast<const f32x4 *>(O + ((size_t)bh * Lq + q) * D + 8 * g);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const f32x4 g0 = gp[8 * s], g1 = gp[8 * s + 1], o0 = op[8 * s], o1 = op[8 * s + 1];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) delta += g0[e] * o0[e] + g1[e] * o1[e];
+            split8(g0, g1, gh[s], gl[s]);
+        }
+        delta += __shfl_xor(delta, 16, kWave);
+        delta += __shfl_xor(delta, 32, kWave);
+    }
+
+    const float *vblocks = V + (size_t)bh * Lk * D;
+    int dst[NCONV];
+#pragma unroll
+    for (int i = 0; i < NCONV; ++i) {
+        const int idx = i * NT + tid;
+        const int key = idx / CPR, c = idx % CPR;
+        const int slot = 16 * ((key >> 2) & 3) + 4 * (key >> 4) + (key & 3);     // as in k_scores_split
+        dst[i] = slot * CPR + (c ^ (slot & 7));
+    }
+    auto convert = [&](const RawBlock<NCONV> &raw, int buf) {
+#pragma unroll
+        for (int i = 0; i < NCONV; ++i) {
+            u32x4 h, l;
+            split8(raw.v[i][0], raw.v[i][1], h, l);
+            Vh[buf][dst[i]] = h;
+            Vl[buf][dst[i]] = l;
+        }
+    };
+
+    const size_t row = (size_t)bh * Lq + q;
+    const float *prow = P + row * (Lk / 2) + 8 * g;
+    float *srow = dS + row * (Lk / 2) + 8 * g;
+    const uint32_t *mrow = meta + ((size_t)bh * (Lq / 16) + (q >> 4)) * nkb * 64 + n * 4 + g;
+
+    RawBlock<NCONV> raw;
+    raw.load(vblocks, tid);
+    convert(raw, 0);
+    if (nkb > 1) raw.load(vblocks + (size_t)KB * D, tid);
+    for (int jb = 0; jb < nkb; ++jb) {
+        const int buf = jb & 1;
+        __syncthreads();
+        if (jb + 1 < nkb) convert(raw, buf ^ 1);
+        if (jb + 2 < nkb) raw.load(vblocks + (size_t)(jb + 2) * KB * D, tid);
+        const f32x4 p0 = *reinterpret_cast<const f32x4 *>(prow + jb * (KB / 2));
+        const f32x4 p1 = *reinterpret_cast<const f32x4 *>(prow + jb * (KB / 2) + 4);
+        const uint32_t word = mrow[jb * 64];
+
+        f32x4 acc[4];       // dP of keys 16g + 4t + r of query n
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+            const int slot = 16 * t + n;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const int pos = slot * CPR + ((4 * s + g) ^ (n & 7));
+                acc[t] = mfma_split(Vh[buf][pos], Vl[buf][pos], gh[s], gl[s], acc[t]);
+            }
+        }
+
+        f32x4 ds[2];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int i = 2 * t + h;                               // pair i: keys 16g + 2i, +1
+                const bool second = (word >> (4 * i + 1)) & 1u;        // code 0xE
+                const float dp = second ? acc[t][2 * h + 1] : acc[t][2 * h];
+                const float p = i < 4 ? p0[i & 3] : p1[i & 3];
+                ds[i >> 2][i & 3] = scale * p * (dp - delta);
+            }
+        f32x4 *sp = reinterpret_cast<f32x4 *>(srow + jb * (KB / 2));
+        sp[0] = ds[0];
+        sp[1] = ds[1];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Transposed sparse product out[BH, Lk, D] = A^T X for A given as kept fp32 values + metadata of the 4-byte
 // mode and X fp32 [BH, Lq, D] (dV = P^T dO and dK = dS^T Q of the backward pass).  The contraction runs over
 // the queries, across which the 1:2 structure does not run, so a workgroup (64 keys of one head) walks the
@@ -806,6 +913,20 @@ hipError_t launch_dense_scores_split(const void *Q, const void *K, const float *
                                      int Lk, int d, float scale, void *S, hipStream_t st) {
     return launch_scores<false>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, S, nullptr, st);
 }
+hipError_t launch_masked_sddmm_ds_split(const void *dO, const void *V, const void *O, const void *P, const void *meta,
+                                        int BH, int Lq, int Lk, int d, float scale, void *dS, hipStream_t st) {
+    const unsigned grid = (unsigned)BH * (unsigned)(Lq / QT);
+    if (d == 64)
+        hipLaunchKernelGGL((k_ds_split<64>), dim3(grid), dim3(NT), 0, st, (const float *)dO, (const float *)V,
+                           (const float *)O, (const float *)P, (const uint32_t *)meta, Lq, Lk, scale, (float *)dS);
+    else if (d == 128)
+        hipLaunchKernelGGL((k_ds_split<128>), dim3(grid), dim3(NT), 0, st, (const float *)dO, (const float *)V,
+                           (const float *)O, (const float *)P, (const uint32_t *)meta, Lq, Lk, scale, (float *)dS);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
 hipError_t launch_spmm_t_split(const void *vals, const void *meta, const void *X, int BH, int Lq, int Lk, int d,
                                void *out, hipStream_t st) {
     const unsigned grid = (unsigned)BH * (unsigned)(Lk / KB);

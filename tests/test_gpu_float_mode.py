@@ -496,3 +496,53 @@ def test_transposed_spmm(BH, Lq, Lk, d):
         # split products (3.01 * 2^-18 per product) + fp32 accumulation of 3 Lq terms
         bound = (3.01 * 2.0 ** -18 + 3 * Lq * U) * (np.abs(Pd).T @ np.abs(Xh))
         assert np.all(np.abs(out[h] - ref) <= bound + 1e-12)
+
+
+@pytest.mark.parametrize("BH,Lq,Lk,d", [(2, 128, 256, 64), (2, 192, 384, 64), (2, 128, 128, 128)])
+def test_backward_against_oracle_through_the_same_selection(BH, Lq, Lk, d):
+    """The kernels are fed the oracle's forward results (weights, metadata, O), so both sides differentiate
+    through exactly the same selection."""
+    scale = 1.0 / math.sqrt(d)
+    Q, K, V = synth.gaussian_qkv(BH, Lq, Lk, d, 1.0, seed=7400 + Lq + d, dtype=torch.float32)
+    dO = torch.randn(BH, Lq, d, generator=torch.Generator().manual_seed(7401 + Lq))
+    Qn, Kn, Vn, dOn = Q.numpy(), K.numpy(), V.numpy(), dO.numpy()
+    kidx, P, meta_c = _oracle_forward_f32(Qn, Kn, scale)
+    O = np.stack([oracle.spmm(P[h], kidx[h], Vn[h]) for h in range(BH)])
+    s = _shape(1, BH, Lq, Lk, d, DFSS_F32_BF16X3)
+    meta = dfss.dfss_meta_from_canonical(_dev(torch.from_numpy(meta_c.view(np.int16))), s)
+    dQ, dK, dV = dfss.dfss_attention_backward(_dev(dO), _dev(Q), _dev(K), _dev(V), _dev(torch.from_numpy(O)),
+                                              _dev(torch.from_numpy(P)), meta, s, scale)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for h in range(BH):
+        rQ, rK, rV = oracle.attention_backward(Qn[h], Kn[h], Vn[h], dOn[h], P[h], kidx[h], scale)
+        for name, got, ref in (("dQ", dQ[h], rQ), ("dK", dK[h], rK), ("dV", dV[h], rV)):
+            # split products drop at most 3.01 * 2^-18 per product; dS = P (dP - delta) cancels, so the bar is
+            # relative to the largest entry of the result, not to each entry
+            err = np.max(np.abs(got.cpu().numpy() - ref)) / np.max(np.abs(ref))
+            worst = max(worst, err)
+            assert err <= 1e-4, (name, h, err)
+    print(f"largest relative error {worst:.2e}")
+
+
+def test_forward_stages_then_backward_on_exact_scores():
+    """GPU forward (three stage calls, integer-valued Q and K: the selection equals the oracle's exactly)
+    followed by the GPU backward, against the oracle end to end."""
+    BH, L, d = 2, 256, 64
+    Q, K, V = synth.integer_qkv(BH, L, L, d, seed=7500, dtype=torch.float32)
+    Q, K = Q * 0.25, K * 0.25                                  # keeps the softmax soft; still exact
+    dO = torch.randn(BH, L, d, generator=torch.Generator().manual_seed(7501))
+    s = _shape(1, BH, L, L, d, DFSS_F32_BF16X3)
+    Qd, Kd, Vd, dOd = _dev(Q), _dev(K), _dev(V), _dev(dO)
+    vals, meta = dfss.dfss_sddmm_prune(Qd, Kd, s, 0.125)
+    dfss.dfss_sparse_softmax(vals, s)
+    O = dfss.dfss_spmm(vals, meta, Vd, s)
+    dQ, dK, dV = dfss.dfss_attention_backward(dOd, Qd, Kd, Vd, O, vals, meta, s, 0.125)
+    torch.cuda.synchronize()
+    Qn, Kn, Vn, dOn = Q.numpy(), K.numpy(), V.numpy(), dO.numpy()
+    kidx, P, meta_c = _oracle_forward_f32(Qn, Kn, 0.125)
+    assert np.array_equal(_meta_np(meta, s), meta_c)           # same selection on both sides
+    for h in range(BH):
+        rQ, rK, rV = oracle.attention_backward(Qn[h], Kn[h], Vn[h], dOn[h], P[h], kidx[h], 0.125)
+        for name, got, ref in (("dQ", dQ[h], rQ), ("dK", dK[h], rK), ("dV", dV[h], rV)):
+            assert np.max(np.abs(got.cpu().numpy() - ref)) <= 1e-4 * np.max(np.abs(ref)), name
