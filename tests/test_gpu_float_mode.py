@@ -272,8 +272,11 @@ def test_calls_replay_correctly_from_a_hip_graph(dtype):
     s = _shape(2, 2, 128, 256, 64, dtype)
     Q, K, V = (_dev(t) for t in synth.gaussian_qkv(4, 128, 256, 64, 1.0, seed=6500, dtype=torch.float32))
     ws = torch.empty(max(dfss.dfss_workspace_bytes(s), dfss.dense_workspace_bytes(s)), dtype=torch.uint8, device=DEV)
-    names = ["attention", "dense", "stages"] + (["dense_fused"] if dtype == DFSS_F32_BF16X3 else [])
-    outs = {k: torch.empty_like(Q) for k in names}
+    split = dtype == DFSS_F32_BF16X3
+    names = ["attention", "dense", "stages"] + (["dense_fused", "dQ", "dK", "dV"] if split else [])
+    outs = {k: torch.empty_like(K if k in ("dK", "dV") else Q) for k in names}
+    dO = torch.randn(Q.shape, generator=torch.Generator().manual_seed(6501)).to(DEV)
+    ws_b = torch.empty(max(dfss.dfss_backward_workspace_bytes(s), 256), dtype=torch.uint8, device=DEV)
     vals = torch.empty((s.BH, s.Lq, s.Lc), dtype=torch.float32, device=DEV)
     meta = torch.empty((s.BH * s.Lq * s.meta_words,), dtype=torch.int16, device=DEV)
 
@@ -285,6 +288,9 @@ def test_calls_replay_correctly_from_a_hip_graph(dtype):
         dfss.dfss_sddmm_prune(Q, K, s, 0.125, vals=vals, meta=meta)
         dfss.dfss_sparse_softmax(vals, s)
         dfss.dfss_spmm(vals, meta, V, s, O=outs["stages"])
+        if split:
+            dfss.dfss_attention_backward(dO, Q, K, V, outs["stages"], vals, meta, s, 0.125, dQ=outs["dQ"],
+                                         dK=outs["dK"], dV=outs["dV"], ws=ws_b)
 
     run_all()
     torch.cuda.synchronize()
