@@ -277,6 +277,9 @@ def main():
     bytes1 = BH * (2.0 * esz * L * d + (esz / 2 + esz / 16) * L * L)
     bytes2 = BH * (esz * L * L)
     bytes3 = BH * ((esz / 2 + esz / 16) * L * L + 2.0 * esz * L * d)
+    flops1_stage = 2.0 * BH * L * L * d
+    peak1 = MFMA_F32_PEAK_TFLOPS if f32 and not split else MFMA_BF16_PEAK_TFLOPS / (3.0 if f32 else 1.0)
+    roof1 = min(peak1, HBM_PEAK_GBS * 1e9 * (flops1_stage / bytes1) / 1e12)
     kernels = {"sddmm_prune": (k1, bytes1), "sparse_softmax": (k2, bytes2), "spmm": (k3, bytes3)}
 
     out = {
@@ -319,9 +322,14 @@ def main():
             "stage_kernel_frac_of_hbm_peak": {k: round(v[1] / (v[0] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
                                               for k, v in kernels.items()},
             "sddmm_prune_tflops": round(2.0 * BH * L * L * d / (k1 * 1e-3) / 1e12, 2),
-            "sddmm_prune_frac_of_mfma_peak": round(2.0 * BH * L * L * d / (k1 * 1e-3) / 1e12
+            "sddmm_prune_frac_of_mfma_peak": round(flops1_stage / (k1 * 1e-3) / 1e12
                                                    / (MFMA_F32_PEAK_TFLOPS if f32 and not split
                                                       else MFMA_BF16_PEAK_TFLOPS), 4),
+            # the lower of the two ceilings of stage 1: the matrix peak (a third of the bf16 peak where every
+            # product is three bf16 products), or the HBM peak times the stage's flops per algorithmic byte
+            # (Q, K read; kept values and metadata written)
+            "sddmm_prune_roofline_tflops": round(roof1, 1),
+            "sddmm_prune_frac_of_min_roofline": round(flops1_stage / (k1 * 1e-3) / 1e12 / roof1, 4),
         },
     }
     if f32:
@@ -373,7 +381,8 @@ def main():
         for k in ("speedup_vs_dense_attention_3stage", "staged_path_speedup_vs_dense_attention_3stage",
                   "dense_attention_3stage_ms_per_step", "dfss_attention_staged_ms_per_step", "stage_kernel_ms",
                   "stage_kernel_GBps", "stage_kernel_frac_of_hbm_peak", "sddmm_prune_tflops",
-                  "sddmm_prune_frac_of_mfma_peak"):
+                  "sddmm_prune_frac_of_mfma_peak", "sddmm_prune_roofline_tflops",
+                  "sddmm_prune_frac_of_min_roofline"):
             out["extra"][k] = None
         out["roofline"]["algorithmic_hbm_bytes_per_launch"] = None
 
