@@ -67,6 +67,10 @@ def parse_args():
     ap.add_argument("--backward", action="store_true",
                     help="also time dfss_attention_backward (gradients through the fixed selection) on the "
                          "results of the three forward stages; reported under extra")
+    ap.add_argument("--unpadded", type=int, default=0, metavar="LEN",
+                    help="also time dfss_attention_ragged / dense_attention_fused_ragged on arrays of LEN queries and "
+                         "keys (LEN <= the workload's L, a multiple of 4; same B, H, d, N:M) next to the call on the "
+                         "workload's padded arrays with the keys >= LEN masked; reported under extra")
     ap.add_argument("--products", choices=("fp32", "bf16x3"), default="bf16x3",
                     help="float workloads only: form the fp32 products on the fp32 matrix instruction (DFSS_F32) or "
                          "from bfloat16 pieces on the bf16 matrix pipe (DFSS_F32_BF16X3, the default)")
@@ -374,6 +378,29 @@ def main():
         out["extra"]["backward_ms_per_step"] = round(t_bwd / K * 1e3, 5)
         out["extra"]["backward_tflops"] = round(flops_bwd / (t_bwd / K) / 1e12, 2)
         out["extra"]["backward_over_staged_forward"] = round((t_bwd / K * 1e3) / ms_staged, 3)
+
+    if args.unpadded:
+        Lr = args.unpadded
+        if not (0 < Lr <= L and Lr % 4 == 0 and has_fused):
+            print("bench.py: --unpadded LEN needs 0 < LEN <= L, LEN % 4 == 0 and a workload with a one-kernel path",
+                  file=sys.stderr)
+            sys.exit(2)
+        b = sets[0]
+        sr = Shape(w.B, w.H, Lr, Lr, d, w.N, w.M, s.dtype)
+        Qr, Kr, Vr = (b[k][:, :Lr].contiguous() for k in ("Q", "K", "V"))
+        Or = torch.empty((BH, Lr, d), dtype=s.torch_dtype, device=dev)
+        pad_bias = torch.zeros((w.B, L), dtype=torch.float32, device=dev)
+        pad_bias[:, Lr:] = float("-inf")
+        t_r = timed(lambda i: dfss.dfss_attention_ragged(Qr, Kr, Vr, None, sr, w.scale, O=Or), K, W, use_graph)
+        t_rd = timed(lambda i: dfss.dense_attention_fused_ragged(Qr, Kr, Vr, None, sr, w.scale, O=Or), K, W, use_graph)
+        t_p = timed(lambda i: dfss.dfss_attention_bias(b["Q"], b["K"], b["V"], pad_bias, s, w.scale, O=b["O"],
+                                                       ws=b["ws"]), K, W, use_graph)
+        out["extra"]["unpadded"] = {
+            "length": Lr, "cache": "warm (one buffer set)",
+            "dfss_attention_ragged_ms_per_step": round(t_r / K * 1e3, 5),
+            "dense_attention_fused_ragged_ms_per_step": round(t_rd / K * 1e3, 5),
+            "padded_and_masked_dfss_attention_bias_ms_per_step": round(t_p / K * 1e3, 5),
+            "algorithmic_tflops": round(3.0 * BH * Lr * Lr * d / (t_r / K) / 1e12, 2)}
 
     if args.block_pattern:
         # only the fused kernels take a block pattern: the three-stage figures would be those of a

@@ -117,7 +117,7 @@ dfss_status dense_attention_fused(const void *Q, const void *K, const void *V, c
  * entirely masked still emits N entries, whose softmax weight is exactly 0.  Sequences whose
  * length is not a multiple of the tile sizes are run by padding the buffers up to Lq % 64 == 0,
  * Lk % 128 == 0 and masking the padded keys this way (padded query rows produce rows the caller
- * ignores).  Precondition: every batch element has at least one key with a finite bias.
+ * ignores), or -- for the whole forward pass -- with the *_ragged calls below, which need no padding.  Precondition: every batch element has at least one key with a finite bias.
  * key_bias == NULL means no bias: each call then equals the call without the suffix.  All other
  * arguments, layouts and error behaviour are those of the call without the suffix.
  * Arithmetic: when scale is a power of two the bias is the initial value of the fp32 accumulator
@@ -150,6 +150,21 @@ dfss_status dfss_attention_blocked(const void *Q, const void *K, const void *V, 
 dfss_status dense_attention_fused_blocked(const void *Q, const void *K, const void *V, const void *key_bias,
                                           const void *block_mask, const dfss_shape *s, float scale, void *O,
                                           void *stream);
+
+/* ---- lengths that are not tile multiples (one-kernel paths) --------------------------- */
+/* The paper's long-sequence tasks have lengths such as 4000 (Sec. 5.1, the retrieval task).  These two
+ * calls take the arrays as they are: Q, O [B*H, Lq, d] and K, V [B*H, Lk, d] with ANY Lq >= 1 and any
+ * Lk <= 8192 that is a multiple of 4 (whole runs of M keys; the key_bias rows [B, Lk] stay 16-byte
+ * aligned); key_bias may be NULL.  dtype: DFSS_BF16 or DFSS_F32_BF16X3.  The function is that of
+ * dfss_attention_bias / dense_attention_fused_bias on those lengths (Eq. 1 over the Lk keys, pruned
+ * per aligned run of M): inside the kernel the absent keys of the last 64-key block count as masked
+ * keys and the absent queries of the last tile are not stored; nothing is read or written past the
+ * arrays.  One kernel, no workspace.  Lengths that are tile multiples give the result of the calls
+ * above bit for bit. */
+dfss_status dfss_attention_ragged(const void *Q, const void *K, const void *V, const void *key_bias,
+                                  const dfss_shape *s, float scale, void *O, void *stream);
+dfss_status dense_attention_fused_ragged(const void *Q, const void *K, const void *V, const void *key_bias,
+                                         const dfss_shape *s, float scale, void *O, void *stream);
 
 /* ---- backward pass through the fixed selection (finetuning, Sec. 5.1) ---------------- */
 /* Transposed sparse product: out[B*H, Lk, d] = A^T X with A given in compressed form (vals,

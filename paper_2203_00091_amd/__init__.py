@@ -15,11 +15,13 @@ from .binding import (  # noqa: F401
     dense_attention_fused,
     dense_attention_fused_bias,
     dense_attention_fused_blocked,
+    dense_attention_fused_ragged,
     dense_workspace_bytes,
     dfss_attention,
     dfss_attention_backward,
     dfss_attention_bias,
     dfss_attention_blocked,
+    dfss_attention_ragged,
     dfss_backward_workspace_bytes,
     dfss_meta_bytes,
     dfss_meta_from_canonical,

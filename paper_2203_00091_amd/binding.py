@@ -24,6 +24,7 @@ EXPORTS = (
     "dfss_sddmm_prune_bias", "dfss_attention_bias", "dense_attention_bias", "dense_attention_fused_bias",
     "dfss_attention_blocked", "dense_attention_fused_blocked", "dfss_spmm_t",
     "dfss_backward_workspace_bytes", "dfss_attention_backward",
+    "dfss_attention_ragged", "dense_attention_fused_ragged",
 )
 
 
@@ -106,6 +107,8 @@ def load_library():
         L.dense_attention_fused_bias.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_attention_blocked.argtypes = [vp, vp, vp, vp, vp, sp, f32, vp, vp]
         L.dense_attention_fused_blocked.argtypes = [vp, vp, vp, vp, vp, sp, f32, vp, vp]
+        L.dfss_attention_ragged.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
+        L.dense_attention_fused_ragged.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_spmm_t.argtypes = [vp, vp, vp, sp, vp, vp]
         L.dfss_attention_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, sp, f32, vp, vp, vp, vp, sz, vp]
         L.dfss_meta_to_canonical.argtypes = [vp, sp, vp, vp]
@@ -114,7 +117,8 @@ def load_library():
                      "dense_attention", "dense_attention_fused", "dfss_meta_to_canonical", "dfss_meta_from_canonical",
                      "dfss_sddmm_prune_bias", "dfss_attention_bias", "dense_attention_bias",
                      "dense_attention_fused_bias", "dfss_attention_blocked", "dense_attention_fused_blocked",
-                     "dfss_spmm_t", "dfss_attention_backward"):
+                     "dfss_attention_ragged", "dense_attention_fused_ragged", "dfss_spmm_t",
+                     "dfss_attention_backward"):
             getattr(L, name).restype = ctypes.c_int
         L.dfss_status_string.argtypes = [ctypes.c_int]
         L.dfss_status_string.restype = ctypes.c_char_p
@@ -310,6 +314,26 @@ def dense_attention_fused_bias(Q, K, V, key_bias, s: Shape, scale: float, O=None
     st = load_library().dense_attention_fused_bias(_q(Q, s), _kv(K, s), _kv(V, s), _bias_ptr(key_bias, s),
                                                    ctypes.byref(s.c()), scale, _q(O, s), _stream())
     _check("dense_attention_fused_bias", st)
+    return O
+
+
+def dfss_attention_ragged(Q, K, V, key_bias, s: Shape, scale: float, O=None):
+    """DFSS forward in one kernel on unpadded arrays: any Lq, Lk a multiple of 4; key_bias may be None."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    st = load_library().dfss_attention_ragged(_q(Q, s), _kv(K, s), _kv(V, s), _bias_ptr(key_bias, s),
+                                              ctypes.byref(s.c()), scale, _q(O, s), _stream())
+    _check("dfss_attention_ragged", st)
+    return O
+
+
+def dense_attention_fused_ragged(Q, K, V, key_bias, s: Shape, scale: float, O=None):
+    """Full attention in one kernel on unpadded arrays (the baseline of dfss_attention_ragged)."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    st = load_library().dense_attention_fused_ragged(_q(Q, s), _kv(K, s), _kv(V, s), _bias_ptr(key_bias, s),
+                                                     ctypes.byref(s.c()), scale, _q(O, s), _stream())
+    _check("dense_attention_fused_ragged", st)
     return O
 
 

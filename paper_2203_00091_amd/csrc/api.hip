@@ -40,6 +40,27 @@ dfss_status check_shape(const dfss_shape *s, bool need_nm, Dims *out) {
     return DFSS_OK;
 }
 
+// Shape rules of the calls that take unpadded lengths (one-kernel paths only): any Lq, Lk a multiple of 4.
+dfss_status check_shape_ragged(const dfss_shape *s, bool need_nm, Dims *out) {
+    if (!s) return DFSS_ERR_NULL;
+    if (s->B <= 0 || s->H <= 0 || s->Lq <= 0 || s->Lk <= 0 || s->d <= 0) return DFSS_ERR_SHAPE;
+    const long long bh = (long long)s->B * s->H;
+    if (bh > 65535) return DFSS_ERR_SHAPE;
+    if (s->Lk % 4 != 0) return DFSS_ERR_SHAPE;
+    if (s->Lk > 8192 || s->Lq > (1 << 20)) return DFSS_ERR_SHAPE;
+    if (s->dtype != DFSS_BF16 && s->dtype != DFSS_F32_BF16X3) return DFSS_ERR_UNSUPPORTED;
+    const bool split = s->dtype == DFSS_F32_BF16X3;
+    if (s->d != 64 && s->d != 128) return DFSS_ERR_UNSUPPORTED;
+    int mode = -1;
+    if (need_nm) {
+        if (s->N == 2 && s->M == 4 && !split) mode = 0;
+        else if (s->N == 1 && s->M == 2) mode = 1;
+        else return DFSS_ERR_UNSUPPORTED;
+    }
+    *out = Dims{(int)bh, s->H, s->Lq, s->Lk, s->d, mode, split, split};
+    return DFSS_OK;
+}
+
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 // scale must be finite and > 0.  Tested on the bit pattern: the library is built with finite-math
 // flags, under which a floating-point comparison may not be relied on to reject NaN.
@@ -260,6 +281,32 @@ dfss_status dense_attention_fused_blocked(const void *Q, const void *K, const vo
                                           const void *block_mask, const dfss_shape *s, float scale, void *O,
                                           void *stream) {
     return attention_blocked(Q, K, V, key_bias, block_mask, s, true, scale, O, stream);
+}
+
+// dense: full attention (N, M ignored)
+static dfss_status attention_ragged(const void *Q, const void *K, const void *V, const void *key_bias,
+                                    const dfss_shape *s, bool dense, float scale, void *O, void *stream) {
+    Dims D;
+    if (!Q || !K || !V || !O) return DFSS_ERR_NULL;
+    if (dfss_status st = check_shape_ragged(s, !dense, &D)) return st;
+    if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias))
+        return DFSS_ERR_SHAPE;
+    if (D.split)
+        return hip_status(dfss::launch_fused_attention_split(Q, K, V, (const float *)key_bias, D.H, nullptr, D.BH, D.Lq,
+                                                             D.Lk, D.d, !dense, scale, O, (hipStream_t)stream));
+    return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, nullptr, D.BH, D.Lq, D.Lk,
+                                                   D.d, dense ? 2 : D.mode, scale, O, (hipStream_t)stream));
+}
+
+dfss_status dfss_attention_ragged(const void *Q, const void *K, const void *V, const void *key_bias,
+                                  const dfss_shape *s, float scale, void *O, void *stream) {
+    return attention_ragged(Q, K, V, key_bias, s, false, scale, O, stream);
+}
+
+dfss_status dense_attention_fused_ragged(const void *Q, const void *K, const void *V, const void *key_bias,
+                                         const dfss_shape *s, float scale, void *O, void *stream) {
+    return attention_ragged(Q, K, V, key_bias, s, true, scale, O, stream);
 }
 
 dfss_status dfss_spmm_t(const void *vals, const void *meta, const void *X, const dfss_shape *s, void *out,

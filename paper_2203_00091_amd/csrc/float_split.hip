@@ -69,6 +69,18 @@ struct RawBlock {
             v[i][1] = p[1];
         }
     }
+    // the same for a block that holds only `rows` rows of CPR 8-float chunks: the places of the absent rows are
+    // filled with the last row (nothing is read past the array)
+    template <int CPR>
+    __device__ __forceinline__ void load_partial(const float *block, int tid, int rows) {
+#pragma unroll
+        for (int i = 0; i < NCONV; ++i) {
+            const int idx = i * THREADS + tid, row = idx / CPR < rows ? idx / CPR : rows - 1;
+            const f32x4 *p = reinterpret_cast<const f32x4 *>(block + 8 * (row * CPR + idx % CPR));
+            v[i][0] = p[0];
+            v[i][1] = p[1];
+        }
+    }
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -599,10 +611,13 @@ __global__ __launch_bounds__(NT, 2) void k_spmm_t_split(const float *__restrict_
 // BIAS: additive key bias as in k_scores_split; a masked key gets weight exactly 0.
 // block_mask (may be null): uint8 [Lq/64][Lk/64] shared by all heads; the 64 x 64 blocks of the score matrix with a
 // zero entry are skipped (the workgroup's 64 queries are one row of blocks), as if all their scores were -inf.
+// RAGGED (implies BIAS; key_bias may then be null): Lq and Lk are not multiples of 64.  Q, O hold Lq rows and K, V,
+// key_bias Lk keys (Lk a multiple of 4); the absent keys of the last block count as masked keys, the absent queries of
+// the last tile are computed on a copy of the last query and not stored.
 // NW waves of 16 queries per workgroup: with 8 waves (Lq a multiple of 128, no block pattern) the conversion
 // of a block is spread over twice the threads and shared by twice the queries (at d = 64 the register budget
 // is then held to 128 so that two such workgroups share a CU).
-template <int D, bool PRUNE, bool BIAS, int NW>
+template <int D, bool PRUNE, bool BIAS, int NW, bool RAGGED = false>
 __global__ __launch_bounds__(NW * 64, (D == 64 && NW == 8) ? 4 : 2) void k_fused_split(const float *__restrict__ Q, const float *__restrict__ K,
                                                        const float *__restrict__ V, const float *__restrict__ key_bias,
                                                        int H, const uint8_t *__restrict__ block_mask, int Lq, int Lk,
@@ -621,11 +636,14 @@ __global__ __launch_bounds__(NW * 64, (D == 64 && NW == 8) ? 4 : 2) void k_fused
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, g = lane >> 4;
-    const unsigned nqt = Lq / QT;
+    static_assert(!RAGGED || BIAS, "ragged lengths use the arithmetic of the biased variant");
+    const unsigned nqt = (Lq + QT - 1) / QT;
     const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
     const unsigned bh = item / nqt, qt = item % nqt;
-    const int nkb = Lk / KB;
-    const int q = qt * QT + wave * 16 + n;
+    const int nkb = (Lk + KB - 1) / KB;
+    const int tail_keys = Lk - (nkb - 1) * KB;     // keys of the last block
+    int q = qt * QT + wave * 16 + n;
+    if (RAGGED && q >= Lq) q = Lq - 1;
 
     u32x4 qh[KS], ql[KS];
     {
@@ -636,7 +654,7 @@ __global__ __launch_bounds__(NW * 64, (D == 64 && NW == 8) ? 4 : 2) void k_fused
 
     const float *kblocks = K + (size_t)bh * Lk * D;
     const float *vblocks = V + (size_t)bh * Lk * D;
-    const float *bias_b = BIAS ? key_bias + (size_t)(bh / H) * Lk + 16 * g : nullptr;
+    const float *bias_b = BIAS && key_bias ? key_bias + (size_t)(bh / H) * Lk + 16 * g : nullptr;
     int dst_k[NCONV], dst_v[NCONV];
 #pragma unroll
     for (int i = 0; i < NCONV; ++i) {
@@ -687,24 +705,34 @@ __global__ __launch_bounds__(NW * 64, (D == 64 && NW == 8) ? 4 : 2) void k_fused
     };
 
     RawBlock<NCONV, NT> rk, rv;
+    auto load_block = [&](int j) {
+        if (RAGGED && j == nkb - 1 && tail_keys < KB) {
+            rk.template load_partial<CPR>(kblocks + (size_t)j * KB * D, tid, tail_keys);
+            rv.template load_partial<CPR>(vblocks + (size_t)j * KB * D, tid, tail_keys);
+        } else {
+            rk.load(kblocks + (size_t)j * KB * D, tid);
+            rv.load(vblocks + (size_t)j * KB * D, tid);
+        }
+    };
     int jb = next_block(0);
-    if (jb < nkb) {
-        rk.load(kblocks + (size_t)jb * KB * D, tid);
-        rv.load(vblocks + (size_t)jb * KB * D, tid);
-    }
+    if (jb < nkb) load_block(jb);
     while (jb < nkb) {
         const int jnext = next_block(jb + 1);
         __syncthreads();            // every wave is done with the images of the previous block
         convert(rk, rv);
-        if (jnext < nkb) {          // the next block travels while this one is used
-            rk.load(kblocks + (size_t)jnext * KB * D, tid);
-            rv.load(vblocks + (size_t)jnext * KB * D, tid);
-        }
+        if (jnext < nkb) load_block(jnext);   // the next block travels while this one is used
         __syncthreads();            // images of block jb complete
         f32x4 kb[4];                // bias of keys 16g + 4t + r of this block
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-            kb[t] = BIAS ? *reinterpret_cast<const f32x4 *>(bias_b + jb * KB + 4 * t) : f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < 4; ++t) {
+            if constexpr (RAGGED) {
+                if (jb * KB + 16 * g + 4 * t >= Lk) kb[t] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+                else if (bias_b) kb[t] = *reinterpret_cast<const f32x4 *>(bias_b + jb * KB + 4 * t);
+                else kb[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+            } else {
+                kb[t] = BIAS ? *reinterpret_cast<const f32x4 *>(bias_b + jb * KB + 4 * t) : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
 
         // scores of keys 16g + 4t + r (tile t, register r) of query n
         f32x4 acc[4];
@@ -804,6 +832,7 @@ __global__ __launch_bounds__(NW * 64, (D == 64 && NW == 8) ? 4 : 2) void k_fused
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const float inv_r = __shfl(inv, 4 * g + r, kWave);
+        if (RAGGED && (int)(qt * QT) + wave * 16 + 4 * g + r >= Lq) continue;
 #pragma unroll
         for (int ds = 0; ds < DS; ++ds) op[(size_t)r * D + ds * 16] = acc_o[ds][r] * inv_r;
     }
@@ -883,14 +912,21 @@ hipError_t launch_fused_attention_split(const void *Q, const void *K, const void
                                         float scale, void *O, hipStream_t st) {
     // 8 waves per workgroup where the 128-query tile divides Lq, is not cut by a 64 x 64 block pattern, and still
     // leaves at least two workgroups per compute unit
-    const bool wide = Lq % 128 == 0 && !block_mask && (long)BH * (Lq / 128) >= 512;
-    const unsigned grid = (unsigned)BH * (unsigned)(Lq / (wide ? 128 : 64));
+    const bool ragged = Lq % 64 != 0 || Lk % 64 != 0;   // (never together with a block pattern)
+    const bool wide = (ragged || Lq % 128 == 0) && !block_mask && (long)BH * ((Lq + 127) / 128) >= 512;
+    const unsigned grid = (unsigned)BH * (unsigned)((Lq + (wide ? 127 : 63)) / (wide ? 128 : 64));
 #define DFSS_LAUNCH_FUSED_SPLIT(DD, PP, BB, WW)                                                                   \
     hipLaunchKernelGGL((k_fused_split<DD, PP, BB, WW>), dim3(grid), dim3(WW * 64), 0, st, (const float *)Q,       \
                        (const float *)K, (const float *)V, key_bias, H, block_mask, Lq, Lk, scale, (float *)O)
 #define DFSS_LAUNCH_FUSED_SPLIT_B(DD, PP)                                 \
     do {                                                                  \
-        if (key_bias && wide) DFSS_LAUNCH_FUSED_SPLIT(DD, PP, true, 8);   \
+        if (ragged && wide)                                               \
+            hipLaunchKernelGGL((k_fused_split<DD, PP, true, 8, true>), dim3(grid), dim3(512), 0, st, (const float *)Q,  \
+                               (const float *)K, (const float *)V, key_bias, H, block_mask, Lq, Lk, scale, (float *)O); \
+        else if (ragged)                                                  \
+            hipLaunchKernelGGL((k_fused_split<DD, PP, true, 4, true>), dim3(grid), dim3(256), 0, st, (const float *)Q,  \
+                               (const float *)K, (const float *)V, key_bias, H, block_mask, Lq, Lk, scale, (float *)O); \
+        else if (key_bias && wide) DFSS_LAUNCH_FUSED_SPLIT(DD, PP, true, 8);   \
         else if (key_bias) DFSS_LAUNCH_FUSED_SPLIT(DD, PP, true, 4);      \
         else if (wide) DFSS_LAUNCH_FUSED_SPLIT(DD, PP, false, 8);         \
         else DFSS_LAUNCH_FUSED_SPLIT(DD, PP, false, 4);                   \

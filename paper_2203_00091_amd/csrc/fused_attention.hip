@@ -38,13 +38,16 @@ constexpr float kLog2e = 1.4426950408889634f;
 enum { MODE_2TO4 = 0, MODE_1TO2 = 1, MODE_DENSE = 2 };
 
 // MASKED: the call carries a key bias and/or a block mask (either pointer may be null).
+// RAGGED (implies MASKED; no block mask): the lengths are not multiples of the tiles.  Q, O hold Lq rows and K, V,
+//   key_bias Lk keys (Lk a multiple of 4); the absent keys of the last block count as masked keys and the absent
+//   queries of the last tile are computed on a copy of the last query and not stored.
 //   key_bias   additive per-key term (fp32, [B][Lk], shared by the H heads of a batch element; -inf masks
 //              a key), joined to the scaled score before the selection: as the initial value of the
 //              accumulators when the scale is folded into Q, else added after the multiplication by scale.
 //   block_mask uint8 [Lq/64][Lk/64], shared by all heads: 64 x 64 blocks of the score matrix with a zero
 //              entry are not part of the attention (hybrid blocked-ELL x N:M sparsity, App. A.1.2: the
 //              block equals the workgroup tile and pruned blocks are skipped).  Needs 64-query workgroups.
-template <int D, int MODE, int NQ, bool PRESCALE, bool MASKED>
+template <int D, int MODE, int NQ, bool PRESCALE, bool MASKED, bool RAGGED = false>
 __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
                                                  const __bf16 *__restrict__ V, const float *__restrict__ key_bias,
                                                  int H, const uint8_t *__restrict__ block_mask, int Lq, int Lk,
@@ -56,13 +59,14 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
     constexpr int DS = D / 16;          // 16-column tiles of O
     constexpr int TQ = 64 * NQ;         // queries per workgroup
     constexpr bool SPARSE = MODE != MODE_DENSE;
+    static_assert(!RAGGED || MASKED, "ragged lengths use the masking machinery");
     __shared__ u32x4 Ks[2][TILE];
     __shared__ u32x4 Vs[2][TILE];
 
     const int tid = threadIdx.x;
     const int w = tid >> 6, l = tid & 63, li = l & 15, kb = l >> 4;
 
-    const unsigned qtiles = Lq / TQ;
+    const unsigned qtiles = (Lq + TQ - 1) / TQ;
     int qt, bh;
     if (MASKED && block_mask) {
         // Row blocks of a block pattern differ widely in work (rows that see every key next to rows
@@ -77,7 +81,8 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
         bh = item / qtiles;
     }
     const int q0 = qt * TQ + w * 16 * NQ;
-    const int nblocks = Lk / KB;
+    const int nblocks = (Lk + KB - 1) / KB;
+    const int tail_keys = Lk - (nblocks - 1) * KB;   // keys of the last block (KB unless the lengths are ragged)
 
     const __bf16 *Kh = K + (size_t)bh * Lk * D;
     const __bf16 *Vh = V + (size_t)bh * Lk * D;
@@ -98,6 +103,19 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
     auto issue_block = [&](int jb, int buf) {
         const uint64_t ks = k_base + (uint64_t)jb * (KB * D * 2);
         const uint64_t vs = v_base + (uint64_t)jb * (KB * D * 2);
+        if (RAGGED && jb == nblocks - 1 && tail_keys < KB) {
+            // partial last block: the places of the absent keys are filled with the block's last key (never
+            // read past the arrays); those keys are masked below, so what is copied there is never used
+#pragma unroll
+            for (int i = 0; i < LPT; ++i) {
+                const int p = i * NT + tid, slot = p / CPR;
+                const int key = (slot & 3) | (((slot >> 4) & 3) << 2) | (((slot >> 2) & 3) << 4);
+                const int kc = key < tail_keys ? key : tail_keys - 1, vc = slot < tail_keys ? slot : tail_keys - 1;
+                async_copy16(ks, 2u * (kc * D + ((p % CPR) ^ (slot & 7)) * 8), lds_k + 16u * (buf * TILE + i * NT));
+                async_copy16(vs, 2u * (vc * D + ((p % CPR) ^ ((slot & 3) << 1)) * 8), lds_v + 16u * (buf * TILE + i * NT));
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < LPT; ++i) async_copy16(ks, 2u * k_off[i], lds_k + 16u * (buf * TILE + i * NT));
 #pragma unroll
@@ -112,8 +130,9 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
     for (int qs = 0; qs < NQ; ++qs)
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
-            const u32x4 raw = *reinterpret_cast<const u32x4 *>(Q + ((size_t)bh * Lq + q0 + 16 * qs + li) * D +
-                                                               32 * s + 8 * kb);
+            int qrow = q0 + 16 * qs + li;
+            if (RAGGED && qrow >= Lq) qrow = Lq - 1;   // absent query of a ragged last tile: computed, not stored
+            const u32x4 raw = *reinterpret_cast<const u32x4 *>(Q + ((size_t)bh * Lq + qrow) * D + 32 * s + 8 * kb);
             if constexpr (PRESCALE) {
                 u32x4 sc;
 #pragma unroll
@@ -150,8 +169,8 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
     // most 128 blocks: two 64-bit masks each, in scalar registers; no LDS, no barrier).
     uint64_t live_lo = ~0ull, live_hi = ~0ull;   // block is visited
     uint64_t bias_lo = 0ull, bias_hi = 0ull;     // block holds a non-zero bias
-    const f32x4 *bias4 = nullptr;   // bias of this lane's 16 keys of a block: keys 64 jb + 16 kb + 4 t + r
-    f32x4 kb4[4];
+    const float *brow = nullptr;    // bias row of this head's batch element
+    f32x4 kb4[4];                   // bias of this lane's 16 keys of a block: keys 64 jb + 16 kb + 4 t + r
     if constexpr (MASKED) {
         if (block_mask) {   // row of the mask that belongs to this workgroup's 64 queries
             const uint8_t *row = block_mask + (size_t)(qt * TQ / 64) * nblocks;
@@ -159,7 +178,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
             live_hi = __ballot(64 + l < nblocks && row[64 + l < nblocks ? 64 + l : 0] != 0);
         }
         if (key_bias) {
-            const float *brow = key_bias + (size_t)(bh / H) * Lk;
+            brow = key_bias + (size_t)(bh / H) * Lk;
             uint64_t real_lo = 0ull, real_hi = 0ull;
             for (int k0 = 0; k0 < Lk; k0 += 4 * 4 * kWave) {   // 256 keys = 4 blocks per load, 4 loads in flight
                 f32x4 b[4];
@@ -186,7 +205,10 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
                 }
             }
             live_lo &= real_lo, live_hi &= real_hi;
-            bias4 = reinterpret_cast<const f32x4 *>(brow + 16 * kb);
+        }
+        if (RAGGED && tail_keys < KB) {   // the absent keys of a partial last block are masked keys
+            if (nblocks <= 64) bias_lo |= 1ull << (nblocks - 1);
+            else bias_hi |= 1ull << (nblocks - 65);
         }
     }
     // smallest live block index >= from, or nblocks
@@ -239,7 +261,16 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
         };
         if (MASKED && with_bias) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t) kb4[t] = bias4[16 * jb + t];
+            for (int t = 0; t < 4; ++t) {
+                const int key = KB * jb + 16 * kb + 4 * t;
+                if constexpr (RAGGED) {
+                    if (key >= Lk) kb4[t] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+                    else if (brow) kb4[t] = *reinterpret_cast<const f32x4 *>(brow + key);
+                    else kb4[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+                } else {
+                    kb4[t] = *reinterpret_cast<const f32x4 *>(brow + key);
+                }
+            }
             if constexpr (PRESCALE) scores(std::true_type{});    // bias = initial value of the accumulators
             else scores(std::false_type{});                      // bias added after the scaling, below
         } else {
@@ -403,7 +434,8 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
         for (int pass = 0; pass < 16 / RPP; ++pass) {
             const int row = pass * RPP + l / CPR, c = l % CPR;
             const u32x4 v = *reinterpret_cast<const u32x4 *>(stage + row * ROWB + c * 16);
-            *reinterpret_cast<u32x4 *>(O + ((size_t)bh * Lq + q0 + 16 * qs + row) * D + c * 8) = v;
+            if (!RAGGED || q0 + 16 * qs + row < Lq)
+                *reinterpret_cast<u32x4 *>(O + ((size_t)bh * Lq + q0 + 16 * qs + row) * D + c * 8) = v;
         }
         wave_lds_sync();   // the staging rows are free for the next tile
     }
@@ -414,15 +446,15 @@ inline bool is_pow2(float x) {
     return frexpf(x, &e) == 0.5f;
 }
 
-template <int MODE, int NQ, bool MASKED>
+template <int MODE, int NQ, bool MASKED, bool RAGGED = false>
 hipError_t launch_nq(const void *Q, const void *K, const void *V, const float *key_bias, int H,
                      const uint8_t *block_mask, int BH, int Lq, int Lk, int d, float scale, void *O, hipStream_t st) {
-    const unsigned grid = (unsigned)((long)BH * (Lq / (64 * NQ)));
+    const unsigned grid = (unsigned)((long)BH * ((Lq + 64 * NQ - 1) / (64 * NQ)));
     const bool pre = is_pow2(scale);
 #define DFSS_LAUNCH(DD, PRE)                                                                                    \
-    hipLaunchKernelGGL((k_fused<DD, MODE, NQ, PRE, MASKED>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)Q,   \
-                       (const __bf16 *)K, (const __bf16 *)V, key_bias, H, block_mask, Lq, Lk, scale,            \
-                       (uint16_t *)O)
+    hipLaunchKernelGGL((k_fused<DD, MODE, NQ, PRE, MASKED, RAGGED>), dim3(grid), dim3(NT), 0, st,               \
+                       (const __bf16 *)Q, (const __bf16 *)K, (const __bf16 *)V, key_bias, H, block_mask, Lq,    \
+                       Lk, scale, (uint16_t *)O)
     if (d == 64) {
         if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
     } else {
@@ -439,6 +471,11 @@ hipError_t launch(const void *Q, const void *K, const void *V, const float *key_
     bool two = Lq % 128 == 0 && (long)BH * (Lq / 128) >= 768;   // at least 3 workgroups per compute unit
     if (const char *f = getenv("DFSS_FUSED_NQ")) two = Lq % 128 == 0 && f[0] == '2';   // for measurements
     if (block_mask) two = false;   // the block of the mask is the 64-query workgroup tile
+    if (Lq % 64 != 0 || Lk % 64 != 0) {   // (never together with a block mask)
+        if ((long)BH * ((Lq + 127) / 128) >= 768)
+            return launch_nq<MODE, 2, true, true>(Q, K, V, key_bias, H, nullptr, BH, Lq, Lk, d, scale, O, st);
+        return launch_nq<MODE, 1, true, true>(Q, K, V, key_bias, H, nullptr, BH, Lq, Lk, d, scale, O, st);
+    }
     if (key_bias || block_mask) {
         if (two) return launch_nq<MODE, 2, true>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, st);
         return launch_nq<MODE, 1, true>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, st);
@@ -464,7 +501,7 @@ hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, c
         else if (f[0] == '3' && f[1] == '2' && f[2] == 'x' && f[3] == '2' && d == 64) tile = 32, nw = 2;
         else if (f[0] == '3' && f[1] == '2' && f[2] == 'x' && f[3] == '4' && Lq % 128 == 0) tile = 32, nw = 4;
     }
-    if (tile == 32 && !key_bias && !block_mask)
+    if (tile == 32 && !key_bias && !block_mask && Lq % 64 == 0 && Lk % 64 == 0)
         return launch_fused_attention32(Q, K, V, BH, Lq, Lk, d, mode, nw, scale, O, st);
     if (mode == 0) return launch<MODE_2TO4>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, st);
     if (mode == 1) return launch<MODE_1TO2>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, st);

@@ -120,6 +120,17 @@ def test_errors_are_reported_before_any_launch():
                                        0.125, aligned, aligned, aligned, ws, 1 << 30, None) == E_UNSUP
     assert lib.dfss_attention(aligned, aligned, aligned, ctypes.byref(f32), 0.125, aligned, ws, 16, None) == E_WS
     assert lib.dense_attention(aligned, aligned, aligned, ctypes.byref(f32), 0.125, aligned, ws, 16, None) == E_WS
+    # unpadded lengths: any Lq, Lk a multiple of 4; bfloat16 or split-product float data only
+    rag = Shape(1, 1, 100, 132, 64).c()
+    assert lib.dfss_attention_ragged(aligned, aligned, None, None, ctypes.byref(rag), 0.125, aligned, None) == E_NULL
+    assert lib.dfss_attention_ragged(aligned, aligned, aligned, odd, ctypes.byref(rag), 0.125, aligned, None) == E_SHAPE
+    assert lib.dfss_attention_ragged(aligned, aligned, aligned, None, ctypes.byref(rag), 0.0, aligned, None) == E_UNSUP
+    for bad_rag in (Shape(1, 1, 100, 130, 64), Shape(1, 1, 100, 8196, 64), Shape(1, 1, 0, 128, 64)):
+        assert lib.dfss_attention_ragged(aligned, aligned, aligned, None, ctypes.byref(bad_rag.c()), 0.125, aligned, None) == E_SHAPE
+        assert lib.dense_attention_fused_ragged(aligned, aligned, aligned, None, ctypes.byref(bad_rag.c()), 0.125, aligned, None) == E_SHAPE
+    for unsup in (Shape(1, 1, 100, 132, 64, 1, 2, dfss.DFSS_F32), Shape(1, 1, 100, 132, 64, 2, 4, dfss.DFSS_F32_BF16X3),
+                  Shape(1, 1, 100, 132, 96), Shape(1, 1, 100, 132, 64, 3, 4)):
+        assert lib.dfss_attention_ragged(aligned, aligned, aligned, None, ctypes.byref(unsup.c()), 0.125, aligned, None) == E_UNSUP
     assert lib.dfss_status_string(0) == b"ok"
     assert lib.dfss_status_string(E_WS) == b"workspace too small"
 

@@ -1,0 +1,174 @@
+"""Lengths that are not tile multiples, through dfss_attention_ragged / dense_attention_fused_ragged
+(needs an MI355X).  The oracle takes any Lq and any Lk that is a multiple of M, so it is run on the
+unpadded arrays directly; the bar is that of the whole path elsewhere (max-abs 2e-2 on O).  The arrays
+handed to the library are exactly as large as the shape says, and O sits in front of a guard region that
+must stay untouched.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2203_00091_amd as dfss
+from paper_2203_00091_amd import DFSS_BF16, DFSS_F32_BF16X3, Shape, synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+GUARD = 4096   # elements behind O that no call may write
+
+
+def _dev(t):
+    return t.to(DEV).contiguous()
+
+
+def _np(t):
+    return t.detach().to("cpu", torch.float32).numpy()
+
+
+def _inputs(BH, Lq, Lk, d, dtype, seed):
+    tdt = torch.bfloat16 if dtype == DFSS_BF16 else torch.float32
+    Q, K, V = synth.gaussian_qkv(BH, Lq, Lk, d, 1.0, seed=seed, dtype=tdt)
+    return Q, K, V, tuple(synth.to_numpy_f32(t) for t in (Q, K, V))
+
+
+def _guarded_out(s):
+    n = s.BH * s.Lq * s.d
+    buf = torch.full((n + GUARD,), 777.0, dtype=s.torch_dtype, device=DEV)
+    return buf, buf[:n].view(s.BH, s.Lq, s.d)
+
+
+def _run(fn, Q, K, V, bias, s, scale):
+    buf, O = _guarded_out(s)
+    fn(_dev(Q), _dev(K), _dev(V), None if bias is None else _dev(bias), s, scale, O=O)
+    torch.cuda.synchronize()
+    assert bool((buf[O.numel():] == 777.0).all()), "wrote behind O"
+    out = _np(O)
+    assert np.isfinite(out).all()
+    return out
+
+
+def _max_err(O, ref, Qn, Kn, scale, dtype, bias=None, H=1, tie=1e-4):
+    """Largest |O - ref|.  For float data (1:2) rows that hold a pair of scores closer than `tie` are set
+    aside: the split products differ from the oracle's fp32 products by up to ~1e-5, so there the other key
+    of the pair may rightly be kept, which moves a short row (few keys, large weights) by far more than
+    rounding does.  (Long rows need no such care: no single weight is large enough.)"""
+    if dtype == DFSS_BF16 or tie == 0:
+        return np.abs(O - ref).max()
+    worst, rows, kept = 0.0, 0, 0
+    for h in range(O.shape[0]):
+        S = oracle.scores(Qn[h], Kn[h], scale)
+        if bias is not None:
+            S = oracle.add_key_bias(S, bias[h // H])
+        with np.errstate(invalid="ignore"):
+            gap = np.abs(S[:, 0::2] - S[:, 1::2])          # nan where both keys are masked
+        safe = ~(gap < tie).any(-1)
+        rows, kept = rows + safe.size, kept + int(safe.sum())
+        if safe.any():
+            worst = max(worst, float(np.abs(O[h] - ref[h])[safe].max()))
+    assert kept >= 0.95 * rows
+    return worst
+
+
+CASES = [
+    # B, H, Lq, Lk, d
+    (2, 2, 100, 100, 64),      # one partial query tile per head, keys end inside the second block
+    (1, 3, 1, 4, 64),          # the smallest: one query, one run of keys
+    (1, 2, 333, 500, 128),     # d = 128; several tiles and a ragged tail on both sides
+    (2, 1, 64, 36, 64),        # a single, partial key block
+    (1, 2, 130, 192, 64),      # keys a multiple of 64 (not of 128), queries ragged
+    (1, 2, 128, 132, 64),      # queries a tile multiple, one run of keys in the last block
+    (4, 12, 2001, 100, 64),    # enough query tiles for the 128-query workgroups of long inputs
+    (4, 12, 1990, 68, 128),    # ... and at d = 128
+]
+
+
+@pytest.mark.parametrize("B,H,Lq,Lk,d", CASES)
+@pytest.mark.parametrize("dtype,N,M", [(DFSS_BF16, 2, 4), (DFSS_BF16, 1, 2), (DFSS_F32_BF16X3, 1, 2)])
+def test_ragged_attention_against_oracle(B, H, Lq, Lk, d, dtype, N, M):
+    Q, K, V, (Qn, Kn, Vn) = _inputs(B * H, Lq, Lk, d, dtype, 8100 + Lq + Lk + d)
+    s = Shape(B, H, Lq, Lk, d, N, M, dtype)
+    scale = 1.0 / math.sqrt(d)
+    O = _run(dfss.dfss_attention_ragged, Q, K, V, None, s, scale)
+    Od = _run(dfss.dense_attention_fused_ragged, Q, K, V, None, s, scale)
+    ref = oracle.attention(Qn, Kn, Vn, N, M, scale)
+    ref_dense = oracle.attention(Qn, Kn, Vn, 1, 1, scale)
+    assert O.shape == ref.shape
+    assert _max_err(O, ref, Qn, Kn, scale, dtype) <= 2e-2
+    assert np.abs(Od - ref_dense).max() <= 2e-2
+
+
+@pytest.mark.parametrize("dtype,N,M", [(DFSS_BF16, 2, 4), (DFSS_F32_BF16X3, 1, 2)])
+@pytest.mark.parametrize("scale", [0.125, 0.11])     # bias as initial accumulator value / added after the scaling
+def test_ragged_attention_with_key_bias(dtype, N, M, scale):
+    """A padding mask (lengths not aligned to anything) plus a finite bias on unpadded arrays whose rows
+    of key_bias are Lk floats long."""
+    B, H, Lq, Lk, d = 3, 2, 150, 332, 64
+    Q, K, V, (Qn, Kn, Vn) = _inputs(B * H, Lq, Lk, d, dtype, 8200)
+    lengths = synth.padding_lengths(B, Lk, 8201)
+    bias = synth.key_padding_bias(lengths, Lk)
+    g = torch.Generator().manual_seed(8202)
+    bias[1] += torch.randn(Lk, generator=g)          # finite terms next to the -inf of the padding
+    s = Shape(B, H, Lq, Lk, d, N, M, dtype)
+    O = _run(dfss.dfss_attention_ragged, Q, K, V, bias, s, scale)
+    Od = _run(dfss.dense_attention_fused_ragged, Q, K, V, bias, s, scale)
+    ref = oracle.attention(Qn, Kn, Vn, N, M, scale, key_bias=bias.numpy(), heads_per_batch=H)
+    ref_dense = oracle.attention(Qn, Kn, Vn, 1, 1, scale, key_bias=bias.numpy(), heads_per_batch=H)
+    assert _max_err(O, ref, Qn, Kn, scale, dtype, bias.numpy(), H) <= 2e-2
+    assert np.abs(Od - ref_dense).max() <= 2e-2
+
+
+@pytest.mark.parametrize("dtype,N,M", [(DFSS_BF16, 2, 4), (DFSS_F32_BF16X3, 1, 2)])
+def test_ragged_equals_padded_and_masked(dtype, N, M):
+    """The definition: the call on unpadded arrays gives what the tile-multiple call gives on arrays padded
+    with arbitrary (finite) rows whose keys are masked -- bit for bit, since the kept scores are the same."""
+    B, H, Lq, Lk, d = 2, 2, 100, 200, 64
+    Lqp, Lkp = 128, 256
+    Q, K, V, _ = _inputs(B * H, Lq, Lk, d, dtype, 8300)
+    Qp, Kp, Vp, _ = _inputs(B * H, Lqp, Lkp, d, dtype, 8301)
+    Qp[:, :Lq], Kp[:, :Lk], Vp[:, :Lk] = Q, K, V
+    bias = torch.zeros((B, Lkp), dtype=torch.float32)
+    bias[:, Lk:] = float("-inf")
+    s, sp = Shape(B, H, Lq, Lk, d, N, M, dtype), Shape(B, H, Lqp, Lkp, d, N, M, dtype)
+    O = _run(dfss.dfss_attention_ragged, Q, K, V, None, s, 0.125)
+    Op = dfss.dfss_attention_bias(_dev(Qp), _dev(Kp), _dev(Vp), _dev(bias), sp, 0.125)
+    torch.cuda.synchronize()
+    assert np.array_equal(O, _np(Op)[:, :Lq])
+
+
+@pytest.mark.parametrize("dtype,N,M", [(DFSS_BF16, 2, 4), (DFSS_F32_BF16X3, 1, 2)])
+def test_ragged_call_on_tile_multiples_equals_the_plain_call(dtype, N, M):
+    B, H, L, d = 2, 2, 256, 64
+    Q, K, V, _ = _inputs(B * H, L, L, d, dtype, 8400)
+    s = Shape(B, H, L, L, d, N, M, dtype)
+    O = _run(dfss.dfss_attention_ragged, Q, K, V, None, s, 0.125)
+    O1 = dfss.dfss_attention(_dev(Q), _dev(K), _dev(V), s, 0.125)
+    torch.cuda.synchronize()
+    assert np.array_equal(O, _np(O1))
+
+
+@pytest.mark.parametrize("dtype,N,M", [(DFSS_BF16, 2, 4), (DFSS_F32_BF16X3, 1, 2)])
+def test_ragged_length_4000(dtype, N, M):
+    """The sequence length of the paper's retrieval task (Sec. 5.1): 4000 = 62.5 blocks of 64 keys.
+    Sampled query rows against the oracle (every key of those rows)."""
+    B, H, L, d = 1, 2, 4000, 64
+    Q, K, V, (Qn, Kn, Vn) = _inputs(B * H, L, L, d, dtype, 8500)
+    s = Shape(B, H, L, L, d, N, M, dtype)
+    O = _run(dfss.dfss_attention_ragged, Q, K, V, None, s, 0.125)
+    rows = np.r_[0:8, 1990:2010, 3960:4000]      # first rows, middle, the ragged last tile
+    for h in range(B * H):
+        ref = oracle.attention(Qn[h][rows], Kn[h], Vn[h], N, M, 0.125)
+        assert _max_err(O[h][rows][None], ref[None], Qn[h][rows][None], Kn[h][None], 0.125, dtype, tie=0) <= 2e-2
+
+
+def test_ragged_rejects_what_it_cannot_run():
+    Q, K, V, _ = _inputs(1, 64, 64, 64, DFSS_BF16, 8600)
+    with pytest.raises(dfss.DfssError):      # Lk not a multiple of 4
+        s = Shape(1, 1, 64, 62, 64, 2, 4)
+        dfss.dfss_attention_ragged(_dev(Q), _dev(K[:, :62]), _dev(V[:, :62]), None, s, 0.125)
+    with pytest.raises(dfss.DfssError):      # exact fp32 products have no one-kernel path
+        s = Shape(1, 1, 64, 64, 64, 1, 2, dfss.DFSS_F32)
+        dfss.dfss_attention_ragged(_dev(Q.float()), _dev(K.float()), _dev(V.float()), None, s, 0.125)
+    torch.cuda.synchronize()
