@@ -94,6 +94,19 @@ __device__ __forceinline__ void wait_async_copies_keep() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (YOUNGER & 15) | ((YOUNGER >> 4) << 14));
 }
 
+// XOR pattern for the 16-byte chunks of row `row` of a tile that is read with the transposing 8-byte LDS read
+// (lane (li, g): row = row0(g) + li / 4, chunk 2 x + (li / 2) % 2, half li % 2, where row0 differs between the lane
+// groups g by a multiple of 8): the 32 lanes served together (two groups) then fall into 32 different pairs of banks.
+// Bits used: row bit 1 (bit 0 alternates the bank halves of 128-byte rows by itself), and bit 3 ^ bit 4 -- whichever
+// of the two tells the lane groups of one instruction apart (row0 = 8 g for the sparse product, 16 g + 8 m for the
+// dense one).
+template <int CPR>
+__device__ __forceinline__ int tr_row_swizzle(int row) {
+    static_assert(CPR == 8 || CPR == 16, "rows of 128 or 256 bytes");
+    const int g = ((row >> 3) ^ (row >> 4)) & 1;
+    return CPR == 8 ? (((row >> 1) & 1) << 1) | (g << 2) : ((row & 3) << 1) | (g << 3);
+}
+
 // Orders this wave's own LDS traffic: writes issued before the call are visible to reads of any
 // lane of the same wave issued after it.  The hardware executes a wave's LDS operations in order;
 // the fences (wavefront scope, no instructions) only keep the compiler from moving them across.

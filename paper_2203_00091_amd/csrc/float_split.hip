@@ -222,7 +222,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_scores_split(const float *__rest
 // codes 2 (i%2) + [code of pair i is 0xE]; one instruction covers the 64-key block.  Dense: matrix step
 // m (0, 1) takes, in lane group g, the keys 32 m + 8 g .. +7 on the dense instruction.  V blocks are
 // converted like K blocks (one block ahead, double-buffered images), into row-major bf16 images whose
-// 16-byte chunk c of key k sits at chunk c ^ 2 (k % 4); the B operand (keys along the contraction) comes
+// 16-byte chunk c of key k sits at chunk c ^ tr_row_swizzle(k); the B operand (keys along the contraction) comes
 // from the transposing LDS read.
 // ---------------------------------------------------------------------------------------------
 template <int D, bool SPARSE, int NW>
@@ -249,7 +249,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_av_split(const float *__restrict
     for (int i = 0; i < NCONV; ++i) {
         const int idx = i * NT + tid;
         const int key = idx / CPR, c = idx % CPR;
-        dst[i] = key * CPR + (c ^ ((key & 3) << 1));
+        dst[i] = key * CPR + (c ^ tr_row_swizzle<CPR>(key));
     }
     auto convert = [&](const RawBlock<NCONV, NT> &raw, int buf) {
 #pragma unroll
@@ -295,10 +295,10 @@ __global__ __launch_bounds__(NW * 64, 2) void k_av_split(const float *__restrict
     const int tr_row = li >> 2;
     const int tr_sub = (li >> 1) & 1;
     const int tr_byte = 8 * (li & 1);
-    const int tr_xor = tr_row << 1;
     auto tr8 = [&](const u32x4 *img, int key0, int ds) {
         const char *base = reinterpret_cast<const char *>(img);
-        const int chunk = (2 * ds + tr_sub) ^ tr_xor;      // key0 is a multiple of 4: (row & 3) == tr_row
+        // key0 is a multiple of 8: the rows key0 + tr_row and key0 + 4 + tr_row share the pattern
+        const int chunk = (2 * ds + tr_sub) ^ tr_row_swizzle<CPR>(key0 + tr_row);
         const s16x4 t0 = lds_read_tr16(base + ((key0 + tr_row) * CPR + chunk) * 16 + tr_byte);
         const s16x4 t1 = lds_read_tr16(base + ((key0 + 4 + tr_row) * CPR + chunk) * 16 + tr_byte);
         return __builtin_bit_cast(u32x4, __builtin_shufflevector(t0, t1, 0, 1, 2, 3, 4, 5, 6, 7));
@@ -662,7 +662,7 @@ __global__ __launch_bounds__(NW * 64, (D == 64 && NW == 8) ? 4 : 2) void k_fused
         const int key = idx / CPR, c = idx % CPR;
         const int slot = 16 * ((key >> 2) & 3) + 4 * (key >> 4) + (key & 3);
         dst_k[i] = slot * CPR + (c ^ (slot & 7));
-        dst_v[i] = key * CPR + (c ^ ((key & 3) << 1));
+        dst_v[i] = key * CPR + (c ^ tr_row_swizzle<CPR>(key));
     }
     auto convert = [&](const RawBlock<NCONV, NT> &rk, const RawBlock<NCONV, NT> &rv) {
 #pragma unroll
@@ -681,10 +681,9 @@ __global__ __launch_bounds__(NW * 64, (D == 64 && NW == 8) ? 4 : 2) void k_fused
     const int tr_row = n >> 2;
     const int tr_sub = (n >> 1) & 1;
     const int tr_byte = 8 * (n & 1);
-    const int tr_xor = tr_row << 1;
     auto tr8 = [&](const u32x4 *img, int key0, int ds) {
         const char *base = reinterpret_cast<const char *>(img);
-        const int chunk = (2 * ds + tr_sub) ^ tr_xor;
+        const int chunk = (2 * ds + tr_sub) ^ tr_row_swizzle<CPR>(key0 + tr_row);   // key0 is a multiple of 8
         const s16x4 t0 = lds_read_tr16(base + ((key0 + tr_row) * CPR + chunk) * 16 + tr_byte);
         const s16x4 t1 = lds_read_tr16(base + ((key0 + 4 + tr_row) * CPR + chunk) * 16 + tr_byte);
         return __builtin_bit_cast(u32x4, __builtin_shufflevector(t0, t1, 0, 1, 2, 3, 4, 5, 6, 7));

@@ -88,7 +88,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
     const __bf16 *Vh = V + (size_t)bh * Lk * D;
 
     // K block in LDS: row slot 16 t + i holds key 16 (i/4) + 4 t + i%4 (tile t, MFMA row i), chunk c
-    // at position slot * CPR + (c ^ (slot & 7)).  V block: row = key, chunk c at row * CPR + (c ^ ((row & 3) << 1)).
+    // at position slot * CPR + (c ^ (slot & 7)).  V block: row = key, chunk c at row * CPR + (c ^ tr_row_swizzle(row)).
     int k_off[LPT], v_off[LPT];
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
         const int slot = p / CPR;
         const int key = (slot & 3) | (((slot >> 4) & 3) << 2) | (((slot >> 2) & 3) << 4);
         k_off[i] = key * D + ((p % CPR) ^ (slot & 7)) * 8;
-        v_off[i] = slot * D + ((p % CPR) ^ ((slot & 3) << 1)) * 8;
+        v_off[i] = slot * D + ((p % CPR) ^ tr_row_swizzle<CPR>(slot)) * 8;
     }
     const uint32_t lds_k = lds_address(&Ks[0][w * 64]), lds_v = lds_address(&Vs[0][w * 64]);
     const uint64_t k_base = uniform_address(Kh), v_base = uniform_address(Vh);
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
                 const int key = (slot & 3) | (((slot >> 4) & 3) << 2) | (((slot >> 2) & 3) << 4);
                 const int kc = key < tail_keys ? key : tail_keys - 1, vc = slot < tail_keys ? slot : tail_keys - 1;
                 async_copy16(ks, 2u * (kc * D + ((p % CPR) ^ (slot & 7)) * 8), lds_k + 16u * (buf * TILE + i * NT));
-                async_copy16(vs, 2u * (vc * D + ((p % CPR) ^ ((slot & 3) << 1)) * 8), lds_v + 16u * (buf * TILE + i * NT));
+                async_copy16(vs, 2u * (vc * D + ((p % CPR) ^ tr_row_swizzle<CPR>(slot)) * 8), lds_v + 16u * (buf * TILE + i * NT));
             }
             return;
         }
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
                                                             one2, one2, one2, one2, one2, one2, one2, one2});
     const bf16x8 ones8 = __builtin_bit_cast(bf16x8, u32x4{one2, one2, one2, one2});
 
-    const int tr_row = li >> 2, tr_sub = (li >> 1) & 1, tr_byte = 8 * (li & 1), tr_xor = tr_row << 1;
+    const int tr_row = li >> 2, tr_sub = (li >> 1) & 1, tr_byte = 8 * (li & 1);
 
     // Blocks to visit.  Blocks that the block mask prunes, and blocks whose 64 keys are all masked by the
     // key bias (-inf), contribute exactly nothing and are skipped, copies included; blocks whose biases
@@ -359,7 +359,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
         const char *vbase = reinterpret_cast<const char *>(&Vs[buf][0]);
         auto tr = [&](int key0, int ds) {
             const int row = key0 + tr_row;
-            const int chunk = (2 * ds + tr_sub) ^ tr_xor;
+            const int chunk = (2 * ds + tr_sub) ^ tr_row_swizzle<CPR>(row);
             return lds_read_tr16(vbase + (row * CPR + chunk) * 16 + tr_byte);
         };
         if constexpr (SPARSE) {
