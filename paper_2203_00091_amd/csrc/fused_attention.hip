@@ -271,10 +271,25 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
                     kb4[t] = *reinterpret_cast<const f32x4 *>(brow + key);
                 }
             }
-            if constexpr (PRESCALE) scores(std::true_type{});    // bias = initial value of the accumulators
-            else scores(std::false_type{});                      // bias added after the scaling, below
+            if constexpr (PRESCALE) {
+                scores(std::true_type{});    // bias = initial value of the accumulators
+            } else {
+                scores(std::false_type{});   // two roundings (product, then sum), never a fused multiply-add
+#pragma unroll
+                for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) acc[qs][t][r] = __fadd_rn(acc[qs][t][r] * scale, kb4[t][r]);
+            }
         } else {
             scores(std::false_type{});
+            if constexpr (!PRESCALE) {
+#pragma unroll
+                for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) acc[qs][t] = acc[qs][t] * scale;
+            }
         }
 
         // ---- prune, block maximum ----
@@ -287,16 +302,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
             m_blk[qs] = -3.0e38f;
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                f32x4 a = acc[qs][t];
-                if constexpr (!PRESCALE) {
-                    a = a * scale;
-                    if constexpr (MASKED) {   // two roundings (product, then sum), never a fused multiply-add
-                        if (with_bias) {
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) a[r] = __fadd_rn(a[r], kb4[t][r]);
-                        }
-                    }
-                }
+                const f32x4 a = acc[qs][t];   // scaled (and biased) above, outside any per-block condition
                 if constexpr (SPARSE) {
                     float lo, hi;
                     uint32_t code;
