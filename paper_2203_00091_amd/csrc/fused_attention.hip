@@ -179,30 +179,33 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
         }
         if (key_bias) {
             brow = key_bias + (size_t)(bh / H) * Lk;
+            // Lane l looks at block l (then 64 + l): 16 float4 loads per lane, all in flight at once, a running
+            // maximum (is any key of the block unmasked?) and the OR of the bit patterns (is any bias non-zero?);
+            // one ballot each turns the lanes' answers into the block bitmaps.  In a partial last block the loads
+            // past the row's end re-read its last float4 (the absent keys are accounted for below).
             uint64_t real_lo = 0ull, real_hi = 0ull;
-            for (int k0 = 0; k0 < Lk; k0 += 4 * 4 * kWave) {   // 256 keys = 4 blocks per load, 4 loads in flight
-                f32x4 b[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int key = k0 + 4 * kWave * u + 4 * l;
-                    b[u] = key < Lk ? *reinterpret_cast<const f32x4 *>(brow + key)
-                                    : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-                }
+            for (int half = 0; half < 2; ++half) {
+                if (64 * half >= nblocks) break;
+                const int blk = 64 * half + l;
+                float mx = -INFINITY;
+                uint32_t bits = 0u;
+                if (blk < nblocks) {
+                    const float *bp = brow + KB * blk;
+                    const int last = Lk - 4 - KB * blk;   // offset of the row's last float4 from the block's start
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    // lanes 16 g .. 16 g + 15 looked at block blk0 + g
-                    const uint64_t m = __ballot(b[u][0] > -INFINITY || b[u][1] > -INFINITY || b[u][2] > -INFINITY ||
-                                                b[u][3] > -INFINITY);
-                    const uint64_t z =
-                        __ballot(b[u][0] != 0.f || b[u][1] != 0.f || b[u][2] != 0.f || b[u][3] != 0.f);
-                    const uint64_t nib = (uint64_t)((m & 0xFFFFull) != 0) | (uint64_t)(((m >> 16) & 0xFFFFull) != 0) << 1 |
-                                         (uint64_t)(((m >> 32) & 0xFFFFull) != 0) << 2 | (uint64_t)((m >> 48) != 0) << 3;
-                    const uint64_t znib = (uint64_t)((z & 0xFFFFull) != 0) | (uint64_t)(((z >> 16) & 0xFFFFull) != 0) << 1 |
-                                          (uint64_t)(((z >> 32) & 0xFFFFull) != 0) << 2 | (uint64_t)((z >> 48) != 0) << 3;
-                    const int blk0 = (k0 + 4 * kWave * u) / KB;
-                    if (blk0 < 64) real_lo |= nib << blk0, bias_lo |= znib << blk0;
-                    else if (blk0 < 128) real_hi |= nib << (blk0 - 64), bias_hi |= znib << (blk0 - 64);
+                    for (int c = 0; c < KB / 4; ++c) {
+                        const f32x4 b = *reinterpret_cast<const f32x4 *>(bp + (RAGGED && 4 * c > last ? last : 4 * c));
+                        mx = fmaxf(fmaxf(mx, b[0]), b[1]);
+                        mx = fmaxf(fmaxf(mx, b[2]), b[3]);
+                        bits |= __float_as_uint(b[0]) | __float_as_uint(b[1]);
+                        bits |= __float_as_uint(b[2]) | __float_as_uint(b[3]);
+                    }
                 }
+                const uint64_t real = __ballot(__float_as_uint(mx) != 0xFF800000u);   // some key above -inf
+                const uint64_t nonzero = __ballot((bits & 0x7FFFFFFFu) != 0u);         // some bias other than +-0
+                if (half == 0) real_lo = real, bias_lo = nonzero;
+                else real_hi = real, bias_hi = nonzero;
             }
             live_lo &= real_lo, live_hi &= real_hi;
         }
@@ -211,29 +214,39 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
             else bias_hi |= 1ull << (nblocks - 65);
         }
     }
-    // smallest live block index >= from, or nblocks
-    auto next_live = [&](int from) -> int {
-        if constexpr (!MASKED) return from;
-        if (from < 64) {
-            const uint64_t m = live_lo >> from;
-            if (m) return from + __builtin_ctzll(m);
-            from = 64;
+    // The blocks still to visit, as a list that is consumed: take the smallest one off (or return nblocks).
+    // Without masks it is a plain counter.
+    if constexpr (MASKED) {   // only blocks that exist
+        if (nblocks < 64) live_lo &= (1ull << nblocks) - 1ull, live_hi = 0ull;
+        else if (nblocks < 128) live_hi &= (1ull << (nblocks - 64)) - 1ull;
+    }
+    int next_plain = 0;
+    auto take_live = [&]() -> int {
+        if constexpr (!MASKED) {
+            return next_plain++;
+        } else {
+            if (live_lo) {
+                const int j = __builtin_ctzll(live_lo);
+                live_lo &= live_lo - 1ull;
+                return j;
+            }
+            if (live_hi) {
+                const int j = __builtin_ctzll(live_hi);
+                live_hi &= live_hi - 1ull;
+                return 64 + j;
+            }
+            return nblocks;
         }
-        if (from < 128) {
-            const uint64_t m = live_hi >> (from - 64);
-            if (m) return from + __builtin_ctzll(m);
-        }
-        return nblocks;
     };
 
-    int jb = next_live(0);
+    int jb = take_live();
+    int jn = take_live();   // the block after this one
     // block 0 (copied speculatively at the top) turned out to be fully masked: overwrite the buffer
     // with the first live block (the two copies of a wave complete in issue order)
     if (MASKED && jb != 0 && jb < nblocks) issue_block(jb, 0);
 
     for (int it = 0; jb < nblocks; ++it) {
         const int buf = it & 1;
-        const int jn = next_live(jb + 1);   // the block after this one
         wait_async_copies();  // vmcnt(0): this block's copies have landed
         __syncthreads();
         if (jn < nblocks) issue_block(jn, buf ^ 1);
@@ -414,6 +427,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
             }
         }
         jb = jn;
+        jn = take_live();
     }
     if constexpr (MASKED) wait_async_copies();   // (only matters if no block was live: the speculative copy)
 
