@@ -37,6 +37,17 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 enum { MODE_2TO4 = 0, MODE_1TO2 = 1, MODE_DENSE = 2 };
 
+// Bit b of the result = some bit of nibble b of m is set (b = 0 .. 15).
+__device__ __forceinline__ uint64_t any_of_4(uint64_t m) {
+    m |= m >> 1;
+    m |= m >> 2;
+    m &= 0x1111111111111111ull;                       // bit 4 b
+    m = (m | (m >> 3)) & 0x0303030303030303ull;       // two per byte
+    m = (m | (m >> 6)) & 0x000F000F000F000Full;       // four per 16 bits
+    m = (m | (m >> 12)) & 0x000000FF000000FFull;      // eight per 32 bits
+    return (m | (m >> 24)) & 0xFFFFull;
+}
+
 // MASKED: the call carries a key bias and/or a block mask (either pointer may be null).
 // RAGGED (implies MASKED; no block mask): the lengths are not multiples of the tiles.  Q, O hold Lq rows and K, V,
 //   key_bias Lk keys (Lk a multiple of 4); the absent keys of the last block count as masked keys and the absent
@@ -184,6 +195,29 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
             // one ballot each turns the lanes' answers into the block bitmaps.  In a partial last block the loads
             // past the row's end re-read its last float4 (the absent keys are accounted for below).
             uint64_t real_lo = 0ull, real_hi = 0ull;
+            if (nblocks <= 16) {
+                // Short rows (the usual padded batch): four lanes per block, four loads each -- a quarter of the
+                // instructions, which every wave of every workgroup spends before its first block.  The ballots
+                // then hold four bits per block; any_of_4 folds them to one.
+                const int blk = l >> 2;
+                float mx = -INFINITY;
+                uint32_t bits = 0u;
+                if (blk < nblocks) {
+                    const float *bp = brow + KB * blk;
+                    const int last = Lk - 4 - KB * blk;
+#pragma unroll
+                    for (int c = 0; c < KB / 16; ++c) {
+                        const int cc = 4 * (KB / 16 * (l & 3) + c);
+                        const f32x4 b = *reinterpret_cast<const f32x4 *>(bp + (RAGGED && cc > last ? last : cc));
+                        mx = fmaxf(fmaxf(mx, b[0]), b[1]);
+                        mx = fmaxf(fmaxf(mx, b[2]), b[3]);
+                        bits |= __float_as_uint(b[0]) | __float_as_uint(b[1]);
+                        bits |= __float_as_uint(b[2]) | __float_as_uint(b[3]);
+                    }
+                }
+                real_lo = any_of_4(__ballot(__float_as_uint(mx) != 0xFF800000u));
+                bias_lo = any_of_4(__ballot((bits & 0x7FFFFFFFu) != 0u));
+            } else
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 if (64 * half >= nblocks) break;
