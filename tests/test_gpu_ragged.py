@@ -102,10 +102,11 @@ def test_ragged_attention_against_oracle(B, H, Lq, Lk, d, dtype, N, M):
 
 @pytest.mark.parametrize("dtype,N,M", [(DFSS_BF16, 2, 4), (DFSS_F32_BF16X3, 1, 2)])
 @pytest.mark.parametrize("scale", [0.125, 0.11])     # bias as initial accumulator value / added after the scaling
-def test_ragged_attention_with_key_bias(dtype, N, M, scale):
+@pytest.mark.parametrize("Lq,Lk", [(150, 332), (70, 1284)])   # 6 and 21 key blocks: both ways of scanning the bias row
+def test_ragged_attention_with_key_bias(dtype, N, M, scale, Lq, Lk):
     """A padding mask (lengths not aligned to anything) plus a finite bias on unpadded arrays whose rows
     of key_bias are Lk floats long."""
-    B, H, Lq, Lk, d = 3, 2, 150, 332, 64
+    B, H, d = 3, 2, 64
     Q, K, V, (Qn, Kn, Vn) = _inputs(B * H, Lq, Lk, d, dtype, 8200)
     lengths = synth.padding_lengths(B, Lk, 8201)
     bias = synth.key_padding_bias(lengths, Lk)
@@ -161,6 +162,26 @@ def test_ragged_length_4000(dtype, N, M):
     for h in range(B * H):
         ref = oracle.attention(Qn[h][rows], Kn[h], Vn[h], N, M, 0.125)
         assert _max_err(O[h][rows][None], ref[None], Qn[h][rows][None], Kn[h][None], 0.125, dtype, tie=0) <= 2e-2
+
+
+@pytest.mark.parametrize("dtype,N,M", [(DFSS_BF16, 2, 4), (DFSS_BF16, 1, 2), (DFSS_F32_BF16X3, 1, 2)])
+def test_ragged_random_shapes(dtype, N, M):
+    """Seeded random lengths (any Lq, Lk a multiple of 4), with and without a padding mask."""
+    rng = np.random.default_rng(8700 + N)
+    for case in range(8):
+        B, H = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+        Lq, Lk = int(rng.integers(1, 300)), 4 * int(rng.integers(1, 200))
+        d = 64 if case % 2 == 0 else 128
+        Q, K, V, (Qn, Kn, Vn) = _inputs(B * H, Lq, Lk, d, dtype, 8710 + case)
+        bias = None
+        if case % 3 == 0:
+            bias = synth.key_padding_bias(synth.padding_lengths(B, Lk, 8750 + case), Lk)
+        s = Shape(B, H, Lq, Lk, d, N, M, dtype)
+        scale = 1.0 / math.sqrt(d)
+        O = _run(dfss.dfss_attention_ragged, Q, K, V, bias, s, scale)
+        kb = None if bias is None else bias.numpy()
+        ref = oracle.attention(Qn, Kn, Vn, N, M, scale, key_bias=kb, heads_per_batch=H)
+        assert _max_err(O, ref, Qn, Kn, scale, dtype, kb, H) <= 2e-2, (case, B, H, Lq, Lk, d)
 
 
 def test_ragged_rejects_what_it_cannot_run():
