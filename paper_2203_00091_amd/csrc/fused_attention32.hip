@@ -324,8 +324,11 @@ hipError_t launch_nw(const void *Q, const void *K, const void *V, int BH, int Lq
                        (const __bf16 *)K, (const __bf16 *)V, Lq, Lk, scale, (uint16_t *)O)
     if (d == 64) {
         if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
-    } else {
+    } else if constexpr (NW == 4) {   // (two-wave workgroups are built for d = 64 only: at d = 128 they need the
+                                      // registers of a whole SIMD and are never asked for)
         if (pre) DFSS_LAUNCH(128, true); else DFSS_LAUNCH(128, false);
+    } else {
+        return hipErrorInvalidValue;
     }
 #undef DFSS_LAUNCH
     return hipGetLastError();
