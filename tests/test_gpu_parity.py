@@ -394,6 +394,7 @@ def test_stage1_key_bias_bit_exact_on_integer_inputs(B, H, Lq, Lk, d, N, M, scal
     (2, 2, 128, 256, 128, 2, 4),
     (8, 12, 384, 384, 64, 2, 4),       # the benchmark shape with a padded batch
     (2, 2, 64, 1280, 64, 2, 4),        # 20 key blocks: the bias row is scanned one block per lane
+    (8, 12, 1024, 256, 64, 2, 4),      # enough query tiles for the 32-queries-per-wave variant with a bias
 ])
 def test_attention_key_bias(B, H, Lq, Lk, d, N, M):
     """Whole path with a padding mask: fused kernel, stage kernels, both dense baselines."""
