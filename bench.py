@@ -169,11 +169,8 @@ def main():
             dfss.dense_attention_fused_bias(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"])
 
     def step_sparse_staged(i):
-        os.environ["DFSS_ATTENTION_PATH"] = "staged"
-        try:
-            step_sparse(i)
-        finally:
-            del os.environ["DFSS_ATTENTION_PATH"]
+        b = sets[i % nsets]
+        dfss.dfss_attention_staged_bias(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"], ws=b["ws"])
 
     n_vals, n_meta = dfss.dfss_vals_bytes(s), dfss.dfss_meta_bytes(s)
     meta_at = (n_vals + 255) // 256 * 256

@@ -14,7 +14,7 @@
  * Supported: bfloat16 inputs, N:M = 2:4 (the paper's bfloat16 mode, Sec. 2.3) and
  * 1:2 on the same 2-byte data; float inputs with 1:2 (the paper's 4-byte mode, see
  * "the 4-byte mode" below); d in {64, 128}; Lq a multiple of 64, Lk a multiple
- * of 128.  Selection rule: larger signed score wins, equal scores -> lower key
+ * of 128 and at most 8192 (the *_ragged calls take any Lq and any Lk % 4 == 0).  Selection rule: larger signed score wins, equal scores -> lower key
  * index wins; comparisons are made on the fp32 value scale*dot, which is then
  * rounded to bfloat16 (nearest-even) for storage (kept as it is in the 4-byte mode).
  *
@@ -67,7 +67,7 @@ size_t dfss_vals_bytes(const dfss_shape *s);
  * the dense matrix in bits; App. A.1.2: code k of a word at bits [4k,4k+3]).  The words
  * are held in the library's own order (see dfss_meta_to_canonical). */
 size_t dfss_meta_bytes(const dfss_shape *s);
-/* Workspace of dfss_attention: room for vals, meta and per-row statistics. */
+/* Workspace of dfss_attention_staged (and of dfss_attention with DFSS_F32): vals, then meta. */
 size_t dfss_workspace_bytes(const dfss_shape *s);
 /* Workspace of dense_attention: the dense bfloat16 score/weight matrix [B*H, Lq, Lk]. */
 size_t dense_workspace_bytes(const dfss_shape *s);
@@ -89,14 +89,26 @@ dfss_status dfss_spmm(const void *vals, const void *meta, const void *V, const d
                       void *O, void *stream);
 
 /* ---- whole forward pass (Eq. 1 with the pruned score matrix) ---------------------- */
-/* ws: device scratch of at least dfss_workspace_bytes(), 256-byte aligned; contents
- * undefined afterwards.  Computes the same function as stage 1 -> 2 -> 3.  By default all
- * three stages run in ONE kernel that keeps the pruned scores in registers (the pruning
- * epilogue of Sec. 3.4 taken to its end: nothing of the score matrix is written); with the
- * environment variable DFSS_ATTENTION_PATH=staged the three stage kernels are run through
- * the workspace instead. */
+/* Computes the same function as stage 1 -> 2 -> 3 in ONE kernel that keeps the pruned scores in
+ * registers (the pruning epilogue of Sec. 3.4 taken to its end: nothing of the score matrix is
+ * written).  ws / ws_bytes: used only with dtype DFSS_F32, which has no one-kernel path and runs the
+ * three stage kernels through ws (then at least dfss_workspace_bytes(), 256-byte aligned); with every
+ * other dtype they are ignored and ws may be NULL.  Which kernel runs depends on the arguments only
+ * (no environment variables, no global state). */
 dfss_status dfss_attention(const void *Q, const void *K, const void *V, const dfss_shape *s,
                            float scale, void *O, void *ws, size_t ws_bytes, void *stream);
+
+/* The same function as the three stage kernels run one after the other (the structure whose latency
+ * the paper reports, Sec. 5.2): stage 1 writes the kept scores and the metadata into ws, stage 2 turns
+ * them into weights in place, stage 3 multiplies by V.  ws: device scratch of at least
+ * dfss_workspace_bytes(), 256-byte aligned; afterwards it holds the weights (at offset 0) and the
+ * metadata (at offset dfss_vals_bytes() rounded up to 256) of this forward pass, which is what
+ * dfss_attention_backward needs.  key_bias (may be NULL) as described below. */
+dfss_status dfss_attention_staged(const void *Q, const void *K, const void *V, const dfss_shape *s,
+                                  float scale, void *O, void *ws, size_t ws_bytes, void *stream);
+dfss_status dfss_attention_staged_bias(const void *Q, const void *K, const void *V, const void *key_bias,
+                                       const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes,
+                                       void *stream);
 
 /* ---- full attention on the same GPU (Eq. 1), the denominator of every speedup ---- */
 /* Same three-stage structure with the dense score matrix stored in bfloat16 in ws
@@ -223,7 +235,7 @@ dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K
  * fp32 kernel.  Several times faster than DFSS_F32, whose matrix instruction is 16x slower.
  * With this dtype dfss_attention runs as ONE kernel that keeps the pruned scores and the weights in
  * registers (same function as the three stages, softmax kept up to date block by block;
- * DFSS_ATTENTION_PATH=staged selects the stage kernels), and dense_attention_fused is available as
+ * dfss_attention_staged runs the stage kernels), and dense_attention_fused is available as
  * the matching full-attention kernel. */
 
 /* ---- metadata order ---------------------------------------------------------------- */
@@ -235,8 +247,8 @@ dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K
  *   lib32[bh][r/16][v/4][r%16][slot(v%4)] = canon32[bh][r][v],  slot(c) = 2*(c%2) + c/2,
  * i.e. the four words of a row for one 128-key block are adjacent (chunk order 0, 2, 1, 3).
  * Both calls take device pointers; `meta` and `canon` must not overlap. */
-dfss_status dfss_meta_to_canonical(const void *meta, const dfss_shape *s, void *canon, void *stream);
-dfss_status dfss_meta_from_canonical(const void *canon, const dfss_shape *s, void *meta, void *stream);
+dfss_status dfss_meta_to_canonical(const void *meta, const dfss_shape *s, uint16_t *canon, void *stream);
+dfss_status dfss_meta_from_canonical(const uint16_t *canon, const dfss_shape *s, void *meta, void *stream);
 
 const char *dfss_status_string(dfss_status st);
 

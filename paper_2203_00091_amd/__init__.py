@@ -22,6 +22,8 @@ from .binding import (  # noqa: F401
     dfss_attention_bias,
     dfss_attention_blocked,
     dfss_attention_ragged,
+    dfss_attention_staged,
+    dfss_attention_staged_bias,
     dfss_backward_workspace_bytes,
     dfss_meta_bytes,
     dfss_meta_from_canonical,

@@ -14,8 +14,7 @@ from dataclasses import dataclass
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# DFSS_LIBRARY_PATH points the binding at another build of the same library (kernel experiments)
-_LIB_PATH = os.environ.get("DFSS_LIBRARY_PATH") or os.path.join(_HERE, "libdfss.so")
+_LIB_PATH = os.path.join(_HERE, "libdfss.so")
 
 EXPORTS = (
     "dfss_vals_bytes", "dfss_meta_bytes", "dfss_workspace_bytes", "dense_workspace_bytes",
@@ -25,7 +24,11 @@ EXPORTS = (
     "dfss_attention_blocked", "dense_attention_fused_blocked", "dfss_spmm_t",
     "dfss_backward_workspace_bytes", "dfss_attention_backward",
     "dfss_attention_ragged", "dense_attention_fused_ragged",
+    "dfss_attention_staged", "dfss_attention_staged_bias",
 )
+# exported for the library's own tests only (csrc/dfss_internal.h)
+INTERNAL_EXPORTS = ("dfss_internal_attention_variant",)
+VARIANT_AUTO, VARIANT_Q16, VARIANT_Q16X2, VARIANT_Q32W2, VARIANT_Q32W4 = range(5)
 
 
 DFSS_BF16, DFSS_F32, DFSS_F32_BF16X3 = 0, 1, 2
@@ -108,6 +111,9 @@ def load_library():
         L.dfss_attention_blocked.argtypes = [vp, vp, vp, vp, vp, sp, f32, vp, vp]
         L.dense_attention_fused_blocked.argtypes = [vp, vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_attention_ragged.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
+        L.dfss_attention_staged.argtypes = [vp, vp, vp, sp, f32, vp, vp, sz, vp]
+        L.dfss_attention_staged_bias.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
+        L.dfss_internal_attention_variant.argtypes = [vp, vp, vp, vp, sp, f32, vp, ctypes.c_int, ctypes.c_int, vp]
         L.dense_attention_fused_ragged.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_spmm_t.argtypes = [vp, vp, vp, sp, vp, vp]
         L.dfss_attention_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, sp, f32, vp, vp, vp, vp, sz, vp]
@@ -118,7 +124,8 @@ def load_library():
                      "dfss_sddmm_prune_bias", "dfss_attention_bias", "dense_attention_bias",
                      "dense_attention_fused_bias", "dfss_attention_blocked", "dense_attention_fused_blocked",
                      "dfss_attention_ragged", "dense_attention_fused_ragged", "dfss_spmm_t",
-                     "dfss_attention_backward"):
+                     "dfss_attention_backward", "dfss_attention_staged", "dfss_attention_staged_bias",
+                     "dfss_internal_attention_variant"):
             getattr(L, name).restype = ctypes.c_int
         L.dfss_status_string.argtypes = [ctypes.c_int]
         L.dfss_status_string.restype = ctypes.c_char_p
@@ -224,16 +231,59 @@ def dfss_spmm(vals, meta, V, s: Shape, O=None):
     return O
 
 
+def _needs_workspace(s: Shape) -> bool:
+    """Only the exact-product float mode runs dfss_attention through a workspace."""
+    return s.dtype == DFSS_F32
+
+
 def dfss_attention(Q, K, V, s: Shape, scale: float, O=None, ws=None):
-    """Whole DFSS forward.  ``ws`` (uint8 device tensor) is allocated if not given."""
+    """Whole DFSS forward in one kernel.  ``ws`` is passed on if given (the library uses it with DFSS_F32 only,
+    where it is allocated here if absent)."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    if ws is None and _needs_workspace(s):
+        ws = _alloc_bytes(dfss_workspace_bytes(s), Q.device)
+    st = load_library().dfss_attention(_q(Q, s), _kv(K, s), _kv(V, s),
+                                       ctypes.byref(s.c()), scale, _q(O, s), _ptr(ws),
+                                       0 if ws is None else ws.numel() * ws.element_size(), _stream())
+    _check("dfss_attention", st)
+    return O
+
+
+def dfss_attention_staged(Q, K, V, s: Shape, scale: float, O=None, ws=None):
+    """Whole DFSS forward as the three stage kernels through ``ws`` (allocated if not given)."""
     if O is None:
         O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
     if ws is None:
         ws = _alloc_bytes(dfss_workspace_bytes(s), Q.device)
-    st = load_library().dfss_attention(_q(Q, s), _kv(K, s), _kv(V, s),
-                                       ctypes.byref(s.c()), scale, _q(O, s), _ptr(ws),
-                                       ws.numel() * ws.element_size(), _stream())
-    _check("dfss_attention", st)
+    st = load_library().dfss_attention_staged(_q(Q, s), _kv(K, s), _kv(V, s),
+                                              ctypes.byref(s.c()), scale, _q(O, s), _ptr(ws),
+                                              ws.numel() * ws.element_size(), _stream())
+    _check("dfss_attention_staged", st)
+    return O
+
+
+def dfss_attention_staged_bias(Q, K, V, key_bias, s: Shape, scale: float, O=None, ws=None):
+    """dfss_attention_staged with an additive key bias (may be None)."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    if ws is None:
+        ws = _alloc_bytes(dfss_workspace_bytes(s), Q.device)
+    st = load_library().dfss_attention_staged_bias(_q(Q, s), _kv(K, s), _kv(V, s), _bias_ptr(key_bias, s),
+                                                   ctypes.byref(s.c()), scale, _q(O, s), _ptr(ws),
+                                                   ws.numel() * ws.element_size(), _stream())
+    _check("dfss_attention_staged_bias", st)
+    return O
+
+
+def internal_attention_variant(Q, K, V, key_bias, s: Shape, scale: float, variant: int, dense: bool = False, O=None):
+    """Test hook: the one-kernel forward pass (DFSS, or full attention if ``dense``) with a named tiling."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    st = load_library().dfss_internal_attention_variant(_q(Q, s), _kv(K, s), _kv(V, s), _bias_ptr(key_bias, s),
+                                                        ctypes.byref(s.c()), scale, _q(O, s), int(variant),
+                                                        int(bool(dense)), _stream())
+    _check("dfss_internal_attention_variant", st)
     return O
 
 
@@ -282,14 +332,14 @@ def dfss_sddmm_prune_bias(Q, K, key_bias, s: Shape, scale: float, vals=None, met
 
 
 def dfss_attention_bias(Q, K, V, key_bias, s: Shape, scale: float, O=None, ws=None):
-    """Whole DFSS forward with an additive key bias."""
+    """Whole DFSS forward (one kernel) with an additive key bias."""
     if O is None:
         O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
-    if ws is None:
+    if ws is None and _needs_workspace(s):
         ws = _alloc_bytes(dfss_workspace_bytes(s), Q.device)
     st = load_library().dfss_attention_bias(_q(Q, s), _kv(K, s), _kv(V, s),
                                             _bias_ptr(key_bias, s), ctypes.byref(s.c()), scale, _q(O, s), _ptr(ws),
-                                            ws.numel() * ws.element_size(), _stream())
+                                            0 if ws is None else ws.numel() * ws.element_size(), _stream())
     _check("dfss_attention_bias", st)
     return O
 

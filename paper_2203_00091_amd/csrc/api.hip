@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include "../../include/dfss.h"
+#include "dfss_internal.h"
 #include "dfss_kernels.hpp"
 
 namespace {
@@ -69,11 +70,6 @@ inline bool bad_scale(float x) {
     memcpy(&u, &x, sizeof(u));
     const bool negative = (u >> 31) != 0, zero = (u & 0x7FFFFFFFu) == 0, inf_or_nan = (u & 0x7F800000u) == 0x7F800000u;
     return negative || zero || inf_or_nan;
-}
-// DFSS_ATTENTION_PATH=staged makes dfss_attention run the three stage kernels through the workspace.
-inline bool staged_path_requested() {
-    const char *v = getenv("DFSS_ATTENTION_PATH");
-    return v && strcmp(v, "staged") == 0;
 }
 inline dfss_status hip_status(hipError_t e) { return e == hipSuccess ? DFSS_OK : DFSS_ERR_HIP; }
 
@@ -157,43 +153,82 @@ dfss_status dfss_spmm(const void *vals, const void *meta, const void *V, const d
     return hip_status(dfss::launch_spmm(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, (hipStream_t)stream));
 }
 
-dfss_status dfss_attention_bias(const void *Q, const void *K, const void *V, const void *key_bias,
-                                const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes, void *stream) {
+// The whole forward pass.  staged: the three stage kernels through the workspace; otherwise one kernel
+// (the exact-product float mode has no one-kernel path and always takes the stages).
+static dfss_status attention_forward(const void *Q, const void *K, const void *V, const void *key_bias,
+                                     const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes, void *stream,
+                                     bool staged, int variant) {
     Dims D;
-    if (!Q || !K || !V || !O || !ws) return DFSS_ERR_NULL;
+    if (!Q || !K || !V || !O) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, true, &D)) return st;
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias))
         return DFSS_ERR_SHAPE;
-    if ((reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0) return DFSS_ERR_SHAPE;
-    if (ws_bytes < dfss_workspace_bytes(s)) return DFSS_ERR_WORKSPACE;
+    if (D.f32 && !D.split) {
+        if (key_bias) return DFSS_ERR_UNSUPPORTED;
+        staged = true;
+    }
     hipStream_t st = (hipStream_t)stream;
     const float *bias = (const float *)key_bias;
-    if (D.f32) {
-        if (key_bias && !D.split) return DFSS_ERR_UNSUPPORTED;
-        if (D.split && !staged_path_requested())
+    if (!staged) {   // the workspace is not touched (and may be NULL)
+        if (D.f32)
             return hip_status(dfss::launch_fused_attention_split(Q, K, V, bias, D.H, nullptr, D.BH, D.Lq, D.Lk, D.d, true,
                                                                  scale, O, st));
-        char *vals = static_cast<char *>(ws);
-        char *meta = vals + align_up(dfss_vals_bytes(s));
+        return hip_status(dfss::launch_fused_attention(Q, K, V, bias, D.H, nullptr, D.BH, D.Lq, D.Lk, D.d, D.mode, scale,
+                                                       O, variant, st));
+    }
+    if (!ws) return DFSS_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0) return DFSS_ERR_SHAPE;
+    if (ws_bytes < dfss_workspace_bytes(s)) return DFSS_ERR_WORKSPACE;
+    char *vals = static_cast<char *>(ws);
+    char *meta = vals + align_up(dfss_vals_bytes(s));
+    if (D.f32) {
         hipError_t e = sddmm_prune_f32(D, Q, K, bias, scale, vals, meta, st);
         if (e == hipSuccess) e = dfss::launch_row_softmax_f32(vals, (long)D.BH * D.Lq, D.Lk / 2, st);
         if (e == hipSuccess) e = spmm_f32(D, vals, meta, V, O, st);
         return hip_status(e);
     }
-    if (!staged_path_requested())
-        return hip_status(dfss::launch_fused_attention(Q, K, V, bias, D.H, nullptr, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, O, st));
-    char *vals = static_cast<char *>(ws);
-    char *meta = vals + align_up(dfss_vals_bytes(s));
     hipError_t e = dfss::launch_sddmm_prune(Q, K, bias, D.H, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, vals, meta, st);
     if (e == hipSuccess) e = dfss::launch_row_softmax(vals, (long)D.BH * D.Lq, D.Lk / 2, st);
     if (e == hipSuccess) e = dfss::launch_spmm(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, st);
     return hip_status(e);
 }
 
+dfss_status dfss_attention_bias(const void *Q, const void *K, const void *V, const void *key_bias,
+                                const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes, void *stream) {
+    return attention_forward(Q, K, V, key_bias, s, scale, O, ws, ws_bytes, stream, false, 0);
+}
+
 dfss_status dfss_attention(const void *Q, const void *K, const void *V, const dfss_shape *s, float scale, void *O,
                            void *ws, size_t ws_bytes, void *stream) {
-    return dfss_attention_bias(Q, K, V, nullptr, s, scale, O, ws, ws_bytes, stream);
+    return attention_forward(Q, K, V, nullptr, s, scale, O, ws, ws_bytes, stream, false, 0);
+}
+
+dfss_status dfss_attention_staged_bias(const void *Q, const void *K, const void *V, const void *key_bias,
+                                       const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes,
+                                       void *stream) {
+    return attention_forward(Q, K, V, key_bias, s, scale, O, ws, ws_bytes, stream, true, 0);
+}
+
+dfss_status dfss_attention_staged(const void *Q, const void *K, const void *V, const dfss_shape *s, float scale,
+                                  void *O, void *ws, size_t ws_bytes, void *stream) {
+    return attention_forward(Q, K, V, nullptr, s, scale, O, ws, ws_bytes, stream, true, 0);
+}
+
+// Test hook (csrc/dfss_internal.h): the one-kernel path with the tiling named by the caller.
+dfss_status dfss_internal_attention_variant(const void *Q, const void *K, const void *V, const void *key_bias,
+                                            const dfss_shape *s, float scale, void *O, int variant, int dense,
+                                            void *stream) {
+    if (variant < 0 || variant > DFSS_VARIANT_LAST) return DFSS_ERR_UNSUPPORTED;
+    if (!dense) return attention_forward(Q, K, V, key_bias, s, scale, O, nullptr, 0, stream, false, variant);
+    Dims D;
+    if (!Q || !K || !V || !O) return DFSS_ERR_NULL;
+    if (dfss_status st = check_shape(s, false, &D)) return st;
+    if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias)) return DFSS_ERR_SHAPE;
+    if (D.f32) return DFSS_ERR_UNSUPPORTED;
+    return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, nullptr, D.BH, D.Lq, D.Lk,
+                                                   D.d, 2, scale, O, variant, (hipStream_t)stream));
 }
 
 dfss_status dense_attention_fused_bias(const void *Q, const void *K, const void *V, const void *key_bias,
@@ -210,7 +245,7 @@ dfss_status dense_attention_fused_bias(const void *Q, const void *K, const void 
                                                              D.Lk, D.d, false, scale, O, (hipStream_t)stream));
     }
     return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, nullptr, D.BH, D.Lq, D.Lk,
-                                                   D.d, 2, scale, O, (hipStream_t)stream));
+                                                   D.d, 2, scale, O, 0, (hipStream_t)stream));
 }
 
 dfss_status dense_attention_fused(const void *Q, const void *K, const void *V, const dfss_shape *s, float scale,
@@ -268,7 +303,7 @@ static dfss_status attention_blocked(const void *Q, const void *K, const void *V
                                                              scale, O, (hipStream_t)stream));
     }
     return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, (const uint8_t *)block_mask,
-                                                   D.BH, D.Lq, D.Lk, D.d, dense ? 2 : D.mode, scale, O,
+                                                   D.BH, D.Lq, D.Lk, D.d, dense ? 2 : D.mode, scale, O, 0,
                                                    (hipStream_t)stream));
 }
 
@@ -296,7 +331,7 @@ static dfss_status attention_ragged(const void *Q, const void *K, const void *V,
         return hip_status(dfss::launch_fused_attention_split(Q, K, V, (const float *)key_bias, D.H, nullptr, D.BH, D.Lq,
                                                              D.Lk, D.d, !dense, scale, O, (hipStream_t)stream));
     return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, nullptr, D.BH, D.Lq, D.Lk,
-                                                   D.d, dense ? 2 : D.mode, scale, O, (hipStream_t)stream));
+                                                   D.d, dense ? 2 : D.mode, scale, O, 0, (hipStream_t)stream));
 }
 
 dfss_status dfss_attention_ragged(const void *Q, const void *K, const void *V, const void *key_bias,
@@ -357,7 +392,7 @@ size_t dfss_backward_workspace_bytes(const dfss_shape *s) {
     return v ? align_up(v) : 0;
 }
 
-dfss_status dfss_meta_to_canonical(const void *meta, const dfss_shape *s, void *canon, void *stream) {
+dfss_status dfss_meta_to_canonical(const void *meta, const dfss_shape *s, uint16_t *canon, void *stream) {
     Dims D;
     if (!meta || !canon) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, true, &D)) return st;
@@ -366,7 +401,7 @@ dfss_status dfss_meta_to_canonical(const void *meta, const dfss_shape *s, void *
                                                 (hipStream_t)stream));
 }
 
-dfss_status dfss_meta_from_canonical(const void *canon, const dfss_shape *s, void *meta, void *stream) {
+dfss_status dfss_meta_from_canonical(const uint16_t *canon, const dfss_shape *s, void *meta, void *stream) {
     Dims D;
     if (!meta || !canon) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, true, &D)) return st;

@@ -24,9 +24,10 @@ hipError_t launch_dense_av(const void *P, const void *V, int BH, int Lq, int Lk,
                            hipStream_t st);
 // Whole forward pass in one kernel.  mode: 0 = 2:4, 1 = 1:2, 2 = dense (full attention, Eq. 1).
 // block_mask: uint8 [Lq/64][Lk/64] shared by all heads (zero = block not part of the attention), or nullptr.
+// variant: a DFSS_VARIANT_* tiling (dfss_internal.h), 0 = chosen from the shape.
 hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, const float *key_bias, int H,
                                   const uint8_t *block_mask, int BH, int Lq, int Lk, int d, int mode, float scale,
-                                  void *O, hipStream_t st);
+                                  void *O, int variant, hipStream_t st);
 // Transposed sparse product out[BH, Lk, d] = A^T X for compressed A (vals + metadata) and X bf16 [BH, Lq, d]:
 // dV = P^T dO and dK = dS^T Q of the backward pass.
 hipError_t launch_spmm_t(const void *vals, const void *meta, const void *X, int BH, int Lq, int Lk, int d, void *out,

@@ -852,19 +852,11 @@ hipError_t launch_scores_nq(const void *Q, const void *K, const float *key_bias,
     return hipGetLastError();
 }
 
-// which tiling: DFSS_SPLIT_TILE = "<waves>x<query groups per wave>" overrides the choice (for measurements)
-inline void split_tile_override(int &nw, int &nq) {
-    if (const char *f = getenv("DFSS_SPLIT_TILE")) {
-        if ((f[0] == '4' || f[0] == '8') && f[1] == 'x' && (f[2] == '1' || f[2] == '2')) nw = f[0] - '0', nq = f[2] - '0';
-    }
-}
-
 template <bool PRUNE>
 hipError_t launch_scores(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk, int d,
                          float scale, void *out, void *meta, hipStream_t st) {
     // 128 queries per workgroup (4 waves x 32 queries) where Lq allows and the grid still fills the chip
     int nw = 4, nq = (Lq % 128 == 0 && (long)BH * (Lq / 128) >= 512) ? 2 : 1;
-    split_tile_override(nw, nq);
     if (Lq % (16 * nw * nq) != 0) nw = 4, nq = 1;
 #define DFSS_LAUNCH_SCORES(DD)                                                                                   \
     do {                                                                                                         \
@@ -893,7 +885,6 @@ hipError_t launch_av(const void *A, const void *meta, const void *V, int BH, int
                      hipStream_t st) {
     // 8 waves per workgroup where the 128-query tile divides Lq and the grid still fills the chip
     int nw = (Lq % 128 == 0 && (long)BH * (Lq / 128) >= 512) ? 8 : 4, nq = 1;
-    split_tile_override(nw, nq);
     if (Lq % (16 * nw) != 0) nw = 4;
     if (d == 64)
         return nw == 8 ? launch_av_nw<64, SPARSE, 8>(A, meta, V, BH, Lq, Lk, O, st)

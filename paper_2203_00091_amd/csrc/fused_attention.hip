@@ -24,6 +24,7 @@
 
 #include <type_traits>
 #include "dfss_device.hpp"
+#include "dfss_internal.h"
 #include "dfss_kernels.hpp"
 
 namespace dfss {
@@ -520,10 +521,12 @@ hipError_t launch_nq(const void *Q, const void *K, const void *V, const float *k
 
 template <int MODE>
 hipError_t launch(const void *Q, const void *K, const void *V, const float *key_bias, int H,
-                  const uint8_t *block_mask, int BH, int Lq, int Lk, int d, float scale, void *O, hipStream_t st) {
+                  const uint8_t *block_mask, int BH, int Lq, int Lk, int d, float scale, void *O, int variant,
+                  hipStream_t st) {
     // 32 queries per wave when that still leaves at least ~2 workgroups per compute unit
     bool two = Lq % 128 == 0 && (long)BH * (Lq / 128) >= 768;   // at least 3 workgroups per compute unit
-    if (const char *f = getenv("DFSS_FUSED_NQ")) two = Lq % 128 == 0 && f[0] == '2';   // for measurements
+    if (variant == DFSS_VARIANT_Q16) two = false;
+    if (variant == DFSS_VARIANT_Q16X2) two = Lq % 128 == 0;
     if (block_mask) two = false;   // the block of the mask is the 64-query workgroup tile
     if (Lq % 64 != 0 || Lk % 64 != 0) {   // (never together with a block mask)
         if ((long)BH * ((Lq + 127) / 128) >= 768)
@@ -545,21 +548,17 @@ hipError_t launch_fused_attention32(const void *Q, const void *K, const void *V,
 
 hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, const float *key_bias, int H,
                                   const uint8_t *block_mask, int BH, int Lq, int Lk, int d, int mode, float scale,
-                                  void *O, hipStream_t st) {
+                                  void *O, int variant, hipStream_t st) {
     // The 16-query kernel is the default.  The 32-query kernel (score MFMA at twice the rate, software
-    // pipelined) only pays off once its larger tiles still fill the chip evenly; it is selected with
-    // DFSS_FUSED_TILE = 32x2 | 32x4 (for measurements), 16 forces the default.
+    // pipelined) runs only when the caller names it.
     int tile = 16, nw = 4;
-    if (const char *f = getenv("DFSS_FUSED_TILE")) {
-        if (f[0] == '1') tile = 16;
-        else if (f[0] == '3' && f[1] == '2' && f[2] == 'x' && f[3] == '2' && d == 64) tile = 32, nw = 2;
-        else if (f[0] == '3' && f[1] == '2' && f[2] == 'x' && f[3] == '4' && Lq % 128 == 0) tile = 32, nw = 4;
-    }
+    if (variant == DFSS_VARIANT_Q32W2 && d == 64) tile = 32, nw = 2;
+    if (variant == DFSS_VARIANT_Q32W4 && Lq % 128 == 0) tile = 32, nw = 4;
     if (tile == 32 && !key_bias && !block_mask && Lq % 64 == 0 && Lk % 64 == 0)
         return launch_fused_attention32(Q, K, V, BH, Lq, Lk, d, mode, nw, scale, O, st);
-    if (mode == 0) return launch<MODE_2TO4>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, st);
-    if (mode == 1) return launch<MODE_1TO2>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, st);
-    return launch<MODE_DENSE>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, st);
+    if (mode == 0) return launch<MODE_2TO4>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, variant, st);
+    if (mode == 1) return launch<MODE_1TO2>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, variant, st);
+    return launch<MODE_DENSE>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, variant, st);
 }
 
 }  // namespace dfss

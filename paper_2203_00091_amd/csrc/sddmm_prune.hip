@@ -469,12 +469,8 @@ hipError_t launch32(const void *Q, const void *K, const float *key_bias, int H, 
 template <int MODE, bool BIAS>
 hipError_t launch_b(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk, int d,
                     float scale, void *out, void *meta, hipStream_t st) {
-    // 32 queries per wave (32x32x16 MFMA) when the query count allows it, else 16 (16x16x32 MFMA);
-    // DFSS_SDDMM_TILE=16 forces the 16-query kernels (for measurements)
-    const char *force = getenv("DFSS_SDDMM_TILE");
-    const bool t16 = force && force[0] == '1';
-    if (Lq % 128 == 0 && !t16) return launch32<MODE, BIAS>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
-    if (Lq % 128 == 0) return launch_nq<MODE, 2, BIAS>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
+    // 32 queries per wave (32x32x16 MFMA) when the query count allows it, else 16 (16x16x32 MFMA)
+    if (Lq % 128 == 0) return launch32<MODE, BIAS>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
     return launch_nq<MODE, 1, BIAS>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
 }
 

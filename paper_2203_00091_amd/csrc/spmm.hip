@@ -180,7 +180,6 @@ hipError_t launch(const void *P, const void *meta, const void *V, int BH, int Lq
     // two row blocks per wave when that still leaves two workgroups per compute unit (measured:
     // from there on the larger tile wins, below it the finer grid does)
     bool rb2 = (Lq % 128 == 0) && ((long)BH * (Lq / 128) >= 512);
-    if (const char *f = getenv("DFSS_SPMM_RB")) rb2 = (Lq % 128 == 0) && f[0] == '2';   // for measurements
     const unsigned grid = (unsigned)((long)BH * (Lq / (rb2 ? 128 : 64)));
 #define DFSS_LAUNCH(DD, RR)                                                                                   \
     hipLaunchKernelGGL((k_av<DD, SPARSE, RR>), dim3(grid), dim3(NT), 0, st, (const uint32_t *)P,              \

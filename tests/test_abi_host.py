@@ -27,6 +27,8 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/dfss.h but not exported"
     assert set(names) == set(binding.EXPORTS)
+    for n in binding.INTERNAL_EXPORTS:      # test hooks, declared in csrc/dfss_internal.h
+        assert hasattr(lib, n), n
 
 
 def test_sizes_follow_the_compressed_footprint():
@@ -92,12 +94,18 @@ def test_errors_are_reported_before_any_launch():
     assert lib.dfss_sparse_softmax(None, ctypes.byref(ok), None) == E_NULL
     assert lib.dfss_spmm(aligned, aligned, aligned, ctypes.byref(ok), None, None) == E_NULL
     ws = ctypes.c_void_p((p.value + 255) // 256 * 256)
-    assert lib.dfss_attention(aligned, aligned, aligned, ctypes.byref(ok), 0.125, aligned, ws, 16, None) == E_WS
+    assert lib.dfss_attention_staged(aligned, aligned, aligned, ctypes.byref(ok), 0.125, aligned, ws, 16, None) == E_WS
+    assert lib.dfss_attention_staged(aligned, aligned, aligned, ctypes.byref(ok), 0.125, aligned, None, 1 << 30, None) == E_NULL
+    assert lib.dfss_attention_staged(aligned, aligned, aligned, ctypes.byref(ok), 0.125, aligned,
+                                     ctypes.c_void_p(ws.value + 16), 1 << 30, None) == E_SHAPE   # workspace not 256-byte aligned
+    assert lib.dfss_attention(None, aligned, aligned, ctypes.byref(ok), 0.125, aligned, None, 0, None) == E_NULL
+    assert lib.dfss_attention(aligned, aligned, aligned, ctypes.byref(ok), -0.125, aligned, None, 0, None) == E_UNSUP
     assert lib.dense_attention(aligned, aligned, aligned, ctypes.byref(ok), 0.125, aligned, ws, 16, None) == E_WS
     # the key-bias entry points validate the same way, and reject a misaligned bias pointer
     assert lib.dfss_sddmm_prune_bias(None, aligned, aligned, ctypes.byref(ok), 0.125, aligned, aligned, None) == E_NULL
     assert lib.dfss_sddmm_prune_bias(aligned, aligned, odd, ctypes.byref(ok), 0.125, aligned, aligned, None) == E_SHAPE
-    assert lib.dfss_attention_bias(aligned, aligned, aligned, aligned, ctypes.byref(ok), 0.125, aligned, ws, 16, None) == E_WS
+    assert lib.dfss_attention_staged_bias(aligned, aligned, aligned, aligned, ctypes.byref(ok), 0.125, aligned, ws, 16, None) == E_WS
+    assert lib.dfss_attention_bias(aligned, aligned, aligned, odd, ctypes.byref(ok), 0.125, aligned, None, 0, None) == E_SHAPE
     assert lib.dense_attention_bias(aligned, aligned, aligned, aligned, ctypes.byref(ok), 0.125, aligned, ws, 16, None) == E_WS
     assert lib.dense_attention_fused_bias(aligned, aligned, aligned, odd, ctypes.byref(ok), 0.125, aligned, None) == E_SHAPE
     assert lib.dense_attention_fused_bias(aligned, aligned, aligned, aligned, ctypes.byref(ok), -1.0, aligned, None) == E_UNSUP

@@ -158,14 +158,13 @@ def test_stages_on_gaussian_inputs(name, dtype):
 @pytest.mark.parametrize("BH,Lq,Lk,d", [(2, 128, 256, 64), (2, 64, 384, 128), (1, 192, 128, 64)])
 @DTYPES
 @pytest.mark.parametrize("path", ["default", "staged"])
-def test_attention_and_dense_baseline(BH, Lq, Lk, d, dtype, path, monkeypatch):
+def test_attention_and_dense_baseline(BH, Lq, Lk, d, dtype, path):
     """default: one kernel where the library has one (bf16x3 products), else the three stages."""
-    if path == "staged":
-        monkeypatch.setenv("DFSS_ATTENTION_PATH", "staged")
     Q, K, V = synth.gaussian_qkv(BH, Lq, Lk, d, 1.0, seed=6300 + Lq + d, dtype=torch.float32)
     scale = 1 / math.sqrt(d)
     s = _shape(1, BH, Lq, Lk, d, dtype)
-    O = dfss.dfss_attention(_dev(Q), _dev(K), _dev(V), s, scale)
+    attention = dfss.dfss_attention_staged if path == "staged" else dfss.dfss_attention
+    O = attention(_dev(Q), _dev(K), _dev(V), s, scale)
     if path == "default" and dtype == DFSS_F32_BF16X3:
         Od = dfss.dense_attention_fused(_dev(Q), _dev(K), _dev(V), s, scale)
     else:
@@ -188,19 +187,17 @@ def test_attention_and_dense_baseline(BH, Lq, Lk, d, dtype, path, monkeypatch):
 
 
 @DTYPES
-def test_stage_calls_compose_to_attention(dtype, monkeypatch):
+def test_stage_calls_compose_to_attention(dtype):
     w = synth.WORKLOADS["tiny_1to2_f32"]
     Q, K, V = (_dev(t) for t in synth.make(w))
     s = _shape(w.B, w.H, w.L, w.L, w.d, dtype)
     vals, meta = dfss.dfss_sddmm_prune(Q, K, s, w.scale)
     O1 = dfss.dfss_spmm(dfss.dfss_sparse_softmax(vals, s), meta, V, s)
-    monkeypatch.setenv("DFSS_ATTENTION_PATH", "staged")
-    O2 = dfss.dfss_attention(Q, K, V, s, w.scale)
+    O2 = dfss.dfss_attention_staged(Q, K, V, s, w.scale)
     torch.cuda.synchronize()
     assert torch.equal(O1, O2)
     if dtype == DFSS_F32_BF16X3:
         # the one-kernel path computes the same function with the softmax in another order
-        monkeypatch.delenv("DFSS_ATTENTION_PATH")
         O3 = dfss.dfss_attention(Q, K, V, s, w.scale)
         torch.cuda.synchronize()
         assert (O3 - O1).abs().max().item() <= 2e-5
@@ -368,7 +365,7 @@ def test_stage1_key_bias_bit_exact_on_integer_inputs(B, H, Lq, Lk, d):
 
 
 @pytest.mark.parametrize("B,H,Lq,Lk,d", [(2, 2, 128, 256, 64), (2, 2, 64, 384, 128)])
-def test_attention_key_bias(B, H, Lq, Lk, d, monkeypatch):
+def test_attention_key_bias(B, H, Lq, Lk, d):
     """Whole path with a padding mask: one kernel, stage kernels, both full-attention baselines."""
     Q, K, V, lengths, bias = _padding_case(B, H, Lq, Lk, d, 6900 + Lq + d, integer=False)
     s = _shape(B, H, Lq, Lk, d, DFSS_F32_BF16X3)
@@ -379,8 +376,7 @@ def test_attention_key_bias(B, H, Lq, Lk, d, monkeypatch):
     Od = dfss.dense_attention_bias(Qd, Kd, Vd, bd, s, scale)
     O0 = dfss.dfss_attention_bias(Qd, Kd, Vd, None, s, scale)          # NULL bias = the plain call
     O1 = dfss.dfss_attention(Qd, Kd, Vd, s, scale)
-    monkeypatch.setenv("DFSS_ATTENTION_PATH", "staged")
-    Os = dfss.dfss_attention_bias(Qd, Kd, Vd, bd, s, scale)
+    Os = dfss.dfss_attention_staged_bias(Qd, Kd, Vd, bd, s, scale)
     torch.cuda.synchronize()
     assert torch.equal(O0, O1)
     Qn, Kn, Vn = Q.numpy(), K.numpy(), V.numpy()

@@ -15,7 +15,7 @@ import torch
 
 import oracle
 import paper_2203_00091_amd as dfss
-from paper_2203_00091_amd import Shape, synth
+from paper_2203_00091_amd import Shape, binding, synth
 
 pytestmark = pytest.mark.gpu
 
@@ -213,12 +213,8 @@ def test_meta_order_round_trip():
 # whole path
 # ----------------------------------------------------------------------------------
 def _staged_attention(Qd, Kd, Vd, s, scale):
-    """dfss_attention through the three stage kernels (environment switch of the library)."""
-    os.environ["DFSS_ATTENTION_PATH"] = "staged"
-    try:
-        return dfss.dfss_attention(Qd, Kd, Vd, s, scale)
-    finally:
-        del os.environ["DFSS_ATTENTION_PATH"]
+    """The three stage kernels through a workspace."""
+    return dfss.dfss_attention_staged(Qd, Kd, Vd, s, scale)
 
 
 def _check_attention(w, heads=None):
@@ -269,20 +265,19 @@ def test_attention_full_size_sampled_heads(name, heads):
     _check_attention(synth.WORKLOADS[name], heads)
 
 
-@pytest.mark.parametrize("tile", ["16", "32x2", "32x4"])
+VARIANTS = [binding.VARIANT_Q16, binding.VARIANT_Q16X2, binding.VARIANT_Q32W2, binding.VARIANT_Q32W4]
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("BH,L,d,N,M", [(3, 256, 64, 2, 4), (2, 384, 64, 1, 2), (2, 256, 128, 2, 4)])
-def test_fused_attention_every_tile_shape(tile, BH, L, d, N, M):
+def test_fused_attention_every_tile_shape(variant, BH, L, d, N, M):
     """Each tiling of the fused kernel (16- or 32-query tiles, 2 or 4 waves) against the oracle."""
     Q, K, V = synth.gaussian_qkv(BH, L, L, d, 1.0, seed=900 + L + d + N)
     s = Shape(1, BH, L, L, d, N, M)
     scale = 1.0 / math.sqrt(d)
-    os.environ["DFSS_FUSED_TILE"] = tile
-    try:
-        O = dfss.dfss_attention(_dev(Q), _dev(K), _dev(V), s, scale)
-        Od = dfss.dense_attention_fused(_dev(Q), _dev(K), _dev(V), s, scale)
-        torch.cuda.synchronize()
-    finally:
-        del os.environ["DFSS_FUSED_TILE"]
+    O = binding.internal_attention_variant(_dev(Q), _dev(K), _dev(V), None, s, scale, variant)
+    Od = binding.internal_attention_variant(_dev(Q), _dev(K), _dev(V), None, s, scale, variant, dense=True)
+    torch.cuda.synchronize()
     Qn, Kn, Vn = (synth.to_numpy_f32(t) for t in (Q, K, V))
     assert np.max(np.abs(_np(O) - oracle.attention(Qn, Kn, Vn, N, M, scale))) <= 2e-2
     assert np.max(np.abs(_np(Od) - oracle.attention(Qn, Kn, Vn, 1, 1, scale))) <= 2e-2
@@ -313,8 +308,8 @@ def test_attention_rectangular(BH, Lq, Lk, d, N, M):
     assert np.max(np.abs(_np(Odf) - ref_dense)) <= 2e-2
 
 
-@pytest.mark.parametrize("tile", ["16", "32x2"])
-def test_fused_attention_rescales_when_late_keys_dominate(tile):
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_fused_attention_rescales_when_late_keys_dominate(variant):
     """Scores that grow along the key axis force the online softmax to raise its reference
     value in later blocks; a constant key makes one block dominate every row."""
     BH, L, d = 2, 256, 64
@@ -323,13 +318,9 @@ def test_fused_attention_rescales_when_late_keys_dominate(tile):
     K = (K.float() + ramp * torch.sign(Q.float().mean(1, keepdim=True))).to(torch.bfloat16)
     Q = (Q.float() * 2.0).to(torch.bfloat16)
     s = Shape(1, BH, L, L, d, 2, 4)
-    os.environ["DFSS_FUSED_TILE"] = tile
-    try:
-        O = dfss.dfss_attention(_dev(Q), _dev(K), _dev(V), s, 0.125)
-        Od = dfss.dense_attention_fused(_dev(Q), _dev(K), _dev(V), s, 0.125)
-        torch.cuda.synchronize()
-    finally:
-        del os.environ["DFSS_FUSED_TILE"]
+    O = binding.internal_attention_variant(_dev(Q), _dev(K), _dev(V), None, s, 0.125, variant)
+    Od = binding.internal_attention_variant(_dev(Q), _dev(K), _dev(V), None, s, 0.125, variant, dense=True)
+    torch.cuda.synchronize()
     Qn, Kn, Vn = (synth.to_numpy_f32(t) for t in (Q, K, V))
     S = np.einsum("hqd,hkd->hqk", Qn, Kn) * 0.125
     assert (S.max(-1) - S[:, :, :64].max(-1)).max() > 8.0   # the first block's maximum is outgrown
@@ -403,11 +394,7 @@ def test_attention_key_bias(B, H, Lq, Lk, d, N, M):
     scale = 1.0 / math.sqrt(d)
     Qd, Kd, Vd, bd = _dev(Q), _dev(K), _dev(V), _dev(bias)
     O = dfss.dfss_attention_bias(Qd, Kd, Vd, bd, s, scale)
-    os.environ["DFSS_ATTENTION_PATH"] = "staged"
-    try:
-        Os = dfss.dfss_attention_bias(Qd, Kd, Vd, bd, s, scale)
-    finally:
-        del os.environ["DFSS_ATTENTION_PATH"]
+    Os = dfss.dfss_attention_staged_bias(Qd, Kd, Vd, bd, s, scale)
     Od = dfss.dense_attention_bias(Qd, Kd, Vd, bd, s, scale)
     Odf = dfss.dense_attention_fused_bias(Qd, Kd, Vd, bd, s, scale)
     O0 = dfss.dfss_attention_bias(Qd, Kd, Vd, None, s, scale)      # NULL bias = the plain call
