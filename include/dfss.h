@@ -121,6 +121,24 @@ dfss_status dense_attention(const void *Q, const void *K, const void *V, const d
 dfss_status dense_attention_fused(const void *Q, const void *K, const void *V, const dfss_shape *s,
                                   float scale, void *O, void *stream);
 
+/* ---- the staged forward pass without a workspace argument ------------------------------------ */
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): dfss_attention_staged_bias with the workspace taken from a fixed
+ * array inside the library instead of from the caller.  key_bias may be NULL.  Same kernels, same
+ * results bit for bit, same validation.  The call allocates and frees nothing; the array
+ * (dfss_static_scratch_bytes() = 32 MiB of device memory per GPU the library runs on, held until the
+ * process ends) bounds the shape: dfss_workspace_bytes(s) must not exceed it, else DFSS_ERR_WORKSPACE
+ * and nothing is launched.  The array's address is looked up on the first call on each device (a
+ * symbol lookup, no allocation), with that device current: make the first call on a device outside
+ * any stream capture, and pass a stream of the current device.  Every call on a GPU uses that GPU's
+ * one array: calls that overlap in time on the same GPU (different streams, or a graph replayed while
+ * another call runs) race on it and give undefined results; calls ordered on one stream are safe.
+ * Nothing in the array needs to be cleared between calls: stage 1 writes every byte that stages 2 and 3
+ * read.  Afterwards the array holds the weights and metadata of the last call. */
+size_t dfss_static_scratch_bytes(void);
+dfss_status dfss_attention_staged_static(const void *Q, const void *K, const void *V, const void *key_bias,
+                                         const dfss_shape *s, float scale, void *O, void *stream);
+
 /* ---- additive key bias (padding mask) ---------------------------------------------- */
 /* The paper has no mask; padded batches need one.  Reading taken: key_bias[b][j] (float32,
  * device, [B, Lk] row-major, 16-byte aligned, shared by the H heads and all queries of batch

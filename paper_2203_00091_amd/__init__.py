@@ -24,6 +24,8 @@ from .binding import (  # noqa: F401
     dfss_attention_ragged,
     dfss_attention_staged,
     dfss_attention_staged_bias,
+    dfss_attention_staged_static,
+    dfss_static_scratch_bytes,
     dfss_backward_workspace_bytes,
     dfss_meta_bytes,
     dfss_meta_from_canonical,

@@ -25,6 +25,7 @@ EXPORTS = (
     "dfss_backward_workspace_bytes", "dfss_attention_backward",
     "dfss_attention_ragged", "dense_attention_fused_ragged",
     "dfss_attention_staged", "dfss_attention_staged_bias",
+    "dfss_static_scratch_bytes", "dfss_attention_staged_static",
 )
 # exported for the library's own tests only (csrc/dfss_internal.h)
 INTERNAL_EXPORTS = ("dfss_internal_attention_variant",)
@@ -113,6 +114,10 @@ def load_library():
         L.dfss_attention_ragged.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_attention_staged.argtypes = [vp, vp, vp, sp, f32, vp, vp, sz, vp]
         L.dfss_attention_staged_bias.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
+        L.dfss_attention_staged_static.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
+        L.dfss_attention_staged_static.restype = ctypes.c_int
+        L.dfss_static_scratch_bytes.argtypes = []
+        L.dfss_static_scratch_bytes.restype = sz
         L.dfss_internal_attention_variant.argtypes = [vp, vp, vp, vp, sp, f32, vp, ctypes.c_int, ctypes.c_int, vp]
         L.dense_attention_fused_ragged.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_spmm_t.argtypes = [vp, vp, vp, sp, vp, vp]
@@ -273,6 +278,18 @@ def dfss_attention_staged_bias(Q, K, V, key_bias, s: Shape, scale: float, O=None
                                                    ctypes.byref(s.c()), scale, _q(O, s), _ptr(ws),
                                                    ws.numel() * ws.element_size(), _stream())
     _check("dfss_attention_staged_bias", st)
+    return O
+
+
+def dfss_static_scratch_bytes() -> int:
+    return int(load_library().dfss_static_scratch_bytes())
+
+
+def dfss_attention_staged_static(Q, K, V, key_bias, s: Shape, scale: float, O):
+    """The staged forward pass with the library's own fixed scratch array; allocates nothing (O is the caller's)."""
+    st = load_library().dfss_attention_staged_static(_q(Q, s), _kv(K, s), _kv(V, s), _bias_ptr(key_bias, s),
+                                                     ctypes.byref(s.c()), scale, _q(O, s), _stream())
+    _check("dfss_attention_staged_static", st)
     return O
 
 

@@ -215,6 +215,42 @@ dfss_status dfss_attention_staged(const void *Q, const void *K, const void *V, c
     return attention_forward(Q, K, V, nullptr, s, scale, O, ws, ws_bytes, stream, true, 0);
 }
 
+// ---- the staged forward pass for callers that cannot allocate ------------------------------------
+// Scratch of the variant below: vals, then meta, as in a caller's workspace.  One array per GPU for the
+// lifetime of the process; host code reaches it only through the address looked up per device.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU (null = not looked up yet)
+
+// Device address of the current device's copy of `scratch` (looked up once per device).
+static dfss_status static_scratch_address(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DFSS_ERR_HIP;
+    void *p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return DFSS_ERR_HIP;
+        __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);   // (racing first calls store the same address)
+    }
+    *out = p;
+    return DFSS_OK;
+}
+
+size_t dfss_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+dfss_status dfss_attention_staged_static(const void *Q, const void *K, const void *V, const void *key_bias,
+                                         const dfss_shape *s, float scale, void *O, void *stream) {
+    // validate first (the size check needs a valid shape), then fetch the scratch address
+    Dims D;
+    if (!Q || !K || !V || !O) return DFSS_ERR_NULL;
+    if (dfss_status st = check_shape(s, true, &D)) return st;
+    const size_t need = dfss_workspace_bytes(s);
+    if (need == 0 || need > kStaticScratchBytes) return DFSS_ERR_WORKSPACE;
+    void *ws = nullptr;
+    if (dfss_status st = static_scratch_address(&ws)) return st;
+    return attention_forward(Q, K, V, key_bias, s, scale, O, ws, kStaticScratchBytes, stream, true, 0);
+}
+
 // Test hook (csrc/dfss_internal.h): the one-kernel path with the tiling named by the caller.
 dfss_status dfss_internal_attention_variant(const void *Q, const void *K, const void *V, const void *key_bias,
                                             const dfss_shape *s, float scale, void *O, int variant, int dense,
