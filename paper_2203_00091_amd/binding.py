@@ -29,7 +29,7 @@ EXPORTS = (
 )
 # exported for the library's own tests only (csrc/dfss_internal.h)
 INTERNAL_EXPORTS = ("dfss_internal_attention_variant",)
-VARIANT_AUTO, VARIANT_Q16, VARIANT_Q16X2, VARIANT_Q32W2, VARIANT_Q32W4 = range(5)
+VARIANT_AUTO, VARIANT_Q16, VARIANT_Q16X2, VARIANT_Q32W2, VARIANT_Q32W4, VARIANT_Q32K2 = range(6)
 
 
 DFSS_BF16, DFSS_F32, DFSS_F32_BF16X3 = 0, 1, 2

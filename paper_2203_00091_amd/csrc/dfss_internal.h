@@ -18,9 +18,10 @@ enum {
     DFSS_VARIANT_AUTO = 0,
     DFSS_VARIANT_Q16 = 1,    /* 16 queries per wave, 16x16x32 matrix instruction, 64-query workgroups   */
     DFSS_VARIANT_Q16X2 = 2,  /* two such query tiles per wave, 128-query workgroups (Lq % 128 == 0)     */
-    DFSS_VARIANT_Q32W2 = 3,  /* 32 queries per wave, 32x32x16 matrix instruction, 2 waves (d = 64 only) */
+    DFSS_VARIANT_Q32W2 = 3,  /* 32 queries per wave, 32x32x16 matrix instruction, 2 waves              */
     DFSS_VARIANT_Q32W4 = 4,  /* ... 4 waves, 128-query workgroups (Lq % 128 == 0)                       */
-    DFSS_VARIANT_LAST = 4
+    DFSS_VARIANT_Q32K2 = 5,  /* 32 queries per pair of waves that split the keys, 4 waves, 64 queries  */
+    DFSS_VARIANT_LAST = 5
 };
 
 /* dfss_attention_bias (dense == 0) or dense_attention_fused_bias (dense != 0) on bfloat16 data with the

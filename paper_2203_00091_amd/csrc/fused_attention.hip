@@ -544,18 +544,33 @@ hipError_t launch(const void *Q, const void *K, const void *V, const float *key_
 }  // namespace
 
 hipError_t launch_fused_attention32(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d,
-                                    int mode, int nw, float scale, void *O, hipStream_t st);
+                                    int mode, int nw, int ks, float scale, void *O, hipStream_t st);
 
 hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, const float *key_bias, int H,
                                   const uint8_t *block_mask, int BH, int Lq, int Lk, int d, int mode, float scale,
                                   void *O, int variant, hipStream_t st) {
-    // The 16-query kernel is the default.  The 32-query kernel (score MFMA at twice the rate, software
-    // pipelined) runs only when the caller names it.
-    int tile = 16, nw = 4;
-    if (variant == DFSS_VARIANT_Q32W2 && d == 64) tile = 32, nw = 2;
-    if (variant == DFSS_VARIANT_Q32W4 && Lq % 128 == 0) tile = 32, nw = 4;
-    if (tile == 32 && !key_bias && !block_mask && Lq % 64 == 0 && Lk % 64 == 0)
-        return launch_fused_attention32(Q, K, V, BH, Lq, Lk, d, mode, nw, scale, O, st);
+    // Calls without bias or block pattern on whole tiles take the 32-queries-per-wave kernel (callers that
+    // name a 16-query tiling get the kernel above).  Its tilings, chosen from the number of 128-query
+    // workgroups per compute unit (measured): four waves x 32 queries where that fills the chip or the grid is
+    // tiny anyway; two waves per 32-query tile (64-query workgroups, twice as many) in between; d = 128
+    // always the former (the merge of the two key halves costs more than it gains there).  Full attention
+    // (the baseline) runs whichever of the two kernels is faster at the shape.
+    const bool plain = !key_bias && !block_mask && Lq % 64 == 0 && Lk % 64 == 0;
+    if (plain && variant != DFSS_VARIANT_Q16 && variant != DFSS_VARIANT_Q16X2) {
+        const long wg128 = (long)BH * (Lq / 128);
+        int nw = Lq % 128 == 0 ? 4 : 2, ks = 1;
+        if (variant == DFSS_VARIANT_AUTO) {
+            if (d == 64 && Lq % 64 == 0 && wg128 >= 320 && wg128 < 640) nw = 4, ks = 2;
+            if (Lq % 128 != 0 && d == 64) nw = 4, ks = 2;            // 64-query workgroups either way
+            const bool old_dense = d == 128 || wg128 >= 448 || Lq % 128 != 0;
+            if (mode == 2 && old_dense) nw = 0;
+            if (mode != 2 && d == 128 && Lq % 128 != 0) nw = 0;       // (two-wave workgroups at d = 128: too many registers)
+        }
+        if (variant == DFSS_VARIANT_Q32W2) nw = 2;
+        if (variant == DFSS_VARIANT_Q32W4 && Lq % 128 == 0) nw = 4;
+        if (variant == DFSS_VARIANT_Q32K2) nw = 4, ks = 2;
+        if (nw != 0) return launch_fused_attention32(Q, K, V, BH, Lq, Lk, d, mode, nw, ks, scale, O, st);
+    }
     if (mode == 0) return launch<MODE_2TO4>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, variant, st);
     if (mode == 1) return launch<MODE_1TO2>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, variant, st);
     return launch<MODE_DENSE>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, variant, st);

