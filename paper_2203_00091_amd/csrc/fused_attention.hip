@@ -560,8 +560,8 @@ hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, c
         const long wg128 = (long)BH * (Lq / 128);
         int nw = Lq % 128 == 0 ? 4 : 2, ks = 1;
         if (variant == DFSS_VARIANT_AUTO) {
-            if (d == 64 && Lq % 64 == 0 && wg128 >= 320 && wg128 < 640) nw = 4, ks = 2;
-            if (Lq % 128 != 0 && d == 64) nw = 4, ks = 2;            // 64-query workgroups either way
+            if (mode != 2 && d == 64 && wg128 >= 320 && wg128 < 640) nw = 4, ks = 2;
+            if (mode != 2 && Lq % 128 != 0 && d == 64) nw = 4, ks = 2;   // 64-query workgroups either way
             const bool old_dense = d == 128 || wg128 >= 448 || Lq % 128 != 0;
             if (mode == 2 && old_dense) nw = 0;
             if (mode != 2 && d == 128 && Lq % 128 != 0) nw = 0;       // (two-wave workgroups at d = 128: too many registers)
