@@ -22,9 +22,9 @@ workload the headline and ``--no-sweep`` times only that one.
 Protocol.  Inputs are resident in HBM before timing starts.  The steps rotate over enough independent
 buffer sets that no step finds its inputs (or, for the multi-kernel paths, its workspace) in the 256 MB
 last-level cache ("cold"; ``--warm`` keeps one set).  The K steps asked for with ``--steps`` are captured in
-one HIP graph; the graph is replayed R times back to back between two HIP events recorded on the stream the
-kernels run on, R chosen so that the timed region lasts at least 20 ms (a single replay of a short graph is
-dominated by the host work around it and by clock ramp-up, so K = 20 and K = 2000 would disagree).
+one HIP graph, R times over (the same K steps, R chosen so that the graph runs for at least 20 ms: a short
+graph is dominated by the host work around its launch and by clock ramp-up, so K = 20 and K = 2000 would
+disagree), and the graph is launched once between two HIP events recorded on the stream the kernels run on.
 ms_per_step = elapsed / (K * R); R is reported as ``config.graph_replays``.
 
 Workloads whose name ends in ``_f32`` run the paper's second precision (float data, 1:2); ``--products``
@@ -91,7 +91,7 @@ def parse_args():
 
 
 class Timer:
-    """Times K steps from a HIP graph, replayed until the timed region is long enough."""
+    """Times K steps from a HIP graph that repeats them until the timed region is long enough."""
 
     def __init__(self, torch, K, W, use_graph):
         self.torch, self.K, self.W, self.use_graph = torch, K, W, use_graph
@@ -124,10 +124,18 @@ class Timer:
         torch.cuda.synchronize()
         once = max(e0.elapsed_time(e1), 1e-3)
         R = max(1, math.ceil(MIN_TIMED_MS / once))
-        torch.cuda.synchronize()       # the bracket: synchronise, R replays between two events, synchronise
-        e0.record()
-        for _ in range(R):
+        if R > 1:
+            # a graph R times as long (the same K steps R times over) instead of R launches of the short one:
+            # no launch gaps inside the timed region
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for _ in range(R):
+                    for i in range(K):
+                        step_fn(i)
             g.replay()
+            torch.cuda.synchronize()
+        e0.record()                    # the bracket: synchronised before, one graph launch, synchronised after
+        g.replay()
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / (K * R), R
