@@ -58,6 +58,9 @@ SWEEP = ("bert_base_L384_2to4", "bert_base_L512_1to2", "long_L1024_2to4", "long_
 # up by workload; a workload without a summary reports null.
 TRAFFIC_FROM_PROFILES = {
     # workload: (bytes per launch, summary file)
+    "long_L4096_2to4": (50.46e6, "profiles/hbm_traffic_k_fused32.md"),
+    "large_head_L2048_d128_2to4": (134.36e6, "profiles/hbm_traffic_k_fused32.md"),
+    "bert_base_L384_2to4": (19.01e6, "profiles/hbm_traffic_k_fused32.md"),
 }
 
 
