@@ -98,12 +98,18 @@ dfss_status dfss_spmm(const void *vals, const void *meta, const void *V, const d
 dfss_status dfss_attention(const void *Q, const void *K, const void *V, const dfss_shape *s,
                            float scale, void *O, void *ws, size_t ws_bytes, void *stream);
 
-/* The same function as the three stage kernels run one after the other (the structure whose latency
- * the paper reports, Sec. 5.2): stage 1 writes the kept scores and the metadata into ws, stage 2 turns
- * them into weights in place, stage 3 multiplies by V.  ws: device scratch of at least
- * dfss_workspace_bytes(), 256-byte aligned; afterwards it holds the weights (at offset 0) and the
- * metadata (at offset dfss_vals_bytes() rounded up to 256) of this forward pass, which is what
- * dfss_attention_backward needs.  key_bias (may be NULL) as described below. */
+/* The same function through the workspace, the structure whose latency the paper reports (Sec. 5.2).
+ * 2-byte dtype: TWO kernels.  Stage 1 writes the kept scores and the metadata into ws; the second kernel
+ * is the stage-3 product with the softmax of stage 2 applied to the scores as it reads them (running row
+ * maximum, sums divided out at the end), which saves the separate pass of App. A.1.3 over all kept values
+ * (one read and one write of them).  Afterwards ws holds the kept SCORES (at offset 0) and the metadata
+ * (at offset dfss_vals_bytes() rounded up to 256) of this forward pass.  The weights that
+ * dfss_attention_backward needs are not formed: run the three stage calls for them.  The result differs
+ * from the three stage calls by roundings only (same kept keys; the weights are rounded to bfloat16 before
+ * instead of after the normalisation).
+ * 4-byte dtypes: the three stage kernels one after the other; ws then holds the weights and the metadata.
+ * ws: device scratch of at least dfss_workspace_bytes(), 256-byte aligned.  key_bias (may be NULL) as
+ * described below. */
 dfss_status dfss_attention_staged(const void *Q, const void *K, const void *V, const dfss_shape *s,
                                   float scale, void *O, void *ws, size_t ws_bytes, void *stream);
 dfss_status dfss_attention_staged_bias(const void *Q, const void *K, const void *V, const void *key_bias,
@@ -133,8 +139,8 @@ dfss_status dense_attention_fused(const void *Q, const void *K, const void *V, c
  * any stream capture, and pass a stream of the current device.  Every call on a GPU uses that GPU's
  * one array: calls that overlap in time on the same GPU (different streams, or a graph replayed while
  * another call runs) race on it and give undefined results; calls ordered on one stream are safe.
- * Nothing in the array needs to be cleared between calls: stage 1 writes every byte that stages 2 and 3
- * read.  Afterwards the array holds the weights and metadata of the last call. */
+ * Nothing in the array needs to be cleared between calls: stage 1 writes every byte that the kernels after
+ * it read.  Afterwards the array holds what ws of dfss_attention_staged holds, for the last call. */
 size_t dfss_static_scratch_bytes(void);
 dfss_status dfss_attention_staged_static(const void *Q, const void *K, const void *V, const void *key_bias,
                                          const dfss_shape *s, float scale, void *O, void *stream);

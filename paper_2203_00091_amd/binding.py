@@ -256,7 +256,8 @@ def dfss_attention(Q, K, V, s: Shape, scale: float, O=None, ws=None):
 
 
 def dfss_attention_staged(Q, K, V, s: Shape, scale: float, O=None, ws=None):
-    """Whole DFSS forward as the three stage kernels through ``ws`` (allocated if not given)."""
+    """Whole DFSS forward through ``ws`` (allocated if not given): stage 1, then the product that applies the
+    softmax as it reads the kept scores (4-byte dtypes: the three stage kernels)."""
     if O is None:
         O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
     if ws is None:

@@ -188,9 +188,9 @@ static dfss_status attention_forward(const void *Q, const void *K, const void *V
         if (e == hipSuccess) e = spmm_f32(D, vals, meta, V, O, st);
         return hip_status(e);
     }
+    // two kernels: the kept scores go to the workspace once and the product applies the softmax as it reads them
     hipError_t e = dfss::launch_sddmm_prune(Q, K, bias, D.H, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, vals, meta, st);
-    if (e == hipSuccess) e = dfss::launch_row_softmax(vals, (long)D.BH * D.Lq, D.Lk / 2, st);
-    if (e == hipSuccess) e = dfss::launch_spmm(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, st);
+    if (e == hipSuccess) e = dfss::launch_softmax_spmm(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, st);
     return hip_status(e);
 }
 

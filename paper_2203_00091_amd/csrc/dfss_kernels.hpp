@@ -19,6 +19,9 @@ hipError_t launch_row_softmax(void *x, long rows, int cols, hipStream_t st);
 // Stage 3 (Sec. 3.1): O = A_sparse V from compressed weights + metadata.
 hipError_t launch_spmm(const void *vals, const void *meta, const void *V, int BH, int Lq, int Lk, int d,
                        void *O, hipStream_t st);
+// The same product on the kept SCORES of stage 1, with the softmax over them applied on the way.
+hipError_t launch_softmax_spmm(const void *scores, const void *meta, const void *V, int BH, int Lq, int Lk, int d,
+                               void *O, hipStream_t st);
 // Dense O = P V with P bfloat16 [BH, Lq, Lk].
 hipError_t launch_dense_av(const void *P, const void *V, int BH, int Lq, int Lk, int d, void *O,
                            hipStream_t st);

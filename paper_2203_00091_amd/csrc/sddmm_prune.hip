@@ -232,11 +232,16 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
     constexpr int LPT = TILE / NT;       // asynchronous copies per thread per block
     constexpr int STEPS = D / 16;        // k-steps of the 32x32x16 MFMA
     constexpr int TQ = 128;              // queries per workgroup (4 waves x 32)
-    __shared__ u32x4 Ks[2][TILE];        // double buffer: the copy of block it+1 runs under the work on block it
-    // per-wave staging of the kept values of one 64-key pair (32 rows x 64 bytes), so that they leave
-    // as 64-byte row segments from consecutive lanes instead of 16-byte pieces scattered over 32 rows
-    __shared__ u32x4 Stage[MODE == MODE_DENSE ? 1 : 4][32 * 4];
-    __shared__ f32x4 Bs[BIAS ? 2 : 1][KB / 4];   // bias of the block's 128 keys, copied along with K
+    // One LDS array, so that d = 128 fits two workgroups per compute unit (2 x 80 KiB):
+    //   Ks     double buffer of K blocks: the copy of block it+1 runs under the work on block it
+    //   Stage  per-wave staging of the kept values of one 128-key block (32 rows x 128 bytes), so that they
+    //          leave as whole 128-byte lines from consecutive lanes instead of 16-byte pieces scattered over
+    //          32 rows
+    //   Bs     bias of the block's 128 keys (double buffer), copied along with K
+    constexpr int STAGE = MODE == MODE_DENSE ? 0 : 32 * 8;   // 16-byte units per wave
+    __shared__ u32x4 Smem[2 * TILE + 4 * STAGE + (BIAS ? 2 * (KB / 4) : 0)];
+    u32x4(*const Ks)[TILE] = reinterpret_cast<u32x4(*)[TILE]>(Smem);
+    f32x4(*const Bs)[KB / 4] = reinterpret_cast<f32x4(*)[KB / 4]>(Smem + 2 * TILE + 4 * STAGE);
 
     const int tid = threadIdx.x;
     const int w = tid >> 6, l = tid & 63, lj = l & 31, h = l >> 5;
@@ -293,11 +298,13 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
     }
 
     const size_t row = (size_t)bh * Lq + q0 + lj;
-    // read-back role of this lane when the staged pair is written out: store c (0/1) covers rows
-    // 16 c + l/4, 16-byte chunk l%4 of the row's 64 bytes; chunks are XOR-swizzled by (row/2)%4
-    const int sb_row = l >> 2, sb_chunk = l & 3;
-    uint32_t *const out_sb0 = out + (((size_t)bh * Lq + q0 + sb_row) * (size_t)(Lk / 2)) / 2 + sb_chunk * 4;
-    uint32_t *const out_sb1 = out_sb0 + (size_t)16 * (Lk / 4);
+    // read-back role of this lane when the staged block is written out: store i (0..3) covers rows
+    // 8 i + l/8, 16-byte chunk l%8 of the row's 128 bytes; chunks are XOR-swizzled by row % 8, which keeps
+    // the 8 lanes of one LDS pass on 8 different chunk columns for the writes (8 rows, one chunk) and for
+    // the reads (one row, 8 chunks)
+    const int sb_row = l >> 3, sb_chunk = l & 7;
+    uint32_t *const out_sb = out + (((size_t)bh * Lq + q0 + sb_row) * (size_t)(Lk / 2)) / 2 + sb_chunk * 4;
+    const size_t sb_step = (size_t)8 * (Lk / 4);   // 8 rows further, in dwords
     // metadata of (row, block jb): 16 bytes at ((row block * blocks + jb) * 16 + row % 16) * 4 words;
     // a lane computes the words of chunks (p = 0, h) and (p = 1, h) = slots 2 h and 2 h + 1 of its row
     u32x4 *const meta_row4 = reinterpret_cast<u32x4 *>(
@@ -308,7 +315,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
         const int buf = it & 1;
         // Block `it` must have landed.  The stores of the previous iteration were issued after its
         // copy and may stay in flight (waiting for them would expose the store latency every block).
-        constexpr int kStores = MODE == MODE_DENSE ? 8 : 5;   // stores per iteration, exactly (or lower): 2 x 2 values + 1 metadata
+        constexpr int kStores = MODE == MODE_DENSE ? 8 : 5;   // stores per iteration, exactly (or lower): 4 of values + 1 of metadata
         if (it == 0) wait_async_copies();
         else wait_async_copies_keep<kStores>();
         __syncthreads();       // ... for every wave, and everybody is done with the block before
@@ -383,30 +390,29 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
                         pk[u][g] = pack_bf16x2(lo, hi);
                         word |= code;
                     }
-                // stage: this lane's 32 bytes are chunks 2h, 2h+1 of row lj
-                u32x4 *const st = Stage[w];
-                const int sw = (lj >> 1) & 3;
-                st[lj * 4 + ((2 * h) ^ sw)] = pk[0];
-                st[lj * 4 + ((2 * h + 1) ^ sw)] = pk[1];
-                wave_lds_sync();
-                // write out: two stores of 16 rows x 64 contiguous bytes
-                const size_t pair_off = (size_t)(KB * jb + 64 * p) / 4;   // dwords into the row of kept values
-                const u32x4 v0 = st[sb_row * 4 + (sb_chunk ^ ((sb_row >> 1) & 3))];
-                const u32x4 v1 = st[(16 + sb_row) * 4 + (sb_chunk ^ (((16 + sb_row) >> 1) & 3))];
-                wave_lds_sync();   // the staging rows are free for the next pair
-                *reinterpret_cast<u32x4 *>(out_sb0 + pair_off) = v0;
-                *reinterpret_cast<u32x4 *>(out_sb1 + pair_off) = v1;
+                // stage: this lane's 32 bytes are chunks 4p + 2h, 4p + 2h + 1 of row lj
+                u32x4 *const st = Smem + 2 * TILE + w * STAGE;
+                st[lj * 8 + ((4 * p + 2 * h) ^ (lj & 7))] = pk[0];
+                st[lj * 8 + ((4 * p + 2 * h + 1) ^ (lj & 7))] = pk[1];
                 mwords[p] = word;
             }
         }
         if constexpr (MODE != MODE_DENSE) {
-            // the two lanes (lj, h = 0/1) of a row hold 8 bytes each: join them through the staging
-            // buffer so that lanes 0..31 store the 16 bytes of rows 0..31 (two contiguous 256-byte runs)
-            u32x2 *const sm = reinterpret_cast<u32x2 *>(Stage[w]);
-            sm[lj * 2 + h] = mwords;
+            u32x4 *const st = Smem + 2 * TILE + w * STAGE;
             wave_lds_sync();
-            const u32x4 m4 = Stage[w][lj];
-            wave_lds_sync();
+            u32x4 v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = st[(8 * i + sb_row) * 8 + (sb_chunk ^ sb_row)];
+            wave_lds_sync();   // the staging rows are free for the next block
+            // the two lanes (lj, h = 0/1) of a row hold 8 bytes of metadata each: lane (lj, 0) takes the other
+            // half from lane (lj, 1), so that lanes 0..31 store the 16 bytes of rows 0..31 (two contiguous
+            // 256-byte runs)
+            const u32x4 m4 = {mwords[0], mwords[1], (uint32_t)__shfl_xor((int)mwords[0], 32),
+                              (uint32_t)__shfl_xor((int)mwords[1], 32)};
+            // four stores of 8 rows x 128 contiguous bytes: one whole line per row
+            uint32_t *const dst = out_sb + (size_t)(KB * jb) / 4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(dst + i * sb_step) = v[i];
             if (h == 0) meta_row4[(size_t)jb * 16] = m4;
         }
     }

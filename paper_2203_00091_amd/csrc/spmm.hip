@@ -7,6 +7,13 @@
 // through the same kernel.  The dense variant (P V of Eq. 1, for the baseline) shares the
 // V staging and uses v_mfma_f32_16x16x32_bf16.
 //
+// The SOFTMAX variant takes the kept SCORES of stage 1 instead of weights and applies the softmax
+// on the way (Sec. 3.1; the max-subtracted form of App. A.1.3 with a running maximum): the scores of
+// a block become exp(s - m) in registers before they enter the matrix instruction, the accumulators and
+// the running sum are rescaled whenever a block raises the maximum m, and the result is divided by the
+// sum at the end.  It replaces the separate softmax kernel (one read and one write of all kept values)
+// in the two-kernel forward pass.
+//
 // V blocks (128 keys x d) are copied global -> LDS by the direct-to-LDS load, double
 // buffered, row-major with an XOR swizzle of the 16-byte chunks; the B operand (keys along
 // the contraction, one d-column per lane) comes from the transposing LDS read.
@@ -26,7 +33,7 @@ namespace {
 constexpr int NT = 256;   // 4 waves
 constexpr int KB = 128;   // keys per block
 
-template <int D, bool SPARSE, int RB>
+template <int D, bool SPARSE, int RB, bool SOFTMAX>
 __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, const uint32_t *__restrict__ meta,
                                               const __bf16 *__restrict__ V, int Lq, int Lk,
                                               uint16_t *__restrict__ O) {
@@ -101,18 +108,76 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
     const int tr_byte = 8 * (li & 1);
     const int tr_xor = tr_row << 1;        // (row & 3) << 1, key0 is a multiple of 4
 
+    // SOFTMAX: running maximum and sum of row li of each row block (the four lane groups kb of a row hold the
+    // same maximum and their own partial sums)
+    static_assert(!SOFTMAX || SPARSE, "the softmax is folded into the sparse product only");
+    constexpr float kLog2e = 1.4426950408889634f;
+    float m_run[RB], l_run[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) m_run[rb] = -INFINITY, l_run[rb] = 0.f;
+
+    // SOFTMAX: turns the kept scores of one block into exp(s - m) in place (m = the running row maximum after the
+    // block) and keeps the sums; the accumulators hold the blocks before it and are rescaled when m rises
+    auto softmax_block = [&](AFrag (&a)[RB]) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            float x[16];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                x[2 * e] = bf16_lo_to_f32(a[rb].v[0][e]);
+                x[2 * e + 1] = bf16_hi_to_f32(a[rb].v[0][e]);
+                x[8 + 2 * e] = bf16_lo_to_f32(a[rb].v[1][e]);
+                x[8 + 2 * e + 1] = bf16_hi_to_f32(a[rb].v[1][e]);
+            }
+            float bm = fmaxf(x[0], x[1]);
+#pragma unroll
+            for (int e = 2; e < 16; e += 2) bm = fmaxf(fmaxf(x[e], x[e + 1]), bm);
+            bm = fmaxf(bm, __shfl_xor(bm, 16, kWave));
+            bm = fmaxf(bm, __shfl_xor(bm, 32, kWave));   // maximum of row li over the block's 64 kept scores
+            const float m_new = fmaxf(m_run[rb], bm);
+            if (__builtin_amdgcn_ballot_w64(m_new > m_run[rb]) != 0) {   // some row of the wave rises: rescale
+                // (a row still at -inf gets the factor 0: its sums are 0 anyway)
+                const float f = m_new > m_run[rb] ? exp2f((m_run[rb] - m_new) * kLog2e) : 1.f;
+                l_run[rb] *= f;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float fr = __shfl(f, 4 * kb + r, kWave);   // accumulator row 4 kb + r
+#pragma unroll
+                    for (int ds = 0; ds < DS; ++ds) acc[rb][ds][r] *= fr;
+                }
+                m_run[rb] = m_new;
+            }
+            // a row whose keys so far are all masked (-inf): subtract 0, its weights are exp(-inf) = 0
+            const float mb = m_new == -INFINITY ? 0.f : m_new * kLog2e;
+            float sum = 0.f;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                x[e] = exp2f(__builtin_fmaf(x[e], kLog2e, -mb));
+                sum += x[e];
+            }
+            l_run[rb] += sum;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                a[rb].v[0][e] = pack_bf16x2(x[2 * e], x[2 * e + 1]);
+                a[rb].v[1][e] = pack_bf16x2(x[8 + 2 * e], x[8 + 2 * e + 1]);
+            }
+        }
+    };
+
+    // The A operand is loaded two blocks ahead: block jb + 1 is in registers while block jb is multiplied, so that the
+    // softmax of block jb + 1 runs on the vector unit under the matrix instructions of block jb.
     issue_block(0, 0);
-    AFrag a_cur[RB], a_nxt[RB];
+    AFrag a_cur[RB], a_nxt[RB], a_far[RB];
     load_a(0, a_cur);
+    if (nblocks > 1) load_a(1, a_nxt);
+    if constexpr (SOFTMAX) softmax_block(a_cur);
 
     for (int jb = 0; jb < nblocks; ++jb) {
         const int buf = jb & 1;
-        wait_async_copies();  // vmcnt(0): this block's V copies and A loads are in
+        wait_async_copies();  // vmcnt(0): this block's V copies and the A loads of the next block are in
         __syncthreads();
-        if (jb + 1 < nblocks) {
-            issue_block(jb + 1, buf ^ 1);
-            load_a(jb + 1, a_nxt);
-        }
+        if (jb + 1 < nblocks) issue_block(jb + 1, buf ^ 1);
+        if (jb + 2 < nblocks) load_a(jb + 2, a_far);
         const char *vbase = reinterpret_cast<const char *>(&Vs[buf][0]);
         auto tr = [&](int key0, int ds) {
             const int row = key0 + tr_row;
@@ -157,24 +222,34 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
             }
         }
         if (jb + 1 < nblocks) {
+            if constexpr (SOFTMAX) softmax_block(a_nxt);
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) a_cur[rb] = a_nxt[rb];
+            for (int rb = 0; rb < RB; ++rb) a_cur[rb] = a_nxt[rb], a_nxt[rb] = a_far[rb];
         }
     }
 
     // acc[rb][ds][r] = O[q][16 ds + li], q = 16 (rb0 + rb) + 4 kb + r
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
+    for (int rb = 0; rb < RB; ++rb) {
+        float inv = 1.f;
+        if constexpr (SOFTMAX) {
+            float l = l_run[rb];
+            l += __shfl_xor(l, 16, kWave);
+            l += __shfl_xor(l, 32, kWave);     // sum of row li over all keys
+            inv = 1.0f / l;
+        }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const size_t q = (size_t)bh * Lq + (size_t)(rb0 + rb) * 16 + 4 * kb + r;
+            const float ir = SOFTMAX ? __shfl(inv, 4 * kb + r, kWave) : 1.f;
 #pragma unroll
             for (int ds = 0; ds < DS; ++ds)
-                O[q * D + 16 * ds + li] = (uint16_t)(pack_bf16x2(acc[rb][ds][r], 0.f) & 0xFFFFu);
+                O[q * D + 16 * ds + li] = (uint16_t)(pack_bf16x2(SOFTMAX ? acc[rb][ds][r] * ir : acc[rb][ds][r], 0.f) & 0xFFFFu);
         }
+    }
 }
 
-template <bool SPARSE>
+template <bool SPARSE, bool SOFTMAX = false>
 hipError_t launch(const void *P, const void *meta, const void *V, int BH, int Lq, int Lk, int d, void *O,
                   hipStream_t st) {
     // two row blocks per wave when that still leaves two workgroups per compute unit (measured:
@@ -182,7 +257,7 @@ hipError_t launch(const void *P, const void *meta, const void *V, int BH, int Lq
     bool rb2 = (Lq % 128 == 0) && ((long)BH * (Lq / 128) >= 512);
     const unsigned grid = (unsigned)((long)BH * (Lq / (rb2 ? 128 : 64)));
 #define DFSS_LAUNCH(DD, RR)                                                                                   \
-    hipLaunchKernelGGL((k_av<DD, SPARSE, RR>), dim3(grid), dim3(NT), 0, st, (const uint32_t *)P,              \
+    hipLaunchKernelGGL((k_av<DD, SPARSE, RR, SOFTMAX>), dim3(grid), dim3(NT), 0, st, (const uint32_t *)P,              \
                        (const uint32_t *)meta, (const __bf16 *)V, Lq, Lk, (uint16_t *)O)
     if (d == 64) {
         if (rb2) DFSS_LAUNCH(64, 2); else DFSS_LAUNCH(64, 1);
@@ -198,6 +273,11 @@ hipError_t launch(const void *P, const void *meta, const void *V, int BH, int Lq
 hipError_t launch_spmm(const void *vals, const void *meta, const void *V, int BH, int Lq, int Lk, int d, void *O,
                        hipStream_t st) {
     return launch<true>(vals, meta, V, BH, Lq, Lk, d, O, st);
+}
+
+hipError_t launch_softmax_spmm(const void *scores, const void *meta, const void *V, int BH, int Lq, int Lk, int d,
+                               void *O, hipStream_t st) {
+    return launch<true, true>(scores, meta, V, BH, Lq, Lk, d, O, st);
 }
 
 hipError_t launch_dense_av(const void *P, const void *V, int BH, int Lq, int Lk, int d, void *O, hipStream_t st) {

@@ -135,11 +135,24 @@ def test_default_call_ragged_call_and_blocked_call(N, M):
     Qd, Kd = Q.to(DEV), K.to(DEV)
     W = _weights_through_identity_v(lambda V: dfss.dfss_attention(Qd, Kd, V, s, 0.125), BH, Lq, Lk, d, torch.bfloat16)
     _compare(W, Qn, Kn, N, M, 0.125)
+    # the two-kernel path (stage 1, then the product that applies the softmax on the way); 192 queries take the
+    # 16-queries-per-wave stage 1, 128 of them the 32-queries-per-wave one
+    W = _weights_through_identity_v(lambda V: dfss.dfss_attention_staged(Qd, Kd, V, s, 0.125), BH, Lq, Lk, d,
+                                    torch.bfloat16)
+    _compare(W, Qn, Kn, N, M, 0.125)
+    s128 = Shape(B, H, 128, Lk, d, N, M)
+    Q128 = Q[:, :128].contiguous().to(DEV)
+    W = _weights_through_identity_v(lambda V: dfss.dfss_attention_staged(Q128, Kd, V, s128, 0.125), BH, 128, Lk, d,
+                                    torch.bfloat16)
+    _compare(W, Qn[:, :128], Kn, N, M, 0.125)
     # padding mask whose ends cut through runs of four
     lengths = torch.tensor([Lk, 203])
     bias = synth.key_padding_bias(lengths, Lk)
     bd = bias.to(DEV)
     W = _weights_through_identity_v(lambda V: dfss.dfss_attention_bias(Qd, Kd, V, bd, s, 0.125), BH, Lq, Lk, d,
+                                    torch.bfloat16)
+    _compare(W, Qn, Kn, N, M, 0.125, key_bias=bias.numpy(), H=H)
+    W = _weights_through_identity_v(lambda V: dfss.dfss_attention_staged_bias(Qd, Kd, V, bd, s, 0.125), BH, Lq, Lk, d,
                                     torch.bfloat16)
     _compare(W, Qn, Kn, N, M, 0.125, key_bias=bias.numpy(), H=H)
     # unpadded lengths: 100 queries, 332 keys

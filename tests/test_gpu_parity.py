@@ -213,7 +213,7 @@ def test_meta_order_round_trip():
 # whole path
 # ----------------------------------------------------------------------------------
 def _staged_attention(Qd, Kd, Vd, s, scale):
-    """The three stage kernels through a workspace."""
+    """The stage kernels through a workspace (stage 1, then the product that applies the softmax as it reads)."""
     return dfss.dfss_attention_staged(Qd, Kd, Vd, s, scale)
 
 
@@ -237,7 +237,10 @@ def _check_attention(w, heads=None):
     ref_dense = oracle.attention(Qn, Kn, Vn, 1, 1, w.scale)
     assert np.max(np.abs(O[heads] - ref)) <= 2e-2
     assert np.max(np.abs(Os[heads] - ref)) <= 2e-2
-    assert np.array_equal(Os, O3)
+    # same stage 1, so the same keys are kept on every head; the staged call normalises after the product (its weights
+    # are exp(s - max) rounded to bfloat16, divided by their sum at the end), the three calls round the normalised
+    # weights: a bfloat16 rounding of the weights and one of the output apart
+    assert np.max(np.abs(Os - O3)) <= 2e-2
     # One kernel against three kernels on EVERY head (no oracle here).  The two paths round their scores
     # differently (the one-kernel path forms them relative to its softmax reference), so where the N-th and
     # (N+1)-th score of a run are a rounding error apart they may keep different keys -- both choices are the
