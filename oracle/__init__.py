@@ -18,7 +18,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "dfss_oracle.c")
-_LIB = os.path.join(_HERE, "liboracle.so")
+# An instrumented build for the test-suite's sanitizer pass: extra gcc flags and a library name of its own, so that
+# it never replaces the plain build.  Test infrastructure only (the HIP library reads no environment).
+_EXTRA_CFLAGS = os.environ.get("DFSS_ORACLE_EXTRA_CFLAGS", "").split()
+_LIB = os.path.join(_HERE, "liboracle" + ("_instrumented" if _EXTRA_CFLAGS else "") + ".so")
 
 _f32p = np.ctypeslib.ndpointer(dtype=np.float32, flags="C_CONTIGUOUS")
 _u8p = np.ctypeslib.ndpointer(dtype=np.uint8, flags="C_CONTIGUOUS")
@@ -31,7 +34,7 @@ def build(force: bool = False) -> str:
     product a plain multiply-then-add sequence, as the oracle's header states."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O3", "-march=native", "-ffp-contract=off", "-fopenmp", "-fPIC",
-               "-shared", "-std=c11", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+               "-shared", "-std=c11", "-Wall", "-Wextra", *_EXTRA_CFLAGS, "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 

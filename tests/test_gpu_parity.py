@@ -339,19 +339,63 @@ def test_fused_attention_rescales_when_late_keys_dominate(variant):
     assert np.max(np.abs(_np(Od) - oracle.attention(Qn, Kn, Vn, 1, 1, 0.125))) <= 2e-2
 
 
+def _poisoned(shape, dtype, fill):
+    t = torch.empty(shape, dtype=dtype, device=DEV)
+    t.view(torch.int16 if dtype == torch.bfloat16 else torch.int32).fill_(-1 if fill else 0)
+    return t
+
+
+def _bits(t):
+    return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).cpu()
+
+
 def test_results_are_deterministic_and_cover_every_byte():
+    """Every output array is written in full and depends on nothing it held before: each call runs twice, on
+    outputs pre-filled with 0x00 and with 0xFF bytes, and the two results must agree bit for bit.  Covers the
+    stage outputs (kept scores, metadata, the softmax in place, O), O of every whole-path entry point and the
+    gradients."""
     w = synth.WORKLOADS["bert_base_L384_2to4"]
     Q, K, V = (_dev(t) for t in synth.make(w))
     s = Shape(w.B, w.H, w.L, w.L, w.d, w.N, w.M)
+    lengths = synth.padding_lengths(w.B, w.L, 4242)
+    bias = _dev(synth.key_padding_bias(lengths, w.L))
+    bm = _dev(synth.block_pattern(w.L // 64, w.L // 64, seed=5, window=1, n_global=1, n_random=1))
+    Lr = 332
+    sr = Shape(w.B, w.H, Lr, Lr, w.d, w.N, w.M)
+    Qr, Kr, Vr = (t[:, :Lr].contiguous() for t in (Q, K, V))
+    dO = _dev(synth.gaussian_qkv(w.BH, w.L, w.L, w.d, 1.0, seed=99)[0])
+    o_shape, bf = (s.BH, s.Lq, s.d), torch.bfloat16
     outs = []
     for fill in (0x00, 0xFF):
-        vals = torch.empty((s.BH, s.Lq, s.Lc), dtype=torch.bfloat16, device=DEV)
-        vals.view(torch.int16).fill_(-1 if fill else 0)
-        meta = torch.full((s.BH * s.Lq * (s.Lk // 16),), -1 if fill else 0, dtype=torch.int16, device=DEV)
+        got = {}
+        vals = _poisoned((s.BH, s.Lq, s.Lc), bf, fill)
+        meta = _poisoned((s.BH * s.Lq * (s.Lk // 16),), torch.bfloat16, fill).view(torch.int16)
         dfss.dfss_sddmm_prune(Q, K, s, w.scale, vals, meta)
+        got["scores"], got["meta"] = _bits(vals), meta.cpu()
+        dfss.dfss_sparse_softmax(vals, s)           # in place: reads what stage 1 wrote, writes every weight
+        got["weights"] = _bits(vals)
+        got["spmm"] = _bits(dfss.dfss_spmm(vals, meta, V, s, O=_poisoned(o_shape, bf, fill)))
+        O = dfss.dfss_attention(Q, K, V, s, w.scale, O=_poisoned(o_shape, bf, fill))
+        got["one kernel"] = _bits(O)
+        ws = _poisoned((dfss.dfss_workspace_bytes(s) // 2,), bf, fill)
+        got["staged"] = _bits(dfss.dfss_attention_staged(Q, K, V, s, w.scale, O=_poisoned(o_shape, bf, fill),
+                                                         ws=ws.view(torch.uint8)))
+        got["bias"] = _bits(dfss.dfss_attention_bias(Q, K, V, bias, s, w.scale, O=_poisoned(o_shape, bf, fill)))
+        got["blocked"] = _bits(dfss.dfss_attention_blocked(Q, K, V, None, bm, s, w.scale,
+                                                           O=_poisoned(o_shape, bf, fill)))
+        got["ragged"] = _bits(dfss.dfss_attention_ragged(Qr, Kr, Vr, None, sr, w.scale,
+                                                         O=_poisoned((s.BH, Lr, s.d), bf, fill)))
+        got["dense"] = _bits(dfss.dense_attention(Q, K, V, s, w.scale, O=_poisoned(o_shape, bf, fill)))
+        got["dense one kernel"] = _bits(dfss.dense_attention_fused(Q, K, V, s, w.scale,
+                                                                   O=_poisoned(o_shape, bf, fill)))
+        dQ, dK, dV = dfss.dfss_attention_backward(dO, Q, K, V, O, vals, meta, s, w.scale,
+                                                  dQ=_poisoned(o_shape, bf, fill), dK=_poisoned(o_shape, bf, fill),
+                                                  dV=_poisoned(o_shape, bf, fill))
+        got["dQ"], got["dK"], got["dV"] = _bits(dQ), _bits(dK), _bits(dV)
         torch.cuda.synchronize()
-        outs.append((vals.view(torch.int16).cpu(), meta.cpu()))
-    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+        outs.append(got)
+    for name in outs[0]:
+        assert torch.equal(outs[0][name], outs[1][name]), name
 
 
 # ----------------------------------------------------------------------------------
