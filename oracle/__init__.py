@@ -73,13 +73,17 @@ def _load():
                                                     c_int, c_int, c_int, c_float, c_int, _f32p]
         L.oracle_attention_bias_batched.restype = c_int
         L.oracle_attention_masked_batched.argtypes = [_f32p, _f32p, _f32p, ctypes.c_void_p, c_int, ctypes.c_void_p,
-                                                      c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_float,
-                                                      c_int, _f32p]
+                                                      ctypes.c_void_p, c_int, c_int, c_int, c_int, c_int, c_int,
+                                                      c_int, c_float, c_int, _f32p]
         L.oracle_attention_masked_batched.restype = c_int
         L.oracle_apply_block_mask.argtypes = [_f32p, c_int, c_int, _u8p, c_int]
         L.oracle_apply_block_mask.restype = c_int
         L.oracle_add_key_bias.argtypes = [_f32p, c_int, c_int, _f32p]
         L.oracle_add_key_bias.restype = None
+        L.oracle_add_mask.argtypes = [_f32p, c_int, c_int, _f32p]
+        L.oracle_add_mask.restype = None
+        L.oracle_causal_mask.argtypes = [c_int, c_int, _f32p]
+        L.oracle_causal_mask.restype = c_int
         L.oracle_attention_backward.argtypes = [_f32p, _f32p, _f32p, _f32p, _f32p, _i32p, c_int, c_int, c_int, c_int,
                                                 c_float, _f32p, _f32p, _f32p, ctypes.c_void_p]
         L.oracle_attention_backward.restype = None
@@ -114,6 +118,23 @@ def add_key_bias(S, bias):
     assert bias.shape == (Lk,)
     _load().oracle_add_key_bias(S, Lq, Lk, bias)
     return S
+
+
+def add_mask(S, mask):
+    """S + mask, both [Lq, Lk] (fp32 add; -inf hides a key from a query)."""
+    S = _f32(S).copy()
+    mask = _f32(mask)
+    assert mask.shape == S.shape, mask.shape
+    _load().oracle_add_mask(S, S.shape[0], S.shape[1], mask)
+    return S
+
+
+def causal_mask(Lq, Lk):
+    """[Lq, Lk] additive mask: 0 where key j <= i + (Lk - Lq) (the queries are the last Lq positions), else -inf."""
+    mask = np.empty((Lq, Lk), np.float32)
+    if _load().oracle_causal_mask(Lq, Lk, mask) != 0:
+        raise ValueError("causal mask needs Lk >= Lq >= 1")
+    return mask
 
 
 def apply_block_mask(S, block_mask, block_size):
@@ -210,13 +231,15 @@ def round_bf16(x):
 
 
 def attention(Q, K, V, N, M, scale, store_bf16=False, key_bias=None, heads_per_batch=1,
-              block_mask=None, block_size=64):
+              block_mask=None, block_size=64, mask=None, causal=False):
     """Whole forward for [BH, L, d] (or [L, d]) inputs; heads run on host threads.
 
     key_bias: optional float32 [BH // heads_per_batch, Lk] (or [Lk] for a single head), added to
     the scaled scores before the N:M selection; -inf masks a key.
     block_mask: optional uint8 [Lq // block_size, Lk // block_size] shared by all heads; blocks with a
     zero entry are not part of the attention (their scores count as -inf).
+    mask: optional float32 [Lq, Lk] shared by all heads, added like the key bias.  causal=True adds
+    causal_mask(Lq, Lk) (on top of ``mask`` if both are given).
     """
     Q, K, V = _f32(Q), _f32(K), _f32(V)
     squeeze = Q.ndim == 2
@@ -225,11 +248,17 @@ def attention(Q, K, V, N, M, scale, store_bf16=False, key_bias=None, heads_per_b
     BH, Lq, d = Q.shape
     Lk = K.shape[1]
     O = np.empty((BH, Lq, d), np.float32)
-    if key_bias is None and block_mask is None:
+    if causal:
+        cm = causal_mask(Lq, Lk)
+        mask = cm if mask is None else (_f32(mask) + cm).astype(np.float32)
+    if key_bias is None and block_mask is None and mask is None:
         rc = _load().oracle_attention_batched(Q, K, V, BH, Lq, Lk, d, N, M, float(scale),
                                               int(bool(store_bf16)), O)
     else:
-        kb = bm = None
+        kb = bm = m2 = None
+        if mask is not None:
+            m2 = _f32(mask)
+            assert m2.shape == (Lq, Lk), m2.shape
         if key_bias is not None:
             kb = _f32(key_bias)
             if kb.ndim == 1:
@@ -240,6 +269,7 @@ def attention(Q, K, V, N, M, scale, store_bf16=False, key_bias=None, heads_per_b
             assert bm.shape == (Lq // block_size, Lk // block_size), bm.shape
         rc = _load().oracle_attention_masked_batched(
             Q, K, V, kb.ctypes.data if kb is not None else None, int(heads_per_batch),
+            m2.ctypes.data if m2 is not None else None,
             bm.ctypes.data if bm is not None else None, int(block_size),
             BH, Lq, Lk, d, N, M, float(scale), int(bool(store_bf16)), O)
     if rc != 0:

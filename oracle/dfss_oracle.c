@@ -26,8 +26,11 @@
  *     comparison, so the comparison sees exactly the value that is stored;
  *   - accumulation of the dot product is fp32, sequential in k (the paper
  *     accumulates in float regardless of input type, App. A.1.2);
- *   - masks are not in the paper: an optional per-key bias is added to the
- *     scaled score in fp32 before the comparison (-inf masks a key);
+ *   - masks are not in the paper: an optional per-key bias, and an optional
+ *     per-(query, key) mask, are added to the scaled score in fp32 before
+ *     the comparison (-inf masks an entry); the causal mask is the
+ *     per-(query, key) mask that hides the keys after the query's own
+ *     position, the queries being the LAST Lq positions of the Lk keys;
  *   - a block of the score matrix pruned by the block pattern (blocked-ELL,
  *     App. A.1.2) acts as if all its scores were -inf;
  *   - position code = lower kept position in bits [1:0], higher in bits [3:2];
@@ -80,6 +83,37 @@ void oracle_add_key_bias(float *S, int Lq, int Lk, const float *bias)
     for (int i = 0; i < Lq; ++i)
         for (int j = 0; j < Lk; ++j)
             S[(size_t)i * Lk + j] = S[(size_t)i * Lk + j] + bias[j];
+}
+
+/* ------------------------------------------------------------------ */
+/* Stage 1a': general additive mask, one term per (query, key):        */
+/* S[i][j] <- S[i][j] + mask[i][j], fp32, BEFORE the N:M comparison    */
+/* (same reading as the key bias: what the comparison sees is what the */
+/* softmax sees).  mask is [Lq][Lk], shared by all heads; -inf hides   */
+/* key j from query i.                                                 */
+/* ------------------------------------------------------------------ */
+void oracle_add_mask(float *S, int Lq, int Lk, const float *mask)
+{
+    for (int i = 0; i < Lq; ++i)
+        for (int j = 0; j < Lk; ++j)
+            S[(size_t)i * Lk + j] = S[(size_t)i * Lk + j] + mask[(size_t)i * Lk + j];
+}
+
+/* The causal mask (decoder self-attention: the paper finetunes and    */
+/* evaluates encoders only, Sec. 5.1; a position must not see later    */
+/* ones) written out as such a mask.  Reading taken for Lq != Lk: the  */
+/* queries are the last Lq of the Lk positions, so query i sits at     */
+/* position i + (Lk - Lq) and sees keys 0 .. i + (Lk - Lq).  Needs     */
+/* Lk >= Lq (every query then sees at least one key).  mask[i][j] = 0  */
+/* for a visible key, -inf for a hidden one.                           */
+int oracle_causal_mask(int Lq, int Lk, float *mask)
+{
+    if (Lq <= 0 || Lk < Lq) return -1;
+    const int off = Lk - Lq;
+    for (int i = 0; i < Lq; ++i)
+        for (int j = 0; j < Lk; ++j)
+            mask[(size_t)i * Lk + j] = j <= i + off ? 0.0f : -INFINITY;
+    return 0;
 }
 
 /* ------------------------------------------------------------------ */
@@ -325,7 +359,7 @@ void oracle_round_bf16_array(const float *x, size_t n, float *y)
 /* before softmax), kidx, P.                                           */
 /* ------------------------------------------------------------------ */
 int oracle_attention_masked(const float *Q, const float *K, const float *V, const float *key_bias,
-                            const uint8_t *block_mask, int block_size,
+                            const float *mask2d, const uint8_t *block_mask, int block_size,
                             int Lq, int Lk, int d, int N, int M, float scale,
                             int store_bf16, float *O,
                             uint8_t *mask_out, float *vals_out, int32_t *kidx_out, float *P_out)
@@ -341,6 +375,7 @@ int oracle_attention_masked(const float *Q, const float *K, const float *V, cons
     if (S && mask && vals && kidx && P) {
         oracle_scores(Q, K, Lq, Lk, d, scale, S);
         if (key_bias) oracle_add_key_bias(S, Lq, Lk, key_bias);   /* NULL = no mask (the paper's case) */
+        if (mask2d) oracle_add_mask(S, Lq, Lk, mask2d);
         rc = block_mask ? oracle_apply_block_mask(S, Lq, Lk, block_mask, block_size) : 0;
         if (rc == 0) rc = oracle_prune(S, Lq, Lk, N, M, mask, vals, kidx);
         if (rc == 0) {
@@ -363,7 +398,7 @@ int oracle_attention_bias(const float *Q, const float *K, const float *V, const 
                           int store_bf16, float *O,
                           uint8_t *mask_out, float *vals_out, int32_t *kidx_out, float *P_out)
 {
-    return oracle_attention_masked(Q, K, V, key_bias, NULL, 0, Lq, Lk, d, N, M, scale, store_bf16, O,
+    return oracle_attention_masked(Q, K, V, key_bias, NULL, NULL, 0, Lq, Lk, d, N, M, scale, store_bf16, O,
                                    mask_out, vals_out, kidx_out, P_out);
 }
 
@@ -372,16 +407,18 @@ int oracle_attention(const float *Q, const float *K, const float *V,
                      int store_bf16, float *O,
                      uint8_t *mask_out, float *vals_out, int32_t *kidx_out, float *P_out)
 {
-    return oracle_attention_masked(Q, K, V, NULL, NULL, 0, Lq, Lk, d, N, M, scale, store_bf16, O,
+    return oracle_attention_masked(Q, K, V, NULL, NULL, NULL, 0, Lq, Lk, d, N, M, scale, store_bf16, O,
                                    mask_out, vals_out, kidx_out, P_out);
 }
 
 /* Heads are independent (App. A.1.2, batched kernel): loop them, in parallel
  * over host threads when built with OpenMP.  Q,K,V,O are [BH][L][d]. */
 /* key_bias (may be NULL) is [BH / heads_per_batch][Lk]: the heads of one batch element share
- * one bias vector (a padding mask belongs to the sequence, not to the head). */
+ * one bias vector (a padding mask belongs to the sequence, not to the head).  mask2d (may be NULL) is
+ * [Lq][Lk], shared by all heads. */
 int oracle_attention_masked_batched(const float *Q, const float *K, const float *V, const float *key_bias,
-                                    int heads_per_batch, const uint8_t *block_mask, int block_size,
+                                    int heads_per_batch, const float *mask2d,
+                                    const uint8_t *block_mask, int block_size,
                                     int BH, int Lq, int Lk, int d, int N, int M,
                                     float scale, int store_bf16, float *O)
 {
@@ -392,7 +429,7 @@ int oracle_attention_masked_batched(const float *Q, const float *K, const float 
     for (int h = 0; h < BH; ++h) {
         const float *bias = key_bias ? key_bias + (size_t)(h / heads_per_batch) * Lk : NULL;
         int rc = oracle_attention_masked(Q + (size_t)h * Lq * d, K + (size_t)h * Lk * d,
-                                         V + (size_t)h * Lk * d, bias, block_mask, block_size,
+                                         V + (size_t)h * Lk * d, bias, mask2d, block_mask, block_size,
                                          Lq, Lk, d, N, M, scale,
                                          store_bf16, O + (size_t)h * Lq * d,
                                          NULL, NULL, NULL, NULL);
@@ -410,7 +447,7 @@ int oracle_attention_bias_batched(const float *Q, const float *K, const float *V
                                   int heads_per_batch, int BH, int Lq, int Lk, int d, int N, int M,
                                   float scale, int store_bf16, float *O)
 {
-    return oracle_attention_masked_batched(Q, K, V, key_bias, heads_per_batch, NULL, 0, BH, Lq, Lk, d, N, M,
+    return oracle_attention_masked_batched(Q, K, V, key_bias, heads_per_batch, NULL, NULL, 0, BH, Lq, Lk, d, N, M,
                                            scale, store_bf16, O);
 }
 
@@ -418,7 +455,7 @@ int oracle_attention_batched(const float *Q, const float *K, const float *V,
                              int BH, int Lq, int Lk, int d, int N, int M,
                              float scale, int store_bf16, float *O)
 {
-    return oracle_attention_masked_batched(Q, K, V, NULL, 1, NULL, 0, BH, Lq, Lk, d, N, M, scale, store_bf16, O);
+    return oracle_attention_masked_batched(Q, K, V, NULL, 1, NULL, NULL, 0, BH, Lq, Lk, d, N, M, scale, store_bf16, O);
 }
 
 /* ------------------------------------------------------------------ */
