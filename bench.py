@@ -80,6 +80,9 @@ def parse_args():
     ap.add_argument("--block-pattern", action="store_true",
                     help="headline only: run the block-masked entry points with a seeded window + global + random "
                          "pattern of 64 x 64 blocks (one-kernel paths only; FLOPs are counted on the kept blocks)")
+    ap.add_argument("--causal", action="store_true",
+                    help="headline only: run the causal entry points (query i sees keys 0 .. i; FLOPs are counted on "
+                         "the visible half of the score matrix)")
     ap.add_argument("--backward", action="store_true",
                     help="headline only: also time dfss_attention_backward on the results of the three forward stages")
     ap.add_argument("--unpadded", type=int, default=0, metavar="LEN",
@@ -181,9 +184,15 @@ def run_workload(name, args, timer, torch, dfss, synth, headline):
         density = float(bm.float().mean())
         block_mask = bm.to(dev)
 
+    causal = bool(headline and args.causal)
+    if causal:
+        density = (L + 1) / (2.0 * L)      # visible entries of the score matrix
+
     def step_sparse(i):
         b = sets[i % nsets]
-        if block_mask is not None:
+        if causal:
+            dfss.dfss_attention_causal(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"])
+        elif block_mask is not None:
             dfss.dfss_attention_blocked(b["Q"], b["K"], b["V"], bias, block_mask, s, w.scale, O=b["O"])
         elif has_fused:
             dfss.dfss_attention_bias(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"])
@@ -192,18 +201,22 @@ def run_workload(name, args, timer, torch, dfss, synth, headline):
 
     def step_dense_fused(i):
         b = sets[i % nsets]
-        if block_mask is not None:
+        if causal:
+            dfss.dense_attention_fused_causal(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"])
+        elif block_mask is not None:
             dfss.dense_attention_fused_blocked(b["Q"], b["K"], b["V"], bias, block_mask, s, w.scale, O=b["O"])
         else:
             dfss.dense_attention_fused_bias(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"])
 
     def step_staged(i):
         b = sets[i % nsets]
-        dfss.dfss_attention_staged_bias(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"], ws=wss[i % nws])
+        fn = dfss.dfss_attention_staged_causal if causal else dfss.dfss_attention_staged_bias
+        fn(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"], ws=wss[i % nws])
 
     def step_dense(i):
         b = sets[i % nsets]
-        dfss.dense_attention_bias(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"], ws=wss[i % nws])
+        fn = dfss.dense_attention_causal if causal else dfss.dense_attention_bias
+        fn(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"], ws=wss[i % nws])
 
     n_vals, n_meta = dfss.dfss_vals_bytes(s), dfss.dfss_meta_bytes(s)
     meta_at = (n_vals + 255) // 256 * 256
@@ -216,7 +229,8 @@ def run_workload(name, args, timer, torch, dfss, synth, headline):
     def step_stage1(i):
         b = sets[i % nsets]
         vals, meta = stage_buffers(i)
-        dfss.dfss_sddmm_prune_bias(b["Q"], b["K"], bias, s, w.scale, vals=vals, meta=meta)
+        fn = dfss.dfss_sddmm_prune_causal if causal else dfss.dfss_sddmm_prune_bias
+        fn(b["Q"], b["K"], bias, s, w.scale, vals=vals, meta=meta)
 
     def step_stage2(i):
         dfss.dfss_sparse_softmax(stage_buffers(i)[0], s)
@@ -309,6 +323,9 @@ def main():
         print(f"bench.py: unknown workload {args.workload}", file=sys.stderr)
         sys.exit(2)
     wl = synth.WORKLOADS[args.workload]
+    if args.causal and (wl.float32 or args.block_pattern):
+        print("bench.py: --causal runs the 2-byte workloads, without --block-pattern", file=sys.stderr)
+        sys.exit(2)
     if wl.float32 and args.products == "fp32" and (args.backward or args.key_padding or args.block_pattern or args.unpadded):
         print("bench.py: with --products fp32 the float workloads run the plain forward pass only", file=sys.stderr)
         sys.exit(2)
@@ -338,7 +355,7 @@ def main():
             del ctx_other
             torch.cuda.empty_cache()
     head, ctx = run_workload(args.workload, args, timer, torch, dfss, synth, headline=True)
-    if not args.no_sweep and args.workload in SWEEP and not (args.key_padding or args.block_pattern):
+    if not args.no_sweep and args.workload in SWEEP and not (args.key_padding or args.block_pattern or args.causal):
         sweep[args.workload] = head
     w, s, sets = ctx["w"], ctx["s"], ctx["sets"]
     bias, block_mask = ctx["bias"], ctx["block_mask"]
@@ -354,12 +371,14 @@ def main():
     ms_direct = (time.perf_counter() - t0) / K * 1e3
 
     flops_alg = ctx["flops_alg"]
-    traffic = TRAFFIC_FROM_PROFILES.get(w.name) if not (args.key_padding or args.block_pattern or f32) else None
+    plain = not (args.key_padding or args.block_pattern or args.causal or f32)
+    traffic = TRAFFIC_FROM_PROFILES.get(w.name) if plain else None
     if has_fused:
         # one kernel per step: the step time between the events IS the kernel's average launch duration
         roofline = {"bound": "mfma",
                     "kernel": ("k_fused_split (dfss_attention, float data, bf16x3 products)" if f32 else
-                               "k_fused32 (dfss_attention, one kernel per step)"),
+                               "k_fused32 (dfss_attention, one kernel per step)" if plain else
+                               "k_fused (the masked one-kernel path, one kernel per step)"),
                     "achieved": round(flops_alg / (ms * 1e-3) / 1e12, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(flops_alg / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                     "traffic": None if traffic is None else traffic[0],
@@ -397,7 +416,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "L": L, "d": d, "N": w.N, "M": w.M,
                    "products": (args.products if f32 else "bf16"),
-                   "key_padding": bool(args.key_padding),
+                   "key_padding": bool(args.key_padding), "causal": bool(args.causal),
                    "block_pattern": (f"window +-1, 1 global, 2 random blocks of 64 x 64, density {ctx['density']:.3f}"
                                      if args.block_pattern else None),
                    "buffer_sets": head["buffer_sets"], "workspace_sets": head["workspace_sets"],
@@ -413,7 +432,8 @@ def main():
         b = sets[0]
         vals = torch.empty((BH, L, s.Lc), dtype=s.torch_dtype, device=dev)
         meta = torch.empty((BH * L * s.meta_words,), dtype=torch.int16, device=dev)
-        dfss.dfss_sddmm_prune_bias(b["Q"], b["K"], bias, s, w.scale, vals=vals, meta=meta)
+        fn = dfss.dfss_sddmm_prune_causal if causal else dfss.dfss_sddmm_prune_bias
+        fn(b["Q"], b["K"], bias, s, w.scale, vals=vals, meta=meta)
         dfss.dfss_sparse_softmax(vals, s)
         O_fwd = dfss.dfss_spmm(vals, meta, b["V"], s)
         dO = torch.randn(BH, L, d, device=dev).to(s.torch_dtype)

@@ -170,6 +170,36 @@ dfss_status dense_attention_bias(const void *Q, const void *K, const void *V, co
 dfss_status dense_attention_fused_bias(const void *Q, const void *K, const void *V, const void *key_bias,
                                        const dfss_shape *s, float scale, void *O, void *stream);
 
+/* ---- causal mask ---------------------------------------------------------------------- */
+/* The paper evaluates encoders only (Sec. 5.1) and has no mask; a decoder needs one.  Reading taken:
+ * the queries are the LAST Lq of the Lk positions (Lk >= Lq, else DFSS_ERR_SHAPE), so query i sits at
+ * position i + (Lk - Lq) and sees keys 0 .. i + (Lk - Lq); the score of a hidden key counts as -inf
+ * BEFORE the N:M comparison of stage 1 (the same place as the key bias), so a hidden key loses against
+ * any visible key of its run of M, and a run that is entirely hidden still emits N entries, whose
+ * softmax weight is exactly 0.  Every query sees at least key 0.  No mask array: the kernels derive
+ * the hidden entries from the indices.  key_bias (may be NULL) is added as in the *_bias calls.
+ * 2-byte dtype only (DFSS_ERR_UNSUPPORTED otherwise).
+ *   dfss_sddmm_prune_causal       stage 1; the hidden entries are part of vals / meta (stages 2 and 3 are
+ *                                 the plain calls)
+ *   dfss_attention_causal         the whole forward pass in one kernel; blocks of 64 keys past the last
+ *                                 visible key of a workgroup's queries are skipped (neither read nor
+ *                                 computed)
+ *   dfss_attention_staged_causal  the same through the workspace (as dfss_attention_staged)
+ *   dense_attention_causal, dense_attention_fused_causal   Eq. 1 with the same mask (the baselines)
+ * All other arguments, layouts and error behaviour are those of the calls without the suffix. */
+dfss_status dfss_sddmm_prune_causal(const void *Q, const void *K, const void *key_bias, const dfss_shape *s,
+                                    float scale, void *vals, void *meta, void *stream);
+dfss_status dfss_attention_causal(const void *Q, const void *K, const void *V, const void *key_bias,
+                                  const dfss_shape *s, float scale, void *O, void *stream);
+dfss_status dfss_attention_staged_causal(const void *Q, const void *K, const void *V, const void *key_bias,
+                                         const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes,
+                                         void *stream);
+dfss_status dense_attention_causal(const void *Q, const void *K, const void *V, const void *key_bias,
+                                   const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes,
+                                   void *stream);
+dfss_status dense_attention_fused_causal(const void *Q, const void *K, const void *V, const void *key_bias,
+                                         const dfss_shape *s, float scale, void *O, void *stream);
+
 /* ---- hybrid block sparsity x N:M (App. A.1.2, "Blocked-ELL Sparsity") ---------------- */
 /* block_mask: device, uint8 [Lq/64, Lk/64] row-major, shared by all B*H heads.  A 64 x 64 block
  * of the score matrix whose entry is zero is not part of the attention: it is skipped (neither

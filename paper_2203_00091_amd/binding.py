@@ -26,6 +26,8 @@ EXPORTS = (
     "dfss_attention_ragged", "dense_attention_fused_ragged",
     "dfss_attention_staged", "dfss_attention_staged_bias",
     "dfss_static_scratch_bytes", "dfss_attention_staged_static",
+    "dfss_sddmm_prune_causal", "dfss_attention_causal", "dfss_attention_staged_causal", "dense_attention_causal",
+    "dense_attention_fused_causal",
 )
 # exported for the library's own tests only (csrc/dfss_internal.h)
 INTERNAL_EXPORTS = ("dfss_internal_attention_variant",)
@@ -115,6 +117,11 @@ def load_library():
         L.dfss_attention_staged.argtypes = [vp, vp, vp, sp, f32, vp, vp, sz, vp]
         L.dfss_attention_staged_bias.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
         L.dfss_attention_staged_static.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
+        L.dfss_sddmm_prune_causal.argtypes = [vp, vp, vp, sp, f32, vp, vp, vp]
+        L.dfss_attention_causal.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
+        L.dfss_attention_staged_causal.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
+        L.dense_attention_causal.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
+        L.dense_attention_fused_causal.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_attention_staged_static.restype = ctypes.c_int
         L.dfss_static_scratch_bytes.argtypes = []
         L.dfss_static_scratch_bytes.restype = sz
@@ -130,7 +137,8 @@ def load_library():
                      "dense_attention_fused_bias", "dfss_attention_blocked", "dense_attention_fused_blocked",
                      "dfss_attention_ragged", "dense_attention_fused_ragged", "dfss_spmm_t",
                      "dfss_attention_backward", "dfss_attention_staged", "dfss_attention_staged_bias",
-                     "dfss_internal_attention_variant"):
+                     "dfss_internal_attention_variant", "dfss_sddmm_prune_causal", "dfss_attention_causal",
+                     "dfss_attention_staged_causal", "dense_attention_causal", "dense_attention_fused_causal"):
             getattr(L, name).restype = ctypes.c_int
         L.dfss_status_string.argtypes = [ctypes.c_int]
         L.dfss_status_string.restype = ctypes.c_char_p
@@ -382,6 +390,64 @@ def dense_attention_fused_bias(Q, K, V, key_bias, s: Shape, scale: float, O=None
     st = load_library().dense_attention_fused_bias(_q(Q, s), _kv(K, s), _kv(V, s), _bias_ptr(key_bias, s),
                                                    ctypes.byref(s.c()), scale, _q(O, s), _stream())
     _check("dense_attention_fused_bias", st)
+    return O
+
+
+def dfss_sddmm_prune_causal(Q, K, key_bias, s: Shape, scale: float, vals=None, meta=None):
+    """Stage 1 under the causal mask (query i sees keys 0 .. i + Lk - Lq); key_bias may be None."""
+    if vals is None:
+        vals = torch.empty((s.BH, s.Lq, s.Lc), dtype=s.torch_dtype, device=Q.device)
+    if meta is None:
+        meta = torch.empty((s.BH * s.Lq * s.meta_words,), dtype=torch.int16, device=Q.device)
+    st = load_library().dfss_sddmm_prune_causal(_q(Q, s), _kv(K, s), _bias_ptr(key_bias, s),
+                                                ctypes.byref(s.c()), scale, _kept(vals, s), _meta(meta, s), _stream())
+    _check("dfss_sddmm_prune_causal", st)
+    return vals, meta
+
+
+def dfss_attention_causal(Q, K, V, key_bias, s: Shape, scale: float, O=None):
+    """Whole DFSS forward in one kernel under the causal mask; key_bias may be None."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    st = load_library().dfss_attention_causal(_q(Q, s), _kv(K, s), _kv(V, s), _bias_ptr(key_bias, s),
+                                              ctypes.byref(s.c()), scale, _q(O, s), _stream())
+    _check("dfss_attention_causal", st)
+    return O
+
+
+def dfss_attention_staged_causal(Q, K, V, key_bias, s: Shape, scale: float, O=None, ws=None):
+    """dfss_attention_staged under the causal mask; key_bias may be None."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    if ws is None:
+        ws = _alloc_bytes(dfss_workspace_bytes(s), Q.device)
+    st = load_library().dfss_attention_staged_causal(_q(Q, s), _kv(K, s), _kv(V, s), _bias_ptr(key_bias, s),
+                                                     ctypes.byref(s.c()), scale, _q(O, s), _ptr(ws),
+                                                     ws.numel() * ws.element_size(), _stream())
+    _check("dfss_attention_staged_causal", st)
+    return O
+
+
+def dense_attention_causal(Q, K, V, key_bias, s: Shape, scale: float, O=None, ws=None):
+    """Full attention (three stages) under the causal mask; key_bias may be None."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    if ws is None:
+        ws = _alloc_bytes(dense_workspace_bytes(s), Q.device)
+    st = load_library().dense_attention_causal(_q(Q, s), _kv(K, s), _kv(V, s), _bias_ptr(key_bias, s),
+                                               ctypes.byref(s.c()), scale, _q(O, s), _ptr(ws),
+                                               ws.numel() * ws.element_size(), _stream())
+    _check("dense_attention_causal", st)
+    return O
+
+
+def dense_attention_fused_causal(Q, K, V, key_bias, s: Shape, scale: float, O=None):
+    """Full attention in one kernel under the causal mask; key_bias may be None."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    st = load_library().dense_attention_fused_causal(_q(Q, s), _kv(K, s), _kv(V, s), _bias_ptr(key_bias, s),
+                                                     ctypes.byref(s.c()), scale, _q(O, s), _stream())
+    _check("dense_attention_fused_causal", st)
     return O
 
 

@@ -113,20 +113,38 @@ size_t dense_workspace_bytes(const dfss_shape *s) {
     return align_up((size_t)D.BH * D.Lq * D.Lk * D.elem());
 }
 
-dfss_status dfss_sddmm_prune_bias(const void *Q, const void *K, const void *key_bias, const dfss_shape *s,
-                                  float scale, void *vals, void *meta, void *stream) {
+// causal: query i sees keys 0 .. i + (Lk - Lq); needs Lk >= Lq and a 2-byte dtype
+static dfss_status bad_causal(const Dims &D) {
+    if (D.f32) return DFSS_ERR_UNSUPPORTED;
+    return D.Lk >= D.Lq ? DFSS_OK : DFSS_ERR_SHAPE;
+}
+
+static dfss_status sddmm_prune(const void *Q, const void *K, const void *key_bias, const dfss_shape *s, float scale,
+                               void *vals, void *meta, void *stream, bool causal) {
     Dims D;
     if (!Q || !K || !vals || !meta) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, true, &D)) return st;
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
     if (misaligned(Q) || misaligned(K) || misaligned(vals) || misaligned(meta) || misaligned(key_bias))
         return DFSS_ERR_SHAPE;
+    if (causal)
+        if (dfss_status st = bad_causal(D)) return st;
     if (D.f32) {
         if (key_bias && !D.split) return DFSS_ERR_UNSUPPORTED;
         return hip_status(sddmm_prune_f32(D, Q, K, (const float *)key_bias, scale, vals, meta, (hipStream_t)stream));
     }
-    return hip_status(dfss::launch_sddmm_prune(Q, K, (const float *)key_bias, D.H, D.BH, D.Lq, D.Lk, D.d, D.mode,
-                                               scale, vals, meta, (hipStream_t)stream));
+    return hip_status(dfss::launch_sddmm_prune(Q, K, (const float *)key_bias, D.H, causal, D.BH, D.Lq, D.Lk, D.d,
+                                               D.mode, scale, vals, meta, (hipStream_t)stream));
+}
+
+dfss_status dfss_sddmm_prune_bias(const void *Q, const void *K, const void *key_bias, const dfss_shape *s,
+                                  float scale, void *vals, void *meta, void *stream) {
+    return sddmm_prune(Q, K, key_bias, s, scale, vals, meta, stream, false);
+}
+
+dfss_status dfss_sddmm_prune_causal(const void *Q, const void *K, const void *key_bias, const dfss_shape *s,
+                                    float scale, void *vals, void *meta, void *stream) {
+    return sddmm_prune(Q, K, key_bias, s, scale, vals, meta, stream, true);
 }
 
 dfss_status dfss_sddmm_prune(const void *Q, const void *K, const dfss_shape *s, float scale, void *vals,
@@ -157,13 +175,15 @@ dfss_status dfss_spmm(const void *vals, const void *meta, const void *V, const d
 // (the exact-product float mode has no one-kernel path and always takes the stages).
 static dfss_status attention_forward(const void *Q, const void *K, const void *V, const void *key_bias,
                                      const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes, void *stream,
-                                     bool staged, int variant) {
+                                     bool staged, int variant, bool causal = false) {
     Dims D;
     if (!Q || !K || !V || !O) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, true, &D)) return st;
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias))
         return DFSS_ERR_SHAPE;
+    if (causal)
+        if (dfss_status cs = bad_causal(D)) return cs;
     if (D.f32 && !D.split) {
         if (key_bias) return DFSS_ERR_UNSUPPORTED;
         staged = true;
@@ -174,8 +194,8 @@ static dfss_status attention_forward(const void *Q, const void *K, const void *V
         if (D.f32)
             return hip_status(dfss::launch_fused_attention_split(Q, K, V, bias, D.H, nullptr, D.BH, D.Lq, D.Lk, D.d, true,
                                                                  scale, O, st));
-        return hip_status(dfss::launch_fused_attention(Q, K, V, bias, D.H, nullptr, D.BH, D.Lq, D.Lk, D.d, D.mode, scale,
-                                                       O, variant, st));
+        return hip_status(dfss::launch_fused_attention(Q, K, V, bias, D.H, nullptr, causal, D.BH, D.Lq, D.Lk, D.d, D.mode,
+                                                       scale, O, variant, st));
     }
     if (!ws) return DFSS_ERR_NULL;
     if ((reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0) return DFSS_ERR_SHAPE;
@@ -189,7 +209,8 @@ static dfss_status attention_forward(const void *Q, const void *K, const void *V
         return hip_status(e);
     }
     // two kernels: the kept scores go to the workspace once and the product applies the softmax as it reads them
-    hipError_t e = dfss::launch_sddmm_prune(Q, K, bias, D.H, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, vals, meta, st);
+    hipError_t e =
+        dfss::launch_sddmm_prune(Q, K, bias, D.H, causal, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, vals, meta, st);
     if (e == hipSuccess) e = dfss::launch_softmax_spmm(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, st);
     return hip_status(e);
 }
@@ -213,6 +234,17 @@ dfss_status dfss_attention_staged_bias(const void *Q, const void *K, const void 
 dfss_status dfss_attention_staged(const void *Q, const void *K, const void *V, const dfss_shape *s, float scale,
                                   void *O, void *ws, size_t ws_bytes, void *stream) {
     return attention_forward(Q, K, V, nullptr, s, scale, O, ws, ws_bytes, stream, true, 0);
+}
+
+dfss_status dfss_attention_causal(const void *Q, const void *K, const void *V, const void *key_bias,
+                                  const dfss_shape *s, float scale, void *O, void *stream) {
+    return attention_forward(Q, K, V, key_bias, s, scale, O, nullptr, 0, stream, false, 0, true);
+}
+
+dfss_status dfss_attention_staged_causal(const void *Q, const void *K, const void *V, const void *key_bias,
+                                         const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes,
+                                         void *stream) {
+    return attention_forward(Q, K, V, key_bias, s, scale, O, ws, ws_bytes, stream, true, 0, true);
 }
 
 // ---- the staged forward pass for callers that cannot allocate ------------------------------------
@@ -263,25 +295,37 @@ dfss_status dfss_internal_attention_variant(const void *Q, const void *K, const 
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias)) return DFSS_ERR_SHAPE;
     if (D.f32) return DFSS_ERR_UNSUPPORTED;
-    return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, nullptr, D.BH, D.Lq, D.Lk,
+    return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, nullptr, 0, D.BH, D.Lq, D.Lk,
                                                    D.d, 2, scale, O, variant, (hipStream_t)stream));
 }
 
-dfss_status dense_attention_fused_bias(const void *Q, const void *K, const void *V, const void *key_bias,
-                                       const dfss_shape *s, float scale, void *O, void *stream) {
+static dfss_status dense_fused(const void *Q, const void *K, const void *V, const void *key_bias, const dfss_shape *s,
+                               float scale, void *O, void *stream, bool causal) {
     Dims D;
     if (!Q || !K || !V || !O) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, false, &D)) return st;
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias))
         return DFSS_ERR_SHAPE;
+    if (causal)
+        if (dfss_status st = bad_causal(D)) return st;
     if (D.f32) {
         if (!D.split) return DFSS_ERR_UNSUPPORTED;
         return hip_status(dfss::launch_fused_attention_split(Q, K, V, (const float *)key_bias, D.H, nullptr, D.BH, D.Lq,
                                                              D.Lk, D.d, false, scale, O, (hipStream_t)stream));
     }
-    return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, nullptr, D.BH, D.Lq, D.Lk,
-                                                   D.d, 2, scale, O, 0, (hipStream_t)stream));
+    return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, nullptr, causal, D.BH, D.Lq,
+                                                   D.Lk, D.d, 2, scale, O, 0, (hipStream_t)stream));
+}
+
+dfss_status dense_attention_fused_bias(const void *Q, const void *K, const void *V, const void *key_bias,
+                                       const dfss_shape *s, float scale, void *O, void *stream) {
+    return dense_fused(Q, K, V, key_bias, s, scale, O, stream, false);
+}
+
+dfss_status dense_attention_fused_causal(const void *Q, const void *K, const void *V, const void *key_bias,
+                                         const dfss_shape *s, float scale, void *O, void *stream) {
+    return dense_fused(Q, K, V, key_bias, s, scale, O, stream, true);
 }
 
 dfss_status dense_attention_fused(const void *Q, const void *K, const void *V, const dfss_shape *s, float scale,
@@ -289,8 +333,8 @@ dfss_status dense_attention_fused(const void *Q, const void *K, const void *V, c
     return dense_attention_fused_bias(Q, K, V, nullptr, s, scale, O, stream);
 }
 
-dfss_status dense_attention_bias(const void *Q, const void *K, const void *V, const void *key_bias,
-                                 const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes, void *stream) {
+static dfss_status dense_staged(const void *Q, const void *K, const void *V, const void *key_bias, const dfss_shape *s,
+                                float scale, void *O, void *ws, size_t ws_bytes, void *stream, bool causal) {
     Dims D;
     if (!Q || !K || !V || !O || !ws) return DFSS_ERR_NULL;
     if (dfss_status st = check_shape(s, false, &D)) return st;
@@ -299,6 +343,8 @@ dfss_status dense_attention_bias(const void *Q, const void *K, const void *V, co
         return DFSS_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0) return DFSS_ERR_SHAPE;
     if (ws_bytes < dense_workspace_bytes(s)) return DFSS_ERR_WORKSPACE;
+    if (causal)
+        if (dfss_status cs = bad_causal(D)) return cs;
     hipStream_t st = (hipStream_t)stream;
     if (D.f32) {
         if (key_bias && !D.split) return DFSS_ERR_UNSUPPORTED;
@@ -311,10 +357,21 @@ dfss_status dense_attention_bias(const void *Q, const void *K, const void *V, co
                         : dfss::launch_dense_av_f32(ws, V, D.BH, D.Lq, D.Lk, D.d, O, st);
         return hip_status(e);
     }
-    hipError_t e = dfss::launch_dense_scores(Q, K, (const float *)key_bias, D.H, D.BH, D.Lq, D.Lk, D.d, scale, ws, st);
+    hipError_t e =
+        dfss::launch_dense_scores(Q, K, (const float *)key_bias, D.H, causal, D.BH, D.Lq, D.Lk, D.d, scale, ws, st);
     if (e == hipSuccess) e = dfss::launch_row_softmax(ws, (long)D.BH * D.Lq, D.Lk, st);
     if (e == hipSuccess) e = dfss::launch_dense_av(ws, V, D.BH, D.Lq, D.Lk, D.d, O, st);
     return hip_status(e);
+}
+
+dfss_status dense_attention_bias(const void *Q, const void *K, const void *V, const void *key_bias,
+                                 const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes, void *stream) {
+    return dense_staged(Q, K, V, key_bias, s, scale, O, ws, ws_bytes, stream, false);
+}
+
+dfss_status dense_attention_causal(const void *Q, const void *K, const void *V, const void *key_bias,
+                                   const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes, void *stream) {
+    return dense_staged(Q, K, V, key_bias, s, scale, O, ws, ws_bytes, stream, true);
 }
 
 dfss_status dense_attention(const void *Q, const void *K, const void *V, const dfss_shape *s, float scale, void *O,
@@ -339,7 +396,7 @@ static dfss_status attention_blocked(const void *Q, const void *K, const void *V
                                                              scale, O, (hipStream_t)stream));
     }
     return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, (const uint8_t *)block_mask,
-                                                   D.BH, D.Lq, D.Lk, D.d, dense ? 2 : D.mode, scale, O, 0,
+                                                   0, D.BH, D.Lq, D.Lk, D.d, dense ? 2 : D.mode, scale, O, 0,
                                                    (hipStream_t)stream));
 }
 
@@ -366,7 +423,7 @@ static dfss_status attention_ragged(const void *Q, const void *K, const void *V,
     if (D.split)
         return hip_status(dfss::launch_fused_attention_split(Q, K, V, (const float *)key_bias, D.H, nullptr, D.BH, D.Lq,
                                                              D.Lk, D.d, !dense, scale, O, (hipStream_t)stream));
-    return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, nullptr, D.BH, D.Lq, D.Lk,
+    return hip_status(dfss::launch_fused_attention(Q, K, V, (const float *)key_bias, D.H, nullptr, 0, D.BH, D.Lq, D.Lk,
                                                    D.d, dense ? 2 : D.mode, scale, O, 0, (hipStream_t)stream));
 }
 

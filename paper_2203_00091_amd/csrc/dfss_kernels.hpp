@@ -9,10 +9,10 @@ namespace dfss {
 // key_bias (where present): fp32 [BH / H][Lk] added to the scaled scores before the selection, or
 // nullptr for none (then H is ignored).
 // Stage 1 (Sec. 3.4, App. A.1.2): scores + N:M pruning epilogue.  mode: 0 = 2:4, 1 = 1:2.
-hipError_t launch_sddmm_prune(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
+hipError_t launch_sddmm_prune(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq, int Lk,
                               int d, int mode, float scale, void *vals, void *meta, hipStream_t st);
 // Dense scores S = scale * Q K^T stored as bfloat16 [BH, Lq, Lk] (Eq. 1), same mainloop.
-hipError_t launch_dense_scores(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
+hipError_t launch_dense_scores(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq, int Lk,
                                int d, float scale, void *S, hipStream_t st);
 // Row softmax in place over bfloat16 rows (App. A.1.3); rows of `cols` elements.
 hipError_t launch_row_softmax(void *x, long rows, int cols, hipStream_t st);
@@ -29,7 +29,7 @@ hipError_t launch_dense_av(const void *P, const void *V, int BH, int Lq, int Lk,
 // block_mask: uint8 [Lq/64][Lk/64] shared by all heads (zero = block not part of the attention), or nullptr.
 // variant: a DFSS_VARIANT_* tiling (dfss_internal.h), 0 = chosen from the shape.
 hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, const float *key_bias, int H,
-                                  const uint8_t *block_mask, int BH, int Lq, int Lk, int d, int mode, float scale,
+                                  const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, int mode, float scale,
                                   void *O, int variant, hipStream_t st);
 // Transposed sparse product out[BH, Lk, d] = A^T X for compressed A (vals + metadata) and X bf16 [BH, Lq, d]:
 // dV = P^T dO and dK = dS^T Q of the backward pass.

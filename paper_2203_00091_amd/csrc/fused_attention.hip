@@ -59,11 +59,16 @@ __device__ __forceinline__ uint64_t any_of_4(uint64_t m) {
 //   block_mask uint8 [Lq/64][Lk/64], shared by all heads: 64 x 64 blocks of the score matrix with a zero
 //              entry are not part of the attention (hybrid blocked-ELL x N:M sparsity, App. A.1.2: the
 //              block equals the workgroup tile and pruned blocks are skipped).  Needs 64-query workgroups.
+//   causal     (MASKED kernels only) non-zero: query i sees keys 0 .. i + (Lk - Lq) (the queries are the last Lq
+//              positions; Lk >= Lq).  The hidden scores count as -inf before the selection.  No array: blocks
+//              past the last visible key of the workgroup's queries are skipped like pruned blocks, and in
+//              the blocks that the diagonal of some query of the workgroup cuts the hidden scores are
+//              overwritten by index.
 template <int D, int MODE, int NQ, bool PRESCALE, bool MASKED, bool RAGGED = false>
 __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
                                                  const __bf16 *__restrict__ V, const float *__restrict__ key_bias,
-                                                 int H, const uint8_t *__restrict__ block_mask, int Lq, int Lk,
-                                                 float scale, uint16_t *__restrict__ O) {
+                                                 int H, const uint8_t *__restrict__ block_mask, int causal, int Lq,
+                                                 int Lk, float scale, uint16_t *__restrict__ O) {
     constexpr int CPR = D / 8;          // 16-byte chunks per row
     constexpr int TILE = KB * CPR;      // chunks per K (or V) block
     constexpr int LPT = TILE / NT;      // direct-to-LDS loads per thread per block and operand
@@ -80,12 +85,14 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
 
     const unsigned qtiles = (Lq + TQ - 1) / TQ;
     int qt, bh;
-    if (MASKED && block_mask) {
+    if (MASKED && (block_mask || causal)) {
         // Row blocks of a block pattern differ widely in work (rows that see every key next to rows
         // that see a window), and the heavy ones usually come first: hand out row block 0 of every
         // head, then row block 1, ... in launch order, so that the long workgroups start at once.
+        // Under the causal mask the work grows with the row block: the last one of every head goes first.
         const unsigned heads = gridDim.x / qtiles;
         qt = blockIdx.x / heads;
+        if (causal && !block_mask) qt = qtiles - 1 - qt;
         bh = blockIdx.x % heads;
     } else {
         const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
@@ -95,6 +102,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
     const int q0 = qt * TQ + w * 16 * NQ;
     const int nblocks = (Lk + KB - 1) / KB;
     const int tail_keys = Lk - (nblocks - 1) * KB;   // keys of the last block (KB unless the lengths are ragged)
+    const int coff = Lk - Lq;                        // causal: query i sits at position i + coff
 
     const __bf16 *Kh = K + (size_t)bh * Lk * D;
     const __bf16 *Vh = V + (size_t)bh * Lk * D;
@@ -248,6 +256,20 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
             if (nblocks <= 64) bias_lo |= 1ull << (nblocks - 1);
             else bias_hi |= 1ull << (nblocks - 65);
         }
+        if (causal) {
+            // the workgroup's queries qt TQ .. see keys up to (their index) + coff: blocks past the last query's
+            // diagonal hold nothing; blocks from the first query's diagonal on are cut for some query
+            // (qt comes out of an integer division, which runs on the vector unit: back to a scalar, so that the
+            // block list stays in scalar registers)
+            const int qt0 = __builtin_amdgcn_readfirstlane(qt) * TQ;
+            const int q_hi = (qt0 + TQ - 1 < Lq ? qt0 + TQ - 1 : Lq - 1) + coff;
+            const int last_blk = q_hi / KB, first_cut = (qt0 + coff + 1) / KB;   // block of the first hidden key
+            if (last_blk < 63) live_lo &= (2ull << last_blk) - 1ull, live_hi = 0ull;
+            else if (last_blk == 63) live_hi = 0ull;
+            else if (last_blk < 127) live_hi &= (2ull << (last_blk - 64)) - 1ull;
+            if (first_cut < 64) bias_lo |= ~0ull << first_cut, bias_hi = ~0ull;
+            else if (first_cut < 128) bias_hi |= ~0ull << (first_cut - 64);
+        }
     }
     // The blocks still to visit, as a list that is consumed: take the smallest one off (or return nblocks).
     // Without masks it is a plain counter.
@@ -316,7 +338,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
                     else if (brow) kb4[t] = *reinterpret_cast<const f32x4 *>(brow + key);
                     else kb4[t] = f32x4{0.f, 0.f, 0.f, 0.f};
                 } else {
-                    kb4[t] = *reinterpret_cast<const f32x4 *>(brow + key);
+                    kb4[t] = brow ? *reinterpret_cast<const f32x4 *>(brow + key) : f32x4{0.f, 0.f, 0.f, 0.f};
                 }
             }
             if constexpr (PRESCALE) {
@@ -337,6 +359,21 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
                 for (int qs = 0; qs < NQ; ++qs)
 #pragma unroll
                     for (int t = 0; t < 4; ++t) acc[qs][t] = acc[qs][t] * scale;
+            }
+        }
+
+        if constexpr (MASKED) {
+            // causal: the scores of keys after the query's own position count as -inf
+            if (causal && KB * jb + KB - 1 > q0 + coff) {   // (the wave's first query already has hidden keys here)
+#pragma unroll
+                for (int qs = 0; qs < NQ; ++qs) {
+                    const int lim = q0 + 16 * qs + li + coff - (KB * jb + 16 * kb);   // key offsets above it are hidden
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            if (4 * t + r > lim) acc[qs][t][r] = -INFINITY;
+                }
             }
         }
 
@@ -503,13 +540,14 @@ inline bool is_pow2(float x) {
 
 template <int MODE, int NQ, bool MASKED, bool RAGGED = false>
 hipError_t launch_nq(const void *Q, const void *K, const void *V, const float *key_bias, int H,
-                     const uint8_t *block_mask, int BH, int Lq, int Lk, int d, float scale, void *O, hipStream_t st) {
+                     const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, float scale, void *O,
+                     hipStream_t st) {
     const unsigned grid = (unsigned)((long)BH * ((Lq + 64 * NQ - 1) / (64 * NQ)));
     const bool pre = is_pow2(scale);
 #define DFSS_LAUNCH(DD, PRE)                                                                                    \
     hipLaunchKernelGGL((k_fused<DD, MODE, NQ, PRE, MASKED, RAGGED>), dim3(grid), dim3(NT), 0, st,               \
-                       (const __bf16 *)Q, (const __bf16 *)K, (const __bf16 *)V, key_bias, H, block_mask, Lq,    \
-                       Lk, scale, (uint16_t *)O)
+                       (const __bf16 *)Q, (const __bf16 *)K, (const __bf16 *)V, key_bias, H, block_mask, causal, \
+                       Lq, Lk, scale, (uint16_t *)O)
     if (d == 64) {
         if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
     } else {
@@ -521,8 +559,8 @@ hipError_t launch_nq(const void *Q, const void *K, const void *V, const float *k
 
 template <int MODE>
 hipError_t launch(const void *Q, const void *K, const void *V, const float *key_bias, int H,
-                  const uint8_t *block_mask, int BH, int Lq, int Lk, int d, float scale, void *O, int variant,
-                  hipStream_t st) {
+                  const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, float scale, void *O,
+                  int variant, hipStream_t st) {
     // 32 queries per wave when that still leaves at least ~2 workgroups per compute unit
     bool two = Lq % 128 == 0 && (long)BH * (Lq / 128) >= 768;   // at least 3 workgroups per compute unit
     if (variant == DFSS_VARIANT_Q16) two = false;
@@ -530,15 +568,16 @@ hipError_t launch(const void *Q, const void *K, const void *V, const float *key_
     if (block_mask) two = false;   // the block of the mask is the 64-query workgroup tile
     if (Lq % 64 != 0 || Lk % 64 != 0) {   // (never together with a block mask)
         if ((long)BH * ((Lq + 127) / 128) >= 768)
-            return launch_nq<MODE, 2, true, true>(Q, K, V, key_bias, H, nullptr, BH, Lq, Lk, d, scale, O, st);
-        return launch_nq<MODE, 1, true, true>(Q, K, V, key_bias, H, nullptr, BH, Lq, Lk, d, scale, O, st);
+            return launch_nq<MODE, 2, true, true>(Q, K, V, key_bias, H, nullptr, causal, BH, Lq, Lk, d, scale, O, st);
+        return launch_nq<MODE, 1, true, true>(Q, K, V, key_bias, H, nullptr, causal, BH, Lq, Lk, d, scale, O, st);
     }
-    if (key_bias || block_mask) {
-        if (two) return launch_nq<MODE, 2, true>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, st);
-        return launch_nq<MODE, 1, true>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, st);
+    if (key_bias || block_mask || causal) {
+        if (two)
+            return launch_nq<MODE, 2, true>(Q, K, V, key_bias, H, block_mask, causal, BH, Lq, Lk, d, scale, O, st);
+        return launch_nq<MODE, 1, true>(Q, K, V, key_bias, H, block_mask, causal, BH, Lq, Lk, d, scale, O, st);
     }
-    if (two) return launch_nq<MODE, 2, false>(Q, K, V, nullptr, 1, nullptr, BH, Lq, Lk, d, scale, O, st);
-    return launch_nq<MODE, 1, false>(Q, K, V, nullptr, 1, nullptr, BH, Lq, Lk, d, scale, O, st);
+    if (two) return launch_nq<MODE, 2, false>(Q, K, V, nullptr, 1, nullptr, 0, BH, Lq, Lk, d, scale, O, st);
+    return launch_nq<MODE, 1, false>(Q, K, V, nullptr, 1, nullptr, 0, BH, Lq, Lk, d, scale, O, st);
 }
 
 }  // namespace
@@ -547,15 +586,15 @@ hipError_t launch_fused_attention32(const void *Q, const void *K, const void *V,
                                     int mode, int nw, int ks, float scale, void *O, hipStream_t st);
 
 hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, const float *key_bias, int H,
-                                  const uint8_t *block_mask, int BH, int Lq, int Lk, int d, int mode, float scale,
-                                  void *O, int variant, hipStream_t st) {
+                                  const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, int mode,
+                                  float scale, void *O, int variant, hipStream_t st) {
     // Calls without bias or block pattern on whole tiles take the 32-queries-per-wave kernel (callers that
     // name a 16-query tiling get the kernel above).  Its tilings, chosen from the number of 128-query
     // workgroups per compute unit (measured): four waves x 32 queries where that fills the chip or the grid is
     // tiny anyway; two waves per 32-query tile (64-query workgroups, twice as many) in between; d = 128
     // always the former (the merge of the two key halves costs more than it gains there).  Full attention
     // (the baseline) runs whichever of the two kernels is faster at the shape.
-    const bool plain = !key_bias && !block_mask && Lq % 64 == 0 && Lk % 64 == 0;
+    const bool plain = !key_bias && !block_mask && !causal && Lq % 64 == 0 && Lk % 64 == 0;
     if (plain && variant != DFSS_VARIANT_Q16 && variant != DFSS_VARIANT_Q16X2) {
         const long wg128 = (long)BH * (Lq / 128);
         int nw = Lq % 128 == 0 ? 4 : 2, ks = 1;
@@ -571,9 +610,11 @@ hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, c
         if (variant == DFSS_VARIANT_Q32K2) nw = 4, ks = 2;
         if (nw != 0) return launch_fused_attention32(Q, K, V, BH, Lq, Lk, d, mode, nw, ks, scale, O, st);
     }
-    if (mode == 0) return launch<MODE_2TO4>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, variant, st);
-    if (mode == 1) return launch<MODE_1TO2>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, variant, st);
-    return launch<MODE_DENSE>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, variant, st);
+    if (mode == 0)
+        return launch<MODE_2TO4>(Q, K, V, key_bias, H, block_mask, causal, BH, Lq, Lk, d, scale, O, variant, st);
+    if (mode == 1)
+        return launch<MODE_1TO2>(Q, K, V, key_bias, H, block_mask, causal, BH, Lq, Lk, d, scale, O, variant, st);
+    return launch<MODE_DENSE>(Q, K, V, key_bias, H, block_mask, causal, BH, Lq, Lk, d, scale, O, variant, st);
 }
 
 }  // namespace dfss

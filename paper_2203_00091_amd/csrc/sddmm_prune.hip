@@ -38,9 +38,12 @@ enum { MODE_2TO4 = 0, MODE_1TO2 = 1, MODE_DENSE = 2 };
 // BIAS: an additive per-key term (fp32 [B][Lk], shared by the H heads of a batch element; -inf masks a
 // key) joins the scaled score before the selection: as the initial value of the accumulators when the
 // scale is folded into Q, else added (as a separate fp32 addition) after the multiplication by scale.
+// causal (non-zero): query i sees keys 0 .. i + (Lk - Lq); the scores of the hidden keys are overwritten with
+// -inf before the selection, by index, in the blocks that reach past the diagonal of the wave's first query
+// (every block is still computed and written: the hidden entries are part of the compressed matrix).
 template <int D, int MODE, int NQ, bool PRESCALE, bool BIAS>
 __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
-                                                 const float *__restrict__ key_bias, int H,
+                                                 const float *__restrict__ key_bias, int H, int causal,
                                                  int Lq, int Lk, float scale, int ksplit, int blocks_per_wg,
                                                  uint32_t *__restrict__ out, uint32_t *__restrict__ meta) {
     constexpr int CPR = D / 8;           // 16-byte chunks per row
@@ -156,9 +159,11 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
             }
             // acc[qs][t][r] = score of query q0 + 16 qs + li and key 128 jb + 32 kb + 16 half + 4 t + r
             const int kbase = KB * jb + 32 * kb + 16 * half;
+            const bool cut = causal && KB * jb + KB - 1 > q0 + Lk - Lq;   // (same for the whole wave)
 #pragma unroll
             for (int qs = 0; qs < NQ; ++qs) {
                 const size_t row = (size_t)bh * Lq + q0 + 16 * qs + li;
+                const int lim = q0 + 16 * qs + li + Lk - Lq - kbase;   // key offsets above it are hidden
                 if constexpr (MODE == MODE_DENSE) {
                     uint32_t p[8];
 #pragma unroll
@@ -170,6 +175,10 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
 #pragma unroll
                                 for (int r = 0; r < 4; ++r) a[r] = __fadd_rn(a[r], kb4[t][r]);
                             }
+                        }
+                        if (cut) {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) a[r] = 4 * t + r > lim ? -INFINITY : a[r];
                         }
                         p[2 * t] = pack_bf16x2(a[0], a[1]);
                         p[2 * t + 1] = pack_bf16x2(a[2], a[3]);
@@ -188,6 +197,10 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
 #pragma unroll
                                 for (int r = 0; r < 4; ++r) a[r] = __fadd_rn(a[r], kb4[t][r]);
                             }
+                        }
+                        if (cut) {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) a[r] = 4 * t + r > lim ? -INFINITY : a[r];
                         }
                         float lo, hi;
                         uint32_t code;
@@ -224,7 +237,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 template <int D, int MODE, bool PRESCALE, bool BIAS>
 __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
-                                                   const float *__restrict__ key_bias, int H,
+                                                   const float *__restrict__ key_bias, int H, int causal,
                                                    int Lq, int Lk, float scale, int ksplit, int blocks_per_wg,
                                                    uint32_t *__restrict__ out, uint32_t *__restrict__ meta) {
     constexpr int CPR = D / 8;           // 16-byte chunks per row
@@ -349,6 +362,8 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
             }
             // acc[u][4g + x] = score of query q0 + lj and key 128 jb + 64 p + 32 h + 16 u + 4 g + x
             const int kbase = KB * jb + 64 * p + 32 * h;
+            const bool cut = causal && KB * jb + 64 * p + 63 > q0 + Lk - Lq;   // (same for the whole wave)
+            const int lim = q0 + lj + Lk - Lq - kbase;                         // key offsets above it are hidden
             if constexpr (MODE == MODE_DENSE) {
                 uint32_t pk[16];
 #pragma unroll
@@ -362,6 +377,10 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
                                 a0 = __fadd_rn(a0, kb4[u][e >> 1][2 * (e & 1)]);
                                 a1 = __fadd_rn(a1, kb4[u][e >> 1][2 * (e & 1) + 1]);
                             }
+                        }
+                        if (cut) {
+                            a0 = 16 * u + 2 * e > lim ? -INFINITY : a0;
+                            a1 = 16 * u + 2 * e + 1 > lim ? -INFINITY : a1;
                         }
                         pk[8 * u + e] = pack_bf16x2(a0, a1);
                     }
@@ -382,6 +401,11 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
                                 a0 = __fadd_rn(a0, kb4[u][g][0]); a1 = __fadd_rn(a1, kb4[u][g][1]);
                                 a2 = __fadd_rn(a2, kb4[u][g][2]); a3 = __fadd_rn(a3, kb4[u][g][3]);
                             }
+                        }
+                        if (cut) {
+                            const int e0 = 16 * u + 4 * g;
+                            a0 = e0 > lim ? -INFINITY : a0; a1 = e0 + 1 > lim ? -INFINITY : a1;
+                            a2 = e0 + 2 > lim ? -INFINITY : a2; a3 = e0 + 3 > lim ? -INFINITY : a3;
                         }
                         float lo, hi;
                         uint32_t code;
@@ -424,8 +448,8 @@ inline bool is_pow2(float x) {
 }
 
 template <int MODE, int NQ, bool BIAS>
-hipError_t launch_nq(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk, int d,
-                     float scale, void *out, void *meta, hipStream_t st) {
+hipError_t launch_nq(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq, int Lk,
+                     int d, float scale, void *out, void *meta, hipStream_t st) {
     const int qtiles = Lq / (64 * NQ);
     const int kblocks = Lk / KB;
     // split the key range until the grid has a few workgroups per compute unit
@@ -437,8 +461,8 @@ hipError_t launch_nq(const void *Q, const void *K, const float *key_bias, int H,
     const bool pre = is_pow2(scale);
 #define DFSS_LAUNCH(DD, PRE)                                                                              \
     hipLaunchKernelGGL((k_sddmm<DD, MODE, NQ, PRE, BIAS>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)Q, \
-                       (const __bf16 *)K, key_bias, H, Lq, Lk, scale, ksplit, per_wg, (uint32_t *)out,      \
-                       (uint32_t *)meta)
+                       (const __bf16 *)K, key_bias, H, causal, Lq, Lk, scale, ksplit, per_wg,              \
+                       (uint32_t *)out, (uint32_t *)meta)
     if (d == 64) {
         if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
     } else {
@@ -449,8 +473,8 @@ hipError_t launch_nq(const void *Q, const void *K, const float *key_bias, int H,
 }
 
 template <int MODE, bool BIAS>
-hipError_t launch32(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk, int d,
-                    float scale, void *out, void *meta, hipStream_t st) {
+hipError_t launch32(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq, int Lk,
+                    int d, float scale, void *out, void *meta, hipStream_t st) {
     const int qtiles = Lq / 128;
     const int kblocks = Lk / KB;
     int ksplit = 1;
@@ -461,8 +485,8 @@ hipError_t launch32(const void *Q, const void *K, const float *key_bias, int H, 
     const bool pre = is_pow2(scale);
 #define DFSS_LAUNCH(DD, PRE)                                                                             \
     hipLaunchKernelGGL((k_sddmm32<DD, MODE, PRE, BIAS>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)Q,  \
-                       (const __bf16 *)K, key_bias, H, Lq, Lk, scale, ksplit, per_wg, (uint32_t *)out,      \
-                       (uint32_t *)meta)
+                       (const __bf16 *)K, key_bias, H, causal, Lq, Lk, scale, ksplit, per_wg,              \
+                       (uint32_t *)out, (uint32_t *)meta)
     if (d == 64) {
         if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
     } else {
@@ -473,31 +497,31 @@ hipError_t launch32(const void *Q, const void *K, const float *key_bias, int H, 
 }
 
 template <int MODE, bool BIAS>
-hipError_t launch_b(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk, int d,
-                    float scale, void *out, void *meta, hipStream_t st) {
+hipError_t launch_b(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq, int Lk,
+                    int d, float scale, void *out, void *meta, hipStream_t st) {
     // 32 queries per wave (32x32x16 MFMA) when the query count allows it, else 16 (16x16x32 MFMA)
-    if (Lq % 128 == 0) return launch32<MODE, BIAS>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
-    return launch_nq<MODE, 1, BIAS>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
+    if (Lq % 128 == 0) return launch32<MODE, BIAS>(Q, K, key_bias, H, causal, BH, Lq, Lk, d, scale, out, meta, st);
+    return launch_nq<MODE, 1, BIAS>(Q, K, key_bias, H, causal, BH, Lq, Lk, d, scale, out, meta, st);
 }
 
 template <int MODE>
-hipError_t launch(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk, int d,
-                  float scale, void *out, void *meta, hipStream_t st) {
-    if (key_bias) return launch_b<MODE, true>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
-    return launch_b<MODE, false>(Q, K, nullptr, 1, BH, Lq, Lk, d, scale, out, meta, st);
+hipError_t launch(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq, int Lk,
+                  int d, float scale, void *out, void *meta, hipStream_t st) {
+    if (key_bias) return launch_b<MODE, true>(Q, K, key_bias, H, causal, BH, Lq, Lk, d, scale, out, meta, st);
+    return launch_b<MODE, false>(Q, K, nullptr, 1, causal, BH, Lq, Lk, d, scale, out, meta, st);
 }
 
 }  // namespace
 
-hipError_t launch_sddmm_prune(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
-                              int d, int mode, float scale, void *vals, void *meta, hipStream_t st) {
-    return mode == 0 ? launch<MODE_2TO4>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, vals, meta, st)
-                     : launch<MODE_1TO2>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, vals, meta, st);
+hipError_t launch_sddmm_prune(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq,
+                              int Lk, int d, int mode, float scale, void *vals, void *meta, hipStream_t st) {
+    return mode == 0 ? launch<MODE_2TO4>(Q, K, key_bias, H, causal, BH, Lq, Lk, d, scale, vals, meta, st)
+                     : launch<MODE_1TO2>(Q, K, key_bias, H, causal, BH, Lq, Lk, d, scale, vals, meta, st);
 }
 
-hipError_t launch_dense_scores(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
-                               int d, float scale, void *S, hipStream_t st) {
-    return launch<MODE_DENSE>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, S, nullptr, st);
+hipError_t launch_dense_scores(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq,
+                               int Lk, int d, float scale, void *S, hipStream_t st) {
+    return launch<MODE_DENSE>(Q, K, key_bias, H, causal, BH, Lq, Lk, d, scale, S, nullptr, st);
 }
 
 }  // namespace dfss

@@ -143,6 +143,32 @@ def test_errors_are_reported_before_any_launch():
     assert lib.dfss_status_string(E_WS) == b"workspace too small"
 
 
+def test_causal_calls_validate_before_any_launch():
+    """More queries than keys is a shape error (the queries are the last Lq positions); 4-byte dtypes are not
+    implemented; everything else is validated as in the calls without the suffix."""
+    lib = dfss.load_library()
+    buf = ctypes.create_string_buffer(1024)
+    a = ctypes.c_void_p((ctypes.cast(buf, ctypes.c_void_p).value + 255) // 256 * 256)
+    E_NULL, E_SHAPE, E_UNSUP, E_WS = 1, 2, 3, 4
+    ok = Shape(1, 1, 128, 256, 64).c()
+    more_queries = Shape(1, 1, 256, 128, 64).c()
+    f32 = Shape(1, 1, 128, 128, 64, 1, 2, dfss.DFSS_F32_BF16X3).c()
+    for shape, want in ((more_queries, E_SHAPE), (f32, E_UNSUP)):
+        r = ctypes.byref(shape)
+        assert lib.dfss_sddmm_prune_causal(a, a, None, r, 0.125, a, a, None) == want
+        assert lib.dfss_attention_causal(a, a, a, None, r, 0.125, a, None) == want
+        assert lib.dfss_attention_staged_causal(a, a, a, None, r, 0.125, a, a, 1 << 40, None) == want
+        assert lib.dense_attention_causal(a, a, a, None, r, 0.125, a, a, 1 << 40, None) == want
+        assert lib.dense_attention_fused_causal(a, a, a, None, r, 0.125, a, None) == want
+    r = ctypes.byref(ok)
+    assert lib.dfss_attention_causal(None, a, a, None, r, 0.125, a, None) == E_NULL
+    assert lib.dfss_attention_causal(a, a, a, None, r, float("nan"), a, None) == E_UNSUP
+    assert lib.dfss_attention_causal(a, a, a, ctypes.c_void_p(a.value + 4), r, 0.125, a, None) == E_SHAPE   # bias alignment
+    assert lib.dfss_attention_staged_causal(a, a, a, None, r, 0.125, a, a, 16, None) == E_WS
+    assert lib.dense_attention_causal(a, a, a, None, r, 0.125, a, a, 16, None) == E_WS
+    assert lib.dfss_sddmm_prune_causal(a, a, None, r, 0.125, None, a, None) == E_NULL
+
+
 def test_binding_refuses_host_tensors():
     import torch
     s = Shape(1, 1, 128, 128, 64)

@@ -360,3 +360,26 @@ def test_quality_of_one_of_two_matches_closed_form(psigma, tol):
     assert abs(oracle.quality_p(S, fixed, psigma / sigma) - 0.5) < 2.5 * tol
     # the full mask has quality exactly 1
     assert abs(oracle.quality_p(S, np.ones_like(m12), 1.0) - 1.0) < 1e-12
+
+
+def test_two_byte_storage_branch_against_torch():
+    """store_bf16 = 1 models the method's 2-byte compressed matrix: the kept scores and the weights pass through
+    bfloat16 where they are stored (Sec. 2.3: the nonzeros keep the data type of the dense matrix).  Pinned against
+    the same chain in torch: its own bfloat16 conversion, topk selection, softmax and matmul (Gaussian inputs: no
+    ties, so topk's tie order does not matter)."""
+    r = np.random.default_rng(77)
+    Lq, Lk, d, N, M = 48, 96, 32, 2, 4
+    Q, K, V = (r.standard_normal(s).astype(np.float32) for s in ((Lq, d), (Lk, d), (Lk, d)))
+    got = oracle.attention(Q, K, V, N, M, 0.25, store_bf16=True)
+    S = torch.from_numpy(oracle.scores(Q, K, 0.25))                    # fp32 scores (pinned elsewhere)
+    G = S.view(Lq, Lk // M, M)
+    idx = G.topk(N, dim=-1).indices.sort(-1).values                    # kept positions, key order
+    vals = G.gather(-1, idx).to(torch.bfloat16).double()               # stored in 2 bytes
+    P = torch.softmax(vals.view(Lq, -1), dim=-1).to(torch.bfloat16).double().view(Lq, Lk // M, N)
+    W = torch.zeros(Lq, Lk // M, M, dtype=torch.float64).scatter_(-1, idx, P).view(Lq, Lk)
+    ref = (W @ torch.from_numpy(V).double()).numpy()
+    assert np.max(np.abs(got - ref)) < 1e-5
+    # and the storage matters: the unrounded function differs, by no more than the roundings allow
+    exact = oracle.attention(Q, K, V, N, M, 0.25, store_bf16=False)
+    diff = np.max(np.abs(got - exact))
+    assert 1e-5 < diff < 2e-2
