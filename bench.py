@@ -432,7 +432,7 @@ def main():
         b = sets[0]
         vals = torch.empty((BH, L, s.Lc), dtype=s.torch_dtype, device=dev)
         meta = torch.empty((BH * L * s.meta_words,), dtype=torch.int16, device=dev)
-        fn = dfss.dfss_sddmm_prune_causal if causal else dfss.dfss_sddmm_prune_bias
+        fn = dfss.dfss_sddmm_prune_causal if args.causal else dfss.dfss_sddmm_prune_bias
         fn(b["Q"], b["K"], bias, s, w.scale, vals=vals, meta=meta)
         dfss.dfss_sparse_softmax(vals, s)
         O_fwd = dfss.dfss_spmm(vals, meta, b["V"], s)

@@ -364,7 +364,9 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
 
         if constexpr (MASKED) {
             // causal: the scores of keys after the query's own position count as -inf
-            if (causal && KB * jb + KB - 1 > q0 + coff) {   // (the wave's first query already has hidden keys here)
+            // (q0 is the same in every lane of the wave; as a scalar, the test is a branch around the masking)
+            if (causal && KB * jb + KB - 1 > __builtin_amdgcn_readfirstlane(q0) + coff) {   // the wave's first query has hidden keys here
+                asm volatile("" ::: "memory");   // (not to be turned into selects that every block would execute)
 #pragma unroll
                 for (int qs = 0; qs < NQ; ++qs) {
                     const int lim = q0 + 16 * qs + li + coff - (KB * jb + 16 * kb);   // key offsets above it are hidden

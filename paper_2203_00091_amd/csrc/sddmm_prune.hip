@@ -38,12 +38,12 @@ enum { MODE_2TO4 = 0, MODE_1TO2 = 1, MODE_DENSE = 2 };
 // BIAS: an additive per-key term (fp32 [B][Lk], shared by the H heads of a batch element; -inf masks a
 // key) joins the scaled score before the selection: as the initial value of the accumulators when the
 // scale is folded into Q, else added (as a separate fp32 addition) after the multiplication by scale.
-// causal (non-zero): query i sees keys 0 .. i + (Lk - Lq); the scores of the hidden keys are overwritten with
+// CAUSAL: query i sees keys 0 .. i + (Lk - Lq); the scores of the hidden keys are overwritten with
 // -inf before the selection, by index, in the blocks that reach past the diagonal of the wave's first query
 // (every block is still computed and written: the hidden entries are part of the compressed matrix).
-template <int D, int MODE, int NQ, bool PRESCALE, bool BIAS>
+template <int D, int MODE, int NQ, bool PRESCALE, bool BIAS, bool CAUSAL>
 __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
-                                                 const float *__restrict__ key_bias, int H, int causal,
+                                                 const float *__restrict__ key_bias, int H,
                                                  int Lq, int Lk, float scale, int ksplit, int blocks_per_wg,
                                                  uint32_t *__restrict__ out, uint32_t *__restrict__ meta) {
     constexpr int CPR = D / 8;           // 16-byte chunks per row
@@ -159,11 +159,23 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
             }
             // acc[qs][t][r] = score of query q0 + 16 qs + li and key 128 jb + 32 kb + 16 half + 4 t + r
             const int kbase = KB * jb + 32 * kb + 16 * half;
-            const bool cut = causal && KB * jb + KB - 1 > q0 + Lk - Lq;   // (same for the whole wave)
+            // causal: hidden scores become -inf on the raw accumulators (the scaling and the bias leave -inf as it is).
+            // q0 is the same in every lane of the wave; as a scalar, the test is one branch around the masking.
+            if (CAUSAL && KB * jb + KB - 1 > __builtin_amdgcn_readfirstlane(q0) + Lk - Lq) {
+                asm volatile("" ::: "memory");   // (not to be turned into selects that every block would execute)
+#pragma unroll
+                for (int qs = 0; qs < NQ; ++qs) {
+                    const int lim = q0 + 16 * qs + li + Lk - Lq - kbase;   // key offsets above it are hidden
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            if (4 * t + r > lim) acc[qs][t][r] = -INFINITY;
+                }
+            }
 #pragma unroll
             for (int qs = 0; qs < NQ; ++qs) {
                 const size_t row = (size_t)bh * Lq + q0 + 16 * qs + li;
-                const int lim = q0 + 16 * qs + li + Lk - Lq - kbase;   // key offsets above it are hidden
                 if constexpr (MODE == MODE_DENSE) {
                     uint32_t p[8];
 #pragma unroll
@@ -175,10 +187,6 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
 #pragma unroll
                                 for (int r = 0; r < 4; ++r) a[r] = __fadd_rn(a[r], kb4[t][r]);
                             }
-                        }
-                        if (cut) {
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) a[r] = 4 * t + r > lim ? -INFINITY : a[r];
                         }
                         p[2 * t] = pack_bf16x2(a[0], a[1]);
                         p[2 * t + 1] = pack_bf16x2(a[2], a[3]);
@@ -197,10 +205,6 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
 #pragma unroll
                                 for (int r = 0; r < 4; ++r) a[r] = __fadd_rn(a[r], kb4[t][r]);
                             }
-                        }
-                        if (cut) {
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) a[r] = 4 * t + r > lim ? -INFINITY : a[r];
                         }
                         float lo, hi;
                         uint32_t code;
@@ -235,9 +239,9 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
 // ---------------------------------------------------------------------------------------------
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-template <int D, int MODE, bool PRESCALE, bool BIAS>
+template <int D, int MODE, bool PRESCALE, bool BIAS, bool CAUSAL>
 __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
-                                                   const float *__restrict__ key_bias, int H, int causal,
+                                                   const float *__restrict__ key_bias, int H,
                                                    int Lq, int Lk, float scale, int ksplit, int blocks_per_wg,
                                                    uint32_t *__restrict__ out, uint32_t *__restrict__ meta) {
     constexpr int CPR = D / 8;           // 16-byte chunks per row
@@ -362,8 +366,17 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
             }
             // acc[u][4g + x] = score of query q0 + lj and key 128 jb + 64 p + 32 h + 16 u + 4 g + x
             const int kbase = KB * jb + 64 * p + 32 * h;
-            const bool cut = causal && KB * jb + 64 * p + 63 > q0 + Lk - Lq;   // (same for the whole wave)
-            const int lim = q0 + lj + Lk - Lq - kbase;                         // key offsets above it are hidden
+            // causal: hidden scores become -inf on the raw accumulators (the scaling and the bias leave -inf as it is).
+            // q0 is the same in every lane of the wave; as a scalar, the test is one branch around the masking.
+            if (CAUSAL && KB * jb + 64 * p + 63 > __builtin_amdgcn_readfirstlane(q0) + Lk - Lq) {
+                asm volatile("" ::: "memory");   // (not to be turned into selects that every block would execute)
+                const int lim = q0 + lj + Lk - Lq - kbase;   // key offsets above it are hidden
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (16 * u + r > lim) acc[u][r] = -INFINITY;
+            }
             if constexpr (MODE == MODE_DENSE) {
                 uint32_t pk[16];
 #pragma unroll
@@ -377,10 +390,6 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
                                 a0 = __fadd_rn(a0, kb4[u][e >> 1][2 * (e & 1)]);
                                 a1 = __fadd_rn(a1, kb4[u][e >> 1][2 * (e & 1) + 1]);
                             }
-                        }
-                        if (cut) {
-                            a0 = 16 * u + 2 * e > lim ? -INFINITY : a0;
-                            a1 = 16 * u + 2 * e + 1 > lim ? -INFINITY : a1;
                         }
                         pk[8 * u + e] = pack_bf16x2(a0, a1);
                     }
@@ -401,11 +410,6 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
                                 a0 = __fadd_rn(a0, kb4[u][g][0]); a1 = __fadd_rn(a1, kb4[u][g][1]);
                                 a2 = __fadd_rn(a2, kb4[u][g][2]); a3 = __fadd_rn(a3, kb4[u][g][3]);
                             }
-                        }
-                        if (cut) {
-                            const int e0 = 16 * u + 4 * g;
-                            a0 = e0 > lim ? -INFINITY : a0; a1 = e0 + 1 > lim ? -INFINITY : a1;
-                            a2 = e0 + 2 > lim ? -INFINITY : a2; a3 = e0 + 3 > lim ? -INFINITY : a3;
                         }
                         float lo, hi;
                         uint32_t code;
@@ -447,8 +451,8 @@ inline bool is_pow2(float x) {
     return frexpf(x, &e) == 0.5f;
 }
 
-template <int MODE, int NQ, bool BIAS>
-hipError_t launch_nq(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq, int Lk,
+template <int MODE, int NQ, bool BIAS, bool CAUSAL>
+hipError_t launch_nq(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
                      int d, float scale, void *out, void *meta, hipStream_t st) {
     const int qtiles = Lq / (64 * NQ);
     const int kblocks = Lk / KB;
@@ -460,8 +464,8 @@ hipError_t launch_nq(const void *Q, const void *K, const float *key_bias, int H,
     const unsigned grid = (unsigned)((long)BH * qtiles * ksplit);
     const bool pre = is_pow2(scale);
 #define DFSS_LAUNCH(DD, PRE)                                                                              \
-    hipLaunchKernelGGL((k_sddmm<DD, MODE, NQ, PRE, BIAS>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)Q, \
-                       (const __bf16 *)K, key_bias, H, causal, Lq, Lk, scale, ksplit, per_wg,              \
+    hipLaunchKernelGGL((k_sddmm<DD, MODE, NQ, PRE, BIAS, CAUSAL>), dim3(grid), dim3(NT), 0, st,               \
+                       (const __bf16 *)Q, (const __bf16 *)K, key_bias, H, Lq, Lk, scale, ksplit, per_wg,       \
                        (uint32_t *)out, (uint32_t *)meta)
     if (d == 64) {
         if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
@@ -472,8 +476,8 @@ hipError_t launch_nq(const void *Q, const void *K, const float *key_bias, int H,
     return hipGetLastError();
 }
 
-template <int MODE, bool BIAS>
-hipError_t launch32(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq, int Lk,
+template <int MODE, bool BIAS, bool CAUSAL>
+hipError_t launch32(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
                     int d, float scale, void *out, void *meta, hipStream_t st) {
     const int qtiles = Lq / 128;
     const int kblocks = Lk / KB;
@@ -484,8 +488,8 @@ hipError_t launch32(const void *Q, const void *K, const float *key_bias, int H, 
     const unsigned grid = (unsigned)((long)BH * qtiles * ksplit);
     const bool pre = is_pow2(scale);
 #define DFSS_LAUNCH(DD, PRE)                                                                             \
-    hipLaunchKernelGGL((k_sddmm32<DD, MODE, PRE, BIAS>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)Q,  \
-                       (const __bf16 *)K, key_bias, H, causal, Lq, Lk, scale, ksplit, per_wg,              \
+    hipLaunchKernelGGL((k_sddmm32<DD, MODE, PRE, BIAS, CAUSAL>), dim3(grid), dim3(NT), 0, st,                \
+                       (const __bf16 *)Q, (const __bf16 *)K, key_bias, H, Lq, Lk, scale, ksplit, per_wg,       \
                        (uint32_t *)out, (uint32_t *)meta)
     if (d == 64) {
         if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
@@ -496,19 +500,23 @@ hipError_t launch32(const void *Q, const void *K, const float *key_bias, int H, 
     return hipGetLastError();
 }
 
-template <int MODE, bool BIAS>
-hipError_t launch_b(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq, int Lk,
+template <int MODE, bool BIAS, bool CAUSAL>
+hipError_t launch_b(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
                     int d, float scale, void *out, void *meta, hipStream_t st) {
     // 32 queries per wave (32x32x16 MFMA) when the query count allows it, else 16 (16x16x32 MFMA)
-    if (Lq % 128 == 0) return launch32<MODE, BIAS>(Q, K, key_bias, H, causal, BH, Lq, Lk, d, scale, out, meta, st);
-    return launch_nq<MODE, 1, BIAS>(Q, K, key_bias, H, causal, BH, Lq, Lk, d, scale, out, meta, st);
+    if (Lq % 128 == 0) return launch32<MODE, BIAS, CAUSAL>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
+    return launch_nq<MODE, 1, BIAS, CAUSAL>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
 }
 
 template <int MODE>
 hipError_t launch(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq, int Lk,
                   int d, float scale, void *out, void *meta, hipStream_t st) {
-    if (key_bias) return launch_b<MODE, true>(Q, K, key_bias, H, causal, BH, Lq, Lk, d, scale, out, meta, st);
-    return launch_b<MODE, false>(Q, K, nullptr, 1, causal, BH, Lq, Lk, d, scale, out, meta, st);
+    if (causal) {
+        if (key_bias) return launch_b<MODE, true, true>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
+        return launch_b<MODE, false, true>(Q, K, nullptr, 1, BH, Lq, Lk, d, scale, out, meta, st);
+    }
+    if (key_bias) return launch_b<MODE, true, false>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
+    return launch_b<MODE, false, false>(Q, K, nullptr, 1, BH, Lq, Lk, d, scale, out, meta, st);
 }
 
 }  // namespace
