@@ -592,16 +592,17 @@ hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, c
                                   float scale, void *O, int variant, hipStream_t st) {
     // Calls without bias or block pattern on whole tiles take the 32-queries-per-wave kernel (callers that
     // name a 16-query tiling get the kernel above).  Its tilings, chosen from the number of 128-query
-    // workgroups per compute unit (measured): four waves x 32 queries where that fills the chip or the grid is
-    // tiny anyway; two waves per 32-query tile (64-query workgroups, twice as many) in between; d = 128
-    // always the former (the merge of the two key halves costs more than it gains there).  Full attention
+    // workgroups (measured): four waves x 32 queries where that fills the chip; two waves per 32-query tile
+    // (64-query workgroups, twice as many, each wave half the keys) where the grid is smaller than the chip's
+    // 256 compute units or leaves its second round half empty; d = 128 always the former (the merge of the
+    // two key halves costs more than it gains there).  Full attention
     // (the baseline) runs whichever of the two kernels is faster at the shape.
     const bool plain = !key_bias && !block_mask && !causal && Lq % 64 == 0 && Lk % 64 == 0;
     if (plain && variant != DFSS_VARIANT_Q16 && variant != DFSS_VARIANT_Q16X2) {
         const long wg128 = (long)BH * (Lq / 128);
         int nw = Lq % 128 == 0 ? 4 : 2, ks = 1;
         if (variant == DFSS_VARIANT_AUTO) {
-            if (mode != 2 && d == 64 && wg128 >= 320 && wg128 < 640) nw = 4, ks = 2;
+            if (mode != 2 && d == 64 && (wg128 < 256 || (wg128 >= 320 && wg128 < 640))) nw = 4, ks = 2;
             if (mode != 2 && Lq % 128 != 0 && d == 64) nw = 4, ks = 2;   // 64-query workgroups either way
             const bool old_dense = d == 128 || wg128 >= 448 || Lq % 128 != 0;
             if (mode == 2 && old_dense) nw = 0;
