@@ -472,34 +472,43 @@ hipError_t launch(const void *Q, const void *K, const void *V, const float *key_
 
 }  // namespace
 
-hipError_t launch_fused_attention32(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d,
-                                    int mode, int nw, int ks, float scale, void *O, hipStream_t st);
+hipError_t launch_fused_attention32(const void *Q, const void *K, const void *V, const float *key_bias, int H,
+                                    const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, int mode,
+                                    int nw, int ks, float scale, void *O, hipStream_t st);
 
 hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, const float *key_bias, int H,
                                   const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, int mode,
                                   float scale, void *O, int variant, hipStream_t st) {
-    // Calls without bias or block pattern on whole tiles take the 32-queries-per-wave kernel (callers that
-    // name a 16-query tiling get the kernel above).  Its tilings, chosen from the number of 128-query
+    // Calls without bias or block pattern on whole tiles take the 32-queries-per-wave kernel, and so do causal calls
+    // (callers that name a 16-query tiling get the kernel above).  Its tilings, chosen from the number of 128-query
     // workgroups (measured): four waves x 32 queries where that fills the chip; two waves per 32-query tile
     // (64-query workgroups, twice as many, each wave half the keys) where the grid is smaller than the chip's
     // 256 compute units or leaves its second round half empty; d = 128 always the former (the merge of the
     // two key halves costs more than it gains there).  Full attention
     // (the baseline) runs whichever of the two kernels is faster at the shape.
-    const bool plain = !key_bias && !block_mask && !causal && Lq % 64 == 0 && Lk % 64 == 0;
-    if (plain && variant != DFSS_VARIANT_Q16 && variant != DFSS_VARIANT_Q16X2) {
+    const bool masked = key_bias || block_mask || causal;
+    // masked calls: the 32-query kernel where it measured faster -- the causal mask (with or without a key bias) at
+    // d = 64 on 128-query workgroups; a key bias alone, block patterns and d = 128 stay with the kernel above
+    const bool masked32 = causal && !block_mask && d == 64 && Lq % 128 == 0 && mode != 2;
+    const bool tiles = Lq % 64 == 0 && Lk % 64 == 0;
+    if (tiles && (!masked || masked32) && variant != DFSS_VARIANT_Q16 && variant != DFSS_VARIANT_Q16X2) {
         const long wg128 = (long)BH * (Lq / 128);
         int nw = Lq % 128 == 0 ? 4 : 2, ks = 1;
-        if (variant == DFSS_VARIANT_AUTO) {
+        if (variant == DFSS_VARIANT_AUTO && !masked) {
             if (mode != 2 && d == 64 && (wg128 < 256 || (wg128 >= 320 && wg128 < 640))) nw = 4, ks = 2;
             if (mode != 2 && Lq % 128 != 0 && d == 64) nw = 4, ks = 2;   // 64-query workgroups either way
             const bool old_dense = d == 128 || wg128 >= 448 || Lq % 128 != 0;
             if (mode == 2 && old_dense) nw = 0;
             if (mode != 2 && d == 128 && Lq % 128 != 0) nw = 0;       // (two-wave workgroups at d = 128: too many registers)
         }
-        if (variant == DFSS_VARIANT_Q32W2) nw = 2;
-        if (variant == DFSS_VARIANT_Q32W4 && Lq % 128 == 0) nw = 4;
-        if (variant == DFSS_VARIANT_Q32K2) nw = 4, ks = 2;
-        if (nw != 0) return launch_fused_attention32(Q, K, V, BH, Lq, Lk, d, mode, nw, ks, scale, O, st);
+        if (!masked) {
+            if (variant == DFSS_VARIANT_Q32W2) nw = 2;
+            if (variant == DFSS_VARIANT_Q32W4 && Lq % 128 == 0) nw = 4;
+            if (variant == DFSS_VARIANT_Q32K2) nw = 4, ks = 2;
+        }
+        if (nw != 0)
+            return launch_fused_attention32(Q, K, V, key_bias, H, nullptr, causal, BH, Lq, Lk, d, mode, nw, ks, scale, O,
+                                            st);
     }
     if (mode == 0)
         return launch<MODE_2TO4>(Q, K, V, key_bias, H, block_mask, causal, BH, Lq, Lk, d, scale, O, variant, st);

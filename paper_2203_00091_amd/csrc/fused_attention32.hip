@@ -34,6 +34,7 @@
 //   O and the row sums: column lj of a 32-column tile, rows (queries) 8(r/4) + 4h + r%4.
 #include <type_traits>
 
+#include "block_list.hpp"
 #include "dfss_device.hpp"
 #include "dfss_kernels.hpp"
 
@@ -68,10 +69,22 @@ __device__ __forceinline__ uint32_t push_position(uint32_t idx, float v) {
 // waves of a query tile share its keys: of every 64-key block, wave ks takes the 32-key tile ks (its own
 // reference value, row sums and partial O, merged at the end through LDS).  Smaller work items, more
 // waves per SIMD: what short sequences and small batches need to fill the chip.
-template <int D, int MODE, int NW, int KS, int OCC>
+// MASKED: the call carries a key bias, a block mask and / or the causal flag (KS = 1 only):
+//   key_bias   additive per-key term (fp32 [B][Lk], shared by the H heads of a batch element; -inf masks a key).
+//              The scores here are raw dot products relative to the reference, so the bias joins them as
+//              bias / scale in the accumulator the score tile starts from (exact for 0, -inf and, with a scale that
+//              is a power of two, for every finite bias).  -inf becomes -1e30: the position bits need a finite number,
+//              and exp2 of it is exactly 0 all the same.
+//   block_mask uint8 [Lq/64][Lk/64] shared by all heads (needs 64-query workgroups, NW = 2: the launchers below do
+//              not instantiate that form, the 16-query kernel measured faster for block patterns); causal: query i
+//              sees keys 0 .. i + (Lk - Lq).  Blocks that hold nothing for the workgroup are skipped (block_list.hpp); hidden
+//              scores of the blocks that the diagonal cuts are overwritten with -1e30 by index.
+template <int D, int MODE, int NW, int KS, int OCC, bool MASKED>
 __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
-                                                        const __bf16 *__restrict__ V, int Lq, int Lk, float scale,
-                                                        uint16_t *__restrict__ O) {
+                                                        const __bf16 *__restrict__ V, const float *__restrict__ key_bias,
+                                                        int H, const uint8_t *__restrict__ block_mask, int causal,
+                                                        int Lq, int Lk, float scale, uint16_t *__restrict__ O) {
+    static_assert(!MASKED || KS == 1, "the masked variants do not split the keys of a block over waves");
     constexpr int NT = 64 * NW;
     constexpr int CPR = D / 8;          // 16-byte chunks per row
     constexpr int TILE = KB * CPR;      // chunks per K (or V) block
@@ -93,11 +106,22 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
     const int qw = w / KS, ks = w % KS;   // query tile of the workgroup, key tile of the block
 
     const unsigned qtiles = Lq / TQ;
-    const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
-    const int qt = item % qtiles;
-    const int bh = item / qtiles;
+    int qt, bh;
+    if (MASKED && (block_mask || causal)) {
+        // row blocks differ widely in work: hand them out across heads in launch order, heavy ones first (with a
+        // block pattern the global rows come first; under the causal mask the work grows with the row block)
+        const unsigned heads = gridDim.x / qtiles;
+        qt = blockIdx.x / heads;
+        if (causal && !block_mask) qt = qtiles - 1 - qt;
+        bh = blockIdx.x % heads;
+    } else {
+        const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
+        qt = item % qtiles;
+        bh = item / qtiles;
+    }
     const int q0 = qt * TQ + qw * 32;
     const int nblocks = Lk / KB;
+    const int coff = Lk - Lq;           // causal: query i sits at position i + coff
 
     // K block in LDS: row slot 32 kt + i (key tile kt, MFMA row i = 8g + 4h' + x) holds key
     // 32 kt + 16 h' + 4 g + x; chunk c sits at slot * CPR + (c ^ (slot & 7)).
@@ -154,32 +178,77 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
         for (int i = 0; i < LPT; ++i)
             async_copy16(vs_ + (uint64_t)(i * SPC) * D * 2, v_off, lds_v + 16u * (buf * TILE + i * NT));
     };
-    issue_block(0, 0);
+    issue_block(0, 0);   // block 0 is copied before anything else (with masks: speculatively)
 
-    // one key block; buf = jb % 2 is a compile-time constant so that every LDS access names its buffer
-    auto block = [&](auto parity, int jb) {
+    const float *brow = nullptr;        // bias row of this head's batch element
+    const float inv_scale = 1.0f / scale;
+    BlockList<MASKED, false> blocks;
+    if constexpr (MASKED) {
+        if (key_bias) brow = key_bias + (size_t)(bh / H) * Lk;
+        blocks.init(key_bias != nullptr, brow, block_mask != nullptr, block_mask + (size_t)(qt * TQ / 64) * nblocks,
+                    causal, qt * TQ, TQ, coff, Lq, Lk, nblocks, l);
+    }
+
+    // one key block; the buffer index is a compile-time constant so that every LDS access names its buffer.
+    // jn: the block after this one (>= nblocks: none); first: this is the first block the workgroup visits
+    auto block = [&](auto parity, int jb, int jn, bool first) {
         constexpr int buf = decltype(parity)::value;
         wait_async_copies();  // vmcnt(0): this block's copies have landed
         __syncthreads();
-        if (jb + 1 < nblocks) issue_block(jb + 1, buf ^ 1);
+        if (jn < nblocks) issue_block(jn, buf ^ 1);
 
         // ---- scores relative to the reference: acc[t][4g + x] = q . k - cref for query q0 + lj,
         //      key 64 jb + 32 (kt0 + t) + 16 h + 4 g + x ----
         f32x16 acc[KT];
+        bool with_bias = false;
+        if constexpr (MASKED) with_bias = brow != nullptr && blocks.has_bias(jb);
+        if (MASKED && with_bias) {
+            // the score tiles start from -c + bias / scale: keys 64 jb + 32 t + 16 h + r of this lane
 #pragma unroll
-        for (int t = 0; t < KT; ++t) {
+            for (int t = 0; t < KT; ++t) {
+                f32x16 cb;
 #pragma unroll
-            for (int s = 0; s < STEPS; ++s) {
-                const bf16x8 ak =
-                    __builtin_bit_cast(bf16x8, Ks[buf][(32 * (kt0 + t) + lj) * CPR + ((2 * s + h) ^ (lj & 7))]);
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, bq[s], s == 0 ? cneg : acc[t], 0, 0, 0);
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 b = *reinterpret_cast<const f32x4 *>(brow + KB * jb + 32 * t + 16 * h + 4 * g);
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) cb[4 * g + x] = cneg[4 * g + x] + fmaxf(b[x] * inv_scale, -1.0e30f);
+                }
+#pragma unroll
+                for (int s = 0; s < STEPS; ++s) {
+                    const bf16x8 ak =
+                        __builtin_bit_cast(bf16x8, Ks[buf][(32 * t + lj) * CPR + ((2 * s + h) ^ (lj & 7))]);
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, bq[s], s == 0 ? cb : acc[t], 0, 0, 0);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < KT; ++t) {
+#pragma unroll
+                for (int s = 0; s < STEPS; ++s) {
+                    const bf16x8 ak =
+                        __builtin_bit_cast(bf16x8, Ks[buf][(32 * (kt0 + t) + lj) * CPR + ((2 * s + h) ^ (lj & 7))]);
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, bq[s], s == 0 ? cneg : acc[t], 0, 0, 0);
+                }
+            }
+        }
+        if constexpr (MASKED) {
+            // causal: the scores of keys after the query's own position count as masked (q0 is the same in every
+            // lane of the wave; as a scalar, the test is one branch around the masking)
+            if (causal && KB * jb + KB - 1 > __builtin_amdgcn_readfirstlane(q0) + coff) {
+                asm volatile("" ::: "memory");   // (not to be turned into selects that every block would execute)
+                const int lim = q0 + lj + coff - (KB * jb + 16 * h);   // key offsets above it are hidden
+#pragma unroll
+                for (int t = 0; t < KT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (32 * t + r > lim) acc[t][r] = -1.0e30f;
             }
         }
 
         // ---- prune; arguments of the weights ----
         float kept[KT][2 * NP];
         uint32_t idx = 0;       // positions: tile t in bits [32 - 16 (KT - t), +16)
-        bool force = jb == 0;   // the first block sets the reference
+        bool force = first;     // the first block sets the reference
         for (;;) {
             float m_blk = -3.0e38f;
 #pragma unroll
@@ -222,7 +291,7 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
             // the reference move by delta (a difference of two bfloat16 numbers: exact)
             const float c_new = up ? bf16_ceil(cref + mq + tau) : cref;
             const float delta = c_new - cref;
-            const float alpha = (up && jb != 0) ? __builtin_amdgcn_exp2f(-delta * k2) : 1.f;
+            const float alpha = (up && !first) ? __builtin_amdgcn_exp2f(-delta * k2) : 1.f;
             cref = c_new;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -230,7 +299,7 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
 #pragma unroll
                 for (int t = 0; t < KT; ++t) acc[t][r] -= delta;
             }
-            if (jb != 0) {
+            if (!first) {
                 // accumulator rows are queries 8 (r/4) + 4 h + r%4: fetch their factors from those columns' lanes
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
@@ -302,9 +371,26 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
             }
         }
     };
-    for (int jb = 0; jb < nblocks; jb += 2) {
-        block(std::integral_constant<int, 0>{}, jb);
-        if (jb + 1 < nblocks) block(std::integral_constant<int, 1>{}, jb + 1);
+    if constexpr (!MASKED) {
+        for (int jb = 0; jb < nblocks; jb += 2) {
+            block(std::integral_constant<int, 0>{}, jb, jb + 1, jb == 0);
+            if (jb + 1 < nblocks) block(std::integral_constant<int, 1>{}, jb + 1, jb + 2, false);
+        }
+    } else {
+        int jb = blocks.take();
+        int jn = blocks.take();   // the block after this one
+        // block 0 (copied speculatively at the top) turned out to hold nothing: overwrite the buffer with the first
+        // live block (the two copies of a wave complete in issue order)
+        if (jb != 0 && jb < nblocks) issue_block(jb, 0);
+        for (bool first = true; jb < nblocks; first = false) {
+            block(std::integral_constant<int, 0>{}, jb, jn, first);
+            jb = jn;
+            jn = blocks.take();
+            if (jb >= nblocks) break;
+            block(std::integral_constant<int, 1>{}, jb, jn, false);
+            jb = jn;
+            jn = blocks.take();
+        }
     }
 
     if constexpr (KS == 2) {
@@ -351,15 +437,17 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
 }
 
 // waves per SIMD the kernels are compiled for (registers per lane <= 512 / OCC)
-#define DFSS_OCC(DD) ((DD) == 128 ? 2 : MODE == MODE_DENSE ? (KS == 2 ? 3 : 2) : 3)
+#define DFSS_OCC(DD) ((DD) == 128 || MASKED ? 2 : MODE == MODE_DENSE ? (KS == 2 ? 3 : 2) : 3)
 
-template <int MODE, int NW, int KS>
-hipError_t launch_nw(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d, float scale,
-                     void *O, hipStream_t st) {
+template <int MODE, int NW, int KS, bool MASKED>
+hipError_t launch_nw(const void *Q, const void *K, const void *V, const float *key_bias, int H,
+                     const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, float scale, void *O,
+                     hipStream_t st) {
     const unsigned grid = (unsigned)((long)BH * (Lq / (32 * NW / KS)));
-#define DFSS_LAUNCH(DD)                                                                                     \
-    hipLaunchKernelGGL((k_fused32<DD, MODE, NW, KS, DFSS_OCC(DD)>), dim3(grid), dim3(64 * NW), 0, st, (const __bf16 *)Q, \
-                       (const __bf16 *)K, (const __bf16 *)V, Lq, Lk, scale, (uint16_t *)O)
+#define DFSS_LAUNCH(DD)                                                                                       \
+    hipLaunchKernelGGL((k_fused32<DD, MODE, NW, KS, DFSS_OCC(DD), MASKED>), dim3(grid), dim3(64 * NW), 0, st, \
+                       (const __bf16 *)Q, (const __bf16 *)K, (const __bf16 *)V, key_bias, H, block_mask,      \
+                       causal, Lq, Lk, scale, (uint16_t *)O)
     if (d == 64) DFSS_LAUNCH(64);
     else DFSS_LAUNCH(128);
 #undef DFSS_LAUNCH
@@ -367,22 +455,31 @@ hipError_t launch_nw(const void *Q, const void *K, const void *V, int BH, int Lq
 }
 
 template <int MODE>
-hipError_t launch_mode(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d, int nw, int ks,
+hipError_t launch_mode(const void *Q, const void *K, const void *V, const float *key_bias, int H,
+                       const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, int nw, int ks,
                        float scale, void *O, hipStream_t st) {
-    if (ks == 2) return launch_nw<MODE, 4, 2>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
-    if (nw == 4) return launch_nw<MODE, 4, 1>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
-    return launch_nw<MODE, 2, 1>(Q, K, V, BH, Lq, Lk, d, scale, O, st);
+    if (key_bias || block_mask || causal) {   // masked calls: 128-query workgroups (block patterns need 64: not here)
+        if (block_mask || nw != 4 || Lq % 128 != 0) return hipErrorInvalidValue;
+        return launch_nw<MODE, 4, 1, true>(Q, K, V, key_bias, H, nullptr, causal, BH, Lq, Lk, d, scale, O, st);
+    }
+    if (ks == 2) return launch_nw<MODE, 4, 2, false>(Q, K, V, nullptr, 1, nullptr, 0, BH, Lq, Lk, d, scale, O, st);
+    if (nw == 4) return launch_nw<MODE, 4, 1, false>(Q, K, V, nullptr, 1, nullptr, 0, BH, Lq, Lk, d, scale, O, st);
+    return launch_nw<MODE, 2, 1, false>(Q, K, V, nullptr, 1, nullptr, 0, BH, Lq, Lk, d, scale, O, st);
 }
 
 }  // namespace
 
 // nw: waves per workgroup (2 or 4); ks: waves that share the keys of one 32-query tile (1, or 2 with nw = 4).
-// Lq must be a multiple of 32 * nw / ks, Lk of 64.
-hipError_t launch_fused_attention32(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d,
-                                    int mode, int nw, int ks, float scale, void *O, hipStream_t st) {
-    if (mode == 0) return launch_mode<MODE_2TO4>(Q, K, V, BH, Lq, Lk, d, nw, ks, scale, O, st);
-    if (mode == 1) return launch_mode<MODE_1TO2>(Q, K, V, BH, Lq, Lk, d, nw, ks, scale, O, st);
-    return launch_mode<MODE_DENSE>(Q, K, V, BH, Lq, Lk, d, nw, ks, scale, O, st);
+// Lq must be a multiple of 32 * nw / ks, Lk of 64.  key_bias and causal as in launch_fused_attention; with either of
+// them nw must be 4 and ks is taken as 1; a block_mask is refused.
+hipError_t launch_fused_attention32(const void *Q, const void *K, const void *V, const float *key_bias, int H,
+                                    const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, int mode,
+                                    int nw, int ks, float scale, void *O, hipStream_t st) {
+    if (mode == 0)
+        return launch_mode<MODE_2TO4>(Q, K, V, key_bias, H, block_mask, causal, BH, Lq, Lk, d, nw, ks, scale, O, st);
+    if (mode == 1)
+        return launch_mode<MODE_1TO2>(Q, K, V, key_bias, H, block_mask, causal, BH, Lq, Lk, d, nw, ks, scale, O, st);
+    return launch_mode<MODE_DENSE>(Q, K, V, key_bias, H, block_mask, causal, BH, Lq, Lk, d, nw, ks, scale, O, st);
 }
 
 }  // namespace dfss
