@@ -8,10 +8,10 @@
 // V staging and uses v_mfma_f32_16x16x32_bf16.
 //
 // The SOFTMAX variant takes the kept SCORES of stage 1 instead of weights and applies the softmax
-// on the way (Sec. 3.1; the max-subtracted form of App. A.1.3 with a running maximum): the scores of
-// a block become exp(s - m) in registers before they enter the matrix instruction, the accumulators and
-// the running sum are rescaled whenever a block raises the maximum m, and the result is divided by the
-// sum at the end.  It replaces the separate softmax kernel (one read and one write of all kept values)
+// on the way (Sec. 3.1; the max-subtracted form of App. A.1.3 with a running reference m in the place of the
+// maximum): the scores of a block become exp(s - m) in registers before they enter the matrix instruction,
+// the accumulators are rescaled when a block exceeds m by more than a threshold, the row sums come from the
+// matrix unit too (an all-ones operand), and the result is divided by the sum at the end.  It replaces the separate softmax kernel (one read and one write of all kept values)
 // in the two-kernel forward pass.
 //
 // V blocks (128 keys x d) are copied global -> LDS by the direct-to-LDS load, double
@@ -108,16 +108,22 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
     const int tr_byte = 8 * (li & 1);
     const int tr_xor = tr_row << 1;        // (row & 3) << 1, key0 is a multiple of 4
 
-    // SOFTMAX: running maximum and sum of row li of each row block (the four lane groups kb of a row hold the
-    // same maximum and their own partial sums)
+    // SOFTMAX: reference value of row li of each row block (the same in the four lane groups kb of a row)
     static_assert(!SOFTMAX || SPARSE, "the softmax is folded into the sparse product only");
     constexpr float kLog2e = 1.4426950408889634f;
-    float m_run[RB], l_run[RB];
+    constexpr float kTau = 8.0f;   // the running reference of a row is raised when a score exceeds it by more than this
+    float m_run[RB];
+    f32x4 acc_l[RB];               // row sums, rows 4 kb + r (from the matrix unit: an all-ones B operand)
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) m_run[rb] = -INFINITY, l_run[rb] = 0.f;
+    for (int rb = 0; rb < RB; ++rb) m_run[rb] = -INFINITY, acc_l[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const uint32_t one2 = 0x3F803F80u;   // two bfloat16 ones
+    typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+    const bf16x16 ones16 = __builtin_bit_cast(bf16x16, u32x8{one2, one2, one2, one2, one2, one2, one2, one2});
 
-    // SOFTMAX: turns the kept scores of one block into exp(s - m) in place (m = the running row maximum after the
-    // block) and keeps the sums; the accumulators hold the blocks before it and are rescaled when m rises
+    // SOFTMAX: turns the kept scores of one block into exp(s - m) in place, m = the row's reference value: the largest
+    // score seen when it was last set.  It is raised (and the accumulators, which hold the blocks before, rescaled)
+    // only when a score exceeds it by more than kTau, so weights stay below e^kTau and the common block needs no
+    // cross-lane traffic; softmax does not depend on m (App. A.1.3 subtracts the row maximum for the same reason).
     auto softmax_block = [&](AFrag (&a)[RB]) {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
@@ -131,31 +137,27 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
             }
             float bm = fmaxf(x[0], x[1]);
 #pragma unroll
-            for (int e = 2; e < 16; e += 2) bm = fmaxf(fmaxf(x[e], x[e + 1]), bm);
-            bm = fmaxf(bm, __shfl_xor(bm, 16, kWave));
-            bm = fmaxf(bm, __shfl_xor(bm, 32, kWave));   // maximum of row li over the block's 64 kept scores
-            const float m_new = fmaxf(m_run[rb], bm);
-            if (__builtin_amdgcn_ballot_w64(m_new > m_run[rb]) != 0) {   // some row of the wave rises: rescale
+            for (int e = 2; e < 16; e += 2) bm = fmaxf(fmaxf(x[e], x[e + 1]), bm);   // this lane's 16 scores
+            // (m_run = -inf, the start: any finite score is above -inf + kTau = -inf)
+            if (__builtin_amdgcn_ballot_w64(bm > m_run[rb] + kTau) != 0) {   // rare after the first blocks
+                bm = fmaxf(bm, __shfl_xor(bm, 16, kWave));
+                bm = fmaxf(bm, __shfl_xor(bm, 32, kWave));   // maximum of row li over the block's 64 kept scores
+                const bool up = bm > m_run[rb] + kTau;       // (the same in the four lanes of a row)
                 // (a row still at -inf gets the factor 0: its sums are 0 anyway)
-                const float f = m_new > m_run[rb] ? exp2f((m_run[rb] - m_new) * kLog2e) : 1.f;
-                l_run[rb] *= f;
+                const float f = up ? exp2f((m_run[rb] - bm) * kLog2e) : 1.f;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const float fr = __shfl(f, 4 * kb + r, kWave);   // accumulator row 4 kb + r
+                    acc_l[rb][r] *= fr;
 #pragma unroll
                     for (int ds = 0; ds < DS; ++ds) acc[rb][ds][r] *= fr;
                 }
-                m_run[rb] = m_new;
+                if (up) m_run[rb] = bm;
             }
             // a row whose keys so far are all masked (-inf): subtract 0, its weights are exp(-inf) = 0
-            const float mb = m_new == -INFINITY ? 0.f : m_new * kLog2e;
-            float sum = 0.f;
+            const float mb = m_run[rb] == -INFINITY ? 0.f : m_run[rb] * kLog2e;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                x[e] = exp2f(__builtin_fmaf(x[e], kLog2e, -mb));
-                sum += x[e];
-            }
-            l_run[rb] += sum;
+            for (int e = 0; e < 16; ++e) x[e] = exp2f(__builtin_fmaf(x[e], kLog2e, -mb));
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 a[rb].v[0][e] = pack_bf16x2(x[2 * e], x[2 * e + 1]);
@@ -206,6 +208,18 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
                                                                                     (int)a_cur[rb].idx, 0, 1);
                     }
                 }
+                if constexpr (SOFTMAX) {   // row sums of the (rounded) weights
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb) {
+                        const bf16x8 a = __builtin_bit_cast(bf16x8, a_cur[rb].v[h]);
+                        if (h == 0)
+                            acc_l[rb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a, ones16, acc_l[rb],
+                                                                                  (int)a_cur[rb].idx, 0, 0);
+                        else
+                            acc_l[rb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a, ones16, acc_l[rb],
+                                                                                  (int)a_cur[rb].idx, 0, 1);
+                    }
+                }
             }
         } else {
 #pragma unroll
@@ -231,17 +245,10 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
     // acc[rb][ds][r] = O[q][16 ds + li], q = 16 (rb0 + rb) + 4 kb + r
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        float inv = 1.f;
-        if constexpr (SOFTMAX) {
-            float l = l_run[rb];
-            l += __shfl_xor(l, 16, kWave);
-            l += __shfl_xor(l, 32, kWave);     // sum of row li over all keys
-            inv = 1.0f / l;
-        }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const size_t q = (size_t)bh * Lq + (size_t)(rb0 + rb) * 16 + 4 * kb + r;
-            const float ir = SOFTMAX ? __shfl(inv, 4 * kb + r, kWave) : 1.f;
+            const float ir = SOFTMAX ? 1.0f / acc_l[rb][r] : 1.f;   // (the sum of row 4 kb + r, in every column)
 #pragma unroll
             for (int ds = 0; ds < DS; ++ds)
                 O[q * D + 16 * ds + li] = (uint16_t)(pack_bf16x2(SOFTMAX ? acc[rb][ds][r] * ir : acc[rb][ds][r], 0.f) & 0xFFFFu);
