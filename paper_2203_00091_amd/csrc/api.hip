@@ -472,8 +472,13 @@ dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K
         if (e == hipSuccess) e = dfss::launch_spmm_t_split(dS, meta, Q, D.BH, D.Lq, D.Lk, D.d, dK, st);     // dK = dS'^T Q
         return hip_status(e);
     }
-    hipError_t e = dfss::launch_masked_sddmm_ds(dO, V, O, P, meta, D.BH, D.Lq, D.Lk, D.d, scale, dS, st);
-    if (e == hipSuccess) e = dfss::launch_spmm(dS, meta, K, D.BH, D.Lq, D.Lk, D.d, dQ, st);      // dQ = dS' K
+    hipError_t e;
+    if (D.d == 64) {   // dS' and dQ = dS' K in one pass over the compressed rows
+        e = dfss::launch_masked_sddmm_ds(dO, V, O, P, meta, K, D.BH, D.Lq, D.Lk, D.d, scale, dS, dQ, st);
+    } else {
+        e = dfss::launch_masked_sddmm_ds(dO, V, O, P, meta, nullptr, D.BH, D.Lq, D.Lk, D.d, scale, dS, nullptr, st);
+        if (e == hipSuccess) e = dfss::launch_spmm(dS, meta, K, D.BH, D.Lq, D.Lk, D.d, dQ, st);   // dQ = dS' K
+    }
     if (e == hipSuccess) e = dfss::launch_spmm_t(P, meta, dO, D.BH, D.Lq, D.Lk, D.d, dV, st);    // dV = P^T dO
     if (e == hipSuccess) e = dfss::launch_spmm_t(dS, meta, Q, D.BH, D.Lq, D.Lk, D.d, dK, st);    // dK = dS'^T Q
     return hip_status(e);

@@ -5,7 +5,8 @@
 // kept entries (Sec. 3.1) and dO the upstream gradient:
 //     dV = P^T dO,   dP = (dO V^T) at the kept positions,   delta_i = dO_i . O_i,
 //     dS = P .* (dP - delta),   dQ = scale dS K,   dK = scale dS^T Q.
-// Two kernels live here; dQ reuses the forward SpMM (stage 3) with K in the place of V.
+// Two kernels live here; dQ comes out of the first one at d = 64 and reuses the forward SpMM (stage 3) with K in the
+// place of V at d = 128.
 //
 //   k_masked_sddmm_ds  dS' = scale * P .* (dO V^T - delta) at the kept positions, written in the
 //                      compressed layout of the forward pass.  It is the stage-1 mainloop with V in
@@ -189,19 +190,27 @@ __global__ __launch_bounds__(NT, 2) void k_spmm_t(const uint32_t *__restrict__ A
 // 32 kb + 16 half .. +15 of query li: four runs of four, of which the position codes name the two
 // kept ones.
 // ------------------------------------------------------------------------------------------------
-template <int D, int NQ>
+// DQ: the same pass also forms dQ = dS' K (the dS' values a lane has just computed ARE the compressed operand of the
+// structured-sparse matrix instruction for its query, and the stored position codes its index operand, exactly as
+// in the forward SpMM), so dS' is not read back for it.  Needs the whole key range in one workgroup (ksplit = 1) and
+// a second LDS tile per block (K in row order for the transposing read): d = 64 only.
+template <int D, int NQ, bool DQ>
 __global__ __launch_bounds__(NT, 2) void k_masked_sddmm_ds(const __bf16 *__restrict__ dO, const __bf16 *__restrict__ V,
                                                            const __bf16 *__restrict__ O,
                                                            const uint32_t *__restrict__ P,
-                                                           const uint32_t *__restrict__ meta, int Lq, int Lk,
+                                                           const uint32_t *__restrict__ meta,
+                                                           const __bf16 *__restrict__ K, int Lq, int Lk,
                                                            float scale, int ksplit, int blocks_per_wg,
-                                                           uint32_t *__restrict__ dS) {
+                                                           uint32_t *__restrict__ dS, uint16_t *__restrict__ dQ) {
     constexpr int CPR = D / 8;           // 16-byte chunks per row
     constexpr int TILE = KB * CPR;       // chunks per V block
     constexpr int LPT = TILE / NT;       // asynchronous copies per thread per block
     constexpr int STEPS = D / 32;        // MFMA k-steps
+    constexpr int DS = D / 16;           // 16-column tiles of dQ
     constexpr int TQ = 64 * NQ;          // queries per workgroup
+    static_assert(!DQ || D == 64, "the fused dQ needs two LDS tiles per block");
     __shared__ u32x4 Vs[2][TILE];
+    __shared__ u32x4 Kr[DQ ? 2 : 1][DQ ? TILE : 1];   // K block, row = key, chunk c at row * CPR + (c ^ ((row & 3) << 1))
 
     const int tid = threadIdx.x;
     const int w = tid >> 6, l = tid & 63, li = l & 15, kb = l >> 4;
@@ -227,10 +236,24 @@ __global__ __launch_bounds__(NT, 2) void k_masked_sddmm_ds(const __bf16 *__restr
         src_off[i] = key * D + c * 8;
     }
     const uint32_t lds_v = lds_address(&Vs[0][w * 64]);
+    int k_off[LPT];
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+        const int p = i * NT + tid;
+        const int row = p / CPR, c = (p % CPR) ^ ((row & 3) << 1);
+        k_off[i] = row * D + c * 8;
+    }
+    const uint32_t lds_k = lds_address(&Kr[0][DQ ? w * 64 : 0]);
+    const __bf16 *Kh = DQ ? K + (size_t)bh * Lk * D : nullptr;
     auto issue_block = [&](int jb, int buf) {
         const __bf16 *src = Vh + (size_t)jb * KB * D;
 #pragma unroll
         for (int i = 0; i < LPT; ++i) async_copy16(src, 2u * src_off[i], lds_v + 16u * (buf * TILE + i * NT));
+        if constexpr (DQ) {
+            const __bf16 *ksrc = Kh + (size_t)jb * KB * D;
+#pragma unroll
+            for (int i = 0; i < LPT; ++i) async_copy16(ksrc, 2u * k_off[i], lds_k + 16u * (buf * TILE + i * NT));
+        }
     };
 
     issue_block(jb0, 0);
@@ -259,6 +282,15 @@ __global__ __launch_bounds__(NT, 2) void k_masked_sddmm_ds(const __bf16 *__restr
 
     const int rb0 = q0 >> 4;                 // first 16-row block of this wave
     const int meta_slot = ((kb & 1) << 1) | (kb >> 1);
+
+    // DQ: accumulators of dQ (rows 4 kb + r of the 16-query tile, column 16 ds + li) and the lane's role in the
+    // transposing read of K (as in the forward SpMM)
+    f32x4 acc_dq[NQ][DS];
+#pragma unroll
+    for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+        for (int ds = 0; ds < DS; ++ds) acc_dq[qs][ds] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int tr_row = li >> 2, tr_sub = (li >> 1) & 1, tr_byte = 8 * (li & 1), tr_xor = tr_row << 1;
 
     for (int it = 0; it < blocks_per_wg; ++it) {
         const int jb = jb0 + it;
@@ -318,8 +350,45 @@ __global__ __launch_bounds__(NT, 2) void k_masked_sddmm_ds(const __bf16 *__restr
                     o[t] = pack_bf16x2(ds_lo, ds_hi);
                 }
                 *reinterpret_cast<u32x4 *>(dS + (row * (size_t)(Lk / 2) + kbase / 2) / 2) = o;
+                if constexpr (DQ) {
+                    // dQ += dS' K over the block's keys 32 c + 16 half .. +15 (c = lane group): instruction `half`
+                    const char *kbase_lds = reinterpret_cast<const char *>(&Kr[buf][0]);
+                    auto tr = [&](int key0, int ds) {
+                        const int krow = key0 + tr_row;
+                        const int chunk = (2 * ds + tr_sub) ^ tr_xor;
+                        return lds_read_tr16(kbase_lds + (krow * CPR + chunk) * 16 + tr_byte);
+                    };
+                    const int k0 = 32 * (kb >> 1) + 16 * half + 8 * (kb & 1);
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, o);
+#pragma unroll
+                    for (int ds = 0; ds < DS; ++ds) {
+                        const s16x4 t0 = tr(k0, ds), t1 = tr(k0 + 4, ds), t2 = tr(64 + k0, ds), t3 = tr(64 + k0 + 4, ds);
+                        const s16x8 lo = __builtin_shufflevector(t0, t1, 0, 1, 2, 3, 4, 5, 6, 7);
+                        const s16x8 hi = __builtin_shufflevector(t2, t3, 0, 1, 2, 3, 4, 5, 6, 7);
+                        const bf16x16 b = __builtin_bit_cast(
+                            bf16x16, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15));
+                        if (half == 0)
+                            acc_dq[qs][ds] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a, b, acc_dq[qs][ds],
+                                                                                       (int)mword[qs], 0, 0);
+                        else
+                            acc_dq[qs][ds] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a, b, acc_dq[qs][ds],
+                                                                                       (int)mword[qs], 0, 1);
+                    }
+                }
             }
         }
+    }
+    if constexpr (DQ) {
+        // acc_dq[qs][ds][r] = dQ[q][16 ds + li], q = q0 + 16 qs + 4 kb + r
+#pragma unroll
+        for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const size_t q = (size_t)bh * Lq + q0 + 16 * qs + 4 * kb + r;
+#pragma unroll
+                for (int ds = 0; ds < DS; ++ds)
+                    dQ[q * D + 16 * ds + li] = (uint16_t)(pack_bf16x2(acc_dq[qs][ds][r], 0.f) & 0xFFFFu);
+            }
     }
 }
 
@@ -343,32 +412,41 @@ namespace dfss {
 
 namespace {
 template <int NQ>
-hipError_t launch_ds_nq(const void *dO, const void *V, const void *O, const void *P, const void *meta, int BH, int Lq,
-                        int Lk, int d, float scale, void *dS, hipStream_t st) {
+hipError_t launch_ds_nq(const void *dO, const void *V, const void *O, const void *P, const void *meta, const void *K,
+                        int BH, int Lq, int Lk, int d, float scale, void *dS, void *dQ, hipStream_t st) {
     const int qtiles = Lq / (64 * NQ);
     const int kblocks = Lk / KB;
-    // split the key range until the grid has a few workgroups per compute unit
+    const bool with_dq = dQ != nullptr;   // (d = 64: checked by the caller)
+    // split the key range until the grid has a few workgroups per compute unit (not with the fused dQ, whose sums
+    // run over all keys of a query)
     int ksplit = 1;
-    while ((long)BH * qtiles * ksplit < 1024 && kblocks % (ksplit * 2) == 0) ksplit *= 2;
-    if ((long)BH * qtiles * ksplit < 1024 && kblocks % 3 == 0 && ksplit == 1) ksplit = 3;
+    if (!with_dq) {
+        while ((long)BH * qtiles * ksplit < 1024 && kblocks % (ksplit * 2) == 0) ksplit *= 2;
+        if ((long)BH * qtiles * ksplit < 1024 && kblocks % 3 == 0 && ksplit == 1) ksplit = 3;
+    }
     const int per_wg = kblocks / ksplit;
     const unsigned grid = (unsigned)((long)BH * qtiles * ksplit);
-    if (d == 64)
-        hipLaunchKernelGGL((k_masked_sddmm_ds<64, NQ>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)dO,
-                           (const __bf16 *)V, (const __bf16 *)O, (const uint32_t *)P, (const uint32_t *)meta, Lq, Lk,
-                           scale, ksplit, per_wg, (uint32_t *)dS);
-    else
-        hipLaunchKernelGGL((k_masked_sddmm_ds<128, NQ>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)dO,
-                           (const __bf16 *)V, (const __bf16 *)O, (const uint32_t *)P, (const uint32_t *)meta, Lq, Lk,
-                           scale, ksplit, per_wg, (uint32_t *)dS);
+#define DFSS_LAUNCH(DD, WITH)                                                                                      \
+    hipLaunchKernelGGL((k_masked_sddmm_ds<DD, NQ, WITH>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)dO,         \
+                       (const __bf16 *)V, (const __bf16 *)O, (const uint32_t *)P, (const uint32_t *)meta,         \
+                       (const __bf16 *)K, Lq, Lk, scale, ksplit, per_wg, (uint32_t *)dS, (uint16_t *)dQ)
+    if (d == 64) {
+        if (with_dq) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
+    } else {
+        DFSS_LAUNCH(128, false);
+    }
+#undef DFSS_LAUNCH
     return hipGetLastError();
 }
 }  // namespace
 
+// K, dQ: both null, or (d = 64 only) the keys and the output of dQ = dS' K, formed in the same pass.
 hipError_t launch_masked_sddmm_ds(const void *dO, const void *V, const void *O, const void *P, const void *meta,
-                                  int BH, int Lq, int Lk, int d, float scale, void *dS, hipStream_t st) {
-    if (Lq % 128 == 0) return launch_ds_nq<2>(dO, V, O, P, meta, BH, Lq, Lk, d, scale, dS, st);
-    return launch_ds_nq<1>(dO, V, O, P, meta, BH, Lq, Lk, d, scale, dS, st);
+                                  const void *K, int BH, int Lq, int Lk, int d, float scale, void *dS, void *dQ,
+                                  hipStream_t st) {
+    if (dQ && d != 64) return hipErrorInvalidValue;
+    if (Lq % 128 == 0) return launch_ds_nq<2>(dO, V, O, P, meta, K, BH, Lq, Lk, d, scale, dS, dQ, st);
+    return launch_ds_nq<1>(dO, V, O, P, meta, K, BH, Lq, Lk, d, scale, dS, dQ, st);
 }
 
 }  // namespace dfss
