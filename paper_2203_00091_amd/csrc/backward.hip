@@ -306,6 +306,7 @@ __global__ __launch_bounds__(NT, 2) void k_masked_sddmm_ds(const __bf16 *__restr
         for (int qs = 0; qs < NQ; ++qs)
             mword[qs] = meta[((((size_t)bh * (Lq / 16) + rb0 + qs) * (Lk / KB) + jb) * 16 + li) * 4 + meta_slot];
 
+        u32x4 ds_out[2][NQ];   // dS' of both halves: a lane's 32 contiguous bytes, stored together
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             const int kbase = KB * jb + 32 * kb + 16 * half;
@@ -349,7 +350,7 @@ __global__ __launch_bounds__(NT, 2) void k_masked_sddmm_ds(const __bf16 *__restr
                     const float ds_hi = bf16_hi_to_f32(pw[qs][t]) * (dp_hi - delta[qs]) * scale;
                     o[t] = pack_bf16x2(ds_lo, ds_hi);
                 }
-                *reinterpret_cast<u32x4 *>(dS + (row * (size_t)(Lk / 2) + kbase / 2) / 2) = o;
+                ds_out[half][qs] = o;
                 if constexpr (DQ) {
                     // dQ += dS' K over the block's keys 32 c + 16 half .. +15 (c = lane group): instruction `half`
                     const char *kbase_lds = reinterpret_cast<const char *>(&Kr[buf][0]);
@@ -376,6 +377,15 @@ __global__ __launch_bounds__(NT, 2) void k_masked_sddmm_ds(const __bf16 *__restr
                     }
                 }
             }
+        }
+        // the two halves of a lane are adjacent in memory (keys 32 kb .. +31 of the row): issued back to back, the
+        // four lanes of a row complete a whole 128-byte line
+#pragma unroll
+        for (int qs = 0; qs < NQ; ++qs) {
+            const size_t row = (size_t)bh * Lq + q0 + 16 * qs + li;
+            u32x4 *dst = reinterpret_cast<u32x4 *>(dS + (row * (size_t)(Lk / 2) + (KB * jb + 32 * kb) / 2) / 2);
+            dst[0] = ds_out[0][qs];
+            dst[1] = ds_out[1][qs];
         }
     }
     if constexpr (DQ) {
