@@ -250,9 +250,9 @@ dfss_status dfss_spmm_t(const void *vals, const void *meta, const void *X, const
  * (run the three stage calls to keep them; they compose to dfss_attention).  Outputs: dQ [B*H, Lq, d],
  * dK, dV [B*H, Lk, d], bfloat16.  ws: device scratch of at least dfss_backward_workspace_bytes(),
  * 256-byte aligned (holds dS).  A key bias of the forward pass needs no extra argument: masked
- * entries have weight 0 and so receive and pass on no gradient.  Four kernels: the stage-1 mainloop
- * with the stored position codes in the place of the selection, the stage-3 SpMM (dQ), and the
- * transposed sparse product twice (dV, dK). */
+ * entries have weight 0 and so receive and pass on no gradient.  Kernels: the stage-1 mainloop with the stored
+ * position codes in the place of the selection (dS; at d = 64 it forms dQ in the same pass, at d = 128 the
+ * stage-3 SpMM does), and the transposed sparse product twice (dV, dK). */
 size_t dfss_backward_workspace_bytes(const dfss_shape *s);
 dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K, const void *V, const void *O,
                                     const void *P, const void *meta, const dfss_shape *s, float scale, void *dQ,
