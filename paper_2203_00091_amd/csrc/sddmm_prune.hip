@@ -129,6 +129,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
 #pragma unroll
         for (int qs = 0; qs < NQ; ++qs) mword[qs] = 0;
 
+        u32x4 kept_out[2][NQ];   // kept values of both halves: a lane's 32 contiguous bytes, stored together
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             f32x4 acc[NQ][4];
@@ -215,11 +216,20 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
                         pk[t] = pack_bf16x2(lo, hi);
                         mword[qs] |= code;
                     }
-                    *reinterpret_cast<u32x4 *>(out + (row * (size_t)(Lk / 2) + kbase / 2) / 2) = pk;
+                    kept_out[half][qs] = pk;
                 }
             }
         }
         if constexpr (MODE != MODE_DENSE) {
+            // the two halves of a lane are adjacent in memory (keys 32 kb .. +31 of the row): issued back to back,
+            // the four lanes of a row complete a whole 128-byte line
+#pragma unroll
+            for (int qs = 0; qs < NQ; ++qs) {
+                const size_t row = (size_t)bh * Lq + q0 + 16 * qs + li;
+                u32x4 *dst = reinterpret_cast<u32x4 *>(out + (row * (size_t)(Lk / 2) + (KB * jb + 32 * kb) / 2) / 2);
+                dst[0] = kept_out[0][qs];
+                dst[1] = kept_out[1][qs];
+            }
 #pragma unroll
             for (int qs = 0; qs < NQ; ++qs)
                 meta[((((size_t)bh * (Lq / 16) + rb0 + qs) * (Lk / KB) + jb) * 16 + li) * 4 + (((kb & 1) << 1) | (kb >> 1))] =
