@@ -266,7 +266,10 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
     //          32 rows
     //   Bs     bias of the block's 128 keys (double buffer), copied along with K
     constexpr int STAGE = MODE == MODE_DENSE ? 0 : 32 * 8;   // 16-byte units per wave
-    __shared__ u32x4 Smem[2 * TILE + 4 * STAGE + (BIAS ? 2 * (KB / 4) : 0)];
+    // (d = 128: K and the staging fill the 80 KiB that let two workgroups share a compute unit, so there the bias
+    // is read from global memory into registers at the top of every block instead)
+    constexpr bool BIAS_LDS = BIAS && D == 64;
+    __shared__ u32x4 Smem[2 * TILE + 4 * STAGE + (BIAS_LDS ? 2 * (KB / 4) : 0)];
     u32x4(*const Ks)[TILE] = reinterpret_cast<u32x4(*)[TILE]>(Smem);
     f32x4(*const Bs)[KB / 4] = reinterpret_cast<f32x4(*)[KB / 4]>(Smem + 2 * TILE + 4 * STAGE);
 
@@ -300,7 +303,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
         const __bf16 *src = Kh + (size_t)jb * KB * D;
 #pragma unroll
         for (int i = 0; i < LPT; ++i) async_copy16(src, 2u * src_off[i], lds_k + 16u * (buf * TILE + i * NT));
-        if constexpr (BIAS) {   // 512 bytes: lanes 0..31 of wave 0 (the copy lands through the same counter as K)
+        if constexpr (BIAS_LDS) {   // 512 bytes: lanes 0..31 of wave 0 (the copy lands through the same counter as K)
             if (tid < KB / 4) async_copy16(bias_b + (size_t)jb * KB, 16u * tid, lds_b + (uint32_t)(buf * KB * 4));
         }
     };
@@ -346,6 +349,17 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
         if (it == 0) wait_async_copies();
         else wait_async_copies_keep<kStores>();
         __syncthreads();       // ... for every wave, and everybody is done with the block before
+        f32x4 kbg[2][2][4];    // (BIAS without LDS) bias of keys 128 jb + 64 p + 32 h + 16 u + 4 g + x, loaded before the
+                               // next block's copies are issued so that waiting for it does not wait for them
+        if constexpr (BIAS && !BIAS_LDS) {
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        kbg[p][u][g] = *reinterpret_cast<const f32x4 *>(bias_b + (size_t)jb * KB + 64 * p + 32 * h + 16 * u + 4 * g);
+        }
         if (it + 1 < blocks_per_wg) issue_block(jb + 1, buf ^ 1);
 
         u32x2 mwords = {0u, 0u};
@@ -357,7 +371,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
 #pragma unroll
                 for (int u = 0; u < 2; ++u)
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) kb4[u][g] = Bs[buf][16 * p + 8 * h + 4 * u + g];
+                    for (int g = 0; g < 4; ++g) kb4[u][g] = BIAS_LDS ? Bs[buf][16 * p + 8 * h + 4 * u + g] : kbg[p][u][g];
             }
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
