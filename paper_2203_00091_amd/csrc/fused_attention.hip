@@ -54,8 +54,12 @@ enum { MODE_2TO4 = 0, MODE_1TO2 = 1, MODE_DENSE = 2 };
 //              past the last visible key of the workgroup's queries are skipped like pruned blocks, and in
 //              the blocks that the diagonal of some query of the workgroup cuts the hidden scores are
 //              overwritten by index.
-template <int D, int MODE, int NQ, bool PRESCALE, bool MASKED, bool RAGGED = false>
-__global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
+//   G          key groups (block patterns only).  The workgroup has G x 4 waves: group g takes every G-th block that the
+//              64 queries visit (the g-th, G + g-th, ... of the list), through K/V buffers of its own; the G partial
+//              results of a query tile are merged through LDS at the end (as the key halves of a split are).
+//              A row block that sees every key then costs 1/G of the time, and the rows of a pattern differ widely.
+template <int D, int MODE, int NQ, bool PRESCALE, bool MASKED, bool RAGGED = false, int G = 1>
+__global__ __launch_bounds__(NT * G, 2) void k_fused(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
                                                  const __bf16 *__restrict__ V, const float *__restrict__ key_bias,
                                                  int H, const uint8_t *__restrict__ block_mask, int causal, int Lq,
                                                  int Lk, float scale, uint16_t *__restrict__ O) {
@@ -67,11 +71,13 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
     constexpr int TQ = 64 * NQ;         // queries per workgroup
     constexpr bool SPARSE = MODE != MODE_DENSE;
     static_assert(!RAGGED || MASKED, "ragged lengths use the masking machinery");
-    __shared__ u32x4 Ks[2][TILE];
-    __shared__ u32x4 Vs[2][TILE];
+    static_assert(G == 1 || (MASKED && !RAGGED && NQ == 1), "key groups: block patterns on 64-query workgroups");
+    __shared__ u32x4 Smem[G * 4 * TILE];   // per key group: two K buffers, then two V buffers
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x & (NT - 1);   // within the key group
     const int w = tid >> 6, l = tid & 63, li = l & 15, kb = l >> 4;
+    const int g = G > 1 ? __builtin_amdgcn_readfirstlane((int)threadIdx.x / NT) : 0;
+    u32x4 *const Ks = Smem + g * (4 * TILE), *const Vs = Ks + 2 * TILE;
 
     const unsigned qtiles = (Lq + TQ - 1) / TQ;
     int qt, bh;
@@ -108,7 +114,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
         k_off[i] = key * D + ((p % CPR) ^ (slot & 7)) * 8;
         v_off[i] = slot * D + ((p % CPR) ^ tr_row_swizzle<CPR>(slot)) * 8;
     }
-    const uint32_t lds_k = lds_address(&Ks[0][w * 64]), lds_v = lds_address(&Vs[0][w * 64]);
+    const uint32_t lds_k = lds_address(&Ks[w * 64]), lds_v = lds_address(&Vs[w * 64]);
     const uint64_t k_base = uniform_address(Kh), v_base = uniform_address(Vh);
     auto issue_block = [&](int jb, int buf) {
         const uint64_t ks = k_base + (uint64_t)jb * (KB * D * 2);
@@ -132,7 +138,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
         for (int i = 0; i < LPT; ++i) async_copy16(vs, 2u * v_off[i], lds_v + 16u * (buf * TILE + i * NT));
     };
 
-    issue_block(0, 0);   // block 0 is copied before anything else (with a key bias: speculatively)
+    if (g == 0) issue_block(0, 0);   // block 0 is copied before anything else (with a key bias or a pattern: speculatively)
 
     // Q operand (B side of Q K^T): lane (column li, chunk kb) of step s holds Q[q][32 s + 8 kb .. +7]
     bf16x8 bq[NQ][STEPS];
@@ -183,18 +189,40 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
     } else {
         blocks.init(false, nullptr, false, nullptr, 0, 0, TQ, 0, Lq, Lk, nblocks, l);
     }
-    auto take_live = [&]() -> int { return blocks.take(); };
+    // The next block of this wave's key group: G blocks come off the list, one per group.  `lead` is group 0's,
+    // the first of the G: while it exists the round exists, and every group passes the round's barrier.
+    int lead_n = 0;
+    auto take_live = [&]() -> int {
+        if constexpr (G == 1) {
+            return lead_n = blocks.take();
+        } else {
+            int mine = nblocks;
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                const int j = blocks.take();
+                if (i == 0) lead_n = j;
+                if (i == g) mine = j;
+            }
+            return mine;
+        }
+    };
     int jb = take_live();
+    int lead = lead_n;
     int jn = take_live();   // the block after this one
     // block 0 (copied speculatively at the top) turned out to be fully masked: overwrite the buffer
     // with the first live block (the two copies of a wave complete in issue order)
-    if (MASKED && jb != 0 && jb < nblocks) issue_block(jb, 0);
+    if (MASKED && (g != 0 || jb != 0) && jb < nblocks) issue_block(jb, 0);
 
-    for (int it = 0; jb < nblocks; ++it) {
+    for (int it = 0; lead < nblocks; ++it) {
         const int buf = it & 1;
         wait_async_copies();  // vmcnt(0): this block's copies have landed
         __syncthreads();
         if (jn < nblocks) issue_block(jn, buf ^ 1);
+        if (G > 1 && jb >= nblocks) {   // this group has no block in the last round
+            jb = jn, lead = lead_n;
+            jn = take_live();
+            continue;
+        }
 
         // ---- scores: acc[qs][t][r] = s(query q0 + 16 qs + li, key 64 jb + 16 kb + 4 t + r) ----
         bool with_bias = false;   // does this block hold a non-zero bias?
@@ -206,7 +234,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
                 bf16x8 ak[4];
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
-                    ak[t] = __builtin_bit_cast(bf16x8, Ks[buf][(16 * t + li) * CPR + ((4 * s + kb) ^ (li & 7))]);
+                    ak[t] = __builtin_bit_cast(bf16x8, Ks[buf * TILE + (16 * t + li) * CPR + ((4 * s + kb) ^ (li & 7))]);
 #pragma unroll
                 for (int qs = 0; qs < NQ; ++qs)
 #pragma unroll
@@ -337,7 +365,7 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
         }
 
         // ---- O += P V ; row sums += P 1 ----
-        const char *vbase = reinterpret_cast<const char *>(&Vs[buf][0]);
+        const char *vbase = reinterpret_cast<const char *>(&Vs[buf * TILE]);
         auto tr = [&](int key0, int ds) {
             const int row = key0 + tr_row;
             const int chunk = (2 * ds + tr_sub) ^ tr_row_swizzle<CPR>(row);
@@ -388,17 +416,57 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
                 }
             }
         }
-        jb = jn;
+        jb = jn, lead = lead_n;
         jn = take_live();
     }
     if constexpr (MASKED) wait_async_copies();   // (only matters if no block was live: the speculative copy)
 
+    if constexpr (G > 1) {
+        // ---- merge the key groups: groups 1 .. G-1 hand (reference, row sums, O) to group 0 through LDS ----
+        // Lane for lane (wave w of every group holds the same queries in the same places): value f of a lane at
+        // float f * 64 + l of the wave's slot.  The slots lie behind the rows that the store of O stages.
+        constexpr int NF = 4 * DS + 5;   // floats per lane
+        __syncthreads();   // every wave is done with the K/V buffers
+        float *const slots = reinterpret_cast<float *>(Smem + 2 * TILE);
+        static_assert((size_t)2 * TILE * 16 + (size_t)(G - 1) * 4 * NF * 64 * 4 <= (size_t)G * 4 * TILE * 16, "the slots fit");
+        if (g != 0) {
+            float *const mine = slots + ((g - 1) * 4 + w) * (NF * 64) + l;
+            mine[0] = m_ref[0];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) mine[(1 + r) * 64] = acc_l[0][r];
+#pragma unroll
+            for (int ds = 0; ds < DS; ++ds)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) mine[(5 + 4 * ds + r) * 64] = acc_o[0][ds][r];
+        }
+        __syncthreads();
+        if (g != 0) return;
+#pragma unroll
+        for (int h = 1; h < G; ++h) {
+            const float *const theirs = slots + ((h - 1) * 4 + w) * (NF * 64) + l;
+            const float m_b = theirs[0];
+            const float m_new = fmaxf(m_ref[0], m_b);
+            const float fa = __builtin_amdgcn_exp2f((m_ref[0] - m_new) * kLog2e);
+            const float fb = __builtin_amdgcn_exp2f((m_b - m_new) * kLog2e);
+            m_ref[0] = m_new;
+            // rows of acc_o/acc_l are queries 4 kb + r: their factors sit in the lanes of that column
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float a_r = __shfl(fa, 4 * kb + r, 64), b_r = __shfl(fb, 4 * kb + r, 64);
+                acc_l[0][r] = acc_l[0][r] * a_r + theirs[(1 + r) * 64] * b_r;
+#pragma unroll
+                for (int ds = 0; ds < DS; ++ds)
+                    acc_o[0][ds][r] = acc_o[0][ds][r] * a_r + theirs[(5 + 4 * ds + r) * 64] * b_r;
+            }
+        }
+    }
+
     // ---- O[q][16 ds + li] = acc_o / row sum, q = q0 + 16 qs + 4 kb + r ----
     // A lane holds single elements of 4 rows; they pass through LDS (the K buffers, free now) so that
     // every lane stores 16 contiguous bytes and a row leaves as one 2 D-byte run.
-    __syncthreads();   // every wave is done reading K
+    if constexpr (G == 1) __syncthreads();   // every wave is done reading K
     constexpr int ROWB = 2 * D + 16;   // padded row: the four lane groups of a column fall into different banks
-    char *const stage = reinterpret_cast<char *>(&Ks[0][0]) + w * (16 * ROWB);
+    char *const stage = reinterpret_cast<char *>(Smem) + w * (16 * ROWB);
     static_assert(4 * 16 * ROWB <= 2 * TILE * 16, "the staging rows fit into the K buffers");
     constexpr int RPP = kWave / CPR;   // rows per read-back pass (CPR lanes x 16 bytes cover a row)
 #pragma unroll
@@ -422,6 +490,13 @@ __global__ __launch_bounds__(NT, 2) void k_fused(const __bf16 *__restrict__ Q, c
         wave_lds_sync();   // the staging rows are free for the next tile
     }
 }
+
+// Block patterns at d = 64: rows of at least this many keys run with two key groups (measured on window + global +
+// random patterns: 13.0 against 15.5 us at 1024 keys, 21 against 28 at 2048, 40 against 51 at 4096, where the row
+// blocks that see every key set the kernel time; a pattern with no such rows loses about a fifth, 26 against 21 us
+// at 4096).  Four groups, or two at d = 128, need the LDS of a whole compute unit: one workgroup per unit, which
+// measured slower than no groups at all.
+constexpr int kGroupsFromKeys = 1024;
 
 inline bool is_pow2(float x) {
     int e;
@@ -447,6 +522,23 @@ hipError_t launch_nq(const void *Q, const void *K, const void *V, const float *k
     return hipGetLastError();
 }
 
+// Block patterns on long rows at d = 64: two key groups.
+template <int MODE>
+hipError_t launch_groups(const void *Q, const void *K, const void *V, const float *key_bias, int H,
+                         const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, float scale, void *O,
+                         hipStream_t st) {
+    const unsigned grid = (unsigned)((long)BH * (Lq / 64));
+    const bool pre = is_pow2(scale);
+#define DFSS_LAUNCH(DD, PRE, GG)                                                                                \
+    hipLaunchKernelGGL((k_fused<DD, MODE, 1, PRE, true, false, GG>), dim3(grid), dim3(NT * GG), 0, st,          \
+                       (const __bf16 *)Q, (const __bf16 *)K, (const __bf16 *)V, key_bias, H, block_mask, causal, \
+                       Lq, Lk, scale, (uint16_t *)O)
+    if (d != 64) return hipErrorInvalidValue;
+    if (pre) DFSS_LAUNCH(64, true, 2); else DFSS_LAUNCH(64, false, 2);
+#undef DFSS_LAUNCH
+    return hipGetLastError();
+}
+
 template <int MODE>
 hipError_t launch(const void *Q, const void *K, const void *V, const float *key_bias, int H,
                   const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, float scale, void *O,
@@ -461,6 +553,8 @@ hipError_t launch(const void *Q, const void *K, const void *V, const float *key_
             return launch_nq<MODE, 2, true, true>(Q, K, V, key_bias, H, nullptr, causal, BH, Lq, Lk, d, scale, O, st);
         return launch_nq<MODE, 1, true, true>(Q, K, V, key_bias, H, nullptr, causal, BH, Lq, Lk, d, scale, O, st);
     }
+    if (block_mask && d == 64 && Lk >= kGroupsFromKeys && variant == DFSS_VARIANT_AUTO)
+        return launch_groups<MODE>(Q, K, V, key_bias, H, block_mask, causal, BH, Lq, Lk, d, scale, O, st);
     if (key_bias || block_mask || causal) {
         if (two)
             return launch_nq<MODE, 2, true>(Q, K, V, key_bias, H, block_mask, causal, BH, Lq, Lk, d, scale, O, st);

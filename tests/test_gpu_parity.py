@@ -563,6 +563,55 @@ def test_attention_blocked(BH, Lq, Lk, d, N, M):
     assert np.max(np.abs(ref - oracle.attention(Qn, Kn, Vn, N, M, scale))) > 0.05
 
 
+@pytest.mark.parametrize("BH,H,L,d,N,M,scale", [
+    (2, 1, 1024, 64, 2, 4, 0.125),      # key groups; the scale folds into Q
+    (2, 2, 1024, 64, 1, 2, 0.11),       # the scale is applied to the scores
+    (2, 1, 1024, 128, 2, 4, 0.0884),    # d = 128: no key groups, same pattern
+    (1, 1, 2048, 64, 2, 4, 0.125),      # 32 key blocks
+])
+def test_attention_blocked_long_rows_of_every_weight(BH, H, L, d, N, M, scale):
+    """At d = 64 rows of 1024 keys and more are cut into key groups inside the workgroup (every group takes every
+    G-th visited block and the partial results are merged).  The pattern gives the row blocks 1, 2, 3, 4, 5, 7, 9
+    and all blocks, at positions that leave some groups without any block or with one block fewer than the
+    others; a key bias masks keys inside and across visited blocks."""
+    nb = L // 64
+    bm = torch.zeros((nb, nb), dtype=torch.uint8)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(8200 + L + d)
+    counts = [nb, 1, 2, 3, 4, 5, 7, 9]
+    for i in range(nb):
+        c = counts[i % len(counts)]
+        bm[i, torch.randperm(nb, generator=g)[:c]] = 1
+    bm[nb - 1] = 0
+    bm[nb - 1, nb - 1] = 1     # only the very last block
+    bm[nb - 2] = 1             # a second full row
+    Q, K, V = synth.gaussian_qkv(BH, L, L, d, 1.0, seed=8201 + L + d)
+    # scores that grow along the keys: later groups' references lie above earlier ones', so the merge rescales
+    K = (K.float() * torch.linspace(0.5, 2.0, L)[None, :, None]).to(torch.bfloat16)
+    bias = torch.zeros((BH // H, L), dtype=torch.float32)
+    bias[0, 100:200] = float("-inf")         # block 1 partly, block 2 fully
+    bias[-1, L - 64 * 3:L - 64] = -1.5       # finite bias in two blocks
+    s = Shape(BH // H, H, L, L, d, N, M)
+    Qd, Kd, Vd, bmd, bd = _dev(Q), _dev(K), _dev(V), _dev(bm), _dev(bias)
+    Qn, Kn, Vn = (synth.to_numpy_f32(t) for t in (Q, K, V))
+    for kb, kbd in ((None, None), (bias, bd)):
+        O = dfss.dfss_attention_blocked(Qd, Kd, Vd, kbd, bmd, s, scale)
+        Od = dfss.dense_attention_fused_blocked(Qd, Kd, Vd, kbd, bmd, s, scale)
+        torch.cuda.synchronize()
+        kw = dict(block_mask=bm.numpy(), block_size=64)
+        if kb is not None:
+            kw.update(key_bias=kb.numpy(), heads_per_batch=H)
+        ref = oracle.attention(Qn, Kn, Vn, N, M, scale, **kw)
+        ref_dense = oracle.attention(Qn, Kn, Vn, 1, 1, scale, **kw)
+        # rows whose every visited key is masked have no defined output: none here except via the bias in row
+        # blocks that see only block 2 of batch element 0
+        ok = np.isfinite(ref).all(-1)
+        assert ok.mean() > 0.9
+        assert np.isfinite(_np(O)[ok]).all()
+        assert np.max(np.abs(_np(O)[ok] - ref[ok])) <= 2e-2
+        assert np.max(np.abs(_np(Od)[ok] - ref_dense[ok])) <= 2e-2
+
+
 def test_attention_blocked_with_key_bias_and_full_pattern():
     B, H, L, d = 2, 2, 384, 64
     Q, K, V, lengths, bias = _padding_case(B, H, L, L, d, 8100, integer=False)
