@@ -172,8 +172,6 @@ __global__ __launch_bounds__(NT * G, 2) void k_fused(const __bf16 *__restrict__ 
         for (int ds = 0; ds < DS; ++ds) acc_o[qs][ds] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
     const uint32_t one2 = 0x3F803F80u;  // two bfloat16 ones
-    const bf16x16 ones16 = __builtin_bit_cast(bf16x16, (uint32_t __attribute__((ext_vector_type(8)))){
-                                                            one2, one2, one2, one2, one2, one2, one2, one2});
     const bf16x8 ones8 = __builtin_bit_cast(bf16x8, u32x4{one2, one2, one2, one2});
 
     const int tr_row = li >> 2, tr_sub = (li >> 1) & 1, tr_byte = 8 * (li & 1);
@@ -391,7 +389,7 @@ __global__ __launch_bounds__(NT * G, 2) void k_fused(const __bf16 *__restrict__ 
 #pragma unroll
             for (int qs = 0; qs < NQ; ++qs) {
                 const bf16x8 a = __builtin_bit_cast(bf16x8, u32x4{pk[qs][0], pk[qs][1], pk[qs][2], pk[qs][3]});
-                acc_l[qs] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a, ones16, acc_l[qs], (int)idx[qs], 0, 0);
+                acc_l[qs] = mfma16(a, ones8, acc_l[qs]);   // (against ones the positions do not matter: dense instruction)
             }
         } else {
             // dense: MFMA m (0/1) contracts the lane's keys 16 kb + 8 m .. +7

@@ -157,8 +157,6 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
         for (int dt = 0; dt < DT; ++dt) acc_o[dt][r] = 0.f;
     }
     const uint32_t one2 = 0x3F803F80u;  // two bfloat16 ones
-    const bf16x16 ones16 =
-        __builtin_bit_cast(bf16x16, u32x8{one2, one2, one2, one2, one2, one2, one2, one2});
     const bf16x8 ones8 = __builtin_bit_cast(bf16x8, u32x4{one2, one2, one2, one2});
 
     // transposing LDS read (per group of 16 lanes): lane s addresses V[key0 + s/4][col0 + 4 (s%4)]
@@ -350,8 +348,9 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
                     if (t + 1 < KT) acc_o[dt] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a, b, acc_o[dt], (int)idx, 0, 0);
                     else acc_o[dt] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a, b, acc_o[dt], (int)idx, 0, 1);
                 }
-                if (t + 1 < KT) acc_l = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a, ones16, acc_l, (int)idx, 0, 0);
-                else acc_l = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a, ones16, acc_l, (int)idx, 0, 1);
+                // row sums: against ones the positions do not matter, so the kept weights go through the dense
+                // instruction as 16 "keys" per row (32 cycles against 43 for the sparse one)
+                acc_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, ones8, acc_l, 0, 0, 0);
             } else {
                 // dense: MFMA m (0/1) contracts the lanes' keys 16 h' + 8 m .. +7 (h' = 0, 1)
 #pragma unroll

@@ -117,8 +117,7 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) m_run[rb] = -INFINITY, acc_l[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
     const uint32_t one2 = 0x3F803F80u;   // two bfloat16 ones
-    typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
-    const bf16x16 ones16 = __builtin_bit_cast(bf16x16, u32x8{one2, one2, one2, one2, one2, one2, one2, one2});
+    const bf16x8 ones8 = __builtin_bit_cast(bf16x8, u32x4{one2, one2, one2, one2});
 
     // SOFTMAX: turns the kept scores of one block into exp(s - m) in place, m = the row's reference value: the largest
     // score seen when it was last set.  It is raised (and the accumulators, which hold the blocks before, rescaled)
@@ -212,12 +211,8 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb) {
                         const bf16x8 a = __builtin_bit_cast(bf16x8, a_cur[rb].v[h]);
-                        if (h == 0)
-                            acc_l[rb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a, ones16, acc_l[rb],
-                                                                                  (int)a_cur[rb].idx, 0, 0);
-                        else
-                            acc_l[rb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a, ones16, acc_l[rb],
-                                                                                  (int)a_cur[rb].idx, 0, 1);
+                        // (against ones the positions do not matter: the dense instruction, 32 "keys" per row)
+                        acc_l[rb] = mfma16(a, ones8, acc_l[rb]);
                     }
                 }
             }
