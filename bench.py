@@ -184,6 +184,12 @@ def run_workload(name, args, timer, torch, dfss, synth, headline):
         density = float(bm.float().mean())
         block_mask = bm.to(dev)
 
+    # block patterns: long row blocks shared between workgroups through a workspace where that measured faster
+    # (2-byte data, d = 64, rows of 2048 keys and more)
+    split_rows = block_mask is not None and not f32 and d == 64 and L >= 2048
+    ws_split = (torch.empty(dfss.dfss_blocked_split_workspace_bytes(s), dtype=torch.uint8, device=dev)
+                if split_rows else None)
+
     causal = bool(headline and args.causal)
     if causal:
         density = (L + 1) / (2.0 * L)      # visible entries of the score matrix
@@ -192,6 +198,8 @@ def run_workload(name, args, timer, torch, dfss, synth, headline):
         b = sets[i % nsets]
         if causal:
             dfss.dfss_attention_causal(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"])
+        elif split_rows:
+            dfss.dfss_attention_blocked_split(b["Q"], b["K"], b["V"], bias, block_mask, s, w.scale, O=b["O"], ws=ws_split)
         elif block_mask is not None:
             dfss.dfss_attention_blocked(b["Q"], b["K"], b["V"], bias, block_mask, s, w.scale, O=b["O"])
         elif has_fused:
@@ -203,6 +211,9 @@ def run_workload(name, args, timer, torch, dfss, synth, headline):
         b = sets[i % nsets]
         if causal:
             dfss.dense_attention_fused_causal(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"])
+        elif split_rows:
+            dfss.dense_attention_fused_blocked_split(b["Q"], b["K"], b["V"], bias, block_mask, s, w.scale, O=b["O"],
+                                                     ws=ws_split)
         elif block_mask is not None:
             dfss.dense_attention_fused_blocked(b["Q"], b["K"], b["V"], bias, block_mask, s, w.scale, O=b["O"])
         else:
@@ -240,8 +251,13 @@ def run_workload(name, args, timer, torch, dfss, synth, headline):
         vals, meta = stage_buffers(i)
         dfss.dfss_spmm(vals, meta, b["V"], s, O=b["O"])
 
+    def step_blocked_plain(i):   # the call without workspace, for comparison
+        b = sets[i % nsets]
+        dfss.dfss_attention_blocked(b["Q"], b["K"], b["V"], bias, block_mask, s, w.scale, O=b["O"])
+
     blocked = block_mask is not None
     ms, replays = timer(step_sparse)
+    ms_blocked_plain = timer(step_blocked_plain)[0] if split_rows else None
     ms_dense_fused = timer(step_dense_fused)[0] if has_fused else None
     if blocked:      # only the one-kernel paths take a block pattern
         ms_staged = ms_dense = k1 = k2 = k3 = None
@@ -271,6 +287,12 @@ def run_workload(name, args, timer, torch, dfss, synth, headline):
         "staged_speedup_vs_dense_attention_3stage": None if blocked else round(ms_dense / ms_staged, 4),
         "speedup_vs_dense_attention_3stage": None if blocked else round(ms_dense / ms, 4),
     }
+    if blocked:
+        res["block_pattern_entry_points"] = ("dfss_attention_blocked_split / dense_attention_fused_blocked_split "
+                                             "(main kernel + merge kernel per step)" if split_rows else
+                                             "dfss_attention_blocked / dense_attention_fused_blocked")
+        res["dfss_attention_blocked_without_workspace_ms"] = (None if ms_blocked_plain is None
+                                                              else round(ms_blocked_plain, 5))
     if not blocked:
         # Algorithmic bytes per head: stage 1 reads Q, K = 4 L d and writes kept values L^2 plus metadata L^2 / 8;
         # stage 2 reads and writes L^2; stage 3 reads 1.125 L^2 + V and writes O (2-byte data; the 4-byte mode doubles all)
@@ -378,7 +400,9 @@ def main():
         roofline = {"bound": "mfma",
                     "kernel": ("k_fused_split (dfss_attention, float data, bf16x3 products)" if f32 else
                                "k_fused32 (dfss_attention, one kernel per step)" if plain else
-                               "k_fused (the masked one-kernel path, one kernel per step)"),
+                               "k_fused + k_merge_split (block pattern, long row blocks shared; two kernels per step)"
+                               if head.get("block_pattern_entry_points", "").startswith("dfss_attention_blocked_split")
+                               else "k_fused (the masked one-kernel path, one kernel per step)"),
                     "achieved": round(flops_alg / (ms * 1e-3) / 1e12, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(flops_alg / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                     "traffic": None if traffic is None else traffic[0],

@@ -217,6 +217,28 @@ dfss_status dense_attention_fused_blocked(const void *Q, const void *K, const vo
                                           const void *block_mask, const dfss_shape *s, float scale, void *O,
                                           void *stream);
 
+/* The same two functions with a workspace, for patterns whose row blocks differ widely in length (a
+ * few "global" row blocks that see every key next to rows that see a window: the pattern family of
+ * the block-sparse long-sequence models the paper combines with).  The first four row blocks of the
+ * pattern that keep more than 16 blocks are each shared between four workgroups, which take every
+ * fourth kept block; their partial results (running reference, row sums, unnormalised O; fp32) pass
+ * through ws and a second kernel merges them in a fixed order, so results are deterministic.  Every
+ * other row block is computed as in the calls above.  Which row blocks are shared depends on
+ * block_mask alone.  Results equal those of the calls above up to the rounding of the merge.
+ * Pays where the long row blocks set the time of the call above: d = 64 and 2048 keys or more
+ * (elsewhere it costs the second launch and gains nothing).
+ * ws: device, 16-byte aligned, at least dfss_blocked_split_workspace_bytes(s) bytes (0 = unsupported
+ * shape or dtype; 2-byte dtype only), caller-owned, contents undefined before and after; no
+ * initialisation needed.  Errors as above, plus DFSS_ERR_WORKSPACE. */
+size_t dfss_blocked_split_workspace_bytes(const dfss_shape *s);
+dfss_status dfss_attention_blocked_split(const void *Q, const void *K, const void *V, const void *key_bias,
+                                         const void *block_mask, const dfss_shape *s, float scale, void *O,
+                                         void *ws, size_t ws_bytes, void *stream);
+dfss_status dense_attention_fused_blocked_split(const void *Q, const void *K, const void *V,
+                                                const void *key_bias, const void *block_mask,
+                                                const dfss_shape *s, float scale, void *O, void *ws,
+                                                size_t ws_bytes, void *stream);
+
 /* ---- lengths that are not tile multiples (one-kernel paths) --------------------------- */
 /* The paper's long-sequence tasks have lengths such as 4000 (Sec. 5.1, the retrieval task).  These two
  * calls take the arrays as they are: Q, O [B*H, Lq, d] and K, V [B*H, Lk, d] with ANY Lq >= 1 and any

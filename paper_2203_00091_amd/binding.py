@@ -28,6 +28,7 @@ EXPORTS = (
     "dfss_static_scratch_bytes", "dfss_attention_staged_static",
     "dfss_sddmm_prune_causal", "dfss_attention_causal", "dfss_attention_staged_causal", "dense_attention_causal",
     "dense_attention_fused_causal",
+    "dfss_blocked_split_workspace_bytes", "dfss_attention_blocked_split", "dense_attention_fused_blocked_split",
 )
 # exported for the library's own tests only (csrc/dfss_internal.h)
 INTERNAL_EXPORTS = ("dfss_internal_attention_variant",)
@@ -98,7 +99,7 @@ def load_library():
         sp = ctypes.POINTER(_CShape)
         vp, sz, f32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float
         for name in ("dfss_vals_bytes", "dfss_meta_bytes", "dfss_workspace_bytes", "dense_workspace_bytes",
-                     "dfss_backward_workspace_bytes"):
+                     "dfss_backward_workspace_bytes", "dfss_blocked_split_workspace_bytes"):
             getattr(L, name).argtypes = [sp]
             getattr(L, name).restype = sz
         L.dfss_sddmm_prune.argtypes = [vp, vp, sp, f32, vp, vp, vp]
@@ -113,6 +114,8 @@ def load_library():
         L.dense_attention_fused_bias.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_attention_blocked.argtypes = [vp, vp, vp, vp, vp, sp, f32, vp, vp]
         L.dense_attention_fused_blocked.argtypes = [vp, vp, vp, vp, vp, sp, f32, vp, vp]
+        L.dfss_attention_blocked_split.argtypes = [vp, vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
+        L.dense_attention_fused_blocked_split.argtypes = [vp, vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
         L.dfss_attention_ragged.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_attention_staged.argtypes = [vp, vp, vp, sp, f32, vp, vp, sz, vp]
         L.dfss_attention_staged_bias.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
@@ -138,7 +141,8 @@ def load_library():
                      "dfss_attention_ragged", "dense_attention_fused_ragged", "dfss_spmm_t",
                      "dfss_attention_backward", "dfss_attention_staged", "dfss_attention_staged_bias",
                      "dfss_internal_attention_variant", "dfss_sddmm_prune_causal", "dfss_attention_causal",
-                     "dfss_attention_staged_causal", "dense_attention_causal", "dense_attention_fused_causal"):
+                     "dfss_attention_staged_causal", "dense_attention_causal", "dense_attention_fused_causal",
+                     "dfss_attention_blocked_split", "dense_attention_fused_blocked_split"):
             getattr(L, name).restype = ctypes.c_int
         L.dfss_status_string.argtypes = [ctypes.c_int]
         L.dfss_status_string.restype = ctypes.c_char_p
@@ -496,6 +500,37 @@ def dense_attention_fused_blocked(Q, K, V, key_bias, block_mask, s: Shape, scale
                                                       _block_mask_ptr(block_mask, s), ctypes.byref(s.c()), scale,
                                                       _q(O, s), _stream())
     _check("dense_attention_fused_blocked", st)
+    return O
+
+
+def dfss_blocked_split_workspace_bytes(s: Shape) -> int:
+    return int(load_library().dfss_blocked_split_workspace_bytes(ctypes.byref(s.c())))
+
+
+def dfss_attention_blocked_split(Q, K, V, key_bias, block_mask, s: Shape, scale: float, O=None, ws=None):
+    """dfss_attention_blocked with a workspace: long row blocks are shared between several workgroups."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    if ws is None:
+        ws = _alloc_bytes(dfss_blocked_split_workspace_bytes(s), Q.device)
+    st = load_library().dfss_attention_blocked_split(_q(Q, s), _kv(K, s), _kv(V, s), _bias_ptr(key_bias, s),
+                                                     _block_mask_ptr(block_mask, s), ctypes.byref(s.c()), scale,
+                                                     _q(O, s), ws.data_ptr(), ws.numel() * ws.element_size(), _stream())
+    _check("dfss_attention_blocked_split", st)
+    return O
+
+
+def dense_attention_fused_blocked_split(Q, K, V, key_bias, block_mask, s: Shape, scale: float, O=None, ws=None):
+    """Block-sparse full attention with the same workspace (the baseline of dfss_attention_blocked_split)."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    if ws is None:
+        ws = _alloc_bytes(dfss_blocked_split_workspace_bytes(s), Q.device)
+    st = load_library().dense_attention_fused_blocked_split(_q(Q, s), _kv(K, s), _kv(V, s), _bias_ptr(key_bias, s),
+                                                            _block_mask_ptr(block_mask, s), ctypes.byref(s.c()), scale,
+                                                            _q(O, s), ws.data_ptr(), ws.numel() * ws.element_size(),
+                                                            _stream())
+    _check("dense_attention_fused_blocked_split", st)
     return O
 
 

@@ -411,6 +411,40 @@ dfss_status dense_attention_fused_blocked(const void *Q, const void *K, const vo
     return attention_blocked(Q, K, V, key_bias, block_mask, s, true, scale, O, stream);
 }
 
+size_t dfss_blocked_split_workspace_bytes(const dfss_shape *s) {
+    Dims D;
+    if (check_shape(s, false, &D) != DFSS_OK || D.f32) return 0;
+    return align_up(dfss::fused_attention_split_workspace_bytes(D.BH, D.Lq, D.d));
+}
+
+static dfss_status attention_blocked_split(const void *Q, const void *K, const void *V, const void *key_bias,
+                                           const void *block_mask, const dfss_shape *s, bool dense, float scale, void *O,
+                                           void *ws, size_t ws_bytes, void *stream) {
+    Dims D;
+    if (!Q || !K || !V || !O || !block_mask || !ws) return DFSS_ERR_NULL;
+    if (dfss_status st = check_shape(s, !dense, &D)) return st;
+    if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
+    if (D.f32) return DFSS_ERR_UNSUPPORTED;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias) || misaligned(ws))
+        return DFSS_ERR_SHAPE;
+    if (ws_bytes < dfss_blocked_split_workspace_bytes(s)) return DFSS_ERR_WORKSPACE;
+    return hip_status(dfss::launch_fused_attention_split_rows(Q, K, V, (const float *)key_bias, D.H,
+                                                              (const uint8_t *)block_mask, D.BH, D.Lq, D.Lk, D.d,
+                                                              dense ? 2 : D.mode, scale, O, ws, (hipStream_t)stream));
+}
+
+dfss_status dfss_attention_blocked_split(const void *Q, const void *K, const void *V, const void *key_bias,
+                                         const void *block_mask, const dfss_shape *s, float scale, void *O, void *ws,
+                                         size_t ws_bytes, void *stream) {
+    return attention_blocked_split(Q, K, V, key_bias, block_mask, s, false, scale, O, ws, ws_bytes, stream);
+}
+
+dfss_status dense_attention_fused_blocked_split(const void *Q, const void *K, const void *V, const void *key_bias,
+                                                const void *block_mask, const dfss_shape *s, float scale, void *O,
+                                                void *ws, size_t ws_bytes, void *stream) {
+    return attention_blocked_split(Q, K, V, key_bias, block_mask, s, true, scale, O, ws, ws_bytes, stream);
+}
+
 // dense: full attention (N, M ignored)
 static dfss_status attention_ragged(const void *Q, const void *K, const void *V, const void *key_bias,
                                     const dfss_shape *s, bool dense, float scale, void *O, void *stream) {

@@ -31,6 +31,12 @@ hipError_t launch_dense_av(const void *P, const void *V, int BH, int Lq, int Lk,
 hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, const float *key_bias, int H,
                                   const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, int mode, float scale,
                                   void *O, int variant, hipStream_t st);
+// The same with a block pattern (block_mask not null) and a workspace of fused_attention_split_workspace_bytes: row
+// blocks that visit many blocks are shared between several workgroups and merged by a second kernel.
+size_t fused_attention_split_workspace_bytes(int BH, int Lq, int d);
+hipError_t launch_fused_attention_split_rows(const void *Q, const void *K, const void *V, const float *key_bias, int H,
+                                             const uint8_t *block_mask, int BH, int Lq, int Lk, int d, int mode,
+                                             float scale, void *O, void *part, hipStream_t st);
 // Transposed sparse product out[BH, Lk, d] = A^T X for compressed A (vals + metadata) and X bf16 [BH, Lq, d]:
 // dV = P^T dO and dK = dS^T Q of the backward pass.
 hipError_t launch_spmm_t(const void *vals, const void *meta, const void *X, int BH, int Lq, int Lk, int d, void *out,

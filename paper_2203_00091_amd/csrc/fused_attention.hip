@@ -39,6 +39,64 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 enum { MODE_2TO4 = 0, MODE_1TO2 = 1, MODE_DENSE = 2 };
 
+// Row blocks of a block pattern that visit more blocks than this are shared between the workgroups of a split launch.
+constexpr int kSplitFromBlocks = 16;
+constexpr int kSplit = 4;        // workgroups per shared row block in a split launch
+constexpr int kSplitSlots = 4;   // row blocks that can be shared
+
+// Split launches: which row blocks are shared is a function of the pattern alone, so every workgroup works it out for
+// itself (a key bias may mask some of the blocks; it does not enter).  The first kSplitSlots row blocks that keep more
+// than kSplitFromBlocks blocks get the slots 0, 1, ... in row order.
+// Blocks kept by row block `row` (one lane per row; 16 bytes at a time where the rows allow).
+__device__ __forceinline__ int kept_blocks(const uint8_t *__restrict__ block_mask, int row, int nblocks) {
+    const uint8_t *const p = block_mask + (size_t)row * nblocks;
+    int kept = 0;
+    if (nblocks % 16 == 0 && (reinterpret_cast<uintptr_t>(block_mask) & 15u) == 0) {
+        for (int j = 0; j < nblocks; j += 16) {
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(p + j);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {   // bit 0 of every byte := OR of its bits
+                uint32_t t = v[e] | (v[e] >> 4);
+                t |= t >> 2;
+                t |= t >> 1;
+                kept += __builtin_popcount(t & 0x01010101u);
+            }
+        }
+    } else {
+        for (int j = 0; j < nblocks; ++j) kept += p[j] != 0;
+    }
+    return kept;
+}
+// Lane mask of the long row blocks among rows c .. c + 63 (the whole wave calls).
+__device__ __forceinline__ uint64_t long_rows(const uint8_t *__restrict__ block_mask, int c, int nrows, int nblocks, int l) {
+    const int kept = c + l < nrows ? kept_blocks(block_mask, c + l, nblocks) : 0;
+    return __ballot(kept > kSplitFromBlocks);
+}
+// Row block that holds slot `slot`, or -1 (the whole wave calls; the result is the same in every lane).
+__device__ __forceinline__ int row_of_slot(const uint8_t *__restrict__ block_mask, int slot, int nrows, int nblocks, int l) {
+    int given = 0;
+    for (int c = 0; c < nrows; c += kWave) {
+        uint64_t m = long_rows(block_mask, c, nrows, nblocks, l);
+        const int n = __builtin_popcountll(m);
+        if (slot < given + n) {
+            for (int i = given; i < slot; ++i) m &= m - 1ull;
+            return c + __builtin_ctzll(m);
+        }
+        given += n;
+    }
+    return -1;
+}
+// Slot of row block `row` (which is a long one), or -1 if the slots ran out before it.
+__device__ __forceinline__ int slot_of_row(const uint8_t *__restrict__ block_mask, int row, int nrows, int nblocks, int l) {
+    int before = 0;
+    for (int c = 0; c < row; c += kWave) {
+        uint64_t m = long_rows(block_mask, c, nrows, nblocks, l);
+        if (row - c < kWave) m &= (1ull << (row - c)) - 1ull;
+        before += __builtin_popcountll(m);
+    }
+    return before < kSplitSlots ? before : -1;
+}
+
 // MASKED: the call carries a key bias and/or a block mask (either pointer may be null).
 // RAGGED (implies MASKED; no block mask): the lengths are not multiples of the tiles.  Q, O hold Lq rows and K, V,
 //   key_bias Lk keys (Lk a multiple of 4); the absent keys of the last block count as masked keys and the absent
@@ -58,11 +116,19 @@ enum { MODE_2TO4 = 0, MODE_1TO2 = 1, MODE_DENSE = 2 };
 //              64 queries visit (the g-th, G + g-th, ... of the list), through K/V buffers of its own; the G partial
 //              results of a query tile are merged through LDS at the end (as the key halves of a split are).
 //              A row block that sees every key then costs 1/G of the time, and the rows of a pattern differ widely.
-template <int D, int MODE, int NQ, bool PRESCALE, bool MASKED, bool RAGGED = false, int G = 1>
+//   SPLIT      (block patterns only) long row blocks are shared between SPLIT workgroups.  The first kSplitSlots row
+//              blocks of the pattern that keep more than kSplitFromBlocks blocks have a slot each (row_of_slot,
+//              slot_of_row).  The launch holds, first, SPLIT - 1 helper workgroups per head and slot (those of an
+//              unused slot leave at once), then one workgroup per head and row block.  The SPLIT workgroups of a
+//              shared row block take every SPLIT-th block of its list and write their partial results (reference,
+//              row sums, unnormalised O; fp32) to `part` [head][slot][SPLIT][64 x (D + 2)]; k_merge_split forms O.
+//              Every other row block is the work of its one workgroup, as in a launch without SPLIT.
+template <int D, int MODE, int NQ, bool PRESCALE, bool MASKED, bool RAGGED = false, int G = 1, int SPLIT = 1>
 __global__ __launch_bounds__(NT * G, 2) void k_fused(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
                                                  const __bf16 *__restrict__ V, const float *__restrict__ key_bias,
                                                  int H, const uint8_t *__restrict__ block_mask, int causal, int Lq,
-                                                 int Lk, float scale, uint16_t *__restrict__ O) {
+                                                 int Lk, float scale, uint16_t *__restrict__ O,
+                                                 float *__restrict__ part) {
     constexpr int CPR = D / 8;          // 16-byte chunks per row
     constexpr int TILE = KB * CPR;      // chunks per K (or V) block
     constexpr int LPT = TILE / NT;      // direct-to-LDS loads per thread per block and operand
@@ -72,6 +138,7 @@ __global__ __launch_bounds__(NT * G, 2) void k_fused(const __bf16 *__restrict__ 
     constexpr bool SPARSE = MODE != MODE_DENSE;
     static_assert(!RAGGED || MASKED, "ragged lengths use the masking machinery");
     static_assert(G == 1 || (MASKED && !RAGGED && NQ == 1), "key groups: block patterns on 64-query workgroups");
+    static_assert(SPLIT == 1 || (MASKED && !RAGGED && NQ == 1 && G == 1), "split rows: block patterns, 64-query workgroups");
     __shared__ u32x4 Smem[G * 4 * TILE];   // per key group: two K buffers, then two V buffers
 
     const int tid = threadIdx.x & (NT - 1);   // within the key group
@@ -81,7 +148,32 @@ __global__ __launch_bounds__(NT * G, 2) void k_fused(const __bf16 *__restrict__ 
 
     const unsigned qtiles = (Lq + TQ - 1) / TQ;
     int qt, bh;
-    if (MASKED && (block_mask || causal)) {
+    int sp = 0, stride = 1, slot = -1;   // SPLIT: place among the workgroups that share the row block; their number; the slot
+    if constexpr (SPLIT > 1) {
+        const int nblk = Lk / KB, lane = threadIdx.x & 63;
+        const unsigned heads = gridDim.x / (kSplitSlots * (SPLIT - 1) + qtiles);
+        const unsigned helpers = heads * kSplitSlots * (SPLIT - 1);
+        if (blockIdx.x < helpers) {   // (the helpers come first in launch order: they belong to the longest row blocks)
+            slot = blockIdx.x / (heads * (SPLIT - 1));
+            const unsigned rest = blockIdx.x % (heads * (SPLIT - 1));
+            sp = 1 + rest / heads;
+            bh = rest % heads;
+            qt = __builtin_amdgcn_readfirstlane(row_of_slot(block_mask, slot, qtiles, nblk, lane));
+            if (qt < 0) return;   // unused slot
+            stride = SPLIT;
+        } else {
+            const unsigned row = blockIdx.x - helpers;   // row block 0 of every head, then row block 1, ...
+            qt = row / heads;
+            bh = row % heads;
+            const uint8_t *const mine = block_mask + (size_t)qt * nblk;
+            const int kept = __builtin_popcountll(__ballot(lane < nblk && mine[lane < nblk ? lane : 0] != 0)) +
+                             __builtin_popcountll(__ballot(64 + lane < nblk && mine[64 + lane < nblk ? 64 + lane : 0] != 0));
+            if (kept > kSplitFromBlocks) {
+                slot = __builtin_amdgcn_readfirstlane(slot_of_row(block_mask, qt, qtiles, nblk, lane));
+                if (slot >= 0) stride = SPLIT;
+            }
+        }
+    } else if (MASKED && (block_mask || causal)) {
         // Row blocks of a block pattern differ widely in work (rows that see every key next to rows
         // that see a window), and the heavy ones usually come first: hand out row block 0 of every
         // head, then row block 1, ... in launch order, so that the long workgroups start at once.
@@ -138,7 +230,21 @@ __global__ __launch_bounds__(NT * G, 2) void k_fused(const __bf16 *__restrict__ 
         for (int i = 0; i < LPT; ++i) async_copy16(vs, 2u * v_off[i], lds_v + 16u * (buf * TILE + i * NT));
     };
 
-    if (g == 0) issue_block(0, 0);   // block 0 is copied before anything else (with a key bias or a pattern: speculatively)
+    // Blocks to visit (block_list.hpp): pruned, fully masked and causally hidden blocks are skipped.
+    const float *brow = nullptr;    // bias row of this head's batch element
+    f32x4 kb4[4];                   // bias of this lane's 16 keys of a block: keys 64 jb + 16 kb + 4 t + r
+    BlockList<MASKED, RAGGED> blocks;
+    auto init_blocks = [&]() {
+        if constexpr (MASKED) {
+            if (key_bias) brow = key_bias + (size_t)(bh / H) * Lk;
+            blocks.init(key_bias != nullptr, brow, block_mask != nullptr, block_mask + (size_t)(qt * TQ / 64) * nblocks,
+                        causal, qt * TQ, TQ, coff, Lq, Lk, nblocks, l);
+        } else {
+            blocks.init(false, nullptr, false, nullptr, 0, 0, TQ, 0, Lq, Lk, nblocks, l);
+        }
+    };
+
+    if (g == 0 && stride == 1) issue_block(0, 0);   // block 0 is copied before anything else (with a key bias or a pattern: speculatively)
 
     // Q operand (B side of Q K^T): lane (column li, chunk kb) of step s holds Q[q][32 s + 8 kb .. +7]
     bf16x8 bq[NQ][STEPS];
@@ -176,23 +282,20 @@ __global__ __launch_bounds__(NT * G, 2) void k_fused(const __bf16 *__restrict__ 
 
     const int tr_row = li >> 2, tr_sub = (li >> 1) & 1, tr_byte = 8 * (li & 1);
 
-    // Blocks to visit (block_list.hpp): pruned, fully masked and causally hidden blocks are skipped.
-    const float *brow = nullptr;    // bias row of this head's batch element
-    f32x4 kb4[4];                   // bias of this lane's 16 keys of a block: keys 64 jb + 16 kb + 4 t + r
-    BlockList<MASKED, RAGGED> blocks;
-    if constexpr (MASKED) {
-        if (key_bias) brow = key_bias + (size_t)(bh / H) * Lk;
-        blocks.init(key_bias != nullptr, brow, block_mask != nullptr, block_mask + (size_t)(qt * TQ / 64) * nblocks,
-                    causal, qt * TQ, TQ, coff, Lq, Lk, nblocks, l);
-    } else {
-        blocks.init(false, nullptr, false, nullptr, 0, 0, TQ, 0, Lq, Lk, nblocks, l);
-    }
+    init_blocks();
     // The next block of this wave's key group: G blocks come off the list, one per group.  `lead` is group 0's,
     // the first of the G: while it exists the round exists, and every group passes the round's barrier.
     int lead_n = 0;
     auto take_live = [&]() -> int {
-        if constexpr (G == 1) {
+        if constexpr (G == 1 && SPLIT == 1) {
             return lead_n = blocks.take();
+        } else if constexpr (SPLIT > 1) {
+            int mine = nblocks;
+            for (int i = 0; i < stride; ++i) {
+                const int j = blocks.take();
+                if (i == sp) mine = j;
+            }
+            return lead_n = __builtin_amdgcn_readfirstlane(mine);   // (the same in every lane; said to the compiler)
         } else {
             int mine = nblocks;
 #pragma unroll
@@ -209,7 +312,7 @@ __global__ __launch_bounds__(NT * G, 2) void k_fused(const __bf16 *__restrict__ 
     int jn = take_live();   // the block after this one
     // block 0 (copied speculatively at the top) turned out to be fully masked: overwrite the buffer
     // with the first live block (the two copies of a wave complete in issue order)
-    if (MASKED && (g != 0 || jb != 0) && jb < nblocks) issue_block(jb, 0);
+    if (MASKED && (g != 0 || stride > 1 || jb != 0) && jb < nblocks) issue_block(jb, 0);
 
     for (int it = 0; lead < nblocks; ++it) {
         const int buf = it & 1;
@@ -419,6 +522,24 @@ __global__ __launch_bounds__(NT * G, 2) void k_fused(const __bf16 *__restrict__ 
     }
     if constexpr (MASKED) wait_async_copies();   // (only matters if no block was live: the speculative copy)
 
+    if constexpr (SPLIT > 1) {
+        if (stride > 1) {
+            // ---- shared row block: this workgroup's partial result goes to `part` (k_merge_split forms O) ----
+            // per (row block, sp): reference of the 64 queries, their row sums, then O [64][D], all fp32 and relative
+            // to the workgroup's own reference
+            float *const P = part + ((size_t)(bh * kSplitSlots + slot) * SPLIT + sp) * (64 * (D + 2));
+            if (kb == 0) P[16 * w + li] = m_ref[0];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int q = 16 * w + 4 * kb + r;
+                if (li == 0) P[64 + q] = acc_l[0][r];
+#pragma unroll
+                for (int ds = 0; ds < DS; ++ds) P[128 + q * D + 16 * ds + li] = acc_o[0][ds][r];
+            }
+            return;
+        }
+    }
+
     if constexpr (G > 1) {
         // ---- merge the key groups: groups 1 .. G-1 hand (reference, row sums, O) to group 0 through LDS ----
         // Lane for lane (wave w of every group holds the same queries in the same places): value f of a lane at
@@ -496,6 +617,44 @@ __global__ __launch_bounds__(NT * G, 2) void k_fused(const __bf16 *__restrict__ 
 // measured slower than no groups at all.
 constexpr int kGroupsFromKeys = 1024;
 
+// O of the row blocks that k_fused<..., SPLIT> shared between workgroups: the SPLIT partial results are brought to the
+// largest of their references and summed (Sec. 3.1's softmax does not depend on the reference), in a fixed order.
+// One workgroup per head and slot.  Thread t: query t / 4, a quarter of the columns.
+template <int D, int SPLIT>
+__global__ __launch_bounds__(NT) void k_merge_split(const float *__restrict__ part, const uint8_t *__restrict__ block_mask,
+                                                    uint16_t *__restrict__ O, int Lq, int Lk) {
+    const unsigned qtiles = Lq / 64, heads = gridDim.x / kSplitSlots;
+    const unsigned slot = blockIdx.x / heads, bh = blockIdx.x % heads;
+    const int qt = row_of_slot(block_mask, slot, qtiles, Lk / KB, threadIdx.x & 63);
+    if (qt < 0) return;
+    const float *const P = part + (size_t)(bh * kSplitSlots + slot) * SPLIT * (64 * (D + 2));
+    const int q = threadIdx.x >> 2, c0 = (threadIdx.x & 3) * (D / 4);
+    float m = -3.0e38f;
+#pragma unroll
+    for (int sp = 0; sp < SPLIT; ++sp) m = fmaxf(m, P[sp * (64 * (D + 2)) + q]);
+    float f[SPLIT], sum = 0.f;
+#pragma unroll
+    for (int sp = 0; sp < SPLIT; ++sp) {
+        f[sp] = __builtin_amdgcn_exp2f((P[sp * (64 * (D + 2)) + q] - m) * kLog2e);
+        sum += P[sp * (64 * (D + 2)) + 64 + q] * f[sp];
+    }
+    const float inv = 1.f / sum;
+    uint16_t *const out = O + ((size_t)bh * Lq + qt * 64 + q) * D + c0;
+#pragma unroll
+    for (int c = 0; c < D / 4; c += 8) {
+        f32x4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int sp = 0; sp < SPLIT; ++sp) {
+            const f32x4 *const src = reinterpret_cast<const f32x4 *>(P + sp * (64 * (D + 2)) + 128 + q * D + c0 + c);
+            a0 += src[0] * f[sp];
+            a1 += src[1] * f[sp];
+        }
+        a0 *= inv, a1 *= inv;
+        *reinterpret_cast<u32x4 *>(out + c) = u32x4{pack_bf16x2(a0[0], a0[1]), pack_bf16x2(a0[2], a0[3]),
+                                                    pack_bf16x2(a1[0], a1[1]), pack_bf16x2(a1[2], a1[3])};
+    }
+}
+
 inline bool is_pow2(float x) {
     int e;
     return frexpf(x, &e) == 0.5f;
@@ -510,7 +669,7 @@ hipError_t launch_nq(const void *Q, const void *K, const void *V, const float *k
 #define DFSS_LAUNCH(DD, PRE)                                                                                    \
     hipLaunchKernelGGL((k_fused<DD, MODE, NQ, PRE, MASKED, RAGGED>), dim3(grid), dim3(NT), 0, st,               \
                        (const __bf16 *)Q, (const __bf16 *)K, (const __bf16 *)V, key_bias, H, block_mask, causal, \
-                       Lq, Lk, scale, (uint16_t *)O)
+                       Lq, Lk, scale, (uint16_t *)O, (float *)nullptr)
     if (d == 64) {
         if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
     } else {
@@ -530,9 +689,34 @@ hipError_t launch_groups(const void *Q, const void *K, const void *V, const floa
 #define DFSS_LAUNCH(DD, PRE, GG)                                                                                \
     hipLaunchKernelGGL((k_fused<DD, MODE, 1, PRE, true, false, GG>), dim3(grid), dim3(NT * GG), 0, st,          \
                        (const __bf16 *)Q, (const __bf16 *)K, (const __bf16 *)V, key_bias, H, block_mask, causal, \
-                       Lq, Lk, scale, (uint16_t *)O)
+                       Lq, Lk, scale, (uint16_t *)O, (float *)nullptr)
     if (d != 64) return hipErrorInvalidValue;
     if (pre) DFSS_LAUNCH(64, true, 2); else DFSS_LAUNCH(64, false, 2);
+#undef DFSS_LAUNCH
+    return hipGetLastError();
+}
+
+// Block patterns with a workspace: kSplit workgroups per row block, then the merge of the shared row blocks.
+template <int MODE>
+hipError_t launch_split(const void *Q, const void *K, const void *V, const float *key_bias, int H,
+                        const uint8_t *block_mask, int BH, int Lq, int Lk, int d, float scale, void *O, float *part,
+                        hipStream_t st) {
+    const unsigned qtiles = Lq / 64;
+    const unsigned grid = (unsigned)BH * (kSplitSlots * (kSplit - 1) + qtiles);
+    const bool pre = is_pow2(scale);
+#define DFSS_LAUNCH(DD, PRE)                                                                                      \
+    hipLaunchKernelGGL((k_fused<DD, MODE, 1, PRE, true, false, 1, kSplit>), dim3(grid), dim3(NT), 0, st,          \
+                       (const __bf16 *)Q, (const __bf16 *)K, (const __bf16 *)V, key_bias, H, block_mask, 0, Lq, Lk, \
+                       scale, (uint16_t *)O, part)
+    if (d == 64) {
+        if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
+        hipLaunchKernelGGL((k_merge_split<64, kSplit>), dim3(BH * kSplitSlots), dim3(NT), 0, st, part, block_mask,
+                           (uint16_t *)O, Lq, Lk);
+    } else {
+        if (pre) DFSS_LAUNCH(128, true); else DFSS_LAUNCH(128, false);
+        hipLaunchKernelGGL((k_merge_split<128, kSplit>), dim3(BH * kSplitSlots), dim3(NT), 0, st, part, block_mask,
+                           (uint16_t *)O, Lq, Lk);
+    }
 #undef DFSS_LAUNCH
     return hipGetLastError();
 }
@@ -567,6 +751,18 @@ hipError_t launch(const void *Q, const void *K, const void *V, const float *key_
 hipError_t launch_fused_attention32(const void *Q, const void *K, const void *V, const float *key_bias, int H,
                                     const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, int mode,
                                     int nw, int ks, float scale, void *O, hipStream_t st);
+
+size_t fused_attention_split_workspace_bytes(int BH, int Lq, int d) {
+    return (size_t)BH * kSplitSlots * kSplit * 64 * (d + 2) * sizeof(float);
+}
+
+hipError_t launch_fused_attention_split_rows(const void *Q, const void *K, const void *V, const float *key_bias, int H,
+                                             const uint8_t *block_mask, int BH, int Lq, int Lk, int d, int mode,
+                                             float scale, void *O, void *part, hipStream_t st) {
+    if (mode == 0) return launch_split<MODE_2TO4>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, (float *)part, st);
+    if (mode == 1) return launch_split<MODE_1TO2>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, (float *)part, st);
+    return launch_split<MODE_DENSE>(Q, K, V, key_bias, H, block_mask, BH, Lq, Lk, d, scale, O, (float *)part, st);
+}
 
 hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, const float *key_bias, int H,
                                   const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, int mode,

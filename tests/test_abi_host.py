@@ -112,6 +112,12 @@ def test_errors_are_reported_before_any_launch():
     assert lib.dfss_attention_blocked(aligned, aligned, aligned, None, None, ctypes.byref(ok), 0.125, aligned, None) == E_NULL
     assert lib.dfss_attention_blocked(aligned, aligned, aligned, None, aligned, ctypes.byref(bad), 0.125, aligned, None) == E_UNSUP
     assert lib.dense_attention_fused_blocked(aligned, aligned, aligned, odd, aligned, ctypes.byref(ok), 0.125, aligned, None) == E_SHAPE
+    assert lib.dfss_attention_blocked_split(aligned, aligned, aligned, None, aligned, ctypes.byref(ok), 0.125, aligned, None, 1 << 30, None) == E_NULL
+    assert lib.dfss_attention_blocked_split(aligned, aligned, aligned, None, aligned, ctypes.byref(ok), 0.125, aligned, ws, 16, None) == E_WS
+    assert lib.dense_attention_fused_blocked_split(aligned, aligned, aligned, None, None, ctypes.byref(ok), 0.125, aligned, ws, 1 << 30, None) == E_NULL
+    assert lib.dense_attention_fused_blocked_split(aligned, aligned, aligned, odd, aligned, ctypes.byref(ok), 0.125, aligned, ws, 1 << 30, None) == E_SHAPE
+    assert lib.dfss_blocked_split_workspace_bytes(ctypes.byref(ok)) > 0
+    assert lib.dfss_blocked_split_workspace_bytes(ctypes.byref(Shape(1, 1, 100, 128, 64).c())) == 0
     assert lib.dfss_spmm_t(aligned, aligned, None, ctypes.byref(ok), aligned, None) == E_NULL
     assert lib.dfss_attention_backward(aligned, aligned, aligned, aligned, aligned, aligned, aligned, ctypes.byref(ok),
                                        0.125, aligned, aligned, aligned, ws, 16, None) == E_WS
@@ -123,6 +129,8 @@ def test_errors_are_reported_before_any_launch():
     assert lib.dfss_sddmm_prune_bias(aligned, aligned, aligned, ctypes.byref(f32), 0.125, aligned, aligned, None) == E_UNSUP
     assert lib.dfss_attention_bias(aligned, aligned, aligned, aligned, ctypes.byref(f32), 0.125, aligned, ws, 1 << 30, None) == E_UNSUP
     assert lib.dfss_attention_blocked(aligned, aligned, aligned, None, aligned, ctypes.byref(f32), 0.125, aligned, None) == E_UNSUP
+    assert lib.dfss_attention_blocked_split(aligned, aligned, aligned, None, aligned, ctypes.byref(f32), 0.125, aligned, ws, 1 << 30, None) == E_UNSUP
+    assert lib.dfss_blocked_split_workspace_bytes(ctypes.byref(f32)) == 0
     assert lib.dfss_spmm_t(aligned, aligned, aligned, ctypes.byref(f32), aligned, None) == E_UNSUP
     assert lib.dfss_attention_backward(aligned, aligned, aligned, aligned, aligned, aligned, aligned, ctypes.byref(f32),
                                        0.125, aligned, aligned, aligned, ws, 1 << 30, None) == E_UNSUP

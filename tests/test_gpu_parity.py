@@ -388,6 +388,10 @@ def test_results_are_deterministic_and_cover_every_byte():
         got["bias"] = _bits(dfss.dfss_attention_bias(Q, K, V, bias, s, w.scale, O=_poisoned(o_shape, bf, fill)))
         got["blocked"] = _bits(dfss.dfss_attention_blocked(Q, K, V, None, bm, s, w.scale,
                                                            O=_poisoned(o_shape, bf, fill)))
+        wsb = _poisoned((dfss.dfss_blocked_split_workspace_bytes(s) // 2,), bf, fill)
+        got["blocked split"] = _bits(dfss.dfss_attention_blocked_split(Q, K, V, None, bm, s, w.scale,
+                                                                       O=_poisoned(o_shape, bf, fill),
+                                                                       ws=wsb.view(torch.uint8)))
         got["ragged"] = _bits(dfss.dfss_attention_ragged(Qr, Kr, Vr, None, sr, w.scale,
                                                          O=_poisoned((s.BH, Lr, s.d), bf, fill)))
         got["dense"] = _bits(dfss.dense_attention(Q, K, V, s, w.scale, O=_poisoned(o_shape, bf, fill)))
@@ -559,6 +563,13 @@ def test_attention_blocked(BH, Lq, Lk, d, N, M):
     ref_dense = oracle.attention(Qn, Kn, Vn, 1, 1, scale, block_mask=bm.numpy(), block_size=64)
     assert np.max(np.abs(_np(O) - ref)) <= 2e-2
     assert np.max(np.abs(_np(Od) - ref_dense)) <= 2e-2
+    # the calls with a workspace (long row blocks shared between workgroups): same function
+    ws = torch.full((dfss.dfss_blocked_split_workspace_bytes(s),), 0xFF, dtype=torch.uint8, device=Qd.device)
+    Os = dfss.dfss_attention_blocked_split(Qd, Kd, Vd, None, bmd, s, scale, ws=ws)
+    Ods = dfss.dense_attention_fused_blocked_split(Qd, Kd, Vd, None, bmd, s, scale, ws=ws)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(_np(Os) - ref)) <= 2e-2
+    assert np.max(np.abs(_np(Ods) - ref_dense)) <= 2e-2
     # the pattern matters: full attention gives something else
     assert np.max(np.abs(ref - oracle.attention(Qn, Kn, Vn, N, M, scale))) > 0.05
 
@@ -566,7 +577,7 @@ def test_attention_blocked(BH, Lq, Lk, d, N, M):
 @pytest.mark.parametrize("BH,H,L,d,N,M,scale", [
     (2, 1, 1024, 64, 2, 4, 0.125),      # key groups; the scale folds into Q
     (2, 2, 1024, 64, 1, 2, 0.11),       # the scale is applied to the scores
-    (2, 1, 1024, 128, 2, 4, 0.0884),    # d = 128: no key groups, same pattern
+    (1, 1, 2048, 128, 2, 4, 0.0884),    # d = 128: no key groups, same pattern
     (1, 1, 2048, 64, 2, 4, 0.125),      # 32 key blocks
 ])
 def test_attention_blocked_long_rows_of_every_weight(BH, H, L, d, N, M, scale):
@@ -610,6 +621,22 @@ def test_attention_blocked_long_rows_of_every_weight(BH, H, L, d, N, M, scale):
         assert np.isfinite(_np(O)[ok]).all()
         assert np.max(np.abs(_np(O)[ok] - ref[ok])) <= 2e-2
         assert np.max(np.abs(_np(Od)[ok] - ref_dense[ok])) <= 2e-2
+        # with a workspace: the row blocks of more than 16 blocks are shared between four workgroups and merged;
+        # the workspace starts out as garbage (nothing in it needs initialising), twice in a row on the same one
+        ws = torch.full((dfss.dfss_blocked_split_workspace_bytes(s),), 0xFF, dtype=torch.uint8, device=Qd.device)
+        for _ in range(2):
+            Os = dfss.dfss_attention_blocked_split(Qd, Kd, Vd, kbd, bmd, s, scale, ws=ws)
+            Ods = dfss.dense_attention_fused_blocked_split(Qd, Kd, Vd, kbd, bmd, s, scale, ws=ws)
+            torch.cuda.synchronize()
+            assert np.isfinite(_np(Os)[ok]).all()
+            assert np.max(np.abs(_np(Os)[ok] - ref[ok])) <= 2e-2
+            assert np.max(np.abs(_np(Ods)[ok] - ref_dense[ok])) <= 2e-2
+        # row blocks that are not shared are computed exactly as without the workspace (d = 128: the call without
+        # workspace has no key groups, so it is the same kernel code)
+        if kb is None and d == 128:
+            light = torch.from_numpy((bm.sum(1) <= 16).numpy().repeat(64)).to(O.device)
+            assert bool(light.any()) and not bool(light.all())
+            assert torch.equal(Os[:, light], O[:, light])
 
 
 def test_attention_blocked_with_key_bias_and_full_pattern():
@@ -651,7 +678,8 @@ def test_calls_replay_correctly_from_a_hip_graph():
     bias = _dev(synth.key_padding_bias(lengths, 256))
     bm = _dev(synth.block_pattern(4, 4, seed=9102, window=0, n_random=0))
     ws = torch.empty(max(dfss.dfss_workspace_bytes(s), dfss.dense_workspace_bytes(s)), dtype=torch.uint8, device=DEV)
-    outs = {k: torch.empty_like(Q) for k in ("fused", "bias", "blocked", "dense", "dense_fused", "stages")}
+    wsb = torch.empty(dfss.dfss_blocked_split_workspace_bytes(s), dtype=torch.uint8, device=DEV)
+    outs = {k: torch.empty_like(Q) for k in ("fused", "bias", "blocked", "blocked_split", "dense", "dense_fused", "stages")}
     vals = torch.empty((s.BH, s.Lq, s.Lc), dtype=torch.bfloat16, device=DEV)
     meta = torch.empty((s.BH * s.Lq * (s.Lk // 16),), dtype=torch.int16, device=DEV)
 
@@ -659,6 +687,7 @@ def test_calls_replay_correctly_from_a_hip_graph():
         dfss.dfss_attention(Q, K, V, s, w.scale, O=outs["fused"], ws=ws)
         dfss.dfss_attention_bias(Q, K, V, bias, s, w.scale, O=outs["bias"], ws=ws)
         dfss.dfss_attention_blocked(Q, K, V, bias, bm, s, w.scale, O=outs["blocked"])
+        dfss.dfss_attention_blocked_split(Q, K, V, bias, bm, s, w.scale, O=outs["blocked_split"], ws=wsb)
         dfss.dense_attention(Q, K, V, s, w.scale, O=outs["dense"], ws=ws)
         dfss.dense_attention_fused(Q, K, V, s, w.scale, O=outs["dense_fused"])
         dfss.dfss_sddmm_prune(Q, K, s, w.scale, vals=vals, meta=meta)
