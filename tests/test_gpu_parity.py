@@ -605,7 +605,11 @@ def test_attention_blocked_long_rows_of_every_weight(BH, H, L, d, N, M, scale):
     s = Shape(BH // H, H, L, L, d, N, M)
     Qd, Kd, Vd, bmd, bd = _dev(Q), _dev(K), _dev(V), _dev(bm), _dev(bias)
     Qn, Kn, Vn = (synth.to_numpy_f32(t) for t in (Q, K, V))
-    for kb, kbd in ((None, None), (bias, bd)):
+    # a padded batch element: only keys 0 .. 99 are real, so a row block that keeps every block visits two, and the
+    # workgroups that share it find one block, one block, none and none
+    short = torch.zeros((BH // H, L), dtype=torch.float32)
+    short[0, 100:] = float("-inf")
+    for kb, kbd in ((None, None), (bias, bd), (short, _dev(short))):
         O = dfss.dfss_attention_blocked(Qd, Kd, Vd, kbd, bmd, s, scale)
         Od = dfss.dense_attention_fused_blocked(Qd, Kd, Vd, kbd, bmd, s, scale)
         torch.cuda.synchronize()
@@ -617,7 +621,7 @@ def test_attention_blocked_long_rows_of_every_weight(BH, H, L, d, N, M, scale):
         # rows whose every visited key is masked have no defined output: none here except via the bias in row
         # blocks that see only block 2 of batch element 0
         ok = np.isfinite(ref).all(-1)
-        assert ok.mean() > 0.9
+        assert ok.mean() > (0.9 if kb is not short else 0.05)
         assert np.isfinite(_np(O)[ok]).all()
         assert np.max(np.abs(_np(O)[ok] - ref[ok])) <= 2e-2
         assert np.max(np.abs(_np(Od)[ok] - ref_dense[ok])) <= 2e-2
