@@ -283,13 +283,13 @@ dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K
 /* ---- the 4-byte mode (Sec. 2.3: 1:2 on float data; App. A.1.1) ------------------------ */
 /* With dfss_shape.dtype = DFSS_F32 the arrays Q, K, V, O, vals (kept scores / weights) and the dense
  * workspace hold float32 instead of bfloat16, and N:M must be 1:2 (2:4 is DFSS_ERR_UNSUPPORTED).
- * Calls that take this dtype: the size functions, dfss_sddmm_prune, dfss_sparse_softmax, dfss_spmm,
- * dfss_attention (always the three stage kernels through the workspace), dense_attention and the two
- * metadata conversions.  With DFSS_F32_BF16X3 (see below) every call of the library is available:
- * also the *_bias variants, the two *_blocked calls, dfss_spmm_t and dfss_attention_backward (all
- * arrays float32 there, dS in the workspace included).  With DFSS_F32 the *_bias variants take
- * key_bias == NULL only and the remaining calls return DFSS_ERR_UNSUPPORTED.
- * (The key bias is added by a separate fp32 addition after the scaling, whatever the scale.)
+ * Calls that take this dtype: the size functions, dfss_sddmm_prune(_bias), dfss_sparse_softmax,
+ * dfss_spmm, dfss_attention(_bias) and dfss_attention_staged(_bias) (always the three stage kernels
+ * through the workspace), dense_attention(_bias) and the two metadata conversions; the remaining
+ * calls return DFSS_ERR_UNSUPPORTED.  With DFSS_F32_BF16X3 (see below) every call of the library
+ * is available: also the one-kernel forms, the *_blocked calls, dfss_spmm_t and
+ * dfss_attention_backward (all arrays float32 there, dS in the workspace included).
+ * (In both, the key bias is added by a separate fp32 addition after the scaling, whatever the scale.)
  * Arithmetic: fp32 products and fp32 accumulation on the fp32 matrix instruction (the paper rounds
  * the float inputs to a shorter mantissa for its tensor cores; this GPU has no such format, so the
  * scores are at least that accurate); the kept scores are stored unrounded.

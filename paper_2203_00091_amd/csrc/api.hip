@@ -74,11 +74,10 @@ inline bool bad_scale(float x) {
 inline dfss_status hip_status(hipError_t e) { return e == hipSuccess ? DFSS_OK : DFSS_ERR_HIP; }
 
 // stage 1 and stage 3 of the 4-byte mode, by the way the products are formed
-// (a key bias is taken with split products only; callers have rejected it otherwise)
 inline hipError_t sddmm_prune_f32(const Dims &D, const void *Q, const void *K, const float *bias, float scale,
                                   void *vals, void *meta, hipStream_t st) {
     return D.split ? dfss::launch_sddmm_prune_split(Q, K, bias, D.H, D.BH, D.Lq, D.Lk, D.d, scale, vals, meta, st)
-                   : dfss::launch_sddmm_prune_f32(Q, K, D.BH, D.Lq, D.Lk, D.d, scale, vals, meta, st);
+                   : dfss::launch_sddmm_prune_f32(Q, K, bias, D.H, D.BH, D.Lq, D.Lk, D.d, scale, vals, meta, st);
 }
 inline hipError_t spmm_f32(const Dims &D, const void *vals, const void *meta, const void *V, void *O, hipStream_t st) {
     return D.split ? dfss::launch_spmm_split(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, st)
@@ -129,10 +128,8 @@ static dfss_status sddmm_prune(const void *Q, const void *K, const void *key_bia
         return DFSS_ERR_SHAPE;
     if (causal)
         if (dfss_status st = bad_causal(D)) return st;
-    if (D.f32) {
-        if (key_bias && !D.split) return DFSS_ERR_UNSUPPORTED;
+    if (D.f32)
         return hip_status(sddmm_prune_f32(D, Q, K, (const float *)key_bias, scale, vals, meta, (hipStream_t)stream));
-    }
     return hip_status(dfss::launch_sddmm_prune(Q, K, (const float *)key_bias, D.H, causal, D.BH, D.Lq, D.Lk, D.d,
                                                D.mode, scale, vals, meta, (hipStream_t)stream));
 }
@@ -184,10 +181,7 @@ static dfss_status attention_forward(const void *Q, const void *K, const void *V
         return DFSS_ERR_SHAPE;
     if (causal)
         if (dfss_status cs = bad_causal(D)) return cs;
-    if (D.f32 && !D.split) {
-        if (key_bias) return DFSS_ERR_UNSUPPORTED;
-        staged = true;
-    }
+    if (D.f32 && !D.split) staged = true;   // (fp32 matrix instructions: the stage kernels only)
     hipStream_t st = (hipStream_t)stream;
     const float *bias = (const float *)key_bias;
     if (!staged) {   // the workspace is not touched (and may be NULL)
@@ -347,10 +341,10 @@ static dfss_status dense_staged(const void *Q, const void *K, const void *V, con
         if (dfss_status cs = bad_causal(D)) return cs;
     hipStream_t st = (hipStream_t)stream;
     if (D.f32) {
-        if (key_bias && !D.split) return DFSS_ERR_UNSUPPORTED;
         hipError_t e = D.split ? dfss::launch_dense_scores_split(Q, K, (const float *)key_bias, D.H, D.BH, D.Lq, D.Lk, D.d,
                                                                  scale, ws, st)
-                               : dfss::launch_dense_scores_f32(Q, K, D.BH, D.Lq, D.Lk, D.d, scale, ws, st);
+                               : dfss::launch_dense_scores_f32(Q, K, (const float *)key_bias, D.H, D.BH, D.Lq, D.Lk, D.d,
+                                                               scale, ws, st);
         if (e == hipSuccess) e = dfss::launch_row_softmax_f32(ws, (long)D.BH * D.Lq, D.Lk, st);
         if (e == hipSuccess)
             e = D.split ? dfss::launch_dense_av_split(ws, V, D.BH, D.Lq, D.Lk, D.d, O, st)

@@ -48,10 +48,10 @@ hipError_t launch_masked_sddmm_ds(const void *dO, const void *V, const void *O, 
                                   hipStream_t st);
 // The 4-byte mode (Sec. 2.3: float data, 1:2): fp32 Q, K, V, kept scores, weights and O; metadata = one
 // 4-bit code per kept float, 32-bit words in the blocked order [BH, Lq/16, Lk/64, 16, 4].
-hipError_t launch_sddmm_prune_f32(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale,
-                                  void *vals, void *meta, hipStream_t st);
-hipError_t launch_dense_scores_f32(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale, void *S,
-                                   hipStream_t st);
+hipError_t launch_sddmm_prune_f32(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
+                                  int d, float scale, void *vals, void *meta, hipStream_t st);
+hipError_t launch_dense_scores_f32(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
+                                   int d, float scale, void *S, hipStream_t st);
 hipError_t launch_row_softmax_f32(void *x, long rows, int cols, hipStream_t st);
 hipError_t launch_spmm_f32(const void *vals, const void *meta, const void *V, int BH, int Lq, int Lk, int d, void *O,
                            hipStream_t st);

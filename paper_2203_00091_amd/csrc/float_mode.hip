@@ -48,8 +48,11 @@ __device__ __forceinline__ int key_of_slot(int slot) {
 // asynchronous copies.  A 16-byte chunk c of the row in LDS slot s is stored at chunk c ^ (s%16),
 // which spreads the 16 rows that one 128-bit read touches over all banks.
 // ---------------------------------------------------------------------------------------------
-template <int D, bool PRUNE>
+// BIAS: key_bias [B][Lk] (fp32, shared by the H heads of a batch element; -inf masks a key) is added to the scaled
+// score before the comparison: score = fl(fl(scale * q.k) + bias), two roundings.
+template <int D, bool PRUNE, bool BIAS>
 __global__ __launch_bounds__(NT, 2) void k_scores_f32(const float *__restrict__ Q, const float *__restrict__ K,
+                                                      const float *__restrict__ key_bias, int H,
                                                       int Lq, int Lk, float scale, float *__restrict__ out,
                                                       uint32_t *__restrict__ meta) {
     constexpr int CPR = D / 4;                   // 16-byte chunks per row
@@ -95,6 +98,7 @@ __global__ __launch_bounds__(NT, 2) void k_scores_f32(const float *__restrict__ 
         for (int c = 0; c < NCOPY; ++c) async_copy16(base, src[c], lds + (uint32_t)((c * 4 + wave) * 1024));
     };
 
+    const float *const brow = BIAS ? key_bias + (size_t)(bh / H) * Lk : nullptr;
     float *orow = out + ((size_t)bh * Lq + q) * (PRUNE ? Lk / 2 : Lk);
     // metadata word of (row group, block jb, row n, lane group g)
     uint32_t *mrow = PRUNE ? meta + ((size_t)bh * (Lq / 16) + (q >> 4)) * nkb * 64 + n * 4 + g : nullptr;
@@ -105,6 +109,13 @@ __global__ __launch_bounds__(NT, 2) void k_scores_f32(const float *__restrict__ 
         if (jb == 0) wait_async_copies();
         else wait_async_copies_keep<NSTORE>();
         __syncthreads();            // block jb landed for all waves; all waves are done with block jb-1
+        // bias of this lane's keys 64 jb + 16 g + 4 t + e, loaded before the next block's copies are issued (the
+        // memory counter retires in order: waiting for these loads must not mean waiting for those copies)
+        f32x4 b4[4];
+        if constexpr (BIAS) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) b4[t] = *reinterpret_cast<const f32x4 *>(brow + jb * KB + 16 * g + 4 * t);
+        }
         if (jb + 1 < nkb) issue_block(jb + 1);
 
         const float *kb = &Ks[jb & 1][0];
@@ -132,7 +143,8 @@ __global__ __launch_bounds__(NT, 2) void k_scores_f32(const float *__restrict__ 
             for (int t = 0; t < 4; ++t)
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
-                    const float s0 = acc[t][2 * h] * scale, s1 = acc[t][2 * h + 1] * scale;
+                    float s0 = acc[t][2 * h] * scale, s1 = acc[t][2 * h + 1] * scale;
+                    if constexpr (BIAS) s0 = __fadd_rn(s0, b4[t][2 * h]), s1 = __fadd_rn(s1, b4[t][2 * h + 1]);
                     const bool second = s1 > s0;
                     const int p = 2 * t + h;
                     kept[p >> 2][p & 3] = second ? s1 : s0;
@@ -145,7 +157,14 @@ __global__ __launch_bounds__(NT, 2) void k_scores_f32(const float *__restrict__ 
         } else {
             f32x4 *sp = reinterpret_cast<f32x4 *>(orow + jb * KB + 16 * g);
 #pragma unroll
-            for (int t = 0; t < 4; ++t) sp[t] = acc[t] * scale;
+            for (int t = 0; t < 4; ++t) {
+                f32x4 v = acc[t] * scale;
+                if constexpr (BIAS) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = __fadd_rn(v[e], b4[t][e]);
+                }
+                sp[t] = v;
+            }
         }
     }
 }
@@ -253,17 +272,19 @@ __global__ __launch_bounds__(NT, 2) void k_av_f32(const float *__restrict__ A, c
 }
 
 template <bool PRUNE>
-hipError_t launch_scores(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale, void *out,
-                         void *meta, hipStream_t st) {
+hipError_t launch_scores(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk, int d,
+                         float scale, void *out, void *meta, hipStream_t st) {
     const unsigned grid = (unsigned)BH * (unsigned)(Lq / QT);
-    if (d == 64)
-        hipLaunchKernelGGL((k_scores_f32<64, PRUNE>), dim3(grid), dim3(NT), 0, st, (const float *)Q, (const float *)K,
-                           Lq, Lk, scale, (float *)out, (uint32_t *)meta);
-    else if (d == 128)
-        hipLaunchKernelGGL((k_scores_f32<128, PRUNE>), dim3(grid), dim3(NT), 0, st, (const float *)Q,
-                           (const float *)K, Lq, Lk, scale, (float *)out, (uint32_t *)meta);
-    else
-        return hipErrorInvalidValue;
+    if (d != 64 && d != 128) return hipErrorInvalidValue;
+#define DFSS_LAUNCH(DD, BB)                                                                                         \
+    hipLaunchKernelGGL((k_scores_f32<DD, PRUNE, BB>), dim3(grid), dim3(NT), 0, st, (const float *)Q, (const float *)K, \
+                       key_bias, H, Lq, Lk, scale, (float *)out, (uint32_t *)meta)
+    if (d == 64) {
+        if (key_bias) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
+    } else {
+        if (key_bias) DFSS_LAUNCH(128, true); else DFSS_LAUNCH(128, false);
+    }
+#undef DFSS_LAUNCH
     return hipGetLastError();
 }
 
@@ -284,13 +305,13 @@ hipError_t launch_av(const void *A, const void *meta, const void *V, int BH, int
 
 }  // namespace
 
-hipError_t launch_sddmm_prune_f32(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale,
-                                  void *vals, void *meta, hipStream_t st) {
-    return launch_scores<true>(Q, K, BH, Lq, Lk, d, scale, vals, meta, st);
+hipError_t launch_sddmm_prune_f32(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
+                                  int d, float scale, void *vals, void *meta, hipStream_t st) {
+    return launch_scores<true>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, vals, meta, st);
 }
-hipError_t launch_dense_scores_f32(const void *Q, const void *K, int BH, int Lq, int Lk, int d, float scale, void *S,
-                                   hipStream_t st) {
-    return launch_scores<false>(Q, K, BH, Lq, Lk, d, scale, S, nullptr, st);
+hipError_t launch_dense_scores_f32(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
+                                   int d, float scale, void *S, hipStream_t st) {
+    return launch_scores<false>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, S, nullptr, st);
 }
 hipError_t launch_spmm_f32(const void *vals, const void *meta, const void *V, int BH, int Lq, int Lk, int d, void *O,
                            hipStream_t st) {

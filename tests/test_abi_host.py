@@ -126,8 +126,9 @@ def test_errors_are_reported_before_any_launch():
     # the 4-byte mode: calls without a float path refuse it, the others validate as usual
     f32 = Shape(1, 1, 128, 128, 64, 1, 2, dfss.DFSS_F32).c()
     assert lib.dense_attention_fused(aligned, aligned, aligned, ctypes.byref(f32), 0.125, aligned, None) == E_UNSUP
-    assert lib.dfss_sddmm_prune_bias(aligned, aligned, aligned, ctypes.byref(f32), 0.125, aligned, aligned, None) == E_UNSUP
-    assert lib.dfss_attention_bias(aligned, aligned, aligned, aligned, ctypes.byref(f32), 0.125, aligned, ws, 1 << 30, None) == E_UNSUP
+    assert lib.dfss_sddmm_prune_bias(aligned, aligned, odd, ctypes.byref(f32), 0.125, aligned, aligned, None) == E_SHAPE
+    assert lib.dfss_attention_bias(aligned, aligned, aligned, aligned, ctypes.byref(f32), 0.125, aligned, ws, 16, None) == E_WS
+    assert lib.dense_attention_bias(aligned, aligned, aligned, aligned, ctypes.byref(f32), 0.125, aligned, ws, 16, None) == E_WS
     assert lib.dfss_attention_blocked(aligned, aligned, aligned, None, aligned, ctypes.byref(f32), 0.125, aligned, None) == E_UNSUP
     assert lib.dfss_attention_blocked_split(aligned, aligned, aligned, None, aligned, ctypes.byref(f32), 0.125, aligned, ws, 1 << 30, None) == E_UNSUP
     assert lib.dfss_blocked_split_workspace_bytes(ctypes.byref(f32)) == 0

@@ -240,11 +240,11 @@ def test_unsupported_combinations_are_refused(dtype):
     if dtype == DFSS_F32:
         with pytest.raises(dfss.DfssError):
             dfss.dense_attention_fused(Q, K, K, s, 0.125)
-    if dtype == DFSS_F32:      # block patterns and a key bias are taken with bf16x3 products only
+    if dtype == DFSS_F32:      # block patterns and the one-kernel forms are taken with bf16x3 products only
         with pytest.raises(dfss.DfssError):
             dfss.dfss_attention_blocked(Q, K, K, None, torch.ones(1, 2, dtype=torch.uint8, device=DEV), s, 0.125)
         with pytest.raises(dfss.DfssError):
-            dfss.dfss_attention_bias(Q, K, K, torch.zeros(1, 128, device=DEV), s, 0.125)
+            dfss.dense_attention_fused_bias(Q, K, K, torch.zeros(1, 128, device=DEV), s, 0.125)
     with pytest.raises(ValueError):          # bfloat16 tensors with a float shape
         dfss.dfss_attention(Q.bfloat16(), K.bfloat16(), K.bfloat16(), s, 0.125)
 
@@ -349,10 +349,11 @@ def _padding_case(B, H, Lq, Lk, d, seed, integer):
     return Q, K, V, lengths, bias
 
 
+@DTYPES
 @pytest.mark.parametrize("B,H,Lq,Lk,d", [(2, 2, 128, 256, 64), (3, 1, 64, 384, 128), (16, 4, 1024, 128, 64)])
-def test_stage1_key_bias_bit_exact_on_integer_inputs(B, H, Lq, Lk, d):
+def test_stage1_key_bias_bit_exact_on_integer_inputs(B, H, Lq, Lk, d, dtype):
     Q, K, _, lengths, bias = _padding_case(B, H, Lq, Lk, d, 6800 + Lq + d, integer=True)
-    s = _shape(B, H, Lq, Lk, d, DFSS_F32_BF16X3)
+    s = _shape(B, H, Lq, Lk, d, dtype)
     vals, meta = dfss.dfss_sddmm_prune_bias(_dev(Q), _dev(K), _dev(bias), s, 0.125)
     torch.cuda.synchronize()
     vals, meta = vals.cpu().numpy(), _meta_np(meta, s)
@@ -388,6 +389,24 @@ def test_attention_key_bias(B, H, Lq, Lk, d):
         assert np.abs(got - ref).max() <= 2e-2, name
     for name, got in (("dense fused", Odf), ("dense 3-stage", Od)):
         assert np.abs(got.cpu().numpy() - refd).max() <= TOL_O[DFSS_F32_BF16X3], name
+    # fp32 matrix instructions: the stage kernels take the bias too (no one-kernel form there)
+    s32 = _shape(B, H, Lq, Lk, d, DFSS_F32)
+    O32 = dfss.dfss_attention_bias(Qd, Kd, Vd, bd, s32, scale)
+    O32s = dfss.dfss_attention_staged_bias(Qd, Kd, Vd, bd, s32, scale)
+    Od32 = dfss.dense_attention_bias(Qd, Kd, Vd, bd, s32, scale)
+    torch.cuda.synchronize()
+    assert torch.equal(O32, O32s)
+    assert np.isfinite(O32.cpu().numpy()).all()
+    assert np.abs(O32.cpu().numpy() - ref).max() <= 2e-2
+    assert np.abs(Od32.cpu().numpy() - refd).max() <= TOL_O[DFSS_F32]
+    for h in range(B * H):
+        S = oracle.add_key_bias(oracle.scores(Qn[h], Kn[h], scale), bias[h // H].numpy())
+        bound = _score_error_bound(Qn[h], Kn[h], scale, DFSS_F32)
+        with np.errstate(invalid="ignore"):
+            gap = np.abs(S[:, 0::2] - S[:, 1::2])
+        safe = (np.isnan(gap) | (gap > 2 * (bound[:, 0::2] + bound[:, 1::2]))).all(-1)
+        assert safe.sum() > 0
+        assert np.abs(O32.cpu().numpy()[h] - ref[h])[safe].max() <= TOL_O[DFSS_F32]
     # rows with no pair inside the error window: fp32-like accuracy of the pruned path
     for h in range(B * H):
         S = oracle.add_key_bias(oracle.scores(Qn[h], Kn[h], scale), bias[h // H].numpy())
