@@ -384,8 +384,8 @@ __global__ __launch_bounds__(NT, 2) void k_masked_sddmm_ds(const __bf16 *__restr
         for (int qs = 0; qs < NQ; ++qs) {
             const size_t row = (size_t)bh * Lq + q0 + 16 * qs + li;
             u32x4 *dst = reinterpret_cast<u32x4 *>(dS + (row * (size_t)(Lk / 2) + (KB * jb + 32 * kb) / 2) / 2);
-            dst[0] = ds_out[0][qs];
-            dst[1] = ds_out[1][qs];
+            __builtin_nontemporal_store(ds_out[0][qs], dst);
+            __builtin_nontemporal_store(ds_out[1][qs], dst + 1);
         }
     }
     if constexpr (DQ) {

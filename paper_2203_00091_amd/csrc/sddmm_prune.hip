@@ -227,13 +227,14 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
             for (int qs = 0; qs < NQ; ++qs) {
                 const size_t row = (size_t)bh * Lq + q0 + 16 * qs + li;
                 u32x4 *dst = reinterpret_cast<u32x4 *>(out + (row * (size_t)(Lk / 2) + (KB * jb + 32 * kb) / 2) / 2);
-                dst[0] = kept_out[0][qs];
-                dst[1] = kept_out[1][qs];
+                __builtin_nontemporal_store(kept_out[0][qs], dst);
+                __builtin_nontemporal_store(kept_out[1][qs], dst + 1);
             }
 #pragma unroll
             for (int qs = 0; qs < NQ; ++qs)
-                meta[((((size_t)bh * (Lq / 16) + rb0 + qs) * (Lk / KB) + jb) * 16 + li) * 4 + (((kb & 1) << 1) | (kb >> 1))] =
-                    mword[qs];
+                __builtin_nontemporal_store(
+                    mword[qs],
+                    &meta[((((size_t)bh * (Lq / 16) + rb0 + qs) * (Lk / KB) + jb) * 16 + li) * 4 + (((kb & 1) << 1) | (kb >> 1))]);
         }
     }
 }
@@ -464,8 +465,8 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
             // four stores of 8 rows x 128 contiguous bytes: one whole line per row
             uint32_t *const dst = out_sb + (size_t)(KB * jb) / 4;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(dst + i * sb_step) = v[i];
-            if (h == 0) meta_row4[(size_t)jb * 16] = m4;
+            for (int i = 0; i < 4; ++i) __builtin_nontemporal_store(v[i], reinterpret_cast<u32x4 *>(dst + i * sb_step));
+            if (h == 0) __builtin_nontemporal_store(m4, &meta_row4[(size_t)jb * 16]);
         }
     }
 }
