@@ -227,14 +227,13 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
             for (int qs = 0; qs < NQ; ++qs) {
                 const size_t row = (size_t)bh * Lq + q0 + 16 * qs + li;
                 u32x4 *dst = reinterpret_cast<u32x4 *>(out + (row * (size_t)(Lk / 2) + (KB * jb + 32 * kb) / 2) / 2);
-                __builtin_nontemporal_store(kept_out[0][qs], dst);
-                __builtin_nontemporal_store(kept_out[1][qs], dst + 1);
+                dst[0] = kept_out[0][qs];
+                dst[1] = kept_out[1][qs];
             }
 #pragma unroll
             for (int qs = 0; qs < NQ; ++qs)
-                __builtin_nontemporal_store(
-                    mword[qs],
-                    &meta[((((size_t)bh * (Lq / 16) + rb0 + qs) * (Lk / KB) + jb) * 16 + li) * 4 + (((kb & 1) << 1) | (kb >> 1))]);
+                meta[((((size_t)bh * (Lq / 16) + rb0 + qs) * (Lk / KB) + jb) * 16 + li) * 4 + (((kb & 1) << 1) | (kb >> 1))] =
+                    mword[qs];
         }
     }
 }
