@@ -14,7 +14,9 @@
  * Supported: bfloat16 inputs, N:M = 2:4 (the paper's bfloat16 mode, Sec. 2.3) and
  * 1:2 on the same 2-byte data; float inputs with 1:2 (the paper's 4-byte mode, see
  * "the 4-byte mode" below); d in {64, 128}; Lq a multiple of 64, Lk a multiple
- * of 128 and at most 8192 (the *_ragged calls take any Lq and any Lk % 4 == 0).  Selection rule: larger signed score wins, equal scores -> lower key
+ * of 128 and at most 8192.  With bfloat16 data the stage calls (stage 1, 2, 3, the staged forward
+ * pass, the three-kernel baseline) and the *_ragged one-kernel calls also take any Lq >= 1 and any
+ * Lk % 4 == 0 ("lengths that are not tile multiples" below).  Selection rule: larger signed score wins, equal scores -> lower key
  * index wins; comparisons are made on the fp32 value scale*dot, which is then
  * rounded to bfloat16 (nearest-even) for storage (kept as it is in the 4-byte mode).
  *
@@ -151,9 +153,9 @@ dfss_status dfss_attention_staged_static(const void *Q, const void *K, const voi
  * element b) is ADDED to the scaled score in fp32 BEFORE the N:M comparison of stage 1, so a
  * masked key (bias = -inf) loses against any unmasked key of its group; a run of M keys that is
  * entirely masked still emits N entries, whose softmax weight is exactly 0.  Sequences whose
- * length is not a multiple of the tile sizes are run by padding the buffers up to Lq % 64 == 0,
- * Lk % 128 == 0 and masking the padded keys this way (padded query rows produce rows the caller
- * ignores), or -- for the whole forward pass -- with the *_ragged calls below, which need no padding.  Precondition: every batch element has at least one key with a finite bias.
+ * length is not a multiple of the tile sizes need no padding of Q, K, V (see "lengths that are not
+ * tile multiples" below); where a caller pads all the same, the padded keys are masked this way.
+ * Precondition: every batch element has at least one key with a finite bias.
  * key_bias == NULL means no bias: each call then equals the call without the suffix.  All other
  * arguments, layouts and error behaviour are those of the call without the suffix.
  * Arithmetic: when scale is a power of two the bias is the initial value of the fp32 accumulator
@@ -239,7 +241,23 @@ dfss_status dense_attention_fused_blocked_split(const void *Q, const void *K, co
                                                 const dfss_shape *s, float scale, void *O, void *ws,
                                                 size_t ws_bytes, void *stream);
 
-/* ---- lengths that are not tile multiples (one-kernel paths) --------------------------- */
+/* ---- lengths that are not tile multiples ------------------------------------------------ */
+/* The stage calls, bfloat16 data.  dfss_sddmm_prune(_bias), dfss_sparse_softmax, dfss_spmm,
+ * dfss_attention_staged(_bias), dfss_attention_staged_static, dense_attention(_bias), the size
+ * functions and the metadata conversions take ANY Lq >= 1 and any Lk <= 8192 that is a multiple of 4
+ * (whole runs of M keys).  Q and O are [B*H, Lq, d], K and V [B*H, Lk, d], key_bias [B, Lk], as
+ * always; only the arrays the library defines -- vals, meta (both word orders), the workspaces --
+ * are laid out for the PADDED lengths LqP = Lq rounded up to a multiple of 64 and LkP = Lk rounded up
+ * to a multiple of 128: vals [B*H, LqP, LkP*N/M], canonical meta [B*H, LqP, LkP/16]
+ * (dfss_vals_bytes etc. report these sizes; tile multiples are their own padded lengths, so nothing
+ * changes for them).  The keys Lk .. LkP-1 do not exist: their scores count as -inf before the
+ * comparison (as under a key bias of -inf), so a run of M keys that is entirely absent emits N
+ * entries of weight exactly 0.  The rows Lq .. LqP-1 of vals and meta hold valid but meaningless
+ * entries, and no such row of O is written; nothing is read or written past the caller's arrays.
+ * The causal calls, the block-pattern calls and the backward pass take tile multiples only
+ * (DFSS_ERR_UNSUPPORTED / DFSS_ERR_SHAPE otherwise), and so do the 4-byte dtypes.
+ *
+ * The one-kernel calls: */
 /* The paper's long-sequence tasks have lengths such as 4000 (Sec. 5.1, the retrieval task).  These two
  * calls take the arrays as they are: Q, O [B*H, Lq, d] and K, V [B*H, Lk, d] with ANY Lq >= 1 and any
  * Lk <= 8192 that is a multiple of 4 (whole runs of M keys; the key_bias rows [B, Lk] stay 16-byte

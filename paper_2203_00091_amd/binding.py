@@ -65,9 +65,21 @@ class Shape:
         return torch.bfloat16 if self.dtype == DFSS_BF16 else torch.float32
 
     @property
+    def LqP(self) -> int:
+        """Rows of the compressed arrays (vals, meta, the dense workspace): Lq, rounded up to a multiple of 64 where
+        the stage calls take an unpadded length (2-byte dtype)."""
+        return (self.Lq + 63) // 64 * 64
+
+    @property
+    def LkP(self) -> int:
+        """Keys of the compressed arrays: Lk, rounded up to a multiple of 128 where the stage calls take an unpadded
+        length."""
+        return (self.Lk + 127) // 128 * 128
+
+    @property
     def meta_words(self) -> int:
         """uint16 metadata words per row: one 4-bit code per 8 bytes of dense data."""
-        return self.Lk // (16 if self.dtype == DFSS_BF16 else 8)
+        return self.LkP // (16 if self.dtype == DFSS_BF16 else 8)
 
     def c(self) -> _CShape:
         return _CShape(self.B, self.H, self.Lq, self.Lk, self.d, self.N, self.M, self.dtype)
@@ -78,7 +90,8 @@ class Shape:
 
     @property
     def Lc(self) -> int:
-        return self.Lk * self.N // self.M
+        """Kept entries per row of the compressed arrays."""
+        return self.LkP * self.N // self.M
 
 
 _lib = None
@@ -191,12 +204,12 @@ def _kv(t, s: Shape):     # K, V and their gradients: [BH, Lk, d]
 
 
 def _kept(t, s: Shape):   # kept scores / weights: [BH, Lq, Lk*N/M]
-    return _data(t, s, s.BH, s.Lq, s.Lc)
+    return _data(t, s, s.BH, s.LqP, s.Lc)
 
 
 def _meta(t: torch.Tensor, s: Shape) -> int:
-    if t.element_size() != 2 or t.numel() != s.BH * s.Lq * s.meta_words:
-        raise ValueError(f"metadata must hold {s.BH * s.Lq * s.meta_words} 16-bit words")
+    if t.element_size() != 2 or t.numel() != s.BH * s.LqP * s.meta_words:
+        raise ValueError(f"metadata must hold {s.BH * s.LqP * s.meta_words} 16-bit words")
     return _ptr(t)
 
 
@@ -223,9 +236,9 @@ def _alloc_bytes(n: int, device) -> torch.Tensor:
 def dfss_sddmm_prune(Q, K, s: Shape, scale: float, vals=None, meta=None):
     """Stage 1.  Returns (vals [BH, Lq, Lk*N/M] in the shape's dtype, meta: 16-bit words in library order)."""
     if vals is None:
-        vals = torch.empty((s.BH, s.Lq, s.Lc), dtype=s.torch_dtype, device=Q.device)
+        vals = torch.empty((s.BH, s.LqP, s.Lc), dtype=s.torch_dtype, device=Q.device)
     if meta is None:
-        meta = torch.empty((s.BH * s.Lq * s.meta_words,), dtype=torch.int16, device=Q.device)
+        meta = torch.empty((s.BH * s.LqP * s.meta_words,), dtype=torch.int16, device=Q.device)
     st = load_library().dfss_sddmm_prune(_q(Q, s), _kv(K, s), ctypes.byref(s.c()), scale,
                                          _kept(vals, s), _meta(meta, s), _stream())
     _check("dfss_sddmm_prune", st)
@@ -352,9 +365,9 @@ def _bias_ptr(key_bias, s: Shape):
 def dfss_sddmm_prune_bias(Q, K, key_bias, s: Shape, scale: float, vals=None, meta=None):
     """Stage 1 with an additive key bias (float32 [B, Lk] device tensor, -inf masks a key)."""
     if vals is None:
-        vals = torch.empty((s.BH, s.Lq, s.Lc), dtype=s.torch_dtype, device=Q.device)
+        vals = torch.empty((s.BH, s.LqP, s.Lc), dtype=s.torch_dtype, device=Q.device)
     if meta is None:
-        meta = torch.empty((s.BH * s.Lq * s.meta_words,), dtype=torch.int16, device=Q.device)
+        meta = torch.empty((s.BH * s.LqP * s.meta_words,), dtype=torch.int16, device=Q.device)
     st = load_library().dfss_sddmm_prune_bias(_q(Q, s), _kv(K, s), _bias_ptr(key_bias, s),
                                               ctypes.byref(s.c()), scale, _kept(vals, s), _meta(meta, s), _stream())
     _check("dfss_sddmm_prune_bias", st)
@@ -400,9 +413,9 @@ def dense_attention_fused_bias(Q, K, V, key_bias, s: Shape, scale: float, O=None
 def dfss_sddmm_prune_causal(Q, K, key_bias, s: Shape, scale: float, vals=None, meta=None):
     """Stage 1 under the causal mask (query i sees keys 0 .. i + Lk - Lq); key_bias may be None."""
     if vals is None:
-        vals = torch.empty((s.BH, s.Lq, s.Lc), dtype=s.torch_dtype, device=Q.device)
+        vals = torch.empty((s.BH, s.LqP, s.Lc), dtype=s.torch_dtype, device=Q.device)
     if meta is None:
-        meta = torch.empty((s.BH * s.Lq * s.meta_words,), dtype=torch.int16, device=Q.device)
+        meta = torch.empty((s.BH * s.LqP * s.meta_words,), dtype=torch.int16, device=Q.device)
     st = load_library().dfss_sddmm_prune_causal(_q(Q, s), _kv(K, s), _bias_ptr(key_bias, s),
                                                 ctypes.byref(s.c()), scale, _kept(vals, s), _meta(meta, s), _stream())
     _check("dfss_sddmm_prune_causal", st)
@@ -570,7 +583,7 @@ def dfss_attention_backward(dO, Q, K, V, O, P, meta, s: Shape, scale: float, dQ=
 def dfss_meta_to_canonical(meta, s: Shape, canon=None):
     """Library word order -> canonical uint16 [BH, Lq, Lk/16] (held as int16 bits)."""
     if canon is None:
-        canon = torch.empty((s.BH, s.Lq, s.meta_words), dtype=torch.int16, device=meta.device)
+        canon = torch.empty((s.BH, s.LqP, s.meta_words), dtype=torch.int16, device=meta.device)
     st = load_library().dfss_meta_to_canonical(_meta(meta, s), ctypes.byref(s.c()), _meta(canon, s), _stream())
     _check("dfss_meta_to_canonical", st)
     return canon
@@ -578,7 +591,7 @@ def dfss_meta_to_canonical(meta, s: Shape, canon=None):
 
 def dfss_meta_from_canonical(canon, s: Shape, meta=None):
     if meta is None:
-        meta = torch.empty((s.BH * s.Lq * s.meta_words,), dtype=torch.int16, device=canon.device)
+        meta = torch.empty((s.BH * s.LqP * s.meta_words,), dtype=torch.int16, device=canon.device)
     st = load_library().dfss_meta_from_canonical(_meta(canon, s), ctypes.byref(s.c()), _meta(meta, s), _stream())
     _check("dfss_meta_from_canonical", st)
     return meta

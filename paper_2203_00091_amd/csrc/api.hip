@@ -17,6 +17,11 @@ struct Dims {
     int BH, H, Lq, Lk, d, mode;
     bool f32;      // the 4-byte mode: fp32 data, 1:2 only, staged kernels only
     bool split;    // ... with products formed from bfloat16 pieces on the bf16 matrix pipe
+    // The stage calls with unpadded lengths (check_shape_stage): Lq, Lk above are the lengths of the compressed arrays'
+    // layout (Lq rounded up to a multiple of 64, Lk to one of 128) and these the lengths of Q, K, V, key_bias and O.
+    // Everywhere else they equal Lq, Lk.
+    int LqR = 0, LkR = 0;
+    bool unpadded() const { return LqR != Lq || LkR != Lk; }
     size_t elem() const { return f32 ? 4 : 2; }
 };
 
@@ -37,7 +42,7 @@ dfss_status check_shape(const dfss_shape *s, bool need_nm, Dims *out) {
         else if (s->N == 1 && s->M == 2) mode = 1;
         else return DFSS_ERR_UNSUPPORTED;
     }
-    if (out) *out = Dims{(int)bh, s->H, s->Lq, s->Lk, s->d, mode, f32, split};
+    if (out) *out = Dims{(int)bh, s->H, s->Lq, s->Lk, s->d, mode, f32, split, s->Lq, s->Lk};
     return DFSS_OK;
 }
 
@@ -58,7 +63,22 @@ dfss_status check_shape_ragged(const dfss_shape *s, bool need_nm, Dims *out) {
         else if (s->N == 1 && s->M == 2) mode = 1;
         else return DFSS_ERR_UNSUPPORTED;
     }
-    *out = Dims{(int)bh, s->H, s->Lq, s->Lk, s->d, mode, split, split};
+    *out = Dims{(int)bh, s->H, s->Lq, s->Lk, s->d, mode, split, split, s->Lq, s->Lk};
+    return DFSS_OK;
+}
+
+// Shape rules of the stage calls (stage 1, 2, 3, the staged forward pass, the three-kernel dense baseline and the size
+// functions): the tile multiples of check_shape, or -- 2-byte dtype -- the unpadded lengths of check_shape_ragged, for
+// which the compressed arrays take the layout of the lengths rounded up to the tiles.
+dfss_status check_shape_stage(const dfss_shape *s, bool need_nm, Dims *out) {
+    const dfss_status tiles = check_shape(s, need_nm, out);
+    if (tiles != DFSS_ERR_SHAPE || !s || s->dtype != DFSS_BF16) return tiles;
+    if (s->Lq % 64 == 0 && s->Lk % 128 == 0) return tiles;   // (refused for another reason)
+    Dims R;
+    if (const dfss_status st = check_shape_ragged(s, need_nm, &R)) return st;
+    R.Lq = (R.LqR + 63) / 64 * 64;
+    R.Lk = (R.LkR + 127) / 128 * 128;
+    *out = R;
     return DFSS_OK;
 }
 
@@ -90,13 +110,13 @@ extern "C" {
 
 size_t dfss_vals_bytes(const dfss_shape *s) {
     Dims D;
-    if (check_shape(s, true, &D) != DFSS_OK) return 0;
+    if (check_shape_stage(s, true, &D) != DFSS_OK) return 0;
     return (size_t)D.BH * D.Lq * (D.Lk / 2) * D.elem();
 }
 
 size_t dfss_meta_bytes(const dfss_shape *s) {
     Dims D;
-    if (check_shape(s, true, &D) != DFSS_OK) return 0;
+    if (check_shape_stage(s, true, &D) != DFSS_OK) return 0;
     return (size_t)D.BH * D.Lq * (D.Lk / (D.f32 ? 8 : 16)) * 2;   // one code per 8 bytes of dense data
 }
 
@@ -108,7 +128,7 @@ size_t dfss_workspace_bytes(const dfss_shape *s) {
 
 size_t dense_workspace_bytes(const dfss_shape *s) {
     Dims D;
-    if (check_shape(s, false, &D) != DFSS_OK) return 0;
+    if (check_shape_stage(s, false, &D) != DFSS_OK) return 0;
     return align_up((size_t)D.BH * D.Lq * D.Lk * D.elem());
 }
 
@@ -122,16 +142,18 @@ static dfss_status sddmm_prune(const void *Q, const void *K, const void *key_bia
                                void *vals, void *meta, void *stream, bool causal) {
     Dims D;
     if (!Q || !K || !vals || !meta) return DFSS_ERR_NULL;
-    if (dfss_status st = check_shape(s, true, &D)) return st;
+    if (dfss_status st = check_shape_stage(s, true, &D)) return st;
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
     if (misaligned(Q) || misaligned(K) || misaligned(vals) || misaligned(meta) || misaligned(key_bias))
         return DFSS_ERR_SHAPE;
-    if (causal)
+    if (causal) {
+        if (D.unpadded()) return DFSS_ERR_UNSUPPORTED;
         if (dfss_status st = bad_causal(D)) return st;
+    }
     if (D.f32)
         return hip_status(sddmm_prune_f32(D, Q, K, (const float *)key_bias, scale, vals, meta, (hipStream_t)stream));
-    return hip_status(dfss::launch_sddmm_prune(Q, K, (const float *)key_bias, D.H, causal, D.BH, D.Lq, D.Lk, D.d,
-                                               D.mode, scale, vals, meta, (hipStream_t)stream));
+    return hip_status(dfss::launch_sddmm_prune(Q, K, (const float *)key_bias, D.H, causal, D.BH, D.Lq, D.Lk, D.LqR, D.LkR,
+                                               D.d, D.mode, scale, vals, meta, (hipStream_t)stream));
 }
 
 dfss_status dfss_sddmm_prune_bias(const void *Q, const void *K, const void *key_bias, const dfss_shape *s,
@@ -152,7 +174,7 @@ dfss_status dfss_sddmm_prune(const void *Q, const void *K, const dfss_shape *s, 
 dfss_status dfss_sparse_softmax(void *vals, const dfss_shape *s, void *stream) {
     Dims D;
     if (!vals) return DFSS_ERR_NULL;
-    if (dfss_status st = check_shape(s, true, &D)) return st;
+    if (dfss_status st = check_shape_stage(s, true, &D)) return st;
     if (misaligned(vals)) return DFSS_ERR_SHAPE;
     if (D.f32) return hip_status(dfss::launch_row_softmax_f32(vals, (long)D.BH * D.Lq, D.Lk / 2, (hipStream_t)stream));
     return hip_status(dfss::launch_row_softmax(vals, (long)D.BH * D.Lq, D.Lk / 2, (hipStream_t)stream));
@@ -162,10 +184,10 @@ dfss_status dfss_spmm(const void *vals, const void *meta, const void *V, const d
                       void *stream) {
     Dims D;
     if (!vals || !meta || !V || !O) return DFSS_ERR_NULL;
-    if (dfss_status st = check_shape(s, true, &D)) return st;
+    if (dfss_status st = check_shape_stage(s, true, &D)) return st;
     if (misaligned(vals) || misaligned(meta) || misaligned(V) || misaligned(O)) return DFSS_ERR_SHAPE;
     if (D.f32) return hip_status(spmm_f32(D, vals, meta, V, O, (hipStream_t)stream));
-    return hip_status(dfss::launch_spmm(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, (hipStream_t)stream));
+    return hip_status(dfss::launch_spmm(vals, meta, V, D.BH, D.Lq, D.Lk, D.LqR, D.LkR, D.d, O, (hipStream_t)stream));
 }
 
 // The whole forward pass.  staged: the three stage kernels through the workspace; otherwise one kernel
@@ -175,12 +197,15 @@ static dfss_status attention_forward(const void *Q, const void *K, const void *V
                                      bool staged, int variant, bool causal = false) {
     Dims D;
     if (!Q || !K || !V || !O) return DFSS_ERR_NULL;
-    if (dfss_status st = check_shape(s, true, &D)) return st;
+    // (unpadded lengths: the staged calls only; the one-kernel calls for them are the *_ragged ones)
+    if (dfss_status st = staged ? check_shape_stage(s, true, &D) : check_shape(s, true, &D)) return st;
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias))
         return DFSS_ERR_SHAPE;
-    if (causal)
+    if (causal) {
+        if (D.unpadded()) return DFSS_ERR_UNSUPPORTED;
         if (dfss_status cs = bad_causal(D)) return cs;
+    }
     if (D.f32 && !D.split) staged = true;   // (fp32 matrix instructions: the stage kernels only)
     hipStream_t st = (hipStream_t)stream;
     const float *bias = (const float *)key_bias;
@@ -204,8 +229,8 @@ static dfss_status attention_forward(const void *Q, const void *K, const void *V
     }
     // two kernels: the kept scores go to the workspace once and the product applies the softmax as it reads them
     hipError_t e =
-        dfss::launch_sddmm_prune(Q, K, bias, D.H, causal, D.BH, D.Lq, D.Lk, D.d, D.mode, scale, vals, meta, st);
-    if (e == hipSuccess) e = dfss::launch_softmax_spmm(vals, meta, V, D.BH, D.Lq, D.Lk, D.d, O, st);
+        dfss::launch_sddmm_prune(Q, K, bias, D.H, causal, D.BH, D.Lq, D.Lk, D.LqR, D.LkR, D.d, D.mode, scale, vals, meta, st);
+    if (e == hipSuccess) e = dfss::launch_softmax_spmm(vals, meta, V, D.BH, D.Lq, D.Lk, D.LqR, D.LkR, D.d, O, st);
     return hip_status(e);
 }
 
@@ -331,14 +356,16 @@ static dfss_status dense_staged(const void *Q, const void *K, const void *V, con
                                 float scale, void *O, void *ws, size_t ws_bytes, void *stream, bool causal) {
     Dims D;
     if (!Q || !K || !V || !O || !ws) return DFSS_ERR_NULL;
-    if (dfss_status st = check_shape(s, false, &D)) return st;
+    if (dfss_status st = check_shape_stage(s, false, &D)) return st;
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(key_bias))
         return DFSS_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0) return DFSS_ERR_SHAPE;
     if (ws_bytes < dense_workspace_bytes(s)) return DFSS_ERR_WORKSPACE;
-    if (causal)
+    if (causal) {
+        if (D.unpadded()) return DFSS_ERR_UNSUPPORTED;
         if (dfss_status cs = bad_causal(D)) return cs;
+    }
     hipStream_t st = (hipStream_t)stream;
     if (D.f32) {
         hipError_t e = D.split ? dfss::launch_dense_scores_split(Q, K, (const float *)key_bias, D.H, D.BH, D.Lq, D.Lk, D.d,
@@ -352,9 +379,9 @@ static dfss_status dense_staged(const void *Q, const void *K, const void *V, con
         return hip_status(e);
     }
     hipError_t e =
-        dfss::launch_dense_scores(Q, K, (const float *)key_bias, D.H, causal, D.BH, D.Lq, D.Lk, D.d, scale, ws, st);
+        dfss::launch_dense_scores(Q, K, (const float *)key_bias, D.H, causal, D.BH, D.Lq, D.Lk, D.LqR, D.LkR, D.d, scale, ws, st);
     if (e == hipSuccess) e = dfss::launch_row_softmax(ws, (long)D.BH * D.Lq, D.Lk, st);
-    if (e == hipSuccess) e = dfss::launch_dense_av(ws, V, D.BH, D.Lq, D.Lk, D.d, O, st);
+    if (e == hipSuccess) e = dfss::launch_dense_av(ws, V, D.BH, D.Lq, D.Lk, D.LqR, D.LkR, D.d, O, st);
     return hip_status(e);
 }
 
@@ -505,7 +532,7 @@ dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K
         e = dfss::launch_masked_sddmm_ds(dO, V, O, P, meta, K, D.BH, D.Lq, D.Lk, D.d, scale, dS, dQ, st);
     } else {
         e = dfss::launch_masked_sddmm_ds(dO, V, O, P, meta, nullptr, D.BH, D.Lq, D.Lk, D.d, scale, dS, nullptr, st);
-        if (e == hipSuccess) e = dfss::launch_spmm(dS, meta, K, D.BH, D.Lq, D.Lk, D.d, dQ, st);   // dQ = dS' K
+        if (e == hipSuccess) e = dfss::launch_spmm(dS, meta, K, D.BH, D.Lq, D.Lk, D.Lq, D.Lk, D.d, dQ, st);   // dQ = dS' K
     }
     if (e == hipSuccess) e = dfss::launch_spmm_t(P, meta, dO, D.BH, D.Lq, D.Lk, D.d, dV, st);    // dV = P^T dO
     if (e == hipSuccess) e = dfss::launch_spmm_t(dS, meta, Q, D.BH, D.Lq, D.Lk, D.d, dK, st);    // dK = dS'^T Q
@@ -521,7 +548,7 @@ size_t dfss_backward_workspace_bytes(const dfss_shape *s) {
 dfss_status dfss_meta_to_canonical(const void *meta, const dfss_shape *s, uint16_t *canon, void *stream) {
     Dims D;
     if (!meta || !canon) return DFSS_ERR_NULL;
-    if (dfss_status st = check_shape(s, true, &D)) return st;
+    if (dfss_status st = check_shape_stage(s, true, &D)) return st;
     if (misaligned(meta) || misaligned(canon)) return DFSS_ERR_SHAPE;
     return hip_status(dfss::launch_meta_reorder(meta, canon, D.BH, D.Lq, D.Lk / (D.f32 ? 16 : 32), true, !D.f32,
                                                 (hipStream_t)stream));
@@ -530,7 +557,7 @@ dfss_status dfss_meta_to_canonical(const void *meta, const dfss_shape *s, uint16
 dfss_status dfss_meta_from_canonical(const uint16_t *canon, const dfss_shape *s, void *meta, void *stream) {
     Dims D;
     if (!meta || !canon) return DFSS_ERR_NULL;
-    if (dfss_status st = check_shape(s, true, &D)) return st;
+    if (dfss_status st = check_shape_stage(s, true, &D)) return st;
     if (misaligned(meta) || misaligned(canon)) return DFSS_ERR_SHAPE;
     return hip_status(dfss::launch_meta_reorder(canon, meta, D.BH, D.Lq, D.Lk / (D.f32 ? 16 : 32), false, !D.f32,
                                                 (hipStream_t)stream));

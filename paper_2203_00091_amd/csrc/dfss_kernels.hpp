@@ -8,22 +8,24 @@ namespace dfss {
 
 // key_bias (where present): fp32 [BH / H][Lk] added to the scaled scores before the selection, or
 // nullptr for none (then H is ignored).
+// LqR, LkR (where present): the real lengths of the caller's arrays (Q, K, V, key_bias, O) when they differ from the
+// layout lengths Lq (a multiple of 64) and Lk (of 128) of the compressed arrays; else equal to Lq, Lk.
 // Stage 1 (Sec. 3.4, App. A.1.2): scores + N:M pruning epilogue.  mode: 0 = 2:4, 1 = 1:2.
 hipError_t launch_sddmm_prune(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq, int Lk,
-                              int d, int mode, float scale, void *vals, void *meta, hipStream_t st);
+                              int LqR, int LkR, int d, int mode, float scale, void *vals, void *meta, hipStream_t st);
 // Dense scores S = scale * Q K^T stored as bfloat16 [BH, Lq, Lk] (Eq. 1), same mainloop.
 hipError_t launch_dense_scores(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq, int Lk,
-                               int d, float scale, void *S, hipStream_t st);
+                               int LqR, int LkR, int d, float scale, void *S, hipStream_t st);
 // Row softmax in place over bfloat16 rows (App. A.1.3); rows of `cols` elements.
 hipError_t launch_row_softmax(void *x, long rows, int cols, hipStream_t st);
 // Stage 3 (Sec. 3.1): O = A_sparse V from compressed weights + metadata.
-hipError_t launch_spmm(const void *vals, const void *meta, const void *V, int BH, int Lq, int Lk, int d,
+hipError_t launch_spmm(const void *vals, const void *meta, const void *V, int BH, int Lq, int Lk, int LqR, int LkR, int d,
                        void *O, hipStream_t st);
 // The same product on the kept SCORES of stage 1, with the softmax over them applied on the way.
-hipError_t launch_softmax_spmm(const void *scores, const void *meta, const void *V, int BH, int Lq, int Lk, int d,
-                               void *O, hipStream_t st);
+hipError_t launch_softmax_spmm(const void *scores, const void *meta, const void *V, int BH, int Lq, int Lk, int LqR,
+                               int LkR, int d, void *O, hipStream_t st);
 // Dense O = P V with P bfloat16 [BH, Lq, Lk].
-hipError_t launch_dense_av(const void *P, const void *V, int BH, int Lq, int Lk, int d, void *O,
+hipError_t launch_dense_av(const void *P, const void *V, int BH, int Lq, int Lk, int LqR, int LkR, int d, void *O,
                            hipStream_t st);
 // Whole forward pass in one kernel.  mode: 0 = 2:4, 1 = 1:2, 2 = dense (full attention, Eq. 1).
 // block_mask: uint8 [Lq/64][Lk/64] shared by all heads (zero = block not part of the attention), or nullptr.

@@ -249,11 +249,19 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
 // ---------------------------------------------------------------------------------------------
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-template <int D, int MODE, bool PRESCALE, bool BIAS, bool CAUSAL>
+// KMASK: 0 = none; 1 = causal (as above); 2 = unpadded lengths: Q holds LqR <= Lq rows per head and K (and key_bias)
+// LkR <= Lk keys, while the outputs keep the layout of the padded lengths Lq (a multiple of 64) and Lk (of 128).
+// The keys LkR .. Lk - 1 do not exist: their scores count as -inf, overwritten by index like the causal ones; their
+// places in a partial last block are filled with the block's last real key, and rows past LqR are computed on a copy
+// of the last query (never read past the arrays).  Waves whose 32 rows lie past Lq store nothing.
+enum { KMASK_NONE = 0, KMASK_CAUSAL = 1, KMASK_UNPADDED = 2 };
+template <int D, int MODE, bool PRESCALE, bool BIAS, int KMASK>
 __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
                                                    const float *__restrict__ key_bias, int H,
-                                                   int Lq, int Lk, float scale, int ksplit, int blocks_per_wg,
-                                                   uint32_t *__restrict__ out, uint32_t *__restrict__ meta) {
+                                                   int Lq, int Lk, int LqR, int LkR, float scale, int ksplit,
+                                                   int blocks_per_wg, uint32_t *__restrict__ out,
+                                                   uint32_t *__restrict__ meta) {
+    constexpr bool CAUSAL = KMASK == KMASK_CAUSAL, UNPADDED = KMASK == KMASK_UNPADDED;
     constexpr int CPR = D / 8;           // 16-byte chunks per row
     constexpr int TILE = KB * CPR;       // chunks per K block
     constexpr int LPT = TILE / NT;       // asynchronous copies per thread per block
@@ -276,15 +284,16 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
     const int tid = threadIdx.x;
     const int w = tid >> 6, l = tid & 63, lj = l & 31, h = l >> 5;
 
-    const unsigned qtiles = Lq / TQ;
+    const unsigned qtiles = (Lq + TQ - 1) / TQ;   // (Lq % 128 == 64 only with unpadded lengths)
     const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
     const int ks_id = item % ksplit;
     const int qt = (item / ksplit) % qtiles;
     const int bh = item / (ksplit * qtiles);
     const int jb0 = ks_id * blocks_per_wg;
     const int q0 = qt * TQ + w * 32;
+    const bool wave_stores = !UNPADDED || __builtin_amdgcn_readfirstlane(q0) < Lq;
 
-    const __bf16 *Kh = K + (size_t)bh * Lk * D;
+    const __bf16 *Kh = K + (size_t)bh * LkR * D;
 
     // LDS position p (16-byte units) = slot * CPR + (c ^ (slot & 7)) holds chunk c of the key of row slot `slot`
     int src_off[LPT];
@@ -297,10 +306,28 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
         src_off[i] = key * D + c * 8;
     }
     const uint32_t lds_k = lds_address(&Ks[0][w * 64]);
-    const float *bias_b = BIAS ? key_bias + (size_t)(bh / H) * Lk : nullptr;
+    const float *bias_b = BIAS ? key_bias + (size_t)(bh / H) * LkR : nullptr;
     const uint32_t lds_b = lds_address(&Bs[0][0]);
     auto issue_block = [&](int jb, int buf) {
         const __bf16 *src = Kh + (size_t)jb * KB * D;
+        const int real = LkR - jb * KB;   // real keys from this block's first one on
+        if (UNPADDED && real < KB) {
+            // partial last block: the places of the absent keys take the block's last real key
+#pragma unroll
+            for (int i = 0; i < LPT; ++i) {
+                const int p = i * NT + tid;
+                const int slot = p / CPR, c = (p % CPR) ^ (slot & 7);
+                const int t = slot >> 5, r = slot & 31;
+                const int key = 64 * (t >> 1) + 32 * ((r >> 2) & 1) + 16 * (t & 1) + 4 * (r >> 3) + (r & 3);
+                async_copy16(src, 2u * ((key < real ? key : real - 1) * D + c * 8), lds_k + 16u * (buf * TILE + i * NT));
+            }
+            if constexpr (BIAS_LDS) {   // (LkR is a multiple of 4: the last float4 of the row stands in for the absent ones)
+                if (tid < KB / 4)
+                    async_copy16(bias_b + (size_t)jb * KB, 16u * (4 * tid < real ? tid : real / 4 - 1),
+                                 lds_b + (uint32_t)(buf * KB * 4));
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < LPT; ++i) async_copy16(src, 2u * src_off[i], lds_k + 16u * (buf * TILE + i * NT));
         if constexpr (BIAS_LDS) {   // 512 bytes: lanes 0..31 of wave 0 (the copy lands through the same counter as K)
@@ -314,8 +341,8 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
     bf16x8 bq[STEPS];
 #pragma unroll
     for (int s = 0; s < STEPS; ++s) {
-        const u32x4 raw =
-            *reinterpret_cast<const u32x4 *>(Q + ((size_t)bh * Lq + q0 + lj) * D + 16 * s + 8 * h);
+        const int qrow = UNPADDED && q0 + lj >= LqR ? LqR - 1 : q0 + lj;
+        const u32x4 raw = *reinterpret_cast<const u32x4 *>(Q + ((size_t)bh * LqR + qrow) * D + 16 * s + 8 * h);
         if constexpr (PRESCALE) {
             u32x4 sc;
 #pragma unroll
@@ -346,7 +373,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
         // Block `it` must have landed.  The stores of the previous iteration were issued after its
         // copy and may stay in flight (waiting for them would expose the store latency every block).
         constexpr int kStores = MODE == MODE_DENSE ? 8 : 5;   // stores per iteration, exactly (or lower): 4 of values + 1 of metadata
-        if (it == 0) wait_async_copies();
+        if (it == 0 || !wave_stores) wait_async_copies();   // (a wave that stores nothing has nothing younger in flight)
         else wait_async_copies_keep<kStores>();
         __syncthreads();       // ... for every wave, and everybody is done with the block before
         f32x4 kbg[2][2][4];    // (BIAS without LDS) bias of keys 128 jb + 64 p + 32 h + 16 u + 4 g + x, loaded before the
@@ -358,7 +385,11 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
                 for (int u = 0; u < 2; ++u)
 #pragma unroll
                     for (int g = 0; g < 4; ++g)
-                        kbg[p][u][g] = *reinterpret_cast<const f32x4 *>(bias_b + (size_t)jb * KB + 64 * p + 32 * h + 16 * u + 4 * g);
+                    {
+                        int key = jb * KB + 64 * p + 32 * h + 16 * u + 4 * g;
+                        if (UNPADDED && key >= LkR) key = LkR - 4;   // (an absent key: masked below, whatever its bias)
+                        kbg[p][u][g] = *reinterpret_cast<const f32x4 *>(bias_b + key);
+                    }
         }
         if (it + 1 < blocks_per_wg) issue_block(jb + 1, buf ^ 1);
 
@@ -392,9 +423,10 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
             const int kbase = KB * jb + 64 * p + 32 * h;
             // causal: hidden scores become -inf on the raw accumulators (the scaling and the bias leave -inf as it is).
             // q0 is the same in every lane of the wave; as a scalar, the test is one branch around the masking.
-            if (CAUSAL && KB * jb + 64 * p + 63 > __builtin_amdgcn_readfirstlane(q0) + Lk - Lq) {
+            if (KMASK != KMASK_NONE &&
+                KB * jb + 64 * p + 63 > (CAUSAL ? __builtin_amdgcn_readfirstlane(q0) + Lk - Lq : LkR - 1)) {
                 asm volatile("" ::: "memory");   // (not to be turned into selects that every block would execute)
-                const int lim = q0 + lj + Lk - Lq - kbase;   // key offsets above it are hidden
+                const int lim = (CAUSAL ? q0 + lj + Lk - Lq : LkR - 1) - kbase;   // key offsets above it are hidden
 #pragma unroll
                 for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -419,7 +451,8 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
                     }
                 u32x4 *dst = reinterpret_cast<u32x4 *>(out + (row * Lk + kbase) / 2);
 #pragma unroll
-                for (int c = 0; c < 4; ++c) dst[c] = u32x4{pk[4 * c], pk[4 * c + 1], pk[4 * c + 2], pk[4 * c + 3]};
+                for (int c = 0; c < 4; ++c)
+                    if (wave_stores) dst[c] = u32x4{pk[4 * c], pk[4 * c + 1], pk[4 * c + 2], pk[4 * c + 3]};
             } else {
                 uint32_t word = 0;
                 u32x4 pk[2];
@@ -463,9 +496,11 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
                               (uint32_t)__shfl_xor((int)mwords[1], 32)};
             // four stores of 8 rows x 128 contiguous bytes: one whole line per row
             uint32_t *const dst = out_sb + (size_t)(KB * jb) / 4;
+            if (wave_stores) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) __builtin_nontemporal_store(v[i], reinterpret_cast<u32x4 *>(dst + i * sb_step));
-            if (h == 0) __builtin_nontemporal_store(m4, &meta_row4[(size_t)jb * 16]);
+                for (int i = 0; i < 4; ++i) __builtin_nontemporal_store(v[i], reinterpret_cast<u32x4 *>(dst + i * sb_step));
+                if (h == 0) __builtin_nontemporal_store(m4, &meta_row4[(size_t)jb * 16]);
+            }
         }
     }
 }
@@ -500,10 +535,10 @@ hipError_t launch_nq(const void *Q, const void *K, const float *key_bias, int H,
     return hipGetLastError();
 }
 
-template <int MODE, bool BIAS, bool CAUSAL>
-hipError_t launch32(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
+template <int MODE, bool BIAS, int KMASK>
+hipError_t launch32(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk, int LqR, int LkR,
                     int d, float scale, void *out, void *meta, hipStream_t st) {
-    const int qtiles = Lq / 128;
+    const int qtiles = (Lq + 127) / 128;
     const int kblocks = Lk / KB;
     int ksplit = 1;
     while ((long)BH * qtiles * ksplit < 1024 && kblocks % (ksplit * 2) == 0) ksplit *= 2;
@@ -512,8 +547,8 @@ hipError_t launch32(const void *Q, const void *K, const float *key_bias, int H, 
     const unsigned grid = (unsigned)((long)BH * qtiles * ksplit);
     const bool pre = is_pow2(scale);
 #define DFSS_LAUNCH(DD, PRE)                                                                             \
-    hipLaunchKernelGGL((k_sddmm32<DD, MODE, PRE, BIAS, CAUSAL>), dim3(grid), dim3(NT), 0, st,                \
-                       (const __bf16 *)Q, (const __bf16 *)K, key_bias, H, Lq, Lk, scale, ksplit, per_wg,       \
+    hipLaunchKernelGGL((k_sddmm32<DD, MODE, PRE, BIAS, KMASK>), dim3(grid), dim3(NT), 0, st,                 \
+                       (const __bf16 *)Q, (const __bf16 *)K, key_bias, H, Lq, Lk, LqR, LkR, scale, ksplit, per_wg, \
                        (uint32_t *)out, (uint32_t *)meta)
     if (d == 64) {
         if (pre) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
@@ -528,13 +563,20 @@ template <int MODE, bool BIAS, bool CAUSAL>
 hipError_t launch_b(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,
                     int d, float scale, void *out, void *meta, hipStream_t st) {
     // 32 queries per wave (32x32x16 MFMA) when the query count allows it, else 16 (16x16x32 MFMA)
-    if (Lq % 128 == 0) return launch32<MODE, BIAS, CAUSAL>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
+    if (Lq % 128 == 0)
+        return launch32<MODE, BIAS, CAUSAL ? KMASK_CAUSAL : KMASK_NONE>(Q, K, key_bias, H, BH, Lq, Lk, Lq, Lk, d, scale, out,
+                                                                         meta, st);
     return launch_nq<MODE, 1, BIAS, CAUSAL>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
 }
 
 template <int MODE>
 hipError_t launch(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq, int Lk,
-                  int d, float scale, void *out, void *meta, hipStream_t st) {
+                  int LqR, int LkR, int d, float scale, void *out, void *meta, hipStream_t st) {
+    if (LqR != Lq || LkR != Lk) {   // unpadded lengths (never with the causal mask)
+        if (key_bias)
+            return launch32<MODE, true, KMASK_UNPADDED>(Q, K, key_bias, H, BH, Lq, Lk, LqR, LkR, d, scale, out, meta, st);
+        return launch32<MODE, false, KMASK_UNPADDED>(Q, K, nullptr, 1, BH, Lq, Lk, LqR, LkR, d, scale, out, meta, st);
+    }
     if (causal) {
         if (key_bias) return launch_b<MODE, true, true>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
         return launch_b<MODE, false, true>(Q, K, nullptr, 1, BH, Lq, Lk, d, scale, out, meta, st);
@@ -546,14 +588,15 @@ hipError_t launch(const void *Q, const void *K, const float *key_bias, int H, in
 }  // namespace
 
 hipError_t launch_sddmm_prune(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq,
-                              int Lk, int d, int mode, float scale, void *vals, void *meta, hipStream_t st) {
-    return mode == 0 ? launch<MODE_2TO4>(Q, K, key_bias, H, causal, BH, Lq, Lk, d, scale, vals, meta, st)
-                     : launch<MODE_1TO2>(Q, K, key_bias, H, causal, BH, Lq, Lk, d, scale, vals, meta, st);
+                              int Lk, int LqR, int LkR, int d, int mode, float scale, void *vals, void *meta,
+                              hipStream_t st) {
+    return mode == 0 ? launch<MODE_2TO4>(Q, K, key_bias, H, causal, BH, Lq, Lk, LqR, LkR, d, scale, vals, meta, st)
+                     : launch<MODE_1TO2>(Q, K, key_bias, H, causal, BH, Lq, Lk, LqR, LkR, d, scale, vals, meta, st);
 }
 
 hipError_t launch_dense_scores(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq,
-                               int Lk, int d, float scale, void *S, hipStream_t st) {
-    return launch<MODE_DENSE>(Q, K, key_bias, H, causal, BH, Lq, Lk, d, scale, S, nullptr, st);
+                               int Lk, int LqR, int LkR, int d, float scale, void *S, hipStream_t st) {
+    return launch<MODE_DENSE>(Q, K, key_bias, H, causal, BH, Lq, Lk, LqR, LkR, d, scale, S, nullptr, st);
 }
 
 }  // namespace dfss

@@ -33,9 +33,12 @@ namespace {
 constexpr int NT = 256;   // 4 waves
 constexpr int KB = 128;   // keys per block
 
-template <int D, bool SPARSE, int RB, bool SOFTMAX>
+// UNPADDED: V holds LkR <= Lk keys per head and O LqR <= Lq rows, while P and meta have the layout of the padded
+// lengths Lq (a multiple of 64) and Lk (of 128).  The weights of the absent keys are 0 (their scores were -inf); their
+// places in a partial last block of V are filled with the block's last real key, and rows past LqR are not stored.
+template <int D, bool SPARSE, int RB, bool SOFTMAX, bool UNPADDED = false>
 __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, const uint32_t *__restrict__ meta,
-                                              const __bf16 *__restrict__ V, int Lq, int Lk,
+                                              const __bf16 *__restrict__ V, int Lq, int Lk, int LqR, int LkR,
                                               uint16_t *__restrict__ O) {
     constexpr int CPR = D / 8;          // 16-byte chunks per V row
     constexpr int TILE = KB * CPR;      // chunks per V block
@@ -56,7 +59,7 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
     const int meta_slot = ((kb & 1) << 1) | (kb >> 1);   // where the word of 32-key chunk kb sits in a row's 16 bytes
 
     // LDS position p (16-byte units) = row * CPR + (c ^ ((row & 3) << 1)) holds chunk c of key `row`
-    const __bf16 *Vh = V + (size_t)bh * Lk * D;
+    const __bf16 *Vh = V + (size_t)bh * LkR * D;
     int src_off[LPT];
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
@@ -67,6 +70,16 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
     const uint32_t lds_v = lds_address(&Vs[0][w * 64]);   // this wave's 1 KB slice of copy 0, buffer 0
     auto issue_block = [&](int jb, int buf) {
         const __bf16 *src = Vh + (size_t)jb * KB * D;
+        const int real = LkR - jb * KB;   // real keys from this block's first one on
+        if (UNPADDED && real < KB) {
+#pragma unroll
+            for (int i = 0; i < LPT; ++i) {
+                const int p = i * NT + tid;
+                const int row = p / CPR, c = (p % CPR) ^ ((row & 3) << 1);
+                async_copy16(src, 2u * ((row < real ? row : real - 1) * D + c * 8), lds_v + 16u * (buf * TILE + i * NT));
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < LPT; ++i) async_copy16(src, 2u * src_off[i], lds_v + 16u * (buf * TILE + i * NT));
     };
@@ -242,7 +255,9 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
     for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const size_t q = (size_t)bh * Lq + (size_t)(rb0 + rb) * 16 + 4 * kb + r;
+            const int qrow = (rb0 + rb) * 16 + 4 * kb + r;
+            if (UNPADDED && qrow >= LqR) continue;
+            const size_t q = (size_t)bh * LqR + qrow;
             const float ir = SOFTMAX ? 1.0f / acc_l[rb][r] : 1.f;   // (the sum of row 4 kb + r, in every column)
 #pragma unroll
             for (int ds = 0; ds < DS; ++ds)
@@ -252,15 +267,24 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
 }
 
 template <bool SPARSE, bool SOFTMAX = false>
-hipError_t launch(const void *P, const void *meta, const void *V, int BH, int Lq, int Lk, int d, void *O,
-                  hipStream_t st) {
+hipError_t launch(const void *P, const void *meta, const void *V, int BH, int Lq, int Lk, int LqR, int LkR, int d,
+                  void *O, hipStream_t st) {
+    if (LqR != Lq || LkR != Lk) {   // unpadded lengths: 64-query workgroups (Lq is a multiple of 64)
+        const unsigned grid = (unsigned)((long)BH * (Lq / 64));
+#define DFSS_LAUNCH(DD)                                                                                             \
+    hipLaunchKernelGGL((k_av<DD, SPARSE, 1, SOFTMAX, true>), dim3(grid), dim3(NT), 0, st, (const uint32_t *)P,     \
+                       (const uint32_t *)meta, (const __bf16 *)V, Lq, Lk, LqR, LkR, (uint16_t *)O)
+        if (d == 64) DFSS_LAUNCH(64); else DFSS_LAUNCH(128);
+#undef DFSS_LAUNCH
+        return hipGetLastError();
+    }
     // two row blocks per wave when that still leaves two workgroups per compute unit (measured:
     // from there on the larger tile wins, below it the finer grid does)
     bool rb2 = (Lq % 128 == 0) && ((long)BH * (Lq / 128) >= 512);
     const unsigned grid = (unsigned)((long)BH * (Lq / (rb2 ? 128 : 64)));
 #define DFSS_LAUNCH(DD, RR)                                                                                   \
     hipLaunchKernelGGL((k_av<DD, SPARSE, RR, SOFTMAX>), dim3(grid), dim3(NT), 0, st, (const uint32_t *)P,              \
-                       (const uint32_t *)meta, (const __bf16 *)V, Lq, Lk, (uint16_t *)O)
+                       (const uint32_t *)meta, (const __bf16 *)V, Lq, Lk, Lq, Lk, (uint16_t *)O)
     if (d == 64) {
         if (rb2) DFSS_LAUNCH(64, 2); else DFSS_LAUNCH(64, 1);
     } else {
@@ -272,18 +296,19 @@ hipError_t launch(const void *P, const void *meta, const void *V, int BH, int Lq
 
 }  // namespace
 
-hipError_t launch_spmm(const void *vals, const void *meta, const void *V, int BH, int Lq, int Lk, int d, void *O,
-                       hipStream_t st) {
-    return launch<true>(vals, meta, V, BH, Lq, Lk, d, O, st);
+hipError_t launch_spmm(const void *vals, const void *meta, const void *V, int BH, int Lq, int Lk, int LqR, int LkR, int d,
+                       void *O, hipStream_t st) {
+    return launch<true>(vals, meta, V, BH, Lq, Lk, LqR, LkR, d, O, st);
 }
 
-hipError_t launch_softmax_spmm(const void *scores, const void *meta, const void *V, int BH, int Lq, int Lk, int d,
-                               void *O, hipStream_t st) {
-    return launch<true, true>(scores, meta, V, BH, Lq, Lk, d, O, st);
+hipError_t launch_softmax_spmm(const void *scores, const void *meta, const void *V, int BH, int Lq, int Lk, int LqR,
+                               int LkR, int d, void *O, hipStream_t st) {
+    return launch<true, true>(scores, meta, V, BH, Lq, Lk, LqR, LkR, d, O, st);
 }
 
-hipError_t launch_dense_av(const void *P, const void *V, int BH, int Lq, int Lk, int d, void *O, hipStream_t st) {
-    return launch<false>(P, nullptr, V, BH, Lq, Lk, d, O, st);
+hipError_t launch_dense_av(const void *P, const void *V, int BH, int Lq, int Lk, int LqR, int LkR, int d, void *O,
+                           hipStream_t st) {
+    return launch<false>(P, nullptr, V, BH, Lq, Lk, LqR, LkR, d, O, st);
 }
 
 }  // namespace dfss

@@ -58,8 +58,9 @@ def test_sizes_follow_the_compressed_footprint():
 
 
 @pytest.mark.parametrize("shape", [
-    Shape(1, 1, 100, 256, 64),       # Lq not a multiple of 64
-    Shape(1, 1, 128, 192, 64),       # Lk not a multiple of 128
+    Shape(1, 1, 100, 250, 64),       # Lk not a multiple of 4 (whole runs of M keys)
+    Shape(1, 1, 100, 256, 64, 1, 2, 2),  # lengths that are not tile multiples: 2-byte dtype only
+    Shape(1, 1, 128, 192, 64, 1, 2, 1),
     Shape(0, 1, 128, 128, 64),
     Shape(1, 1, 128, 128, 64, 3, 4),  # N:M not implemented
     Shape(1, 1, 128, 128, 96),       # head size not implemented
@@ -74,6 +75,20 @@ def test_invalid_shapes_have_zero_size(shape):
     assert dfss.dfss_workspace_bytes(shape) == 0
 
 
+def odd_early(aligned):
+    return ctypes.c_void_p(aligned.value + 2)
+
+
+def test_unpadded_lengths_take_the_layout_of_the_padded_ones():
+    """Stage calls on lengths that are not tile multiples (2-byte dtype): the compressed arrays are laid out for Lq
+    rounded up to a multiple of 64 and Lk to a multiple of 128."""
+    s, p = Shape(2, 3, 100, 260, 64), Shape(2, 3, 128, 384, 64)
+    for f in (dfss.dfss_vals_bytes, dfss.dfss_meta_bytes, dfss.dfss_workspace_bytes, dfss.dense_workspace_bytes):
+        assert f(s) == f(p) > 0
+    assert (s.LqP, s.LkP, s.Lc, s.meta_words) == (128, 384, 192, 24)
+    assert (p.LqP, p.LkP) == (128, 384)
+
+
 def test_errors_are_reported_before_any_launch():
     lib = dfss.load_library()
     ok = Shape(1, 1, 128, 128, 64).c()
@@ -83,8 +98,12 @@ def test_errors_are_reported_before_any_launch():
     E_NULL, E_SHAPE, E_UNSUP, E_WS = 1, 2, 3, 4
     assert lib.dfss_sddmm_prune(None, aligned, ctypes.byref(ok), 0.125, aligned, aligned, None) == E_NULL
     assert lib.dfss_sddmm_prune(aligned, aligned, None, 0.125, aligned, aligned, None) == E_NULL
-    bad = Shape(1, 1, 100, 128, 64).c()
+    bad = Shape(1, 1, 100, 130, 64).c()    # (Lq = 100 alone is fine: unpadded lengths; Lk must hold whole runs of 4)
     assert lib.dfss_sddmm_prune(aligned, aligned, ctypes.byref(bad), 0.125, aligned, aligned, None) == E_SHAPE
+    unp = Shape(1, 1, 100, 132, 64).c()    # unpadded lengths: the stage calls take them, with the same checks
+    assert lib.dfss_sddmm_prune(aligned, odd_early(aligned), ctypes.byref(unp), 0.125, aligned, aligned, None) == E_SHAPE
+    assert lib.dfss_sddmm_prune_causal(aligned, aligned, None, ctypes.byref(unp), 0.125, aligned, aligned, None) == E_UNSUP
+    assert lib.dfss_attention(aligned, aligned, aligned, ctypes.byref(unp), 0.125, aligned, None, 0, None) == E_SHAPE
     bad = Shape(1, 1, 128, 128, 64, 4, 8).c()
     assert lib.dfss_sddmm_prune(aligned, aligned, ctypes.byref(bad), 0.125, aligned, aligned, None) == E_UNSUP
     for scale in (0.0, -1.0, float("inf"), float("nan")):

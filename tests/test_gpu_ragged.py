@@ -193,3 +193,82 @@ def test_ragged_rejects_what_it_cannot_run():
         s = Shape(1, 1, 64, 64, 64, 1, 2, dfss.DFSS_F32)
         dfss.dfss_attention_ragged(_dev(Q.float()), _dev(K.float()), _dev(V.float()), None, s, 0.125)
     torch.cuda.synchronize()
+
+
+# ----------------------------------------------------------------------------------
+# the stage calls on unpadded lengths (2-byte dtype): the compressed arrays take the layout of the
+# padded lengths (Lq to a multiple of 64, Lk to one of 128); Q, K, V, key_bias and O are the caller's
+# ----------------------------------------------------------------------------------
+def _meta_canonical(meta, s):
+    return dfss.dfss_meta_to_canonical(meta, s).cpu().numpy().view(np.uint16).reshape(s.BH, s.LqP, s.meta_words)
+
+
+@pytest.mark.parametrize("B,H,Lq,Lk,d,N,M,scale", [
+    (1, 2, 100, 132, 64, 2, 4, 0.125),       # one partial row tile, a partial second key block
+    (2, 2, 250, 1000, 64, 1, 2, 0.11),       # Lq_P % 128 == 0, scale applied to the scores
+    (1, 3, 200, 516, 128, 2, 4, 0.0884),     # d = 128; Lq_P = 256 with rows 200..255 absent; 4 real keys in the last block
+    (1, 1, 4000, 4000, 64, 2, 4, 0.125),     # the long-sequence length of Sec. 5.1
+    (1, 2, 70, 128, 64, 2, 4, 0.125),        # Lk a tile multiple, Lq not: the upper half of the workgroup stores nothing
+])
+def test_stage_calls_on_unpadded_lengths(B, H, Lq, Lk, d, N, M, scale):
+    s = Shape(B, H, Lq, Lk, d, N, M)
+    assert (s.LqP, s.LkP) != (Lq, Lk)
+    bias = torch.zeros((B, Lk), dtype=torch.float32)
+    bias[0, Lk // 2:Lk // 2 + 37] = float("-inf")
+    bias[-1, 5:Lk:7] = -0.75
+    # stage 1 on integer inputs: kept values and positions of the real rows bit for bit; absent keys count as -inf
+    if Lq <= 250:
+        Q, K, _ = synth.integer_qkv(B * H, Lq, Lk, d, seed=8700 + Lq + Lk)
+        Qn, Kn = synth.to_numpy_f32(Q), synth.to_numpy_f32(K)
+        for kb in (None, bias):
+            vals, meta = dfss.dfss_sddmm_prune_bias(_dev(Q), _dev(K), None if kb is None else _dev(kb), s, scale)
+            torch.cuda.synchronize()
+            assert tuple(vals.shape) == (s.BH, s.LqP, s.Lc)
+            v, mc = vals.float().cpu().numpy(), _meta_canonical(meta, s)
+            for h in range(s.BH):
+                S = oracle.scores(Qn[h], Kn[h], scale)
+                if kb is not None:
+                    S = oracle.add_key_bias(S, kb[h // H].numpy())
+                Sp = np.full((Lq, s.LkP), -np.inf, dtype=np.float32)
+                Sp[:, :Lk] = S
+                _, vref, kidx = oracle.prune(Sp, N, M)
+                assert np.array_equal(mc[h, :Lq], oracle.encode_meta(kidx, s.LkP)), f"metadata differs in head {h}"
+                assert np.array_equal(v[h, :Lq], oracle.round_bf16(vref)), f"kept scores differ in head {h}"
+    # the whole path on Gaussian inputs: the three stage calls, the staged call, the three-kernel baseline
+    Q, K, V = synth.gaussian_qkv(B * H, Lq, Lk, d, 1.0, seed=8701 + Lq + Lk)
+    Qd, Kd, Vd = _dev(Q), _dev(K), _dev(V)
+    Qn, Kn, Vn = (synth.to_numpy_f32(t) for t in (Q, K, V))
+    gscale = 1.0 / math.sqrt(d) if scale != 0.125 else 0.125
+    for kb in (None, bias):
+        kw = {} if kb is None else dict(key_bias=kb.numpy(), heads_per_batch=H)
+        kbd = None if kb is None else _dev(kb)
+        ref = oracle.attention(Qn, Kn, Vn, N, M, gscale, **kw)
+        refd = oracle.attention(Qn, Kn, Vn, 1, 1, gscale, **kw)
+        vals, meta = dfss.dfss_sddmm_prune_bias(Qd, Kd, kbd, s, gscale)
+        dfss.dfss_sparse_softmax(vals, s)
+        buf, O3 = _guarded_out(s)
+        dfss.dfss_spmm(vals, meta, Vd, s, O=O3)
+        bufs, Os = _guarded_out(s)
+        dfss.dfss_attention_staged_bias(Qd, Kd, Vd, kbd, s, gscale, O=Os)
+        bufd, Od = _guarded_out(s)
+        dfss.dense_attention_bias(Qd, Kd, Vd, kbd, s, gscale, O=Od)
+        Of = dfss.dfss_attention_ragged(Qd, Kd, Vd, kbd, s, gscale)
+        torch.cuda.synchronize()
+        for name, b_, o_, r_ in (("three stages", buf, O3, ref), ("staged", bufs, Os, ref), ("dense", bufd, Od, refd)):
+            assert bool((b_[o_.numel():] == 777.0).all()), f"{name}: wrote behind O"
+            got = _np(o_)
+            assert np.isfinite(got).all(), name
+            assert np.abs(got - r_).max() <= 2e-2, name
+        assert np.abs(_np(Os) - _np(Of)).max() <= 2e-2     # the one-kernel call on the same lengths
+
+
+def test_unpadded_stage_calls_refuse_what_they_cannot_run():
+    Q, K, V, _ = _inputs(1, 100, 132, 64, DFSS_BF16, 8800)
+    s = Shape(1, 1, 100, 132, 64, 2, 4)
+    with pytest.raises(dfss.DfssError):      # the causal mask is defined on tile multiples only
+        dfss.dfss_sddmm_prune_causal(_dev(Q), _dev(K), None, s, 0.125)
+    with pytest.raises(dfss.DfssError):      # the one-kernel call for these lengths is dfss_attention_ragged
+        dfss.dfss_attention(_dev(Q), _dev(K), _dev(V), s, 0.125)
+    sf = Shape(1, 1, 100, 132, 64, 1, 2, DFSS_F32_BF16X3)
+    assert dfss.dfss_vals_bytes(sf) == 0     # 4-byte dtypes: tile multiples only
+    torch.cuda.synchronize()
