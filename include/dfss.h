@@ -243,9 +243,9 @@ dfss_status dense_attention_fused_blocked_split(const void *Q, const void *K, co
 
 /* ---- lengths that are not tile multiples ------------------------------------------------ */
 /* The stage calls, bfloat16 data.  dfss_sddmm_prune(_bias), dfss_sparse_softmax, dfss_spmm,
- * dfss_attention_staged(_bias), dfss_attention_staged_static, dense_attention(_bias), the size
- * functions and the metadata conversions take ANY Lq >= 1 and any Lk <= 8192 that is a multiple of 4
- * (whole runs of M keys).  Q and O are [B*H, Lq, d], K and V [B*H, Lk, d], key_bias [B, Lk], as
+ * dfss_attention_staged(_bias), dfss_attention_staged_static, dense_attention(_bias), dfss_spmm_t,
+ * dfss_attention_backward, the size functions and the metadata conversions take ANY Lq >= 1 and any
+ * Lk <= 8192 that is a multiple of 4 (whole runs of M keys).  Q and O are [B*H, Lq, d], K and V [B*H, Lk, d], key_bias [B, Lk], as
  * always; only the arrays the library defines -- vals, meta (both word orders), the workspaces --
  * are laid out for the PADDED lengths LqP = Lq rounded up to a multiple of 64 and LkP = Lk rounded up
  * to a multiple of 128: vals [B*H, LqP, LkP*N/M], canonical meta [B*H, LqP, LkP/16]
@@ -254,8 +254,11 @@ dfss_status dense_attention_fused_blocked_split(const void *Q, const void *K, co
  * comparison (as under a key bias of -inf), so a run of M keys that is entirely absent emits N
  * entries of weight exactly 0.  The rows Lq .. LqP-1 of vals and meta hold valid but meaningless
  * entries, and no such row of O is written; nothing is read or written past the caller's arrays.
- * The causal calls, the block-pattern calls and the backward pass take tile multiples only
- * (DFSS_ERR_UNSUPPORTED / DFSS_ERR_SHAPE otherwise), and so do the 4-byte dtypes.
+ * The backward calls take P, meta (and dS in the workspace) in the same padded layout, whatever the
+ * rows past Lq hold: those rows take no part in dK and dV, the absent keys (weight 0) none in dQ,
+ * and dQ [B*H, Lq, d], dK, dV [B*H, Lk, d] are written for the real rows only.
+ * The causal calls and the block-pattern calls take tile multiples only (DFSS_ERR_UNSUPPORTED /
+ * DFSS_ERR_SHAPE otherwise), and so do the 4-byte dtypes.
  *
  * The one-kernel calls: */
 /* The paper's long-sequence tasks have lengths such as 4000 (Sec. 5.1, the retrieval task).  These two

@@ -496,13 +496,13 @@ dfss_status dfss_spmm_t(const void *vals, const void *meta, const void *X, const
                         void *stream) {
     Dims D;
     if (!vals || !meta || !X || !out) return DFSS_ERR_NULL;
-    if (dfss_status st = check_shape(s, true, &D)) return st;
+    if (dfss_status st = check_shape_stage(s, true, &D)) return st;
     if (misaligned(vals) || misaligned(meta) || misaligned(X) || misaligned(out)) return DFSS_ERR_SHAPE;
     if (D.f32) {
         if (!D.split) return DFSS_ERR_UNSUPPORTED;
         return hip_status(dfss::launch_spmm_t_split(vals, meta, X, D.BH, D.Lq, D.Lk, D.d, out, (hipStream_t)stream));
     }
-    return hip_status(dfss::launch_spmm_t(vals, meta, X, D.BH, D.Lq, D.Lk, D.d, out, (hipStream_t)stream));
+    return hip_status(dfss::launch_spmm_t(vals, meta, X, D.BH, D.Lq, D.Lk, D.LqR, D.LkR, D.d, out, (hipStream_t)stream));
 }
 
 dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K, const void *V, const void *O,
@@ -510,7 +510,7 @@ dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K
                                     void *dK, void *dV, void *ws, size_t ws_bytes, void *stream) {
     Dims D;
     if (!dO || !Q || !K || !V || !O || !P || !meta || !dQ || !dK || !dV || !ws) return DFSS_ERR_NULL;
-    if (dfss_status st = check_shape(s, true, &D)) return st;
+    if (dfss_status st = check_shape_stage(s, true, &D)) return st;
     if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
     if (misaligned(dO) || misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(P) ||
         misaligned(meta) || misaligned(dQ) || misaligned(dK) || misaligned(dV))
@@ -529,13 +529,14 @@ dfss_status dfss_attention_backward(const void *dO, const void *Q, const void *K
     }
     hipError_t e;
     if (D.d == 64) {   // dS' and dQ = dS' K in one pass over the compressed rows
-        e = dfss::launch_masked_sddmm_ds(dO, V, O, P, meta, K, D.BH, D.Lq, D.Lk, D.d, scale, dS, dQ, st);
+        e = dfss::launch_masked_sddmm_ds(dO, V, O, P, meta, K, D.BH, D.Lq, D.Lk, D.LqR, D.LkR, D.d, scale, dS, dQ, st);
     } else {
-        e = dfss::launch_masked_sddmm_ds(dO, V, O, P, meta, nullptr, D.BH, D.Lq, D.Lk, D.d, scale, dS, nullptr, st);
-        if (e == hipSuccess) e = dfss::launch_spmm(dS, meta, K, D.BH, D.Lq, D.Lk, D.Lq, D.Lk, D.d, dQ, st);   // dQ = dS' K
+        e = dfss::launch_masked_sddmm_ds(dO, V, O, P, meta, nullptr, D.BH, D.Lq, D.Lk, D.LqR, D.LkR, D.d, scale, dS,
+                                         nullptr, st);
+        if (e == hipSuccess) e = dfss::launch_spmm(dS, meta, K, D.BH, D.Lq, D.Lk, D.LqR, D.LkR, D.d, dQ, st);   // dQ = dS' K
     }
-    if (e == hipSuccess) e = dfss::launch_spmm_t(P, meta, dO, D.BH, D.Lq, D.Lk, D.d, dV, st);    // dV = P^T dO
-    if (e == hipSuccess) e = dfss::launch_spmm_t(dS, meta, Q, D.BH, D.Lq, D.Lk, D.d, dK, st);    // dK = dS'^T Q
+    if (e == hipSuccess) e = dfss::launch_spmm_t(P, meta, dO, D.BH, D.Lq, D.Lk, D.LqR, D.LkR, D.d, dV, st);    // dV = P^T dO
+    if (e == hipSuccess) e = dfss::launch_spmm_t(dS, meta, Q, D.BH, D.Lq, D.Lk, D.LqR, D.LkR, D.d, dK, st);    // dK = dS'^T Q
     return hip_status(e);
 }
 

@@ -34,9 +34,12 @@ constexpr int KB = 128;   // keys per block
 // One workgroup owns 128 keys of one head (wave w: keys 32 w .. 32 w + 31, all D columns) and walks
 // over the queries 64 at a time.
 // ------------------------------------------------------------------------------------------------
-template <int D>
+// UNP: X holds LqR <= Lq rows per head and out LkR <= Lk rows, while A and meta have the layout of the padded lengths
+// Lq (a multiple of 64) and Lk (of 128).  The rows LqR .. Lq - 1 of A hold meaningless entries: they are expanded to
+// zeros; the places of the absent rows of a partial last X tile take its last real row; keys past LkR are not stored.
+template <int D, bool UNP>
 __global__ __launch_bounds__(NT, 2) void k_spmm_t(const uint32_t *__restrict__ A, const uint32_t *__restrict__ meta,
-                                                  const __bf16 *__restrict__ X, int Lq, int Lk,
+                                                  const __bf16 *__restrict__ X, int Lq, int Lk, int LqR, int LkR,
                                                   uint16_t *__restrict__ out) {
     constexpr int QB = 64;              // queries per step
     constexpr int CPR = D / 8;          // 16-byte chunks per X row
@@ -57,7 +60,7 @@ __global__ __launch_bounds__(NT, 2) void k_spmm_t(const uint32_t *__restrict__ A
     const int nq = Lq / QB;
 
     // X tile in LDS: row = query, chunk c at row * CPR + (c ^ ((row & 3) << 1))
-    const __bf16 *Xh = X + (size_t)bh * Lq * D;
+    const __bf16 *Xh = X + (size_t)bh * LqR * D;
     int src_off[LPT];
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
@@ -68,6 +71,16 @@ __global__ __launch_bounds__(NT, 2) void k_spmm_t(const uint32_t *__restrict__ A
     const uint32_t lds_x = lds_address(&Xs[0][w * 64]);
     auto issue_x = [&](int qb, int buf) {
         const __bf16 *src = Xh + (size_t)qb * QB * D;
+        const int real = LqR - qb * QB;   // real rows from this tile's first one on
+        if (UNP && real < QB) {
+#pragma unroll
+            for (int i = 0; i < LPT; ++i) {
+                const int p = i * NT + tid;
+                const int row = p / CPR, c = (p % CPR) ^ ((row & 3) << 1);
+                async_copy16(src, 2u * ((row < real ? row : real - 1) * D + c * 8), lds_x + 16u * (buf * XT + i * NT));
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < LPT; ++i) async_copy16(src, 2u * src_off[i], lds_x + 16u * (buf * XT + i * NT));
     };
@@ -88,8 +101,13 @@ __global__ __launch_bounds__(NT, 2) void k_spmm_t(const uint32_t *__restrict__ A
         r.word = meta[((((size_t)bh * (Lq / 16) + (q >> 4)) * kblocks + jblk) * 16 + (q & 15)) * 4 + meta_slot];
         return r;
     };
-    auto expand_a = [&](const ARaw &r, int buf) {
+    auto expand_a = [&](const ARaw &r, int buf, int qb) {
         u32x4 *dst = reinterpret_cast<u32x4 *>(&Ad[buf][aq * AROW + ac * 64]);
+        if (UNP && qb * QB + aq >= LqR) {   // a row past the end: it takes no part in the sums
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dst[i] = u32x4{0u, 0u, 0u, 0u};
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {       // 8 keys = 2 groups per 16 bytes
             u32x4 o;
@@ -126,7 +144,7 @@ __global__ __launch_bounds__(NT, 2) void k_spmm_t(const uint32_t *__restrict__ A
     // the X tile one step ahead into the other LDS buffer.
     auto step = [&](int qb, ARaw &r) {
         const int buf = qb & 1;
-        expand_a(r, buf);
+        expand_a(r, buf, qb);
         // X(qb) must have landed; the three loads of A(qb + 1), issued after its copy, may stay in flight
         if (qb >= 1 && qb + 1 < nq) wait_async_copies_keep<3>();
         else wait_async_copies();
@@ -175,7 +193,9 @@ __global__ __launch_bounds__(NT, 2) void k_spmm_t(const uint32_t *__restrict__ A
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const size_t key = (size_t)bh * Lk + (size_t)jblk * KB + 32 * w + 16 * mt + 4 * g + r;
+            const int krow = jblk * KB + 32 * w + 16 * mt + 4 * g + r;
+            if (UNP && krow >= LkR) continue;
+            const size_t key = (size_t)bh * LkR + krow;
 #pragma unroll
             for (int nt = 0; nt < DS; ++nt)
                 out[key * D + 16 * nt + li] = (uint16_t)(pack_bf16x2(acc[mt][nt][r], 0.f) & 0xFFFFu);
@@ -194,13 +214,17 @@ __global__ __launch_bounds__(NT, 2) void k_spmm_t(const uint32_t *__restrict__ A
 // structured-sparse matrix instruction for its query, and the stored position codes its index operand, exactly as
 // in the forward SpMM), so dS' is not read back for it.  Needs the whole key range in one workgroup (ksplit = 1) and
 // a second LDS tile per block (K in row order for the transposing read): d = 64 only.
-template <int D, int NQ, bool DQ>
+// UNP: dO, O, dQ hold LqR <= Lq rows per head and V, K LkR <= Lk keys, while P, meta and dS have the layout of the
+// padded lengths.  Rows past LqR are computed on a copy of the last row (their dS' is meaningless and the transposed
+// products skip it), the places of absent keys in a partial last block take the block's last key (their weights are
+// 0, so their dS' is 0), and rows of dQ past LqR are not stored.
+template <int D, int NQ, bool DQ, bool UNP>
 __global__ __launch_bounds__(NT, 2) void k_masked_sddmm_ds(const __bf16 *__restrict__ dO, const __bf16 *__restrict__ V,
                                                            const __bf16 *__restrict__ O,
                                                            const uint32_t *__restrict__ P,
                                                            const uint32_t *__restrict__ meta,
-                                                           const __bf16 *__restrict__ K, int Lq, int Lk,
-                                                           float scale, int ksplit, int blocks_per_wg,
+                                                           const __bf16 *__restrict__ K, int Lq, int Lk, int LqR,
+                                                           int LkR, float scale, int ksplit, int blocks_per_wg,
                                                            uint32_t *__restrict__ dS, uint16_t *__restrict__ dQ) {
     constexpr int CPR = D / 8;           // 16-byte chunks per row
     constexpr int TILE = KB * CPR;       // chunks per V block
@@ -226,7 +250,7 @@ __global__ __launch_bounds__(NT, 2) void k_masked_sddmm_ds(const __bf16 *__restr
     // LDS position p (16-byte units) = slot * CPR + (c ^ (slot & 7)) holds chunk c of the key stored in row
     // slot `slot`; slot 16 t' + i (MFMA tile t', row i) holds key 32 (i/4) + 4 t' + i%4 ... in the order that
     // gives a lane 16 consecutive keys per half
-    const __bf16 *Vh = V + (size_t)bh * Lk * D;
+    const __bf16 *Vh = V + (size_t)bh * LkR * D;
     int src_off[LPT];
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
@@ -244,9 +268,29 @@ __global__ __launch_bounds__(NT, 2) void k_masked_sddmm_ds(const __bf16 *__restr
         k_off[i] = row * D + c * 8;
     }
     const uint32_t lds_k = lds_address(&Kr[0][DQ ? w * 64 : 0]);
-    const __bf16 *Kh = DQ ? K + (size_t)bh * Lk * D : nullptr;
+    const __bf16 *Kh = DQ ? K + (size_t)bh * LkR * D : nullptr;
     auto issue_block = [&](int jb, int buf) {
         const __bf16 *src = Vh + (size_t)jb * KB * D;
+        const int real = LkR - jb * KB;   // real keys from this block's first one on
+        if (UNP && real < KB) {
+#pragma unroll
+            for (int i = 0; i < LPT; ++i) {
+                const int p = i * NT + tid;
+                const int slot = p / CPR, c = (p % CPR) ^ (slot & 7);
+                const int key = (slot & 3) | (((slot >> 4) & 7) << 2) | (((slot >> 2) & 3) << 5);
+                async_copy16(src, 2u * ((key < real ? key : real - 1) * D + c * 8), lds_v + 16u * (buf * TILE + i * NT));
+            }
+            if constexpr (DQ) {
+                const __bf16 *ksrc = Kh + (size_t)jb * KB * D;
+#pragma unroll
+                for (int i = 0; i < LPT; ++i) {
+                    const int p = i * NT + tid;
+                    const int row = p / CPR, c = (p % CPR) ^ ((row & 3) << 1);
+                    async_copy16(ksrc, 2u * ((row < real ? row : real - 1) * D + c * 8), lds_k + 16u * (buf * TILE + i * NT));
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < LPT; ++i) async_copy16(src, 2u * src_off[i], lds_v + 16u * (buf * TILE + i * NT));
         if constexpr (DQ) {
@@ -267,7 +311,8 @@ __global__ __launch_bounds__(NT, 2) void k_masked_sddmm_ds(const __bf16 *__restr
         float part = 0.f;
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
-            const size_t off = ((size_t)bh * Lq + q0 + 16 * qs + li) * D + 32 * s + 8 * kb;
+            const int qrow = UNP && q0 + 16 * qs + li >= LqR ? LqR - 1 : q0 + 16 * qs + li;
+            const size_t off = ((size_t)bh * LqR + qrow) * D + 32 * s + 8 * kb;
             const u32x4 g = *reinterpret_cast<const u32x4 *>(dO + off);
             const u32x4 o = *reinterpret_cast<const u32x4 *>(O + off);
             bq[qs][s] = __builtin_bit_cast(bf16x8, g);
@@ -394,7 +439,9 @@ __global__ __launch_bounds__(NT, 2) void k_masked_sddmm_ds(const __bf16 *__restr
         for (int qs = 0; qs < NQ; ++qs)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const size_t q = (size_t)bh * Lq + q0 + 16 * qs + 4 * kb + r;
+                const int qrow = q0 + 16 * qs + 4 * kb + r;
+                if (UNP && qrow >= LqR) continue;
+                const size_t q = (size_t)bh * LqR + qrow;
 #pragma unroll
                 for (int ds = 0; ds < DS; ++ds)
                     dQ[q * D + 16 * ds + li] = (uint16_t)(pack_bf16x2(acc_dq[qs][ds][r], 0.f) & 0xFFFFu);
@@ -404,15 +451,19 @@ __global__ __launch_bounds__(NT, 2) void k_masked_sddmm_ds(const __bf16 *__restr
 
 }  // namespace
 
-hipError_t launch_spmm_t(const void *vals, const void *meta, const void *X, int BH, int Lq, int Lk, int d, void *out,
-                         hipStream_t st) {
+hipError_t launch_spmm_t(const void *vals, const void *meta, const void *X, int BH, int Lq, int Lk, int LqR, int LkR,
+                         int d, void *out, hipStream_t st) {
     const unsigned grid = (unsigned)((long)BH * (Lk / KB));
-    if (d == 64)
-        hipLaunchKernelGGL((k_spmm_t<64>), dim3(grid), dim3(NT), 0, st, (const uint32_t *)vals, (const uint32_t *)meta,
-                           (const __bf16 *)X, Lq, Lk, (uint16_t *)out);
-    else
-        hipLaunchKernelGGL((k_spmm_t<128>), dim3(grid), dim3(NT), 0, st, (const uint32_t *)vals,
-                           (const uint32_t *)meta, (const __bf16 *)X, Lq, Lk, (uint16_t *)out);
+    const bool unp = LqR != Lq || LkR != Lk;
+#define DFSS_LAUNCH(DD, UU)                                                                                        \
+    hipLaunchKernelGGL((k_spmm_t<DD, UU>), dim3(grid), dim3(NT), 0, st, (const uint32_t *)vals, (const uint32_t *)meta, \
+                       (const __bf16 *)X, Lq, Lk, LqR, LkR, (uint16_t *)out)
+    if (d == 64) {
+        if (unp) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
+    } else {
+        if (unp) DFSS_LAUNCH(128, true); else DFSS_LAUNCH(128, false);
+    }
+#undef DFSS_LAUNCH
     return hipGetLastError();
 }
 
@@ -421,9 +472,10 @@ hipError_t launch_spmm_t(const void *vals, const void *meta, const void *X, int 
 namespace dfss {
 
 namespace {
-template <int NQ>
+template <int NQ, bool UNP>
 hipError_t launch_ds_nq(const void *dO, const void *V, const void *O, const void *P, const void *meta, const void *K,
-                        int BH, int Lq, int Lk, int d, float scale, void *dS, void *dQ, hipStream_t st) {
+                        int BH, int Lq, int Lk, int LqR, int LkR, int d, float scale, void *dS, void *dQ,
+                        hipStream_t st) {
     const int qtiles = Lq / (64 * NQ);
     const int kblocks = Lk / KB;
     const bool with_dq = dQ != nullptr;   // (d = 64: checked by the caller)
@@ -437,9 +489,9 @@ hipError_t launch_ds_nq(const void *dO, const void *V, const void *O, const void
     const int per_wg = kblocks / ksplit;
     const unsigned grid = (unsigned)((long)BH * qtiles * ksplit);
 #define DFSS_LAUNCH(DD, WITH)                                                                                      \
-    hipLaunchKernelGGL((k_masked_sddmm_ds<DD, NQ, WITH>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)dO,         \
+    hipLaunchKernelGGL((k_masked_sddmm_ds<DD, NQ, WITH, UNP>), dim3(grid), dim3(NT), 0, st, (const __bf16 *)dO,    \
                        (const __bf16 *)V, (const __bf16 *)O, (const uint32_t *)P, (const uint32_t *)meta,         \
-                       (const __bf16 *)K, Lq, Lk, scale, ksplit, per_wg, (uint32_t *)dS, (uint16_t *)dQ)
+                       (const __bf16 *)K, Lq, Lk, LqR, LkR, scale, ksplit, per_wg, (uint32_t *)dS, (uint16_t *)dQ)
     if (d == 64) {
         if (with_dq) DFSS_LAUNCH(64, true); else DFSS_LAUNCH(64, false);
     } else {
@@ -452,11 +504,16 @@ hipError_t launch_ds_nq(const void *dO, const void *V, const void *O, const void
 
 // K, dQ: both null, or (d = 64 only) the keys and the output of dQ = dS' K, formed in the same pass.
 hipError_t launch_masked_sddmm_ds(const void *dO, const void *V, const void *O, const void *P, const void *meta,
-                                  const void *K, int BH, int Lq, int Lk, int d, float scale, void *dS, void *dQ,
-                                  hipStream_t st) {
+                                  const void *K, int BH, int Lq, int Lk, int LqR, int LkR, int d, float scale, void *dS,
+                                  void *dQ, hipStream_t st) {
     if (dQ && d != 64) return hipErrorInvalidValue;
-    if (Lq % 128 == 0) return launch_ds_nq<2>(dO, V, O, P, meta, K, BH, Lq, Lk, d, scale, dS, dQ, st);
-    return launch_ds_nq<1>(dO, V, O, P, meta, K, BH, Lq, Lk, d, scale, dS, dQ, st);
+    if (LqR != Lq || LkR != Lk) {
+        if (Lq % 128 == 0)
+            return launch_ds_nq<2, true>(dO, V, O, P, meta, K, BH, Lq, Lk, LqR, LkR, d, scale, dS, dQ, st);
+        return launch_ds_nq<1, true>(dO, V, O, P, meta, K, BH, Lq, Lk, LqR, LkR, d, scale, dS, dQ, st);
+    }
+    if (Lq % 128 == 0) return launch_ds_nq<2, false>(dO, V, O, P, meta, K, BH, Lq, Lk, Lq, Lk, d, scale, dS, dQ, st);
+    return launch_ds_nq<1, false>(dO, V, O, P, meta, K, BH, Lq, Lk, Lq, Lk, d, scale, dS, dQ, st);
 }
 
 }  // namespace dfss

@@ -41,13 +41,13 @@ hipError_t launch_fused_attention_split_rows(const void *Q, const void *K, const
                                              float scale, void *O, void *part, hipStream_t st);
 // Transposed sparse product out[BH, Lk, d] = A^T X for compressed A (vals + metadata) and X bf16 [BH, Lq, d]:
 // dV = P^T dO and dK = dS^T Q of the backward pass.
-hipError_t launch_spmm_t(const void *vals, const void *meta, const void *X, int BH, int Lq, int Lk, int d, void *out,
-                         hipStream_t st);
+hipError_t launch_spmm_t(const void *vals, const void *meta, const void *X, int BH, int Lq, int Lk, int LqR, int LkR,
+                         int d, void *out, hipStream_t st);
 // dS' = scale * P .* (dO V^T - delta) at the kept positions (delta_q = dO_q . O_q), compressed like P.
 // K, dQ: both null, or (d = 64 only) the keys and the output of dQ = dS' K, formed in the same pass.
 hipError_t launch_masked_sddmm_ds(const void *dO, const void *V, const void *O, const void *P, const void *meta,
-                                  const void *K, int BH, int Lq, int Lk, int d, float scale, void *dS, void *dQ,
-                                  hipStream_t st);
+                                  const void *K, int BH, int Lq, int Lk, int LqR, int LkR, int d, float scale, void *dS,
+                                  void *dQ, hipStream_t st);
 // The 4-byte mode (Sec. 2.3: float data, 1:2): fp32 Q, K, V, kept scores, weights and O; metadata = one
 // 4-bit code per kept float, 32-bit words in the blocked order [BH, Lq/16, Lk/64, 16, 4].
 hipError_t launch_sddmm_prune_f32(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk,

@@ -126,3 +126,77 @@ def test_forward_stages_then_backward_on_exact_scores():
         for name, got, ref in (("dQ", _np(dQ[h]), rQ), ("dK", _np(dK[h]), rK), ("dV", _np(dV[h]), rV)):
             tol = 2.0 ** -7 * np.max(np.abs(ref)) + 1e-4
             assert np.max(np.abs(got - ref)) <= tol, (name, h)
+
+
+# ----------------------------------------------------------------------------------
+# lengths that are not tile multiples: P, meta and dS' keep the layout of the padded lengths
+# ----------------------------------------------------------------------------------
+def _padded_forward(Qn, Kn, N, M, scale, s):
+    """The oracle's forward results in the padded layout: absent keys count as -inf; the rows past Lq hold finite
+    junk (weights 0.25, codes 0x4) that no gradient may depend on."""
+    BH, Lq, Lk = Qn.shape[0], Qn.shape[1], Kn.shape[1]
+    kidx, P = [], []
+    Pp = np.full((BH, s.LqP, s.Lc), 0.25, dtype=np.float32)
+    mp = np.full((BH, s.LqP, s.meta_words), 0x4444, dtype=np.uint16)
+    for h in range(BH):
+        Sp = np.full((Lq, s.LkP), -np.inf, dtype=np.float32)
+        Sp[:, :Lk] = oracle.scores(Qn[h], Kn[h], scale)
+        _, vals, ki = oracle.prune(Sp, N, M)
+        Ph = oracle.round_bf16(oracle.softmax_kept(oracle.round_bf16(vals)))
+        Pp[h, :Lq] = Ph
+        mp[h, :Lq] = oracle.encode_meta(ki, s.LkP)
+        # for the oracle's backward pass: the kept entries that are real keys (the absent ones have weight 0)
+        kidx.append(ki)
+        P.append(Ph)
+    return kidx, P, Pp, mp
+
+
+@pytest.mark.parametrize("BH,Lq,Lk,d,N,M", [
+    (2, 100, 132, 64, 2, 4),       # fused dQ; one partial query tile, a partial second key block
+    (2, 250, 516, 64, 1, 2),       # 32 queries per wave in the dS kernel (LqP = 256), 4 real keys in the last block
+    (2, 70, 260, 128, 2, 4),       # d = 128: dQ through the forward product kernel
+])
+def test_backward_on_unpadded_lengths(BH, Lq, Lk, d, N, M):
+    scale = 1.0 / math.sqrt(d)
+    Q, K, V = synth.gaussian_qkv(BH, Lq, Lk, d, 1.0, seed=9700 + Lq + d)
+    g = torch.Generator().manual_seed(9701 + Lq)
+    dO = torch.randn(BH, Lq, d, generator=g).to(torch.bfloat16)
+    Qn, Kn, Vn, dOn = (synth.to_numpy_f32(t) for t in (Q, K, V, dO))
+    s = Shape(1, BH, Lq, Lk, d, N, M)
+    assert (s.LqP, s.LkP) != (Lq, Lk)
+    kidx, P, Pp, mp = _padded_forward(Qn, Kn, N, M, scale, s)
+    # O of the forward pass from the real keys only (weights of absent keys are 0; their indices point past Lk)
+    O = []
+    for h in range(BH):
+        Pd = np.zeros((Lq, s.LkP))
+        np.put_along_axis(Pd, kidx[h].astype(np.int64), P[h].astype(np.float64), axis=1)
+        O.append(oracle.round_bf16((Pd[:, :Lk] @ Vn[h].astype(np.float64)).astype(np.float32)))
+    O = np.stack(O)
+    meta = dfss.dfss_meta_from_canonical(_dev(torch.from_numpy(mp.view(np.int16))), s)
+    guard = 4096
+    bufs = [torch.full((n + guard,), 777.0, dtype=torch.bfloat16, device=DEV) for n in (BH * Lq * d, BH * Lk * d, BH * Lk * d)]
+    dQ, dK, dV = (b[:b.numel() - guard].view(BH, L, d) for b, L in zip(bufs, (Lq, Lk, Lk)))
+    dfss.dfss_attention_backward(_dev(dO), _dev(Q), _dev(K), _dev(V), _dev(_bf16(O)), _dev(_bf16(Pp)), meta, s, scale,
+                                 dQ=dQ, dK=dK, dV=dV)
+    X = torch.randn(BH, Lq, d, generator=g).to(torch.bfloat16)
+    T = dfss.dfss_spmm_t(_dev(_bf16(Pp)), meta, _dev(X), s)
+    torch.cuda.synchronize()
+    for b in bufs:
+        assert bool((b[b.numel() - guard:] == 777.0).all()), "wrote behind a gradient"
+    assert tuple(T.shape) == (BH, Lk, d)
+    dQ, dK, dV, T, Xn = _np(dQ), _np(dK), _np(dV), _np(T), synth.to_numpy_f32(X)
+    for h in range(BH):
+        real = kidx[h] < Lk                          # kept entries that are real keys
+        ki = np.where(real, kidx[h], 0)
+        Pr = np.where(real, P[h], 0.0).astype(np.float32)
+        assert np.all(P[h][~real] == 0.0)
+        rQ, rK, rV = oracle.attention_backward(Qn[h], Kn[h], Vn[h], dOn[h], Pr, ki.astype(np.int32), scale)
+        for name, got, ref in (("dQ", dQ[h], rQ), ("dK", dK[h], rK), ("dV", dV[h], rV)):
+            assert np.isfinite(got).all(), name
+            tol = 2.0 ** -7 * np.max(np.abs(ref)) + 1e-4
+            err = np.max(np.abs(got - ref))
+            assert err <= tol, (name, h, err, tol)
+        Pd = np.zeros((Lq, s.LkP))
+        np.put_along_axis(Pd, kidx[h].astype(np.int64), P[h].astype(np.float64), axis=1)
+        refT = Pd[:, :Lk].T @ Xn[h].astype(np.float64)
+        assert np.max(np.abs(T[h] - refT)) <= 2.0 ** -8 * np.max(np.abs(refT)) + 1e-4
