@@ -566,6 +566,10 @@ hipError_t launch_b(const void *Q, const void *K, const float *key_bias, int H, 
     if (Lq % 128 == 0)
         return launch32<MODE, BIAS, CAUSAL ? KMASK_CAUSAL : KMASK_NONE>(Q, K, key_bias, H, BH, Lq, Lk, Lq, Lk, d, scale, out,
                                                                          meta, st);
+    // Lq = 64 (mod 128): the same kernel with the upper half of the last workgroup idle (its waves store nothing; the
+    // mechanism of the unpadded lengths) is faster than 16 queries per wave; the causal mask keeps the latter
+    if constexpr (!CAUSAL)
+        return launch32<MODE, BIAS, KMASK_UNPADDED>(Q, K, key_bias, H, BH, Lq, Lk, Lq, Lk, d, scale, out, meta, st);
     return launch_nq<MODE, 1, BIAS, CAUSAL>(Q, K, key_bias, H, BH, Lq, Lk, d, scale, out, meta, st);
 }
 
