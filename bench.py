@@ -495,6 +495,16 @@ def main():
             "dense_attention_fused_ragged_ms_per_step": round(t_rd, 5),
             "padded_and_masked_dfss_attention_bias_ms_per_step": round(t_p, 5),
             "algorithmic_tflops": round(3.0 * BH * Lr * Lr * d / (t_r * 1e-3) / 1e12, 2)}
+        if not f32:   # the stage calls take the same lengths (2-byte data)
+            wsr = torch.empty(max(dfss.dfss_workspace_bytes(sr), dfss.dense_workspace_bytes(sr)), dtype=torch.uint8,
+                              device=dev)
+            t_s = timer(lambda i: dfss.dfss_attention_staged(Qr, Kr, Vr, sr, w.scale, O=Or, ws=wsr))[0]
+            t_d3 = timer(lambda i: dfss.dense_attention(Qr, Kr, Vr, sr, w.scale, O=Or, ws=wsr))[0]
+            t_sp = timer(lambda i: dfss.dfss_attention_staged(b["Q"], b["K"], b["V"], s, w.scale, O=b["O"], ws=ctx["wss"][0]))[0]
+            out["extra"]["unpadded"].update({
+                "dfss_attention_staged_ms_per_step": round(t_s, 5),
+                "dense_attention_3stage_ms_per_step": round(t_d3, 5),
+                "dfss_attention_staged_at_the_padded_length_ms_per_step": round(t_sp, 5)})
 
     if not args.no_cpu_baseline:
         import oracle
