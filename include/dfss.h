@@ -202,6 +202,30 @@ dfss_status dense_attention_causal(const void *Q, const void *K, const void *V, 
 dfss_status dense_attention_fused_causal(const void *Q, const void *K, const void *V, const void *key_bias,
                                          const dfss_shape *s, float scale, void *O, void *stream);
 
+/* ---- general additive mask (stage calls) ------------------------------------------------ */
+/* mask: device, float32 [Lq, Lk] row-major, 16-byte aligned, shared by all B*H heads (relative
+ * position terms, arbitrary visibility patterns; -inf hides a key from a query).  mask[i][j] is ADDED
+ * to the scaled score of query i and key j in fp32 BEFORE the N:M comparison of stage 1 -- the reading
+ * of the key bias and of the causal mask, which are its special cases (a mask of 0 / -inf along the
+ * diagonal gives the causal calls' results bit for bit); a run of M keys that is entirely hidden from
+ * a query still emits N entries of weight exactly 0.  Precondition: every query sees at least one
+ * key.  Arithmetic and rounding: those of the key bias.  2-byte dtype only (DFSS_ERR_UNSUPPORTED
+ * otherwise); lengths as in the stage calls (tile multiples, or any Lq and Lk % 4 == 0 with the
+ * compressed arrays in the padded layout).  No block is skipped and the mask costs 4 bytes of reads
+ * per score: where a mask is causal or a padding mask, the dedicated calls are the fast ones.
+ *   dfss_sddmm_prune_mask        stage 1 (stages 2 and 3 are the plain calls)
+ *   dfss_attention_staged_mask   the forward pass through the workspace (as dfss_attention_staged)
+ *   dense_attention_mask         Eq. 1 with the same mask, three kernels (the baseline)
+ * All other arguments, layouts and error behaviour are those of the calls without the suffix. */
+dfss_status dfss_sddmm_prune_mask(const void *Q, const void *K, const void *mask, const dfss_shape *s,
+                                  float scale, void *vals, void *meta, void *stream);
+dfss_status dfss_attention_staged_mask(const void *Q, const void *K, const void *V, const void *mask,
+                                       const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes,
+                                       void *stream);
+dfss_status dense_attention_mask(const void *Q, const void *K, const void *V, const void *mask,
+                                 const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes,
+                                 void *stream);
+
 /* ---- hybrid block sparsity x N:M (App. A.1.2, "Blocked-ELL Sparsity") ---------------- */
 /* block_mask: device, uint8 [Lq/64, Lk/64] row-major, shared by all B*H heads.  A 64 x 64 block
  * of the score matrix whose entry is zero is not part of the attention: it is skipped (neither

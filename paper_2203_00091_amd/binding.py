@@ -29,6 +29,7 @@ EXPORTS = (
     "dfss_sddmm_prune_causal", "dfss_attention_causal", "dfss_attention_staged_causal", "dense_attention_causal",
     "dense_attention_fused_causal",
     "dfss_blocked_split_workspace_bytes", "dfss_attention_blocked_split", "dense_attention_fused_blocked_split",
+    "dfss_sddmm_prune_mask", "dfss_attention_staged_mask", "dense_attention_mask",
 )
 # exported for the library's own tests only (csrc/dfss_internal.h)
 INTERNAL_EXPORTS = ("dfss_internal_attention_variant",)
@@ -129,6 +130,9 @@ def load_library():
         L.dense_attention_fused_blocked.argtypes = [vp, vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_attention_blocked_split.argtypes = [vp, vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
         L.dense_attention_fused_blocked_split.argtypes = [vp, vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
+        L.dfss_sddmm_prune_mask.argtypes = [vp, vp, vp, sp, f32, vp, vp, vp]
+        L.dfss_attention_staged_mask.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
+        L.dense_attention_mask.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
         L.dfss_attention_ragged.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_attention_staged.argtypes = [vp, vp, vp, sp, f32, vp, vp, sz, vp]
         L.dfss_attention_staged_bias.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
@@ -155,7 +159,8 @@ def load_library():
                      "dfss_attention_backward", "dfss_attention_staged", "dfss_attention_staged_bias",
                      "dfss_internal_attention_variant", "dfss_sddmm_prune_causal", "dfss_attention_causal",
                      "dfss_attention_staged_causal", "dense_attention_causal", "dense_attention_fused_causal",
-                     "dfss_attention_blocked_split", "dense_attention_fused_blocked_split"):
+                     "dfss_attention_blocked_split", "dense_attention_fused_blocked_split",
+                     "dfss_sddmm_prune_mask", "dfss_attention_staged_mask", "dense_attention_mask"):
             getattr(L, name).restype = ctypes.c_int
         L.dfss_status_string.argtypes = [ctypes.c_int]
         L.dfss_status_string.restype = ctypes.c_char_p
@@ -513,6 +518,49 @@ def dense_attention_fused_blocked(Q, K, V, key_bias, block_mask, s: Shape, scale
                                                       _block_mask_ptr(block_mask, s), ctypes.byref(s.c()), scale,
                                                       _q(O, s), _stream())
     _check("dense_attention_fused_blocked", st)
+    return O
+
+
+def _mask_ptr(mask: torch.Tensor, s: Shape) -> int:
+    if mask.dtype != torch.float32 or mask.numel() != s.Lq * s.Lk:
+        raise ValueError(f"the mask must be float32 [{s.Lq}, {s.Lk}]")
+    return _ptr(mask)
+
+
+def dfss_sddmm_prune_mask(Q, K, mask, s: Shape, scale: float, vals=None, meta=None):
+    """Stage 1 with an additive mask [Lq, Lk] shared by all heads."""
+    if vals is None:
+        vals = torch.empty((s.BH, s.LqP, s.Lc), dtype=s.torch_dtype, device=Q.device)
+    if meta is None:
+        meta = torch.empty((s.BH * s.LqP * s.meta_words,), dtype=torch.int16, device=Q.device)
+    st = load_library().dfss_sddmm_prune_mask(_q(Q, s), _kv(K, s), _mask_ptr(mask, s), ctypes.byref(s.c()), scale,
+                                              _kept(vals, s), _meta(meta, s), _stream())
+    _check("dfss_sddmm_prune_mask", st)
+    return vals, meta
+
+
+def dfss_attention_staged_mask(Q, K, V, mask, s: Shape, scale: float, O=None, ws=None):
+    """dfss_attention_staged with an additive mask [Lq, Lk] shared by all heads."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    if ws is None:
+        ws = _alloc_bytes(dfss_workspace_bytes(s), Q.device)
+    st = load_library().dfss_attention_staged_mask(_q(Q, s), _kv(K, s), _kv(V, s), _mask_ptr(mask, s),
+                                                   ctypes.byref(s.c()), scale, _q(O, s), _ptr(ws),
+                                                   ws.numel() * ws.element_size(), _stream())
+    _check("dfss_attention_staged_mask", st)
+    return O
+
+
+def dense_attention_mask(Q, K, V, mask, s: Shape, scale: float, O=None, ws=None):
+    """Full attention (three kernels) with the same mask."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    if ws is None:
+        ws = _alloc_bytes(dense_workspace_bytes(s), Q.device)
+    st = load_library().dense_attention_mask(_q(Q, s), _kv(K, s), _kv(V, s), _mask_ptr(mask, s), ctypes.byref(s.c()),
+                                             scale, _q(O, s), _ptr(ws), ws.numel() * ws.element_size(), _stream())
+    _check("dense_attention_mask", st)
     return O
 
 

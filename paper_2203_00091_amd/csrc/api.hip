@@ -466,6 +466,54 @@ dfss_status dense_attention_fused_blocked_split(const void *Q, const void *K, co
     return attention_blocked_split(Q, K, V, key_bias, block_mask, s, true, scale, O, ws, ws_bytes, stream);
 }
 
+// ---- additive mask [Lq, Lk] shared by all heads (stage calls, 2-byte dtype) ----
+// what: 0 = stage 1 only (out0 = vals, out1 = meta), 1 = the staged forward pass, 2 = the three-kernel dense baseline
+static dfss_status with_mask(int what, const void *Q, const void *K, const void *V, const void *mask, const dfss_shape *s,
+                             float scale, void *out0, void *out1, void *ws, size_t ws_bytes, void *stream) {
+    Dims D;
+    if (!Q || !K || !mask || !out0) return DFSS_ERR_NULL;
+    if (what == 0 ? !out1 : (!V || !ws)) return DFSS_ERR_NULL;
+    if (dfss_status st = check_shape_stage(s, what != 2, &D)) return st;
+    if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
+    if (D.f32) return DFSS_ERR_UNSUPPORTED;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(mask) || misaligned(out0) || misaligned(out1))
+        return DFSS_ERR_SHAPE;
+    hipStream_t st = (hipStream_t)stream;
+    const float *m = (const float *)mask;
+    if (what == 0)
+        return hip_status(dfss::launch_sddmm_prune_mask(Q, K, m, D.BH, D.Lq, D.Lk, D.LqR, D.LkR, D.d, D.mode, scale, out0,
+                                                        out1, st));
+    if ((reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0) return DFSS_ERR_SHAPE;
+    if (ws_bytes < (what == 1 ? dfss_workspace_bytes(s) : dense_workspace_bytes(s))) return DFSS_ERR_WORKSPACE;
+    if (what == 1) {
+        char *vals = static_cast<char *>(ws);
+        char *meta = vals + align_up(dfss_vals_bytes(s));
+        hipError_t e = dfss::launch_sddmm_prune_mask(Q, K, m, D.BH, D.Lq, D.Lk, D.LqR, D.LkR, D.d, D.mode, scale, vals, meta, st);
+        if (e == hipSuccess) e = dfss::launch_softmax_spmm(vals, meta, V, D.BH, D.Lq, D.Lk, D.LqR, D.LkR, D.d, out0, st);
+        return hip_status(e);
+    }
+    hipError_t e = dfss::launch_dense_scores_mask(Q, K, m, D.BH, D.Lq, D.Lk, D.LqR, D.LkR, D.d, scale, ws, st);
+    if (e == hipSuccess) e = dfss::launch_row_softmax(ws, (long)D.BH * D.Lq, D.Lk, st);
+    if (e == hipSuccess) e = dfss::launch_dense_av(ws, V, D.BH, D.Lq, D.Lk, D.LqR, D.LkR, D.d, out0, st);
+    return hip_status(e);
+}
+
+dfss_status dfss_sddmm_prune_mask(const void *Q, const void *K, const void *mask, const dfss_shape *s, float scale,
+                                  void *vals, void *meta, void *stream) {
+    return with_mask(0, Q, K, nullptr, mask, s, scale, vals, meta, nullptr, 0, stream);
+}
+
+dfss_status dfss_attention_staged_mask(const void *Q, const void *K, const void *V, const void *mask,
+                                       const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes,
+                                       void *stream) {
+    return with_mask(1, Q, K, V, mask, s, scale, O, nullptr, ws, ws_bytes, stream);
+}
+
+dfss_status dense_attention_mask(const void *Q, const void *K, const void *V, const void *mask, const dfss_shape *s,
+                                 float scale, void *O, void *ws, size_t ws_bytes, void *stream) {
+    return with_mask(2, Q, K, V, mask, s, scale, O, nullptr, ws, ws_bytes, stream);
+}
+
 // dense: full attention (N, M ignored)
 static dfss_status attention_ragged(const void *Q, const void *K, const void *V, const void *key_bias,
                                     const dfss_shape *s, bool dense, float scale, void *O, void *stream) {

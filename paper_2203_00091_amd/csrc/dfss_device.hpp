@@ -116,6 +116,15 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// product + c in two roundings, whatever the compiler's contraction rules: the (already rounded) product passes through
+// an empty assembly statement, so that it cannot be folded into a fused multiply-add with the addition (a plain
+// addition -- also __fadd_rn -- was seen fused in one instantiation and not in another).  The bias and mask additions
+// are specified with two roundings (they must give the oracle's kept values and positions bit for bit).
+__device__ __forceinline__ float add_unfused(float product, float c) {
+    asm("" : "+v"(product));
+    return product + c;
+}
+
 // N:M selection on the fp32 accumulators (arXiv 2203.00091, Sec. 2.3, App. A.1.1).  The comparisons of
 // a run of four scores are taken as 64-bit lane masks (one bit per lane of the wave) so that the
 // boolean logic runs on the scalar unit, off the vector ALU that the MFMA epilogue is short of; the

@@ -16,6 +16,12 @@ hipError_t launch_sddmm_prune(const void *Q, const void *K, const float *key_bia
 // Dense scores S = scale * Q K^T stored as bfloat16 [BH, Lq, Lk] (Eq. 1), same mainloop.
 hipError_t launch_dense_scores(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq, int Lk,
                                int LqR, int LkR, int d, float scale, void *S, hipStream_t st);
+// The same two with an additive mask fp32 [LqR][LkR] shared by all heads (added like the key bias; -inf hides a key
+// from a query) in the place of the per-key bias.
+hipError_t launch_sddmm_prune_mask(const void *Q, const void *K, const float *mask, int BH, int Lq, int Lk, int LqR,
+                                   int LkR, int d, int mode, float scale, void *vals, void *meta, hipStream_t st);
+hipError_t launch_dense_scores_mask(const void *Q, const void *K, const float *mask, int BH, int Lq, int Lk, int LqR,
+                                    int LkR, int d, float scale, void *S, hipStream_t st);
 // Row softmax in place over bfloat16 rows (App. A.1.3); rows of `cols` elements.
 hipError_t launch_row_softmax(void *x, long rows, int cols, hipStream_t st);
 // Stage 3 (Sec. 3.1): O = A_sparse V from compressed weights + metadata.

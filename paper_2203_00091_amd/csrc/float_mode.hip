@@ -144,7 +144,7 @@ __global__ __launch_bounds__(NT, 2) void k_scores_f32(const float *__restrict__ 
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     float s0 = acc[t][2 * h] * scale, s1 = acc[t][2 * h + 1] * scale;
-                    if constexpr (BIAS) s0 = __fadd_rn(s0, b4[t][2 * h]), s1 = __fadd_rn(s1, b4[t][2 * h + 1]);
+                    if constexpr (BIAS) s0 = add_unfused(s0, b4[t][2 * h]), s1 = add_unfused(s1, b4[t][2 * h + 1]);
                     const bool second = s1 > s0;
                     const int p = 2 * t + h;
                     kept[p >> 2][p & 3] = second ? s1 : s0;
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(NT, 2) void k_scores_f32(const float *__restrict__ 
                 f32x4 v = acc[t] * scale;
                 if constexpr (BIAS) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = __fadd_rn(v[e], b4[t][e]);
+                    for (int e = 0; e < 4; ++e) v[e] = add_unfused(v[e], b4[t][e]);
                 }
                 sp[t] = v;
             }

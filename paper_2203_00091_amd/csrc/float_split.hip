@@ -45,7 +45,7 @@ __device__ __forceinline__ bf16x8 as_bf16x8(const u32x4 &v) { return __builtin_b
 template <bool BIAS>
 __device__ __forceinline__ float scaled_score(float dot, float scale, float bias) {
     const float s = __fmul_rn(dot, scale);
-    return BIAS ? __fadd_rn(s, bias) : s;
+    return BIAS ? add_unfused(s, bias) : s;
 }
 
 // acc += a . b with a = ah + al, b = bh + bl (small terms first)

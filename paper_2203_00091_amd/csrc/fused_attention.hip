@@ -367,7 +367,7 @@ __global__ __launch_bounds__(NT * G, 2) void k_fused(const __bf16 *__restrict__ 
 #pragma unroll
                     for (int t = 0; t < 4; ++t)
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) acc[qs][t][r] = __fadd_rn(acc[qs][t][r] * scale, kb4[t][r]);
+                        for (int r = 0; r < 4; ++r) acc[qs][t][r] = add_unfused(acc[qs][t][r] * scale, kb4[t][r]);
             }
         } else {
             scores(std::false_type{});

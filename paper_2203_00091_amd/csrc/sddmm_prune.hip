@@ -186,7 +186,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
                             a = a * scale;
                             if constexpr (BIAS) {
 #pragma unroll
-                                for (int r = 0; r < 4; ++r) a[r] = __fadd_rn(a[r], kb4[t][r]);
+                                for (int r = 0; r < 4; ++r) a[r] = add_unfused(a[r], kb4[t][r]);
                             }
                         }
                         p[2 * t] = pack_bf16x2(a[0], a[1]);
@@ -204,7 +204,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
                             a = a * scale;
                             if constexpr (BIAS) {
 #pragma unroll
-                                for (int r = 0; r < 4; ++r) a[r] = __fadd_rn(a[r], kb4[t][r]);
+                                for (int r = 0; r < 4; ++r) a[r] = add_unfused(a[r], kb4[t][r]);
                             }
                         }
                         float lo, hi;
@@ -255,7 +255,10 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // places in a partial last block are filled with the block's last real key, and rows past LqR are computed on a copy
 // of the last query (never read past the arrays).  Waves whose 32 rows lie past Lq store nothing.
 enum { KMASK_NONE = 0, KMASK_CAUSAL = 1, KMASK_UNPADDED = 2 };
-template <int D, int MODE, bool PRESCALE, bool BIAS, int KMASK>
+// MASK2D (with BIAS): key_bias is an additive mask [LqR][LkR] (fp32, shared by all heads; -inf hides a key from a
+// query) instead of a per-key bias: every lane reads the 16 values of its own query's row from global memory at the
+// top of a block (the path of the per-key bias at d = 128); H is ignored.
+template <int D, int MODE, bool PRESCALE, bool BIAS, int KMASK, bool MASK2D = false>
 __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
                                                    const float *__restrict__ key_bias, int H,
                                                    int Lq, int Lk, int LqR, int LkR, float scale, int ksplit,
@@ -276,7 +279,8 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
     constexpr int STAGE = MODE == MODE_DENSE ? 0 : 32 * 8;   // 16-byte units per wave
     // (d = 128: K and the staging fill the 80 KiB that let two workgroups share a compute unit, so there the bias
     // is read from global memory into registers at the top of every block instead)
-    constexpr bool BIAS_LDS = BIAS && D == 64;
+    static_assert(!MASK2D || BIAS, "the 2-D mask travels the bias path");
+    constexpr bool BIAS_LDS = BIAS && D == 64 && !MASK2D;
     __shared__ u32x4 Smem[2 * TILE + 4 * STAGE + (BIAS_LDS ? 2 * (KB / 4) : 0)];
     u32x4(*const Ks)[TILE] = reinterpret_cast<u32x4(*)[TILE]>(Smem);
     f32x4(*const Bs)[KB / 4] = reinterpret_cast<f32x4(*)[KB / 4]>(Smem + 2 * TILE + 4 * STAGE);
@@ -306,7 +310,9 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
         src_off[i] = key * D + c * 8;
     }
     const uint32_t lds_k = lds_address(&Ks[0][w * 64]);
-    const float *bias_b = BIAS ? key_bias + (size_t)(bh / H) * LkR : nullptr;
+    const float *bias_b = !BIAS ? nullptr
+                          : MASK2D ? key_bias + (size_t)(UNPADDED && q0 + lj >= LqR ? LqR - 1 : q0 + lj) * LkR
+                                   : key_bias + (size_t)(bh / H) * LkR;
     const uint32_t lds_b = lds_address(&Bs[0][0]);
     auto issue_block = [&](int jb, int buf) {
         const __bf16 *src = Kh + (size_t)jb * KB * D;
@@ -443,8 +449,8 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
                         if constexpr (!PRESCALE) {
                             a0 *= scale; a1 *= scale;
                             if constexpr (BIAS) {
-                                a0 = __fadd_rn(a0, kb4[u][e >> 1][2 * (e & 1)]);
-                                a1 = __fadd_rn(a1, kb4[u][e >> 1][2 * (e & 1) + 1]);
+                                a0 = add_unfused(a0, kb4[u][e >> 1][2 * (e & 1)]);
+                                a1 = add_unfused(a1, kb4[u][e >> 1][2 * (e & 1) + 1]);
                             }
                         }
                         pk[8 * u + e] = pack_bf16x2(a0, a1);
@@ -464,8 +470,8 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
                         if constexpr (!PRESCALE) {
                             a0 *= scale; a1 *= scale; a2 *= scale; a3 *= scale;
                             if constexpr (BIAS) {
-                                a0 = __fadd_rn(a0, kb4[u][g][0]); a1 = __fadd_rn(a1, kb4[u][g][1]);
-                                a2 = __fadd_rn(a2, kb4[u][g][2]); a3 = __fadd_rn(a3, kb4[u][g][3]);
+                                a0 = add_unfused(a0, kb4[u][g][0]); a1 = add_unfused(a1, kb4[u][g][1]);
+                                a2 = add_unfused(a2, kb4[u][g][2]); a3 = add_unfused(a3, kb4[u][g][3]);
                             }
                         }
                         float lo, hi;
@@ -535,7 +541,7 @@ hipError_t launch_nq(const void *Q, const void *K, const float *key_bias, int H,
     return hipGetLastError();
 }
 
-template <int MODE, bool BIAS, int KMASK>
+template <int MODE, bool BIAS, int KMASK, bool MASK2D = false>
 hipError_t launch32(const void *Q, const void *K, const float *key_bias, int H, int BH, int Lq, int Lk, int LqR, int LkR,
                     int d, float scale, void *out, void *meta, hipStream_t st) {
     const int qtiles = (Lq + 127) / 128;
@@ -547,7 +553,7 @@ hipError_t launch32(const void *Q, const void *K, const float *key_bias, int H, 
     const unsigned grid = (unsigned)((long)BH * qtiles * ksplit);
     const bool pre = is_pow2(scale);
 #define DFSS_LAUNCH(DD, PRE)                                                                             \
-    hipLaunchKernelGGL((k_sddmm32<DD, MODE, PRE, BIAS, KMASK>), dim3(grid), dim3(NT), 0, st,                 \
+    hipLaunchKernelGGL((k_sddmm32<DD, MODE, PRE, BIAS, KMASK, MASK2D>), dim3(grid), dim3(NT), 0, st,         \
                        (const __bf16 *)Q, (const __bf16 *)K, key_bias, H, Lq, Lk, LqR, LkR, scale, ksplit, per_wg, \
                        (uint32_t *)out, (uint32_t *)meta)
     if (d == 64) {
@@ -601,6 +607,27 @@ hipError_t launch_sddmm_prune(const void *Q, const void *K, const float *key_bia
 hipError_t launch_dense_scores(const void *Q, const void *K, const float *key_bias, int H, int causal, int BH, int Lq,
                                int Lk, int LqR, int LkR, int d, float scale, void *S, hipStream_t st) {
     return launch<MODE_DENSE>(Q, K, key_bias, H, causal, BH, Lq, Lk, LqR, LkR, d, scale, S, nullptr, st);
+}
+
+namespace {
+template <int MODE>
+hipError_t launch_mask2d(const void *Q, const void *K, const float *mask, int BH, int Lq, int Lk, int LqR, int LkR, int d,
+                         float scale, void *out, void *meta, hipStream_t st) {
+    if (LqR != Lq || LkR != Lk || Lq % 128 != 0)
+        return launch32<MODE, true, KMASK_UNPADDED, true>(Q, K, mask, 1, BH, Lq, Lk, LqR, LkR, d, scale, out, meta, st);
+    return launch32<MODE, true, KMASK_NONE, true>(Q, K, mask, 1, BH, Lq, Lk, LqR, LkR, d, scale, out, meta, st);
+}
+}  // namespace
+
+hipError_t launch_sddmm_prune_mask(const void *Q, const void *K, const float *mask, int BH, int Lq, int Lk, int LqR,
+                                   int LkR, int d, int mode, float scale, void *vals, void *meta, hipStream_t st) {
+    return mode == 0 ? launch_mask2d<MODE_2TO4>(Q, K, mask, BH, Lq, Lk, LqR, LkR, d, scale, vals, meta, st)
+                     : launch_mask2d<MODE_1TO2>(Q, K, mask, BH, Lq, Lk, LqR, LkR, d, scale, vals, meta, st);
+}
+
+hipError_t launch_dense_scores_mask(const void *Q, const void *K, const float *mask, int BH, int Lq, int Lk, int LqR,
+                                    int LkR, int d, float scale, void *S, hipStream_t st) {
+    return launch_mask2d<MODE_DENSE>(Q, K, mask, BH, Lq, Lk, LqR, LkR, d, scale, S, nullptr, st);
 }
 
 }  // namespace dfss

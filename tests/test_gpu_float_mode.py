@@ -350,16 +350,17 @@ def _padding_case(B, H, Lq, Lk, d, seed, integer):
 
 
 @DTYPES
+@pytest.mark.parametrize("scale", [0.125, float(np.float32(1.0 / 3.0))], ids=["pow2", "third"])
 @pytest.mark.parametrize("B,H,Lq,Lk,d", [(2, 2, 128, 256, 64), (3, 1, 64, 384, 128), (16, 4, 1024, 128, 64)])
-def test_stage1_key_bias_bit_exact_on_integer_inputs(B, H, Lq, Lk, d, dtype):
+def test_stage1_key_bias_bit_exact_on_integer_inputs(B, H, Lq, Lk, d, dtype, scale):
     Q, K, _, lengths, bias = _padding_case(B, H, Lq, Lk, d, 6800 + Lq + d, integer=True)
     s = _shape(B, H, Lq, Lk, d, dtype)
-    vals, meta = dfss.dfss_sddmm_prune_bias(_dev(Q), _dev(K), _dev(bias), s, 0.125)
+    vals, meta = dfss.dfss_sddmm_prune_bias(_dev(Q), _dev(K), _dev(bias), s, scale)
     torch.cuda.synchronize()
     vals, meta = vals.cpu().numpy(), _meta_np(meta, s)
     assert int((lengths % 2 != 0).sum()) > 0
     for h in range(B * H) if B * H <= 8 else (0, 5, B * H - 1):
-        S = oracle.add_key_bias(oracle.scores(Q[h].numpy(), K[h].numpy(), 0.125), bias[h // H].numpy())
+        S = oracle.add_key_bias(oracle.scores(Q[h].numpy(), K[h].numpy(), scale), bias[h // H].numpy())
         _, v, kidx = oracle.prune(S, 1, 2)
         assert np.array_equal(meta[h], oracle.encode_meta_f32(kidx, Lk)), f"metadata differs in head {h}"
         assert np.array_equal(vals[h], v), f"kept scores differ in head {h}"      # includes -inf entries

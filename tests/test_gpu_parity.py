@@ -425,6 +425,8 @@ def _padding_case(B, H, Lq, Lk, d, seed, integer):
     (2, 2, 128, 256, 128, 1, 2, 0.125),     # d = 128, 1:2
     (2, 2, 128, 256, 64, 2, 4, float(np.float32(1.0 / 3.0))),   # bias added after the scaling
     (2, 2, 64, 128, 64, 2, 4, float(np.float32(1.0 / 3.0))),
+    (2, 2, 128, 256, 128, 2, 4, float(np.float32(1.0 / 3.0))),   # d = 128: the bias comes from global memory
+    (2, 1, 192, 256, 128, 1, 2, float(np.float32(1.0 / 3.0))),
 ])
 def test_stage1_key_bias_bit_exact_on_integer_inputs(B, H, Lq, Lk, d, N, M, scale):
     """Padding masks cut through groups (lengths are not multiples of 4): masks, metadata and kept
