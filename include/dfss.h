@@ -202,7 +202,7 @@ dfss_status dense_attention_causal(const void *Q, const void *K, const void *V, 
 dfss_status dense_attention_fused_causal(const void *Q, const void *K, const void *V, const void *key_bias,
                                          const dfss_shape *s, float scale, void *O, void *stream);
 
-/* ---- general additive mask (stage calls) ------------------------------------------------ */
+/* ---- general additive mask ---------------------------------------------------------------- */
 /* mask: device, float32 [Lq, Lk] row-major, 16-byte aligned, shared by all B*H heads (relative
  * position terms, arbitrary visibility patterns; -inf hides a key from a query).  mask[i][j] is ADDED
  * to the scaled score of query i and key j in fp32 BEFORE the N:M comparison of stage 1 -- the reading
@@ -225,6 +225,18 @@ dfss_status dfss_attention_staged_mask(const void *Q, const void *K, const void 
 dfss_status dense_attention_mask(const void *Q, const void *K, const void *V, const void *mask,
                                  const dfss_shape *s, float scale, void *O, void *ws, size_t ws_bytes,
                                  void *stream);
+
+/* The same mask in the one-kernel forward pass (nothing but O is written; Sec. 3.1 as dfss_attention
+ * computes it).  mask as above; mask[i][j] joins the scaled score before the selection -- when scale is
+ * a power of two as the initial value of the fp32 accumulation (one rounding less than in the stage
+ * calls), so the two families agree to the tolerance of the one-kernel calls, not bit for bit.  Lengths
+ * as in the _ragged calls: any Lq, Lk % 4 == 0, arrays unpadded (Q, O [B*H, Lq, d]; K, V [B*H, Lk, d]).
+ * Every 64-key block is visited.  2-byte dtype only.  dense_attention_fused_mask is Eq. 1 with the same
+ * mask in one kernel (the baseline). */
+dfss_status dfss_attention_mask(const void *Q, const void *K, const void *V, const void *mask, const dfss_shape *s,
+                                float scale, void *O, void *stream);
+dfss_status dense_attention_fused_mask(const void *Q, const void *K, const void *V, const void *mask,
+                                       const dfss_shape *s, float scale, void *O, void *stream);
 
 /* ---- hybrid block sparsity x N:M (App. A.1.2, "Blocked-ELL Sparsity") ---------------- */
 /* block_mask: device, uint8 [Lq/64, Lk/64] row-major, shared by all B*H heads.  A 64 x 64 block

@@ -30,6 +30,7 @@ EXPORTS = (
     "dense_attention_fused_causal",
     "dfss_blocked_split_workspace_bytes", "dfss_attention_blocked_split", "dense_attention_fused_blocked_split",
     "dfss_sddmm_prune_mask", "dfss_attention_staged_mask", "dense_attention_mask",
+    "dfss_attention_mask", "dense_attention_fused_mask",
 )
 # exported for the library's own tests only (csrc/dfss_internal.h)
 INTERNAL_EXPORTS = ("dfss_internal_attention_variant",)
@@ -133,6 +134,8 @@ def load_library():
         L.dfss_sddmm_prune_mask.argtypes = [vp, vp, vp, sp, f32, vp, vp, vp]
         L.dfss_attention_staged_mask.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
         L.dense_attention_mask.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
+        L.dfss_attention_mask.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
+        L.dense_attention_fused_mask.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_attention_ragged.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_attention_staged.argtypes = [vp, vp, vp, sp, f32, vp, vp, sz, vp]
         L.dfss_attention_staged_bias.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
@@ -160,7 +163,8 @@ def load_library():
                      "dfss_internal_attention_variant", "dfss_sddmm_prune_causal", "dfss_attention_causal",
                      "dfss_attention_staged_causal", "dense_attention_causal", "dense_attention_fused_causal",
                      "dfss_attention_blocked_split", "dense_attention_fused_blocked_split",
-                     "dfss_sddmm_prune_mask", "dfss_attention_staged_mask", "dense_attention_mask"):
+                     "dfss_sddmm_prune_mask", "dfss_attention_staged_mask", "dense_attention_mask",
+                     "dfss_attention_mask", "dense_attention_fused_mask"):
             getattr(L, name).restype = ctypes.c_int
         L.dfss_status_string.argtypes = [ctypes.c_int]
         L.dfss_status_string.restype = ctypes.c_char_p
@@ -561,6 +565,26 @@ def dense_attention_mask(Q, K, V, mask, s: Shape, scale: float, O=None, ws=None)
     st = load_library().dense_attention_mask(_q(Q, s), _kv(K, s), _kv(V, s), _mask_ptr(mask, s), ctypes.byref(s.c()),
                                              scale, _q(O, s), _ptr(ws), ws.numel() * ws.element_size(), _stream())
     _check("dense_attention_mask", st)
+    return O
+
+
+def dfss_attention_mask(Q, K, V, mask, s: Shape, scale: float, O=None):
+    """DFSS forward in one kernel with an additive mask fp32 [Lq, Lk] (any Lq, Lk a multiple of 4; arrays unpadded)."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    st = load_library().dfss_attention_mask(_q(Q, s), _kv(K, s), _kv(V, s), _mask_ptr(mask, s), ctypes.byref(s.c()),
+                                            scale, _q(O, s), _stream())
+    _check("dfss_attention_mask", st)
+    return O
+
+
+def dense_attention_fused_mask(Q, K, V, mask, s: Shape, scale: float, O=None):
+    """Full attention in one kernel with the same mask (the baseline of dfss_attention_mask)."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    st = load_library().dense_attention_fused_mask(_q(Q, s), _kv(K, s), _kv(V, s), _mask_ptr(mask, s),
+                                                   ctypes.byref(s.c()), scale, _q(O, s), _stream())
+    _check("dense_attention_fused_mask", st)
     return O
 
 

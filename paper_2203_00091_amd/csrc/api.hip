@@ -514,6 +514,29 @@ dfss_status dense_attention_mask(const void *Q, const void *K, const void *V, co
     return with_mask(2, Q, K, V, mask, s, scale, O, nullptr, ws, ws_bytes, stream);
 }
 
+// One kernel, general mask; lengths as in the _ragged calls.  dense: full attention (N, M ignored)
+static dfss_status attention_mask_fused(const void *Q, const void *K, const void *V, const void *mask,
+                                        const dfss_shape *s, bool dense, float scale, void *O, void *stream) {
+    Dims D;
+    if (!Q || !K || !V || !mask || !O) return DFSS_ERR_NULL;
+    if (dfss_status st = check_shape_ragged(s, !dense, &D)) return st;
+    if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
+    if (D.f32) return DFSS_ERR_UNSUPPORTED;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(mask)) return DFSS_ERR_SHAPE;
+    return hip_status(dfss::launch_fused_attention_mask(Q, K, V, (const float *)mask, D.BH, D.Lq, D.Lk, D.d,
+                                                        dense ? 2 : D.mode, scale, O, (hipStream_t)stream));
+}
+
+dfss_status dfss_attention_mask(const void *Q, const void *K, const void *V, const void *mask, const dfss_shape *s,
+                                float scale, void *O, void *stream) {
+    return attention_mask_fused(Q, K, V, mask, s, false, scale, O, stream);
+}
+
+dfss_status dense_attention_fused_mask(const void *Q, const void *K, const void *V, const void *mask,
+                                       const dfss_shape *s, float scale, void *O, void *stream) {
+    return attention_mask_fused(Q, K, V, mask, s, true, scale, O, stream);
+}
+
 // dense: full attention (N, M ignored)
 static dfss_status attention_ragged(const void *Q, const void *K, const void *V, const void *key_bias,
                                     const dfss_shape *s, bool dense, float scale, void *O, void *stream) {

@@ -36,6 +36,9 @@ hipError_t launch_dense_av(const void *P, const void *V, int BH, int Lq, int Lk,
 // Whole forward pass in one kernel.  mode: 0 = 2:4, 1 = 1:2, 2 = dense (full attention, Eq. 1).
 // block_mask: uint8 [Lq/64][Lk/64] shared by all heads (zero = block not part of the attention), or nullptr.
 // variant: a DFSS_VARIANT_* tiling (dfss_internal.h), 0 = chosen from the shape.
+// The same with an additive mask fp32 [Lq][Lk] shared by all heads (any Lq; Lk a multiple of 4); mode 2 = full attention.
+hipError_t launch_fused_attention_mask(const void *Q, const void *K, const void *V, const float *mask, int BH, int Lq,
+                                       int Lk, int d, int mode, float scale, void *O, hipStream_t st);
 hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, const float *key_bias, int H,
                                   const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, int mode, float scale,
                                   void *O, int variant, hipStream_t st);

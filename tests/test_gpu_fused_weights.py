@@ -31,11 +31,13 @@ DEV = "cuda:0"
 REL, ABS = 2.0 ** -6, 1e-6
 
 
-def _dense_weights(Qn, Kn, N, M, scale, key_bias=None, block_mask=None):
+def _dense_weights(Qn, Kn, N, M, scale, key_bias=None, block_mask=None, mask=None):
     """The oracle's weight matrix of one head, dense [Lq, Lk] (0 at dropped keys), and the kept mask."""
     S = oracle.scores(Qn, Kn, scale)
     if key_bias is not None:
         S = oracle.add_key_bias(S, key_bias)
+    if mask is not None:
+        S = oracle.add_mask(S, mask)
     if block_mask is not None:
         S = oracle.apply_block_mask(S, block_mask, 64)
     mask, vals, kidx = oracle.prune(S, N, M)
@@ -62,11 +64,11 @@ def _weights_through_identity_v(run, BH, Lq, Lk, d, tdtype):
     return out
 
 
-def _compare(Wgpu, Qn, Kn, N, M, scale, key_bias=None, H=1, block_mask=None, rel=REL):
+def _compare(Wgpu, Qn, Kn, N, M, scale, key_bias=None, H=1, block_mask=None, rel=REL, mask=None):
     ties = 0
     for h in range(Qn.shape[0]):
         kb = None if key_bias is None else key_bias[h // H]
-        W, kept, S = _dense_weights(Qn[h], Kn[h], N, M, scale, kb, block_mask)
+        W, kept, S = _dense_weights(Qn[h], Kn[h], N, M, scale, kb, block_mask, mask)
         got = Wgpu[h].astype(np.float64)
         dropped_weight = np.abs(got[~kept])
         assert dropped_weight.max(initial=0.0) == 0.0, \
@@ -168,6 +170,43 @@ def test_default_call_ragged_call_and_blocked_call(N, M):
     W = _weights_through_identity_v(lambda V: dfss.dfss_attention_blocked(Qd, Kd, V, None, bmd, s, 0.125), BH, Lq, Lk, d,
                                     torch.bfloat16)
     _compare(W, Qn, Kn, N, M, 0.125, block_mask=bm.numpy())
+
+
+@pytest.mark.parametrize("BH,Lq,Lk,d,N,M,scale", [
+    (2, 128, 384, 64, 2, 4, 0.125),                              # the mask is the initial value of the accumulators
+    (2, 192, 256, 64, 1, 2, float(np.float32(1.0 / 3.0))),       # the mask is added after the scaling
+    (1, 128, 256, 128, 2, 4, 0.125),
+    (2, 100, 332, 64, 2, 4, 0.125),                              # unpadded lengths
+    (1, 70, 140, 128, 1, 2, float(np.float32(1.0 / 3.0))),
+])
+def test_general_mask_in_the_one_kernel_call(BH, Lq, Lk, d, N, M, scale):
+    """dfss_attention_mask: quarter-integer terms and -inf entries (whole runs of four and whole 64-key blocks of a
+    query hidden); with integer Q, K every biased score is exact on both sides, so the selection must agree with the
+    oracle's, ties included."""
+    Q, K, Qn, Kn = _int_qk(BH, Lq, Lk, d, seed=8500 + Lq + Lk)
+    g = torch.Generator().manual_seed(8501 + Lq)
+    mask = torch.zeros((Lq, Lk), dtype=torch.float32)
+    r = torch.rand((Lq, Lk), generator=g)
+    mask[r < 1 / 3] = (torch.randint(-8, 9, (Lq, Lk), generator=g).float() / 4)[r < 1 / 3]
+    mask[r > 5 / 6] = float("-inf")
+    mask[(torch.rand((Lq, Lk // 4), generator=g) < 0.1).repeat_interleave(4, dim=1)] = float("-inf")
+    mask[Lq // 2:, :64] = float("-inf")            # the first block hidden from half of the queries
+    mask[: Lq // 3, 64:128] = float("-inf")        # the second from a third
+    mask[:, 130] = 0.0                             # every query sees a key
+    s = Shape(1, BH, Lq, Lk, d, N, M)
+    Qd, Kd, md = Q.to(DEV), K.to(DEV), mask.to(DEV)
+    W = _weights_through_identity_v(lambda V: dfss.dfss_attention_mask(Qd, Kd, V, md, s, scale), BH, Lq, Lk, d,
+                                    torch.bfloat16)
+    ties = _compare(W, Qn, Kn, N, M, scale, mask=mask.numpy())
+    assert ties > 100
+    # the baseline: nothing is dropped
+    W = _weights_through_identity_v(lambda V: dfss.dense_attention_fused_mask(Qd, Kd, V, md, s, scale), BH, Lq, Lk, d,
+                                    torch.bfloat16)
+    for h in range(BH):
+        S = oracle.add_mask(oracle.scores(Qn[h], Kn[h], scale), mask.numpy()).astype(np.float64)
+        P = np.exp(S - S.max(-1, keepdims=True))
+        P /= P.sum(-1, keepdims=True)
+        assert (np.abs(W[h] - P) <= REL * P + ABS).all()
 
 
 def test_float_one_kernel_path():

@@ -4,7 +4,9 @@
     unpadded lengths, both scale paths;
   * the special cases: a causal mask gives the causal call's kept values and metadata bit for bit, a mask whose rows
     all equal a key bias gives the key-bias call's;
-  * O of the staged call and of the three-kernel baseline within 2e-2 of the oracle on Gaussian inputs.
+  * O of the staged call, of the one-kernel calls (dfss_attention_mask, dense_attention_fused_mask) and of the
+    three-kernel baseline within 2e-2 of the oracle on Gaussian inputs (the one-kernel call's selection is checked
+    weight by weight in test_gpu_fused_weights.py).
 """
 import math
 
@@ -117,15 +119,41 @@ def test_attention_with_a_mask(BH, Lq, Lk, d, N, M):
     vals, meta = dfss.dfss_sddmm_prune_mask(Qd, Kd, md, s, scale)
     dfss.dfss_sparse_softmax(vals, s)
     O3 = dfss.dfss_spmm(vals, meta, Vd, s)
+    O1 = dfss.dfss_attention_mask(Qd, Kd, Vd, md, s, scale)
+    O1p = dfss.dfss_attention_mask(Qd, Kd, Vd, md, s, 0.125)       # a power of two: the other scale path
+    Od1 = dfss.dense_attention_fused_mask(Qd, Kd, Vd, md, s, scale)
     torch.cuda.synchronize()
     Qn, Kn, Vn = (synth.to_numpy_f32(t) for t in (Q, K, V))
     ref = oracle.attention(Qn, Kn, Vn, N, M, scale, mask=mask.numpy())
     refd = oracle.attention(Qn, Kn, Vn, 1, 1, scale, mask=mask.numpy())
     assert np.abs(ref - oracle.attention(Qn, Kn, Vn, N, M, scale)).max() > 0.05      # the mask matters
-    for name, got, r in (("staged", O, ref), ("three stages", O3, ref), ("dense", Od, refd)):
+    refp = oracle.attention(Qn, Kn, Vn, N, M, 0.125, mask=mask.numpy())
+    for name, got, r in (("staged", O, ref), ("three stages", O3, ref), ("dense", Od, refd), ("one kernel", O1, ref),
+                         ("one kernel, scale 1/8", O1p, refp), ("dense, one kernel", Od1, refd)):
         got = _np(got)
         assert np.isfinite(got).all(), name
         assert np.abs(got - r).max() <= 2e-2, name
+
+
+def test_one_kernel_mask_special_cases():
+    """A causal mask gives the causal call's result, a zero mask the plain call's (to the rounding of different
+    tilings); unpadded lengths included."""
+    for BH, Lq, Lk, d in ((3, 256, 384, 64), (2, 200, 328, 128)):
+        Q, K, V = synth.gaussian_qkv(BH, Lq, Lk, d, 1.0, seed=9930 + Lq)
+        s = Shape(1, BH, Lq, Lk, d, 2, 4)
+        Qd, Kd, Vd = _dev(Q), _dev(K), _dev(V)
+        scale = 1.0 / math.sqrt(d)
+        cm = torch.from_numpy(oracle.causal_mask(Lq, Lk))
+        O1 = dfss.dfss_attention_mask(Qd, Kd, Vd, _dev(cm), s, scale)
+        O2 = dfss.dfss_attention_staged_causal(Qd, Kd, Vd, None, s, scale) if Lq % 64 == 0 else O1
+        O3 = dfss.dfss_attention_mask(Qd, Kd, Vd, torch.zeros((Lq, Lk), device=DEV), s, scale)
+        O4 = dfss.dfss_attention_ragged(Qd, Kd, Vd, None, s, scale)
+        torch.cuda.synchronize()
+        assert (O1.float() - O2.float()).abs().max().item() <= 2e-2
+        assert (O3.float() - O4.float()).abs().max().item() <= 2e-2
+        Qn, Kn, Vn = (synth.to_numpy_f32(t) for t in (Q, K, V))
+        ref = oracle.attention(Qn, Kn, Vn, 2, 4, scale, mask=cm.numpy())
+        assert np.abs(_np(O1) - ref).max() <= 2e-2
 
 
 def test_mask_calls_refuse_what_they_cannot_run():
@@ -133,6 +161,8 @@ def test_mask_calls_refuse_what_they_cannot_run():
     Q = torch.zeros(1, 128, 64, device=DEV)
     with pytest.raises(dfss.DfssError):       # 2-byte dtype only
         dfss.dfss_attention_staged_mask(Q, Q, Q, torch.zeros(128, 128, device=DEV), s, 0.125)
+    with pytest.raises(dfss.DfssError):
+        dfss.dfss_attention_mask(Q, Q, Q, torch.zeros(128, 128, device=DEV), s, 0.125)
     s2 = Shape(1, 1, 128, 128, 64)
     with pytest.raises(ValueError):           # the mask is [Lq, Lk]
         dfss.dfss_sddmm_prune_mask(Q.bfloat16(), Q.bfloat16(), torch.zeros(128, 64, device=DEV), s2, 0.125)
