@@ -83,6 +83,9 @@ def parse_args():
     ap.add_argument("--causal", action="store_true",
                     help="headline only: run the causal entry points (query i sees keys 0 .. i; FLOPs are counted on "
                          "the visible half of the score matrix)")
+    ap.add_argument("--general-mask", action="store_true",
+                    help="headline only: run the entry points that take an additive mask [L, L] (a seeded relative-"
+                         "position term, finite everywhere; 4 bytes of reads per score)")
     ap.add_argument("--backward", action="store_true",
                     help="headline only: also time dfss_attention_backward on the results of the three forward stages")
     ap.add_argument("--unpadded", type=int, default=0, metavar="LEN",
@@ -194,9 +197,15 @@ def run_workload(name, args, timer, torch, dfss, synth, headline):
     if causal:
         density = (L + 1) / (2.0 * L)      # visible entries of the score matrix
 
+    gmask = None
+    if headline and args.general_mask:
+        gmask = synth.relative_position_mask(L, L, seed=w.seed + 11).to(dev)
+
     def step_sparse(i):
         b = sets[i % nsets]
-        if causal:
+        if gmask is not None:
+            dfss.dfss_attention_mask(b["Q"], b["K"], b["V"], gmask, s, w.scale, O=b["O"])
+        elif causal:
             dfss.dfss_attention_causal(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"])
         elif split_rows:
             dfss.dfss_attention_blocked_split(b["Q"], b["K"], b["V"], bias, block_mask, s, w.scale, O=b["O"], ws=ws_split)
@@ -209,7 +218,9 @@ def run_workload(name, args, timer, torch, dfss, synth, headline):
 
     def step_dense_fused(i):
         b = sets[i % nsets]
-        if causal:
+        if gmask is not None:
+            dfss.dense_attention_fused_mask(b["Q"], b["K"], b["V"], gmask, s, w.scale, O=b["O"])
+        elif causal:
             dfss.dense_attention_fused_causal(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"])
         elif split_rows:
             dfss.dense_attention_fused_blocked_split(b["Q"], b["K"], b["V"], bias, block_mask, s, w.scale, O=b["O"],
@@ -221,11 +232,17 @@ def run_workload(name, args, timer, torch, dfss, synth, headline):
 
     def step_staged(i):
         b = sets[i % nsets]
+        if gmask is not None:
+            dfss.dfss_attention_staged_mask(b["Q"], b["K"], b["V"], gmask, s, w.scale, O=b["O"], ws=wss[i % nws])
+            return
         fn = dfss.dfss_attention_staged_causal if causal else dfss.dfss_attention_staged_bias
         fn(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"], ws=wss[i % nws])
 
     def step_dense(i):
         b = sets[i % nsets]
+        if gmask is not None:
+            dfss.dense_attention_mask(b["Q"], b["K"], b["V"], gmask, s, w.scale, O=b["O"], ws=wss[i % nws])
+            return
         fn = dfss.dense_attention_causal if causal else dfss.dense_attention_bias
         fn(b["Q"], b["K"], b["V"], bias, s, w.scale, O=b["O"], ws=wss[i % nws])
 
@@ -240,6 +257,9 @@ def run_workload(name, args, timer, torch, dfss, synth, headline):
     def step_stage1(i):
         b = sets[i % nsets]
         vals, meta = stage_buffers(i)
+        if gmask is not None:
+            dfss.dfss_sddmm_prune_mask(b["Q"], b["K"], gmask, s, w.scale, vals=vals, meta=meta)
+            return
         fn = dfss.dfss_sddmm_prune_causal if causal else dfss.dfss_sddmm_prune_bias
         fn(b["Q"], b["K"], bias, s, w.scale, vals=vals, meta=meta)
 
@@ -345,6 +365,10 @@ def main():
         print(f"bench.py: unknown workload {args.workload}", file=sys.stderr)
         sys.exit(2)
     wl = synth.WORKLOADS[args.workload]
+    if args.general_mask and (wl.float32 or args.block_pattern or args.causal or args.key_padding or args.backward):
+        print("bench.py: --general-mask runs the 2-byte workloads, forward pass, without the other mask flags",
+              file=sys.stderr)
+        sys.exit(2)
     if args.causal and (wl.float32 or args.block_pattern):
         print("bench.py: --causal runs the 2-byte workloads, without --block-pattern", file=sys.stderr)
         sys.exit(2)
@@ -377,7 +401,8 @@ def main():
             del ctx_other
             torch.cuda.empty_cache()
     head, ctx = run_workload(args.workload, args, timer, torch, dfss, synth, headline=True)
-    if not args.no_sweep and args.workload in SWEEP and not (args.key_padding or args.block_pattern or args.causal):
+    if not args.no_sweep and args.workload in SWEEP and not (args.key_padding or args.block_pattern or args.causal
+                                                             or args.general_mask):
         sweep[args.workload] = head
     w, s, sets = ctx["w"], ctx["s"], ctx["sets"]
     bias, block_mask = ctx["bias"], ctx["block_mask"]
@@ -393,7 +418,7 @@ def main():
     ms_direct = (time.perf_counter() - t0) / K * 1e3
 
     flops_alg = ctx["flops_alg"]
-    plain = not (args.key_padding or args.block_pattern or args.causal or f32)
+    plain = not (args.key_padding or args.block_pattern or args.causal or args.general_mask or f32)
     traffic = TRAFFIC_FROM_PROFILES.get(w.name) if plain else None
     if has_fused:
         # one kernel per step: the step time between the events IS the kernel's average launch duration
@@ -407,7 +432,8 @@ def main():
                     "unit": "TFLOP/s", "frac": round(flops_alg / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                     "traffic": None if traffic is None else traffic[0],
                     "traffic_source": None if traffic is None else traffic[1],
-                    "algorithmic_hbm_bytes_per_launch": None if block_mask is not None else 4.0 * esz * BH * L * d,
+                    "algorithmic_hbm_bytes_per_launch": (None if block_mask is not None else
+                                                         4.0 * esz * BH * L * d + (4.0 * L * L if args.general_mask else 0.0)),
                     "avg_launch_ms": round(ms, 5), "algorithmic_flops_per_launch": flops_alg}
         if f32:   # every algorithmic product is executed as three bf16 products
             roofline["executed_matrix_flops_per_launch"] = 3.0 * flops_alg
@@ -441,6 +467,7 @@ def main():
         "config": {"workload": w.name, "B": w.B, "H": w.H, "L": L, "d": d, "N": w.N, "M": w.M,
                    "products": (args.products if f32 else "bf16"),
                    "key_padding": bool(args.key_padding), "causal": bool(args.causal),
+                   "general_mask": bool(args.general_mask),
                    "block_pattern": (f"window +-1, 1 global, 2 random blocks of 64 x 64, density {ctx['density']:.3f}"
                                      if args.block_pattern else None),
                    "buffer_sets": head["buffer_sets"], "workspace_sets": head["workspace_sets"],

@@ -120,6 +120,17 @@ def key_padding_bias(lengths: torch.Tensor, Lk: int):
     return bias
 
 
+def relative_position_mask(Lq: int, Lk: int, seed: int, slope: float = 0.01):
+    """float32 [Lq, Lk]: a relative-position term -slope * |i + (Lk - Lq) - j| plus a seeded term per distance
+    (one value for every diagonal, Gaussian, sigma 0.1): finite everywhere, different in every entry of a row."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    per_distance = 0.1 * torch.randn(Lq + Lk, generator=g)
+    i = torch.arange(Lq).view(Lq, 1) + (Lk - Lq)
+    j = torch.arange(Lk).view(1, Lk)
+    return (-slope * (i - j).abs().float() + per_distance[i - j + Lq]).contiguous()
+
+
 def block_pattern(nq: int, nk: int, seed: int, window: int = 1, n_global: int = 1, n_random: int = 2):
     """uint8 [nq, nk] block pattern in the style of the block-sparse long-sequence models the paper
     combines with (sliding window of +-`window` blocks around the diagonal, `n_global` leading key
