@@ -178,6 +178,8 @@ def test_default_call_ragged_call_and_blocked_call(N, M):
     (1, 128, 256, 128, 2, 4, 0.125),
     (2, 100, 332, 64, 2, 4, 0.125),                              # unpadded lengths
     (1, 70, 140, 128, 1, 2, float(np.float32(1.0 / 3.0))),
+    (96, 1024, 192, 64, 2, 4, 0.125),                            # many heads and row blocks: several launch tiles
+    (96, 1000, 132, 64, 1, 2, float(np.float32(1.0 / 3.0))),     # the same on unpadded lengths
 ])
 def test_general_mask_in_the_one_kernel_call(BH, Lq, Lk, d, N, M, scale):
     """dfss_attention_mask: quarter-integer terms and -inf entries (whole runs of four and whole 64-key blocks of a
