@@ -369,6 +369,7 @@ def test_results_are_deterministic_and_cover_every_byte():
     sr = Shape(w.B, w.H, Lr, Lr, w.d, w.N, w.M)
     Qr, Kr, Vr = (t[:, :Lr].contiguous() for t in (Q, K, V))
     dO = _dev(synth.gaussian_qkv(w.BH, w.L, w.L, w.d, 1.0, seed=99)[0])
+    gm = _dev(synth.relative_position_mask(Lr, Lr, seed=98))
     o_shape, bf = (s.BH, s.Lq, s.d), torch.bfloat16
     outs = []
     for fill in (0x00, 0xFF):
@@ -394,6 +395,12 @@ def test_results_are_deterministic_and_cover_every_byte():
                                                                        ws=wsb.view(torch.uint8)))
         got["ragged"] = _bits(dfss.dfss_attention_ragged(Qr, Kr, Vr, None, sr, w.scale,
                                                          O=_poisoned((s.BH, Lr, s.d), bf, fill)))
+        got["mask"] = _bits(dfss.dfss_attention_mask(Qr, Kr, Vr, gm, sr, w.scale,
+                                                     O=_poisoned((s.BH, Lr, s.d), bf, fill)))
+        ws = _poisoned((dfss.dfss_workspace_bytes(sr) // 2,), bf, fill)
+        got["staged mask"] = _bits(dfss.dfss_attention_staged_mask(Qr, Kr, Vr, gm, sr, w.scale,
+                                                                   O=_poisoned((s.BH, Lr, s.d), bf, fill),
+                                                                   ws=ws.view(torch.uint8)))
         got["dense"] = _bits(dfss.dense_attention(Q, K, V, s, w.scale, O=_poisoned(o_shape, bf, fill)))
         got["dense one kernel"] = _bits(dfss.dense_attention_fused(Q, K, V, s, w.scale,
                                                                    O=_poisoned(o_shape, bf, fill)))
@@ -685,7 +692,9 @@ def test_calls_replay_correctly_from_a_hip_graph():
     bm = _dev(synth.block_pattern(4, 4, seed=9102, window=0, n_random=0))
     ws = torch.empty(max(dfss.dfss_workspace_bytes(s), dfss.dense_workspace_bytes(s)), dtype=torch.uint8, device=DEV)
     wsb = torch.empty(dfss.dfss_blocked_split_workspace_bytes(s), dtype=torch.uint8, device=DEV)
-    outs = {k: torch.empty_like(Q) for k in ("fused", "bias", "blocked", "blocked_split", "dense", "dense_fused", "stages")}
+    outs = {k: torch.empty_like(Q) for k in ("fused", "bias", "blocked", "blocked_split", "dense", "dense_fused", "stages",
+                                             "mask", "staged_mask")}
+    gm = _dev(synth.relative_position_mask(256, 256, seed=9103))
     vals = torch.empty((s.BH, s.Lq, s.Lc), dtype=torch.bfloat16, device=DEV)
     meta = torch.empty((s.BH * s.Lq * (s.Lk // 16),), dtype=torch.int16, device=DEV)
 
@@ -696,6 +705,8 @@ def test_calls_replay_correctly_from_a_hip_graph():
         dfss.dfss_attention_blocked_split(Q, K, V, bias, bm, s, w.scale, O=outs["blocked_split"], ws=wsb)
         dfss.dense_attention(Q, K, V, s, w.scale, O=outs["dense"], ws=ws)
         dfss.dense_attention_fused(Q, K, V, s, w.scale, O=outs["dense_fused"])
+        dfss.dfss_attention_mask(Q, K, V, gm, s, w.scale, O=outs["mask"])
+        dfss.dfss_attention_staged_mask(Q, K, V, gm, s, w.scale, O=outs["staged_mask"], ws=ws)
         dfss.dfss_sddmm_prune(Q, K, s, w.scale, vals=vals, meta=meta)
         dfss.dfss_sparse_softmax(vals, s)
         dfss.dfss_spmm(vals, meta, V, s, O=outs["stages"])
