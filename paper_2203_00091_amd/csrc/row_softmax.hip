@@ -57,7 +57,7 @@ __global__ __launch_bounds__(NT) void k_row_softmax(uint32_t *__restrict__ x, lo
     for (int i = 0; i < NCH; ++i)
 #pragma unroll
         for (int e = 0; e < EPC; ++e) {
-            v[i][e] = exp2f(v[i][e] * kLog2e - mb);  // exp(x - max); padding lanes give exp2(-inf) = 0
+            v[i][e] = __builtin_amdgcn_exp2f(v[i][e] * kLog2e - mb);  // exp(x - max); padding lanes give exp2(-inf) = 0
             s += v[i][e];
         }
     s = wave_xor_sum(s, TPR);

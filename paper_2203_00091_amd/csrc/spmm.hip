@@ -156,7 +156,7 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
                 bm = fmaxf(bm, __shfl_xor(bm, 32, kWave));   // maximum of row li over the block's 64 kept scores
                 const bool up = bm > m_run[rb] + kTau;       // (the same in the four lanes of a row)
                 // (a row still at -inf gets the factor 0: its sums are 0 anyway)
-                const float f = up ? exp2f((m_run[rb] - bm) * kLog2e) : 1.f;
+                const float f = up ? __builtin_amdgcn_exp2f((m_run[rb] - bm) * kLog2e) : 1.f;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const float fr = __shfl(f, 4 * kb + r, kWave);   // accumulator row 4 kb + r
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
             // a row whose keys so far are all masked (-inf): subtract 0, its weights are exp(-inf) = 0
             const float mb = m_run[rb] == -INFINITY ? 0.f : m_run[rb] * kLog2e;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) x[e] = exp2f(__builtin_fmaf(x[e], kLog2e, -mb));
+            for (int e = 0; e < 16; ++e) x[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], kLog2e, -mb));
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 a[rb].v[0][e] = pack_bf16x2(x[2 * e], x[2 * e + 1]);
