@@ -180,18 +180,23 @@ __global__ __launch_bounds__(NT, 2) void k_av(const uint32_t *__restrict__ P, co
 
     // The A operand is loaded two blocks ahead: block jb + 1 is in registers while block jb is multiplied, so that the
     // softmax of block jb + 1 runs on the vector unit under the matrix instructions of block jb.
-    issue_block(0, 0);
+    // Order of the blocks: workgroup g starts at block g mod nblocks and wraps around (neither the product nor the
+    // softmax with its running reference depends on the order).  The rows of P are a power of two apart for the usual
+    // lengths, so that workgroups marching from block 0 in step would all read the same few memory channels at a time.
+    const int rot = __builtin_amdgcn_readfirstlane((int)(item % (unsigned)nblocks));
+    auto blk = [&](int it) { return it + rot < nblocks ? it + rot : it + rot - nblocks; };
+    issue_block(blk(0), 0);
     AFrag a_cur[RB], a_nxt[RB], a_far[RB];
-    load_a(0, a_cur);
-    if (nblocks > 1) load_a(1, a_nxt);
+    load_a(blk(0), a_cur);
+    if (nblocks > 1) load_a(blk(1), a_nxt);
     if constexpr (SOFTMAX) softmax_block(a_cur);
 
-    for (int jb = 0; jb < nblocks; ++jb) {
+    for (int jb = 0; jb < nblocks; ++jb) {   // jb: place in the order
         const int buf = jb & 1;
         wait_async_copies();  // vmcnt(0): this block's V copies and the A loads of the next block are in
         __syncthreads();
-        if (jb + 1 < nblocks) issue_block(jb + 1, buf ^ 1);
-        if (jb + 2 < nblocks) load_a(jb + 2, a_far);
+        if (jb + 1 < nblocks) issue_block(blk(jb + 1), buf ^ 1);
+        if (jb + 2 < nblocks) load_a(blk(jb + 2), a_far);
         const char *vbase = reinterpret_cast<const char *>(&Vs[buf][0]);
         auto tr = [&](int key0, int ds) {
             const int row = key0 + tr_row;
