@@ -90,7 +90,12 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
         }
     };
 
-    issue_block(jb0, 0);
+    // Order of the blocks: workgroup g starts g blocks into its range and wraps around (the blocks of stage 1 do not
+    // depend on one another).  Rows of the compressed matrix are a power of two apart for the usual lengths: workgroups
+    // marching from their first block in step would all write the same few memory channels at a time.
+    const int rot = __builtin_amdgcn_readfirstlane((int)(item % (unsigned)blocks_per_wg));
+    auto blk = [&](int it) { return jb0 + (it + rot < blocks_per_wg ? it + rot : it + rot - blocks_per_wg); };
+    issue_block(blk(0), 0);
 
     // Q operand: lane (column li, chunk kb) of MFMA step s holds Q[q][32 s + 8 kb .. +7]
     bf16x8 bq[NQ][STEPS];
@@ -114,7 +119,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
     const int rb0 = q0 >> 4;                 // first 16-row block of this wave
 
     for (int it = 0; it < blocks_per_wg; ++it) {
-        const int jb = jb0 + it;
+        const int jb = blk(it);
         const int buf = it & 1;
         // this block's copies (issued one iteration ago) have landed for every wave; the stores of
         // the previous iteration, issued after those copies, stay in flight
@@ -123,7 +128,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm(const __bf16 *__restrict__ Q, c
         else wait_async_copies_keep<kStoresPerBlock>();
         __syncthreads();
         // every wave has also finished reading the other buffer: refill it
-        if (it + 1 < blocks_per_wg) issue_block(jb + 1, buf ^ 1);
+        if (it + 1 < blocks_per_wg) issue_block(blk(it + 1), buf ^ 1);
 
         uint32_t mword[NQ];
 #pragma unroll
@@ -341,7 +346,12 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
         }
     };
 
-    issue_block(jb0, 0);
+    // Order of the blocks: workgroup g starts g blocks into its range and wraps around (the blocks of stage 1 do not
+    // depend on one another).  Rows of the compressed matrix are a power of two apart for the usual lengths: workgroups
+    // marching from their first block in step would all write the same few memory channels at a time.
+    const int rot = __builtin_amdgcn_readfirstlane((int)(item % (unsigned)blocks_per_wg));
+    auto blk = [&](int it) { return jb0 + (it + rot < blocks_per_wg ? it + rot : it + rot - blocks_per_wg); };
+    issue_block(blk(0), 0);
 
     // Q operand: lane (column lj, half h) of step s holds Q[q][16 s + 8 h .. +7]
     bf16x8 bq[STEPS];
@@ -374,7 +384,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
         meta + (((size_t)bh * (Lq / 16) + ((q0 + lj) >> 4)) * (Lk / KB) * 16 + (lj & 15)) * 4);
 
     for (int it = 0; it < blocks_per_wg; ++it) {
-        const int jb = jb0 + it;
+        const int jb = blk(it);
         const int buf = it & 1;
         // Block `it` must have landed.  The stores of the previous iteration were issued after its
         // copy and may stay in flight (waiting for them would expose the store latency every block).
@@ -397,7 +407,7 @@ __global__ __launch_bounds__(NT, 2) void k_sddmm32(const __bf16 *__restrict__ Q,
                         kbg[p][u][g] = *reinterpret_cast<const f32x4 *>(bias_b + key);
                     }
         }
-        if (it + 1 < blocks_per_wg) issue_block(jb + 1, buf ^ 1);
+        if (it + 1 < blocks_per_wg) issue_block(blk(it + 1), buf ^ 1);
 
         u32x2 mwords = {0u, 0u};
 #pragma unroll
