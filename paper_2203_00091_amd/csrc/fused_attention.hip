@@ -168,6 +168,7 @@ __global__ __launch_bounds__(NT * G, 2) void k_fused(const __bf16 *__restrict__ 
     const unsigned qtiles = (Lq + TQ - 1) / TQ;
     int qt, bh;
     int sp = 0, stride = 1, slot = -1;   // SPLIT: place among the workgroups that share the row block; their number; the slot
+    [[maybe_unused]] int first_blk = 0, visits = 0;   // MASK2D: the block this workgroup starts at; blocks taken so far
     if constexpr (SPLIT > 1) {
         const int nblk = Lk / KB, lane = threadIdx.x & 63;
         const unsigned heads = gridDim.x / (kSplitSlots * (SPLIT - 1) + qtiles);
@@ -211,6 +212,11 @@ __global__ __launch_bounds__(NT * G, 2) void k_fused(const __bf16 *__restrict__ 
         bh = (tile % T.hts) * T.th + in % T.th;
         qt = (tile / T.hts) * T.tr + in / T.th;
         if (bh >= H || qt >= (int)qtiles) return;   // the tiles overhang the grid of heads x row blocks
+        // Row block qt starts at key block qt (mod their number) and wraps around -- the order of the blocks does not
+        // matter to Sec. 3.1's softmax.  The heads of a row block stay in step (they share its mask rows through the
+        // L2); the row blocks, whose mask rows are a power of two apart for the usual lengths, no longer read the same
+        // few memory channels at the same time.
+        first_blk = __builtin_amdgcn_readfirstlane(qt % ((Lk + KB - 1) / KB));
     } else {
         const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
         qt = item % qtiles;
@@ -275,7 +281,7 @@ __global__ __launch_bounds__(NT * G, 2) void k_fused(const __bf16 *__restrict__ 
         }
     };
 
-    if (g == 0 && stride == 1) issue_block(0, 0);   // block 0 is copied before anything else (with a key bias or a pattern: speculatively)
+    if (!MASK2D && g == 0 && stride == 1) issue_block(0, 0);   // block 0 is copied before anything else (with a key bias or a pattern: speculatively)
 
     // Q operand (B side of Q K^T): lane (column li, chunk kb) of step s holds Q[q][32 s + 8 kb .. +7]
     bf16x8 bq[NQ][STEPS];
@@ -318,7 +324,12 @@ __global__ __launch_bounds__(NT * G, 2) void k_fused(const __bf16 *__restrict__ 
     // the first of the G: while it exists the round exists, and every group passes the round's barrier.
     int lead_n = 0;
     auto take_live = [&]() -> int {
-        if constexpr (G == 1 && SPLIT == 1) {
+        if constexpr (MASK2D) {
+            const int j = first_blk + visits;
+            lead_n = visits < nblocks ? (j < nblocks ? j : j - nblocks) : nblocks;
+            ++visits;
+            return lead_n;
+        } else if constexpr (G == 1 && SPLIT == 1) {
             return lead_n = blocks.take();
         } else if constexpr (SPLIT > 1) {
             int mine = nblocks;
@@ -343,7 +354,7 @@ __global__ __launch_bounds__(NT * G, 2) void k_fused(const __bf16 *__restrict__ 
     int jn = take_live();   // the block after this one
     // block 0 (copied speculatively at the top) turned out to be fully masked: overwrite the buffer
     // with the first live block (the two copies of a wave complete in issue order)
-    if (MASKED && (g != 0 || stride > 1 || jb != 0) && jb < nblocks) issue_block(jb, 0);
+    if (MASKED && (MASK2D || g != 0 || stride > 1 || jb != 0) && jb < nblocks) issue_block(jb, 0);
 
     // General mask.  d = 64 (MASK_LDS): the 16 x 64 entries of a wave's queries and a block's keys are read as whole
     // rows -- load i of lane l: row 4 i + l / 16, 16-byte piece l % 16, so that a load covers four runs of 256
