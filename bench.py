@@ -177,10 +177,11 @@ def run_workload(name, args, timer, torch, dfss, synth, headline):
     wss = [torch.empty(ws_bytes, dtype=torch.uint8, device=dev) for _ in range(nws)]
     torch.cuda.synchronize()
 
-    bias = None
+    bias = key_len = None
     if headline and args.key_padding:
         lengths = synth.padding_lengths(w.B, L, w.seed + 7)
         bias = synth.key_padding_bias(lengths, L).to(dev)
+        key_len = lengths.to(torch.int32).to(dev)
     block_mask, density = None, 1.0
     if headline and args.block_pattern:
         bm = synth.block_pattern(L // 64, L // 64, seed=w.seed + 9, window=1, n_global=1, n_random=2)
@@ -275,6 +276,13 @@ def run_workload(name, args, timer, torch, dfss, synth, headline):
         b = sets[i % nsets]
         dfss.dfss_attention_blocked(b["Q"], b["K"], b["V"], bias, block_mask, s, w.scale, O=b["O"])
 
+    # a padded batch given by its lengths instead of a bias array (2-byte data, no other mask)
+    varlen = key_len is not None and not f32 and block_mask is None and not causal
+
+    def step_varlen(i):
+        b = sets[i % nsets]
+        dfss.dfss_attention_varlen(b["Q"], b["K"], b["V"], key_len, s, w.scale, O=b["O"])
+
     blocked = block_mask is not None
     ms, replays = timer(step_sparse)
     ms_blocked_plain = timer(step_blocked_plain)[0] if split_rows else None
@@ -307,6 +315,10 @@ def run_workload(name, args, timer, torch, dfss, synth, headline):
         "staged_speedup_vs_dense_attention_3stage": None if blocked else round(ms_dense / ms_staged, 4),
         "speedup_vs_dense_attention_3stage": None if blocked else round(ms_dense / ms, 4),
     }
+    if varlen:
+        res["key_lengths"] = [int(x) for x in lengths]
+        res["dfss_attention_varlen_ms"] = round(timer(step_varlen)[0], 5)
+        res["varlen_speedup_vs_dense_attention_fused"] = round(ms_dense_fused / res["dfss_attention_varlen_ms"], 4)
     if blocked:
         res["block_pattern_entry_points"] = ("dfss_attention_blocked_split / dense_attention_fused_blocked_split "
                                              "(main kernel + merge kernel per step)" if split_rows else

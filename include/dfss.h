@@ -172,6 +172,18 @@ dfss_status dense_attention_bias(const void *Q, const void *K, const void *V, co
 dfss_status dense_attention_fused_bias(const void *Q, const void *K, const void *V, const void *key_bias,
                                        const dfss_shape *s, float scale, void *O, void *stream);
 
+/* A padding mask given by its lengths: key_len, device, int32 [B], 4-byte aligned; keys
+ * key_len[b] .. Lk - 1 of batch element b are padding (as if key_bias[b][j] were -inf there and 0
+ * before; 1 <= key_len[b] <= Lk, values outside are clamped).  The arrays keep the padded shape
+ * [B*H, Lk, d]; precondition: the padding rows of K and V hold finite numbers (a kept padding key
+ * has weight exactly 0, and 0 x infinity is not 0).  One kernel; every block before the one a
+ * sequence ends in costs what it costs without padding, the blocks after it are not visited and no
+ * bias array is read -- the fast call for padded batches.  2-byte dtype, tile shapes (Lq % 64 == 0,
+ * Lk % 128 == 0).  The baseline on a padded batch is dense_attention_fused_bias with the equivalent
+ * bias (the library's fastest full attention on such input). */
+dfss_status dfss_attention_varlen(const void *Q, const void *K, const void *V, const void *key_len,
+                                  const dfss_shape *s, float scale, void *O, void *stream);
+
 /* ---- causal mask ---------------------------------------------------------------------- */
 /* The paper evaluates encoders only (Sec. 5.1) and has no mask; a decoder needs one.  Reading taken:
  * the queries are the LAST Lq of the Lk positions (Lk >= Lq, else DFSS_ERR_SHAPE), so query i sits at

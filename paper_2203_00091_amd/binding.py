@@ -31,6 +31,7 @@ EXPORTS = (
     "dfss_blocked_split_workspace_bytes", "dfss_attention_blocked_split", "dense_attention_fused_blocked_split",
     "dfss_sddmm_prune_mask", "dfss_attention_staged_mask", "dense_attention_mask",
     "dfss_attention_mask", "dense_attention_fused_mask",
+    "dfss_attention_varlen",
 )
 # exported for the library's own tests only (csrc/dfss_internal.h)
 INTERNAL_EXPORTS = ("dfss_internal_attention_variant",)
@@ -135,6 +136,7 @@ def load_library():
         L.dfss_attention_staged_mask.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
         L.dense_attention_mask.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp, sz, vp]
         L.dfss_attention_mask.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
+        L.dfss_attention_varlen.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
         L.dense_attention_fused_mask.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_attention_ragged.argtypes = [vp, vp, vp, vp, sp, f32, vp, vp]
         L.dfss_attention_staged.argtypes = [vp, vp, vp, sp, f32, vp, vp, sz, vp]
@@ -164,7 +166,8 @@ def load_library():
                      "dfss_attention_staged_causal", "dense_attention_causal", "dense_attention_fused_causal",
                      "dfss_attention_blocked_split", "dense_attention_fused_blocked_split",
                      "dfss_sddmm_prune_mask", "dfss_attention_staged_mask", "dense_attention_mask",
-                     "dfss_attention_mask", "dense_attention_fused_mask"):
+                     "dfss_attention_mask", "dense_attention_fused_mask",
+                     "dfss_attention_varlen"):
             getattr(L, name).restype = ctypes.c_int
         L.dfss_status_string.argtypes = [ctypes.c_int]
         L.dfss_status_string.restype = ctypes.c_char_p
@@ -565,6 +568,22 @@ def dense_attention_mask(Q, K, V, mask, s: Shape, scale: float, O=None, ws=None)
     st = load_library().dense_attention_mask(_q(Q, s), _kv(K, s), _kv(V, s), _mask_ptr(mask, s), ctypes.byref(s.c()),
                                              scale, _q(O, s), _ptr(ws), ws.numel() * ws.element_size(), _stream())
     _check("dense_attention_mask", st)
+    return O
+
+
+def _len_ptr(key_len: torch.Tensor, s: Shape) -> int:
+    if key_len.dtype != torch.int32 or key_len.numel() != s.B:
+        raise ValueError(f"key_len must be int32 [B] = [{s.B}]")
+    return _ptr(key_len)
+
+
+def dfss_attention_varlen(Q, K, V, key_len, s: Shape, scale: float, O=None):
+    """DFSS forward in one kernel on a padded batch: keys key_len[b] .. Lk - 1 of batch element b are padding."""
+    if O is None:
+        O = torch.empty((s.BH, s.Lq, s.d), dtype=s.torch_dtype, device=Q.device)
+    st = load_library().dfss_attention_varlen(_q(Q, s), _kv(K, s), _kv(V, s), _len_ptr(key_len, s), ctypes.byref(s.c()),
+                                              scale, _q(O, s), _stream())
+    _check("dfss_attention_varlen", st)
     return O
 
 

@@ -514,6 +514,20 @@ dfss_status dense_attention_mask(const void *Q, const void *K, const void *V, co
     return with_mask(2, Q, K, V, mask, s, scale, O, nullptr, ws, ws_bytes, stream);
 }
 
+// One kernel, padded batch given by its key lengths.
+dfss_status dfss_attention_varlen(const void *Q, const void *K, const void *V, const void *key_len, const dfss_shape *s,
+                                  float scale, void *O, void *stream) {
+    Dims D;
+    if (!Q || !K || !V || !key_len || !O) return DFSS_ERR_NULL;
+    if (dfss_status st = check_shape(s, true, &D)) return st;
+    if (bad_scale(scale)) return DFSS_ERR_UNSUPPORTED;
+    if (D.f32) return DFSS_ERR_UNSUPPORTED;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O)) return DFSS_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(key_len) & 3u) != 0) return DFSS_ERR_SHAPE;
+    return hip_status(dfss::launch_fused_attention_varlen(Q, K, V, (const int *)key_len, D.H, D.BH, D.Lq, D.Lk, D.d,
+                                                          D.mode, scale, O, (hipStream_t)stream));
+}
+
 // One kernel, general mask; lengths as in the _ragged calls.  dense: full attention (N, M ignored)
 static dfss_status attention_mask_fused(const void *Q, const void *K, const void *V, const void *mask,
                                         const dfss_shape *s, bool dense, float scale, void *O, void *stream) {

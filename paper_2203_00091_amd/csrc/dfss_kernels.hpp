@@ -36,6 +36,10 @@ hipError_t launch_dense_av(const void *P, const void *V, int BH, int Lq, int Lk,
 // Whole forward pass in one kernel.  mode: 0 = 2:4, 1 = 1:2, 2 = dense (full attention, Eq. 1).
 // block_mask: uint8 [Lq/64][Lk/64] shared by all heads (zero = block not part of the attention), or nullptr.
 // variant: a DFSS_VARIANT_* tiling (dfss_internal.h), 0 = chosen from the shape.
+// The same for a padded batch given by its lengths: key_len int32 [BH / H] on the device (keys key_len[b] .. Lk - 1 of batch
+// element b are padding); Lq a multiple of 64, Lk of 64; mode 0 or 1.
+hipError_t launch_fused_attention_varlen(const void *Q, const void *K, const void *V, const int *key_len, int H, int BH,
+                                         int Lq, int Lk, int d, int mode, float scale, void *O, hipStream_t st);
 // The same with an additive mask fp32 [Lq][Lk] shared by all heads (any Lq; Lk a multiple of 4); mode 2 = full attention.
 hipError_t launch_fused_attention_mask(const void *Q, const void *K, const void *V, const float *mask, int BH, int Lq,
                                        int Lk, int d, int mode, float scale, void *O, hipStream_t st);

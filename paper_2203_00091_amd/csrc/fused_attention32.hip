@@ -79,12 +79,19 @@ __device__ __forceinline__ uint32_t push_position(uint32_t idx, float v) {
 //              not instantiate that form, the 16-query kernel measured faster for block patterns); causal: query i
 //              sees keys 0 .. i + (Lk - Lq).  Blocks that hold nothing for the workgroup are skipped (block_list.hpp); hidden
 //              scores of the blocks that the diagonal cuts are overwritten with -1e30 by index.
-template <int D, int MODE, int NW, int KS, int OCC, bool MASKED>
+// VARLEN (unmasked kernels with KS = 1): key_len[b] keys of batch element b = head / H are real (1 <= key_len[b] <= Lk; the
+//   arrays are padded to Lk).  A head's workgroups walk only the blocks that hold real keys, and in the block a
+//   sequence ends in the scores of the keys past its end are overwritten by index -- no bias array is read, and every
+//   other block costs what it costs without padding.  (Block 0 always holds key 0, so the first block sets a finite
+//   reference.)
+template <int D, int MODE, int NW, int KS, int OCC, bool MASKED, bool VARLEN = false>
 __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
                                                         const __bf16 *__restrict__ V, const float *__restrict__ key_bias,
                                                         int H, const uint8_t *__restrict__ block_mask, int causal,
-                                                        int Lq, int Lk, float scale, uint16_t *__restrict__ O) {
+                                                        int Lq, int Lk, float scale, uint16_t *__restrict__ O,
+                                                        const int *__restrict__ key_len) {
     static_assert(!MASKED || KS == 1, "the masked variants do not split the keys of a block over waves");
+    static_assert(!VARLEN || (KS == 1 && !MASKED), "key lengths: whole blocks per wave, no other mask");
     constexpr int NT = 64 * NW;
     constexpr int CPR = D / 8;          // 16-byte chunks per row
     constexpr int TILE = KB * CPR;      // chunks per K (or V) block
@@ -118,9 +125,20 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
         const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
         qt = item % qtiles;
         bh = item / qtiles;
+        if constexpr (VARLEN) {
+            // neighbours in launch order come from different batch elements, so that every XCD (and compute unit)
+            // gets long and short sequences alike
+            const unsigned nb = gridDim.x / qtiles / (unsigned)H;
+            bh = (bh % nb) * H + bh / nb;
+        }
     }
     const int q0 = qt * TQ + qw * 32;
-    const int nblocks = Lk / KB;
+    int lk_eff = Lk;   // VARLEN: real keys of this head
+    if constexpr (VARLEN) {
+        const int n = __builtin_amdgcn_readfirstlane(key_len[bh / H]);
+        lk_eff = n < 1 ? 1 : n > Lk ? Lk : n;
+    }
+    const int nblocks = VARLEN ? (lk_eff + KB - 1) / KB : Lk / KB;
     const int coff = Lk - Lq;           // causal: query i sits at position i + coff
 
     // K block in LDS: row slot 32 kt + i (key tile kt, MFMA row i = 8g + 4h' + x) holds key
@@ -227,6 +245,17 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
                         __builtin_bit_cast(bf16x8, Ks[buf][(32 * (kt0 + t) + lj) * CPR + ((2 * s + h) ^ (lj & 7))]);
                     acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, bq[s], s == 0 ? cneg : acc[t], 0, 0, 0);
                 }
+            }
+        }
+        if constexpr (VARLEN) {
+            if (KB * jb + KB > lk_eff) {   // the block the sequence ends in: keys from lk_eff on count as masked
+                asm volatile("" ::: "memory");   // (a branch, not selects that every block would execute)
+                const int lim = lk_eff - 1 - (KB * jb + 16 * h);   // key offsets above it are padding
+#pragma unroll
+                for (int t = 0; t < KT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (32 * t + r > lim) acc[t][r] = -1.0e30f;
             }
         }
         if constexpr (MASKED) {
@@ -438,15 +467,15 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
 // waves per SIMD the kernels are compiled for (registers per lane <= 512 / OCC)
 #define DFSS_OCC(DD) ((DD) == 128 || MASKED ? 2 : MODE == MODE_DENSE ? (KS == 2 ? 3 : 2) : 3)
 
-template <int MODE, int NW, int KS, bool MASKED>
+template <int MODE, int NW, int KS, bool MASKED, bool VARLEN = false>
 hipError_t launch_nw(const void *Q, const void *K, const void *V, const float *key_bias, int H,
                      const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, float scale, void *O,
-                     hipStream_t st) {
+                     hipStream_t st, const int *key_len = nullptr) {
     const unsigned grid = (unsigned)((long)BH * (Lq / (32 * NW / KS)));
 #define DFSS_LAUNCH(DD)                                                                                       \
-    hipLaunchKernelGGL((k_fused32<DD, MODE, NW, KS, DFSS_OCC(DD), MASKED>), dim3(grid), dim3(64 * NW), 0, st, \
+    hipLaunchKernelGGL((k_fused32<DD, MODE, NW, KS, DFSS_OCC(DD), MASKED, VARLEN>), dim3(grid), dim3(64 * NW), 0, st, \
                        (const __bf16 *)Q, (const __bf16 *)K, (const __bf16 *)V, key_bias, H, block_mask,      \
-                       causal, Lq, Lk, scale, (uint16_t *)O)
+                       causal, Lq, Lk, scale, (uint16_t *)O, key_len)
     if (d == 64) DFSS_LAUNCH(64);
     else DFSS_LAUNCH(128);
 #undef DFSS_LAUNCH
@@ -466,7 +495,25 @@ hipError_t launch_mode(const void *Q, const void *K, const void *V, const float 
     return launch_nw<MODE, 2, 1, false>(Q, K, V, nullptr, 1, nullptr, 0, BH, Lq, Lk, d, scale, O, st);
 }
 
+template <int MODE>
+hipError_t launch_varlen(const void *Q, const void *K, const void *V, const int *key_len, int H, int BH, int Lq, int Lk,
+                         int d, float scale, void *O, hipStream_t st) {
+    if (Lq % 128 == 0)
+        return launch_nw<MODE, 4, 1, false, true>(Q, K, V, nullptr, H, nullptr, 0, BH, Lq, Lk, d, scale, O, st, key_len);
+    return launch_nw<MODE, 2, 1, false, true>(Q, K, V, nullptr, H, nullptr, 0, BH, Lq, Lk, d, scale, O, st, key_len);
+}
+
 }  // namespace
+
+// Padded batches given by their lengths: key_len int32 [BH / H] (device), Lq a multiple of 64, Lk (the padded length) of 64;
+// mode 0 or 1 (full attention on padded batches stays with the key-bias path: this kernel's full-attention form is the
+// slower one at most shapes).
+hipError_t launch_fused_attention_varlen(const void *Q, const void *K, const void *V, const int *key_len, int H, int BH,
+                                         int Lq, int Lk, int d, int mode, float scale, void *O, hipStream_t st) {
+    if (mode == 0) return launch_varlen<MODE_2TO4>(Q, K, V, key_len, H, BH, Lq, Lk, d, scale, O, st);
+    if (mode == 1) return launch_varlen<MODE_1TO2>(Q, K, V, key_len, H, BH, Lq, Lk, d, scale, O, st);
+    return hipErrorInvalidValue;
+}
 
 // nw: waves per workgroup (2 or 4); ks: waves that share the keys of one 32-query tile (1, or 2 with nw = 4).
 // Lq must be a multiple of 32 * nw / ks, Lk of 64.  key_bias and causal as in launch_fused_attention; with either of

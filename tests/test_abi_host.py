@@ -149,6 +149,10 @@ def test_errors_are_reported_before_any_launch():
     assert lib.dfss_attention_mask(aligned, aligned, aligned, aligned, ctypes.byref(Shape(1, 1, 100, 130, 64).c()), 0.125, aligned, None) == E_SHAPE
     assert lib.dense_attention_fused_mask(aligned, aligned, aligned, aligned, ctypes.byref(ok), float("nan"), aligned, None) == E_UNSUP
     assert lib.dense_attention_fused_mask(aligned, aligned, aligned, aligned, ctypes.byref(ok), 0.125, None, None) == E_NULL
+    assert lib.dfss_attention_varlen(aligned, aligned, aligned, None, ctypes.byref(ok), 0.125, aligned, None) == E_NULL
+    assert lib.dfss_attention_varlen(aligned, aligned, aligned, odd, ctypes.byref(ok), 0.125, aligned, None) == E_SHAPE
+    assert lib.dfss_attention_varlen(aligned, aligned, aligned, aligned, ctypes.byref(unp), 0.125, aligned, None) == E_SHAPE
+    assert lib.dfss_attention_varlen(aligned, aligned, aligned, aligned, ctypes.byref(ok), 0.0, aligned, None) == E_UNSUP
     assert lib.dfss_spmm_t(aligned, aligned, None, ctypes.byref(ok), aligned, None) == E_NULL
     assert lib.dfss_attention_backward(aligned, aligned, aligned, aligned, aligned, aligned, aligned, ctypes.byref(ok),
                                        0.125, aligned, aligned, aligned, ws, 16, None) == E_WS
@@ -168,6 +172,7 @@ def test_errors_are_reported_before_any_launch():
     x3 = Shape(1, 1, 128, 128, 64, 1, 2, dfss.DFSS_F32_BF16X3).c()
     assert lib.dfss_attention_mask(aligned, aligned, aligned, aligned, ctypes.byref(x3), 0.125, aligned, None) == E_UNSUP
     assert lib.dense_attention_fused_mask(aligned, aligned, aligned, aligned, ctypes.byref(x3), 0.125, aligned, None) == E_UNSUP
+    assert lib.dfss_attention_varlen(aligned, aligned, aligned, aligned, ctypes.byref(f32), 0.125, aligned, None) == E_UNSUP
     assert lib.dfss_spmm_t(aligned, aligned, aligned, ctypes.byref(f32), aligned, None) == E_UNSUP
     assert lib.dfss_attention_backward(aligned, aligned, aligned, aligned, aligned, aligned, aligned, ctypes.byref(f32),
                                        0.125, aligned, aligned, aligned, ws, 1 << 30, None) == E_UNSUP

@@ -211,6 +211,27 @@ def test_general_mask_in_the_one_kernel_call(BH, Lq, Lk, d, N, M, scale):
         assert (np.abs(W[h] - P) <= REL * P + ABS).all()
 
 
+@pytest.mark.parametrize("B,H,Lq,Lk,d,N,M,scale,lengths", [
+    (3, 2, 128, 384, 64, 2, 4, 0.125, (384, 203, 1)),                       # 128-query workgroups; one key only
+    (2, 2, 192, 256, 64, 1, 2, float(np.float32(1.0 / 3.0)), (64, 130)),    # 64-query workgroups; an end on a block edge
+    (2, 1, 128, 256, 128, 2, 4, 0.125, (255, 66)),
+])
+def test_padded_batch_given_by_its_lengths(B, H, Lq, Lk, d, N, M, scale, lengths):
+    """dfss_attention_varlen: the padding keys must carry weight exactly 0 and the selection among the real keys (runs
+    of four that the end of a sequence cuts included) must be the oracle's with the equivalent -inf bias."""
+    BH = B * H
+    Q, K, Qn, Kn = _int_qk(BH, Lq, Lk, d, seed=8600 + Lk + d)
+    s = Shape(B, H, Lq, Lk, d, N, M)
+    lens = torch.tensor(lengths, dtype=torch.int32)
+    bias = synth.key_padding_bias(lens, Lk)
+    Qd, Kd, ld = Q.to(DEV), K.to(DEV), lens.to(DEV)
+    W = _weights_through_identity_v(lambda V: dfss.dfss_attention_varlen(Qd, Kd, V, ld, s, scale), BH, Lq, Lk, d,
+                                    torch.bfloat16)
+    _compare(W, Qn, Kn, N, M, scale, key_bias=bias.numpy(), H=H)
+    for b in range(B):
+        assert (W[b * H:(b + 1) * H, :, lengths[b]:] == 0).all()
+
+
 def test_float_one_kernel_path():
     """The 4-byte mode's one-kernel path (split products; integer inputs are exact in its bfloat16 pieces)."""
     BH, Lq, Lk, d = 2, 128, 256, 64

@@ -489,6 +489,27 @@ def test_attention_key_bias(B, H, Lq, Lk, d, N, M):
     assert torch.isfinite(O.float()).all() and torch.isfinite(Os.float()).all()
 
 
+@pytest.mark.parametrize("B,H,Lq,L,d,N,M", [(4, 3, 512, 512, 64, 2, 4), (2, 2, 384, 384, 128, 1, 2),
+                                             (3, 2, 192, 640, 64, 2, 4)])
+def test_attention_varlen_equals_the_padding_bias(B, H, Lq, L, d, N, M):
+    """A padded batch given by its lengths: against the oracle with the equivalent -inf bias, and against the
+    key-bias call; junk in the padding rows of K (finite) must not matter."""
+    Q, K, V, lengths, bias = _padding_case(B, H, Lq, L, d, seed=7300 + L, integer=False)
+    s = Shape(B, H, Lq, L, d, N, M)
+    scale = 1.0 / math.sqrt(d)
+    Kj = K.clone()
+    for b in range(B):
+        Kj[b * H:(b + 1) * H, int(lengths[b]):] = 37.0
+    lens = lengths.to(torch.int32)
+    O = dfss.dfss_attention_varlen(_dev(Q), _dev(Kj), _dev(V), _dev(lens), s, scale)
+    Ob = dfss.dfss_attention_bias(_dev(Q), _dev(K), _dev(V), _dev(bias), s, scale)
+    torch.cuda.synchronize()
+    Qn, Kn, Vn = (synth.to_numpy_f32(t) for t in (Q, K, V))
+    ref = oracle.attention(Qn, Kn, Vn, N, M, scale, key_bias=bias.numpy(), heads_per_batch=H)
+    assert np.abs(_np(O) - ref).max() <= 2e-2
+    assert (O.float() - Ob.float()).abs().max().item() <= 2e-2
+
+
 def test_attention_key_bias_first_blocks_fully_masked():
     """Masked keys at the START of the sequence: whole leading 64-key blocks contribute nothing and
     the running softmax reference must not turn them into NaN."""
