@@ -387,6 +387,8 @@ def test_results_are_deterministic_and_cover_every_byte():
         got["staged"] = _bits(dfss.dfss_attention_staged(Q, K, V, s, w.scale, O=_poisoned(o_shape, bf, fill),
                                                          ws=ws.view(torch.uint8)))
         got["bias"] = _bits(dfss.dfss_attention_bias(Q, K, V, bias, s, w.scale, O=_poisoned(o_shape, bf, fill)))
+        got["varlen"] = _bits(dfss.dfss_attention_varlen(Q, K, V, _dev(lengths.to(torch.int32)), s, w.scale,
+                                                         O=_poisoned(o_shape, bf, fill)))
         got["blocked"] = _bits(dfss.dfss_attention_blocked(Q, K, V, None, bm, s, w.scale,
                                                            O=_poisoned(o_shape, bf, fill)))
         wsb = _poisoned((dfss.dfss_blocked_split_workspace_bytes(s) // 2,), bf, fill)
@@ -714,7 +716,8 @@ def test_calls_replay_correctly_from_a_hip_graph():
     ws = torch.empty(max(dfss.dfss_workspace_bytes(s), dfss.dense_workspace_bytes(s)), dtype=torch.uint8, device=DEV)
     wsb = torch.empty(dfss.dfss_blocked_split_workspace_bytes(s), dtype=torch.uint8, device=DEV)
     outs = {k: torch.empty_like(Q) for k in ("fused", "bias", "blocked", "blocked_split", "dense", "dense_fused", "stages",
-                                             "mask", "staged_mask")}
+                                             "mask", "staged_mask", "varlen")}
+    lens = _dev(lengths.to(torch.int32))
     gm = _dev(synth.relative_position_mask(256, 256, seed=9103))
     vals = torch.empty((s.BH, s.Lq, s.Lc), dtype=torch.bfloat16, device=DEV)
     meta = torch.empty((s.BH * s.Lq * (s.Lk // 16),), dtype=torch.int16, device=DEV)
@@ -727,6 +730,7 @@ def test_calls_replay_correctly_from_a_hip_graph():
         dfss.dense_attention(Q, K, V, s, w.scale, O=outs["dense"], ws=ws)
         dfss.dense_attention_fused(Q, K, V, s, w.scale, O=outs["dense_fused"])
         dfss.dfss_attention_mask(Q, K, V, gm, s, w.scale, O=outs["mask"])
+        dfss.dfss_attention_varlen(Q, K, V, lens, s, w.scale, O=outs["varlen"])
         dfss.dfss_attention_staged_mask(Q, K, V, gm, s, w.scale, O=outs["staged_mask"], ws=ws)
         dfss.dfss_sddmm_prune(Q, K, s, w.scale, vals=vals, meta=meta)
         dfss.dfss_sparse_softmax(vals, s)
