@@ -891,9 +891,10 @@ hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, c
     // two key halves costs more than it gains there).  Full attention
     // (the baseline) runs whichever of the two kernels is faster at the shape.
     const bool masked = key_bias || block_mask || causal;
-    // masked calls: the 32-query kernel where it measured faster -- the causal mask (with or without a key bias) at
-    // d = 64 on 128-query workgroups; a key bias alone, block patterns and d = 128 stay with the kernel above
-    const bool masked32 = causal && !block_mask && d == 64 && Lq % 128 == 0 && mode != 2;
+    // masked calls: the 32-query kernel where it measured faster -- the causal mask on 128-query workgroups (alone: its
+    // form without the masking machinery, d = 64 and 128; with a key bias: the masked form, d = 64); a key bias alone
+    // and block patterns stay with the kernel above
+    const bool masked32 = causal && !block_mask && (d == 64 || !key_bias) && Lq % 128 == 0 && mode != 2;
     const bool tiles = Lq % 64 == 0 && Lk % 64 == 0;
     if (tiles && (!masked || masked32) && variant != DFSS_VARIANT_Q16 && variant != DFSS_VARIANT_Q16X2) {
         const long wg128 = (long)BH * (Lq / 128);

@@ -84,7 +84,10 @@ __device__ __forceinline__ uint32_t push_position(uint32_t idx, float v) {
 //   sequence ends in the scores of the keys past its end are overwritten by index -- no bias array is read, and every
 //   other block costs what it costs without padding.  (Block 0 always holds key 0, so the first block sets a finite
 //   reference.)
-template <int D, int MODE, int NW, int KS, int OCC, bool MASKED, bool VARLEN = false>
+// CAUSAL_ONLY (the same kernels): the causal mask and nothing else (query i sees keys 0 .. i + Lk - Lq), by the same two
+//   means: a workgroup walks the blocks up to the last key its last query sees, and in the blocks that the diagonal of
+//   a wave's queries cuts the hidden scores are overwritten by index.  Launch order: last row block of every head first.
+template <int D, int MODE, int NW, int KS, int OCC, bool MASKED, bool VARLEN = false, bool CAUSAL_ONLY = false>
 __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
                                                         const __bf16 *__restrict__ V, const float *__restrict__ key_bias,
                                                         int H, const uint8_t *__restrict__ block_mask, int causal,
@@ -92,6 +95,7 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
                                                         const int *__restrict__ key_len) {
     static_assert(!MASKED || KS == 1, "the masked variants do not split the keys of a block over waves");
     static_assert(!VARLEN || (KS == 1 && !MASKED), "key lengths: whole blocks per wave, no other mask");
+    static_assert(!CAUSAL_ONLY || (KS == 1 && !MASKED && !VARLEN), "causal alone: whole blocks per wave, no other mask");
     constexpr int NT = 64 * NW;
     constexpr int CPR = D / 8;          // 16-byte chunks per row
     constexpr int TILE = KB * CPR;      // chunks per K (or V) block
@@ -114,12 +118,12 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
 
     const unsigned qtiles = Lq / TQ;
     int qt, bh;
-    if (MASKED && (block_mask || causal)) {
+    if (CAUSAL_ONLY || (MASKED && (block_mask || causal))) {
         // row blocks differ widely in work: hand them out across heads in launch order, heavy ones first (with a
         // block pattern the global rows come first; under the causal mask the work grows with the row block)
         const unsigned heads = gridDim.x / qtiles;
         qt = blockIdx.x / heads;
-        if (causal && !block_mask) qt = qtiles - 1 - qt;
+        if (CAUSAL_ONLY || (causal && !block_mask)) qt = qtiles - 1 - qt;
         bh = blockIdx.x % heads;
     } else {
         const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);
@@ -138,8 +142,10 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
         const int n = __builtin_amdgcn_readfirstlane(key_len[bh / H]);
         lk_eff = n < 1 ? 1 : n > Lk ? Lk : n;
     }
-    const int nblocks = VARLEN ? (lk_eff + KB - 1) / KB : Lk / KB;
     const int coff = Lk - Lq;           // causal: query i sits at position i + coff
+    const int nblocks = VARLEN        ? (lk_eff + KB - 1) / KB
+                        : CAUSAL_ONLY ? (__builtin_amdgcn_readfirstlane(qt) * TQ + TQ - 1 + coff) / KB + 1
+                                      : Lk / KB;
 
     // K block in LDS: row slot 32 kt + i (key tile kt, MFMA row i = 8g + 4h' + x) holds key
     // 32 kt + 16 h' + 4 g + x; chunk c sits at slot * CPR + (c ^ (slot & 7)).
@@ -251,6 +257,17 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
             if (KB * jb + KB > lk_eff) {   // the block the sequence ends in: keys from lk_eff on count as masked
                 asm volatile("" ::: "memory");   // (a branch, not selects that every block would execute)
                 const int lim = lk_eff - 1 - (KB * jb + 16 * h);   // key offsets above it are padding
+#pragma unroll
+                for (int t = 0; t < KT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (32 * t + r > lim) acc[t][r] = -1.0e30f;
+            }
+        }
+        if constexpr (CAUSAL_ONLY) {
+            if (KB * jb + KB - 1 > __builtin_amdgcn_readfirstlane(q0) + coff) {   // the wave's first query has hidden keys here
+                asm volatile("" ::: "memory");   // (a branch, not selects that every block would execute)
+                const int lim = q0 + lj + coff - (KB * jb + 16 * h);   // key offsets above it are hidden
 #pragma unroll
                 for (int t = 0; t < KT; ++t)
 #pragma unroll
@@ -467,13 +484,13 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
 // waves per SIMD the kernels are compiled for (registers per lane <= 512 / OCC)
 #define DFSS_OCC(DD) ((DD) == 128 || MASKED ? 2 : MODE == MODE_DENSE ? (KS == 2 ? 3 : 2) : 3)
 
-template <int MODE, int NW, int KS, bool MASKED, bool VARLEN = false>
+template <int MODE, int NW, int KS, bool MASKED, bool VARLEN = false, bool CAUSAL_ONLY = false>
 hipError_t launch_nw(const void *Q, const void *K, const void *V, const float *key_bias, int H,
                      const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, float scale, void *O,
                      hipStream_t st, const int *key_len = nullptr) {
     const unsigned grid = (unsigned)((long)BH * (Lq / (32 * NW / KS)));
 #define DFSS_LAUNCH(DD)                                                                                       \
-    hipLaunchKernelGGL((k_fused32<DD, MODE, NW, KS, DFSS_OCC(DD), MASKED, VARLEN>), dim3(grid), dim3(64 * NW), 0, st, \
+    hipLaunchKernelGGL((k_fused32<DD, MODE, NW, KS, DFSS_OCC(DD), MASKED, VARLEN, CAUSAL_ONLY>), dim3(grid), dim3(64 * NW), 0, st, \
                        (const __bf16 *)Q, (const __bf16 *)K, (const __bf16 *)V, key_bias, H, block_mask,      \
                        causal, Lq, Lk, scale, (uint16_t *)O, key_len)
     if (d == 64) DFSS_LAUNCH(64);
@@ -488,6 +505,10 @@ hipError_t launch_mode(const void *Q, const void *K, const void *V, const float 
                        float scale, void *O, hipStream_t st) {
     if (key_bias || block_mask || causal) {   // masked calls: 128-query workgroups (block patterns need 64: not here)
         if (block_mask || nw != 4 || Lq % 128 != 0) return hipErrorInvalidValue;
+        if constexpr (MODE != MODE_DENSE) {
+            if (!key_bias)   // the causal mask alone: the kernel without the masking machinery
+                return launch_nw<MODE, 4, 1, false, false, true>(Q, K, V, nullptr, H, nullptr, 1, BH, Lq, Lk, d, scale, O, st);
+        }
         return launch_nw<MODE, 4, 1, true>(Q, K, V, key_bias, H, nullptr, causal, BH, Lq, Lk, d, scale, O, st);
     }
     if (ks == 2) return launch_nw<MODE, 4, 2, false>(Q, K, V, nullptr, 1, nullptr, 0, BH, Lq, Lk, d, scale, O, st);
