@@ -510,6 +510,14 @@ def test_attention_varlen_equals_the_padding_bias(B, H, Lq, L, d, N, M):
     ref = oracle.attention(Qn, Kn, Vn, N, M, scale, key_bias=bias.numpy(), heads_per_batch=H)
     assert np.abs(_np(O) - ref).max() <= 2e-2
     assert (O.float() - Ob.float()).abs().max().item() <= 2e-2
+    # lengths outside 1 .. Lk are clamped
+    wild = lens.clone()
+    wild[0], wild[-1] = L + 77, 0
+    clamped = wild.clamp(1, L)
+    Ow = dfss.dfss_attention_varlen(_dev(Q), _dev(Kj), _dev(V), _dev(wild), s, scale)
+    Oc = dfss.dfss_attention_varlen(_dev(Q), _dev(Kj), _dev(V), _dev(clamped), s, scale)
+    torch.cuda.synchronize()
+    assert torch.equal(Ow.view(torch.int16), Oc.view(torch.int16))
 
 
 def test_attention_key_bias_first_blocks_fully_masked():
