@@ -830,6 +830,16 @@ hipError_t launch_split(const void *Q, const void *K, const void *V, const float
     return hipGetLastError();
 }
 
+}  // namespace
+
+hipError_t launch_fused_attention32(const void *Q, const void *K, const void *V, const float *key_bias, int H,
+                                    const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, int mode,
+                                    int nw, int ks, float scale, void *O, hipStream_t st);
+hipError_t launch_fused_attention32_ragged(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d,
+                                           int mode, float scale, void *O, hipStream_t st);
+
+namespace {
+
 template <int MODE>
 hipError_t launch(const void *Q, const void *K, const void *V, const float *key_bias, int H,
                   const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, float scale, void *O,
@@ -840,6 +850,15 @@ hipError_t launch(const void *Q, const void *K, const void *V, const float *key_
     if (variant == DFSS_VARIANT_Q16X2) two = Lq % 128 == 0;
     if (block_mask) two = false;   // the block of the mask is the 64-query workgroup tile
     if (Lq % 64 != 0 || Lk % 64 != 0) {   // (never together with a block mask)
+        // no mask at all and enough 128-query workgroups for the chip: the 32-query kernel (103 against 119 us at
+        // 4000 x 4000, 24 heads).  Rows of fewer than 256 keys stay with the kernel below, which compares full fp32
+        // scores: that kernel's comparison gives up the two lowest mantissa bits, and in a short row the weight that a
+        // near-tie decided the other way is large.
+        if constexpr (MODE != MODE_DENSE) {
+            if (!key_bias && !causal && variant == DFSS_VARIANT_AUTO && Lk >= 256 &&
+                (long)BH * ((Lq + 127) / 128) >= 512)
+                return launch_fused_attention32_ragged(Q, K, V, BH, Lq, Lk, d, MODE == MODE_2TO4 ? 0 : 1, scale, O, st);
+        }
         if ((long)BH * ((Lq + 127) / 128) >= 768)
             return launch_nq<MODE, 2, true, true>(Q, K, V, key_bias, H, nullptr, causal, BH, Lq, Lk, d, scale, O, st);
         return launch_nq<MODE, 1, true, true>(Q, K, V, key_bias, H, nullptr, causal, BH, Lq, Lk, d, scale, O, st);
@@ -856,10 +875,6 @@ hipError_t launch(const void *Q, const void *K, const void *V, const float *key_
 }
 
 }  // namespace
-
-hipError_t launch_fused_attention32(const void *Q, const void *K, const void *V, const float *key_bias, int H,
-                                    const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, int mode,
-                                    int nw, int ks, float scale, void *O, hipStream_t st);
 
 size_t fused_attention_split_workspace_bytes(int BH, int Lq, int d) {
     return (size_t)BH * kSplitSlots * kSplit * 64 * (d + 2) * sizeof(float);

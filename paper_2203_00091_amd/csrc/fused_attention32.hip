@@ -87,7 +87,11 @@ __device__ __forceinline__ uint32_t push_position(uint32_t idx, float v) {
 // CAUSAL_ONLY (the same kernels): the causal mask and nothing else (query i sees keys 0 .. i + Lk - Lq), by the same two
 //   means: a workgroup walks the blocks up to the last key its last query sees, and in the blocks that the diagonal of
 //   a wave's queries cuts the hidden scores are overwritten by index.  Launch order: last row block of every head first.
-template <int D, int MODE, int NW, int KS, int OCC, bool MASKED, bool VARLEN = false, bool CAUSAL_ONLY = false>
+// RAGGED (the same kernels): lengths that are no tile multiples (any Lq; Lk a multiple of 4), arrays unpadded.  Absent
+//   queries of the last tile read the last query and are not stored; the places of absent keys in the last block are
+//   copied from the block's last key (never past the arrays) and their scores overwritten like padding keys.
+template <int D, int MODE, int NW, int KS, int OCC, bool MASKED, bool VARLEN = false, bool CAUSAL_ONLY = false,
+          bool RAGGED = false>
 __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 *__restrict__ Q, const __bf16 *__restrict__ K,
                                                         const __bf16 *__restrict__ V, const float *__restrict__ key_bias,
                                                         int H, const uint8_t *__restrict__ block_mask, int causal,
@@ -96,6 +100,7 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
     static_assert(!MASKED || KS == 1, "the masked variants do not split the keys of a block over waves");
     static_assert(!VARLEN || (KS == 1 && !MASKED), "key lengths: whole blocks per wave, no other mask");
     static_assert(!CAUSAL_ONLY || (KS == 1 && !MASKED && !VARLEN), "causal alone: whole blocks per wave, no other mask");
+    static_assert(!RAGGED || (KS == 1 && !MASKED && !VARLEN && !CAUSAL_ONLY), "ragged lengths: whole blocks per wave, no mask");
     constexpr int NT = 64 * NW;
     constexpr int CPR = D / 8;          // 16-byte chunks per row
     constexpr int TILE = KB * CPR;      // chunks per K (or V) block
@@ -116,7 +121,7 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
     const int w = tid >> 6, l = tid & 63, lj = l & 31, h = l >> 5;
     const int qw = w / KS, ks = w % KS;   // query tile of the workgroup, key tile of the block
 
-    const unsigned qtiles = Lq / TQ;
+    const unsigned qtiles = RAGGED ? (Lq + TQ - 1) / TQ : Lq / TQ;
     int qt, bh;
     if (CAUSAL_ONLY || (MASKED && (block_mask || causal))) {
         // row blocks differ widely in work: hand them out across heads in launch order, heavy ones first (with a
@@ -143,9 +148,10 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
         lk_eff = n < 1 ? 1 : n > Lk ? Lk : n;
     }
     const int coff = Lk - Lq;           // causal: query i sits at position i + coff
-    const int nblocks = VARLEN        ? (lk_eff + KB - 1) / KB
-                        : CAUSAL_ONLY ? (__builtin_amdgcn_readfirstlane(qt) * TQ + TQ - 1 + coff) / KB + 1
-                                      : Lk / KB;
+    const int nblocks = VARLEN || RAGGED ? (lk_eff + KB - 1) / KB
+                        : CAUSAL_ONLY    ? (__builtin_amdgcn_readfirstlane(qt) * TQ + TQ - 1 + coff) / KB + 1
+                                         : Lk / KB;
+    [[maybe_unused]] const int tail_keys = Lk - (nblocks - 1) * KB;   // RAGGED: keys of the last block
 
     // K block in LDS: row slot 32 kt + i (key tile kt, MFMA row i = 8g + 4h' + x) holds key
     // 32 kt + 16 h' + 4 g + x; chunk c sits at slot * CPR + (c ^ (slot & 7)).
@@ -156,16 +162,18 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
     static_assert(SPC % 8 == 0, "the slot bits that a thread's copies differ in are bits 3, 4 and 5");
     const int slot0 = tid / CPR;
     const int key0 = (slot0 & 32) | (((slot0 >> 2) & 1) << 4) | (((slot0 >> 3) & 3) << 2) | (slot0 & 3);
-    const uint32_t k_off = 2u * (key0 * D + ((tid % CPR) ^ (slot0 & 7)) * 8);
-    const uint32_t v_off = 2u * (slot0 * D + ((tid % CPR) ^ ((slot0 & 3) << 1)) * 8);
+    const int k_chunk = ((tid % CPR) ^ (slot0 & 7)) * 8, v_chunk = ((tid % CPR) ^ ((slot0 & 3) << 1)) * 8;
+    const uint32_t k_off = 2u * (key0 * D + k_chunk);
+    const uint32_t v_off = 2u * (slot0 * D + v_chunk);
     const uint32_t lds_k = lds_address(&Ks[0][w * 64]), lds_v = lds_address(&Vs[0][w * 64]);
     const uint64_t k_base = uniform_address(K + (size_t)bh * Lk * D), v_base = uniform_address(V + (size_t)bh * Lk * D);
     // Q operand (B side of Q K^T): lane (column lj, half h) of step s holds Q[q][16 s + 8 h .. +7]
     bf16x8 bq[STEPS];
+    const int qrow = RAGGED && q0 + lj >= Lq ? Lq - 1 : q0 + lj;
 #pragma unroll
     for (int s = 0; s < STEPS; ++s)
         bq[s] = __builtin_bit_cast(
-            bf16x8, *reinterpret_cast<const u32x4 *>(Q + ((size_t)bh * Lq + q0 + lj) * D + 16 * s + 8 * h));
+            bf16x8, *reinterpret_cast<const u32x4 *>(Q + ((size_t)bh * Lq + qrow) * D + 16 * s + 8 * h));
 
     const float k2 = scale * kLog2e;       // weight = exp2(s' * k2)
     const float tau = kTau / scale;        // kTau in units of the raw dot product
@@ -192,6 +200,16 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
     auto issue_block = [&](int jb, int buf) {
         const uint64_t ks_ = k_base + (uint64_t)jb * (KB * D * 2);
         const uint64_t vs_ = v_base + (uint64_t)jb * (KB * D * 2);
+        if (RAGGED && jb == nblocks - 1 && tail_keys < KB) {   // partial last block: absent keys -> the block's last key
+#pragma unroll
+            for (int i = 0; i < LPT; ++i) {
+                const int key = key0 + (((i * SPC) >> 3) & 1) * 4 + (((i * SPC) >> 4) & 1) * 8 + ((i * SPC) & 32);
+                const int row = slot0 + i * SPC;
+                async_copy16(ks_, 2u * ((key < tail_keys ? key : tail_keys - 1) * D + k_chunk), lds_k + 16u * (buf * TILE + i * NT));
+                async_copy16(vs_, 2u * ((row < tail_keys ? row : tail_keys - 1) * D + v_chunk), lds_v + 16u * (buf * TILE + i * NT));
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < LPT; ++i)
             async_copy16(ks_ + (uint64_t)((((i * SPC) >> 3) & 1) * 4 + (((i * SPC) >> 4) & 1) * 8 + ((i * SPC) & 32)) * D * 2, k_off,
@@ -253,7 +271,7 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
                 }
             }
         }
-        if constexpr (VARLEN) {
+        if constexpr (VARLEN || RAGGED) {
             if (KB * jb + KB > lk_eff) {   // the block the sequence ends in: keys from lk_eff on count as masked
                 asm volatile("" ::: "memory");   // (a branch, not selects that every block would execute)
                 const int lim = lk_eff - 1 - (KB * jb + 16 * h);   // key offsets above it are padding
@@ -474,6 +492,7 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const float inv = __builtin_amdgcn_rcpf(acc_l[r]);
+        if (RAGGED && q0 + 8 * (r >> 2) + 4 * h + (r & 3) >= Lq) continue;   // an absent query
         const size_t q = (size_t)bh * Lq + q0 + 8 * (r >> 2) + 4 * h + (r & 3);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
@@ -484,13 +503,13 @@ __global__ __launch_bounds__(64 * NW, OCC * 4 / NW) void k_fused32(const __bf16 
 // waves per SIMD the kernels are compiled for (registers per lane <= 512 / OCC)
 #define DFSS_OCC(DD) ((DD) == 128 || MASKED ? 2 : MODE == MODE_DENSE ? (KS == 2 ? 3 : 2) : 3)
 
-template <int MODE, int NW, int KS, bool MASKED, bool VARLEN = false, bool CAUSAL_ONLY = false>
+template <int MODE, int NW, int KS, bool MASKED, bool VARLEN = false, bool CAUSAL_ONLY = false, bool RAGGED = false>
 hipError_t launch_nw(const void *Q, const void *K, const void *V, const float *key_bias, int H,
                      const uint8_t *block_mask, int causal, int BH, int Lq, int Lk, int d, float scale, void *O,
                      hipStream_t st, const int *key_len = nullptr) {
-    const unsigned grid = (unsigned)((long)BH * (Lq / (32 * NW / KS)));
+    const unsigned grid = (unsigned)((long)BH * ((Lq + (RAGGED ? 32 * NW / KS - 1 : 0)) / (32 * NW / KS)));
 #define DFSS_LAUNCH(DD)                                                                                       \
-    hipLaunchKernelGGL((k_fused32<DD, MODE, NW, KS, DFSS_OCC(DD), MASKED, VARLEN, CAUSAL_ONLY>), dim3(grid), dim3(64 * NW), 0, st, \
+    hipLaunchKernelGGL((k_fused32<DD, MODE, NW, KS, DFSS_OCC(DD), MASKED, VARLEN, CAUSAL_ONLY, RAGGED>), dim3(grid), dim3(64 * NW), 0, st, \
                        (const __bf16 *)Q, (const __bf16 *)K, (const __bf16 *)V, key_bias, H, block_mask,      \
                        causal, Lq, Lk, scale, (uint16_t *)O, key_len)
     if (d == 64) DFSS_LAUNCH(64);
@@ -533,6 +552,17 @@ hipError_t launch_fused_attention_varlen(const void *Q, const void *K, const voi
                                          int Lq, int Lk, int d, int mode, float scale, void *O, hipStream_t st) {
     if (mode == 0) return launch_varlen<MODE_2TO4>(Q, K, V, key_len, H, BH, Lq, Lk, d, scale, O, st);
     if (mode == 1) return launch_varlen<MODE_1TO2>(Q, K, V, key_len, H, BH, Lq, Lk, d, scale, O, st);
+    return hipErrorInvalidValue;
+}
+
+// Lengths that are no tile multiples (any Lq, Lk a multiple of 4), arrays unpadded, no mask; mode 0 or 1; 128-query
+// workgroups.
+hipError_t launch_fused_attention32_ragged(const void *Q, const void *K, const void *V, int BH, int Lq, int Lk, int d,
+                                           int mode, float scale, void *O, hipStream_t st) {
+    if (mode == 0)
+        return launch_nw<MODE_2TO4, 4, 1, false, false, false, true>(Q, K, V, nullptr, 1, nullptr, 0, BH, Lq, Lk, d, scale, O, st);
+    if (mode == 1)
+        return launch_nw<MODE_1TO2, 4, 1, false, false, false, true>(Q, K, V, nullptr, 1, nullptr, 0, BH, Lq, Lk, d, scale, O, st);
     return hipErrorInvalidValue;
 }
 

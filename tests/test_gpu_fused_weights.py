@@ -232,6 +232,19 @@ def test_padded_batch_given_by_its_lengths(B, H, Lq, Lk, d, N, M, scale, lengths
         assert (W[b * H:(b + 1) * H, :, lengths[b]:] == 0).all()
 
 
+def test_ragged_call_on_a_grid_that_fills_the_chip():
+    """dfss_attention_ragged on many heads runs the 32-queries-per-wave kernel: weight by weight, with a last
+    query tile of 8 rows and a last key block of 4 keys."""
+    BH, Lq, Lk, d, N, M = 64, 904, 260, 64, 2, 4
+    Q, K, Qn, Kn = _int_qk(BH, Lq, Lk, d, seed=8700)
+    s = Shape(1, BH, Lq, Lk, d, N, M)
+    Qd, Kd = Q.to(DEV), K.to(DEV)
+    W = _weights_through_identity_v(lambda V: dfss.dfss_attention_ragged(Qd, Kd, V, None, s, 0.125), BH, Lq, Lk, d,
+                                    torch.bfloat16)
+    ties = _compare(W[::8], Qn[::8], Kn[::8], N, M, 0.125)
+    assert ties > 100
+
+
 def test_float_one_kernel_path():
     """The 4-byte mode's one-kernel path (split products; integer inputs are exact in its bfloat16 pieces)."""
     BH, Lq, Lk, d = 2, 128, 256, 64

@@ -164,6 +164,27 @@ def test_ragged_length_4000(dtype, N, M):
         assert _max_err(O[h][rows][None], ref[None], Qn[h][rows][None], Kn[h][None], 0.125, dtype, tie=0) <= 2e-2
 
 
+@pytest.mark.parametrize("BH,Lq,Lk,d,N,M,scale", [
+    (96, 700, 332, 64, 2, 4, 0.125),                              # 576 workgroups of 128 queries: the 32-query kernel
+    (128, 417, 1284, 64, 1, 2, float(np.float32(1.0 / 3.0))),     # a last tile of 33 queries, a last block of 4 keys
+    (64, 1000, 260, 128, 2, 4, 0.125),                            # d = 128
+    (24, 4000, 4000, 64, 2, 4, 0.125),                            # the retrieval length at the bench's head count
+])
+def test_ragged_lengths_on_grids_that_fill_the_chip(BH, Lq, Lk, d, N, M, scale):
+    """Calls without a mask whose 128-query workgroups fill the chip take the 32-queries-per-wave kernel.  Sampled
+    heads and query rows against the oracle (every key of those rows); O in front of a guard region."""
+    Q, K, V, (Qn, Kn, Vn) = _inputs(BH, Lq, Lk, d, DFSS_BF16, 8800 + Lq)
+    s = Shape(1, BH, Lq, Lk, d, N, M)
+    O = _run(dfss.dfss_attention_ragged, Q, K, V, None, s, scale)
+    rows = np.unique(np.r_[0:6, Lq // 2:Lq // 2 + 6, max(Lq - 40, 0):Lq])
+    for h in (0, BH // 2, BH - 1):
+        ref = oracle.attention(Qn[h][rows], Kn[h], Vn[h], N, M, scale)
+        assert np.abs(O[h][rows] - ref).max() <= 2e-2, h
+    # every head and row: against the 16-queries-per-wave kernel (a zero key bias selects it)
+    O16 = _run(dfss.dfss_attention_ragged, Q, K, V, torch.zeros((1, Lk)), s, scale)
+    assert np.abs(O - O16).max() <= 2e-2
+
+
 @pytest.mark.parametrize("dtype,N,M", [(DFSS_BF16, 2, 4), (DFSS_BF16, 1, 2), (DFSS_F32_BF16X3, 1, 2)])
 def test_ragged_random_shapes(dtype, N, M):
     """Seeded random lengths (any Lq, Lk a multiple of 4), with and without a padding mask."""
