@@ -850,13 +850,14 @@ hipError_t launch(const void *Q, const void *K, const void *V, const float *key_
     if (variant == DFSS_VARIANT_Q16X2) two = Lq % 128 == 0;
     if (block_mask) two = false;   // the block of the mask is the 64-query workgroup tile
     if (Lq % 64 != 0 || Lk % 64 != 0) {   // (never together with a block mask)
-        // no mask at all and enough 128-query workgroups for the chip: the 32-query kernel (103 against 119 us at
-        // 4000 x 4000, 24 heads).  Rows of fewer than 256 keys stay with the kernel below, which compares full fp32
-        // scores: that kernel's comparison gives up the two lowest mantissa bits, and in a short row the weight that a
-        // near-tie decided the other way is large.
+        // no mask at all and at least half as many 128-query workgroups as compute units: the 32-query kernel (103
+        // against 119 us at 4000 x 4000 with 24 heads, 51 against 61 us with 8; 64 against 96 us at d = 128, 32 heads x
+        // 2000).  Rows of fewer than 256 keys stay with the kernel below, which compares full fp32 scores: that
+        // kernel's comparison gives up the two lowest mantissa bits, and in a short row the weight that a near-tie
+        // decided the other way is large.
         if constexpr (MODE != MODE_DENSE) {
             if (!key_bias && !causal && variant == DFSS_VARIANT_AUTO && Lk >= 256 &&
-                (long)BH * ((Lq + 127) / 128) >= 512)
+                (long)BH * ((Lq + 127) / 128) >= 128)
                 return launch_fused_attention32_ragged(Q, K, V, BH, Lq, Lk, d, MODE == MODE_2TO4 ? 0 : 1, scale, O, st);
         }
         if ((long)BH * ((Lq + 127) / 128) >= 768)
