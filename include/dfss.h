@@ -15,7 +15,7 @@
  * 1:2 on the same 2-byte data; float inputs with 1:2 (the paper's 4-byte mode, see
  * "the 4-byte mode" below); d in {64, 128}; Lq a multiple of 64, Lk a multiple
  * of 128 and at most 8192.  With bfloat16 data the stage calls (stage 1, 2, 3, the staged forward
- * pass, the three-kernel baseline) and the *_ragged one-kernel calls also take any Lq >= 1 and any
+ * pass, the three-kernel baseline), the *_ragged one-kernel calls and the one-kernel *_mask calls also take any Lq >= 1 and any
  * Lk % 4 == 0 ("lengths that are not tile multiples" below).  Selection rule: larger signed score wins, equal scores -> lower key
  * index wins; comparisons are made on the fp32 value scale*dot, which is then
  * rounded to bfloat16 (nearest-even) for storage (kept as it is in the 4-byte mode).
