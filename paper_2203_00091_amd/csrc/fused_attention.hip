@@ -901,11 +901,13 @@ hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, c
                                   float scale, void *O, int variant, hipStream_t st) {
     // Calls without bias or block pattern on whole tiles take the 32-queries-per-wave kernel, and so do causal calls
     // (callers that name a 16-query tiling get the kernel above).  Its tilings, chosen from the number of 128-query
-    // workgroups (measured): four waves x 32 queries where that fills the chip; two waves per 32-query tile
-    // (64-query workgroups, twice as many, each wave half the keys) where the grid is smaller than the chip's
-    // 256 compute units or leaves its second round half empty; d = 128 always the former (the merge of the
+    // workgroups and the key length (measured): four waves x 32 queries as a rule; two waves per 32-query tile
+    // (64-query workgroups, twice as many, each wave half the keys) where the grid is at most one and a half
+    // workgroups per compute unit and the keys number 1024 or more (2048 where the grid already gives nearly
+    // every compute unit a workgroup of its own); d = 128 always the former (the merge of the
     // two key halves costs more than it gains there).  Full attention
-    // (the baseline) runs whichever of the two kernels is faster at the shape.
+    // (the baseline) runs the 16-query kernel below: the faster of the two at every shape measured (96 heads x 384,
+    // 24 heads x 1024 .. 4096, 192 heads x 512, d = 128), the 32-query form being reachable through the test hook.
     const bool masked = key_bias || block_mask || causal;
     // masked calls: the 32-query kernel where it measured faster -- the causal mask on 128-query workgroups (alone: its
     // form without the masking machinery, d = 64 and 128; with a key bias: the masked form, d = 64); a key bias alone
@@ -916,10 +918,11 @@ hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, c
         const long wg128 = (long)BH * (Lq / 128);
         int nw = Lq % 128 == 0 ? 4 : 2, ks = 1;
         if (variant == DFSS_VARIANT_AUTO && !masked) {
-            if (mode != 2 && d == 64 && (wg128 < 256 || (wg128 >= 320 && wg128 < 640))) nw = 4, ks = 2;
+            // the key split doubles the workgroups: it pays while all of them still fit the chip at once (3 x 256
+            // four-wave workgroups) and the sequence is long enough to carry the merge of the two halves
+            if (mode != 2 && d == 64 && wg128 <= 384 && Lk >= (wg128 > 160 && wg128 <= 256 ? 2048 : 1024)) nw = 4, ks = 2;
             if (mode != 2 && Lq % 128 != 0 && d == 64) nw = 4, ks = 2;   // 64-query workgroups either way
-            const bool old_dense = d == 128 || wg128 >= 448 || Lq % 128 != 0;
-            if (mode == 2 && old_dense) nw = 0;
+            if (mode == 2) nw = 0;   // full attention: the 16-query kernel measured faster at every shape tried
             if (mode != 2 && d == 128 && Lq % 128 != 0) nw = 0;       // (two-wave workgroups at d = 128: too many registers)
         }
         if (!masked) {
