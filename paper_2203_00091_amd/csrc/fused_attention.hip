@@ -922,6 +922,11 @@ hipError_t launch_fused_attention(const void *Q, const void *K, const void *V, c
             // four-wave workgroups) and the sequence is long enough to carry the merge of the two halves
             if (mode != 2 && d == 64 && wg128 <= 384 && Lk >= (wg128 > 160 && wg128 <= 256 ? 2048 : 1024)) nw = 4, ks = 2;
             if (mode != 2 && Lq % 128 != 0 && d == 64) nw = 4, ks = 2;   // 64-query workgroups either way
+            // ... unless the grid is large: then 128-query workgroups, the last one of a head half empty (the kernel
+            // of the unpadded lengths), beat 64-query ones (38.6 against 46.7 us at 24 heads x 2112, 19.3 against
+            // 22.8 at 192 x 448, 157 against 199 at d = 128, 64 x 2112; at 216 .. 384 workgroups level or 3-10 % behind)
+            if (mode != 2 && Lq % 128 != 0 && (long)BH * (Lq / 128 + 1) > 384)
+                return launch_fused_attention32_ragged(Q, K, V, BH, Lq, Lk, d, mode, scale, O, st);
             if (mode == 2) nw = 0;   // full attention: the 16-query kernel measured faster at every shape tried
             if (mode != 2 && d == 128 && Lq % 128 != 0) nw = 0;       // (two-wave workgroups at d = 128: too many registers)
         }

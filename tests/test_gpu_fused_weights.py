@@ -245,6 +245,21 @@ def test_ragged_call_on_a_grid_that_fills_the_chip():
     assert ties > 100
 
 
+@pytest.mark.parametrize("BH,Lq,Lk,d,N,M,scale", [
+    (200, 192, 256, 64, 2, 4, 0.125),
+    (200, 192, 128, 128, 1, 2, 0.0625),
+])
+def test_default_call_with_half_a_workgroup_left_over_on_a_large_grid(BH, Lq, Lk, d, N, M, scale):
+    """Lq an odd multiple of 64 on more than 384 workgroups: dfss_attention runs 128-query workgroups whose last
+    one per head is half empty.  Weight by weight against the oracle, every eighth head."""
+    Q, K, Qn, Kn = _int_qk(BH, Lq, Lk, d, seed=8800 + d)
+    s = Shape(1, BH, Lq, Lk, d, N, M)
+    Qd, Kd = Q.to(DEV), K.to(DEV)
+    W = _weights_through_identity_v(lambda V: dfss.dfss_attention(Qd, Kd, V, s, scale), BH, Lq, Lk, d, torch.bfloat16)
+    ties = _compare(W[::8], Qn[::8], Kn[::8], N, M, scale)
+    assert ties > 100
+
+
 def test_float_one_kernel_path():
     """The 4-byte mode's one-kernel path (split products; integer inputs are exact in its bfloat16 pieces)."""
     BH, Lq, Lk, d = 2, 128, 256, 64
